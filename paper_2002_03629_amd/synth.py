@@ -1,0 +1,214 @@
+"""Seeded synthetic inputs: network shapes, degrees, weights and noise.
+
+This module only *draws data*.  It holds none of the sampler's arithmetic (no masks,
+no forward pass, no decision rule) and imports neither the HIP binding nor the CPU
+oracle, so both sides of a parity test can be handed the very same arrays.
+
+Workload shapes follow the paper's autoregressive-sampling experiment (Section 5.3.1
+and Appendix C.3: MADE over T = 784 raster-ordered pixels, about 100 images sampled
+in parallel); the trained weights and the image data sets are replaced by seeded
+random networks of the same shape.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import numpy as np
+
+SEED_BASE = 2002036290
+
+
+@dataclass
+class Workload:
+    """One named synthetic workload (shape of the network plus batch and seeds)."""
+    name: str
+    D: int                      # number of positions (T in the paper)
+    C: int                      # 1 = Bernoulli positions, >1 = C-way categorical positions
+    hidden: List[int]           # widths of the hidden masked layers
+    dtype: str                  # "f32" or "bf16" (weights and hidden activations)
+    N: int                      # batch (independent samples drawn in parallel)
+    degree_rule: str            # "cyclic" or "random"
+    weight_rule: str            # "std0.1" or "fan_in"
+    seed: int = SEED_BASE
+    gain: float = 1.0           # extra factor on every weight (coupling strength sweeps)
+    block_sizes: List[int] = field(default_factory=list)
+
+
+def workload(name: str) -> Workload:
+    """The benchmark configurations plus reduced versions used by the tests."""
+    table = {
+        # tiny fp32 MADE, natural ordering
+        "cfg1": Workload("cfg1", 64, 1, [256], "f32", 16, "cyclic", "std0.1", SEED_BASE + 1),
+        # MNIST-shaped binary MADE
+        "cfg2": Workload("cfg2", 784, 1, [2000, 2000], "bf16", 128, "random", "fan_in", SEED_BASE + 2,
+                         block_sizes=[16, 64, 196]),
+        # 256-way categorical MADE
+        "cfg4": Workload("cfg4", 1024, 256, [4096, 4096], "bf16", 64, "random", "fan_in", SEED_BASE + 4),
+        # reduced shapes with ragged tiles (nothing is a multiple of 32)
+        "small_f32": Workload("small_f32", 50, 1, [77, 45], "f32", 9, "random", "fan_in", SEED_BASE + 11, gain=3.0),
+        "small_bf16": Workload("small_bf16", 100, 1, [203, 150], "bf16", 37, "random", "fan_in", SEED_BASE + 12,
+                               gain=3.0),
+        "mid_bf16": Workload("mid_bf16", 196, 1, [500, 500], "bf16", 70, "random", "fan_in", SEED_BASE + 13,
+                             gain=2.0),
+        "small_cat": Workload("small_cat", 24, 256, [96, 80], "bf16", 10, "random", "fan_in", SEED_BASE + 14,
+                              gain=3.0),
+        "small_cat_f32": Workload("small_cat_f32", 12, 5, [40], "f32", 7, "random", "fan_in", SEED_BASE + 15,
+                                  gain=3.0),
+    }
+    return table[name]
+
+
+def _rng(seed: int) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(int(seed)))
+
+
+def bf16_representable(a: np.ndarray) -> np.ndarray:
+    """fp32 array whose values are the inputs rounded to the nearest bfloat16 (ties to even).
+
+    Pure data preparation: the library and the oracle both receive these already
+    representable numbers, so neither has to agree with the other on how to round weights.
+    """
+    bits = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    lsb = (bits >> 16) & 1
+    rounded = ((bits + 0x7FFF + lsb) >> 16) << 16
+    return rounded.astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+def hidden_degrees(rule: str, D: int, widths: List[int], seed: int) -> List[np.ndarray]:
+    """Degree (1..D-1) of every hidden unit, one int32 array per hidden layer."""
+    g = _rng(seed)
+    out = []
+    for H in widths:
+        if D < 2:
+            raise ValueError("need D >= 2 for hidden degrees")
+        if rule == "cyclic":
+            m = 1 + (np.arange(H) % (D - 1))
+        elif rule == "random":
+            m = g.integers(1, D, size=H)
+        else:
+            raise ValueError(rule)
+        out.append(m.astype(np.int32))
+    return out
+
+
+def dense_weights(D: int, C: int, widths: List[int], rule: str, seed: int, gain: float = 1.0,
+                  bf16: bool = False) -> List[np.ndarray]:
+    """Unmasked fp32 weight matrices, row-major [out, in], one per layer (L hidden + output).
+
+    "std0.1": every entry N(0, 0.1^2).  "fan_in": N(0, 1/fan_in) with fan_in the dense
+    input width of the layer.  The output layer has D*C rows, row index t*C + c.
+    """
+    g = _rng(seed)
+    dims = [D] + list(widths) + [D * C]
+    Ws = []
+    for l in range(len(dims) - 1):
+        fan_in, fan_out = dims[l], dims[l + 1]
+        std = 0.1 if rule == "std0.1" else (1.0 / np.sqrt(fan_in))
+        w = g.standard_normal(size=(fan_out, fan_in), dtype=np.float32)
+        w *= np.float32(std * gain)
+        Ws.append(bf16_representable(w) if bf16 else w)
+    return Ws
+
+
+def uniform_noise(N: int, D: int, seed: int) -> np.ndarray:
+    """u[N, D] fp32 in [0, 1): the fixed per-position noise of a Bernoulli sampler."""
+    u = _rng(seed).random(size=(N, D), dtype=np.float32)
+    return np.minimum(u, np.float32(1.0 - 2.0 ** -24))
+
+
+def gumbel_noise(N: int, D: int, C: int, seed: int) -> np.ndarray:
+    """g[N, D, C] fp32 standard Gumbel values, computed once in fp64 from clamped uniforms."""
+    u = _rng(seed).random(size=(N, D, C))
+    u = np.clip(u, 2.0 ** -24, 1.0 - 2.0 ** -24)
+    return (-np.log(-np.log(u))).astype(np.float32)
+
+
+@dataclass
+class Network:
+    """Raw description handed to both `made_init` and the oracle."""
+    D: int
+    C: int
+    hidden: List[int]
+    dtype: str
+    degrees: List[np.ndarray]
+    W: List[np.ndarray]
+    b: List[Optional[np.ndarray]]
+
+
+def make_network(w: Workload, with_bias: bool = False) -> Network:
+    degs = hidden_degrees(w.degree_rule, w.D, w.hidden, w.seed + 1)
+    Ws = dense_weights(w.D, w.C, w.hidden, w.weight_rule, w.seed, w.gain, bf16=(w.dtype == "bf16"))
+    bs: List[Optional[np.ndarray]] = [None] * len(Ws)
+    if with_bias:
+        g = _rng(w.seed + 3)
+        bs = []
+        for W in Ws:
+            b = (0.3 * g.standard_normal(size=W.shape[0])).astype(np.float32)
+            bs.append(bf16_representable(b) if w.dtype == "bf16" else b)
+    return Network(w.D, w.C, list(w.hidden), w.dtype, degs, Ws, bs)
+
+
+def make_noise(w: Workload, rep: int = 0, N: Optional[int] = None) -> np.ndarray:
+    n = w.N if N is None else N
+    seed = w.seed + 2 + 10 * rep
+    return uniform_noise(n, w.D, seed) if w.C == 1 else gumbel_noise(n, w.D, w.C, seed)
+
+
+# ---------------------------------------------------------------------------------------------
+# Hand-built networks whose dependency structure is one of the paper's worked examples
+# (Section 4.1).  Only weights/biases are chosen here; what they imply is asserted in the tests.
+# ---------------------------------------------------------------------------------------------
+
+def independent_network(D: int, H: int, seed: int, dtype: str = "f32") -> Network:
+    """Example 1: every weight zero, arbitrary output biases -> positions are independent."""
+    degs = hidden_degrees("cyclic", D, [H], 0)
+    W = [np.zeros((H, D), np.float32), np.zeros((D, H), np.float32)]
+    bV = (2.0 * _rng(seed).standard_normal(size=D)).astype(np.float32)
+    if dtype == "bf16":
+        bV = bf16_representable(bV)
+    return Network(D, 1, [H], dtype, degs, W, [np.zeros(H, np.float32), bV])
+
+
+def first_only_network(D: int, H: int, seed: int, dtype: str = "f32") -> Network:
+    """Example 2: only position 1 feeds the network; its own bias forces x_1 = 1."""
+    g = _rng(seed)
+    degs = hidden_degrees("cyclic", D, [H], 0)
+    W1 = np.zeros((H, D), np.float32)
+    W1[:, 0] = (1.0 + g.random(size=H)).astype(np.float32)
+    WV = (4.0 * g.standard_normal(size=(D, H)) / np.sqrt(H)).astype(np.float32)
+    bV = np.zeros(D, np.float32)
+    bV[0] = 30.0
+    if dtype == "bf16":
+        W1, WV = bf16_representable(W1), bf16_representable(WV)
+    return Network(D, 1, [H], dtype, degs, [W1, WV], [np.zeros(H, np.float32), bV])
+
+
+def copy_chain_network(D: int, dtype: str = "f32") -> Network:
+    """Example 3: a strict Markov chain.  Hidden unit k (degree k) copies x_k, output t+1 reads
+    only that unit; biases make x_1 = 1 and x_t = x_{t-1}, so a 1 walks one position per pass."""
+    H = D - 1
+    degs = [np.arange(1, D, dtype=np.int32)]
+    W1 = np.zeros((H, D), np.float32)
+    WV = np.zeros((D, H), np.float32)
+    for k in range(H):
+        W1[k, k] = 1.0          # unit of degree k+1 reads position k+1 (0-based column k)
+        WV[k + 1, k] = 64.0     # position k+2 (0-based row k+1) reads that unit
+    bV = np.full(D, -32.0, np.float32)
+    bV[0] = 32.0
+    return Network(D, 1, [H], dtype, degs, [W1, WV], [np.zeros(H, np.float32), bV])
+
+
+def skip_network(D: int, H: int, skip: int, seed: int, dtype: str = "f32") -> Network:
+    """Position t reads only positions <= t - skip, so the dependency DAG's longest path has
+    ceil(D / skip) state nodes (the critical-path remark of Section 4.1)."""
+    g = _rng(seed)
+    degs = hidden_degrees("cyclic", D, [H], 0)
+    W1 = (3.0 * g.standard_normal(size=(H, D)) / np.sqrt(D)).astype(np.float32)
+    WV = (6.0 * g.standard_normal(size=(D, H)) / np.sqrt(H)).astype(np.float32)
+    m = degs[0]
+    for t in range(1, D + 1):
+        WV[t - 1, m > t - skip] = 0.0
+    if dtype == "bf16":
+        W1, WV = bf16_representable(W1), bf16_representable(WV)
+    return Network(D, 1, [H], dtype, degs, [W1, WV], [np.zeros(H, np.float32), np.zeros(D, np.float32)])
