@@ -1,0 +1,142 @@
+/*
+ * jacobi_made.h -- C ABI of libjacobi_made.so (MI355X / gfx950, HIP).
+ *
+ * Autoregressive sampling from a MADE-style masked MLP written as the feedforward
+ * recurrence  s_t = h_t(u, s_{1:t-1}),  1 <= t <= T  (paper Section 2.1, Eq. 1; the
+ * sampling instance is Appendix A.3: T = D positions, s_t = the t-th symbol, u = fixed
+ * per-position noise) and solved either one position at a time or by the parallel
+ * fixed-point iterations of Section 3: nonlinear Jacobi (Algorithm 1) and the block
+ * hybrid GS-Jacobi (Algorithm 3).  With tolerance 0 all three return the same symbols
+ * (Propositions 1 and 2).
+ *
+ * Conventions for every entry point
+ *   - returns MADE_OK (0) or a negative made_status; nothing throws or aborts across the
+ *     ABI; made_last_error() gives a thread-local message for the last failure.
+ *   - "host" pointers are ordinary CPU memory, read during the call only.
+ *   - "device" pointers are HIP device memory on the device that was current in
+ *     made_init; they stay owned by the caller and are never freed or retained.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The
+ *     *_sample calls synchronise `stream` before returning (their stop test needs the
+ *     device's answer); made_forward_logits only enqueues work.
+ *   - one model must not be used from two host threads at once (it owns scratch memory).
+ */
+#ifndef JACOBI_MADE_H
+#define JACOBI_MADE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct made_model made_model; /* opaque; owned by the library */
+
+typedef enum made_status {
+  MADE_OK = 0,
+  MADE_ERR_ARG = -1,           /* NULL / out-of-range argument, inconsistent sizes        */
+  MADE_ERR_NOMEM = -2,         /* host or device allocation failed                        */
+  MADE_ERR_HIP = -3,           /* a HIP runtime call failed (message has the HIP error)   */
+  MADE_ERR_NOT_CONVERGED = -4  /* max_iters passes ran and some sample was still changing;
+                                  x_out then holds the current iterate                    */
+} made_status;
+
+enum { MADE_F32 = 0, MADE_BF16 = 1 };
+
+typedef struct made_config {
+  int32_t D;             /* number of positions (T in the paper), 2 <= D                  */
+  int32_t C;             /* 1: Bernoulli positions; 2..256: C-way categorical positions    */
+  int32_t n_hidden;      /* L >= 1 hidden masked layers                                   */
+  const int32_t* hidden; /* host, [L] widths                                              */
+  int32_t dtype;         /* MADE_F32: fp32 weights/activations; MADE_BF16: bf16 weights and
+                            hidden activations (rounded to nearest even after bias+ReLU),
+                            fp32 accumulation, fp32 logits                                */
+} made_config;
+
+/*
+ * made_init -- build the masked network h_t is made of (the MADE the paper samples from in
+ * Section 5.3.1; masks are the construction of the model it cites).
+ *   degrees : host, [L] pointers; degrees[l] has hidden[l] entries in [1, D-1].
+ *   W       : host, [L+1] pointers to UNMASKED row-major [out, in] fp32 matrices; layer L is
+ *             the output layer with D*C rows, row t*C + c = class c of position t (0-based).
+ *             With MADE_BF16 every value is converted to bf16 (nearest even).
+ *   b       : host, [L+1] pointers to fp32 biases, any of them (or b itself) may be NULL = 0.
+ * Masks: input position d (1-based) has degree d; a hidden unit of degree m reads units of
+ * degree <= m; output rows of position t read last-layer units of degree < t.  The library
+ * multiplies the masks in, reorders hidden units by degree (invisible from outside) and
+ * uploads the result.  *out receives the model; release it with made_free.
+ */
+int made_init(const made_config* cfg, const int32_t* const* degrees, const float* const* W,
+              const float* const* b, made_model** out);
+
+/* made_free -- release the model and all of its device scratch memory.  NULL is accepted. */
+int made_free(made_model* m);
+
+/*
+ * made_forward_logits -- one pass over the whole network: the logits every h_t reads
+ * (Section 5.3.1: one forward propagation yields all positions at once).
+ *   x      : device, uint8 [N, D] symbols (Bernoulli: 0/1; categorical: 0..C-1, entering the
+ *            network as the scalar (x - 128)/128 per position).
+ *   logits : device, fp32 [N, D, C].
+ * Asynchronous on `stream`.
+ */
+int made_forward_logits(made_model* m, const uint8_t* x, int32_t N, float* logits, void* stream);
+
+/*
+ * Noise (the input u of Eq. 1, fixed for the whole call; Appendix A.3):
+ *   Bernoulli  : device fp32 u[N, D] in [0, 1);  x_t = 1  iff  u_t < sigmoid(z_t)
+ *   categorical: device fp32 g[N, D, C] standard Gumbel values;  x_t = argmax_c (z_tc + g_tc),
+ *                lowest index on ties.
+ */
+
+/*
+ * sequential_sample -- the feedforward computation itself (Section 2.1): for t = 1..D,
+ * x_t = h_t(u, x_{1:t-1}).
+ *   mode 0: every step runs the whole network, as the paper's baseline does (Section 5.3.1);
+ *   mode 1: every step evaluates only what position t can see (hidden units of degree < t and
+ *           the output rows of t) -- same result, the lean engineering baseline.
+ *   x_out : device uint8 [N, D].
+ */
+int sequential_sample(made_model* m, const float* noise, int32_t N, int32_t mode, uint8_t* x_out,
+                      void* stream);
+
+/*
+ * jacobi_sample -- Algorithm 1 with tolerance 0, each of the N samples an independent system.
+ * Starting from x_init (NULL = zeros), every pass recomputes all D positions in parallel from
+ * the previous iterate.  A sample stops at the first pass k that leaves it unchanged, or at
+ * k = D (exact by Proposition 1); stopped samples leave the batch.
+ *   max_iters : cap on passes, <= 0 or > D means D.  If the cap is below D and a sample is still
+ *               changing the call returns MADE_ERR_NOT_CONVERGED.
+ *   x_out     : device uint8 [N, D] (may alias x_init).
+ *   iters_out : device int32 [N] or NULL; the stopping k of every sample (it counts the pass
+ *               that only confirmed the fixed point).
+ */
+int jacobi_sample(made_model* m, const float* noise, int32_t N, const uint8_t* x_init,
+                  int32_t max_iters, uint8_t* x_out, int32_t* iters_out, void* stream);
+
+/*
+ * gs_jacobi_sample -- Algorithm 3 with tolerance 0: blocks of `block` consecutive positions
+ * (the last one may be short) are solved one after the other; inside block [a, b] Jacobi passes
+ * update only the block's positions against the final values of earlier blocks, until the block
+ * is unchanged or |block| passes ran.  Block positions start from x_init (NULL = zeros).
+ *   iters_out : device int32 [N] or NULL; per sample, the sum over blocks of inner passes.
+ */
+int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, const uint8_t* x_init,
+                     int32_t block, uint8_t* x_out, int32_t* iters_out, void* stream);
+
+/*
+ * made_last_stats -- counters of the most recent *_sample call on this model (host side):
+ *   out[0] passes launched (network passes over the still-active part of the batch)
+ *   out[1] sum over passes of active samples (sample-passes; the unit of algorithmic work)
+ *   out[2] kernels launched
+ *   out[3] host waits on the device
+ * n = number of int64 slots available in out (extra slots are left untouched).
+ */
+int made_last_stats(const made_model* m, int64_t* out, int32_t n);
+
+/* made_last_error -- message of the calling thread's most recent failure ("" if none). */
+const char* made_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JACOBI_MADE_H */

@@ -189,13 +189,14 @@ def fixed_point_check(model: MadeModel, x: np.ndarray, noise: np.ndarray) -> Tup
 
 def jacobi_reference(model: MadeModel, noise: np.ndarray, x_init: Optional[np.ndarray] = None,
                      max_iters: Optional[int] = None, record: bool = False):
-    """Returns (x, iters[N], converged[N], trajectory or None).
+    """Returns (x, iters[N], converged[N], trajectory or None, min_margin[N]).
 
     Each sample stops at the first k with s^k == s^{k-1}, or at k = T (= D); `iters` is that
     stopping k, so it includes the pass that merely confirms the fixed point.  A sample
     that stopped is left untouched afterwards (it is a fixed point, so further passes would
     not change it).  With max_iters < D a sample may end unconverged (converged[n] False).
     trajectory[k] is s^k for the whole batch (stopped samples keep their value).
+    min_margin[n] is the smallest decision margin sample n met in any of its passes.
     """
     N, D = noise.shape[0], model.D
     cap = D if (max_iters is None or max_iters <= 0) else min(max_iters, D)
@@ -203,11 +204,13 @@ def jacobi_reference(model: MadeModel, noise: np.ndarray, x_init: Optional[np.nd
     iters = np.zeros(N, dtype=np.int32)
     done = np.zeros(N, dtype=bool)
     traj = [x.copy()] if record else None
+    min_margin = np.full(N, np.inf)
     k = 0
     while not done.all() and k < cap:
         k += 1
         act = np.flatnonzero(~done)
-        new, _ = jacobi_pass(model, x[act], noise[act])
+        new, margin = jacobi_pass(model, x[act], noise[act])
+        min_margin[act] = np.minimum(min_margin[act], margin.min(axis=1))
         same = (new == x[act]).all(axis=1)
         x[act] = new
         iters[act] = k
@@ -216,7 +219,7 @@ def jacobi_reference(model: MadeModel, noise: np.ndarray, x_init: Optional[np.nd
             done[act] = True                            # the "k = T" clause: exact by Prop. 1
         if record:
             traj.append(x.copy())
-    return x, iters, done, traj
+    return x, iters, done, traj, min_margin
 
 
 # --------------------------------------------------------------------------------------
@@ -230,7 +233,7 @@ def block_partition(D: int, block: int) -> List[Tuple[int, int]]:
 
 def gs_jacobi_reference(model: MadeModel, noise: np.ndarray, block: int,
                         x_init: Optional[np.ndarray] = None):
-    """Returns (x, iters[N], per_block_iters[N, M]).
+    """Returns (x, iters[N], per_block_iters[N, M], min_margin[N]).
 
     For block [a, b): the block's positions start from x_init (zeros by default), then
     s_j^k = h_j(u, s_{1:a-1} final, s^{k-1}_{a:j-1}) for all j in the block at once, until the
@@ -241,6 +244,7 @@ def gs_jacobi_reference(model: MadeModel, noise: np.ndarray, block: int,
     x = np.zeros((N, D), dtype=np.uint8) if x_init is None else np.array(x_init, dtype=np.uint8)
     parts = block_partition(D, block)
     per_block = np.zeros((N, len(parts)), dtype=np.int32)
+    min_margin = np.full(N, np.inf)
     for i, (a, b) in enumerate(parts):
         done = np.zeros(N, dtype=bool)
         k = 0
@@ -248,7 +252,8 @@ def gs_jacobi_reference(model: MadeModel, noise: np.ndarray, block: int,
             k += 1
             act = np.flatnonzero(~done)
             z = logits_all(model, x[act])[:, a:b]        # positions of this block only
-            new, _ = decide(z, noise[act, a:b], model.C)
+            new, margin = decide(z, noise[act, a:b], model.C)
+            min_margin[act] = np.minimum(min_margin[act], margin.min(axis=1))
             same = (new == x[act, a:b]).all(axis=1)
             xa = x[act]
             xa[:, a:b] = new
@@ -257,7 +262,7 @@ def gs_jacobi_reference(model: MadeModel, noise: np.ndarray, block: int,
             done[act[same]] = True
             if k == b - a:
                 done[act] = True
-    return x, per_block.sum(axis=1).astype(np.int32), per_block
+    return x, per_block.sum(axis=1).astype(np.int32), per_block, min_margin
 
 
 # --------------------------------------------------------------------------------------

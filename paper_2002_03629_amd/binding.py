@@ -1,0 +1,161 @@
+"""ctypes binding of libjacobi_made.so: argument marshalling only.
+
+Function names and argument order follow include/jacobi_made.h.  Device buffers are torch
+tensors (torch is used for device memory and streams, nothing else); host arrays are numpy.
+There is no fallback: if the shared library is missing, `lib()` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libjacobi_made.so")
+
+MADE_OK, MADE_ERR_ARG, MADE_ERR_NOMEM, MADE_ERR_HIP, MADE_ERR_NOT_CONVERGED = 0, -1, -2, -3, -4
+MADE_F32, MADE_BF16 = 0, 1
+
+EXPORTS = ["made_init", "made_free", "made_forward_logits", "sequential_sample", "jacobi_sample",
+           "gs_jacobi_sample", "made_last_stats", "made_last_error"]
+
+
+class MadeError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"libjacobi_made status {code}: {message}")
+        self.code = code
+
+
+class made_config(C.Structure):
+    _fields_ = [("D", C.c_int32), ("C", C.c_int32), ("n_hidden", C.c_int32),
+                ("hidden", C.POINTER(C.c_int32)), ("dtype", C.c_int32)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load the HIP library (once).  Fails loudly when it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2002_03629_amd.build` "
+                               "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64p = C.c_void_p, C.c_int32, C.POINTER(C.c_int64)
+        L.made_init.argtypes = [C.POINTER(made_config), C.POINTER(C.POINTER(C.c_int32)),
+                                C.POINTER(C.POINTER(C.c_float)), C.POINTER(C.POINTER(C.c_float)), C.POINTER(vp)]
+        L.made_free.argtypes = [vp]
+        L.made_forward_logits.argtypes = [vp, vp, i32, vp, vp]
+        L.sequential_sample.argtypes = [vp, vp, i32, i32, vp, vp]
+        L.jacobi_sample.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
+        L.gs_jacobi_sample.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
+        L.made_last_stats.argtypes = [vp, i64p, i32]
+        L.made_last_error.argtypes = []
+        L.made_last_error.restype = C.c_char_p
+        for name in EXPORTS[:-1]:
+            getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def made_last_error() -> str:
+    return lib().made_last_error().decode()
+
+
+def _check(code: int) -> None:
+    if code != MADE_OK:
+        raise MadeError(code, made_last_error())
+
+
+def _ptr(t, dtype=None) -> Optional[int]:
+    """Device pointer of a contiguous torch tensor (or None)."""
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("device tensors must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream or None
+
+
+def made_init(D: int, Cn: int, hidden: Sequence[int], dtype: int, degrees: Sequence[np.ndarray],
+              W: Sequence[np.ndarray], b: Optional[Sequence[Optional[np.ndarray]]] = None) -> int:
+    """Returns the opaque model handle (an integer address)."""
+    L = len(hidden)
+    hid = np.ascontiguousarray(hidden, dtype=np.int32)
+    cfg = made_config(int(D), int(Cn), L, hid.ctypes.data_as(C.POINTER(C.c_int32)), int(dtype))
+    keep = []
+    deg_arr = (C.POINTER(C.c_int32) * L)()
+    for l in range(L):
+        a = np.ascontiguousarray(degrees[l], dtype=np.int32)
+        if a.shape != (hidden[l],):
+            raise ValueError("degrees[%d] has shape %s" % (l, a.shape))
+        keep.append(a)
+        deg_arr[l] = a.ctypes.data_as(C.POINTER(C.c_int32))
+    dims = [D] + list(hidden) + [D * Cn]
+    W_arr = (C.POINTER(C.c_float) * (L + 1))()
+    b_arr = (C.POINTER(C.c_float) * (L + 1))()
+    for l in range(L + 1):
+        a = np.ascontiguousarray(W[l], dtype=np.float32)
+        if a.shape != (dims[l + 1], dims[l]):
+            raise ValueError("W[%d] has shape %s, expected %s" % (l, a.shape, (dims[l + 1], dims[l])))
+        keep.append(a)
+        W_arr[l] = a.ctypes.data_as(C.POINTER(C.c_float))
+        bl = None if b is None else b[l]
+        if bl is not None:
+            bb = np.ascontiguousarray(bl, dtype=np.float32)
+            if bb.shape != (dims[l + 1],):
+                raise ValueError("b[%d] has shape %s" % (l, bb.shape))
+            keep.append(bb)
+            b_arr[l] = bb.ctypes.data_as(C.POINTER(C.c_float))
+    out = C.c_void_p()
+    _check(lib().made_init(C.byref(cfg), deg_arr, W_arr, b_arr, C.byref(out)))
+    return out.value
+
+
+def made_free(model: Optional[int]) -> None:
+    _check(lib().made_free(model))
+
+
+def made_forward_logits(model: int, x, N: int, logits, stream=None) -> None:
+    import torch
+    _check(lib().made_forward_logits(model, _ptr(x, torch.uint8), N, _ptr(logits, torch.float32), _stream(stream)))
+
+
+def sequential_sample(model: int, noise, N: int, mode: int, x_out, stream=None) -> None:
+    import torch
+    _check(lib().sequential_sample(model, _ptr(noise, torch.float32), N, mode, _ptr(x_out, torch.uint8),
+                                   _stream(stream)))
+
+
+def jacobi_sample(model: int, noise, N: int, x_init, max_iters: int, x_out, iters_out=None, stream=None) -> None:
+    import torch
+    _check(lib().jacobi_sample(model, _ptr(noise, torch.float32), N, _ptr(x_init, torch.uint8), max_iters,
+                               _ptr(x_out, torch.uint8), _ptr(iters_out, torch.int32), _stream(stream)))
+
+
+def gs_jacobi_sample(model: int, noise, N: int, x_init, block: int, x_out, iters_out=None, stream=None) -> None:
+    import torch
+    _check(lib().gs_jacobi_sample(model, _ptr(noise, torch.float32), N, _ptr(x_init, torch.uint8), block,
+                                  _ptr(x_out, torch.uint8), _ptr(iters_out, torch.int32), _stream(stream)))
+
+
+def made_last_stats(model: int) -> dict:
+    buf = (C.c_int64 * 4)()
+    _check(lib().made_last_stats(model, buf, 4))
+    return {"passes": buf[0], "sample_passes": buf[1], "kernels": buf[2], "host_waits": buf[3]}
+
+
+def model_from_network(net) -> int:
+    """made_init from a synth.Network description."""
+    return made_init(net.D, net.C, net.hidden, MADE_BF16 if net.dtype == "bf16" else MADE_F32, net.degrees, net.W,
+                     net.b)

@@ -1,0 +1,601 @@
+// libjacobi_made.so: host side of the C ABI declared in include/jacobi_made.h.
+//
+// Host code builds the masked, degree-sorted network (made_init) and schedules passes:
+//   sequential_sample  -- Eq. 1, one position per step
+//   jacobi_sample      -- Algorithm 1, tolerance 0, per-sample stopping
+//   gs_jacobi_sample   -- Algorithm 3, tolerance 0
+// Every arithmetic step of a pass runs in the HIP kernels of kernels.hpp.
+#include "../../include/jacobi_made.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <string>
+#include <vector>
+
+#include "kernels.hpp"
+
+using namespace jm;
+
+// ------------------------------------------------------------------------------------------------
+// errors
+// ------------------------------------------------------------------------------------------------
+static thread_local std::string g_last_error;
+
+static int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_last_error = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                               \
+  do {                                                                                              \
+    hipError_t e_ = (expr);                                                                         \
+    if (e_ != hipSuccess)                                                                           \
+      return fail(e_ == hipErrorOutOfMemory ? MADE_ERR_NOMEM : MADE_ERR_HIP, "%s failed: %s (%s:%d)", #expr, \
+                  hipGetErrorString(e_), __FILE__, __LINE__);                                       \
+  } while (0)
+
+#define TRY(expr)            \
+  do {                       \
+    int rc_ = (expr);        \
+    if (rc_ != MADE_OK) return rc_; \
+  } while (0)
+
+static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+// ------------------------------------------------------------------------------------------------
+// model
+// ------------------------------------------------------------------------------------------------
+struct Layer {
+  int in_dim = 0, out_dim = 0;   // real sizes
+  int in_pad = 0, out_pad = 0;   // padded to multiples of 64 (zero filled)
+  int n_tiles = 0;               // out_pad / 32
+  void* W = nullptr;             // device, [out_pad, in_pad] of T, mask applied, units sorted by degree
+  float* bias = nullptr;         // device, [out_pad]
+  int* tile_kend = nullptr;      // device, [n_tiles]
+  std::vector<int> h_tile_kend;  // host copy
+};
+
+struct Workspace {
+  int N_cap = 0;
+  void* enc = nullptr;               // [N_pad, D_pad] network input of the current iterate
+  std::vector<void*> act;            // hidden activations, [N_pad, pad(H_l)]
+  float* zbuf = nullptr;             // categorical only: logits [N, D*C]
+  int* rows[2] = {nullptr, nullptr};
+  int* n_rows[2] = {nullptr, nullptr};
+  int* changed = nullptr;
+  int* iters = nullptr;
+  int* flags = nullptr;
+  int* h_pin = nullptr;              // pinned host mirror of active counts, one slot per pass
+  int h_pin_len = 0;
+  hipEvent_t ev[2] = {nullptr, nullptr};
+};
+
+struct made_model {
+  int D = 0, C = 1, L = 0, dtype = MADE_F32, device = 0;
+  std::vector<int> hidden;
+  std::vector<Layer> layers;                  // L hidden + 1 output
+  // cnt_lt[l][t] = number of units of hidden layer l with degree < t (t = 0..D); units are sorted by
+  // degree, so these are prefix lengths
+  std::vector<std::vector<int>> cnt_lt;
+  Workspace ws;
+  int64_t stats[4] = {0, 0, 0, 0};
+};
+
+static size_t elem_size(const made_model* m) { return m->dtype == MADE_BF16 ? 2 : 4; }
+static int chunk_elems(const made_model* m) { return m->dtype == MADE_BF16 ? 64 : 32; }
+
+static uint16_t host_f32_to_bf16(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+static void free_workspace(Workspace& w) {
+  if (w.enc) (void)hipFree(w.enc);
+  for (void* p : w.act)
+    if (p) (void)hipFree(p);
+  if (w.zbuf) (void)hipFree(w.zbuf);
+  for (int i = 0; i < 2; ++i) {
+    if (w.rows[i]) (void)hipFree(w.rows[i]);
+    if (w.n_rows[i]) (void)hipFree(w.n_rows[i]);
+    if (w.ev[i]) (void)hipEventDestroy(w.ev[i]);
+  }
+  if (w.changed) (void)hipFree(w.changed);
+  if (w.iters) (void)hipFree(w.iters);
+  if (w.flags) (void)hipFree(w.flags);
+  if (w.h_pin) (void)hipHostFree(w.h_pin);
+  w = Workspace();
+}
+
+static int ensure_workspace(made_model* m, int N, bool need_z) {
+  Workspace& w = m->ws;
+  need_z = need_z && m->C > 1;
+  const int need_pin = m->D + 4;
+  if (N <= w.N_cap && (!need_z || w.zbuf) && w.h_pin_len >= need_pin) return MADE_OK;
+  const int cap = std::max(N, w.N_cap);
+  const bool had_z = w.zbuf != nullptr;
+  free_workspace(w);
+  const int n_pad = round_up(cap, TILE);
+  const size_t es = elem_size(m);
+  const size_t enc_bytes = (size_t)n_pad * m->layers[0].in_pad * es;
+  HIP_TRY(hipMalloc(&w.enc, enc_bytes));
+  HIP_TRY(hipMemset(w.enc, 0, enc_bytes));
+  w.act.assign(m->L, nullptr);
+  for (int l = 0; l < m->L; ++l) {
+    const size_t bytes = (size_t)n_pad * m->layers[l + 1].in_pad * es;
+    HIP_TRY(hipMalloc(&w.act[l], bytes));
+    HIP_TRY(hipMemset(w.act[l], 0, bytes));
+  }
+  if ((need_z || had_z) && m->C > 1) {
+    HIP_TRY(hipMalloc((void**)&w.zbuf, (size_t)cap * m->D * m->C * sizeof(float)));
+  }
+  for (int i = 0; i < 2; ++i) {
+    HIP_TRY(hipMalloc((void**)&w.rows[i], (size_t)n_pad * sizeof(int)));
+    HIP_TRY(hipMalloc((void**)&w.n_rows[i], sizeof(int)));
+    HIP_TRY(hipEventCreateWithFlags(&w.ev[i], hipEventDisableTiming));
+  }
+  HIP_TRY(hipMalloc((void**)&w.changed, (size_t)n_pad * sizeof(int)));
+  HIP_TRY(hipMalloc((void**)&w.iters, (size_t)n_pad * sizeof(int)));
+  HIP_TRY(hipMalloc((void**)&w.flags, sizeof(int)));
+  HIP_TRY(hipHostMalloc((void**)&w.h_pin, (size_t)need_pin * sizeof(int), hipHostMallocDefault));
+  w.h_pin_len = need_pin;
+  w.N_cap = cap;
+  return MADE_OK;
+}
+
+extern "C" int made_free(made_model* m) {
+  if (!m) return MADE_OK;
+  for (Layer& l : m->layers) {
+    if (l.W) (void)hipFree(l.W);
+    if (l.bias) (void)hipFree(l.bias);
+    if (l.tile_kend) (void)hipFree(l.tile_kend);
+  }
+  free_workspace(m->ws);
+  delete m;
+  return MADE_OK;
+}
+
+extern "C" const char* made_last_error(void) { return g_last_error.c_str(); }
+
+extern "C" int made_last_stats(const made_model* m, int64_t* out, int32_t n) {
+  if (!m || !out || n < 0) return fail(MADE_ERR_ARG, "made_last_stats: NULL argument");
+  for (int i = 0; i < n && i < 4; ++i) out[i] = m->stats[i];
+  return MADE_OK;
+}
+
+static int validate_config(const made_config* cfg, const int32_t* const* degrees, const float* const* W) {
+  if (!cfg || !degrees || !W) return fail(MADE_ERR_ARG, "made_init: NULL argument");
+  if (cfg->D < 2 || cfg->D > (1 << 20)) return fail(MADE_ERR_ARG, "made_init: D=%d out of range [2, 2^20]", cfg->D);
+  if (cfg->C < 1 || cfg->C > 256) return fail(MADE_ERR_ARG, "made_init: C=%d out of range [1, 256]", cfg->C);
+  if (cfg->n_hidden < 1 || cfg->n_hidden > 64 || !cfg->hidden)
+    return fail(MADE_ERR_ARG, "made_init: n_hidden=%d out of range [1, 64] or hidden NULL", cfg->n_hidden);
+  if (cfg->dtype != MADE_F32 && cfg->dtype != MADE_BF16) return fail(MADE_ERR_ARG, "made_init: unknown dtype %d", cfg->dtype);
+  if ((int64_t)cfg->D * cfg->C > (int64_t)1 << 28) return fail(MADE_ERR_ARG, "made_init: D*C too large");
+  for (int l = 0; l < cfg->n_hidden; ++l) {
+    if (cfg->hidden[l] < 1 || cfg->hidden[l] > (1 << 20))
+      return fail(MADE_ERR_ARG, "made_init: hidden[%d]=%d out of range", l, cfg->hidden[l]);
+    if (!degrees[l] || !W[l]) return fail(MADE_ERR_ARG, "made_init: degrees[%d] or W[%d] is NULL", l, l);
+    for (int k = 0; k < cfg->hidden[l]; ++k)
+      if (degrees[l][k] < 1 || degrees[l][k] > cfg->D - 1)
+        return fail(MADE_ERR_ARG, "made_init: degrees[%d][%d]=%d outside [1, D-1]", l, k, degrees[l][k]);
+  }
+  if (!W[cfg->n_hidden]) return fail(MADE_ERR_ARG, "made_init: W[%d] (output layer) is NULL", cfg->n_hidden);
+  return MADE_OK;
+}
+
+extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, const float* const* W,
+                         const float* const* b, made_model** out) {
+  if (!out) return fail(MADE_ERR_ARG, "made_init: out is NULL");
+  *out = nullptr;
+  TRY(validate_config(cfg, degrees, W));
+  made_model* m = new (std::nothrow) made_model();
+  if (!m) return fail(MADE_ERR_NOMEM, "made_init: host allocation failed");
+  m->D = cfg->D;
+  m->C = cfg->C;
+  m->L = cfg->n_hidden;
+  m->dtype = cfg->dtype;
+  m->hidden.assign(cfg->hidden, cfg->hidden + cfg->n_hidden);
+  hipError_t e = hipGetDevice(&m->device);
+  if (e != hipSuccess) {
+    delete m;
+    return fail(MADE_ERR_HIP, "hipGetDevice failed: %s", hipGetErrorString(e));
+  }
+
+  const int L = m->L, D = m->D, C = m->C;
+  // in_deg[i]: degree of input i of the current layer, in its storage order; perm_prev maps storage
+  // order -> caller's column index.
+  std::vector<int> in_deg(D), perm_prev(D);
+  for (int d = 0; d < D; ++d) { in_deg[d] = d + 1; perm_prev[d] = d; }
+  m->layers.resize(L + 1);
+  m->cnt_lt.resize(L);
+
+  int rc = MADE_OK;
+  try {
+    for (int l = 0; l <= L && rc == MADE_OK; ++l) {
+      Layer& ly = m->layers[l];
+      const bool is_out = (l == L);
+      ly.in_dim = (int)in_deg.size();
+      ly.out_dim = is_out ? D * C : m->hidden[l];
+      ly.in_pad = round_up(ly.in_dim, 64);
+      ly.out_pad = round_up(ly.out_dim, 64);
+      ly.n_tiles = ly.out_pad / TILE;
+
+      // storage order of the output units and their degree threshold
+      std::vector<int> perm(ly.out_dim), out_deg(ly.out_dim);
+      if (is_out) {
+        for (int j = 0; j < ly.out_dim; ++j) { perm[j] = j; out_deg[j] = j / C + 1; }  // position t (1-based)
+      } else {
+        std::iota(perm.begin(), perm.end(), 0);
+        const int32_t* dg = degrees[l];
+        std::stable_sort(perm.begin(), perm.end(), [dg](int a2, int b2) { return dg[a2] < dg[b2]; });
+        for (int j = 0; j < ly.out_dim; ++j) out_deg[j] = dg[perm[j]];
+        std::vector<int>& cl = m->cnt_lt[l];
+        cl.assign(D + 2, 0);
+        for (int t = 0; t <= D + 1; ++t)
+          cl[t] = (int)(std::lower_bound(out_deg.begin(), out_deg.end(), t) - out_deg.begin());
+      }
+      // visible prefix per output unit: inputs are sorted by degree, so "degree <= m" (hidden) or
+      // "degree < t" (output) is a prefix of the K axis
+      std::vector<int> klen(ly.out_dim);
+      for (int j = 0; j < ly.out_dim; ++j) {
+        if (is_out)
+          klen[j] = (int)(std::lower_bound(in_deg.begin(), in_deg.end(), out_deg[j]) - in_deg.begin());
+        else
+          klen[j] = (int)(std::upper_bound(in_deg.begin(), in_deg.end(), out_deg[j]) - in_deg.begin());
+      }
+      const int kc = chunk_elems(m);
+      ly.h_tile_kend.assign(ly.n_tiles, 0);
+      for (int j = 0; j < ly.out_dim; ++j) {
+        int& te = ly.h_tile_kend[j / TILE];
+        te = std::max(te, round_up(klen[j], kc));
+      }
+
+      const size_t n_w = (size_t)ly.out_pad * ly.in_pad;
+      const size_t es = elem_size(m);
+      std::vector<uint8_t> host(n_w * es, 0);
+      const float* Wl = W[l];
+      for (int j = 0; j < ly.out_dim; ++j) {
+        const float* src = Wl + (size_t)perm[j] * ly.in_dim;
+        const int kl = klen[j];
+        if (m->dtype == MADE_BF16) {
+          uint16_t* dst = (uint16_t*)host.data() + (size_t)j * ly.in_pad;
+          for (int i = 0; i < kl; ++i) dst[i] = host_f32_to_bf16(src[perm_prev[i]]);
+        } else {
+          float* dst = (float*)host.data() + (size_t)j * ly.in_pad;
+          for (int i = 0; i < kl; ++i) dst[i] = src[perm_prev[i]];
+        }
+      }
+      std::vector<float> hb(ly.out_pad, 0.f);
+      if (b && b[l])
+        for (int j = 0; j < ly.out_dim; ++j) hb[j] = b[l][perm[j]];
+
+      hipError_t he = hipMalloc(&ly.W, n_w * es);
+      if (he == hipSuccess) he = hipMemcpy(ly.W, host.data(), n_w * es, hipMemcpyHostToDevice);
+      if (he == hipSuccess) he = hipMalloc((void**)&ly.bias, ly.out_pad * sizeof(float));
+      if (he == hipSuccess) he = hipMemcpy(ly.bias, hb.data(), ly.out_pad * sizeof(float), hipMemcpyHostToDevice);
+      if (he == hipSuccess) he = hipMalloc((void**)&ly.tile_kend, ly.n_tiles * sizeof(int));
+      if (he == hipSuccess)
+        he = hipMemcpy(ly.tile_kend, ly.h_tile_kend.data(), ly.n_tiles * sizeof(int), hipMemcpyHostToDevice);
+      if (he != hipSuccess)
+        rc = fail(he == hipErrorOutOfMemory ? MADE_ERR_NOMEM : MADE_ERR_HIP, "made_init: layer %d upload failed: %s", l,
+                  hipGetErrorString(he));
+      if (!is_out) {
+        in_deg = out_deg;
+        perm_prev = perm;
+      }
+    }
+  } catch (const std::bad_alloc&) {
+    rc = fail(MADE_ERR_NOMEM, "made_init: host allocation failed");
+  }
+  if (rc != MADE_OK) {
+    made_free(m);
+    return rc;
+  }
+  *out = m;
+  return MADE_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// launches
+// ------------------------------------------------------------------------------------------------
+struct RowSet {            // which samples a pass covers
+  const int* rows;         // device list or NULL (identity)
+  const int* n_rows_ptr;   // device count or NULL
+  int n_rows;              // host-side upper bound (grid size) and value when n_rows_ptr is NULL
+};
+
+struct SampleIO {          // what the sampling epilogue reads and writes
+  const float* noise;
+  uint8_t* x;
+  int t_lo, t_hi;
+};
+
+template <typename T, int EPI>
+static void launch_layer_t(const LayerArgs& a, int n_tiles, int row_tiles, hipStream_t s) {
+  hipLaunchKernelGGL((masked_layer_kernel<T, EPI>), dim3(n_tiles, row_tiles), dim3(256), 0, s, a);
+}
+
+template <int EPI>
+static void launch_layer(const made_model* m, const LayerArgs& a, int n_tiles, int row_tiles, hipStream_t s) {
+  if (m->dtype == MADE_BF16)
+    launch_layer_t<bf16_t, EPI>(a, n_tiles, row_tiles, s);
+  else
+    launch_layer_t<float, EPI>(a, n_tiles, row_tiles, s);
+}
+
+static LayerArgs base_args(const made_model* m, int l, const void* A, const RowSet& rs) {
+  const Layer& ly = m->layers[l];
+  LayerArgs a;
+  memset(&a, 0, sizeof a);
+  a.A = A;
+  a.lda = ly.in_pad;
+  a.W = ly.W;
+  a.ldw = ly.in_pad;
+  a.bias = ly.bias;
+  a.tile_kend = ly.tile_kend;
+  a.k_cap = ly.in_pad;
+  a.tile_begin = 0;
+  a.rows = rs.rows;
+  a.n_rows_ptr = rs.n_rows_ptr;
+  a.n_rows = rs.n_rows;
+  a.n_cols = ly.out_dim;
+  return a;
+}
+
+// Hidden layers for the samples of `rs`.  unit_limit[l] < 0 means the whole layer; otherwise only the
+// first unit_limit[l] (degree-sorted) units are evaluated, reading only the first in_limit inputs.
+static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, int in_limit0, hipStream_t s) {
+  const int row_tiles = (rs.n_rows + TILE - 1) / TILE;
+  const int kc = chunk_elems(m);
+  int in_limit = in_limit0;
+  for (int l = 0; l < m->L; ++l) {
+    const Layer& ly = m->layers[l];
+    LayerArgs a = base_args(m, l, l == 0 ? m->ws.enc : m->ws.act[l - 1], rs);
+    a.out = m->ws.act[l];
+    a.ldo = m->layers[l + 1].in_pad;
+    int tiles = ly.n_tiles;
+    if (unit_limit && unit_limit[l] >= 0) tiles = std::min(tiles, (unit_limit[l] + TILE - 1) / TILE);
+    if (in_limit >= 0) a.k_cap = std::min(ly.in_pad, round_up(in_limit, kc));
+    if (tiles > 0) {
+      launch_layer<EPI_RELU>(m, a, tiles, row_tiles, s);
+      m->stats[2]++;
+    }
+    in_limit = (unit_limit && unit_limit[l] >= 0) ? unit_limit[l] : -1;
+  }
+  HIP_TRY(hipGetLastError());
+  return MADE_OK;
+}
+
+// Output layer + draw for positions [t_lo, t_hi).  whole = evaluate every output tile regardless.
+static int run_output_sample(made_model* m, const RowSet& rs, const SampleIO& io, bool whole, int k_limit,
+                             hipStream_t s) {
+  const Layer& ly = m->layers[m->L];
+  const int row_tiles = (rs.n_rows + TILE - 1) / TILE;
+  const int kc = chunk_elems(m);
+  LayerArgs a = base_args(m, m->L, m->ws.act[m->L - 1], rs);
+  if (k_limit >= 0) a.k_cap = std::min(ly.in_pad, round_up(k_limit, kc));
+  const int C = m->C;
+  int tile_lo = 0, tile_hi = ly.n_tiles;
+  if (!whole) {
+    tile_lo = (io.t_lo * C) / TILE;
+    tile_hi = (io.t_hi * C + TILE - 1) / TILE;
+  }
+  a.tile_begin = tile_lo;
+  if (C == 1) {
+    a.noise = io.noise;
+    a.x = io.x;
+    a.enc = m->ws.enc;
+    a.ld_enc = m->layers[0].in_pad;
+    a.changed = m->ws.changed;
+    a.D = m->D;
+    a.t_lo = io.t_lo;
+    a.t_hi = io.t_hi;
+    launch_layer<EPI_BERNOULLI>(m, a, tile_hi - tile_lo, row_tiles, s);
+    m->stats[2]++;
+  } else {
+    a.out = m->ws.zbuf;
+    a.ldo = m->D * C;
+    launch_layer<EPI_LOGITS>(m, a, tile_hi - tile_lo, row_tiles, s);
+    const int span = io.t_hi - io.t_lo;
+    const long long waves = (long long)rs.n_rows * span;
+    const int blocks = (int)((waves + 3) / 4);
+    if (m->dtype == MADE_BF16)
+      hipLaunchKernelGGL((gumbel_argmax_kernel<bf16_t>), dim3(blocks), dim3(256), 0, s, m->ws.zbuf, m->D * C, io.noise,
+                         io.x, (bf16_t*)m->ws.enc, m->layers[0].in_pad, m->ws.changed, rs.rows, rs.n_rows_ptr,
+                         rs.n_rows, m->D, C, io.t_lo, io.t_hi);
+    else
+      hipLaunchKernelGGL((gumbel_argmax_kernel<float>), dim3(blocks), dim3(256), 0, s, m->ws.zbuf, m->D * C, io.noise,
+                         io.x, (float*)m->ws.enc, m->layers[0].in_pad, m->ws.changed, rs.rows, rs.n_rows_ptr,
+                         rs.n_rows, m->D, C, io.t_lo, io.t_hi);
+    m->stats[2] += 2;
+  }
+  HIP_TRY(hipGetLastError());
+  return MADE_OK;
+}
+
+static int launch_init_state(made_model* m, const uint8_t* x_init, uint8_t* x, int N, hipStream_t s) {
+  const size_t total = (size_t)N * m->D;
+  const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
+  if (m->dtype == MADE_BF16)
+    hipLaunchKernelGGL((init_state_kernel<bf16_t>), dim3(blocks), dim3(256), 0, s, x_init, x, (bf16_t*)m->ws.enc,
+                       m->layers[0].in_pad, N, m->D, m->C);
+  else
+    hipLaunchKernelGGL((init_state_kernel<float>), dim3(blocks), dim3(256), 0, s, x_init, x, (float*)m->ws.enc,
+                       m->layers[0].in_pad, N, m->D, m->C);
+  m->stats[2]++;
+  HIP_TRY(hipGetLastError());
+  return MADE_OK;
+}
+
+static int launch_reset_rows(made_model* m, int which, int N, bool clear_iters, hipStream_t s) {
+  hipLaunchKernelGGL(reset_rows_kernel, dim3((N + 255) / 256), dim3(256), 0, s, m->ws.rows[which], m->ws.n_rows[which], N,
+                     m->ws.changed, clear_iters ? m->ws.iters : nullptr, clear_iters ? m->ws.flags : nullptr);
+  m->stats[2]++;
+  HIP_TRY(hipGetLastError());
+  return MADE_OK;
+}
+
+static int check_call(made_model* m, const void* noise, int32_t N, const void* x_out, const char* who) {
+  if (!m) return fail(MADE_ERR_ARG, "%s: model is NULL", who);
+  if (N < 0) return fail(MADE_ERR_ARG, "%s: N=%d is negative", who, N);
+  if (N > (1 << 22)) return fail(MADE_ERR_ARG, "%s: N=%d exceeds 2^22", who, N);
+  if (N > 0 && (!noise || !x_out)) return fail(MADE_ERR_ARG, "%s: NULL noise or output pointer", who);
+  HIP_TRY(hipSetDevice(m->device));
+  return MADE_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// entry points
+// ------------------------------------------------------------------------------------------------
+extern "C" int made_forward_logits(made_model* m, const uint8_t* x, int32_t N, float* logits, void* stream) {
+  TRY(check_call(m, x, N, logits, "made_forward_logits"));
+  if (N == 0) return MADE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  TRY(ensure_workspace(m, N, false));
+  TRY(launch_init_state(m, x, nullptr, N, s));
+  RowSet rs{nullptr, nullptr, N};
+  TRY(run_hidden(m, rs, nullptr, -1, s));
+  LayerArgs a = base_args(m, m->L, m->ws.act[m->L - 1], rs);
+  a.out = logits;
+  a.ldo = m->D * m->C;
+  launch_layer<EPI_LOGITS>(m, a, m->layers[m->L].n_tiles, (N + TILE - 1) / TILE, s);
+  HIP_TRY(hipGetLastError());
+  return MADE_OK;
+}
+
+extern "C" int sequential_sample(made_model* m, const float* noise, int32_t N, int32_t mode, uint8_t* x_out,
+                                 void* stream) {
+  TRY(check_call(m, noise, N, x_out, "sequential_sample"));
+  if (mode != 0 && mode != 1) return fail(MADE_ERR_ARG, "sequential_sample: mode=%d must be 0 or 1", mode);
+  if (N == 0) return MADE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  memset(m->stats, 0, sizeof m->stats);
+  TRY(ensure_workspace(m, N, true));
+  TRY(launch_init_state(m, nullptr, x_out, N, s));
+  TRY(launch_reset_rows(m, 0, N, true, s));
+  RowSet rs{nullptr, nullptr, N};
+  std::vector<int> limit(m->L);
+  for (int p = 0; p < m->D; ++p) {  // p = 0-based position, its 1-based index is t = p + 1
+    SampleIO io{noise, x_out, p, p + 1};
+    if (mode == 0) {
+      TRY(run_hidden(m, rs, nullptr, -1, s));
+      TRY(run_output_sample(m, rs, io, true, -1, s));
+    } else {
+      // position t reads last-layer units of degree < t; those read units of degree <= their own
+      for (int l = 0; l < m->L; ++l) limit[l] = m->cnt_lt[l][p + 1];
+      TRY(run_hidden(m, rs, limit.data(), p, s));
+      TRY(run_output_sample(m, rs, io, false, limit[m->L - 1], s));
+    }
+    m->stats[0]++;
+    m->stats[1] += N;
+  }
+  HIP_TRY(hipStreamSynchronize(s));
+  m->stats[3]++;
+  return MADE_OK;
+}
+
+// Jacobi passes over positions [t_lo, t_hi) of the samples listed in rows[0], at most `cap` of them.
+// The host enqueues pass k + 1 before it waits for the active count after pass k, so the device never
+// idles on the stop test; a pass enqueued after the batch emptied finds zero active rows and does nothing.
+// Active counts land in the pinned log h_pin[1 + i] (i = running pass index of the whole call).
+static int iterate_block(made_model* m, const float* noise, uint8_t* x, int N, int t_lo, int t_hi, int cap,
+                         bool flag_unconverged, const int* hidden_limit, int in_limit, int out_k_limit,
+                         std::vector<char>& first_of_block, hipStream_t s) {
+  Workspace& w = m->ws;
+  for (int k = 1; k <= cap; ++k) {
+    const int in = (k - 1) & 1, out = k & 1;
+    const int slot = 1 + (int)first_of_block.size();
+    if (slot >= w.h_pin_len) return fail(MADE_ERR_HIP, "internal: pass log overflow");
+    RowSet rs{w.rows[in], w.n_rows[in], N};
+    SampleIO io{noise, x, t_lo, t_hi};
+    TRY(run_hidden(m, rs, hidden_limit, in_limit, s));
+    TRY(run_output_sample(m, rs, io, false, out_k_limit, s));
+    hipLaunchKernelGGL(retire_kernel, dim3(1), dim3(256), 0, s, w.rows[in], w.n_rows[in], w.rows[out], w.n_rows[out],
+                       w.changed, w.iters, (int)(k == cap), (int)flag_unconverged, w.flags);
+    m->stats[2]++;
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpyAsync(&w.h_pin[slot], w.n_rows[out], sizeof(int), hipMemcpyDeviceToHost, s));
+    first_of_block.push_back(k == 1);
+    if (k < cap) {
+      HIP_TRY(hipEventRecord(w.ev[out], s));
+      if (k >= 2) {  // result of pass k - 1, while pass k is already queued
+        HIP_TRY(hipEventSynchronize(w.ev[in]));
+        m->stats[3]++;
+        if (w.h_pin[slot - 1] == 0) break;
+      }
+    }
+  }
+  return MADE_OK;
+}
+
+static int finish_call(made_model* m, int N, int32_t* iters_out, bool check_flag,
+                       const std::vector<char>& first_of_block, hipStream_t s) {
+  Workspace& w = m->ws;
+  if (iters_out) HIP_TRY(hipMemcpyAsync(iters_out, w.iters, (size_t)N * sizeof(int), hipMemcpyDeviceToDevice, s));
+  if (check_flag) HIP_TRY(hipMemcpyAsync(&w.h_pin[0], w.flags, sizeof(int), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  m->stats[3]++;
+  int active_in = 0;
+  for (size_t i = 0; i < first_of_block.size(); ++i) {
+    if (first_of_block[i]) active_in = N;
+    if (active_in > 0) {
+      m->stats[0]++;
+      m->stats[1] += active_in;
+    }
+    active_in = w.h_pin[1 + i];
+  }
+  if (check_flag && w.h_pin[0])
+    return fail(MADE_ERR_NOT_CONVERGED, "samples were still changing after the last allowed pass");
+  return MADE_OK;
+}
+
+extern "C" int jacobi_sample(made_model* m, const float* noise, int32_t N, const uint8_t* x_init, int32_t max_iters,
+                             uint8_t* x_out, int32_t* iters_out, void* stream) {
+  TRY(check_call(m, noise, N, x_out, "jacobi_sample"));
+  if (N == 0) return MADE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  memset(m->stats, 0, sizeof m->stats);
+  TRY(ensure_workspace(m, N, true));
+  const int cap = (max_iters <= 0 || max_iters > m->D) ? m->D : max_iters;
+  TRY(launch_init_state(m, x_init, x_out, N, s));
+  TRY(launch_reset_rows(m, 0, N, true, s));
+  std::vector<char> log;
+  TRY(iterate_block(m, noise, x_out, N, 0, m->D, cap, cap < m->D, nullptr, -1, -1, log, s));
+  return finish_call(m, N, iters_out, cap < m->D, log, s);
+}
+
+extern "C" int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, const uint8_t* x_init, int32_t block,
+                                uint8_t* x_out, int32_t* iters_out, void* stream) {
+  TRY(check_call(m, noise, N, x_out, "gs_jacobi_sample"));
+  if (block < 1) return fail(MADE_ERR_ARG, "gs_jacobi_sample: block=%d must be >= 1", block);
+  if (N == 0) return MADE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  memset(m->stats, 0, sizeof m->stats);
+  TRY(ensure_workspace(m, N, true));
+  TRY(launch_init_state(m, x_init, x_out, N, s));
+  TRY(launch_reset_rows(m, 0, N, true, s));
+  std::vector<int> limit(m->L);
+  std::vector<char> log;
+  for (int a = 0; a < m->D; a += block) {
+    const int b = std::min(a + block, m->D);          // block = 0-based positions [a, b)
+    if (a > 0) TRY(launch_reset_rows(m, 0, N, false, s));
+    // positions < b read last-layer units of degree < b (1-based b), i.e. degree <= b - 1
+    for (int l = 0; l < m->L; ++l) limit[l] = m->cnt_lt[l][b];
+    TRY(iterate_block(m, noise, x_out, N, a, b, b - a, false, limit.data(), b - 1, limit[m->L - 1], log, s));
+  }
+  return finish_call(m, N, iters_out, false, log, s);
+}

@@ -48,11 +48,11 @@ def workload(name: str) -> Workload:
         # reduced shapes with ragged tiles (nothing is a multiple of 32)
         "small_f32": Workload("small_f32", 50, 1, [77, 45], "f32", 9, "random", "fan_in", SEED_BASE + 11, gain=3.0),
         "small_bf16": Workload("small_bf16", 100, 1, [203, 150], "bf16", 37, "random", "fan_in", SEED_BASE + 12,
-                               gain=3.0),
+                               gain=2.0),
         "mid_bf16": Workload("mid_bf16", 196, 1, [500, 500], "bf16", 70, "random", "fan_in", SEED_BASE + 13,
                              gain=2.0),
         "small_cat": Workload("small_cat", 24, 256, [96, 80], "bf16", 10, "random", "fan_in", SEED_BASE + 14,
-                              gain=3.0),
+                              gain=1.5),
         "small_cat_f32": Workload("small_cat_f32", 12, 5, [40], "f32", 7, "random", "fan_in", SEED_BASE + 15,
                                   gain=3.0),
     }

@@ -1,0 +1,99 @@
+"""Helpers shared by the GPU parity tests (test code; may import both the binding and the oracle)."""
+import numpy as np
+import torch
+
+from oracle import made_oracle as O
+from paper_2002_03629_amd import binding as B
+
+MARGIN = 1e-3          # positions whose oracle decision margin is below this are exempt from bit-exactness
+LOGIT_TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
+
+
+def oracle_models(net):
+    """(exact fp64 model, model whose hidden activations are rounded like the library's)."""
+    exact = O.build_model(net.D, net.C, net.degrees, net.W, net.b, None)
+    same = O.build_model(net.D, net.C, net.degrees, net.W, net.b, "bf16") if net.dtype == "bf16" else exact
+    return exact, same
+
+
+class GpuModel:
+    def __init__(self, net):
+        self.net = net
+        self.h = B.model_from_network(net)
+
+    def close(self):
+        if self.h:
+            B.made_free(self.h)
+            self.h = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    def logits(self, x):
+        N = x.shape[0]
+        out = torch.empty((N, self.net.D, self.net.C), dtype=torch.float32, device="cuda")
+        B.made_forward_logits(self.h, dev(x), N, out)
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+
+    def jacobi(self, noise, x_init=None, max_iters=0):
+        N = noise.shape[0]
+        x = torch.empty((N, self.net.D), dtype=torch.uint8, device="cuda")
+        it = torch.empty((N,), dtype=torch.int32, device="cuda")
+        B.jacobi_sample(self.h, dev(noise), N, None if x_init is None else dev(x_init), max_iters, x, it)
+        return x.cpu().numpy(), it.cpu().numpy()
+
+    def gs_jacobi(self, noise, block, x_init=None):
+        N = noise.shape[0]
+        x = torch.empty((N, self.net.D), dtype=torch.uint8, device="cuda")
+        it = torch.empty((N,), dtype=torch.int32, device="cuda")
+        B.gs_jacobi_sample(self.h, dev(noise), N, None if x_init is None else dev(x_init), block, x, it)
+        return x.cpu().numpy(), it.cpu().numpy()
+
+    def sequential(self, noise, mode):
+        N = noise.shape[0]
+        x = torch.empty((N, self.net.D), dtype=torch.uint8, device="cuda")
+        B.sequential_sample(self.h, dev(noise), N, mode, x)
+        return x.cpu().numpy()
+
+    def stats(self):
+        return B.made_last_stats(self.h)
+
+
+def assert_logits_close(z_gpu, z_ref, tol):
+    """max |z_gpu - z_ref| <= tol * rms(z_ref) (the logits of a random network are centred on 0, so
+    the error is scaled by the tensor's own size rather than element by element)."""
+    rms = max(1e-6, float(np.sqrt(np.mean(z_ref ** 2))))
+    err = float(np.abs(z_gpu - z_ref).max())
+    assert err <= tol * rms, f"logit error {err:.3e} > {tol} * rms {rms:.3e}"
+    return err / rms
+
+
+def assert_sample_parity(model_same, noise, x_gpu, x_oracle=None, margin_oracle=None):
+    """The library's symbols against the oracle.
+
+    1. Fixed-point certificate: at the library's own output x, every position must equal the
+       oracle's decision from x, unless the oracle's margin there is below MARGIN.
+    2. Wherever the oracle's own sequential run never came within MARGIN of a decision boundary,
+       the symbols must be identical.
+    Returns (exempt positions, fraction of samples that are bit-identical or None).
+    """
+    ok, margin = O.fixed_point_check(model_same, x_gpu, noise)
+    bad = ~ok & (margin >= MARGIN)
+    assert not bad.any(), f"{int(bad.sum())} positions differ from the oracle's decision with margin >= {MARGIN}"
+    exempt = int((~ok).sum())
+    frac = None
+    if x_oracle is not None:
+        same = (x_gpu == x_oracle).all(axis=1)
+        frac = float(same.mean())
+        if margin_oracle is not None:
+            clear = margin_oracle.min(axis=1) >= MARGIN
+            assert same[clear].all(), "a sample with every margin >= 1e-3 differs from the sequential oracle"
+    return exempt, frac

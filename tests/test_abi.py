@@ -1,0 +1,43 @@
+"""The C-ABI library loads without a GPU and exports every symbol the header declares."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2002_03629_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "jacobi_made.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:const\s+char\s*\*|int)\s+(\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_header_symbols_are_exported():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2002_03629_amd import build
+        build.build_library(verbose=False)
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS), names
+    L = ctypes.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_argument_errors_need_no_gpu():
+    L = binding.lib()
+    assert L.made_free(None) == binding.MADE_OK
+    assert L.made_init(None, None, None, None, None) == binding.MADE_ERR_ARG
+    out = ctypes.c_void_p()
+    assert L.made_init(None, None, None, None, ctypes.byref(out)) == binding.MADE_ERR_ARG
+    assert "NULL" in binding.made_last_error()
+    assert L.jacobi_sample(None, None, 4, None, 0, None, None, None) == binding.MADE_ERR_ARG
+    assert L.gs_jacobi_sample(None, None, 4, None, 0, None, None, None) == binding.MADE_ERR_ARG
+    assert L.sequential_sample(None, None, 4, 0, None, None) == binding.MADE_ERR_ARG
+    assert L.made_forward_logits(None, None, 4, None, None) == binding.MADE_ERR_ARG
+    with pytest.raises(binding.MadeError):
+        binding._check(L.made_last_stats(None, None, 4))

@@ -1,0 +1,44 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+A full sequential oracle run of the whole batch would take minutes, so the whole batch is graded
+with the one-pass fixed-point certificate (the triangular system has a unique solution) and a
+sub-batch is compared with the oracle's own sequential run symbol by symbol."""
+import numpy as np
+import pytest
+
+from oracle import made_oracle as O
+from paper_2002_03629_amd import synth as S
+
+from gpu_util import LOGIT_TOL, MARGIN, GpuModel, assert_logits_close, assert_sample_parity, oracle_models
+
+pytestmark = pytest.mark.gpu
+
+
+def test_cfg2_jacobi_and_gs_jacobi_full_batch():
+    w = S.workload("cfg2")
+    net = S.make_network(w)
+    exact, same = oracle_models(net)
+    noise = S.make_noise(w)
+    sub = 6
+    xs, mg = O.sequential_sample(same, noise[:sub])
+    xr, it_ref, _, _, mm = O.jacobi_reference(same, noise)
+    with GpuModel(net) as g:
+        x, it = g.jacobi(noise)
+        exempt, _ = assert_sample_parity(same, noise, x)
+        assert_sample_parity(same, noise[:sub], x[:sub], xs, mg)
+        assert (it[mm >= MARGIN] == it_ref[mm >= MARGIN]).all()
+        print(f"cfg2 jacobi: passes mean {it.mean():.2f} max {it.max()}, exempt positions {exempt}, "
+              f"identical to oracle jacobi: {(x == xr).all(axis=1).mean():.3f}")
+        z = g.logits(x[:16])
+        assert_logits_close(z, O.logits_all(exact, x[:16]), LOGIT_TOL["bf16"])
+        for block in w.block_sizes:
+            xb, itb = g.gs_jacobi(noise, block)
+            assert_sample_parity(same, noise, xb)
+            assert_sample_parity(same, noise[:sub], xb[:sub], xs, mg)
+            ref = O.gs_jacobi_reference(same, noise[:sub], block)
+            clear = ref[3] >= MARGIN
+            assert (itb[:sub][clear] == ref[1][clear]).all()
+        for mode in (0, 1):
+            xq = g.sequential(noise, mode)
+            assert_sample_parity(same, noise, xq)
+            assert_sample_parity(same, noise[:sub], xq[:sub], xs, mg)

@@ -1,0 +1,170 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs.  Symbols must be bit-exact except where the oracle's decision margin is below 1e-3;
+logits agree to 1e-4 (fp32 path) / 2e-2 (bf16 path) of the tensor's rms."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import made_oracle as O
+from paper_2002_03629_amd import binding as B
+from paper_2002_03629_amd import synth as S
+
+from gpu_util import LOGIT_TOL, MARGIN, GpuModel, assert_logits_close, assert_sample_parity, dev, oracle_models
+
+pytestmark = pytest.mark.gpu
+
+SMALL = ["cfg1", "small_f32", "small_bf16", "mid_bf16", "small_cat", "small_cat_f32"]
+
+
+def _symbols(w, rng, N):
+    hi = 2 if w.C == 1 else w.C
+    return rng.integers(0, hi, size=(N, w.D)).astype(np.uint8)
+
+
+@pytest.mark.parametrize("name", SMALL)
+def test_forward_logits(name):
+    w = S.workload(name)
+    net = S.make_network(w, with_bias=True)
+    exact, same = oracle_models(net)
+    x = _symbols(w, np.random.default_rng(1), w.N)
+    with GpuModel(net) as g:
+        z = g.logits(x)
+    assert_logits_close(z, O.logits_all(exact, x), LOGIT_TOL[w.dtype])
+    # against the oracle that rounds hidden activations the same way only fp32 summation order remains
+    assert_logits_close(z, O.logits_all(same, x), 2e-3 if w.dtype == "bf16" else 1e-4)
+
+
+@pytest.mark.parametrize("name", SMALL)
+def test_jacobi_matches_sequential_oracle(name):
+    w = S.workload(name)
+    net = S.make_network(w, with_bias=True)
+    _, same = oracle_models(net)
+    noise = S.make_noise(w)
+    xs, margins = O.sequential_sample(same, noise)
+    xr, it_ref, _, _, mm = O.jacobi_reference(same, noise)
+    with GpuModel(net) as g:
+        x, it = g.jacobi(noise)
+        st = g.stats()
+        x2, it2 = g.jacobi(noise)                       # determinism: same symbols and same counts
+        assert (x2 == x).all() and (it2 == it).all()
+        hi = 2 if w.C == 1 else w.C
+        for init in (np.full((w.N, w.D), hi - 1, np.uint8), _symbols(w, np.random.default_rng(2), w.N), xs):
+            xi, iti = g.jacobi(noise, init)
+            assert_sample_parity(same, noise, xi, xs, margins)
+            ref_i = O.jacobi_reference(same, noise, init)
+            clear = ref_i[4] >= MARGIN
+            assert (iti[clear] == ref_i[1][clear]).all()
+    assert_sample_parity(same, noise, x, xs, margins)
+    assert (it >= 1).all() and (it <= w.D).all()
+    clear = mm >= MARGIN
+    assert (it[clear] == it_ref[clear]).all()
+    assert st["passes"] == it.max() and st["sample_passes"] == it.sum()
+
+
+@pytest.mark.parametrize("name", SMALL)
+@pytest.mark.parametrize("mode", [0, 1])
+def test_sequential_matches_oracle(name, mode):
+    w = S.workload(name)
+    net = S.make_network(w, with_bias=True)
+    _, same = oracle_models(net)
+    noise = S.make_noise(w)
+    xs, margins = O.sequential_sample(same, noise)
+    with GpuModel(net) as g:
+        x = g.sequential(noise, mode)
+    assert_sample_parity(same, noise, x, xs, margins)
+
+
+@pytest.mark.parametrize("name", SMALL)
+def test_gs_jacobi_every_block_size(name):
+    w = S.workload(name)
+    net = S.make_network(w, with_bias=True)
+    _, same = oracle_models(net)
+    noise = S.make_noise(w)
+    xs, margins = O.sequential_sample(same, noise)
+    with GpuModel(net) as g:
+        for block in [1, 5, 16, 33, w.D - 1, w.D, w.D + 7]:
+            x, it = g.gs_jacobi(noise, block)
+            assert_sample_parity(same, noise, x, xs, margins)
+            xr, it_ref, per_block, mm = O.gs_jacobi_reference(same, noise, block)
+            clear = mm >= MARGIN
+            assert (it[clear] == it_ref[clear]).all(), (block, it, it_ref)
+            if block == 1:
+                assert (it == w.D).all()
+        init = _symbols(w, np.random.default_rng(3), w.N)
+        x, it = g.gs_jacobi(noise, 7, init)
+        assert_sample_parity(same, noise, x, xs, margins)
+        ref = O.gs_jacobi_reference(same, noise, 7, init)
+        assert (it[ref[3] >= MARGIN] == ref[1][ref[3] >= MARGIN]).all()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_section4_1_examples_on_gpu(dtype):
+    # Example 1: independent positions -> right after one pass, confirmed by the second
+    net = S.independent_network(40, 70, seed=9, dtype=dtype)
+    _, same = oracle_models(net)
+    u = S.uniform_noise(33, 40, 1)
+    xs, mg = O.sequential_sample(same, u)
+    with GpuModel(net) as g:
+        x, it = g.jacobi(u, 1 - xs)
+    assert_sample_parity(same, u, x, xs, mg)
+    assert (it[mg.min(axis=1) >= MARGIN] == 2).all()
+    # Example 2: everything hangs on position 1 -> right after two passes
+    net = S.first_only_network(40, 70, seed=10, dtype=dtype)
+    _, same = oracle_models(net)
+    xs, mg = O.sequential_sample(same, u)
+    ref = O.jacobi_reference(same, u)
+    with GpuModel(net) as g:
+        x, it = g.jacobi(u)
+    assert_sample_parity(same, u, x, xs, mg)
+    clear = ref[4] >= MARGIN
+    assert (it[clear] == ref[1][clear]).all() and it.max() <= 3
+    # Example 3: Markov chain -> exactly T passes, ended by the k = T clause
+    T = 45
+    net = S.copy_chain_network(T, dtype=dtype)
+    u = S.uniform_noise(5, T, 3) * 0.98 + 0.01
+    with GpuModel(net) as g:
+        x, it = g.jacobi(u)
+        assert (x == 1).all() and (it == T).all()
+        with pytest.raises(B.MadeError) as e:
+            g.jacobi(u, None, 10)
+        assert e.value.code == B.MADE_ERR_NOT_CONVERGED
+        x, it = g.gs_jacobi(u, 8)
+        assert (x == 1).all() and (it == T).all()
+        assert (g.sequential(u, 0) == 1).all() and (g.sequential(u, 1) == 1).all()
+
+
+def test_edge_cases():
+    w = S.workload("small_bf16")
+    net = S.make_network(w, with_bias=True)
+    _, same = oracle_models(net)
+    with GpuModel(net) as g:
+        # empty batch: nothing to do, nothing touched
+        empty = torch.empty((0, w.D), dtype=torch.uint8, device="cuda")
+        B.jacobi_sample(g.h, torch.empty((0, w.D), device="cuda"), 0, None, 0, empty, None)
+        B.gs_jacobi_sample(g.h, torch.empty((0, w.D), device="cuda"), 0, None, 4, empty, None)
+        B.sequential_sample(g.h, torch.empty((0, w.D), device="cuda"), 0, 0, empty)
+        # batch sizes around the 32-row tile, growing and shrinking (workspace reuse)
+        for N in (1, 31, 32, 33, 97, 5):
+            noise = S.make_noise(w, rep=N, N=N)
+            xs, mg = O.sequential_sample(same, noise)
+            x, it = g.jacobi(noise)
+            assert_sample_parity(same, noise, x, xs, mg)
+        # argument errors come back as status codes
+        noise = dev(S.make_noise(w))
+        x = torch.empty((w.N, w.D), dtype=torch.uint8, device="cuda")
+        for call in (lambda: B.gs_jacobi_sample(g.h, noise, w.N, None, 0, x, None),
+                     lambda: B.sequential_sample(g.h, noise, w.N, 2, x),
+                     lambda: B.jacobi_sample(g.h, None, w.N, None, 0, x, None),
+                     lambda: B.jacobi_sample(g.h, noise, -1, None, 0, x, None)):
+            with pytest.raises(B.MadeError) as e:
+                call()
+            assert e.value.code == B.MADE_ERR_ARG
+        # x_out may alias x_init
+        init = dev(np.random.default_rng(0).integers(0, 2, (w.N, w.D)).astype(np.uint8))
+        B.jacobi_sample(g.h, noise, w.N, init, 0, init, None)
+        xs, mg = O.sequential_sample(same, S.make_noise(w))
+        assert_sample_parity(same, S.make_noise(w), init.cpu().numpy(), xs, mg)
+    with pytest.raises(B.MadeError):
+        B.made_init(1, 1, [4], B.MADE_F32, [np.ones(4, np.int32)], [np.zeros((4, 1)), np.zeros((1, 4))])
+    with pytest.raises(B.MadeError):     # degree outside [1, D-1]
+        B.made_init(4, 1, [3], B.MADE_F32, [np.array([1, 2, 4], np.int32)], [np.zeros((3, 4)), np.zeros((4, 3))])

@@ -273,7 +273,7 @@ def test_jacobi_equals_sequential_any_init(name):
     inits = [None, np.full((w.N, w.D), hi - 1, np.uint8),
              np.random.default_rng(0).integers(0, hi, (w.N, w.D)).astype(np.uint8), xs]
     for i, init in enumerate(inits):
-        xj, iters, done, traj = O.jacobi_reference(model, noise, init, record=True)
+        xj, iters, done, traj, _ = O.jacobi_reference(model, noise, init, record=True)
         assert (xj == xs).all() and done.all()
         assert (iters <= w.D).all() and (iters >= 1).all()
         # induction hypothesis in the proof of Prop. 1: after k passes the first k positions are final
@@ -293,7 +293,7 @@ def test_jacobi_max_iters_reports_unconverged():
     net = S.copy_chain_network(12)
     model = _model(net)
     u = S.uniform_noise(3, 12, 5) * 0.98 + 0.01
-    x, iters, done, _ = O.jacobi_reference(model, u, None, max_iters=5)
+    x, iters, done, _, _ = O.jacobi_reference(model, u, None, max_iters=5)
     assert (iters == 5).all() and not done.any()
     assert (x[:, :5] == 1).all() and (x[:, 5:] == 0).all()
 
@@ -321,7 +321,7 @@ def test_example1_independent_one_iteration():
     u = S.uniform_noise(6, 20, 1)
     xs, _ = O.sequential_sample(model, u)
     init = 1 - xs                                     # start everywhere wrong
-    xj, iters, done, traj = O.jacobi_reference(model, u, init, record=True)
+    xj, iters, done, traj, _ = O.jacobi_reference(model, u, init, record=True)
     assert (xj == xs).all() and _first_exact(traj, xs) == [1] * 6
     assert (iters == 2).all()                         # one pass to reach it + one to confirm
 
@@ -333,7 +333,7 @@ def test_example2_skip_to_first_two_iterations():
     u = S.uniform_noise(16, 20, 2)
     xs, _ = O.sequential_sample(model, u)
     assert (xs[:, 0] == 1).all()
-    xj, iters, done, traj = O.jacobi_reference(model, u, None, record=True)
+    xj, iters, done, traj, _ = O.jacobi_reference(model, u, None, record=True)
     fe = _first_exact(traj, xs)
     assert (xj == xs).all() and max(fe) == 2 and (iters <= 3).all()
     assert (np.array(fe) + 1 == iters).all()
@@ -347,7 +347,7 @@ def test_example3_markov_chain_needs_T_iterations():
     u = S.uniform_noise(4, T, 3) * 0.98 + 0.01
     xs, _ = O.sequential_sample(model, u)
     assert (xs == 1).all()
-    xj, iters, done, traj = O.jacobi_reference(model, u, None, record=True)
+    xj, iters, done, traj, _ = O.jacobi_reference(model, u, None, record=True)
     assert (xj == xs).all() and (iters == T).all() and done.all()
     assert _first_exact(traj, xs) == [T] * 4
     for k in range(T + 1):                            # the 1 walks one position per pass
@@ -361,7 +361,7 @@ def test_critical_path_bound(skip):
     model = _model(net)
     u = S.uniform_noise(32, D, 4)
     xs, _ = O.sequential_sample(model, u)
-    xj, iters, done, traj = O.jacobi_reference(model, u, 1 - xs, record=True)
+    xj, iters, done, traj, _ = O.jacobi_reference(model, u, 1 - xs, record=True)
     assert (xj == xs).all()
     assert max(_first_exact(traj, xs)) <= math.ceil(D / skip)
 
@@ -374,9 +374,9 @@ def test_gs_jacobi_exact_for_every_block_size(name):
     model = _model(net)
     noise = S.make_noise(w)
     xs, _ = O.sequential_sample(model, noise)
-    xj, it_j, _, _ = O.jacobi_reference(model, noise)
+    xj, it_j, _, _, _ = O.jacobi_reference(model, noise)
     for B in [1, 2, 7, 16, w.D - 1, w.D, w.D + 5]:
-        xg, iters, per_block = O.gs_jacobi_reference(model, noise, B)
+        xg, iters, per_block, _ = O.gs_jacobi_reference(model, noise, B)
         parts = O.block_partition(w.D, B)
         assert parts[0][0] == 0 and parts[-1][1] == w.D
         assert all(p[1] == q[0] for p, q in zip(parts, parts[1:]))
@@ -396,7 +396,7 @@ def test_gs_jacobi_chain_uses_block_size_iterations():
     T = 12
     model = _model(S.copy_chain_network(T))
     u = S.uniform_noise(2, T, 3) * 0.98 + 0.01
-    x, iters, per_block = O.gs_jacobi_reference(model, u, 5)
+    x, iters, per_block, _ = O.gs_jacobi_reference(model, u, 5)
     assert (x == 1).all() and (per_block == np.array([5, 5, 2])[None, :]).all()
 
 
