@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: Jacobi sampling (Algorithm 1) of the MNIST-shaped
+binary MADE (D = 784, 2 x 2000 hidden, bf16, batch 128), synthetic seeded weights and noise.
+
+One "step" = one jacobi_sample call on one batch whose noise is already resident in HBM: every
+pass of the whole masked network, the sampling epilogue, the per-sample stop test and the final
+synchronisation are inside the timed region.  Prints ONE JSON line (see README).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3
+
+
+def cpu_baseline(w, net, noise, budget_s=20.0):
+    """The numpy oracle's sequential sampler, as it stands, on a bounded sub-batch."""
+    from oracle import made_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    model = O.build_model(net.D, net.C, net.degrees, net.W, net.b, "bf16" if net.dtype == "bf16" else None)
+    n = 2
+    t0 = time.perf_counter()
+    O.sequential_sample(model, noise[:n])
+    dt = time.perf_counter() - t0
+    # grow the sample so that the timed run takes roughly budget_s, capped at the batch
+    n2 = int(min(noise.shape[0], max(n, n * budget_s / max(dt, 1e-3) * 0.5)))
+    t0 = time.perf_counter()
+    xs, _ = O.sequential_sample(model, noise[:n2])
+    dt = time.perf_counter() - t0
+    return {"value": n2 / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"oracle sequential_sample (numpy fp64, bf16-rounded activations) on {n2} of {noise.shape[0]} "
+                      f"samples of one batch, {dt:.1f} s"}, xs, n2
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip sequential / GS-Jacobi side measurements")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (samples are independent systems; see DESIGN.md "
+              "for how the path would shard). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2002_03629_amd import binding as B
+    from paper_2002_03629_amd import synth as S
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    w = S.workload(args.workload)
+    net = S.make_network(w)
+    model = B.model_from_network(net)
+    n_layers = len(net.hidden) + 1
+    nnz = B.made_layer_nnz(model, n_layers)
+    N, D = w.N, w.D
+
+    n_noise = min(args.steps, 32)
+    noises_host = [S.make_noise(w, rep=r) for r in range(n_noise)]
+    noises = [torch.from_numpy(a).cuda() for a in noises_host]
+    x = torch.empty((N, D), dtype=torch.uint8, device="cuda")
+    iters = torch.empty((N,), dtype=torch.int32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        B.jacobi_sample(model, noises[i % n_noise], N, None, 0, x, iters, stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    # ---- timed region (events off): whole-call throughput
+    it_sum, it_max, sample_passes, passes = 0.0, 0, 0, 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    # ---- same region again with per-layer HIP events on the launch stream (roofline of the dominant kernel)
+    B.made_set_profiling(model, True)
+    layer_ms = np.zeros(n_layers)
+    layer_launches = np.zeros(n_layers, dtype=np.int64)
+    layer_flops = np.zeros(n_layers)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+        ms, cnt = B.made_last_profile(model, n_layers)
+        st = B.made_last_stats(model)
+        layer_ms += ms
+        layer_launches += np.array(cnt)
+        layer_flops += 2.0 * np.array(nnz, dtype=np.float64) * st["sample_passes"]
+        sample_passes += st["sample_passes"]
+        passes += st["passes"]
+        itc = iters.cpu().numpy()
+        it_sum += itc.mean()
+        it_max = max(it_max, int(itc.max()))
+    torch.cuda.synchronize()
+    elapsed_prof = time.perf_counter() - t0
+    B.made_set_profiling(model, False)
+
+    dom = int(np.argmax(layer_ms))
+    dom_avg_us = layer_ms[dom] / max(1, layer_launches[dom]) * 1e3
+    achieved = layer_flops[dom] / (layer_ms[dom] * 1e-3) / 1e12 if layer_ms[dom] > 0 else 0.0
+    peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_F32_TFLOPS
+    layer_name = (f"masked_layer_kernel layer {dom} ({'output+sampling epilogue' if dom == n_layers - 1 else 'hidden'})")
+
+    result = {
+        "metric": "samples/s (Jacobi vs sequential, same output); iters to converge; MFMA util",
+        "value": N * args.steps / elapsed,
+        "unit": "samples/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: MADE D={D} hidden={w.hidden} C={w.C} batch={N} Jacobi (Algorithm 1), "
+                               f"seeded N(0,1/fan_in) weights, random degrees, fixed U(0,1) noise"},
+        "iters_mean": it_sum / args.steps,
+        "iters_max": it_max,
+        "passes_per_step": passes / args.steps,
+        "roofline": {
+            "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+            "traffic": None, "kernel": layer_name, "avg_launch_us": dom_avg_us,
+            "launches": int(layer_launches[dom]),
+            "per_layer_avg_us": [float(m / max(1, c) * 1e3) for m, c in zip(layer_ms, layer_launches)],
+            "note": "algorithmic flops = 2*nnz(W*mask) per active sample per pass; durations from HIP events "
+                    "around each launch on the launch stream (second pass over the same steps)",
+        },
+        "whole_call_tflops": 2.0 * sum(nnz) * sample_passes / elapsed_prof / 1e12,
+        "ms_per_step_with_events": elapsed_prof / args.steps * 1e3,
+    }
+
+    # ---- side measurements: on-GPU sequential sampler (speedup denominator) and GS-Jacobi
+    x_jac = None
+    if not args.no_extras:
+        xq = torch.empty_like(x)
+        B.jacobi_sample(model, noises[0], N, None, 0, x, iters, stream)
+        torch.cuda.synchronize()
+        x_jac = x.clone()
+        extras = {}
+        for mode, name in ((0, "sequential_whole_network"), (1, "sequential_lean")):
+            B.sequential_sample(model, noises[0], N, mode, xq, stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            reps = 3
+            for _ in range(reps):
+                B.sequential_sample(model, noises[0], N, mode, xq, stream)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / reps
+            extras[name] = {"samples_per_s": N / dt, "ms_per_batch": dt * 1e3,
+                            "same_output_as_jacobi": bool(torch.equal(xq, x_jac)),
+                            "jacobi_speedup": (N * args.steps / elapsed) / (N / dt)}
+        for blk in (w.block_sizes or []):
+            B.gs_jacobi_sample(model, noises[0], N, None, blk, xq, iters, stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            reps = 5
+            for _ in range(reps):
+                B.gs_jacobi_sample(model, noises[0], N, None, blk, xq, iters, stream)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / reps
+            itc = iters.cpu().numpy()
+            st = B.made_last_stats(model)
+            extras[f"gs_jacobi_B{blk}"] = {"samples_per_s": N / dt, "ms_per_batch": dt * 1e3,
+                                           "iters_mean": float(itc.mean()), "iters_max": int(itc.max()),
+                                           "batch_passes": int(st["passes"]),
+                                           "same_output_as_jacobi": bool(torch.equal(xq, x_jac))}
+        result["extras"] = extras
+
+    if not args.no_cpu_baseline:
+        base, xs, n2 = cpu_baseline(w, net, noises_host[0])
+        result["cpu_baseline"] = base
+        if x_jac is not None:
+            result["cpu_baseline"]["gpu_matches_oracle_on_sample"] = bool(
+                np.array_equal(x_jac[:n2].cpu().numpy(), xs))
+    else:
+        result["cpu_baseline"] = None
+
+    B.made_free(model)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

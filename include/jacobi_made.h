@@ -133,6 +133,22 @@ int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, const uint8_t
  */
 int made_last_stats(const made_model* m, int64_t* out, int32_t n);
 
+/*
+ * made_set_profiling -- when enabled, every masked-layer launch of the *_sample calls is bracketed by
+ * HIP events on the caller's stream; made_last_profile then returns, per layer (0..L-1 hidden, L =
+ * output layer incl. its sampling epilogue), the summed duration in milliseconds and the number of
+ * launches of the most recent *_sample call.  n must be L+1.  Off by default (events cost time).
+ */
+int made_set_profiling(made_model* m, int32_t enable);
+int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_t n);
+
+/*
+ * made_layer_nnz -- number of visible (mask = 1) weights of each of the L+1 layers: one pass over one
+ * sample costs 2 * sum(nnz) floating-point operations, the algorithmic work of one evaluation of all
+ * h_t (Section 5.3.1).  n must be L+1.
+ */
+int made_layer_nnz(const made_model* m, int64_t* nnz, int32_t n);
+
 /* made_last_error -- message of the calling thread's most recent failure ("" if none). */
 const char* made_last_error(void);
 

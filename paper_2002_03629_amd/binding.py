@@ -18,7 +18,8 @@ MADE_OK, MADE_ERR_ARG, MADE_ERR_NOMEM, MADE_ERR_HIP, MADE_ERR_NOT_CONVERGED = 0,
 MADE_F32, MADE_BF16 = 0, 1
 
 EXPORTS = ["made_init", "made_free", "made_forward_logits", "sequential_sample", "jacobi_sample",
-           "gs_jacobi_sample", "made_last_stats", "made_last_error"]
+           "gs_jacobi_sample", "made_last_stats", "made_set_profiling", "made_last_profile", "made_layer_nnz",
+           "made_last_error"]
 
 
 class MadeError(RuntimeError):
@@ -42,6 +43,9 @@ def lib() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2002_03629_amd.build` "
                                "(there is no CPU fallback)")
+        # Device pointers and streams come from torch, so the library must run on the very HIP runtime
+        # torch has loaded: import torch first, then the loader resolves libamdhip64.so.7 to that copy.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp, i32, i64p = C.c_void_p, C.c_int32, C.POINTER(C.c_int64)
         L.made_init.argtypes = [C.POINTER(made_config), C.POINTER(C.POINTER(C.c_int32)),
@@ -52,6 +56,9 @@ def lib() -> C.CDLL:
         L.jacobi_sample.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
         L.gs_jacobi_sample.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
         L.made_last_stats.argtypes = [vp, i64p, i32]
+        L.made_set_profiling.argtypes = [vp, i32]
+        L.made_last_profile.argtypes = [vp, C.POINTER(C.c_double), i64p, i32]
+        L.made_layer_nnz.argtypes = [vp, i64p, i32]
         L.made_last_error.argtypes = []
         L.made_last_error.restype = C.c_char_p
         for name in EXPORTS[:-1]:
@@ -153,6 +160,24 @@ def made_last_stats(model: int) -> dict:
     buf = (C.c_int64 * 4)()
     _check(lib().made_last_stats(model, buf, 4))
     return {"passes": buf[0], "sample_passes": buf[1], "kernels": buf[2], "host_waits": buf[3]}
+
+
+def made_set_profiling(model: int, enable: bool) -> None:
+    _check(lib().made_set_profiling(model, 1 if enable else 0))
+
+
+def made_last_profile(model: int, n_layers: int):
+    """(ms[n_layers], launches[n_layers]) of the most recent *_sample call; n_layers = L + 1."""
+    ms = (C.c_double * n_layers)()
+    cnt = (C.c_int64 * n_layers)()
+    _check(lib().made_last_profile(model, ms, cnt, n_layers))
+    return list(ms), list(cnt)
+
+
+def made_layer_nnz(model: int, n_layers: int) -> List[int]:
+    buf = (C.c_int64 * n_layers)()
+    _check(lib().made_layer_nnz(model, buf, n_layers))
+    return list(buf)
 
 
 def model_from_network(net) -> int:

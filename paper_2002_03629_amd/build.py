@@ -19,9 +19,9 @@ FLAGS = [
 ]
 
 
-def build_library(verbose: bool = True) -> str:
+def build_library(verbose: bool = True, out_path: str = LIB_PATH, defines=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB_PATH]
+    cmd = [hipcc] + FLAGS + ["-D" + d for d in defines] + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", out_path]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -30,7 +30,7 @@ def build_library(verbose: bool = True) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
-    return LIB_PATH
+    return out_path
 
 
 if __name__ == "__main__":

@@ -10,6 +10,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -77,9 +78,10 @@ struct Workspace {
   int* changed = nullptr;
   int* iters = nullptr;
   int* flags = nullptr;
-  int* h_pin = nullptr;              // pinned host mirror of active counts, one slot per pass
+  int* done_ctr = nullptr;           // workgroups-finished counter of the pass's last kernel
+  volatile int* h_pin = nullptr;     // pinned, device-visible host words: [0] flags copy, [1 + i] active count after pass i
+  int* d_pin = nullptr;              // the same memory as the device addresses it
   int h_pin_len = 0;
-  hipEvent_t ev[2] = {nullptr, nullptr};
 };
 
 struct made_model {
@@ -91,6 +93,13 @@ struct made_model {
   std::vector<std::vector<int>> cnt_lt;
   Workspace ws;
   int64_t stats[4] = {0, 0, 0, 0};
+  // optional per-layer timing with HIP events on the caller's stream
+  bool profiling = false;
+  std::vector<hipEvent_t> ev_pool;            // pairs: [2i] before, [2i+1] after a layer launch
+  std::vector<int> ev_layer;                  // layer index of pair i in the current call
+  std::vector<double> prof_ms;                // [L+1] summed duration of that layer's launches, last call
+  std::vector<int64_t> prof_launches;         // [L+1]
+  std::vector<int64_t> nnz;                   // [L+1] visible (mask = 1) weights per layer
 };
 
 static size_t elem_size(const made_model* m) { return m->dtype == MADE_BF16 ? 2 : 4; }
@@ -112,12 +121,12 @@ static void free_workspace(Workspace& w) {
   for (int i = 0; i < 2; ++i) {
     if (w.rows[i]) (void)hipFree(w.rows[i]);
     if (w.n_rows[i]) (void)hipFree(w.n_rows[i]);
-    if (w.ev[i]) (void)hipEventDestroy(w.ev[i]);
   }
+  if (w.done_ctr) (void)hipFree(w.done_ctr);
   if (w.changed) (void)hipFree(w.changed);
   if (w.iters) (void)hipFree(w.iters);
   if (w.flags) (void)hipFree(w.flags);
-  if (w.h_pin) (void)hipHostFree(w.h_pin);
+  if (w.h_pin) (void)hipHostFree((void*)w.h_pin);
   w = Workspace();
 }
 
@@ -145,13 +154,16 @@ static int ensure_workspace(made_model* m, int N, bool need_z) {
   }
   for (int i = 0; i < 2; ++i) {
     HIP_TRY(hipMalloc((void**)&w.rows[i], (size_t)n_pad * sizeof(int)));
+    HIP_TRY(hipMemset(w.rows[i], 0, (size_t)n_pad * sizeof(int)));   // kernels may read past the active count
     HIP_TRY(hipMalloc((void**)&w.n_rows[i], sizeof(int)));
-    HIP_TRY(hipEventCreateWithFlags(&w.ev[i], hipEventDisableTiming));
   }
+  HIP_TRY(hipMalloc((void**)&w.done_ctr, sizeof(int)));
+  HIP_TRY(hipMemset(w.done_ctr, 0, sizeof(int)));
   HIP_TRY(hipMalloc((void**)&w.changed, (size_t)n_pad * sizeof(int)));
   HIP_TRY(hipMalloc((void**)&w.iters, (size_t)n_pad * sizeof(int)));
   HIP_TRY(hipMalloc((void**)&w.flags, sizeof(int)));
-  HIP_TRY(hipHostMalloc((void**)&w.h_pin, (size_t)need_pin * sizeof(int), hipHostMallocDefault));
+  HIP_TRY(hipHostMalloc((void**)&w.h_pin, (size_t)need_pin * sizeof(int), hipHostMallocMapped));
+  HIP_TRY(hipHostGetDevicePointer((void**)&w.d_pin, (void*)w.h_pin, 0));
   w.h_pin_len = need_pin;
   w.N_cap = cap;
   return MADE_OK;
@@ -165,6 +177,7 @@ extern "C" int made_free(made_model* m) {
     if (l.tile_kend) (void)hipFree(l.tile_kend);
   }
   free_workspace(m->ws);
+  for (hipEvent_t e : m->ev_pool) (void)hipEventDestroy(e);
   delete m;
   return MADE_OK;
 }
@@ -174,6 +187,26 @@ extern "C" const char* made_last_error(void) { return g_last_error.c_str(); }
 extern "C" int made_last_stats(const made_model* m, int64_t* out, int32_t n) {
   if (!m || !out || n < 0) return fail(MADE_ERR_ARG, "made_last_stats: NULL argument");
   for (int i = 0; i < n && i < 4; ++i) out[i] = m->stats[i];
+  return MADE_OK;
+}
+
+extern "C" int made_set_profiling(made_model* m, int32_t enable) {
+  if (!m) return fail(MADE_ERR_ARG, "made_set_profiling: model is NULL");
+  m->profiling = enable != 0;
+  return MADE_OK;
+}
+
+extern "C" int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_t n) {
+  if (!m || !ms || !launches) return fail(MADE_ERR_ARG, "made_last_profile: NULL argument");
+  if (n != m->L + 1) return fail(MADE_ERR_ARG, "made_last_profile: n=%d, the model has %d layers", n, m->L + 1);
+  for (int i = 0; i < n; ++i) { ms[i] = m->prof_ms[i]; launches[i] = m->prof_launches[i]; }
+  return MADE_OK;
+}
+
+extern "C" int made_layer_nnz(const made_model* m, int64_t* nnz, int32_t n) {
+  if (!m || !nnz) return fail(MADE_ERR_ARG, "made_layer_nnz: NULL argument");
+  if (n != m->L + 1) return fail(MADE_ERR_ARG, "made_layer_nnz: n=%d, the model has %d layers", n, m->L + 1);
+  for (int i = 0; i < n; ++i) nnz[i] = m->nnz[i];
   return MADE_OK;
 }
 
@@ -257,6 +290,7 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
         else
           klen[j] = (int)(std::upper_bound(in_deg.begin(), in_deg.end(), out_deg[j]) - in_deg.begin());
       }
+      m->nnz.push_back(std::accumulate(klen.begin(), klen.end(), (int64_t)0));
       const int kc = chunk_elems(m);
       ly.h_tile_kend.assign(ly.n_tiles, 0);
       for (int j = 0; j < ly.out_dim; ++j) {
@@ -305,6 +339,8 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
     made_free(m);
     return rc;
   }
+  m->prof_ms.assign(L + 1, 0.0);
+  m->prof_launches.assign(L + 1, 0);
   *out = m;
   return MADE_OK;
 }
@@ -322,19 +358,53 @@ struct SampleIO {          // what the sampling epilogue reads and writes
   const float* noise;
   uint8_t* x;
   int t_lo, t_hi;
+  RetireArgs retire;       // retire.enabled = 0: no stop test after this pass (sequential sampling)
 };
 
 template <typename T, int EPI>
-static void launch_layer_t(const LayerArgs& a, int n_tiles, int row_tiles, hipStream_t s) {
-  hipLaunchKernelGGL((masked_layer_kernel<T, EPI>), dim3(n_tiles, row_tiles), dim3(256), 0, s, a);
+static void launch_layer_t(LayerArgs a, int n_tiles, int row_tiles, hipStream_t s) {
+  a.n_launch_tiles = n_tiles;
+  a.row_tiles = row_tiles;
+  const int groups = (n_tiles + XCDS - 1) / XCDS;     // tile groups of 8, one tile per XCD
+  hipLaunchKernelGGL((masked_layer_kernel<T, EPI>), dim3(groups * XCDS * row_tiles), dim3(NW * 64), 0, s, a);
+}
+
+static void prof_mark(made_model* m, int layer, bool after, hipStream_t s) {
+  if (!m->profiling) return;
+  const size_t pair = after ? m->ev_layer.size() - 1 : m->ev_layer.size();
+  if (!after) {
+    while (m->ev_pool.size() < 2 * (pair + 1)) {
+      hipEvent_t e = nullptr;
+      if (hipEventCreate(&e) != hipSuccess) { m->profiling = false; return; }
+      m->ev_pool.push_back(e);
+    }
+    m->ev_layer.push_back(layer);
+  }
+  (void)hipEventRecord(m->ev_pool[2 * pair + (after ? 1 : 0)], s);
+}
+
+// after the stream has been synchronised: fold the event pairs of this call into per-layer sums
+static void prof_collect(made_model* m) {
+  std::fill(m->prof_ms.begin(), m->prof_ms.end(), 0.0);
+  std::fill(m->prof_launches.begin(), m->prof_launches.end(), 0);
+  for (size_t i = 0; i < m->ev_layer.size(); ++i) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, m->ev_pool[2 * i], m->ev_pool[2 * i + 1]) == hipSuccess) {
+      m->prof_ms[m->ev_layer[i]] += ms;
+      m->prof_launches[m->ev_layer[i]]++;
+    }
+  }
+  m->ev_layer.clear();
 }
 
 template <int EPI>
-static void launch_layer(const made_model* m, const LayerArgs& a, int n_tiles, int row_tiles, hipStream_t s) {
+static void launch_layer(made_model* m, int layer, const LayerArgs& a, int n_tiles, int row_tiles, hipStream_t s) {
+  prof_mark(m, layer, false, s);
   if (m->dtype == MADE_BF16)
     launch_layer_t<bf16_t, EPI>(a, n_tiles, row_tiles, s);
   else
     launch_layer_t<float, EPI>(a, n_tiles, row_tiles, s);
+  prof_mark(m, layer, true, s);
 }
 
 static LayerArgs base_args(const made_model* m, int l, const void* A, const RowSet& rs) {
@@ -371,7 +441,7 @@ static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, in
     if (unit_limit && unit_limit[l] >= 0) tiles = std::min(tiles, (unit_limit[l] + TILE - 1) / TILE);
     if (in_limit >= 0) a.k_cap = std::min(ly.in_pad, round_up(in_limit, kc));
     if (tiles > 0) {
-      launch_layer<EPI_RELU>(m, a, tiles, row_tiles, s);
+      launch_layer<EPI_RELU>(m, l, a, tiles, row_tiles, s);
       m->stats[2]++;
     }
     in_limit = (unit_limit && unit_limit[l] >= 0) ? unit_limit[l] : -1;
@@ -404,23 +474,24 @@ static int run_output_sample(made_model* m, const RowSet& rs, const SampleIO& io
     a.D = m->D;
     a.t_lo = io.t_lo;
     a.t_hi = io.t_hi;
-    launch_layer<EPI_BERNOULLI>(m, a, tile_hi - tile_lo, row_tiles, s);
+    a.retire = io.retire;
+    launch_layer<EPI_BERNOULLI>(m, m->L, a, tile_hi - tile_lo, row_tiles, s);
     m->stats[2]++;
   } else {
     a.out = m->ws.zbuf;
     a.ldo = m->D * C;
-    launch_layer<EPI_LOGITS>(m, a, tile_hi - tile_lo, row_tiles, s);
+    launch_layer<EPI_LOGITS>(m, m->L, a, tile_hi - tile_lo, row_tiles, s);
     const int span = io.t_hi - io.t_lo;
     const long long waves = (long long)rs.n_rows * span;
     const int blocks = (int)((waves + 3) / 4);
     if (m->dtype == MADE_BF16)
       hipLaunchKernelGGL((gumbel_argmax_kernel<bf16_t>), dim3(blocks), dim3(256), 0, s, m->ws.zbuf, m->D * C, io.noise,
                          io.x, (bf16_t*)m->ws.enc, m->layers[0].in_pad, m->ws.changed, rs.rows, rs.n_rows_ptr,
-                         rs.n_rows, m->D, C, io.t_lo, io.t_hi);
+                         rs.n_rows, m->D, C, io.t_lo, io.t_hi, io.retire);
     else
       hipLaunchKernelGGL((gumbel_argmax_kernel<float>), dim3(blocks), dim3(256), 0, s, m->ws.zbuf, m->D * C, io.noise,
                          io.x, (float*)m->ws.enc, m->layers[0].in_pad, m->ws.changed, rs.rows, rs.n_rows_ptr,
-                         rs.n_rows, m->D, C, io.t_lo, io.t_hi);
+                         rs.n_rows, m->D, C, io.t_lo, io.t_hi, io.retire);
     m->stats[2] += 2;
   }
   HIP_TRY(hipGetLastError());
@@ -443,7 +514,8 @@ static int launch_init_state(made_model* m, const uint8_t* x_init, uint8_t* x, i
 
 static int launch_reset_rows(made_model* m, int which, int N, bool clear_iters, hipStream_t s) {
   hipLaunchKernelGGL(reset_rows_kernel, dim3((N + 255) / 256), dim3(256), 0, s, m->ws.rows[which], m->ws.n_rows[which], N,
-                     m->ws.changed, clear_iters ? m->ws.iters : nullptr, clear_iters ? m->ws.flags : nullptr);
+                     m->ws.changed, clear_iters ? m->ws.iters : nullptr, clear_iters ? m->ws.flags : nullptr,
+                     m->ws.done_ctr);
   m->stats[2]++;
   HIP_TRY(hipGetLastError());
   return MADE_OK;
@@ -465,6 +537,8 @@ extern "C" int made_forward_logits(made_model* m, const uint8_t* x, int32_t N, f
   TRY(check_call(m, x, N, logits, "made_forward_logits"));
   if (N == 0) return MADE_OK;
   hipStream_t s = (hipStream_t)stream;
+  const bool was_profiling = m->profiling;
+  m->profiling = false;  // this call does not wait for the stream, so it cannot read event times
   TRY(ensure_workspace(m, N, false));
   TRY(launch_init_state(m, x, nullptr, N, s));
   RowSet rs{nullptr, nullptr, N};
@@ -472,7 +546,8 @@ extern "C" int made_forward_logits(made_model* m, const uint8_t* x, int32_t N, f
   LayerArgs a = base_args(m, m->L, m->ws.act[m->L - 1], rs);
   a.out = logits;
   a.ldo = m->D * m->C;
-  launch_layer<EPI_LOGITS>(m, a, m->layers[m->L].n_tiles, (N + TILE - 1) / TILE, s);
+  launch_layer<EPI_LOGITS>(m, m->L, a, m->layers[m->L].n_tiles, (N + TILE - 1) / TILE, s);
+  m->profiling = was_profiling;
   HIP_TRY(hipGetLastError());
   return MADE_OK;
 }
@@ -484,13 +559,14 @@ extern "C" int sequential_sample(made_model* m, const float* noise, int32_t N, i
   if (N == 0) return MADE_OK;
   hipStream_t s = (hipStream_t)stream;
   memset(m->stats, 0, sizeof m->stats);
+  m->ev_layer.clear();
   TRY(ensure_workspace(m, N, true));
   TRY(launch_init_state(m, nullptr, x_out, N, s));
   TRY(launch_reset_rows(m, 0, N, true, s));
   RowSet rs{nullptr, nullptr, N};
   std::vector<int> limit(m->L);
   for (int p = 0; p < m->D; ++p) {  // p = 0-based position, its 1-based index is t = p + 1
-    SampleIO io{noise, x_out, p, p + 1};
+    SampleIO io{noise, x_out, p, p + 1, RetireArgs{}};
     if (mode == 0) {
       TRY(run_hidden(m, rs, nullptr, -1, s));
       TRY(run_output_sample(m, rs, io, true, -1, s));
@@ -505,12 +581,27 @@ extern "C" int sequential_sample(made_model* m, const float* noise, int32_t N, i
   }
   HIP_TRY(hipStreamSynchronize(s));
   m->stats[3]++;
+  prof_collect(m);
   return MADE_OK;
 }
 
+// Wait (bounded) until the device has written the active count of pass-log slot `slot`.
+static int wait_slot(made_model* m, int slot, int* value) {
+  volatile int* p = &m->ws.h_pin[slot];
+  const auto t0 = std::chrono::steady_clock::now();
+  for (uint64_t spins = 0;; ++spins) {
+    const int v = *p;
+    if (v >= 0) { *value = v; return MADE_OK; }
+    if ((spins & 0xffff) == 0xffff &&
+        std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() > 30.0)
+      return fail(MADE_ERR_HIP, "device did not report the stop test of a pass within 30 s");
+  }
+}
+
 // Jacobi passes over positions [t_lo, t_hi) of the samples listed in rows[0], at most `cap` of them.
-// The host enqueues pass k + 1 before it waits for the active count after pass k, so the device never
-// idles on the stop test; a pass enqueued after the batch emptied finds zero active rows and does nothing.
+// The last workgroup of each pass writes the new active count into pinned host memory; the host enqueues
+// pass k + 1 before it looks at the count after pass k, so the device never idles on the stop test.  A pass
+// enqueued after the batch emptied finds zero active rows and does nothing.
 // Active counts land in the pinned log h_pin[1 + i] (i = running pass index of the whole call).
 static int iterate_block(made_model* m, const float* noise, uint8_t* x, int N, int t_lo, int t_hi, int cap,
                          bool flag_unconverged, const int* hidden_limit, int in_limit, int out_k_limit,
@@ -520,23 +611,29 @@ static int iterate_block(made_model* m, const float* noise, uint8_t* x, int N, i
     const int in = (k - 1) & 1, out = k & 1;
     const int slot = 1 + (int)first_of_block.size();
     if (slot >= w.h_pin_len) return fail(MADE_ERR_HIP, "internal: pass log overflow");
+    w.h_pin[slot] = -1;
     RowSet rs{w.rows[in], w.n_rows[in], N};
-    SampleIO io{noise, x, t_lo, t_hi};
+    SampleIO io{noise, x, t_lo, t_hi, RetireArgs{}};
+    io.retire.rows_in = w.rows[in];
+    io.retire.n_in = w.n_rows[in];
+    io.retire.rows_out = w.rows[out];
+    io.retire.n_out = w.n_rows[out];
+    io.retire.changed = w.changed;
+    io.retire.iters = w.iters;
+    io.retire.flags = w.flags;
+    io.retire.done_ctr = w.done_ctr;
+    io.retire.host_slot = w.d_pin + slot;
+    io.retire.last_pass = (k == cap);
+    io.retire.flag_unconverged = flag_unconverged;
+    io.retire.enabled = 1;
     TRY(run_hidden(m, rs, hidden_limit, in_limit, s));
     TRY(run_output_sample(m, rs, io, false, out_k_limit, s));
-    hipLaunchKernelGGL(retire_kernel, dim3(1), dim3(256), 0, s, w.rows[in], w.n_rows[in], w.rows[out], w.n_rows[out],
-                       w.changed, w.iters, (int)(k == cap), (int)flag_unconverged, w.flags);
-    m->stats[2]++;
-    HIP_TRY(hipGetLastError());
-    HIP_TRY(hipMemcpyAsync(&w.h_pin[slot], w.n_rows[out], sizeof(int), hipMemcpyDeviceToHost, s));
     first_of_block.push_back(k == 1);
-    if (k < cap) {
-      HIP_TRY(hipEventRecord(w.ev[out], s));
-      if (k >= 2) {  // result of pass k - 1, while pass k is already queued
-        HIP_TRY(hipEventSynchronize(w.ev[in]));
-        m->stats[3]++;
-        if (w.h_pin[slot - 1] == 0) break;
-      }
+    if (k >= 2 && k < cap) {  // result of pass k - 1, while pass k is already queued
+      int left = 0;
+      TRY(wait_slot(m, slot - 1, &left));
+      m->stats[3]++;
+      if (left == 0) break;
     }
   }
   return MADE_OK;
@@ -546,9 +643,10 @@ static int finish_call(made_model* m, int N, int32_t* iters_out, bool check_flag
                        const std::vector<char>& first_of_block, hipStream_t s) {
   Workspace& w = m->ws;
   if (iters_out) HIP_TRY(hipMemcpyAsync(iters_out, w.iters, (size_t)N * sizeof(int), hipMemcpyDeviceToDevice, s));
-  if (check_flag) HIP_TRY(hipMemcpyAsync(&w.h_pin[0], w.flags, sizeof(int), hipMemcpyDeviceToHost, s));
+  if (check_flag) HIP_TRY(hipMemcpyAsync((void*)&w.h_pin[0], w.flags, sizeof(int), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipStreamSynchronize(s));
   m->stats[3]++;
+  prof_collect(m);
   int active_in = 0;
   for (size_t i = 0; i < first_of_block.size(); ++i) {
     if (first_of_block[i]) active_in = N;
@@ -569,6 +667,7 @@ extern "C" int jacobi_sample(made_model* m, const float* noise, int32_t N, const
   if (N == 0) return MADE_OK;
   hipStream_t s = (hipStream_t)stream;
   memset(m->stats, 0, sizeof m->stats);
+  m->ev_layer.clear();
   TRY(ensure_workspace(m, N, true));
   const int cap = (max_iters <= 0 || max_iters > m->D) ? m->D : max_iters;
   TRY(launch_init_state(m, x_init, x_out, N, s));
@@ -585,6 +684,7 @@ extern "C" int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, co
   if (N == 0) return MADE_OK;
   hipStream_t s = (hipStream_t)stream;
   memset(m->stats, 0, sizeof m->stats);
+  m->ev_layer.clear();
   TRY(ensure_workspace(m, N, true));
   TRY(launch_init_state(m, x_init, x_out, N, s));
   TRY(launch_reset_rows(m, 0, N, true, s));
