@@ -54,6 +54,8 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip sequential / GS-Jacobi side measurements")
+    ap.add_argument("--path", choices=["persistent", "layers"], default="persistent",
+                    help="persistent: one cooperative launch per call; layers: one launch per layer and pass")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (samples are independent systems; see DESIGN.md "
@@ -70,8 +72,11 @@ def main() -> int:
     w = S.workload(args.workload)
     net = S.make_network(w)
     model = B.model_from_network(net)
+    B.made_set_option(model, B.MADE_OPT_PERSISTENT, int(args.path == "persistent"))
     n_layers = len(net.hidden) + 1
     nnz = B.made_layer_nnz(model, n_layers)
+    n_slots = n_layers + 1                     # per-layer kernels + the persistent whole-call kernel
+    flops_per_sample_pass = 2.0 * np.array(list(nnz) + [sum(nnz)], dtype=np.float64)
     N, D = w.N, w.D
 
     n_noise = min(args.steps, 32)
@@ -99,18 +104,18 @@ def main() -> int:
 
     # ---- same region again with per-layer HIP events on the launch stream (roofline of the dominant kernel)
     B.made_set_profiling(model, True)
-    layer_ms = np.zeros(n_layers)
-    layer_launches = np.zeros(n_layers, dtype=np.int64)
-    layer_flops = np.zeros(n_layers)
+    layer_ms = np.zeros(n_slots)
+    layer_launches = np.zeros(n_slots, dtype=np.int64)
+    layer_flops = np.zeros(n_slots)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(i)
-        ms, cnt = B.made_last_profile(model, n_layers)
+        ms, cnt = B.made_last_profile(model, n_slots)
         st = B.made_last_stats(model)
         layer_ms += ms
         layer_launches += np.array(cnt)
-        layer_flops += 2.0 * np.array(nnz, dtype=np.float64) * st["sample_passes"]
+        layer_flops += flops_per_sample_pass * st["sample_passes"] * (np.array(cnt) > 0)
         sample_passes += st["sample_passes"]
         passes += st["passes"]
         itc = iters.cpu().numpy()
@@ -124,7 +129,11 @@ def main() -> int:
     dom_avg_us = layer_ms[dom] / max(1, layer_launches[dom]) * 1e3
     achieved = layer_flops[dom] / (layer_ms[dom] * 1e-3) / 1e12 if layer_ms[dom] > 0 else 0.0
     peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_F32_TFLOPS
-    layer_name = (f"masked_layer_kernel layer {dom} ({'output+sampling epilogue' if dom == n_layers - 1 else 'hidden'})")
+    if dom == n_layers:
+        layer_name = "persistent_sampler_kernel (all passes of a call: hidden layers, output layer + sampling, stop test)"
+    else:
+        layer_name = (f"masked_layer_kernel layer {dom} "
+                      f"({'output+sampling epilogue' if dom == n_layers - 1 else 'hidden'})")
 
     result = {
         "metric": "samples/s (Jacobi vs sequential, same output); iters to converge; MFMA util",
@@ -140,7 +149,8 @@ def main() -> int:
         "dtype": w.dtype,
         "data": "synthetic",
         "config": {"workload": f"{w.name}: MADE D={D} hidden={w.hidden} C={w.C} batch={N} Jacobi (Algorithm 1), "
-                               f"seeded N(0,1/fan_in) weights, random degrees, fixed U(0,1) noise"},
+                               f"seeded N(0,1/fan_in) weights, random degrees, fixed U(0,1) noise",
+                   "path": args.path},
         "iters_mean": it_sum / args.steps,
         "iters_max": it_max,
         "passes_per_step": passes / args.steps,
@@ -148,7 +158,7 @@ def main() -> int:
             "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
             "traffic": None, "kernel": layer_name, "avg_launch_us": dom_avg_us,
             "launches": int(layer_launches[dom]),
-            "per_layer_avg_us": [float(m / max(1, c) * 1e3) for m, c in zip(layer_ms, layer_launches)],
+            "per_slot_avg_us": [float(m / max(1, c) * 1e3) for m, c in zip(layer_ms, layer_launches)],
             "note": "algorithmic flops = 2*nnz(W*mask) per active sample per pass; durations from HIP events "
                     "around each launch on the launch stream (second pass over the same steps)",
         },

@@ -135,12 +135,23 @@ int made_last_stats(const made_model* m, int64_t* out, int32_t n);
 
 /*
  * made_set_profiling -- when enabled, every masked-layer launch of the *_sample calls is bracketed by
- * HIP events on the caller's stream; made_last_profile then returns, per layer (0..L-1 hidden, L =
- * output layer incl. its sampling epilogue), the summed duration in milliseconds and the number of
- * launches of the most recent *_sample call.  n must be L+1.  Off by default (events cost time).
+ * HIP events on the caller's stream; made_last_profile then returns the summed duration in milliseconds
+ * and the number of launches of the most recent *_sample call for: slots 0..L-1 the hidden layers, slot L
+ * the output layer incl. its sampling epilogue, slot L+1 the persistent whole-call kernel (see
+ * made_set_option).  n must be L+2.  Off by default (events cost time).
  */
 int made_set_profiling(made_model* m, int32_t enable);
 int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_t n);
+
+/*
+ * made_set_option -- execution choices that never change results.
+ *   MADE_OPT_PERSISTENT (default 0): 1 = serve jacobi_sample / gs_jacobi_sample of Bernoulli models with
+ *   batch <= 2048 from ONE cooperative launch that keeps a workgroup per CU resident and separates layers by
+ *   a grid-wide barrier; 0 = one kernel launch per layer and pass.  Same results either way; on MI355X the
+ *   per-layer launches are currently the faster of the two at batch 128, hence the default.
+ */
+enum { MADE_OPT_PERSISTENT = 1 };
+int made_set_option(made_model* m, int32_t option, int32_t value);
 
 /*
  * made_layer_nnz -- number of visible (mask = 1) weights of each of the L+1 layers: one pass over one

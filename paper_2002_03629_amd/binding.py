@@ -18,7 +18,8 @@ MADE_OK, MADE_ERR_ARG, MADE_ERR_NOMEM, MADE_ERR_HIP, MADE_ERR_NOT_CONVERGED = 0,
 MADE_F32, MADE_BF16 = 0, 1
 
 EXPORTS = ["made_init", "made_free", "made_forward_logits", "sequential_sample", "jacobi_sample",
-           "gs_jacobi_sample", "made_last_stats", "made_set_profiling", "made_last_profile", "made_layer_nnz",
+           "gs_jacobi_sample", "made_last_stats", "made_set_profiling", "made_last_profile", "made_set_option",
+           "made_layer_nnz",
            "made_last_error"]
 
 
@@ -59,6 +60,7 @@ def lib() -> C.CDLL:
         L.made_set_profiling.argtypes = [vp, i32]
         L.made_last_profile.argtypes = [vp, C.POINTER(C.c_double), i64p, i32]
         L.made_layer_nnz.argtypes = [vp, i64p, i32]
+        L.made_set_option.argtypes = [vp, i32, i32]
         L.made_last_error.argtypes = []
         L.made_last_error.restype = C.c_char_p
         for name in EXPORTS[:-1]:
@@ -166,11 +168,18 @@ def made_set_profiling(model: int, enable: bool) -> None:
     _check(lib().made_set_profiling(model, 1 if enable else 0))
 
 
-def made_last_profile(model: int, n_layers: int):
-    """(ms[n_layers], launches[n_layers]) of the most recent *_sample call; n_layers = L + 1."""
-    ms = (C.c_double * n_layers)()
-    cnt = (C.c_int64 * n_layers)()
-    _check(lib().made_last_profile(model, ms, cnt, n_layers))
+MADE_OPT_PERSISTENT = 1
+
+
+def made_set_option(model: int, option: int, value: int) -> None:
+    _check(lib().made_set_option(model, option, value))
+
+
+def made_last_profile(model: int, n_slots: int):
+    """(ms[n_slots], launches[n_slots]) of the most recent *_sample call; n_slots = L + 2."""
+    ms = (C.c_double * n_slots)()
+    cnt = (C.c_int64 * n_slots)()
+    _check(lib().made_last_profile(model, ms, cnt, n_slots))
     return list(ms), list(cnt)
 
 

@@ -61,11 +61,13 @@ static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 struct Layer {
   int in_dim = 0, out_dim = 0;   // real sizes
   int in_pad = 0, out_pad = 0;   // padded to multiples of 64 (zero filled)
+  int k_chunks = 0;              // in_pad / (elements per 128 bytes): K chunks per row group
   int n_tiles = 0;               // out_pad / 32
-  void* W = nullptr;             // device, [out_pad, in_pad] of T, mask applied, units sorted by degree
+  void* W = nullptr;             // device, out_pad x in_pad of T in fragment-major layout, mask applied, units sorted by degree
   float* bias = nullptr;         // device, [out_pad]
   int* tile_kend = nullptr;      // device, [n_tiles]
   std::vector<int> h_tile_kend;  // host copy
+  int* cnt_lt = nullptr;         // device, hidden layers only: [D + 2] prefix lengths by degree
 };
 
 struct Workspace {
@@ -79,6 +81,9 @@ struct Workspace {
   int* iters = nullptr;
   int* flags = nullptr;
   int* done_ctr = nullptr;           // workgroups-finished counter of the pass's last kernel
+  int n_pad = 0;
+  unsigned* bar = nullptr;           // persistent kernel: grid barrier counter
+  long long* dev_stats = nullptr;    // persistent kernel: [passes, sample-passes]
   volatile int* h_pin = nullptr;     // pinned, device-visible host words: [0] flags copy, [1 + i] active count after pass i
   int* d_pin = nullptr;              // the same memory as the device addresses it
   int h_pin_len = 0;
@@ -100,6 +105,8 @@ struct made_model {
   std::vector<double> prof_ms;                // [L+1] summed duration of that layer's launches, last call
   std::vector<int64_t> prof_launches;         // [L+1]
   std::vector<int64_t> nnz;                   // [L+1] visible (mask = 1) weights per layer
+  int persist_grid = 0;                       // workgroups of the persistent kernel (0 = not usable)
+  int use_persistent = 0;                     // made_set_option(MADE_OPT_PERSISTENT); off: measured slower, see header
 };
 
 static size_t elem_size(const made_model* m) { return m->dtype == MADE_BF16 ? 2 : 4; }
@@ -123,6 +130,8 @@ static void free_workspace(Workspace& w) {
     if (w.n_rows[i]) (void)hipFree(w.n_rows[i]);
   }
   if (w.done_ctr) (void)hipFree(w.done_ctr);
+  if (w.bar) (void)hipFree(w.bar);
+  if (w.dev_stats) (void)hipFree(w.dev_stats);
   if (w.changed) (void)hipFree(w.changed);
   if (w.iters) (void)hipFree(w.iters);
   if (w.flags) (void)hipFree(w.flags);
@@ -133,7 +142,7 @@ static void free_workspace(Workspace& w) {
 static int ensure_workspace(made_model* m, int N, bool need_z) {
   Workspace& w = m->ws;
   need_z = need_z && m->C > 1;
-  const int need_pin = m->D + 4;
+  const int need_pin = m->D + 8;
   if (N <= w.N_cap && (!need_z || w.zbuf) && w.h_pin_len >= need_pin) return MADE_OK;
   const int cap = std::max(N, w.N_cap);
   const bool had_z = w.zbuf != nullptr;
@@ -159,7 +168,10 @@ static int ensure_workspace(made_model* m, int N, bool need_z) {
   }
   HIP_TRY(hipMalloc((void**)&w.done_ctr, sizeof(int)));
   HIP_TRY(hipMemset(w.done_ctr, 0, sizeof(int)));
-  HIP_TRY(hipMalloc((void**)&w.changed, (size_t)n_pad * sizeof(int)));
+  HIP_TRY(hipMalloc((void**)&w.changed, (size_t)2 * n_pad * sizeof(int)));
+  w.n_pad = n_pad;
+  HIP_TRY(hipMalloc((void**)&w.bar, sizeof(unsigned)));
+  HIP_TRY(hipMalloc((void**)&w.dev_stats, 2 * sizeof(long long)));
   HIP_TRY(hipMalloc((void**)&w.iters, (size_t)n_pad * sizeof(int)));
   HIP_TRY(hipMalloc((void**)&w.flags, sizeof(int)));
   HIP_TRY(hipHostMalloc((void**)&w.h_pin, (size_t)need_pin * sizeof(int), hipHostMallocMapped));
@@ -175,6 +187,7 @@ extern "C" int made_free(made_model* m) {
     if (l.W) (void)hipFree(l.W);
     if (l.bias) (void)hipFree(l.bias);
     if (l.tile_kend) (void)hipFree(l.tile_kend);
+    if (l.cnt_lt) (void)hipFree(l.cnt_lt);
   }
   free_workspace(m->ws);
   for (hipEvent_t e : m->ev_pool) (void)hipEventDestroy(e);
@@ -198,9 +211,18 @@ extern "C" int made_set_profiling(made_model* m, int32_t enable) {
 
 extern "C" int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_t n) {
   if (!m || !ms || !launches) return fail(MADE_ERR_ARG, "made_last_profile: NULL argument");
-  if (n != m->L + 1) return fail(MADE_ERR_ARG, "made_last_profile: n=%d, the model has %d layers", n, m->L + 1);
+  if (n != m->L + 2) return fail(MADE_ERR_ARG, "made_last_profile: n=%d, expected L+2=%d", n, m->L + 2);
   for (int i = 0; i < n; ++i) { ms[i] = m->prof_ms[i]; launches[i] = m->prof_launches[i]; }
   return MADE_OK;
+}
+
+extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
+  if (!m) return fail(MADE_ERR_ARG, "made_set_option: model is NULL");
+  if (option == MADE_OPT_PERSISTENT) {
+    m->use_persistent = value != 0;
+    return MADE_OK;
+  }
+  return fail(MADE_ERR_ARG, "made_set_option: unknown option %d", option);
 }
 
 extern "C" int made_layer_nnz(const made_model* m, int64_t* nnz, int32_t n) {
@@ -264,6 +286,7 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
       ly.in_dim = (int)in_deg.size();
       ly.out_dim = is_out ? D * C : m->hidden[l];
       ly.in_pad = round_up(ly.in_dim, 64);
+      ly.k_chunks = ly.in_pad / chunk_elems(m);
       ly.out_pad = round_up(ly.out_dim, 64);
       ly.n_tiles = ly.out_pad / TILE;
 
@@ -306,11 +329,11 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
         const float* src = Wl + (size_t)perm[j] * ly.in_dim;
         const int kl = klen[j];
         if (m->dtype == MADE_BF16) {
-          uint16_t* dst = (uint16_t*)host.data() + (size_t)j * ly.in_pad;
-          for (int i = 0; i < kl; ++i) dst[i] = host_f32_to_bf16(src[perm_prev[i]]);
+          uint16_t* dst = (uint16_t*)host.data();
+          for (int i = 0; i < kl; ++i) dst[frag_offset<bf16_t>(j, i, ly.k_chunks)] = host_f32_to_bf16(src[perm_prev[i]]);
         } else {
-          float* dst = (float*)host.data() + (size_t)j * ly.in_pad;
-          for (int i = 0; i < kl; ++i) dst[i] = src[perm_prev[i]];
+          float* dst = (float*)host.data();
+          for (int i = 0; i < kl; ++i) dst[frag_offset<float>(j, i, ly.k_chunks)] = src[perm_prev[i]];
         }
       }
       std::vector<float> hb(ly.out_pad, 0.f);
@@ -324,6 +347,11 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
       if (he == hipSuccess) he = hipMalloc((void**)&ly.tile_kend, ly.n_tiles * sizeof(int));
       if (he == hipSuccess)
         he = hipMemcpy(ly.tile_kend, ly.h_tile_kend.data(), ly.n_tiles * sizeof(int), hipMemcpyHostToDevice);
+      if (he == hipSuccess && !is_out) {
+        he = hipMalloc((void**)&ly.cnt_lt, m->cnt_lt[l].size() * sizeof(int));
+        if (he == hipSuccess)
+          he = hipMemcpy(ly.cnt_lt, m->cnt_lt[l].data(), m->cnt_lt[l].size() * sizeof(int), hipMemcpyHostToDevice);
+      }
       if (he != hipSuccess)
         rc = fail(he == hipErrorOutOfMemory ? MADE_ERR_NOMEM : MADE_ERR_HIP, "made_init: layer %d upload failed: %s", l,
                   hipGetErrorString(he));
@@ -339,8 +367,20 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
     made_free(m);
     return rc;
   }
-  m->prof_ms.assign(L + 1, 0.0);
-  m->prof_launches.assign(L + 1, 0);
+  m->prof_ms.assign(L + 2, 0.0);
+  m->prof_launches.assign(L + 2, 0);
+  // The persistent kernel needs every workgroup resident at once: one per CU, if the device can do that.
+  {
+    int coop = 0, cus = 0, per_cu = 0;
+    hipError_t pe = hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, m->device);
+    if (pe == hipSuccess) pe = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, m->device);
+    if (pe == hipSuccess)
+      pe = m->dtype == MADE_BF16
+               ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, persistent_sampler_kernel<bf16_t>, NW * 64, 0)
+               : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, persistent_sampler_kernel<float>, NW * 64, 0);
+    if (pe == hipSuccess && coop && per_cu >= 1 && C == 1 && L + 1 <= PERSIST_MAX_LAYERS) m->persist_grid = cus;
+    (void)hipGetLastError();
+  }
   *out = m;
   return MADE_OK;
 }
@@ -412,9 +452,8 @@ static LayerArgs base_args(const made_model* m, int l, const void* A, const RowS
   LayerArgs a;
   memset(&a, 0, sizeof a);
   a.A = A;
-  a.lda = ly.in_pad;
   a.W = ly.W;
-  a.ldw = ly.in_pad;
+  a.k_chunks = ly.k_chunks;
   a.bias = ly.bias;
   a.tile_kend = ly.tile_kend;
   a.k_cap = ly.in_pad;
@@ -436,7 +475,7 @@ static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, in
     const Layer& ly = m->layers[l];
     LayerArgs a = base_args(m, l, l == 0 ? m->ws.enc : m->ws.act[l - 1], rs);
     a.out = m->ws.act[l];
-    a.ldo = m->layers[l + 1].in_pad;
+    a.out_chunks = m->layers[l + 1].k_chunks;
     int tiles = ly.n_tiles;
     if (unit_limit && unit_limit[l] >= 0) tiles = std::min(tiles, (unit_limit[l] + TILE - 1) / TILE);
     if (in_limit >= 0) a.k_cap = std::min(ly.in_pad, round_up(in_limit, kc));
@@ -469,7 +508,7 @@ static int run_output_sample(made_model* m, const RowSet& rs, const SampleIO& io
     a.noise = io.noise;
     a.x = io.x;
     a.enc = m->ws.enc;
-    a.ld_enc = m->layers[0].in_pad;
+    a.enc_chunks = m->layers[0].k_chunks;
     a.changed = m->ws.changed;
     a.D = m->D;
     a.t_lo = io.t_lo;
@@ -486,11 +525,11 @@ static int run_output_sample(made_model* m, const RowSet& rs, const SampleIO& io
     const int blocks = (int)((waves + 3) / 4);
     if (m->dtype == MADE_BF16)
       hipLaunchKernelGGL((gumbel_argmax_kernel<bf16_t>), dim3(blocks), dim3(256), 0, s, m->ws.zbuf, m->D * C, io.noise,
-                         io.x, (bf16_t*)m->ws.enc, m->layers[0].in_pad, m->ws.changed, rs.rows, rs.n_rows_ptr,
+                         io.x, (bf16_t*)m->ws.enc, m->layers[0].k_chunks, m->ws.changed, rs.rows, rs.n_rows_ptr,
                          rs.n_rows, m->D, C, io.t_lo, io.t_hi, io.retire);
     else
       hipLaunchKernelGGL((gumbel_argmax_kernel<float>), dim3(blocks), dim3(256), 0, s, m->ws.zbuf, m->D * C, io.noise,
-                         io.x, (float*)m->ws.enc, m->layers[0].in_pad, m->ws.changed, rs.rows, rs.n_rows_ptr,
+                         io.x, (float*)m->ws.enc, m->layers[0].k_chunks, m->ws.changed, rs.rows, rs.n_rows_ptr,
                          rs.n_rows, m->D, C, io.t_lo, io.t_hi, io.retire);
     m->stats[2] += 2;
   }
@@ -503,10 +542,10 @@ static int launch_init_state(made_model* m, const uint8_t* x_init, uint8_t* x, i
   const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
   if (m->dtype == MADE_BF16)
     hipLaunchKernelGGL((init_state_kernel<bf16_t>), dim3(blocks), dim3(256), 0, s, x_init, x, (bf16_t*)m->ws.enc,
-                       m->layers[0].in_pad, N, m->D, m->C);
+                       m->layers[0].k_chunks, N, m->D, m->C);
   else
     hipLaunchKernelGGL((init_state_kernel<float>), dim3(blocks), dim3(256), 0, s, x_init, x, (float*)m->ws.enc,
-                       m->layers[0].in_pad, N, m->D, m->C);
+                       m->layers[0].k_chunks, N, m->D, m->C);
   m->stats[2]++;
   HIP_TRY(hipGetLastError());
   return MADE_OK;
@@ -661,6 +700,82 @@ static int finish_call(made_model* m, int N, int32_t* iters_out, bool check_flag
   return MADE_OK;
 }
 
+// The whole call in one cooperative launch (see persistent_sampler_kernel).  Returns 1 in *done when the call
+// was served this way, 0 when the caller must take the stream-ordered path.
+static int run_persistent(made_model* m, const float* noise, int N, const uint8_t* x_init, uint8_t* x, int block,
+                          int cap, bool flag_unconverged, int32_t* iters_out, hipStream_t s, bool* done) {
+  *done = false;
+  if (!m->use_persistent || m->persist_grid <= 0 || N > PERSIST_MAX_N) return MADE_OK;
+  Workspace& w = m->ws;
+  PersistArgs p;
+  memset(&p, 0, sizeof p);
+  for (int l = 0; l <= m->L; ++l) {
+    const Layer& ly = m->layers[l];
+    PersistLayer& pl = p.layer[l];
+    pl.W = ly.W;
+    pl.bias = ly.bias;
+    pl.tile_kend = ly.tile_kend;
+    pl.cnt_lt = ly.cnt_lt;
+    pl.out = l < m->L ? w.act[l] : nullptr;
+    pl.in_pad = ly.in_pad;
+    pl.k_chunks = ly.k_chunks;
+    pl.n_tiles = ly.n_tiles;
+    pl.out_dim = ly.out_dim;
+    pl.out_chunks = l < m->L ? m->layers[l + 1].k_chunks : 0;
+  }
+  p.L = m->L;
+  p.enc = w.enc;
+  p.enc_chunks = m->layers[0].k_chunks;
+  p.noise = noise;
+  p.x_init = x_init;
+  p.x = x;
+  p.N = N;
+  p.D = m->D;
+  p.block = block;
+  p.cap = cap;
+  p.flag_unconverged = flag_unconverged;
+  p.changed = w.changed;
+  p.n_pad = w.n_pad;
+  p.iters = w.iters;
+  p.flags = w.flags;
+  p.bar = w.bar;
+  p.stats = w.dev_stats;
+  p.spin_limit = 1u << 22;
+  HIP_TRY(hipMemsetAsync(w.bar, 0, sizeof(unsigned), s));
+  HIP_TRY(hipMemsetAsync(w.flags, 0, sizeof(int), s));
+  void* args[] = {&p};
+  prof_mark(m, m->L + 1, false, s);
+  hipError_t e = m->dtype == MADE_BF16
+                     ? hipLaunchCooperativeKernel((const void*)persistent_sampler_kernel<bf16_t>, dim3(m->persist_grid),
+                                                  dim3(NW * 64), args, 0, s)
+                     : hipLaunchCooperativeKernel((const void*)persistent_sampler_kernel<float>, dim3(m->persist_grid),
+                                                  dim3(NW * 64), args, 0, s);
+  prof_mark(m, m->L + 1, true, s);
+  if (e != hipSuccess) {   // not launchable as a co-resident grid on this device: take the other path from now on
+    (void)hipGetLastError();
+    m->persist_grid = 0;
+    m->ev_layer.clear();
+    HIP_TRY(hipStreamSynchronize(s));
+    return MADE_OK;
+  }
+  m->stats[2] += 1;
+  if (iters_out) HIP_TRY(hipMemcpyAsync(iters_out, w.iters, (size_t)N * sizeof(int), hipMemcpyDeviceToDevice, s));
+  HIP_TRY(hipMemcpyAsync((void*)&w.h_pin[0], w.flags, sizeof(int), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipMemcpyAsync((void*)&w.h_pin[2], w.dev_stats, 2 * sizeof(long long), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  m->stats[3] += 1;
+  prof_collect(m);
+  long long st[2];
+  memcpy(st, (const void*)&w.h_pin[2], sizeof st);
+  m->stats[0] = st[0];
+  m->stats[1] = st[1];
+  *done = true;
+  const int flags = w.h_pin[0];
+  if (flags & 2) return fail(MADE_ERR_HIP, "persistent kernel: grid barrier timed out (workgroups not co-resident?)");
+  if (flags & 1) return fail(MADE_ERR_NOT_CONVERGED, "samples were still changing after the last allowed pass");
+  return MADE_OK;
+}
+
 extern "C" int jacobi_sample(made_model* m, const float* noise, int32_t N, const uint8_t* x_init, int32_t max_iters,
                              uint8_t* x_out, int32_t* iters_out, void* stream) {
   TRY(check_call(m, noise, N, x_out, "jacobi_sample"));
@@ -670,6 +785,9 @@ extern "C" int jacobi_sample(made_model* m, const float* noise, int32_t N, const
   m->ev_layer.clear();
   TRY(ensure_workspace(m, N, true));
   const int cap = (max_iters <= 0 || max_iters > m->D) ? m->D : max_iters;
+  bool done = false;
+  TRY(run_persistent(m, noise, N, x_init, x_out, m->D, cap, cap < m->D, iters_out, s, &done));
+  if (done) return MADE_OK;
   TRY(launch_init_state(m, x_init, x_out, N, s));
   TRY(launch_reset_rows(m, 0, N, true, s));
   std::vector<char> log;
@@ -686,6 +804,9 @@ extern "C" int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, co
   memset(m->stats, 0, sizeof m->stats);
   m->ev_layer.clear();
   TRY(ensure_workspace(m, N, true));
+  bool done = false;
+  TRY(run_persistent(m, noise, N, x_init, x_out, block, m->D, false, iters_out, s, &done));
+  if (done) return MADE_OK;
   TRY(launch_init_state(m, x_init, x_out, N, s));
   TRY(launch_reset_rows(m, 0, N, true, s));
   std::vector<int> limit(m->L);
@@ -699,3 +820,16 @@ extern "C" int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, co
   }
   return finish_call(m, N, iters_out, false, log, s);
 }
+
+#ifdef JM_TRACE
+// development aid (only in builds with -DJM_TRACE): read and clear the barrier time stamps
+extern "C" int jm_debug_read_trace(unsigned long long* out) {
+  if (hipMemcpyFromSymbol(out, HIP_SYMBOL(jm::g_trace), sizeof(unsigned long long) * 64 * 256 * 5) != hipSuccess) return -1;
+  static std::vector<unsigned long long> zeros(64 * 256 * 5, 0);
+  (void)hipMemcpyToSymbol(HIP_SYMBOL(jm::g_trace), zeros.data(), sizeof(unsigned long long) * 64 * 256 * 5);
+  return 0;
+}
+extern "C" int jm_debug_read_tile_trace(unsigned long long* out) {
+  return hipMemcpyFromSymbol(out, HIP_SYMBOL(jm::g_tile_trace), sizeof(unsigned long long) * 1024 * 8) == hipSuccess ? 0 : -1;
+}
+#endif

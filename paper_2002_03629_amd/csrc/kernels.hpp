@@ -33,6 +33,23 @@ template <> struct Elem<float> {
   static __device__ __forceinline__ float from_f32(float f) { return f; }
 };
 
+// Fragment-major layout of every MFMA operand matrix (masked weights, network input, hidden activations).
+//
+// A [rows, K] matrix is cut into groups of 32 rows and chunks of KC = 2 * EPL columns (128 bytes per row).
+// Block (group g, chunk c) holds 32 x KC elements, stored in exactly the order a wave consumes them:
+//     [slot s = 0..3][half h = 0..1][row r = 0..31][16 bytes]
+// where the 16 bytes are columns  c*KC + h*EPL + s*P .. + P  of row 32*g + r  (P = elements per 16 bytes).
+// Lane (r, h) of a wave needs, for MFMA step s, exactly those 16 bytes, so each of the wave's four loads
+// per chunk reads one contiguous 1 KB run instead of 64 scattered 16-byte pieces (which makes the
+// texture-address path, not memory, the limit).  Blocks are stored chunk-major inside a group.
+template <typename T>
+__host__ __device__ __forceinline__ size_t frag_offset(int row, int k, int k_chunks) {
+  constexpr int EPL = Elem<T>::EPL, KC = 2 * EPL, P = 16 / (int)sizeof(T);
+  const int g = row >> 5, r = row & 31, c = k / KC, kk = k % KC;
+  const int h = kk / EPL, s = (kk % EPL) / P, i = kk % P;
+  return ((size_t)g * k_chunks + c) * (size_t)(KC * 32) + (size_t)(((s * 2 + h) * 32 + r) * P + i);
+}
+
 constexpr int TILE = 32;   // output tile: 32 samples x 32 units per workgroup
 #ifndef JM_NW
 #define JM_NW 8
@@ -41,7 +58,8 @@ constexpr int TILE = 32;   // output tile: 32 samples x 32 units per workgroup
 #define JM_PD 4
 #endif
 constexpr int NW = JM_NW;  // waves per workgroup; they split the K range between them
-constexpr int PD = JM_PD;  // K chunks a wave keeps in flight (all their loads are issued before the first MFMA)
+constexpr int PD = JM_PD;  // K chunks a wave keeps in flight (all their loads are issued before the first MFMA); <= 8
+static_assert(PD >= 1 && PD <= 8, "prefetch depth must be 1..8");
 constexpr int XCDS = 8;    // workgroup i is dispatched to XCD i % 8; each XCD has its own L2
 
 enum Epilogue { EPI_RELU = 0, EPI_LOGITS = 1, EPI_BERNOULLI = 2 };
@@ -64,11 +82,11 @@ struct RetireArgs {
 };
 
 struct LayerArgs {
-  // operands: A = activations [sample, lda], W = masked weights [unit, ldw], both K-contiguous
+  // operands, both in fragment-major layout with k_chunks chunks per row group:
+  // A = activations [sample, K], W = masked weights [unit, K]
   const void* A;
-  int lda;
   const void* W;
-  int ldw;
+  int k_chunks;
   const float* bias;     // [out_pad]
   const int* tile_kend;  // per 32-unit tile: K extent that holds non-zero (visible) weights, chunk-rounded
   int k_cap;             // additional upper limit on K (chunk-rounded)
@@ -79,20 +97,33 @@ struct LayerArgs {
   const int* rows;
   const int* n_rows_ptr;
   int n_rows;
-  // EPI_RELU: out = activations [sample, ldo] of type T.  EPI_LOGITS: out = float [sample, ldo]
+  // EPI_RELU: out = next layer's activations (fragment-major, out_chunks chunks).  EPI_LOGITS: float [sample, ldo]
   void* out;
   int ldo;
+  int out_chunks;
   int n_cols;            // real (unpadded) number of units of this layer
   // EPI_BERNOULLI
   const float* noise;    // u[sample, D]
   uint8_t* x;            // [sample, D], updated in place
-  void* enc;             // network input of the next pass, T [sample, ld_enc]
-  int ld_enc;
+  void* enc;             // network input of the next pass (fragment-major, enc_chunks chunks)
+  int enc_chunks;
   int* changed;          // per-sample count of positions whose symbol changed
   int D;
   int t_lo, t_hi;        // only positions in [t_lo, t_hi) are re-drawn
   RetireArgs retire;
 };
+
+// Store that other workgroups of the SAME kernel will read after a grid barrier.  COH = true writes through to
+// device-coherent memory (device-scope atomic store: the XCDs' L2 caches are not coherent with each other), so
+// that the barrier does not have to write back a whole L2; COH = false is an ordinary store, enough when the
+// reader is a later kernel.
+template <bool COH, typename V>
+__device__ __forceinline__ void publish(V* p, V v) {
+  if (COH)
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else
+    *p = v;
+}
 
 template <typename T>
 __device__ __forceinline__ void mfma_chunk(const uint4 (&a)[4], const uint4 (&b)[4], f32x16& acc);
@@ -184,135 +215,428 @@ __device__ __forceinline__ void finish_pass(const RetireArgs& r, int total_workg
   if (is_last_s) retire_tail(r);
 }
 
+#ifdef JM_TRACE
+__device__ unsigned long long g_tile_trace[1024 * 8];
+#define JM_TSTAMP(i, drain)                                                           \
+  do {                                                                                \
+    if (drain) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");            \
+    if (threadIdx.x == 0 && blockIdx.x < 1024) g_tile_trace[blockIdx.x * 8 + (i)] = wall_clock64(); \
+  } while (0)
+#else
+#define JM_TSTAMP(i, drain) do { } while (0)
+#endif
+
+// CNT chunks c0, c0 + NW, ... of one wave: every load is issued before the first MFMA.  Ap / Wp point at
+// the lane's 16 bytes of slot 0 in chunk 0 of its row group; a chunk is 256 uint4, a slot 64 uint4.
+template <typename T, int CNT>
+__device__ __forceinline__ void chunk_group(const uint4* Ap, const uint4* Wp, int c0, f32x16& acc) {
+  static_assert(CNT >= 1 && CNT <= PD, "group larger than the prefetch depth");
+  uint4 av[CNT][4], bv[CNT][4];
+#pragma unroll
+  for (int p = 0; p < CNT; ++p) {
+    const uint4* ap = Ap + (size_t)(c0 + p * NW) * 256;
+    const uint4* wp = Wp + (size_t)(c0 + p * NW) * 256;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) { av[p][s] = ap[s * 64]; bv[p][s] = wp[s * 64]; }
+  }
+  // keep the scheduler from sinking loads between the MFMAs to save registers: the point is to have
+  // every load of the group in flight at once
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int p = 0; p < CNT; ++p) mfma_chunk<T>(av[p], bv[p], acc);
+}
+
 // One masked dense layer on a 32 x 32 output tile per workgroup.
 //
 // Lane (r = lane % 32, h = lane / 32) of a wave owns sample row r and weight row r of the tile and
-// loads 64 contiguous bytes of each per K chunk, the h-th half of the chunk.  The MFMA contracts
-// lane-held K slices of A against the same slices of B, so which physical K a slot carries does
-// not matter as long as both operands agree -- this keeps every global load 64 bytes wide and
-// contiguous.  At batch sizes around 100 a tile's whole K range is only a few hundred KB, so the
-// kernel is bound by memory latency and by the rate at which waves can be dispatched, not by
-// bandwidth or MFMA rate: a workgroup has only 4 waves, they take K chunks round-robin, and each
-// wave issues the loads of up to PD chunks before its first MFMA, which puts (nearly) the entire
-// tile in flight at once.  Partial tiles are summed through LDS in a fixed
-// order (deterministic results).  Workgroups are numbered so that the sample tiles sharing a
-// weight tile run on the same XCD and hit that XCD's L2.
-template <typename T, int EPI>
-__global__ __launch_bounds__(NW * 64) void masked_layer_kernel(LayerArgs a) {
+// per K chunk holds 64 bytes of each, the h-th half of the chunk.  The MFMA contracts lane-held K
+// slices of A against the same slices of B, so which physical K a slot carries does not matter as
+// long as both operands agree.  Both operands live in the fragment-major layout described at
+// frag_offset, so every wave-wide load is one contiguous kilobyte.  At batch sizes around 100 a tile's whole K range is only a few hundred KB, so the
+// work is bound by memory latency, not by bandwidth or MFMA rate: the waves of a workgroup take K
+// chunks round-robin and each issues the loads of up to PD chunks before its first MFMA, which puts
+// most of the tile in flight at once.  Partial tiles are summed through LDS in a fixed order
+// (deterministic results).
+//
+// rows/n_rows: the active-sample list (global or LDS memory) and its length; entries past n_rows are
+// stale but valid sample ids.  `part` is the workgroup's LDS scratch.  All threads of the workgroup
+// call this together; the tile (rel_tile, row0) is uniform.
+template <typename T, int EPI, bool COH>
+__device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, int row0, const int* rows, int n_rows,
+                                             float (*part)[TILE][TILE + 1]) {
   constexpr int EPL = Elem<T>::EPL;
   constexpr int KC = 2 * EPL;
   constexpr int EPT = TILE * TILE / (NW * 64);   // tile elements each thread finishes in the epilogue
-  __shared__ float part[NW][TILE][TILE + 1];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int r = lane & 31, h = lane >> 5;
+  const int tile = a.tile_begin + rel_tile;
+  const int col0 = tile * TILE;
+  const int cc = threadIdx.x & 31, col = col0 + cc;
 
-  const int xcd = blockIdx.x % XCDS, slot = blockIdx.x / XCDS;
-  const int row0 = (slot % a.row_tiles) * TILE;
-  const int rel_tile = (slot / a.row_tiles) * XCDS + xcd;
-  if (rel_tile < a.n_launch_tiles) {   // (uniform per workgroup)
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int r = lane & 31, h = lane >> 5;
-    const int tile = a.tile_begin + rel_tile;
-    const int col0 = tile * TILE;
-    const int cc = threadIdx.x & 31, col = col0 + cc;
-
-    // Everything that does not depend on other loads is requested up front, so the kernel is a chain of
-    // only three memory round trips (bookkeeping, operands, results).  Entries of `rows` past the active
-    // count are stale but valid sample ids, so they can be read before the count is known.
-    const int n_rows = a.n_rows_ptr ? *a.n_rows_ptr : a.n_rows;
-    const int my_sample = a.rows ? a.rows[row0 + r] : (row0 + r < a.n_rows ? row0 + r : 0);
-    int k_end = a.tile_kend[tile];
-    const float bias = a.bias[col];
-    int e_sample[EPT];
+  JM_TSTAMP(0, 0);
+  // Everything that does not depend on other loads is requested up front, so a tile is a chain of only
+  // three memory round trips (bookkeeping, operands, results).
+  const int my_sample = rows ? rows[row0 + r] : (row0 + r < a.n_rows ? row0 + r : 0);
+  int k_end = a.tile_kend[tile];
+  const float bias = a.bias[col];
+  int e_sample[EPT];
+#pragma unroll
+  for (int j = 0; j < EPT; ++j) {
+    const int rr = (threadIdx.x >> 5) + j * (NW * 2);
+    e_sample[j] = rows ? rows[row0 + rr] : (row0 + rr < a.n_rows ? row0 + rr : 0);
+  }
+  float e_noise[EPT];
+  uint8_t e_xold[EPT];
+  const bool col_live = EPI == EPI_BERNOULLI && col >= a.t_lo && col < a.t_hi;
+  if (EPI == EPI_BERNOULLI) {
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
-      const int rr = (threadIdx.x >> 5) + j * (NW * 2);
-      e_sample[j] = a.rows ? a.rows[row0 + rr] : (row0 + rr < a.n_rows ? row0 + rr : 0);
-    }
-    float e_noise[EPT];
-    uint8_t e_xold[EPT];
-    const bool col_live = EPI == EPI_BERNOULLI && col >= a.t_lo && col < a.t_hi;
-    if (EPI == EPI_BERNOULLI) {
-#pragma unroll
-      for (int j = 0; j < EPT; ++j) {
-        e_noise[j] = 0.f;
-        e_xold[j] = 0;
-        if (col_live) {
-          const size_t idx = (size_t)e_sample[j] * a.D + col;
-          e_noise[j] = a.noise[idx];
-          e_xold[j] = a.x[idx];
-        }
-      }
-    }
-
-    if (row0 < n_rows) {
-      const T* Ap = (const T*)a.A + (size_t)my_sample * a.lda + h * EPL;
-      const T* Wp = (const T*)a.W + (size_t)(col0 + r) * a.ldw + h * EPL;
-      if (k_end > a.k_cap) k_end = a.k_cap;
-
-      f32x16 acc;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-
-      const int n_chunks = (k_end + KC - 1) / KC;
-      const int n_mine = (n_chunks - wave + NW - 1) / NW;   // chunks wave, wave + NW, ... belong to this wave
-      for (int base = 0; base < n_mine; base += PD) {
-        uint4 av[PD][4], bv[PD][4];
-#pragma unroll
-        for (int p = 0; p < PD; ++p) {
-          if (base + p < n_mine) {
-            const int kc = ((base + p) * NW + wave) * KC;
-            const uint4* ap = (const uint4*)(Ap + kc);
-            const uint4* wp = (const uint4*)(Wp + kc);
-#pragma unroll
-            for (int s = 0; s < 4; ++s) { av[p][s] = ap[s]; bv[p][s] = wp[s]; }
-          }
-        }
-#pragma unroll
-        for (int p = 0; p < PD; ++p)
-          if (base + p < n_mine) mfma_chunk<T>(av[p], bv[p], acc);
-      }
-
-      // acc[i] is the tile element (row = 8*(i/4) + 4*h + i%4, col = r): rows come from A = samples
-#pragma unroll
-      for (int i = 0; i < 16; ++i) part[wave][(i >> 2) * 8 + h * 4 + (i & 3)][r] = acc[i];
-      __syncthreads();
-
-#pragma unroll
-      for (int j = 0; j < EPT; ++j) {
-        const int rr = (threadIdx.x >> 5) + j * (NW * 2);
-        const bool row_ok = row0 + rr < n_rows;
-        const int sample = e_sample[j];
-        float v = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) v += part[w][rr][cc];
-        v += bias;
-
-        if (EPI == EPI_RELU) {
-          if (row_ok) ((T*)a.out)[(size_t)sample * a.ldo + col] = Elem<T>::from_f32(fmaxf(v, 0.f));
-        } else if (EPI == EPI_LOGITS) {
-          if (row_ok && col < a.n_cols) ((float*)a.out)[(size_t)sample * a.ldo + col] = v;
-        } else {  // EPI_BERNOULLI: x_t = 1 iff u_t < sigmoid(z_t); count changes per sample
-          int cnt = 0;
-          if (row_ok && col_live) {
-            const float p = 1.0f / (1.0f + expf(-v));
-            const uint8_t xn = e_noise[j] < p ? 1 : 0;
-            cnt = (xn != e_xold[j]);
-            if (cnt) {   // an unchanged symbol (and its encoding) is already in place
-              a.x[(size_t)sample * a.D + col] = xn;
-              ((T*)a.enc)[(size_t)sample * a.ld_enc + col] = Elem<T>::from_f32((float)xn);
-            }
-          }
-          // the 32 lanes of a half-wave hold one sample row of the tile
-          cnt += __shfl_xor(cnt, 1);
-          cnt += __shfl_xor(cnt, 2);
-          cnt += __shfl_xor(cnt, 4);
-          cnt += __shfl_xor(cnt, 8);
-          cnt += __shfl_xor(cnt, 16);
-          if (cc == 0 && cnt > 0) count_changed(&a.changed[sample], cnt);
-        }
+      e_noise[j] = 0.f;
+      e_xold[j] = 0;
+      if (col_live) {
+        const size_t idx = (size_t)e_sample[j] * a.D + col;
+        e_noise[j] = a.noise[idx];
+        e_xold[j] = a.x[idx];
       }
     }
   }
+
+  JM_TSTAMP(1, 1);
+  const uint4* Ap = (const uint4*)a.A + (size_t)(my_sample >> 5) * a.k_chunks * 256 + h * 32 + (my_sample & 31);
+  const uint4* Wp = (const uint4*)a.W + (size_t)tile * a.k_chunks * 256 + h * 32 + r;
+  if (k_end > a.k_cap) k_end = a.k_cap;
+
+  f32x16 acc;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+
+  // Chunks wave, wave + NW, ... belong to this wave.  They are taken in straight-line groups: all loads of
+  // a group are issued before its first MFMA (no branches inside a group, so nothing forces an early wait).
+  const int n_chunks = (k_end + KC - 1) / KC;
+  const int n_mine = (n_chunks - wave + NW - 1) / NW;   // wave-uniform (scalar)
+  int base = 0;
+  for (; base + PD <= n_mine; base += PD) chunk_group<T, PD>(Ap, Wp, base * NW + wave, acc);
+  switch (n_mine - base) {
+    case 7: chunk_group<T, (PD > 7 ? 7 : 1)>(Ap, Wp, base * NW + wave, acc); break;
+    case 6: chunk_group<T, (PD > 6 ? 6 : 1)>(Ap, Wp, base * NW + wave, acc); break;
+    case 5: chunk_group<T, (PD > 5 ? 5 : 1)>(Ap, Wp, base * NW + wave, acc); break;
+    case 4: chunk_group<T, (PD > 4 ? 4 : 1)>(Ap, Wp, base * NW + wave, acc); break;
+    case 3: chunk_group<T, (PD > 3 ? 3 : 1)>(Ap, Wp, base * NW + wave, acc); break;
+    case 2: chunk_group<T, (PD > 2 ? 2 : 1)>(Ap, Wp, base * NW + wave, acc); break;
+    case 1: chunk_group<T, 1>(Ap, Wp, base * NW + wave, acc); break;
+    default: break;
+  }
+
+  JM_TSTAMP(2, 1);
+  // acc[i] is the tile element (row = 8*(i/4) + 4*h + i%4, col = r): rows come from A = samples
+#pragma unroll
+  for (int i = 0; i < 16; ++i) part[wave][(i >> 2) * 8 + h * 4 + (i & 3)][r] = acc[i];
+  __syncthreads();
+  JM_TSTAMP(3, 1);
+
+#pragma unroll
+  for (int j = 0; j < EPT; ++j) {
+    const int rr = (threadIdx.x >> 5) + j * (NW * 2);
+    const bool row_ok = row0 + rr < n_rows;
+    const int sample = e_sample[j];
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) v += part[w][rr][cc];
+    v += bias;
+
+    if (EPI == EPI_RELU) {
+      if (row_ok) publish<COH>((T*)a.out + frag_offset<T>(sample, col, a.out_chunks), Elem<T>::from_f32(fmaxf(v, 0.f)));
+    } else if (EPI == EPI_LOGITS) {
+      if (row_ok && col < a.n_cols) ((float*)a.out)[(size_t)sample * a.ldo + col] = v;
+    } else {  // EPI_BERNOULLI: x_t = 1 iff u_t < sigmoid(z_t); count changes per sample
+      int cnt = 0;
+      if (row_ok && col_live) {
+        const float p = 1.0f / (1.0f + expf(-v));
+        const uint8_t xn = e_noise[j] < p ? 1 : 0;
+        cnt = (xn != e_xold[j]);
+        if (cnt) {   // an unchanged symbol (and its encoding) is already in place
+          publish<COH>(a.x + (size_t)sample * a.D + col, xn);
+          publish<COH>((T*)a.enc + frag_offset<T>(sample, col, a.enc_chunks), Elem<T>::from_f32((float)xn));
+        }
+      }
+      // the 32 lanes of a half-wave hold one sample row of the tile
+      cnt += __shfl_xor(cnt, 1);
+      cnt += __shfl_xor(cnt, 2);
+      cnt += __shfl_xor(cnt, 4);
+      cnt += __shfl_xor(cnt, 8);
+      cnt += __shfl_xor(cnt, 16);
+      if (cc == 0 && cnt > 0) count_changed(&a.changed[sample], cnt);
+    }
+  }
+  JM_TSTAMP(4, 0);
+  JM_TSTAMP(5, 1);
+}
+
+// Map a linear work item to (unit tile, sample tile) so that the sample tiles sharing a weight tile,
+// and the unit tiles sharing an activation tile, fall on the same XCD (item i runs on XCD i % 8 when
+// items are workgroup indices).  Returns false for padding items.
+__device__ __forceinline__ bool item_to_tile(int item, int n_tiles, int row_tiles, int& rel_tile, int& row0) {
+  const int xcd = item % XCDS, slot = item / XCDS;
+  row0 = (slot % row_tiles) * TILE;
+  rel_tile = (slot / row_tiles) * XCDS + xcd;
+  return rel_tile < n_tiles;
+}
+
+// Stand-alone launch of one layer (one tile per workgroup).  Used when the batch or the model is too
+// large for the persistent kernel below, for categorical models and for sequential sampling.
+template <typename T, int EPI>
+__global__ __launch_bounds__(NW * 64) void masked_layer_kernel(LayerArgs a) {
+  __shared__ float part[NW][TILE][TILE + 1];
+  int rel_tile, row0;
+  if (item_to_tile(blockIdx.x, a.n_launch_tiles, a.row_tiles, rel_tile, row0)) {
+    const int n_rows = a.n_rows_ptr ? *a.n_rows_ptr : a.n_rows;
+    if (row0 < n_rows) compute_tile<T, EPI, false>(a, rel_tile, row0, a.rows, n_rows, part);
+  }
   if (EPI == EPI_BERNOULLI && a.retire.enabled) finish_pass(a.retire, gridDim.x);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Persistent kernel: the whole of Algorithm 1 (or Algorithm 3) in one cooperative launch.
+//
+// At batch ~100 a pass is three layers of a few microseconds each, and a dependent kernel launch
+// costs about as much as a layer.  Here one workgroup per CU stays resident for the entire call;
+// layers are separated by a grid-wide barrier instead of a kernel boundary, the stop test and the
+// compaction of the active list are recomputed by every workgroup from the per-sample changed
+// counters (identical inputs, identical result, no extra barrier), and the host synchronises once.
+// ------------------------------------------------------------------------------------------------
+constexpr int PERSIST_MAX_N = 2048;       // active list is kept in LDS
+constexpr int PERSIST_MAX_LAYERS = 8;
+
+struct PersistLayer {
+  const void* W;
+  const float* bias;
+  const int* tile_kend;
+  const int* cnt_lt;     // hidden layers: cnt_lt[t] = units of degree < t (prefix length); NULL for the output layer
+  void* out;             // hidden layers: activation buffer [sample, ldo]
+  int in_pad, k_chunks, out_chunks, n_tiles, out_dim;
+};
+
+struct PersistArgs {
+  PersistLayer layer[PERSIST_MAX_LAYERS];
+  int L;                 // hidden layers; layer[L] is the output layer
+  void* enc;
+  int enc_chunks;
+  const float* noise;
+  const uint8_t* x_init;
+  uint8_t* x;
+  int N, D;
+  int block;             // GS-Jacobi block size; >= D means plain Jacobi (one block)
+  int cap;               // plain Jacobi: pass limit (<= D)
+  int flag_unconverged;
+  int* changed;          // [2][n_pad] per-sample changed counters, alternating by pass
+  int n_pad;
+  int* iters;            // [N]
+  int* flags;            // bit 0 unconverged, bit 1 barrier timed out
+  unsigned* bar;         // grid barrier arrival counter (zero at launch)
+  long long* stats;      // [0] passes, [1] sample-passes
+  unsigned spin_limit;   // barrier gives up after this many polls (never reached unless the launch was not co-resident)
+};
+
+// Grid-wide barrier for a cooperative (co-resident) launch.  Everything a workgroup wrote for others went
+// out through publish<true> (write-through, device scope); each thread waits until its stores are
+// acknowledged, then thread 0 arrives and polls until all workgroups have arrived, and a device-scope acquire
+// drops this XCD's possibly stale cached copies.  (A device-scope release fence instead would write back the
+// whole L2 once per arriving workgroup, 32 times per XCD and barrier, stalling the workgroups still at work.)
+// The wait is bounded: on timeout bit 1 of *flags is set and every workgroup leaves the kernel at its next
+// check, so the grid always drains.
+#ifndef JM_SLEEP
+#define JM_SLEEP 1
+#endif
+#ifdef JM_TRACE
+// development aid: per workgroup and barrier, the times of arrival / after release fence / after the
+// arrival atomic / after the wait / after the acquire fence
+__device__ unsigned long long g_trace[64 * 256 * 5];
+#define JM_STAMP(tag)                                                                            \
+  do {                                                                                           \
+    const unsigned b_ = epoch / gridDim.x - 1;                                                   \
+    if (b_ < 64 && blockIdx.x < 256) g_trace[(b_ * 256 + blockIdx.x) * 5 + (tag)-1] = wall_clock64(); \
+  } while (0)
+#else
+#define JM_STAMP(tag) do { } while (0)
+#endif
+
+__device__ __forceinline__ bool grid_barrier(unsigned* bar, unsigned& epoch, int* flags, unsigned spin_limit) {
+  __shared__ int ok_s;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    epoch += gridDim.x;
+    JM_STAMP(1);
+    JM_STAMP(2);
+    __hip_atomic_fetch_add(bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    JM_STAMP(3);
+    int ok = 1;
+    unsigned spins = 0;
+    while ((int)(__hip_atomic_load(bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - epoch) < 0) {
+      __builtin_amdgcn_s_sleep(JM_SLEEP);
+      if (++spins > spin_limit ||
+          ((spins & 255) == 0 && (__hip_atomic_load(flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 2))) {
+        __hip_atomic_fetch_or(flags, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ok = 0;
+        break;
+      }
+    }
+    JM_STAMP(4);
+#ifndef JM_NO_ACQUIRE   // (timing experiments only: without it other workgroups' writes may be read stale)
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+#endif
+    JM_STAMP(5);
+    ok_s = ok;
+  }
+  __syncthreads();
+  return ok_s != 0;
+}
+
+template <typename T>
+__global__ __launch_bounds__(NW * 64) void persistent_sampler_kernel(PersistArgs p) {
+  __shared__ float part[NW][TILE][TILE + 1];
+  __shared__ int rows_s[PERSIST_MAX_N];
+  __shared__ int wave_total[NW];
+  constexpr int NT = NW * 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  unsigned epoch = 0;
+  const int N = p.N, D = p.D, L = p.L;
+
+  // x = x_init (or zeros) and its network encoding
+  for (size_t i = (size_t)blockIdx.x * NT + threadIdx.x; i < (size_t)N * D; i += (size_t)gridDim.x * NT) {
+    const int n = (int)(i / D), t = (int)(i % D);
+    const uint8_t v = p.x_init ? p.x_init[i] : 0;
+    publish<true>(p.x + i, v);
+    publish<true>((T*)p.enc + frag_offset<T>(n, t, p.enc_chunks), Elem<T>::from_f32((float)v));
+  }
+  if (blockIdx.x == 0) {
+    for (int i = threadIdx.x; i < N; i += NT) p.iters[i] = 0;
+    for (int i = threadIdx.x; i < 2 * p.n_pad; i += NT) publish<true>(p.changed + i, 0);
+  }
+  if (!grid_barrier(p.bar, epoch, p.flags, p.spin_limit)) return;
+
+  long long n_passes = 0, n_sample_passes = 0;
+  int parity = 0;
+  const bool gs = p.block < D;
+  for (int a0 = 0; a0 < D; a0 += p.block) {
+    const int b0 = min(a0 + p.block, D);          // block = 0-based positions [a0, b0)
+    for (int i = threadIdx.x; i < N; i += NT) rows_s[i] = i;
+    int n_rows = N;
+    __syncthreads();
+    const int cap = gs ? (b0 - a0) : p.cap;
+    for (int k = 1; k <= cap && n_rows > 0; ++k) {
+      const int row_tiles = (n_rows + TILE - 1) / TILE;
+      int* changed = p.changed + parity * p.n_pad;
+      // ---- hidden layers (GS: only units of degree < b0 matter to positions <= b0)
+      int in_limit = gs ? b0 - 1 : -1;
+      for (int l = 0; l < L; ++l) {
+        const PersistLayer& ly = p.layer[l];
+        LayerArgs a = {};
+        a.A = l == 0 ? p.enc : p.layer[l - 1].out;
+        a.W = ly.W;
+        a.k_chunks = ly.k_chunks;
+        a.bias = ly.bias;
+        a.tile_kend = ly.tile_kend;
+        a.k_cap = ly.in_pad;
+        if (in_limit >= 0) a.k_cap = min(ly.in_pad, (in_limit + 2 * Elem<T>::EPL - 1) / (2 * Elem<T>::EPL) * (2 * Elem<T>::EPL));
+        a.tile_begin = 0;
+        a.n_rows = N;
+        a.out = ly.out;
+        a.out_chunks = ly.out_chunks;
+        a.n_cols = ly.out_dim;
+        int tiles = ly.n_tiles;
+        if (gs) {
+          const int lim = ly.cnt_lt[b0];
+          tiles = min(tiles, (lim + TILE - 1) / TILE);
+          in_limit = lim;
+        }
+        const int groups = (tiles + XCDS - 1) / XCDS;
+        const int items = groups * XCDS * row_tiles;
+        for (int item = blockIdx.x; item < items; item += gridDim.x) {
+          int rel_tile, row0;
+          if (item_to_tile(item, tiles, row_tiles, rel_tile, row0)) {
+            compute_tile<T, EPI_RELU, true>(a, rel_tile, row0, rows_s, n_rows, part);
+            __syncthreads();   // `part` is reused by the next item
+          }
+        }
+        if (!grid_barrier(p.bar, epoch, p.flags, p.spin_limit)) return;
+      }
+      // ---- output layer with the sampling epilogue, positions [a0, b0)
+      {
+        const PersistLayer& ly = p.layer[L];
+        LayerArgs a = {};
+        a.A = p.layer[L - 1].out;
+        a.W = ly.W;
+        a.k_chunks = ly.k_chunks;
+        a.bias = ly.bias;
+        a.tile_kend = ly.tile_kend;
+        a.k_cap = ly.in_pad;
+        if (in_limit >= 0) a.k_cap = min(ly.in_pad, (in_limit + 2 * Elem<T>::EPL - 1) / (2 * Elem<T>::EPL) * (2 * Elem<T>::EPL));
+        a.tile_begin = a0 / TILE;
+        a.n_rows = N;
+        a.n_cols = ly.out_dim;
+        a.noise = p.noise;
+        a.x = p.x;
+        a.enc = p.enc;
+        a.enc_chunks = p.enc_chunks;
+        a.changed = changed;
+        a.D = D;
+        a.t_lo = a0;
+        a.t_hi = b0;
+        const int tiles = (b0 + TILE - 1) / TILE - a.tile_begin;
+        const int groups = (tiles + XCDS - 1) / XCDS;
+        const int items = groups * XCDS * row_tiles;
+        for (int item = blockIdx.x; item < items; item += gridDim.x) {
+          int rel_tile, row0;
+          if (item_to_tile(item, tiles, row_tiles, rel_tile, row0)) {
+            compute_tile<T, EPI_BERNOULLI, true>(a, rel_tile, row0, rows_s, n_rows, part);
+            __syncthreads();
+          }
+        }
+        if (!grid_barrier(p.bar, epoch, p.flags, p.spin_limit)) return;
+      }
+      // ---- stop test and compaction, recomputed identically by every workgroup.  Workgroup 0 also keeps
+      //      the per-sample pass counts and clears the counters the pass after next will use (every
+      //      workgroup finished reading those before it arrived at this pass's barriers).
+      n_passes += 1;
+      n_sample_passes += n_rows;
+      const bool last_pass = (k == cap);
+      int new_n = 0;
+      for (int start = 0; start < n_rows; start += NT) {
+        const int rix = start + threadIdx.x;
+        int sample = -1;
+        bool keep = false;
+        if (rix < n_rows) {
+          sample = rows_s[rix];
+          const int c = __hip_atomic_load(&changed[sample], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          keep = (c > 0) && !last_pass;
+          if (blockIdx.x == 0) {
+            p.iters[sample] += 1;
+            if (c > 0 && last_pass && p.flag_unconverged) atomicOr(p.flags, 1);
+          }
+        }
+        const unsigned long long mask = __ballot(keep);
+        const int before = __popcll(mask & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_total[wave] = __popcll(mask);
+        __syncthreads();                       // all reads of this chunk of rows_s are done
+        int off = new_n;
+        for (int w = 0; w < wave; ++w) off += wave_total[w];
+        if (keep) rows_s[off + before] = sample;   // off + before <= rix: never overtakes an unread entry
+        for (int w = 0; w < NW; ++w) new_n += wave_total[w];
+        __syncthreads();
+      }
+      if (blockIdx.x == 0) {
+        int* other = p.changed + (parity ^ 1) * p.n_pad;
+        for (int i = threadIdx.x; i < N; i += NT) publish<true>(other + i, 0);
+      }
+      n_rows = new_n;
+      parity ^= 1;
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    p.stats[0] = n_passes;
+    p.stats[1] = n_sample_passes;
+  }
 }
 
 // Gumbel-max draw for categorical positions from logits held in memory:
@@ -320,7 +644,7 @@ __global__ __launch_bounds__(NW * 64) void masked_layer_kernel(LayerArgs a) {
 template <typename T>
 __global__ __launch_bounds__(256) void gumbel_argmax_kernel(const float* __restrict__ z, int ldz,
                                                             const float* __restrict__ g, uint8_t* x, T* enc,
-                                                            int ld_enc, int* changed, const int* rows,
+                                                            int enc_chunks, int* changed, const int* rows,
                                                             const int* n_rows_ptr, int n_rows_fixed, int D, int C,
                                                             int t_lo, int t_hi, RetireArgs retire) {
   const int n_rows = n_rows_ptr ? *n_rows_ptr : n_rows_fixed;
@@ -349,7 +673,7 @@ __global__ __launch_bounds__(256) void gumbel_argmax_kernel(const float* __restr
     const uint8_t xn = (uint8_t)best_c;
     if (xn != x[idx]) count_changed(&changed[sample], 1);
     x[idx] = xn;
-    enc[(size_t)sample * ld_enc + t] = Elem<T>::from_f32(((float)xn - 128.0f) * (1.0f / 128.0f));
+    enc[frag_offset<T>(sample, t, enc_chunks)] = Elem<T>::from_f32(((float)xn - 128.0f) * (1.0f / 128.0f));
   }
   }
   if (retire.enabled) finish_pass(retire, gridDim.x);
@@ -357,14 +681,14 @@ __global__ __launch_bounds__(256) void gumbel_argmax_kernel(const float* __restr
 
 // Start of a call: x = x_init (or zeros), enc = network input of x, bookkeeping cleared.
 template <typename T>
-__global__ void init_state_kernel(const uint8_t* x_init, uint8_t* x, T* enc, int ld_enc, int N, int D, int C) {
+__global__ void init_state_kernel(const uint8_t* x_init, uint8_t* x, T* enc, int enc_chunks, int N, int D, int C) {
   const size_t total = (size_t)N * D;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     const int n = (int)(i / D), t = (int)(i % D);
     const uint8_t v = x_init ? x_init[i] : 0;
     if (x) x[i] = v;
     const float e = (C == 1) ? (float)v : ((float)v - 128.0f) * (1.0f / 128.0f);
-    enc[(size_t)n * ld_enc + t] = Elem<T>::from_f32(e);
+    enc[frag_offset<T>(n, t, enc_chunks)] = Elem<T>::from_f32(e);
   }
 }
 

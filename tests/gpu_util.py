@@ -20,10 +20,14 @@ def oracle_models(net):
     return exact, same
 
 
+PERSISTENT = True      # execution path the models below are switched to (the tests run both)
+
+
 class GpuModel:
-    def __init__(self, net):
+    def __init__(self, net, persistent=None):
         self.net = net
         self.h = B.model_from_network(net)
+        B.made_set_option(self.h, B.MADE_OPT_PERSISTENT, int(PERSISTENT if persistent is None else persistent))
 
     def close(self):
         if self.h:

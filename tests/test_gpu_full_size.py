@@ -14,7 +14,8 @@ from gpu_util import LOGIT_TOL, MARGIN, GpuModel, assert_logits_close, assert_sa
 pytestmark = pytest.mark.gpu
 
 
-def test_cfg2_jacobi_and_gs_jacobi_full_batch():
+@pytest.mark.parametrize("persistent", [True, False])
+def test_cfg2_jacobi_and_gs_jacobi_full_batch(persistent):
     w = S.workload("cfg2")
     net = S.make_network(w)
     exact, same = oracle_models(net)
@@ -22,7 +23,7 @@ def test_cfg2_jacobi_and_gs_jacobi_full_batch():
     sub = 6
     xs, mg = O.sequential_sample(same, noise[:sub])
     xr, it_ref, _, _, mm = O.jacobi_reference(same, noise)
-    with GpuModel(net) as g:
+    with GpuModel(net, persistent) as g:
         x, it = g.jacobi(noise)
         exempt, _ = assert_sample_parity(same, noise, x)
         assert_sample_parity(same, noise[:sub], x[:sub], xs, mg)

@@ -13,6 +13,16 @@ from gpu_util import LOGIT_TOL, MARGIN, GpuModel, assert_logits_close, assert_sa
 
 pytestmark = pytest.mark.gpu
 
+
+@pytest.fixture(autouse=True, params=["persistent", "per-layer launches"])
+def execution_path(request):
+    """Every test runs on both execution paths of the library (they must agree with the oracle alike)."""
+    import gpu_util
+    gpu_util.PERSISTENT = request.param == "persistent"
+    yield
+    gpu_util.PERSISTENT = True
+
+
 SMALL = ["cfg1", "small_f32", "small_bf16", "mid_bf16", "small_cat", "small_cat_f32"]
 
 
