@@ -54,7 +54,7 @@ def main() -> int:
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip sequential / GS-Jacobi side measurements")
-    ap.add_argument("--path", choices=["persistent", "layers"], default="persistent",
+    ap.add_argument("--path", choices=["persistent", "layers"], default="layers",
                     help="persistent: one cooperative launch per call; layers: one launch per layer and pass")
     args = ap.parse_args()
     if args.gpus != 1:
