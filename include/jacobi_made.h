@@ -149,8 +149,11 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   batch <= 2048 from ONE cooperative launch that keeps a workgroup per CU resident and separates layers by
  *   a grid-wide barrier; 0 = one kernel launch per layer and pass.  Same results either way; on MI355X the
  *   per-layer launches are currently the faster of the two at batch 128, hence the default.
+ *   MADE_OPT_FUSED_CATEGORICAL (default 1): for C = 256, draw the Gumbel-max symbols inside the output layer's
+ *   kernel (logits stay in registers); 0 = write the logits to scratch memory and draw in a second kernel, as
+ *   models with other C always do.
  */
-enum { MADE_OPT_PERSISTENT = 1 };
+enum { MADE_OPT_PERSISTENT = 1, MADE_OPT_FUSED_CATEGORICAL = 2 };
 int made_set_option(made_model* m, int32_t option, int32_t value);
 
 /*

@@ -169,6 +169,7 @@ def made_set_profiling(model: int, enable: bool) -> None:
 
 
 MADE_OPT_PERSISTENT = 1
+MADE_OPT_FUSED_CATEGORICAL = 2
 
 
 def made_set_option(model: int, option: int, value: int) -> None:

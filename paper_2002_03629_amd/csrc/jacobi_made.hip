@@ -106,6 +106,7 @@ struct made_model {
   std::vector<int64_t> prof_launches;         // [L+1]
   std::vector<int64_t> nnz;                   // [L+1] visible (mask = 1) weights per layer
   int persist_grid = 0;                       // workgroups of the persistent kernel (0 = not usable)
+  int fused_categorical = 1;                  // made_set_option(MADE_OPT_FUSED_CATEGORICAL)
   int use_persistent = 0;                     // made_set_option(MADE_OPT_PERSISTENT); off: measured slower, see header
 };
 
@@ -147,7 +148,7 @@ static int ensure_workspace(made_model* m, int N, bool need_z) {
   const int cap = std::max(N, w.N_cap);
   const bool had_z = w.zbuf != nullptr;
   free_workspace(w);
-  const int n_pad = round_up(cap, TILE);
+  const int n_pad = round_up(cap, 2 * TILE);   // the 64-sample kernels read list entries of a whole tile pair
   const size_t es = elem_size(m);
   const size_t enc_bytes = (size_t)n_pad * m->layers[0].in_pad * es;
   HIP_TRY(hipMalloc(&w.enc, enc_bytes));
@@ -220,6 +221,10 @@ extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
   if (!m) return fail(MADE_ERR_ARG, "made_set_option: model is NULL");
   if (option == MADE_OPT_PERSISTENT) {
     m->use_persistent = value != 0;
+    return MADE_OK;
+  }
+  if (option == MADE_OPT_FUSED_CATEGORICAL) {
+    m->fused_categorical = value != 0;
     return MADE_OK;
   }
   return fail(MADE_ERR_ARG, "made_set_option: unknown option %d", option);
@@ -515,6 +520,37 @@ static int run_output_sample(made_model* m, const RowSet& rs, const SampleIO& io
     a.t_hi = io.t_hi;
     a.retire = io.retire;
     launch_layer<EPI_BERNOULLI>(m, m->L, a, tile_hi - tile_lo, row_tiles, s);
+    m->stats[2]++;
+  } else if (C == CAT_C && m->fused_categorical) {
+    CatArgs c;
+    memset(&c, 0, sizeof c);
+    c.A = a.A;
+    c.W = a.W;
+    c.k_chunks = a.k_chunks;
+    c.bias = a.bias;
+    c.tile_kend = a.tile_kend;
+    c.k_cap = a.k_cap;
+    c.rows = rs.rows;
+    c.n_rows_ptr = rs.n_rows_ptr;
+    c.n_rows = rs.n_rows;
+    c.noise = io.noise;
+    c.x = io.x;
+    c.enc = m->ws.enc;
+    c.enc_chunks = m->layers[0].k_chunks;
+    c.changed = m->ws.changed;
+    c.D = m->D;
+    c.t_lo = io.t_lo;
+    c.t_hi = io.t_hi;
+    c.t_begin = whole ? 0 : io.t_lo;
+    c.n_pos = whole ? m->D : io.t_hi - io.t_lo;
+    c.pair_tiles = (rs.n_rows + 2 * TILE - 1) / (2 * TILE);
+    c.retire = io.retire;
+    prof_mark(m, m->L, false, s);
+    if (m->dtype == MADE_BF16)
+      hipLaunchKernelGGL((categorical_output_kernel<bf16_t>), dim3(c.n_pos * c.pair_tiles), dim3(CAT_WAVES * 64), 0, s, c);
+    else
+      hipLaunchKernelGGL((categorical_output_kernel<float>), dim3(c.n_pos * c.pair_tiles), dim3(CAT_WAVES * 64), 0, s, c);
+    prof_mark(m, m->L, true, s);
     m->stats[2]++;
   } else {
     a.out = m->ws.zbuf;

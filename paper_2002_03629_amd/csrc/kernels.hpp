@@ -639,6 +639,174 @@ __global__ __launch_bounds__(NW * 64) void persistent_sampler_kernel(PersistArgs
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Output layer of a 256-class categorical model with the Gumbel-max draw fused in: the logits never
+// leave the registers.
+//
+// A workgroup owns ONE position t and up to 64 active samples; it streams the 256 weight rows of t
+// exactly once (this layer is the model's HBM stream: 2 GiB dense for D = 1024, K = 4096, of which the
+// degree-sorted prefix structure lets it skip about half).  Each of the 4 waves owns 64 classes
+// (two 32-row weight tiles) against both 32-sample tiles: 4 accumulator tiles, no split of K, so the
+// sum order is fixed.  The MFMA takes the WEIGHTS as its row operand: an accumulator lane then holds
+// 16 classes of one sample, the 256-way argmax is 32 in-register compares, one cross-half shuffle and a
+// 4-entry combine through LDS.  Positions with the longest visible prefix are scheduled first.
+// ------------------------------------------------------------------------------------------------
+constexpr int CAT_C = 256;
+constexpr int CAT_WAVES = 4;
+constexpr int CAT_PD = 2;
+
+struct CatArgs {
+  const void* A;         // last hidden layer's activations (fragment-major, k_chunks chunks)
+  const void* W;         // output weights, rows t*256 + c (fragment-major)
+  int k_chunks;
+  const float* bias;     // [D*256]
+  const int* tile_kend;  // per 32-row tile; the 8 tiles of a position share one value
+  int k_cap;
+  const int* rows;
+  const int* n_rows_ptr;
+  int n_rows;
+  const float* noise;    // g[sample, D, 256]
+  uint8_t* x;
+  void* enc;
+  int enc_chunks;
+  int* changed;
+  int D;
+  int t_lo, t_hi;        // positions whose symbol is re-drawn
+  int t_begin, n_pos;    // positions this launch evaluates
+  int pair_tiles;        // sample tiles of 64 this launch covers
+  RetireArgs retire;
+};
+
+template <typename T, int CNT, bool TWO>
+__device__ __forceinline__ void cat_group(const uint4* W0, const uint4* W1, const uint4* A0, const uint4* A1, int c0,
+                                          f32x16 (&acc)[2][2]) {
+  uint4 w0[CNT][4], w1[CNT][4], a0[CNT][4], a1[CNT][4];
+#pragma unroll
+  for (int p = 0; p < CNT; ++p) {
+    const size_t o = (size_t)(c0 + p) * 256;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      w0[p][s] = W0[o + s * 64];
+      w1[p][s] = W1[o + s * 64];
+      a0[p][s] = A0[o + s * 64];
+      if (TWO) a1[p][s] = A1[o + s * 64];
+    }
+  }
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int p = 0; p < CNT; ++p) {
+    mfma_chunk<T>(w0[p], a0[p], acc[0][0]);
+    mfma_chunk<T>(w1[p], a0[p], acc[1][0]);
+    if (TWO) {
+      mfma_chunk<T>(w0[p], a1[p], acc[0][1]);
+      mfma_chunk<T>(w1[p], a1[p], acc[1][1]);
+    }
+  }
+}
+
+template <typename T, bool TWO>
+__device__ __forceinline__ void cat_stream(const uint4* W0, const uint4* W1, const uint4* A0, const uint4* A1,
+                                           int n_chunks, f32x16 (&acc)[2][2]) {
+  int c = 0;
+  for (; c + CAT_PD <= n_chunks; c += CAT_PD) cat_group<T, CAT_PD, TWO>(W0, W1, A0, A1, c, acc);
+  if (c < n_chunks) cat_group<T, 1, TWO>(W0, W1, A0, A1, c, acc);
+}
+
+template <typename T>
+__global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatArgs a) {
+  static_assert(CAT_PD == 2, "the remainder handling assumes a prefetch depth of 2");
+  constexpr int KC = 2 * Elem<T>::EPL;
+  __shared__ float sm_val[CAT_WAVES][64];
+  __shared__ int sm_idx[CAT_WAVES][64];
+  const int n_rows = a.n_rows_ptr ? *a.n_rows_ptr : a.n_rows;
+  const int pos_i = blockIdx.x / a.pair_tiles, pair = blockIdx.x % a.pair_tiles;
+  const int t = a.t_begin + a.n_pos - 1 - pos_i;
+  const int row0 = pair * 64;
+  if (row0 < n_rows) {   // (uniform per workgroup)
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r = lane & 31, h = lane >> 5;
+    const bool two = row0 + 32 < n_rows;
+    const int n0 = a.rows ? a.rows[row0 + r] : (row0 + r < a.n_rows ? row0 + r : 0);
+    const int n1 = a.rows ? a.rows[row0 + 32 + r] : (row0 + 32 + r < a.n_rows ? row0 + 32 + r : 0);
+    int k_end = a.tile_kend[t * (CAT_C / TILE)];
+    if (k_end > a.k_cap) k_end = a.k_cap;
+    const int n_chunks = (k_end + KC - 1) / KC;
+    const size_t group = (size_t)a.k_chunks * 256;
+    const uint4* W0 = (const uint4*)a.W + (size_t)(t * (CAT_C / TILE) + wave * 2) * group + h * 32 + r;
+    const uint4* W1 = W0 + group;
+    const uint4* A0 = (const uint4*)a.A + (size_t)(n0 >> 5) * group + h * 32 + (n0 & 31);
+    const uint4* A1 = (const uint4*)a.A + (size_t)(n1 >> 5) * group + h * 32 + (n1 & 31);
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[q][j][i] = 0.f;
+    if (two)
+      cat_stream<T, true>(W0, W1, A0, A1, n_chunks, acc);
+    else
+      cat_stream<T, false>(W0, W1, A0, A1, n_chunks, acc);
+
+    // acc[q][j][i]: class (wave*2 + q)*32 + 8*(i/4) + 4*h + i%4 of sample tile j's row r
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      if (j == 0 || two) {
+        const int sample = j ? n1 : n0;
+        const float* gp = a.noise + ((size_t)sample * a.D + t) * CAT_C;
+        const float* bp = a.bias + (size_t)t * CAT_C;
+        float best = -INFINITY;
+        int best_c = 0x7fffffff;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            const int cb = (wave * 2 + q) * 32 + 8 * i4 + 4 * h;
+            const float4 gv = *(const float4*)(gp + cb);
+            const float4 bv = *(const float4*)(bp + cb);
+            const float v0 = (acc[q][j][i4 * 4 + 0] + bv.x) + gv.x;
+            const float v1 = (acc[q][j][i4 * 4 + 1] + bv.y) + gv.y;
+            const float v2 = (acc[q][j][i4 * 4 + 2] + bv.z) + gv.z;
+            const float v3 = (acc[q][j][i4 * 4 + 3] + bv.w) + gv.w;
+            // classes are visited in increasing order, so a strict compare keeps the lowest index of a tie
+            if (v0 > best) { best = v0; best_c = cb; }
+            if (v1 > best) { best = v1; best_c = cb + 1; }
+            if (v2 > best) { best = v2; best_c = cb + 2; }
+            if (v3 > best) { best = v3; best_c = cb + 3; }
+          }
+        }
+        const float ob = __shfl_xor(best, 32);
+        const int oc = __shfl_xor(best_c, 32);
+        if (ob > best || (ob == best && oc < best_c)) { best = ob; best_c = oc; }
+        if (h == 0) {
+          sm_val[wave][32 * j + r] = best;
+          sm_idx[wave][32 * j + r] = best_c;
+        }
+      }
+    }
+    __syncthreads();
+    if (threadIdx.x < 64 && row0 + (int)threadIdx.x < n_rows && t >= a.t_lo && t < a.t_hi) {
+      const int sl = threadIdx.x;
+      float best = sm_val[0][sl];
+      int best_c = sm_idx[0][sl];
+#pragma unroll
+      for (int w = 1; w < CAT_WAVES; ++w)
+        if (sm_val[w][sl] > best) { best = sm_val[w][sl]; best_c = sm_idx[w][sl]; }   // waves hold increasing classes
+      const int sample = a.rows ? a.rows[row0 + sl] : row0 + sl;
+      const size_t idx = (size_t)sample * a.D + t;
+      const uint8_t xn = (uint8_t)best_c;
+      if (xn != a.x[idx]) {
+        a.x[idx] = xn;
+        ((T*)a.enc)[frag_offset<T>(sample, t, a.enc_chunks)] =
+            Elem<T>::from_f32(((float)xn - 128.0f) * (1.0f / 128.0f));
+        count_changed(&a.changed[sample], 1);
+      }
+    }
+  }
+  if (a.retire.enabled) finish_pass(a.retire, gridDim.x);
+}
+
 // Gumbel-max draw for categorical positions from logits held in memory:
 // x[n, t] = argmax_c (z[n, t, c] + g[n, t, c]), lowest c on ties.  One wave per (row, t).
 template <typename T>

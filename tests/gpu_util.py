@@ -20,7 +20,8 @@ def oracle_models(net):
     return exact, same
 
 
-PERSISTENT = True      # execution path the models below are switched to (the tests run both)
+PERSISTENT = False     # execution path the models below are switched to (the tests run both)
+FUSED_CATEGORICAL = True
 
 
 class GpuModel:
@@ -28,6 +29,7 @@ class GpuModel:
         self.net = net
         self.h = B.model_from_network(net)
         B.made_set_option(self.h, B.MADE_OPT_PERSISTENT, int(PERSISTENT if persistent is None else persistent))
+        B.made_set_option(self.h, B.MADE_OPT_FUSED_CATEGORICAL, int(FUSED_CATEGORICAL))
 
     def close(self):
         if self.h:

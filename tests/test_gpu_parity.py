@@ -14,13 +14,19 @@ from gpu_util import LOGIT_TOL, MARGIN, GpuModel, assert_logits_close, assert_sa
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=["persistent", "per-layer launches"])
+@pytest.fixture(autouse=True, params=["per-layer launches", "persistent", "unfused categorical"])
 def execution_path(request):
-    """Every test runs on both execution paths of the library (they must agree with the oracle alike)."""
+    """Every test runs on every execution path of the library (they must all agree with the oracle)."""
     import gpu_util
+    if request.param == "unfused categorical":
+        name = getattr(request.node, "callspec", None) and request.node.callspec.params.get("name")
+        if name != "small_cat":
+            pytest.skip("only the 256-class workload has a fused and an unfused output path")
     gpu_util.PERSISTENT = request.param == "persistent"
+    gpu_util.FUSED_CATEGORICAL = request.param != "unfused categorical"
     yield
-    gpu_util.PERSISTENT = True
+    gpu_util.PERSISTENT = False
+    gpu_util.FUSED_CATEGORICAL = True
 
 
 SMALL = ["cfg1", "small_f32", "small_bf16", "mid_bf16", "small_cat", "small_cat_f32"]
