@@ -23,8 +23,9 @@ PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3
 
 
-def cpu_baseline(w, net, noise, budget_s=20.0):
-    """The numpy oracle's sequential sampler, as it stands, on a bounded sub-batch."""
+def cpu_baseline(w, net, noises, budget_s=12.0):
+    """The numpy oracle's sequential sampler, as it stands, on a bounded sample of the workload: whole batches
+    (different noise each) until about budget_s seconds of CPU work are done, at least one batch."""
     from oracle import made_oracle as O
     try:
         from threadpoolctl import threadpool_info
@@ -32,18 +33,36 @@ def cpu_baseline(w, net, noise, budget_s=20.0):
     except Exception:
         cores = 1
     model = O.build_model(net.D, net.C, net.degrees, net.W, net.b, "bf16" if net.dtype == "bf16" else None)
-    n = 2
+    sub = noises[0].shape[0] if net.D * net.C < (1 << 16) else min(8, noises[0].shape[0])   # huge models: 8 samples
+    O.sequential_sample(model, noises[0][:1])              # warm the BLAS threads
+    done, xs0 = 0, None
     t0 = time.perf_counter()
-    O.sequential_sample(model, noise[:n])
+    for r in range(len(noises)):
+        xs, _ = O.sequential_sample(model, noises[r][:sub])
+        if r == 0:
+            xs0 = xs
+        done += sub
+        if time.perf_counter() - t0 > budget_s:
+            break
     dt = time.perf_counter() - t0
-    # grow the sample so that the timed run takes roughly budget_s, capped at the batch
-    n2 = int(min(noise.shape[0], max(n, n * budget_s / max(dt, 1e-3) * 0.5)))
-    t0 = time.perf_counter()
-    xs, _ = O.sequential_sample(model, noise[:n2])
-    dt = time.perf_counter() - t0
-    return {"value": n2 / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"oracle sequential_sample (numpy fp64, bf16-rounded activations) on {n2} of {noise.shape[0]} "
-                      f"samples of one batch, {dt:.1f} s"}, xs, n2
+    return {"value": done / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"oracle sequential_sample (numpy fp64, activations rounded as on the GPU) on {done} samples "
+                      f"({done // sub} x {sub} of a batch of {noises[0].shape[0]}), {dt:.1f} s"}, xs0, sub
+
+
+def measured_traffic(workload: str, path: str, dom_is_output: bool):
+    """HBM bytes per launch of the dominant kernel, as measured with rocprofv3 PMC counters in a separate run
+    (counters cannot be read from inside this process); the summary under profiles/ holds the figure."""
+    if workload != "cfg2" or path != "layers" or not dom_is_output:
+        return None
+    fn = os.path.join(ROOT, "profiles", "cfg2_jacobi_pmc_traffic.txt")
+    try:
+        for line in open(fn):
+            if line.startswith("traffic_bytes_per_launch"):
+                return int(line.rsplit(":", 1)[1])
+    except OSError:
+        pass
+    return None
 
 
 def main() -> int:
@@ -56,6 +75,9 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true", help="skip sequential / GS-Jacobi side measurements")
     ap.add_argument("--path", choices=["persistent", "layers"], default="layers",
                     help="persistent: one cooperative launch per call; layers: one launch per layer and pass")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="no timing: run 20 device copies of 64 MiB (calibration of FETCH_SIZE / WRITE_SIZE), then "
+                         "20 steps; meant to run under `rocprofv3 --pmc ...`")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (samples are independent systems; see DESIGN.md "
@@ -88,6 +110,19 @@ def main() -> int:
 
     def step(i):
         B.jacobi_sample(model, noises[i % n_noise], N, None, 0, x, iters, stream)
+
+    if args.pmc_probe:
+        src = torch.ones((16 << 20,), dtype=torch.float32, device="cuda")     # 64 MiB read + 64 MiB written per copy
+        dst = torch.empty_like(src)
+        for _ in range(20):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        for i in range(20):
+            step(i)
+        torch.cuda.synchronize()
+        B.made_free(model)
+        print(json.dumps({"pmc_probe": True, "copy_bytes_read": 64 << 20, "copy_bytes_written": 64 << 20}))
+        return 0
 
     for i in range(args.warmup):
         step(i)
@@ -127,8 +162,19 @@ def main() -> int:
 
     dom = int(np.argmax(layer_ms))
     dom_avg_us = layer_ms[dom] / max(1, layer_launches[dom]) * 1e3
-    achieved = layer_flops[dom] / (layer_ms[dom] * 1e-3) / 1e12 if layer_ms[dom] > 0 else 0.0
-    peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_F32_TFLOPS
+    es = 2 if w.dtype == "bf16" else 4
+    # A layer whose visible weights exceed the chip's caches (32 MB L2 + 256 MB Infinity Cache) must be
+    # streamed from HBM once per pass; at batch <= 128 that puts it far below the MFMA ridge: HBM-bound.
+    hbm_bound = dom < n_layers and nnz[dom] * es > 288e6
+    if hbm_bound:
+        noise_bytes = 4.0 * D * w.C * (w.C > 1) + 4.0 * D * (w.C == 1)       # per active sample
+        act_bytes = es * (w.hidden[-1] if dom == n_layers - 1 else 0)
+        dom_bytes = layer_launches[dom] * nnz[dom] * es + sample_passes * (noise_bytes + act_bytes)
+        achieved = dom_bytes / (layer_ms[dom] * 1e-3) / 1e9
+        peak, unit, bound = 8000.0, "GB/s", "hbm"
+    else:
+        achieved = layer_flops[dom] / (layer_ms[dom] * 1e-3) / 1e12 if layer_ms[dom] > 0 else 0.0
+        peak, unit, bound = (PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_F32_TFLOPS), "TFLOP/s", "mfma"
     if dom == n_layers:
         layer_name = "persistent_sampler_kernel (all passes of a call: hidden layers, output layer + sampling, stop test)"
     else:
@@ -155,12 +201,15 @@ def main() -> int:
         "iters_max": it_max,
         "passes_per_step": passes / args.steps,
         "roofline": {
-            "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-            "traffic": None, "kernel": layer_name, "avg_launch_us": dom_avg_us,
+            "bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+            "traffic": measured_traffic(w.name, args.path, dom == n_layers - 1), "kernel": layer_name, "avg_launch_us": dom_avg_us,
             "launches": int(layer_launches[dom]),
             "per_slot_avg_us": [float(m / max(1, c) * 1e3) for m, c in zip(layer_ms, layer_launches)],
-            "note": "algorithmic flops = 2*nnz(W*mask) per active sample per pass; durations from HIP events "
-                    "around each launch on the launch stream (second pass over the same steps)",
+            "mfma_tflops": layer_flops[dom] / (layer_ms[dom] * 1e-3) / 1e12 if layer_ms[dom] > 0 else 0.0,
+            "note": "algorithmic flops = 2*nnz(W*mask) per active sample per pass; algorithmic bytes (hbm bound) = "
+                    "visible weights once per launch + noise and last-hidden activations per active sample; "
+                    "durations from HIP events around each launch on the launch stream (second pass over the "
+                    "same steps)",
         },
         "whole_call_tflops": 2.0 * sum(nnz) * sample_passes / elapsed_prof / 1e12,
         "ms_per_step_with_events": elapsed_prof / args.steps * 1e3,
@@ -204,7 +253,7 @@ def main() -> int:
         result["extras"] = extras
 
     if not args.no_cpu_baseline:
-        base, xs, n2 = cpu_baseline(w, net, noises_host[0])
+        base, xs, n2 = cpu_baseline(w, net, noises_host)
         result["cpu_baseline"] = base
         if x_jac is not None:
             result["cpu_baseline"]["gpu_matches_oracle_on_sample"] = bool(

@@ -64,7 +64,8 @@ class MadeModel:
     D: int                      # positions (T in the paper)
     C: int                      # 1: Bernoulli position, >1: C-way categorical position
     masks: List[np.ndarray]     # L+1 boolean masks, [out, in]
-    WM: List[np.ndarray]        # L+1 masked weights (W * mask), float64, [out, in]
+    WM: List[np.ndarray]        # L+1 masked weights (W * mask), [out, in], float64; a multi-GiB layer given as
+                                # float32 is kept as float32 (an exact copy; all arithmetic on it is float64)
     b: List[np.ndarray]         # L+1 biases, float64
     act_round: Optional[str]    # None, or "bf16": round every hidden activation to bfloat16
 
@@ -95,7 +96,14 @@ def build_model(D: int, C: int, degrees: Sequence[np.ndarray], W: Sequence[np.nd
     WM, bb = [], []
     for Wl, Ml, bl in zip(W, masks, b):
         assert Wl.shape == Ml.shape, (Wl.shape, Ml.shape)
-        WM.append(np.where(Ml, np.asarray(Wl, dtype=np.float64), 0.0))
+        Wl = np.asarray(Wl)
+        keep32 = Wl.dtype == np.float32 and Wl.size > (1 << 27)      # only multi-GiB layers stay float32
+        masked = np.array(Wl, dtype=np.float32 if keep32 else np.float64, copy=True)
+        rows = max(1, (1 << 26) // Wl.shape[1])         # row blocks only bound the temporaries
+        for r0 in range(0, Wl.shape[0], rows):
+            blk = masked[r0:r0 + rows]
+            blk[~Ml[r0:r0 + rows]] = 0.0
+        WM.append(masked)
         bb.append(np.zeros(Wl.shape[0]) if bl is None else np.asarray(bl, dtype=np.float64))
     assert act_round in (None, "bf16")
     return MadeModel(D, C, masks, WM, bb, act_round)
@@ -109,11 +117,23 @@ def encode(x: np.ndarray, C: int) -> np.ndarray:
     return x if C == 1 else (x - 128.0) / 128.0
 
 
+def affine(h: np.ndarray, WM: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """h (W * M)^T + b in float64.  Weights stored as float32 are widened (exactly) block of rows by block
+    of rows, which only limits memory: every product and sum is float64."""
+    if WM.dtype == np.float64:
+        return h @ WM.T + b
+    out = np.empty((h.shape[0], WM.shape[0]))
+    rows = max(1, (1 << 25) // WM.shape[1])
+    for r0 in range(0, WM.shape[0], rows):
+        out[:, r0:r0 + rows] = h @ WM[r0:r0 + rows].astype(np.float64).T
+    return out + b
+
+
 def last_hidden(model: MadeModel, x: np.ndarray) -> np.ndarray:
     """h_L for a batch of symbol vectors x[N, D]: h_l = ReLU((W_l * M_l) h_{l-1} + b_l)."""
     h = encode(x, model.C)
     for WM, b in zip(model.WM[:-1], model.b[:-1]):
-        h = np.maximum(h @ WM.T + b, 0.0)
+        h = np.maximum(affine(h, WM, b), 0.0)
         if model.act_round == "bf16":
             h = round_to_bf16(h)
     return h
@@ -122,7 +142,7 @@ def last_hidden(model: MadeModel, x: np.ndarray) -> np.ndarray:
 def logits_all(model: MadeModel, x: np.ndarray) -> np.ndarray:
     """Logits of every position, z[N, D, C], from one pass over the whole network."""
     h = last_hidden(model, x)
-    z = h @ model.WM[-1].T + model.b[-1]
+    z = affine(h, model.WM[-1], model.b[-1])
     return z.reshape(x.shape[0], model.D, model.C)
 
 
@@ -130,7 +150,7 @@ def logits_at(model: MadeModel, x: np.ndarray, t: int) -> np.ndarray:
     """Logits of position t (0-based) only, z[N, C]: the quantity h_t needs."""
     h = last_hidden(model, x)
     rows = slice(t * model.C, (t + 1) * model.C)
-    return h @ model.WM[-1][rows].T + model.b[-1][rows]
+    return affine(h, model.WM[-1][rows], model.b[-1][rows])
 
 
 def decide(z: np.ndarray, noise: np.ndarray, C: int) -> Tuple[np.ndarray, np.ndarray]:

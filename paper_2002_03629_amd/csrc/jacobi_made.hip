@@ -18,6 +18,7 @@
 #include <new>
 #include <numeric>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "kernels.hpp"
@@ -330,16 +331,32 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
       const size_t es = elem_size(m);
       std::vector<uint8_t> host(n_w * es, 0);
       const float* Wl = W[l];
-      for (int j = 0; j < ly.out_dim; ++j) {
-        const float* src = Wl + (size_t)perm[j] * ly.in_dim;
-        const int kl = klen[j];
-        if (m->dtype == MADE_BF16) {
-          uint16_t* dst = (uint16_t*)host.data();
-          for (int i = 0; i < kl; ++i) dst[frag_offset<bf16_t>(j, i, ly.k_chunks)] = host_f32_to_bf16(src[perm_prev[i]]);
-        } else {
-          float* dst = (float*)host.data();
-          for (int i = 0; i < kl; ++i) dst[frag_offset<float>(j, i, ly.k_chunks)] = src[perm_prev[i]];
+      // mask, permute, convert and lay out in fragment-major order; rows are independent, so large layers
+      // (the 2 GiB output layer of a 256-class model) are filled by several host threads
+      auto fill_rows = [&](int j0, int j1) {
+        for (int j = j0; j < j1; ++j) {
+          const float* src = Wl + (size_t)perm[j] * ly.in_dim;
+          const int kl = klen[j];
+          if (m->dtype == MADE_BF16) {
+            uint16_t* dst = (uint16_t*)host.data();
+            for (int i = 0; i < kl; ++i) dst[frag_offset<bf16_t>(j, i, ly.k_chunks)] = host_f32_to_bf16(src[perm_prev[i]]);
+          } else {
+            float* dst = (float*)host.data();
+            for (int i = 0; i < kl; ++i) dst[frag_offset<float>(j, i, ly.k_chunks)] = src[perm_prev[i]];
+          }
         }
+      };
+      const int n_threads = n_w > ((size_t)1 << 24) ? 16 : 1;
+      if (n_threads == 1) {
+        fill_rows(0, ly.out_dim);
+      } else {
+        std::vector<std::thread> pool;
+        const int per = (ly.out_dim + n_threads - 1) / n_threads;
+        for (int i = 0; i < n_threads; ++i) {
+          const int j0 = std::min(ly.out_dim, i * per), j1 = std::min(ly.out_dim, (i + 1) * per);
+          if (j0 < j1) pool.emplace_back(fill_rows, j0, j1);
+        }
+        for (std::thread& th : pool) th.join();
       }
       std::vector<float> hb(ly.out_pad, 0.f);
       if (b && b[l])

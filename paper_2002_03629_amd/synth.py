@@ -14,6 +14,8 @@ from __future__ import annotations
 from dataclasses import dataclass, field
 from typing import List, Optional
 
+import os
+
 import numpy as np
 
 SEED_BASE = 2002036290
@@ -69,10 +71,20 @@ def bf16_representable(a: np.ndarray) -> np.ndarray:
     Pure data preparation: the library and the oracle both receive these already
     representable numbers, so neither has to agree with the other on how to round weights.
     """
-    bits = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
-    lsb = (bits >> 16) & 1
-    rounded = ((bits + 0x7FFF + lsb) >> 16) << 16
-    return rounded.astype(np.uint32).view(np.float32).reshape(a.shape)
+    out = np.array(a, dtype=np.float32, copy=True, order="C")
+    _round_bf16_inplace(out)
+    return out
+
+
+def _round_bf16_inplace(out: np.ndarray) -> None:
+    flat = out.reshape(-1).view(np.uint32)
+    step = 1 << 24                                   # bounded temporaries for multi-GiB matrices
+    for i in range(0, flat.size, step):
+        bits = flat[i:i + step]
+        lsb = (bits >> np.uint32(16)) & np.uint32(1)
+        # no finite normal weight is within 0x8000 of the uint32 range's end, so this cannot wrap
+        bits += np.uint32(0x7FFF) + lsb
+        bits &= np.uint32(0xFFFF0000)
 
 
 def hidden_degrees(rule: str, D: int, widths: List[int], seed: int) -> List[np.ndarray]:
@@ -105,9 +117,29 @@ def dense_weights(D: int, C: int, widths: List[int], rule: str, seed: int, gain:
     for l in range(len(dims) - 1):
         fan_in, fan_out = dims[l], dims[l + 1]
         std = 0.1 if rule == "std0.1" else (1.0 / np.sqrt(fan_in))
-        w = g.standard_normal(size=(fan_out, fan_in), dtype=np.float32)
-        w *= np.float32(std * gain)
-        Ws.append(bf16_representable(w) if bf16 else w)
+        scale = np.float32(std * gain)
+        if fan_out * fan_in <= (1 << 26):
+            w = g.standard_normal(size=(fan_out, fan_in), dtype=np.float32)
+            w *= scale
+            if bf16:
+                _round_bf16_inplace(w)
+        else:
+            # multi-GiB layer: row blocks are drawn from jumped copies of the layer's own stream, in parallel
+            w = np.empty((fan_out, fan_in), dtype=np.float32)
+            rows = max(1, (1 << 24) // fan_in)
+
+            def draw(i, w=w, rows=rows, l=l, scale=scale):
+                blk = w[i * rows:(i + 1) * rows]
+                gb = np.random.Generator(np.random.Philox(int(seed)).jumped(1 + 65536 * (l + 1) + i))
+                gb.standard_normal(size=blk.shape, dtype=np.float32, out=blk)
+                blk *= scale
+                if bf16:
+                    _round_bf16_inplace(blk)
+
+            from concurrent.futures import ThreadPoolExecutor
+            with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+                list(pool.map(draw, range((fan_out + rows - 1) // rows)))
+        Ws.append(w)
     return Ws
 
 

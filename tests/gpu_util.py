@@ -1,4 +1,8 @@
 """Helpers shared by the GPU parity tests (test code; may import both the binding and the oracle)."""
+import dataclasses
+import os
+import time
+
 import numpy as np
 import torch
 
@@ -9,6 +13,18 @@ MARGIN = 1e-3          # positions whose oracle decision margin is below this ar
 LOGIT_TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 
+def progress(msg):
+    """Long tests leave a trace outside pytest's capture so that a watcher sees they are alive."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    d = os.path.join(root, "gpurun_out")
+    try:
+        os.makedirs(d, exist_ok=True)
+        with open(os.path.join(d, "test_progress.log"), "a") as f:
+            f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
+    except OSError:
+        pass
+
+
 def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to("cuda")
 
@@ -16,7 +32,8 @@ def dev(a):
 def oracle_models(net):
     """(exact fp64 model, model whose hidden activations are rounded like the library's)."""
     exact = O.build_model(net.D, net.C, net.degrees, net.W, net.b, None)
-    same = O.build_model(net.D, net.C, net.degrees, net.W, net.b, "bf16") if net.dtype == "bf16" else exact
+    # the two differ only in the activation-rounding switch; share the (possibly multi-GiB) arrays
+    same = dataclasses.replace(exact, act_round="bf16") if net.dtype == "bf16" else exact
     return exact, same
 
 

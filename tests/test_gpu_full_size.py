@@ -9,7 +9,8 @@ import pytest
 from oracle import made_oracle as O
 from paper_2002_03629_amd import synth as S
 
-from gpu_util import LOGIT_TOL, MARGIN, GpuModel, assert_logits_close, assert_sample_parity, oracle_models
+from gpu_util import (LOGIT_TOL, MARGIN, GpuModel, assert_logits_close, assert_sample_parity, oracle_models,
+                      progress)
 
 pytestmark = pytest.mark.gpu
 
@@ -43,3 +44,39 @@ def test_cfg2_jacobi_and_gs_jacobi_full_batch(persistent):
             xq = g.sequential(noise, mode)
             assert_sample_parity(same, noise, xq)
             assert_sample_parity(same, noise[:sub], xq[:sub], xs, mg)
+
+
+@pytest.mark.timeout(900)
+def test_cfg4_categorical_full_size():
+    """D = 1024 positions x 256 classes, 2 x 4096 hidden, 2 GiB output layer, batch 64.  The whole batch is
+    certified with one oracle pass per sample; a sub-batch is compared with the oracle's sequential run."""
+    w = S.workload("cfg4")
+    progress("cfg4: drawing the network")
+    net = S.make_network(w)
+    progress("cfg4: building the oracle models")
+    exact, same = oracle_models(net)
+    noise = S.make_noise(w)
+    sub = 2
+    progress("cfg4: oracle sequential run of 2 samples")
+    xs, mg = O.sequential_sample(same, noise[:sub])
+    progress("cfg4: made_init")
+    with GpuModel(net) as g:
+        progress("cfg4: jacobi on the GPU, then the oracle certificate")
+        x, it = g.jacobi(noise)
+        exempt, _ = assert_sample_parity(same, noise, x)
+        assert_sample_parity(same, noise[:sub], x[:sub], xs, mg)
+        st = g.stats()
+        print(f"cfg4 jacobi: passes mean {it.mean():.2f} max {it.max()}, exempt positions {exempt}, stats {st}")
+        progress("cfg4: oracle jacobi of 8 samples")
+        ref = O.jacobi_reference(same, noise[:8])
+        clear = ref[4] >= MARGIN
+        assert (it[:8][clear] == ref[1][clear]).all()
+        z = g.logits(x[:2])
+        assert_logits_close(z, O.logits_all(exact, x[:2]), LOGIT_TOL["bf16"])
+        progress("cfg4: gs-jacobi, sequential")
+        xb, itb = g.gs_jacobi(noise, 128)
+        assert_sample_parity(same, noise, xb)
+        assert_sample_parity(same, noise[:sub], xb[:sub], xs, mg)
+        xq = g.sequential(noise[:8], 1)
+        assert_sample_parity(same, noise[:8], xq)
+        assert_sample_parity(same, noise[:sub], xq[:sub], xs, mg)
