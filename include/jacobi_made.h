@@ -152,8 +152,13 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   MADE_OPT_FUSED_CATEGORICAL (default 1): for C = 256, draw the Gumbel-max symbols inside the output layer's
  *   kernel (logits stay in registers); 0 = write the logits to scratch memory and draw in a second kernel, as
  *   models with other C always do.
+ *   MADE_OPT_CHAINS (default 1, range 1..8): the batch is cut into this many contiguous sub-batches of whole
+ *   32-sample tiles, each iterated on its own internal stream (samples are independent systems), so that the
+ *   chains' dependent kernel launches can overlap.  The caller's stream waits for all of them before the call
+ *   returns.  With one host thread enqueuing, more chains mean proportionally more launches; at batch 128 on
+ *   MI355X that costs more than the overlap gains, hence the default of a single chain.
  */
-enum { MADE_OPT_PERSISTENT = 1, MADE_OPT_FUSED_CATEGORICAL = 2 };
+enum { MADE_OPT_PERSISTENT = 1, MADE_OPT_FUSED_CATEGORICAL = 2, MADE_OPT_CHAINS = 3 };
 int made_set_option(made_model* m, int32_t option, int32_t value);
 
 /*

@@ -71,23 +71,53 @@ struct Layer {
   int* cnt_lt = nullptr;         // device, hidden layers only: [D + 2] prefix lengths by degree
 };
 
+// A chain is a contiguous range of the batch's samples that is iterated on its own HIP stream.  Samples are
+// independent systems (each has its own noise), so chains never exchange anything; running several of them
+// concurrently overlaps the dispatch latency of one chain's dependent kernels with another chain's work.
+struct Chain {
+  hipStream_t own_stream = nullptr;  // created with the chain
+  hipStream_t stream = nullptr;      // the stream this call runs the chain on (the caller's when there is one chain)
+  hipEvent_t done_ev = nullptr;
+  int* rows[2] = {nullptr, nullptr};
+  int* n_rows[2] = {nullptr, nullptr};
+  int* done_ctr = nullptr;           // workgroups-finished counter of the pass's last kernel
+  volatile int* h_pin = nullptr;     // pinned, device-visible: [i] = active count after this chain's i-th pass
+  int* d_pin = nullptr;              // the same memory as the device addresses it
+  int pin_len = 0, rows_cap = 0;
+  // per call
+  int first = 0, count = 0;
+  size_t block = 0;                  // index into the call's block list
+  int k_enq = 0, k_conf = 0;         // passes of the current block enqueued / whose result the host has seen
+  bool block_started = false, finished = false, iters_cleared = false;
+  std::vector<char> log_first;       // per enqueued pass: was it the first of its block
+};
+
+static void free_chain(Chain& c) {
+  for (int i = 0; i < 2; ++i) {
+    if (c.rows[i]) (void)hipFree(c.rows[i]);
+    if (c.n_rows[i]) (void)hipFree(c.n_rows[i]);
+  }
+  if (c.done_ctr) (void)hipFree(c.done_ctr);
+  if (c.h_pin) (void)hipHostFree((void*)c.h_pin);
+  if (c.done_ev) (void)hipEventDestroy(c.done_ev);
+  if (c.own_stream) (void)hipStreamDestroy(c.own_stream);
+  c = Chain();
+}
+
 struct Workspace {
   int N_cap = 0;
   void* enc = nullptr;               // [N_pad, D_pad] network input of the current iterate
   std::vector<void*> act;            // hidden activations, [N_pad, pad(H_l)]
   float* zbuf = nullptr;             // categorical only: logits [N, D*C]
-  int* rows[2] = {nullptr, nullptr};
-  int* n_rows[2] = {nullptr, nullptr};
   int* changed = nullptr;
   int* iters = nullptr;
   int* flags = nullptr;
-  int* done_ctr = nullptr;           // workgroups-finished counter of the pass's last kernel
   int n_pad = 0;
+  std::vector<Chain> chains;         // independent sub-batches, each on its own stream
+  hipEvent_t fork_ev = nullptr;
   unsigned* bar = nullptr;           // persistent kernel: grid barrier counter
   long long* dev_stats = nullptr;    // persistent kernel: [passes, sample-passes]
-  volatile int* h_pin = nullptr;     // pinned, device-visible host words: [0] flags copy, [1 + i] active count after pass i
-  int* d_pin = nullptr;              // the same memory as the device addresses it
-  int h_pin_len = 0;
+  volatile int* h_pin = nullptr;     // pinned host words: [0] flags copy, [2..5] persistent kernel's statistics
 };
 
 struct made_model {
@@ -107,6 +137,7 @@ struct made_model {
   std::vector<int64_t> prof_launches;         // [L+1]
   std::vector<int64_t> nnz;                   // [L+1] visible (mask = 1) weights per layer
   int persist_grid = 0;                       // workgroups of the persistent kernel (0 = not usable)
+  int n_chains = 1;                           // made_set_option(MADE_OPT_CHAINS)
   int fused_categorical = 1;                  // made_set_option(MADE_OPT_FUSED_CATEGORICAL)
   int use_persistent = 0;                     // made_set_option(MADE_OPT_PERSISTENT); off: measured slower, see header
 };
@@ -127,11 +158,9 @@ static void free_workspace(Workspace& w) {
   for (void* p : w.act)
     if (p) (void)hipFree(p);
   if (w.zbuf) (void)hipFree(w.zbuf);
-  for (int i = 0; i < 2; ++i) {
-    if (w.rows[i]) (void)hipFree(w.rows[i]);
-    if (w.n_rows[i]) (void)hipFree(w.n_rows[i]);
-  }
-  if (w.done_ctr) (void)hipFree(w.done_ctr);
+  for (Chain& c : w.chains) free_chain(c);
+  w.chains.clear();
+  if (w.fork_ev) (void)hipEventDestroy(w.fork_ev);
   if (w.bar) (void)hipFree(w.bar);
   if (w.dev_stats) (void)hipFree(w.dev_stats);
   if (w.changed) (void)hipFree(w.changed);
@@ -144,8 +173,7 @@ static void free_workspace(Workspace& w) {
 static int ensure_workspace(made_model* m, int N, bool need_z) {
   Workspace& w = m->ws;
   need_z = need_z && m->C > 1;
-  const int need_pin = m->D + 8;
-  if (N <= w.N_cap && (!need_z || w.zbuf) && w.h_pin_len >= need_pin) return MADE_OK;
+  if (N <= w.N_cap && (!need_z || w.zbuf)) return MADE_OK;
   const int cap = std::max(N, w.N_cap);
   const bool had_z = w.zbuf != nullptr;
   free_workspace(w);
@@ -163,23 +191,39 @@ static int ensure_workspace(made_model* m, int N, bool need_z) {
   if ((need_z || had_z) && m->C > 1) {
     HIP_TRY(hipMalloc((void**)&w.zbuf, (size_t)cap * m->D * m->C * sizeof(float)));
   }
-  for (int i = 0; i < 2; ++i) {
-    HIP_TRY(hipMalloc((void**)&w.rows[i], (size_t)n_pad * sizeof(int)));
-    HIP_TRY(hipMemset(w.rows[i], 0, (size_t)n_pad * sizeof(int)));   // kernels may read past the active count
-    HIP_TRY(hipMalloc((void**)&w.n_rows[i], sizeof(int)));
-  }
-  HIP_TRY(hipMalloc((void**)&w.done_ctr, sizeof(int)));
-  HIP_TRY(hipMemset(w.done_ctr, 0, sizeof(int)));
+  HIP_TRY(hipEventCreateWithFlags(&w.fork_ev, hipEventDisableTiming));
   HIP_TRY(hipMalloc((void**)&w.changed, (size_t)2 * n_pad * sizeof(int)));
   w.n_pad = n_pad;
   HIP_TRY(hipMalloc((void**)&w.bar, sizeof(unsigned)));
   HIP_TRY(hipMalloc((void**)&w.dev_stats, 2 * sizeof(long long)));
   HIP_TRY(hipMalloc((void**)&w.iters, (size_t)n_pad * sizeof(int)));
   HIP_TRY(hipMalloc((void**)&w.flags, sizeof(int)));
-  HIP_TRY(hipHostMalloc((void**)&w.h_pin, (size_t)need_pin * sizeof(int), hipHostMallocMapped));
-  HIP_TRY(hipHostGetDevicePointer((void**)&w.d_pin, (void*)w.h_pin, 0));
-  w.h_pin_len = need_pin;
+  HIP_TRY(hipHostMalloc((void**)&w.h_pin, 8 * sizeof(int), hipHostMallocDefault));
   w.N_cap = cap;
+  return MADE_OK;
+}
+
+// Chain i of n_chains with room for rows_cap samples and a pass log of pin_len entries.
+static int ensure_chain(made_model* m, size_t i, int rows_cap, int pin_len) {
+  Workspace& w = m->ws;
+  if (w.chains.size() <= i) w.chains.resize(i + 1);
+  Chain& c = w.chains[i];
+  if (c.own_stream && c.rows_cap >= rows_cap && c.pin_len >= pin_len) return MADE_OK;
+  free_chain(c);
+  rows_cap = round_up(rows_cap, 2 * TILE);
+  HIP_TRY(hipStreamCreateWithFlags(&c.own_stream, hipStreamNonBlocking));
+  HIP_TRY(hipEventCreateWithFlags(&c.done_ev, hipEventDisableTiming));
+  for (int b = 0; b < 2; ++b) {
+    HIP_TRY(hipMalloc((void**)&c.rows[b], (size_t)rows_cap * sizeof(int)));
+    HIP_TRY(hipMemset(c.rows[b], 0, (size_t)rows_cap * sizeof(int)));   // kernels may read past the active count
+    HIP_TRY(hipMalloc((void**)&c.n_rows[b], sizeof(int)));
+  }
+  HIP_TRY(hipMalloc((void**)&c.done_ctr, sizeof(int)));
+  HIP_TRY(hipMemset(c.done_ctr, 0, sizeof(int)));
+  HIP_TRY(hipHostMalloc((void**)&c.h_pin, (size_t)pin_len * sizeof(int), hipHostMallocMapped));
+  HIP_TRY(hipHostGetDevicePointer((void**)&c.d_pin, (void*)c.h_pin, 0));
+  c.rows_cap = rows_cap;
+  c.pin_len = pin_len;
   return MADE_OK;
 }
 
@@ -226,6 +270,11 @@ extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
   }
   if (option == MADE_OPT_FUSED_CATEGORICAL) {
     m->fused_categorical = value != 0;
+    return MADE_OK;
+  }
+  if (option == MADE_OPT_CHAINS) {
+    if (value < 1 || value > 8) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_CHAINS=%d outside [1, 8]", value);
+    m->n_chains = value;
     return MADE_OK;
   }
   return fail(MADE_ERR_ARG, "made_set_option: unknown option %d", option);
@@ -604,15 +653,6 @@ static int launch_init_state(made_model* m, const uint8_t* x_init, uint8_t* x, i
   return MADE_OK;
 }
 
-static int launch_reset_rows(made_model* m, int which, int N, bool clear_iters, hipStream_t s) {
-  hipLaunchKernelGGL(reset_rows_kernel, dim3((N + 255) / 256), dim3(256), 0, s, m->ws.rows[which], m->ws.n_rows[which], N,
-                     m->ws.changed, clear_iters ? m->ws.iters : nullptr, clear_iters ? m->ws.flags : nullptr,
-                     m->ws.done_ctr);
-  m->stats[2]++;
-  HIP_TRY(hipGetLastError());
-  return MADE_OK;
-}
-
 static int check_call(made_model* m, const void* noise, int32_t N, const void* x_out, const char* who) {
   if (!m) return fail(MADE_ERR_ARG, "%s: model is NULL", who);
   if (N < 0) return fail(MADE_ERR_ARG, "%s: N=%d is negative", who, N);
@@ -644,6 +684,188 @@ extern "C" int made_forward_logits(made_model* m, const uint8_t* x, int32_t N, f
   return MADE_OK;
 }
 
+// One block of a call's schedule: positions [a, b) are iterated at most `cap` times (Algorithm 1: a single
+// block [0, D); Algorithm 3: consecutive blocks; sequential sampling: D blocks of one position and one pass).
+struct Block {
+  int a = 0, b = 0, cap = 0;
+  bool stop_test = true;          // false: no retire step (a one-pass block needs no stop test)
+  bool whole_network = false;     // evaluate every output tile even though only [a, b) is re-drawn
+  bool limited = false;           // evaluate only hidden units of degree < b (1-based), see run_hidden
+  std::vector<int> hidden_limit;  // [L] when limited
+  int in_limit = -1, out_k_limit = -1;
+};
+
+static Block make_block(const made_model* m, int a, int b, int cap, bool limited) {
+  Block blk;
+  blk.a = a;
+  blk.b = b;
+  blk.cap = cap;
+  blk.limited = limited;
+  if (limited) {
+    // positions <= b (1-based) read last-layer units of degree < b; those read units of degree <= their own,
+    // and inputs of index <= b - 1
+    blk.hidden_limit.resize(m->L);
+    for (int l = 0; l < m->L; ++l) blk.hidden_limit[l] = m->cnt_lt[l][b];
+    blk.in_limit = b - 1;
+    blk.out_k_limit = blk.hidden_limit[m->L - 1];
+  }
+  return blk;
+}
+
+// Enqueue the next pass of chain c's current block on the chain's stream.
+static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* noise, uint8_t* x,
+                        bool flag_unconverged) {
+  Workspace& w = m->ws;
+  hipStream_t s = c.stream;
+  if (!c.block_started) {
+    // the active list restarts as the chain's whole range (blocks without a stop test never shrink it)
+    if (blk.stop_test || !c.iters_cleared) {
+      hipLaunchKernelGGL(reset_rows_kernel, dim3((c.count + 255) / 256), dim3(256), 0, s, c.rows[0], c.n_rows[0],
+                         c.first, c.count, w.changed, c.iters_cleared ? nullptr : w.iters, c.done_ctr);
+      m->stats[2]++;
+      c.iters_cleared = true;
+    }
+    c.block_started = true;
+  }
+  const int k = c.k_enq + 1;
+  const int in = (k - 1) & 1, out = k & 1;
+  RowSet rs{c.rows[in], c.n_rows[in], c.count};
+  SampleIO io{noise, x, blk.a, blk.b, RetireArgs{}};
+  if (blk.stop_test) {
+    const int slot = (int)c.log_first.size();
+    if (slot >= c.pin_len) return fail(MADE_ERR_HIP, "internal: pass log overflow");
+    c.h_pin[slot] = -1;
+    io.retire.rows_in = c.rows[in];
+    io.retire.n_in = c.n_rows[in];
+    io.retire.rows_out = c.rows[out];
+    io.retire.n_out = c.n_rows[out];
+    io.retire.changed = w.changed;
+    io.retire.iters = w.iters;
+    io.retire.flags = w.flags;
+    io.retire.done_ctr = c.done_ctr;
+    io.retire.host_slot = c.d_pin + slot;
+    io.retire.last_pass = (k == blk.cap);
+    io.retire.flag_unconverged = flag_unconverged;
+    io.retire.enabled = 1;
+    c.log_first.push_back(k == 1);
+  } else {
+    rs = RowSet{c.rows[0], nullptr, c.count};   // no stop test: every sample of the chain takes the pass
+  }
+  TRY(run_hidden(m, rs, blk.limited ? blk.hidden_limit.data() : nullptr, blk.in_limit, s));
+  TRY(run_output_sample(m, rs, io, blk.whole_network, blk.out_k_limit, s));
+  c.k_enq = k;
+  return MADE_OK;
+}
+
+// Run the block list on every chain.  Each chain works through the blocks on its own stream; the host keeps
+// at most two unconfirmed passes per chain in flight (a pass enqueued after its chain emptied finds zero
+// active rows and does nothing), and moves a chain to its next block as soon as the block's pass limit is
+// enqueued or the device reported the chain's block as unchanged.  Returns after the caller's stream has been
+// made to wait for all chains and has been synchronised.
+static int run_chains(made_model* m, const std::vector<Block>& blocks, const float* noise, const uint8_t* x_init,
+                      uint8_t* x, int N, bool flag_unconverged, int32_t* iters_out, hipStream_t s) {
+  Workspace& w = m->ws;
+  // split the batch into chains of whole 32-sample tiles
+  int want = std::max(1, std::min(m->n_chains, (N + TILE - 1) / TILE));
+  const int per = round_up((N + want - 1) / want, TILE);
+  const int n_chains = (N + per - 1) / per;
+  int total_passes = 0;
+  for (const Block& b : blocks) total_passes += b.cap;
+  for (int i = 0; i < n_chains; ++i) {
+    TRY(ensure_chain(m, (size_t)i, per, total_passes + 8));
+    Chain& c = w.chains[i];
+    c.first = i * per;
+    c.count = std::min(per, N - c.first);
+    c.block = 0;
+    c.k_enq = c.k_conf = 0;
+    c.block_started = c.finished = c.iters_cleared = false;
+    c.log_first.clear();
+    c.stream = n_chains == 1 ? s : c.own_stream;   // a single chain needs no fork and join
+  }
+  TRY(launch_init_state(m, x_init, x, N, s));
+  HIP_TRY(hipMemsetAsync(w.flags, 0, sizeof(int), s));
+  if (n_chains > 1) {
+    HIP_TRY(hipEventRecord(w.fork_ev, s));
+    for (int i = 0; i < n_chains; ++i) HIP_TRY(hipStreamWaitEvent(w.chains[i].stream, w.fork_ev, 0));
+  }
+
+  int n_finished = 0;
+  auto last_progress = std::chrono::steady_clock::now();
+  uint64_t spins = 0;
+  while (n_finished < n_chains) {
+    bool progressed = false;
+    for (int i = 0; i < n_chains; ++i) {
+      Chain& c = w.chains[i];
+      if (c.finished) continue;
+      const Block& blk = blocks[c.block];
+      bool block_done = false;
+      if (c.k_enq < blk.cap && c.k_enq - c.k_conf <= 1) {
+        TRY(enqueue_pass(m, c, blk, noise, x, flag_unconverged));
+        progressed = true;
+      }
+      if (!blk.stop_test) {
+        c.k_conf = c.k_enq;
+        block_done = c.k_enq == blk.cap;
+      } else {
+        // look (without blocking) at the oldest unconfirmed pass of this block
+        if (c.k_conf < c.k_enq) {
+          const int slot = (int)c.log_first.size() - (c.k_enq - c.k_conf);
+          const int left = c.h_pin[slot];
+          if (left >= 0) {
+            c.k_conf++;
+            progressed = true;
+            if (left == 0) block_done = true;
+          }
+        }
+        if (c.k_enq == blk.cap) block_done = true;   // nothing more may be enqueued for this block
+      }
+      if (block_done) {
+        c.block++;
+        c.k_enq = c.k_conf = 0;
+        c.block_started = false;
+        if (c.block == blocks.size()) {
+          c.finished = true;
+          n_finished++;
+          if (n_chains > 1) {
+            HIP_TRY(hipEventRecord(c.done_ev, c.stream));
+            HIP_TRY(hipStreamWaitEvent(s, c.done_ev, 0));
+          }
+        }
+        progressed = true;
+      }
+    }
+    if (progressed) {
+      last_progress = std::chrono::steady_clock::now();
+    } else if ((++spins & 0xfff) == 0 &&
+               std::chrono::duration<double>(std::chrono::steady_clock::now() - last_progress).count() > 30.0) {
+      return fail(MADE_ERR_HIP, "device did not report the stop test of a pass within 30 s");
+    }
+  }
+  if (iters_out) HIP_TRY(hipMemcpyAsync(iters_out, w.iters, (size_t)N * sizeof(int), hipMemcpyDeviceToDevice, s));
+  HIP_TRY(hipMemcpyAsync((void*)&w.h_pin[0], w.flags, sizeof(int), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  m->stats[3]++;
+  prof_collect(m);
+  // statistics from the chains' pass logs (complete now that everything has run)
+  for (int i = 0; i < n_chains; ++i) {
+    const Chain& c = w.chains[i];
+    int64_t passes = 0;
+    int active_in = 0;
+    for (size_t j = 0; j < c.log_first.size(); ++j) {
+      if (c.log_first[j]) active_in = c.count;
+      if (active_in > 0) {
+        passes++;
+        m->stats[1] += active_in;
+      }
+      active_in = c.h_pin[j];
+    }
+    m->stats[0] = std::max(m->stats[0], passes);
+  }
+  if (w.h_pin[0] & 1)
+    return fail(MADE_ERR_NOT_CONVERGED, "samples were still changing after the last allowed pass");
+  return MADE_OK;
+}
+
 extern "C" int sequential_sample(made_model* m, const float* noise, int32_t N, int32_t mode, uint8_t* x_out,
                                  void* stream) {
   TRY(check_call(m, noise, N, x_out, "sequential_sample"));
@@ -653,103 +875,17 @@ extern "C" int sequential_sample(made_model* m, const float* noise, int32_t N, i
   memset(m->stats, 0, sizeof m->stats);
   m->ev_layer.clear();
   TRY(ensure_workspace(m, N, true));
-  TRY(launch_init_state(m, nullptr, x_out, N, s));
-  TRY(launch_reset_rows(m, 0, N, true, s));
-  RowSet rs{nullptr, nullptr, N};
-  std::vector<int> limit(m->L);
+  std::vector<Block> blocks;
+  blocks.reserve(m->D);
   for (int p = 0; p < m->D; ++p) {  // p = 0-based position, its 1-based index is t = p + 1
-    SampleIO io{noise, x_out, p, p + 1, RetireArgs{}};
-    if (mode == 0) {
-      TRY(run_hidden(m, rs, nullptr, -1, s));
-      TRY(run_output_sample(m, rs, io, true, -1, s));
-    } else {
-      // position t reads last-layer units of degree < t; those read units of degree <= their own
-      for (int l = 0; l < m->L; ++l) limit[l] = m->cnt_lt[l][p + 1];
-      TRY(run_hidden(m, rs, limit.data(), p, s));
-      TRY(run_output_sample(m, rs, io, false, limit[m->L - 1], s));
-    }
-    m->stats[0]++;
-    m->stats[1] += N;
+    Block blk = make_block(m, p, p + 1, 1, mode == 1);
+    blk.stop_test = false;
+    blk.whole_network = (mode == 0);
+    blocks.push_back(std::move(blk));
   }
-  HIP_TRY(hipStreamSynchronize(s));
-  m->stats[3]++;
-  prof_collect(m);
-  return MADE_OK;
-}
-
-// Wait (bounded) until the device has written the active count of pass-log slot `slot`.
-static int wait_slot(made_model* m, int slot, int* value) {
-  volatile int* p = &m->ws.h_pin[slot];
-  const auto t0 = std::chrono::steady_clock::now();
-  for (uint64_t spins = 0;; ++spins) {
-    const int v = *p;
-    if (v >= 0) { *value = v; return MADE_OK; }
-    if ((spins & 0xffff) == 0xffff &&
-        std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() > 30.0)
-      return fail(MADE_ERR_HIP, "device did not report the stop test of a pass within 30 s");
-  }
-}
-
-// Jacobi passes over positions [t_lo, t_hi) of the samples listed in rows[0], at most `cap` of them.
-// The last workgroup of each pass writes the new active count into pinned host memory; the host enqueues
-// pass k + 1 before it looks at the count after pass k, so the device never idles on the stop test.  A pass
-// enqueued after the batch emptied finds zero active rows and does nothing.
-// Active counts land in the pinned log h_pin[1 + i] (i = running pass index of the whole call).
-static int iterate_block(made_model* m, const float* noise, uint8_t* x, int N, int t_lo, int t_hi, int cap,
-                         bool flag_unconverged, const int* hidden_limit, int in_limit, int out_k_limit,
-                         std::vector<char>& first_of_block, hipStream_t s) {
-  Workspace& w = m->ws;
-  for (int k = 1; k <= cap; ++k) {
-    const int in = (k - 1) & 1, out = k & 1;
-    const int slot = 1 + (int)first_of_block.size();
-    if (slot >= w.h_pin_len) return fail(MADE_ERR_HIP, "internal: pass log overflow");
-    w.h_pin[slot] = -1;
-    RowSet rs{w.rows[in], w.n_rows[in], N};
-    SampleIO io{noise, x, t_lo, t_hi, RetireArgs{}};
-    io.retire.rows_in = w.rows[in];
-    io.retire.n_in = w.n_rows[in];
-    io.retire.rows_out = w.rows[out];
-    io.retire.n_out = w.n_rows[out];
-    io.retire.changed = w.changed;
-    io.retire.iters = w.iters;
-    io.retire.flags = w.flags;
-    io.retire.done_ctr = w.done_ctr;
-    io.retire.host_slot = w.d_pin + slot;
-    io.retire.last_pass = (k == cap);
-    io.retire.flag_unconverged = flag_unconverged;
-    io.retire.enabled = 1;
-    TRY(run_hidden(m, rs, hidden_limit, in_limit, s));
-    TRY(run_output_sample(m, rs, io, false, out_k_limit, s));
-    first_of_block.push_back(k == 1);
-    if (k >= 2 && k < cap) {  // result of pass k - 1, while pass k is already queued
-      int left = 0;
-      TRY(wait_slot(m, slot - 1, &left));
-      m->stats[3]++;
-      if (left == 0) break;
-    }
-  }
-  return MADE_OK;
-}
-
-static int finish_call(made_model* m, int N, int32_t* iters_out, bool check_flag,
-                       const std::vector<char>& first_of_block, hipStream_t s) {
-  Workspace& w = m->ws;
-  if (iters_out) HIP_TRY(hipMemcpyAsync(iters_out, w.iters, (size_t)N * sizeof(int), hipMemcpyDeviceToDevice, s));
-  if (check_flag) HIP_TRY(hipMemcpyAsync((void*)&w.h_pin[0], w.flags, sizeof(int), hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipStreamSynchronize(s));
-  m->stats[3]++;
-  prof_collect(m);
-  int active_in = 0;
-  for (size_t i = 0; i < first_of_block.size(); ++i) {
-    if (first_of_block[i]) active_in = N;
-    if (active_in > 0) {
-      m->stats[0]++;
-      m->stats[1] += active_in;
-    }
-    active_in = w.h_pin[1 + i];
-  }
-  if (check_flag && w.h_pin[0])
-    return fail(MADE_ERR_NOT_CONVERGED, "samples were still changing after the last allowed pass");
+  TRY(run_chains(m, blocks, noise, nullptr, x_out, N, false, nullptr, s));
+  m->stats[0] = m->D;
+  m->stats[1] = (int64_t)m->D * N;
   return MADE_OK;
 }
 
@@ -841,11 +977,8 @@ extern "C" int jacobi_sample(made_model* m, const float* noise, int32_t N, const
   bool done = false;
   TRY(run_persistent(m, noise, N, x_init, x_out, m->D, cap, cap < m->D, iters_out, s, &done));
   if (done) return MADE_OK;
-  TRY(launch_init_state(m, x_init, x_out, N, s));
-  TRY(launch_reset_rows(m, 0, N, true, s));
-  std::vector<char> log;
-  TRY(iterate_block(m, noise, x_out, N, 0, m->D, cap, cap < m->D, nullptr, -1, -1, log, s));
-  return finish_call(m, N, iters_out, cap < m->D, log, s);
+  std::vector<Block> blocks(1, make_block(m, 0, m->D, cap, false));
+  return run_chains(m, blocks, noise, x_init, x_out, N, cap < m->D, iters_out, s);
 }
 
 extern "C" int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, const uint8_t* x_init, int32_t block,
@@ -860,18 +993,12 @@ extern "C" int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, co
   bool done = false;
   TRY(run_persistent(m, noise, N, x_init, x_out, block, m->D, false, iters_out, s, &done));
   if (done) return MADE_OK;
-  TRY(launch_init_state(m, x_init, x_out, N, s));
-  TRY(launch_reset_rows(m, 0, N, true, s));
-  std::vector<int> limit(m->L);
-  std::vector<char> log;
+  std::vector<Block> blocks;
   for (int a = 0; a < m->D; a += block) {
     const int b = std::min(a + block, m->D);          // block = 0-based positions [a, b)
-    if (a > 0) TRY(launch_reset_rows(m, 0, N, false, s));
-    // positions < b read last-layer units of degree < b (1-based b), i.e. degree <= b - 1
-    for (int l = 0; l < m->L; ++l) limit[l] = m->cnt_lt[l][b];
-    TRY(iterate_block(m, noise, x_out, N, a, b, b - a, false, limit.data(), b - 1, limit[m->L - 1], log, s));
+    blocks.push_back(make_block(m, a, b, b - a, true));
   }
-  return finish_call(m, N, iters_out, false, log, s);
+  return run_chains(m, blocks, noise, x_init, x_out, N, false, iters_out, s);
 }
 
 #ifdef JM_TRACE

@@ -860,18 +860,19 @@ __global__ void init_state_kernel(const uint8_t* x_init, uint8_t* x, T* enc, int
   }
 }
 
-__global__ void reset_rows_kernel(int* rows, int* n_rows, int N, int* changed, int* iters, int* flags,
+// A chain's active list becomes its whole sample range [first, first + count) again (start of a call or of
+// a GS-Jacobi block).
+__global__ void reset_rows_kernel(int* rows, int* n_rows, int first, int count, int* changed, int* iters,
                                   int* done_ctr) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < N) {
-    rows[i] = i;
-    changed[i] = 0;
-    if (iters) iters[i] = 0;
+  if (i < count) {
+    rows[i] = first + i;
+    changed[first + i] = 0;
+    if (iters) iters[first + i] = 0;
   }
   if (i == 0) {
-    *n_rows = N;
+    *n_rows = count;
     *done_ctr = 0;
-    if (flags) *flags = 0;
   }
 }
 

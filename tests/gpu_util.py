@@ -39,6 +39,7 @@ def oracle_models(net):
 
 PERSISTENT = False     # execution path the models below are switched to (the tests run both)
 FUSED_CATEGORICAL = True
+CHAINS = 4
 
 
 class GpuModel:
@@ -47,6 +48,7 @@ class GpuModel:
         self.h = B.model_from_network(net)
         B.made_set_option(self.h, B.MADE_OPT_PERSISTENT, int(PERSISTENT if persistent is None else persistent))
         B.made_set_option(self.h, B.MADE_OPT_FUSED_CATEGORICAL, int(FUSED_CATEGORICAL))
+        B.made_set_option(self.h, B.MADE_OPT_CHAINS, CHAINS)
 
     def close(self):
         if self.h:

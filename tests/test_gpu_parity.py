@@ -14,7 +14,7 @@ from gpu_util import LOGIT_TOL, MARGIN, GpuModel, assert_logits_close, assert_sa
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=["per-layer launches", "persistent", "unfused categorical"])
+@pytest.fixture(autouse=True, params=["per-layer launches", "single chain", "persistent", "unfused categorical"])
 def execution_path(request):
     """Every test runs on every execution path of the library (they must all agree with the oracle)."""
     import gpu_util
@@ -24,9 +24,11 @@ def execution_path(request):
             pytest.skip("only the 256-class workload has a fused and an unfused output path")
     gpu_util.PERSISTENT = request.param == "persistent"
     gpu_util.FUSED_CATEGORICAL = request.param != "unfused categorical"
+    gpu_util.CHAINS = 1 if request.param == "single chain" else 4
     yield
     gpu_util.PERSISTENT = False
     gpu_util.FUSED_CATEGORICAL = True
+    gpu_util.CHAINS = 4
 
 
 SMALL = ["cfg1", "small_f32", "small_bf16", "mid_bf16", "small_cat", "small_cat_f32"]
