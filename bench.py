@@ -75,6 +75,9 @@ def main() -> int:
     ap.add_argument("--no-extras", action="store_true", help="skip sequential / GS-Jacobi side measurements")
     ap.add_argument("--path", choices=["persistent", "layers"], default="layers",
                     help="persistent: one cooperative launch per call; layers: one launch per layer and pass")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (supplementary sweeps)")
+    ap.add_argument("--big-tile-batch", type=int, default=0,
+                    help="batch size from which the 256 x 256 tile kernels are used (0 = library default)")
     ap.add_argument("--chains", type=int, default=0, help="sub-batches on separate streams (0 = library default)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="no timing: run 20 device copies of 64 MiB (calibration of FETCH_SIZE / WRITE_SIZE), then "
@@ -93,11 +96,16 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     w = S.workload(args.workload)
+    if args.batch > 0:
+        import dataclasses
+        w = dataclasses.replace(w, N=args.batch)
     net = S.make_network(w)
     model = B.model_from_network(net)
     B.made_set_option(model, B.MADE_OPT_PERSISTENT, int(args.path == "persistent"))
     if args.chains > 0:
         B.made_set_option(model, B.MADE_OPT_CHAINS, args.chains)
+    if args.big_tile_batch > 0:
+        B.made_set_option(model, B.MADE_OPT_BIG_TILE_BATCH, args.big_tile_batch)
     n_layers = len(net.hidden) + 1
     nnz = B.made_layer_nnz(model, n_layers)
     n_slots = n_layers + 1                     # per-layer kernels + the persistent whole-call kernel

@@ -157,8 +157,11 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   chains' dependent kernel launches can overlap.  The caller's stream waits for all of them before the call
  *   returns.  With one host thread enqueuing, more chains mean proportionally more launches; at batch 128 on
  *   MI355X that costs more than the overlap gains, hence the default of a single chain.
+ *   MADE_OPT_BIG_TILE_BATCH (default 4096): batches (chains) of at least this many samples run the masked
+ *   layers with 256 x 256 workgroup tiles staged through LDS instead of 32 x 32 tiles (on the D = 784,
+ *   2 x 2000 network the two cross over near 5000 samples).
  */
-enum { MADE_OPT_PERSISTENT = 1, MADE_OPT_FUSED_CATEGORICAL = 2, MADE_OPT_CHAINS = 3 };
+enum { MADE_OPT_PERSISTENT = 1, MADE_OPT_FUSED_CATEGORICAL = 2, MADE_OPT_CHAINS = 3, MADE_OPT_BIG_TILE_BATCH = 4 };
 int made_set_option(made_model* m, int32_t option, int32_t value);
 
 /*

@@ -171,6 +171,7 @@ def made_set_profiling(model: int, enable: bool) -> None:
 MADE_OPT_PERSISTENT = 1
 MADE_OPT_FUSED_CATEGORICAL = 2
 MADE_OPT_CHAINS = 3
+MADE_OPT_BIG_TILE_BATCH = 4
 
 
 def made_set_option(model: int, option: int, value: int) -> None:

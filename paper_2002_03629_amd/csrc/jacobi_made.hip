@@ -137,6 +137,7 @@ struct made_model {
   std::vector<int64_t> prof_launches;         // [L+1]
   std::vector<int64_t> nnz;                   // [L+1] visible (mask = 1) weights per layer
   int persist_grid = 0;                       // workgroups of the persistent kernel (0 = not usable)
+  int big_batch = 4096;                       // made_set_option(MADE_OPT_BIG_TILE_BATCH); measured crossover ~5000
   int n_chains = 1;                           // made_set_option(MADE_OPT_CHAINS)
   int fused_categorical = 1;                  // made_set_option(MADE_OPT_FUSED_CATEGORICAL)
   int use_persistent = 0;                     // made_set_option(MADE_OPT_PERSISTENT); off: measured slower, see header
@@ -270,6 +271,11 @@ extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
   }
   if (option == MADE_OPT_FUSED_CATEGORICAL) {
     m->fused_categorical = value != 0;
+    return MADE_OK;
+  }
+  if (option == MADE_OPT_BIG_TILE_BATCH) {
+    if (value < 1) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_BIG_TILE_BATCH=%d must be >= 1", value);
+    m->big_batch = value;
     return MADE_OK;
   }
   if (option == MADE_OPT_CHAINS) {
@@ -508,13 +514,32 @@ static void prof_collect(made_model* m) {
   m->ev_layer.clear();
 }
 
+template <typename T, int EPI>
+static void launch_big_t(LayerArgs a, int n_tiles, int n_rows_max, hipStream_t s) {
+  static bool configured = false;   // (per instantiation) allow 128 KB of dynamic LDS
+  if (!configured) {
+    (void)hipFuncSetAttribute((const void*)masked_layer_big_kernel<T, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              BIG_LDS_BYTES);
+    configured = true;
+  }
+  a.n_launch_tiles = n_tiles;
+  a.row_tiles = (n_rows_max + BIG_ROWS - 1) / BIG_ROWS;
+  const int big_cols = (n_tiles + BIG_T - 1) / BIG_T;
+  a.big_by_rows = a.row_tiles >= big_cols;
+  const int groups = ((a.big_by_rows ? a.row_tiles : big_cols) + XCDS - 1) / XCDS;
+  const int other = a.big_by_rows ? big_cols : a.row_tiles;
+  hipLaunchKernelGGL((masked_layer_big_kernel<T, EPI>), dim3(groups * XCDS * other), dim3(256), BIG_LDS_BYTES, s, a);
+}
+
 template <int EPI>
 static void launch_layer(made_model* m, int layer, const LayerArgs& a, int n_tiles, int row_tiles, hipStream_t s) {
   prof_mark(m, layer, false, s);
-  if (m->dtype == MADE_BF16)
-    launch_layer_t<bf16_t, EPI>(a, n_tiles, row_tiles, s);
-  else
-    launch_layer_t<float, EPI>(a, n_tiles, row_tiles, s);
+  const bool big = a.n_rows >= m->big_batch;
+  if (m->dtype == MADE_BF16) {
+    if (big) launch_big_t<bf16_t, EPI>(a, n_tiles, a.n_rows, s); else launch_layer_t<bf16_t, EPI>(a, n_tiles, row_tiles, s);
+  } else {
+    if (big) launch_big_t<float, EPI>(a, n_tiles, a.n_rows, s); else launch_layer_t<float, EPI>(a, n_tiles, row_tiles, s);
+  }
   prof_mark(m, layer, true, s);
 }
 
@@ -532,6 +557,7 @@ static LayerArgs base_args(const made_model* m, int l, const void* A, const RowS
   a.rows = rs.rows;
   a.n_rows_ptr = rs.n_rows_ptr;
   a.n_rows = rs.n_rows;
+  a.n_rows_pad = round_up(std::max(rs.n_rows, 1), 2 * TILE);
   a.n_cols = ly.out_dim;
   return a;
 }
@@ -585,6 +611,7 @@ static int run_output_sample(made_model* m, const RowSet& rs, const SampleIO& io
     a.t_lo = io.t_lo;
     a.t_hi = io.t_hi;
     a.retire = io.retire;
+    a.io_aligned = (m->D % 16 == 0) && ((uintptr_t)io.noise % 16 == 0) && ((uintptr_t)io.x % 16 == 0);
     launch_layer<EPI_BERNOULLI>(m, m->L, a, tile_hi - tile_lo, row_tiles, s);
     m->stats[2]++;
   } else if (C == CAT_C && m->fused_categorical) {
@@ -720,8 +747,9 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
   if (!c.block_started) {
     // the active list restarts as the chain's whole range (blocks without a stop test never shrink it)
     if (blk.stop_test || !c.iters_cleared) {
-      hipLaunchKernelGGL(reset_rows_kernel, dim3((c.count + 255) / 256), dim3(256), 0, s, c.rows[0], c.n_rows[0],
-                         c.first, c.count, w.changed, c.iters_cleared ? nullptr : w.iters, c.done_ctr);
+      const int padded = round_up(c.count, 2 * TILE);   // <= c.rows_cap
+      hipLaunchKernelGGL(reset_rows_kernel, dim3((padded + 255) / 256), dim3(256), 0, s, c.rows[0], c.n_rows[0],
+                         c.first, c.count, padded, w.changed, c.iters_cleared ? nullptr : w.iters, c.done_ctr);
       m->stats[2]++;
       c.iters_cleared = true;
     }

@@ -9,7 +9,22 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 namespace jm {
+
+// Compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>).  Used where an index
+// into a register array MUST be a constant (a loop the compiler declines to unroll would push the array,
+// e.g. 256 accumulators, into scratch memory).
+template <typename F, int... Is>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
 
 typedef uint16_t bf16_t;  // storage type; arithmetic goes through float
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -27,10 +42,23 @@ template <typename T> struct Elem;
 template <> struct Elem<bf16_t> {
   static constexpr int EPL = 32;  // elements one lane loads per K chunk (64 bytes)
   static __device__ __forceinline__ bf16_t from_f32(float f) { return f32_to_bf16(f); }
+  // 16 bytes = elements v[0..7], ReLU applied (registers only: no array whose address is taken)
+  static __device__ __forceinline__ uint4 relu_piece(const float* v) {
+    uint4 o;
+    o.x = (uint32_t)f32_to_bf16(fmaxf(v[0], 0.f)) | ((uint32_t)f32_to_bf16(fmaxf(v[1], 0.f)) << 16);
+    o.y = (uint32_t)f32_to_bf16(fmaxf(v[2], 0.f)) | ((uint32_t)f32_to_bf16(fmaxf(v[3], 0.f)) << 16);
+    o.z = (uint32_t)f32_to_bf16(fmaxf(v[4], 0.f)) | ((uint32_t)f32_to_bf16(fmaxf(v[5], 0.f)) << 16);
+    o.w = (uint32_t)f32_to_bf16(fmaxf(v[6], 0.f)) | ((uint32_t)f32_to_bf16(fmaxf(v[7], 0.f)) << 16);
+    return o;
+  }
 };
 template <> struct Elem<float> {
   static constexpr int EPL = 16;
   static __device__ __forceinline__ float from_f32(float f) { return f; }
+  static __device__ __forceinline__ uint4 relu_piece(const float* v) {
+    return make_uint4(__float_as_uint(fmaxf(v[0], 0.f)), __float_as_uint(fmaxf(v[1], 0.f)),
+                      __float_as_uint(fmaxf(v[2], 0.f)), __float_as_uint(fmaxf(v[3], 0.f)));
+  }
 };
 
 // Fragment-major layout of every MFMA operand matrix (masked weights, network input, hidden activations).
@@ -93,10 +121,13 @@ struct LayerArgs {
   int tile_begin;        // first unit tile this launch covers
   int n_launch_tiles;    // unit tiles this launch covers
   int row_tiles;         // sample tiles this launch covers (upper bound; tiles beyond n_rows idle)
+  int big_by_rows;       // 256 x 256 kernel only: XCDs own sample tiles (1) or unit tiles (0)
+  int io_aligned;        // 256 x 256 kernel only: D % 16 == 0 and noise / x are 16-byte aligned
   // active samples: rows[0 .. *n_rows_ptr) are sample ids (NULL = identity, n_rows fixed)
   const int* rows;
   const int* n_rows_ptr;
   int n_rows;
+  int n_rows_pad;        // entries the list `rows` holds (reads past the active count stay inside it)
   // EPI_RELU: out = next layer's activations (fragment-major, out_chunks chunks).  EPI_LOGITS: float [sample, ldo]
   void* out;
   int ldo;
@@ -185,6 +216,13 @@ __device__ __forceinline__ void retire_tail(const RetireArgs& r) {
       base_s += tot;
     }
     __syncthreads();
+  }
+  // the next pass reads whole tiles of the new list: pad it with a valid id of this call (anything older
+  // in those slots may stem from a call with a larger batch)
+  if (n_rows > 0) {
+    const int fill = r.rows_in[0];
+    const int new_n = base_s;
+    for (int i = new_n + threadIdx.x; i < ((new_n + 63) & ~63); i += nthreads) r.rows_out[i] = fill;
   }
   if (threadIdx.x == 0) {
     *r.n_out = base_s;
@@ -396,6 +434,214 @@ __global__ __launch_bounds__(NW * 64) void masked_layer_kernel(LayerArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// Large-batch variant of the masked layer: 256 samples x 256 units per workgroup.
+//
+// With hundreds of active samples a layer is a real GEMM and the 32 x 32 tiles above would re-read
+// every operand byte from L2 (16 FLOP per byte).  Here 4 waves each own 128 x 128 outputs (4 x 4 MFMA
+// tiles, 256 accumulator registers); per K chunk the workgroup copies 8 sample blocks and 8 weight
+// blocks (4 KB each) into LDS once, double buffered, and every wave reads its 4 + 4 fragments from
+// there: 512 FLOP per byte fetched from L2.  Because global memory already holds both operands in
+// fragment order, the LDS image is a plain copy and every ds_read_b128 is conflict free.
+// ------------------------------------------------------------------------------------------------
+constexpr int BIG_W = 4;                 // MFMA tiles per wave and dimension
+constexpr int BIG_T = 2 * BIG_W;         // tiles per workgroup and dimension (2 x 2 waves)
+constexpr int BIG_ROWS = BIG_T * TILE;   // 256
+constexpr int BIG_LDS_BYTES = 2 * 2 * BIG_T * 256 * 16;   // 2 stages x (8 + 8) blocks x 4 KB = 128 KB
+
+template <typename T>
+__device__ __forceinline__ void mfma_step(const uint4& a, const uint4& b, f32x16& acc);
+template <>
+__device__ __forceinline__ void mfma_step<bf16_t>(const uint4& a, const uint4& b, f32x16& acc) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+}
+template <>
+__device__ __forceinline__ void mfma_step<float>(const uint4& a, const uint4& b, f32x16& acc) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+}
+
+template <typename T, int EPI>
+__global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
+  constexpr int KC = 2 * Elem<T>::EPL;
+  extern __shared__ uint4 big_lds[];     // [stage][block 0..7 = samples, 8..15 = units][256]
+  const int n_rows = a.n_rows_ptr ? *a.n_rows_ptr : a.n_rows;
+  const int big_cols = (a.n_launch_tiles + BIG_T - 1) / BIG_T;
+  // Workgroup i runs on XCD i % 8.  An XCD should own whichever operand is larger (it then streams only
+  // the smaller one through its L2): sample tiles when samples outnumber units, unit tiles otherwise.
+  const int xcd = blockIdx.x % XCDS, slot = blockIdx.x / XCDS;
+  int wg_m, wg_n;                                           // row_tiles counts 256-sample tiles here
+  if (a.big_by_rows) {
+    wg_n = slot % big_cols;
+    wg_m = (slot / big_cols) * XCDS + xcd;
+  } else {
+    wg_m = slot % a.row_tiles;
+    wg_n = (slot / a.row_tiles) * XCDS + xcd;
+  }
+  const int row0 = wg_m * BIG_ROWS;
+  if (wg_n < big_cols && wg_m < a.row_tiles && row0 < n_rows) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r = lane & 31, h = lane >> 5;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int rel_tile0 = wg_n * BIG_T;
+    const int tile0 = a.tile_begin + rel_tile0;
+    const int live_tiles = min(BIG_T, a.n_launch_tiles - rel_tile0);
+
+    int k_end = 0;
+    for (int j = 0; j < live_tiles; ++j) k_end = max(k_end, a.tile_kend[tile0 + j]);
+    if (k_end > a.k_cap) k_end = a.k_cap;
+    const int n_chunks = (k_end + KC - 1) / KC;
+    const size_t group = (size_t)a.k_chunks * 256;
+
+    // Operand blocks go from global memory straight into LDS (global_load_lds_dwordx4: lane i of a wave
+    // deposits its 16 bytes at the wave's LDS base + 16 i), so a chunk in flight costs no registers.  Two
+    // stages: the next chunk lands while the current one is multiplied.  (A four-stage ring of half chunks
+    // was measured and is not faster: the loop is bound by the MFMA/LDS issue rate of one wave per SIMD, not
+    // by memory latency.)  This thread copies element `tid` of each of the 16 blocks of a chunk; offsets are
+    // in 16-byte units (the host refuses operand buffers of 64 GiB and more).
+    uint32_t offA[BIG_T];
+#pragma unroll
+    for (int q = 0; q < BIG_T; ++q) {
+      const int row = row0 + q * TILE + (tid & 31);
+      const int sample = a.rows ? a.rows[min(row, a.n_rows_pad - 1)] : (row < a.n_rows ? row : 0);
+      offA[q] = (uint32_t)((size_t)(sample >> 5) * group) + (tid & ~31) + (sample & 31);
+    }
+    const uint4* Abase = (const uint4*)a.A;
+    const uint4* Wbase = (const uint4*)a.W + (size_t)tile0 * group + tid;
+    const int last_live = live_tiles - 1;                     // tiles past the layer's end repeat the last one
+
+    f32x16 acc[BIG_W][BIG_W];
+#pragma unroll
+    for (int i = 0; i < BIG_W; ++i)
+#pragma unroll
+      for (int j = 0; j < BIG_W; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    typedef __attribute__((address_space(1))) const void gptr_t;
+    typedef __attribute__((address_space(3))) void lptr_t;
+    auto issue_chunk = [&](int c, int stage) {
+      const uint32_t co = (uint32_t)c * 256;
+      uint4* dst = big_lds + stage * (2 * BIG_T * 256) + wave * 64;
+#pragma unroll
+      for (int q = 0; q < BIG_T; ++q) {
+        __builtin_amdgcn_global_load_lds((gptr_t*)(Abase + offA[q] + co), (lptr_t*)(dst + q * 256), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gptr_t*)(Wbase + (size_t)min(q, last_live) * group + co),
+                                         (lptr_t*)(dst + (BIG_T + q) * 256), 16, 0, 0);
+      }
+    };
+    if (n_chunks > 0) issue_chunk(0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    for (int c = 0; c < n_chunks; ++c) {
+      const uint4* cur = big_lds + (c & 1) * (2 * BIG_T * 256);
+      if (c + 1 < n_chunks) issue_chunk(c + 1, (c + 1) & 1);   // lands while this chunk is consumed
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        uint4 af[BIG_W], bf[BIG_W];
+#pragma unroll
+        for (int i = 0; i < BIG_W; ++i) af[i] = cur[(wm * BIG_W + i) * 256 + s * 64 + lane];
+#pragma unroll
+        for (int j = 0; j < BIG_W; ++j) bf[j] = cur[(BIG_T + wn * BIG_W + j) * 256 + s * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < BIG_W; ++i)
+#pragma unroll
+          for (int j = 0; j < BIG_W; ++j) mfma_step<T>(af[i], bf[j], acc[i][j]);
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the next chunk has arrived in the other stage
+      __syncthreads();
+    }
+
+    // ---- epilogue.  acc[i][j][e]: row = row0 + (wm*4 + i)*32 + 8*(e/4) + 4*h + e%4, unit = (tile0 + wn*4 + j)*32 + r.
+    // The operand stages are free now.  The workgroup's 256 sample ids go through LDS, and every 32 x 32
+    // accumulator tile is turned through a wave-private LDS patch so that a lane ends up with 16 consecutive
+    // units of ONE sample: results, noise and symbols then move in 16-byte pieces.
+    int* ids = (int*)big_lds;
+    float (*patch)[TILE + 1] = (float (*)[TILE + 1])((char*)big_lds + 1024 + wave * (TILE * (TILE + 1) * 4));
+    {
+      const int row = row0 + tid;
+      ids[tid] = row < n_rows ? (a.rows ? a.rows[row] : row) : -1;
+    }
+    __syncthreads();
+    constexpr int P = 16 / (int)sizeof(T);          // elements per 16-byte piece of the fragment layout
+    const int rr = lane >> 1, c16 = (lane & 1) * 16;  // this lane's row and first column inside a tile
+    const bool vec_io = a.io_aligned != 0;            // 16-byte reads of noise / symbols need aligned rows
+    static_for<BIG_W>([&](auto I) {
+      constexpr int i = decltype(I)::value;
+      const int sample = ids[(wm * BIG_W + i) * TILE + rr];
+      int cnt = 0;
+      static_for<BIG_W>([&](auto J) {
+        constexpr int j = decltype(J)::value;
+        const int rel_tile = rel_tile0 + wn * BIG_W + j;
+        const int col0 = (a.tile_begin + min(rel_tile, a.n_launch_tiles - 1)) * TILE + c16;
+        const bool ok = rel_tile < a.n_launch_tiles && sample >= 0;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) patch[8 * (e >> 2) + 4 * h + (e & 3)][r] = acc[i][j][e];
+        // (same wave wrote and reads the patch: the compiler's LDS counter wait orders them)
+        float v[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) v[c] = patch[rr][c16 + c] + a.bias[col0 + c];
+        if (EPI == EPI_RELU) {
+          if (ok) {
+#pragma unroll
+            for (int g = 0; g < 16 / P; ++g)
+              *(uint4*)((T*)a.out + frag_offset<T>(sample, col0 + g * P, a.out_chunks)) = Elem<T>::relu_piece(v + g * P);
+          }
+        } else if (EPI == EPI_LOGITS) {
+          if (ok) {
+#pragma unroll
+            for (int c = 0; c < 16; ++c)
+              if (col0 + c < a.n_cols) ((float*)a.out)[(size_t)sample * a.ldo + col0 + c] = v[c];
+          }
+        } else if (ok && col0 < a.t_hi && col0 + 16 > a.t_lo) {
+          const size_t idx = (size_t)sample * a.D + col0;
+          float u[16];
+          uint8_t xo[16];
+          if (vec_io && col0 + 16 <= a.D) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              const float4 t4 = *(const float4*)(a.noise + idx + 4 * g);
+              u[4 * g + 0] = t4.x;
+              u[4 * g + 1] = t4.y;
+              u[4 * g + 2] = t4.z;
+              u[4 * g + 3] = t4.w;
+            }
+            const uint4 xw = *(const uint4*)(a.x + idx);
+            const uint32_t xws[4] = {xw.x, xw.y, xw.z, xw.w};
+#pragma unroll
+            for (int c = 0; c < 16; ++c) xo[c] = (uint8_t)((xws[c >> 2] >> (8 * (c & 3))) & 0xffu);
+          } else {
+#pragma unroll
+            for (int c = 0; c < 16; ++c) {
+              const bool in = col0 + c < a.D;
+              u[c] = in ? a.noise[idx + c] : 2.0f;
+              xo[c] = in ? a.x[idx + c] : 0;
+            }
+          }
+#pragma unroll
+          for (int c = 0; c < 16; ++c) {
+            const int col = col0 + c;
+            const float p = 1.0f / (1.0f + expf(-v[c]));
+            const uint8_t xn = u[c] < p ? 1 : 0;
+            if (col >= a.t_lo && col < a.t_hi && xn != xo[c]) {
+              cnt++;
+              a.x[idx + c] = xn;
+              ((T*)a.enc)[frag_offset<T>(sample, col, a.enc_chunks)] = Elem<T>::from_f32((float)xn);
+            }
+          }
+        }
+      });
+      if (EPI == EPI_BERNOULLI) {   // the two lanes of a row
+        cnt += __shfl_xor(cnt, 1);
+        if ((lane & 1) == 0 && cnt > 0) count_changed(&a.changed[sample], cnt);
+      }
+    });
+  }
+  if (EPI == EPI_BERNOULLI && a.retire.enabled) finish_pass(a.retire, gridDim.x);
+}
+
+// ------------------------------------------------------------------------------------------------
 // Persistent kernel: the whole of Algorithm 1 (or Algorithm 3) in one cooperative launch.
 //
 // At batch ~100 a pass is three layers of a few microseconds each, and a dependent kernel launch
@@ -520,7 +766,9 @@ __global__ __launch_bounds__(NW * 64) void persistent_sampler_kernel(PersistArgs
   const bool gs = p.block < D;
   for (int a0 = 0; a0 < D; a0 += p.block) {
     const int b0 = min(a0 + p.block, D);          // block = 0-based positions [a0, b0)
-    for (int i = threadIdx.x; i < N; i += NT) rows_s[i] = i;
+    // entries past the active count are read as sample ids too (their results are discarded), so the whole
+    // padded list must hold valid ids
+    for (int i = threadIdx.x; i < PERSIST_MAX_N; i += NT) rows_s[i] = i < N ? i : 0;
     int n_rows = N;
     __syncthreads();
     const int cap = gs ? (b0 - a0) : p.cap;
@@ -862,11 +1110,13 @@ __global__ void init_state_kernel(const uint8_t* x_init, uint8_t* x, T* enc, int
 
 // A chain's active list becomes its whole sample range [first, first + count) again (start of a call or of
 // a GS-Jacobi block).
-__global__ void reset_rows_kernel(int* rows, int* n_rows, int first, int count, int* changed, int* iters,
+// Entries past the count, up to the list's padded length, are read as sample ids by the tile kernels (their
+// results are discarded), so they are set to a valid id of this call as well.
+__global__ void reset_rows_kernel(int* rows, int* n_rows, int first, int count, int padded, int* changed, int* iters,
                                   int* done_ctr) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < padded) rows[i] = i < count ? first + i : first;
   if (i < count) {
-    rows[i] = first + i;
     changed[first + i] = 0;
     if (iters) iters[first + i] = 0;
   }

@@ -43,12 +43,14 @@ CHAINS = 4
 
 
 class GpuModel:
-    def __init__(self, net, persistent=None):
+    def __init__(self, net, persistent=None, big_tile_batch=None):
         self.net = net
         self.h = B.model_from_network(net)
         B.made_set_option(self.h, B.MADE_OPT_PERSISTENT, int(PERSISTENT if persistent is None else persistent))
         B.made_set_option(self.h, B.MADE_OPT_FUSED_CATEGORICAL, int(FUSED_CATEGORICAL))
         B.made_set_option(self.h, B.MADE_OPT_CHAINS, CHAINS)
+        if big_tile_batch is not None:
+            B.made_set_option(self.h, B.MADE_OPT_BIG_TILE_BATCH, big_tile_batch)
 
     def close(self):
         if self.h:

@@ -80,3 +80,24 @@ def test_cfg4_categorical_full_size():
         xq = g.sequential(noise[:8], 1)
         assert_sample_parity(same, noise[:8], xq)
         assert_sample_parity(same, noise[:sub], xq[:sub], xs, mg)
+
+
+def test_cfg2_large_batch_vector_epilogue():
+    """cfg2's network at batch 300: the 256 x 256 tile kernels with the 16-byte epilogue I/O (D % 16 == 0)."""
+    import dataclasses
+    w = dataclasses.replace(S.workload("cfg2"), N=300)
+    net = S.make_network(w)
+    exact, same = oracle_models(net)
+    noise = S.make_noise(w)
+    sub = 4
+    xs, mg = O.sequential_sample(same, noise[:sub])
+    ref = O.jacobi_reference(same, noise)
+    with GpuModel(net, big_tile_batch=256) as g:
+        x, it = g.jacobi(noise)
+        assert_sample_parity(same, noise, x)
+        assert_sample_parity(same, noise[:sub], x[:sub], xs, mg)
+        assert (it[ref[4] >= MARGIN] == ref[1][ref[4] >= MARGIN]).all()
+        z = g.logits(x[:300])
+        assert_logits_close(z, O.logits_all(exact, x), LOGIT_TOL["bf16"])
+        xb, _ = g.gs_jacobi(noise, 196)
+        assert_sample_parity(same, noise, xb)

@@ -186,3 +186,28 @@ def test_edge_cases():
         B.made_init(1, 1, [4], B.MADE_F32, [np.ones(4, np.int32)], [np.zeros((4, 1)), np.zeros((1, 4))])
     with pytest.raises(B.MadeError):     # degree outside [1, D-1]
         B.made_init(4, 1, [3], B.MADE_F32, [np.array([1, 2, 4], np.int32)], [np.zeros((3, 4)), np.zeros((4, 3))])
+
+
+@pytest.mark.parametrize("name,N", [("mid_bf16", 700), ("small_f32", 300), ("small_bf16", 515)])
+def test_large_batch_uses_big_tiles(name, N):
+    """Large batches run the layers with 256 x 256 workgroup tiles (the threshold is lowered to 256 samples here
+    so that the oracle stays cheap); same parity bar."""
+    import dataclasses
+    w = dataclasses.replace(S.workload(name), N=N)
+    net = S.make_network(w, with_bias=True)
+    exact, same = oracle_models(net)
+    noise = S.make_noise(w)
+    x0 = _symbols(w, np.random.default_rng(4), N)
+    xs, margins = O.sequential_sample(same, noise)
+    ref = O.jacobi_reference(same, noise)
+    with GpuModel(net, big_tile_batch=256) as g:
+        z = g.logits(x0)
+        assert_logits_close(z, O.logits_all(exact, x0), LOGIT_TOL[w.dtype])
+        x, it = g.jacobi(noise)
+        assert_sample_parity(same, noise, x, xs, margins)
+        clear = ref[4] >= MARGIN
+        assert (it[clear] == ref[1][clear]).all()
+        xb, itb = g.gs_jacobi(noise, 33)
+        assert_sample_parity(same, noise, xb, xs, margins)
+        xq = g.sequential(noise, 1)
+        assert_sample_parity(same, noise, xq, xs, margins)
