@@ -244,3 +244,72 @@ def skip_network(D: int, H: int, skip: int, seed: int, dtype: str = "f32") -> Ne
     if dtype == "bf16":
         W1, WV = bf16_representable(W1), bf16_representable(WV)
     return Network(D, 1, [H], dtype, degs, [W1, WV], [np.zeros(H, np.float32), np.zeros(D, np.float32)])
+
+
+# ---------------------------------------------------------------------------------------------
+# Masked convolutional (PixelCNN-style) workloads: H x W images, 3 colours, one C-way state per sub-pixel
+# ---------------------------------------------------------------------------------------------
+
+@dataclass
+class ConvWorkload:
+    name: str
+    H: int
+    W: int
+    C: int                      # classes per sub-pixel
+    F: int                      # feature channels
+    k: int                      # kernel size
+    n_conv: int                 # masked k x k layers (first of type A, rest of type B); a 1 x 1 head follows
+    dtype: str
+    N: int
+    seed: int
+    gain: float = 1.0
+
+
+def conv_workload(name: str) -> ConvWorkload:
+    table = {
+        # 32 x 32 x 3 image, 256-way sub-pixels, 8 masked 5 x 5 layers of 128 channels, batch 32
+        "cfg5": ConvWorkload("cfg5", 32, 32, 256, 128, 5, 8, "bf16", 32, SEED_BASE + 5),
+        # reduced shapes for the parity tests (the width stays 32: one row of pixels per 32-row operand group)
+        "small_conv": ConvWorkload("small_conv", 3, 32, 256, 64, 5, 3, "bf16", 3, SEED_BASE + 21, gain=1.5),
+        "small_conv_f32": ConvWorkload("small_conv_f32", 2, 32, 256, 64, 3, 2, "f32", 2, SEED_BASE + 22, gain=2.0),
+    }
+    return table[name]
+
+
+@dataclass
+class ConvNetwork:
+    H: int
+    W: int
+    C: int
+    F: int
+    k: int
+    dtype: str
+    W_: List[np.ndarray]        # [F, k, k, 3], (n_conv - 1) x [F, k, k, F], [3*C, 1, 1, F]; unmasked fp32
+    b: List[Optional[np.ndarray]]
+
+    @property
+    def D(self) -> int:
+        return self.H * self.W * 3
+
+
+def make_conv_network(w: ConvWorkload, with_bias: bool = False) -> ConvNetwork:
+    g = _rng(w.seed)
+    shapes = [(w.F, w.k, w.k, 3)] + [(w.F, w.k, w.k, w.F)] * (w.n_conv - 1) + [(3 * w.C, 1, 1, w.F)]
+    Ws, bs = [], []
+    for shp in shapes:
+        fan_in = shp[1] * shp[2] * shp[3]
+        wt = g.standard_normal(size=shp, dtype=np.float32) * np.float32(w.gain / np.sqrt(fan_in))
+        if w.dtype == "bf16":
+            _round_bf16_inplace(wt)
+        Ws.append(wt)
+        if with_bias:
+            bb = (0.2 * g.standard_normal(size=shp[0])).astype(np.float32)
+            bs.append(bf16_representable(bb) if w.dtype == "bf16" else bb)
+        else:
+            bs.append(None)
+    return ConvNetwork(w.H, w.W, w.C, w.F, w.k, w.dtype, Ws, bs)
+
+
+def make_conv_noise(w: ConvWorkload, rep: int = 0, N: Optional[int] = None) -> np.ndarray:
+    n = w.N if N is None else N
+    return gumbel_noise(n, w.H * w.W * 3, w.C, w.seed + 2 + 10 * rep)
