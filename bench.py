@@ -50,6 +50,32 @@ def cpu_baseline(w, net, noises, budget_s=12.0):
                       f"({done // sub} x {sub} of a batch of {noises[0].shape[0]}), {dt:.1f} s"}, xs0, sub
 
 
+def cpu_baseline_conv(w, net, noise, budget_s=12.0):
+    """The conv oracle's sequential sampler (Eq. 1) on a bounded sample: the first states of ONE image, one network
+    evaluation per state exactly as conv_sequential_sample does it; every state costs the same, so the time per
+    state scales to the D states of a whole image."""
+    from oracle import conv_oracle as CO
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    model = CO.build_conv_model(net.H, net.W, net.C, net.F, net.k, net.W_, net.b,
+                                "bf16" if net.dtype == "bf16" else None)
+    x = np.zeros((1, model.D), dtype=np.uint8)
+    CO.conv_logits_all(model, x)                              # warm the BLAS threads
+    t0 = time.perf_counter()
+    t = 0
+    while t < model.D and time.perf_counter() - t0 < budget_s:
+        z_t = CO.conv_logits_all(model, x)[:, t]
+        x[:, t], _ = CO.decide(z_t, noise[:1, t], model.C)
+        t += 1
+    dt = time.perf_counter() - t0
+    return {"value": 1.0 / (dt / t * model.D), "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"oracle conv_sequential_sample steps (numpy fp64, activations rounded as on the GPU): the first "
+                      f"{t} of {model.D} states of one image in {dt:.1f} s, scaled to a whole image"}, x[:, :t], t
+
+
 def measured_traffic(workload: str, path: str, dom_is_output: bool):
     """HBM bytes per launch of the dominant kernel, as measured with rocprofv3 PMC counters in a separate run
     (counters cannot be read from inside this process); the summary under profiles/ holds the figure."""
@@ -95,25 +121,30 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
-    w = S.workload(args.workload)
+    import dataclasses
+    conv = args.workload in ("cfg5", "small_conv", "small_conv_f32")
+    w = S.conv_workload(args.workload) if conv else S.workload(args.workload)
     if args.batch > 0:
-        import dataclasses
         w = dataclasses.replace(w, N=args.batch)
-    net = S.make_network(w)
-    model = B.model_from_network(net)
+    if conv:
+        net = S.make_conv_network(w)
+        model = B.conv_model_from_network(net)
+    else:
+        net = S.make_network(w)
+        model = B.model_from_network(net)
     B.made_set_option(model, B.MADE_OPT_PERSISTENT, int(args.path == "persistent"))
     if args.chains > 0:
         B.made_set_option(model, B.MADE_OPT_CHAINS, args.chains)
     if args.big_tile_batch > 0:
         B.made_set_option(model, B.MADE_OPT_BIG_TILE_BATCH, args.big_tile_batch)
-    n_layers = len(net.hidden) + 1
+    n_layers = (w.n_conv if conv else len(net.hidden)) + 1
     nnz = B.made_layer_nnz(model, n_layers)
     n_slots = n_layers + 1                     # per-layer kernels + the persistent whole-call kernel
     flops_per_sample_pass = 2.0 * np.array(list(nnz) + [sum(nnz)], dtype=np.float64)
-    N, D = w.N, w.D
+    N, D = w.N, net.D
 
-    n_noise = min(args.steps, 32)
-    noises_host = [S.make_noise(w, rep=r) for r in range(n_noise)]
+    n_noise = min(args.steps, 4 if conv else 32)
+    noises_host = [S.make_conv_noise(w, rep=r) if conv else S.make_noise(w, rep=r) for r in range(n_noise)]
     noises = [torch.from_numpy(a).cuda() for a in noises_host]
     x = torch.empty((N, D), dtype=torch.uint8, device="cuda")
     iters = torch.empty((N,), dtype=torch.int32, device="cuda")
@@ -161,7 +192,8 @@ def main() -> int:
         st = B.made_last_stats(model)
         layer_ms += ms
         layer_launches += np.array(cnt)
-        layer_flops += flops_per_sample_pass * st["sample_passes"] * (np.array(cnt) > 0)
+        # (the convolutional trunk evaluates every image of the batch in every pass)
+        layer_flops += flops_per_sample_pass * (N * st["passes"] if conv else st["sample_passes"]) * (np.array(cnt) > 0)
         sample_passes += st["sample_passes"]
         passes += st["passes"]
         itc = iters.cpu().numpy()
@@ -176,7 +208,7 @@ def main() -> int:
     es = 2 if w.dtype == "bf16" else 4
     # A layer whose visible weights exceed the chip's caches (32 MB L2 + 256 MB Infinity Cache) must be
     # streamed from HBM once per pass; at batch <= 128 that puts it far below the MFMA ridge: HBM-bound.
-    hbm_bound = dom < n_layers and nnz[dom] * es > 288e6
+    hbm_bound = (not conv) and dom < n_layers and nnz[dom] * es > 288e6
     if hbm_bound:
         noise_bytes = 4.0 * D * w.C * (w.C > 1) + 4.0 * D * (w.C == 1)       # per active sample
         act_bytes = es * (w.hidden[-1] if dom == n_layers - 1 else 0)
@@ -186,7 +218,11 @@ def main() -> int:
     else:
         achieved = layer_flops[dom] / (layer_ms[dom] * 1e-3) / 1e12 if layer_ms[dom] > 0 else 0.0
         peak, unit, bound = (PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_F32_TFLOPS), "TFLOP/s", "mfma"
-    if dom == n_layers:
+    if conv:
+        layer_name = ("conv_first_kernel" if dom == 0 else
+                      f"conv_layer_kernel layer {dom} (k x k masked convolution as implicit GEMM)" if dom < n_layers - 1
+                      else "categorical_output_kernel (1 x 1 head + Gumbel-max)")
+    elif dom == n_layers:
         layer_name = "persistent_sampler_kernel (all passes of a call: hidden layers, output layer + sampling, stop test)"
     else:
         layer_name = (f"masked_layer_kernel layer {dom} "
@@ -205,8 +241,11 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": w.dtype,
         "data": "synthetic",
-        "config": {"workload": f"{w.name}: MADE D={D} hidden={w.hidden} C={w.C} batch={N} Jacobi (Algorithm 1), "
-                               f"seeded N(0,1/fan_in) weights, random degrees, fixed U(0,1) noise",
+        "config": {"workload": (f"{w.name}: masked conv net {w.H}x{w.W}x3 states, {w.n_conv} masked {w.k}x{w.k} layers of "
+                                f"{w.F} channels + 1x1 head, C={w.C}, batch={N}, Jacobi (Algorithm 1), seeded weights, "
+                                f"fixed Gumbel noise") if conv else
+                               (f"{w.name}: MADE D={D} hidden={w.hidden} C={w.C} batch={N} Jacobi (Algorithm 1), "
+                                f"seeded N(0,1/fan_in) weights, random degrees, fixed U(0,1) noise"),
                    "path": args.path},
         "iters_mean": it_sum / args.steps,
         "iters_max": it_max,
@@ -222,7 +261,7 @@ def main() -> int:
                     "durations from HIP events around each launch on the launch stream (second pass over the "
                     "same steps)",
         },
-        "whole_call_tflops": 2.0 * sum(nnz) * sample_passes / elapsed_prof / 1e12,
+        "whole_call_tflops": 2.0 * sum(nnz) * (N * passes if conv else sample_passes) / elapsed_prof / 1e12,
         "ms_per_step_with_events": elapsed_prof / args.steps * 1e3,
     }
 
@@ -234,11 +273,11 @@ def main() -> int:
         torch.cuda.synchronize()
         x_jac = x.clone()
         extras = {}
-        for mode, name in ((0, "sequential_whole_network"), (1, "sequential_lean")):
+        for mode, name in ((0, "sequential_whole_network"),) if conv else ((0, "sequential_whole_network"), (1, "sequential_lean")):
             B.sequential_sample(model, noises[0], N, mode, xq, stream)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            reps = 3
+            reps = 1 if conv else 3
             for _ in range(reps):
                 B.sequential_sample(model, noises[0], N, mode, xq, stream)
             torch.cuda.synchronize()
@@ -246,7 +285,7 @@ def main() -> int:
             extras[name] = {"samples_per_s": N / dt, "ms_per_batch": dt * 1e3,
                             "same_output_as_jacobi": bool(torch.equal(xq, x_jac)),
                             "jacobi_speedup": (N * args.steps / elapsed) / (N / dt)}
-        for blk in (w.block_sizes or []):
+        for blk in ([] if conv else (w.block_sizes or [])):
             B.gs_jacobi_sample(model, noises[0], N, None, blk, xq, iters, stream)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
@@ -263,7 +302,14 @@ def main() -> int:
                                            "same_output_as_jacobi": bool(torch.equal(xq, x_jac))}
         result["extras"] = extras
 
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and conv:
+        base, xs, n2 = cpu_baseline_conv(w, net, noises_host[0])
+        result["cpu_baseline"] = base
+        if x_jac is not None:
+            # early states depend on early states only: the oracle's first states are final
+            result["cpu_baseline"]["gpu_matches_oracle_on_sample"] = bool(
+                np.array_equal(x_jac[:1, :n2].cpu().numpy(), xs))
+    elif not args.no_cpu_baseline:
         base, xs, n2 = cpu_baseline(w, net, noises_host)
         result["cpu_baseline"] = base
         if x_jac is not None:

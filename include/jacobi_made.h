@@ -68,6 +68,33 @@ typedef struct made_config {
 int made_init(const made_config* cfg, const int32_t* const* degrees, const float* const* W,
               const float* const* b, made_model** out);
 
+/*
+ * made_conv_init -- a PixelCNN-style masked convolutional network in place of the masked MLP (the paper's second
+ * sampling experiment, Section 5.3.2, uses a network of this kind; states are sub-pixels in raster-scan order,
+ * Section 5.3).  The image is H x 32 pixels with 3 colours; state t = (y * 32 + x) * 3 + colour, D = H * 32 * 3,
+ * every state C = 256-way categorical, entering the network as (symbol - 128) / 128.
+ *   W[0]          : host fp32 [F, k, k, 3]   first layer, mask type A
+ *   W[1..n_conv-1]: host fp32 [F, k, k, F]   mask type B
+ *   W[n_conv]     : host fp32 [3*256, F]     1 x 1 head, mask type B; rows colour*256 + class
+ *   b             : [n_conv + 1] biases or NULL.  ReLU after every k x k layer.
+ * Tap (ky, kx) reads the input at offset (ky - k/2, kx - k/2), zero outside the image.  Masks: taps above, or in
+ * the same row to the left, are fully visible; taps below or to the right are not; at the centre tap an output
+ * of group j sees inputs of group < j (type A; input colour c is group c) or <= j (type B).  The F features form
+ * three groups of sizes ceil(F/3), ceil((F - s0)/2), rest; head rows of colour c are group c.
+ * Supported: F in {64, 128}, k odd <= 7, n_conv >= 2.  The model works with made_forward_logits, jacobi_sample,
+ * gs_jacobi_sample (blocks of consecutive states; every inner pass evaluates the whole network) and
+ * sequential_sample (both modes evaluate the whole network at every step: no activation cache).
+ */
+typedef struct made_conv_config {
+  int32_t H, W;   /* image height; width (must be 32)          */
+  int32_t C;      /* classes per sub-pixel (must be 256)       */
+  int32_t F;      /* feature channels                          */
+  int32_t k;      /* kernel size of the masked layers          */
+  int32_t n_conv; /* number of k x k masked layers             */
+  int32_t dtype;  /* MADE_F32 or MADE_BF16                     */
+} made_conv_config;
+int made_conv_init(const made_conv_config* cfg, const float* const* W, const float* const* b, made_model** out);
+
 /* made_free -- release the model and all of its device scratch memory.  NULL is accepted. */
 int made_free(made_model* m);
 
@@ -165,9 +192,10 @@ enum { MADE_OPT_PERSISTENT = 1, MADE_OPT_FUSED_CATEGORICAL = 2, MADE_OPT_CHAINS 
 int made_set_option(made_model* m, int32_t option, int32_t value);
 
 /*
- * made_layer_nnz -- number of visible (mask = 1) weights of each of the L+1 layers: one pass over one
- * sample costs 2 * sum(nnz) floating-point operations, the algorithmic work of one evaluation of all
- * h_t (Section 5.3.1).  n must be L+1.
+ * made_layer_nnz -- multiply-accumulates one pass over one sample needs in each of the L+1 layers, counting
+ * visible (mask = 1) weights only (for the convolutional model: visible weights x pixels): one pass costs
+ * 2 * sum(nnz) floating-point operations, the algorithmic work of one evaluation of all h_t (Section 5.3.1).
+ * n must be L+1 (L = n_conv for the convolutional model).
  */
 int made_layer_nnz(const made_model* m, int64_t* nnz, int32_t n);
 

@@ -3,7 +3,7 @@
 TEST INFRASTRUCTURE ONLY (see made_oracle.py for the rules; nothing in the product path imports this).
 
 The paper's second sampling experiment (Section 5.3.2) uses a masked convolutional network whose states
-are visited in raster-scan order (Section 5.3: "pixel-by-pixel in raster scan order").  That architecture
+are visited one pixel after the other in raster-scan order (Section 5.3).  That architecture
 and its checkpoint are not available; this is a plain masked-convolution stand-in with the same kind of
 state space: an H x W image with 3 channels, one state per sub-pixel in (row, column, channel) order,
 C-way categorical states drawn by Gumbel-max from fixed noise (Appendix A.3).  The feedforward recurrence

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libjacobi_m
 MADE_OK, MADE_ERR_ARG, MADE_ERR_NOMEM, MADE_ERR_HIP, MADE_ERR_NOT_CONVERGED = 0, -1, -2, -3, -4
 MADE_F32, MADE_BF16 = 0, 1
 
-EXPORTS = ["made_init", "made_free", "made_forward_logits", "sequential_sample", "jacobi_sample",
+EXPORTS = ["made_init", "made_conv_init", "made_free", "made_forward_logits", "sequential_sample", "jacobi_sample",
            "gs_jacobi_sample", "made_last_stats", "made_set_profiling", "made_last_profile", "made_set_option",
            "made_layer_nnz",
            "made_last_error"]
@@ -32,6 +32,11 @@ class MadeError(RuntimeError):
 class made_config(C.Structure):
     _fields_ = [("D", C.c_int32), ("C", C.c_int32), ("n_hidden", C.c_int32),
                 ("hidden", C.POINTER(C.c_int32)), ("dtype", C.c_int32)]
+
+
+class made_conv_config(C.Structure):
+    _fields_ = [("H", C.c_int32), ("W", C.c_int32), ("C", C.c_int32), ("F", C.c_int32), ("k", C.c_int32),
+                ("n_conv", C.c_int32), ("dtype", C.c_int32)]
 
 
 _lib = None
@@ -51,6 +56,8 @@ def lib() -> C.CDLL:
         vp, i32, i64p = C.c_void_p, C.c_int32, C.POINTER(C.c_int64)
         L.made_init.argtypes = [C.POINTER(made_config), C.POINTER(C.POINTER(C.c_int32)),
                                 C.POINTER(C.POINTER(C.c_float)), C.POINTER(C.POINTER(C.c_float)), C.POINTER(vp)]
+        L.made_conv_init.argtypes = [C.POINTER(made_conv_config), C.POINTER(C.POINTER(C.c_float)),
+                                     C.POINTER(C.POINTER(C.c_float)), C.POINTER(vp)]
         L.made_free.argtypes = [vp]
         L.made_forward_logits.argtypes = [vp, vp, i32, vp, vp]
         L.sequential_sample.argtypes = [vp, vp, i32, i32, vp, vp]
@@ -129,6 +136,39 @@ def made_init(D: int, Cn: int, hidden: Sequence[int], dtype: int, degrees: Seque
     out = C.c_void_p()
     _check(lib().made_init(C.byref(cfg), deg_arr, W_arr, b_arr, C.byref(out)))
     return out.value
+
+
+def made_conv_init(H: int, W: int, Cn: int, F: int, k: int, n_conv: int, dtype: int, Wts: Sequence[np.ndarray],
+                   b: Optional[Sequence[Optional[np.ndarray]]] = None) -> int:
+    """Returns the opaque handle of a masked convolutional model (see include/jacobi_made.h)."""
+    cfg = made_conv_config(int(H), int(W), int(Cn), int(F), int(k), int(n_conv), int(dtype))
+    shapes = [(F, k, k, 3)] + [(F, k, k, F)] * (n_conv - 1) + [(3 * Cn, 1, 1, F)]
+    keep = []
+    W_arr = (C.POINTER(C.c_float) * (n_conv + 1))()
+    b_arr = (C.POINTER(C.c_float) * (n_conv + 1))()
+    for l, shp in enumerate(shapes):
+        a = np.ascontiguousarray(Wts[l], dtype=np.float32)
+        if a.shape != shp and a.shape != (shp[0], shp[3]):
+            raise ValueError("W[%d] has shape %s, expected %s" % (l, a.shape, shp))
+        keep.append(a)
+        W_arr[l] = a.ctypes.data_as(C.POINTER(C.c_float))
+        bl = None if b is None else b[l]
+        if bl is not None:
+            bb = np.ascontiguousarray(bl, dtype=np.float32)
+            if bb.shape != (shp[0],):
+                raise ValueError("b[%d] has shape %s" % (l, bb.shape))
+            keep.append(bb)
+            b_arr[l] = bb.ctypes.data_as(C.POINTER(C.c_float))
+    out = C.c_void_p()
+    _check(lib().made_conv_init(C.byref(cfg), W_arr, b_arr, C.byref(out)))
+    return out.value
+
+
+def conv_model_from_network(net) -> int:
+    """made_conv_init from a synth.ConvNetwork description."""
+    n_conv = len(net.W_) - 1
+    return made_conv_init(net.H, net.W, net.C, net.F, net.k, n_conv, MADE_BF16 if net.dtype == "bf16" else MADE_F32,
+                          net.W_, net.b)
 
 
 def made_free(model: Optional[int]) -> None:

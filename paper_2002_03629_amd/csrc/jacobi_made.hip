@@ -120,7 +120,23 @@ struct Workspace {
   volatile int* h_pin = nullptr;     // pinned host words: [0] flags copy, [2..5] persistent kernel's statistics
 };
 
+// Masked convolutional model (arch 1): first layer 3 -> F (type A), n_conv - 1 layers F -> F (type B), 1 x 1 head.
+struct ConvNet {
+  int H = 0, F = 0, k = 0, n_conv = 0, n_taps = 0;
+  int* taps = nullptr;               // device [n_taps][2] visible taps (dy, dx), the centre tap last
+  float* w0 = nullptr;               // first layer, masked fp32 [F][n_taps][3]
+  float* b0 = nullptr;
+  std::vector<void*> w;              // layers 1 .. n_conv-1: [F x n_taps*F] tap-major K, fragment-major
+  std::vector<float*> bias;
+  void* w_head = nullptr;            // [3*256 x F], fragment-major
+  float* b_head = nullptr;
+  int* head_tile_kend = nullptr;     // [3*8]
+  void* act[2] = {nullptr, nullptr}; // ping-pong activations for the current batch capacity
+};
+
 struct made_model {
+  int arch = 0;                               // 0 masked MLP, 1 masked convolutional network
+  ConvNet conv;
   int D = 0, C = 1, L = 0, dtype = MADE_F32, device = 0;
   std::vector<int> hidden;
   std::vector<Layer> layers;                  // L hidden + 1 output
@@ -143,8 +159,6 @@ struct made_model {
   int use_persistent = 0;                     // made_set_option(MADE_OPT_PERSISTENT); off: measured slower, see header
 };
 
-static size_t elem_size(const made_model* m) { return m->dtype == MADE_BF16 ? 2 : 4; }
-static int chunk_elems(const made_model* m) { return m->dtype == MADE_BF16 ? 64 : 32; }
 
 static uint16_t host_f32_to_bf16(float f) {
   uint32_t u;
@@ -153,6 +167,9 @@ static uint16_t host_f32_to_bf16(float f) {
   u += 0x7fffu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
 }
+
+static size_t elem_size(const made_model* m) { return m->dtype == MADE_BF16 ? 2 : 4; }
+static int chunk_elems(const made_model* m) { return m->dtype == MADE_BF16 ? 64 : 32; }
 
 static void free_workspace(Workspace& w) {
   if (w.enc) (void)hipFree(w.enc);
@@ -173,6 +190,28 @@ static void free_workspace(Workspace& w) {
 
 static int ensure_workspace(made_model* m, int N, bool need_z) {
   Workspace& w = m->ws;
+  if (m->arch == 1) {
+    if (N <= w.N_cap) return MADE_OK;
+    const int cap = std::max(N, w.N_cap);
+    free_workspace(w);
+    ConvNet& cv = m->conv;
+    for (int i = 0; i < 2; ++i) {
+      if (cv.act[i]) (void)hipFree(cv.act[i]);
+      cv.act[i] = nullptr;
+      const size_t bytes = (size_t)cap * cv.H * 32 * cv.F * elem_size(m);
+      HIP_TRY(hipMalloc(&cv.act[i], bytes));
+      HIP_TRY(hipMemset(cv.act[i], 0, bytes));
+    }
+    const int n_pad = round_up(cap, 2 * TILE);
+    HIP_TRY(hipEventCreateWithFlags(&w.fork_ev, hipEventDisableTiming));
+    HIP_TRY(hipMalloc((void**)&w.changed, (size_t)2 * n_pad * sizeof(int)));
+    w.n_pad = n_pad;
+    HIP_TRY(hipMalloc((void**)&w.iters, (size_t)n_pad * sizeof(int)));
+    HIP_TRY(hipMalloc((void**)&w.flags, sizeof(int)));
+    HIP_TRY(hipHostMalloc((void**)&w.h_pin, 8 * sizeof(int), hipHostMallocDefault));
+    w.N_cap = cap;
+    return MADE_OK;
+  }
   need_z = need_z && m->C > 1;
   if (N <= w.N_cap && (!need_z || w.zbuf)) return MADE_OK;
   const int cap = std::max(N, w.N_cap);
@@ -237,6 +276,16 @@ extern "C" int made_free(made_model* m) {
     if (l.cnt_lt) (void)hipFree(l.cnt_lt);
   }
   free_workspace(m->ws);
+  {
+    ConvNet& cv = m->conv;
+    void* ptrs[] = {cv.taps, cv.w0, cv.b0, cv.w_head, cv.b_head, cv.head_tile_kend, cv.act[0], cv.act[1]};
+    for (void* p : ptrs)
+      if (p) (void)hipFree(p);
+    for (void* p : cv.w)
+      if (p) (void)hipFree(p);
+    for (float* p : cv.bias)
+      if (p) (void)hipFree(p);
+  }
   for (hipEvent_t e : m->ev_pool) (void)hipEventDestroy(e);
   delete m;
   return MADE_OK;
@@ -462,6 +511,161 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
   return MADE_OK;
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// masked convolutional model
+// ------------------------------------------------------------------------------------------------
+static void conv_group_of_feature(int F, std::vector<int>& grp) {
+  const int s0 = (F + 2) / 3, s1 = (F - s0 + 1) / 2;
+  grp.resize(F);
+  for (int f = 0; f < F; ++f) grp[f] = f < s0 ? 0 : (f < s0 + s1 ? 1 : 2);
+}
+
+template <typename V>
+static hipError_t upload(V** dev, const std::vector<V>& host) {
+  hipError_t e = hipMalloc((void**)dev, std::max<size_t>(host.size(), 1) * sizeof(V));
+  if (e == hipSuccess && !host.empty()) e = hipMemcpy(*dev, host.data(), host.size() * sizeof(V), hipMemcpyHostToDevice);
+  return e;
+}
+
+extern "C" int made_conv_init(const made_conv_config* cfg, const float* const* W, const float* const* b,
+                              made_model** out) {
+  if (!out) return fail(MADE_ERR_ARG, "made_conv_init: out is NULL");
+  *out = nullptr;
+  if (!cfg || !W) return fail(MADE_ERR_ARG, "made_conv_init: NULL argument");
+  if (cfg->W != 32) return fail(MADE_ERR_ARG, "made_conv_init: image width %d, only 32 is supported", cfg->W);
+  if (cfg->H < 1 || cfg->H > 4096) return fail(MADE_ERR_ARG, "made_conv_init: H=%d out of range [1, 4096]", cfg->H);
+  if (cfg->C != CAT_C) return fail(MADE_ERR_ARG, "made_conv_init: C=%d, only 256 classes are supported", cfg->C);
+  if (cfg->dtype != MADE_F32 && cfg->dtype != MADE_BF16) return fail(MADE_ERR_ARG, "made_conv_init: unknown dtype %d", cfg->dtype);
+  if (cfg->F != 64 && cfg->F != 128) return fail(MADE_ERR_ARG, "made_conv_init: F=%d, supported: 64, 128", cfg->F);
+  if (cfg->k < 1 || cfg->k > CONV_MAX_K || cfg->k % 2 == 0)
+    return fail(MADE_ERR_ARG, "made_conv_init: k=%d must be odd and <= %d", cfg->k, CONV_MAX_K);
+  if (cfg->n_conv < 2 || cfg->n_conv > 62) return fail(MADE_ERR_ARG, "made_conv_init: n_conv=%d out of range [2, 62]", cfg->n_conv);
+  for (int l = 0; l <= cfg->n_conv; ++l)
+    if (!W[l]) return fail(MADE_ERR_ARG, "made_conv_init: W[%d] is NULL", l);
+
+  made_model* m = new (std::nothrow) made_model();
+  if (!m) return fail(MADE_ERR_NOMEM, "made_conv_init: host allocation failed");
+  m->arch = 1;
+  m->dtype = cfg->dtype;
+  m->C = cfg->C;
+  m->D = cfg->H * cfg->W * 3;
+  m->L = cfg->n_conv;
+  hipError_t e = hipGetDevice(&m->device);
+  if (e != hipSuccess) {
+    delete m;
+    return fail(MADE_ERR_HIP, "hipGetDevice failed: %s", hipGetErrorString(e));
+  }
+  ConvNet& cv = m->conv;
+  cv.H = cfg->H;
+  cv.F = cfg->F;
+  cv.k = cfg->k;
+  cv.n_conv = cfg->n_conv;
+  const int F = cfg->F, k = cfg->k, mid = k / 2, kc = chunk_elems(m), kch = F / kc;
+  std::vector<int> grp;
+  conv_group_of_feature(F, grp);
+  // visible taps: strictly above, or same row strictly left; the centre tap (partly visible) last
+  std::vector<int> taps;
+  std::vector<int> tap_kykx;
+  for (int ky = 0; ky < k; ++ky)
+    for (int kx = 0; kx < k; ++kx)
+      if (ky < mid || (ky == mid && kx < mid)) {
+        taps.push_back(ky - mid);
+        taps.push_back(kx - mid);
+        tap_kykx.push_back(ky * k + kx);
+      }
+  taps.push_back(0);
+  taps.push_back(0);
+  tap_kykx.push_back(mid * k + mid);
+  cv.n_taps = (int)tap_kykx.size();
+  const int64_t pixels = (int64_t)cfg->H * cfg->W;
+  int rc = MADE_OK;
+  try {
+    e = upload(&cv.taps, taps);
+    // first layer: fp32 [F][n_taps][3]; centre tap: colour c visible iff c < group(f)
+    std::vector<float> w0((size_t)F * cv.n_taps * 3, 0.f), b0(F, 0.f);
+    int64_t nnz0 = 0;
+    for (int f = 0; f < F; ++f)
+      for (int t = 0; t < cv.n_taps; ++t)
+        for (int c = 0; c < 3; ++c) {
+          const bool centre = t == cv.n_taps - 1;
+          if (centre && !(c < grp[f])) continue;
+          w0[((size_t)f * cv.n_taps + t) * 3 + c] = W[0][((size_t)f * k * k + tap_kykx[t]) * 3 + c];
+          nnz0++;
+        }
+    if (b && b[0]) b0.assign(b[0], b[0] + F);
+    if (e == hipSuccess) e = upload(&cv.w0, w0);
+    if (e == hipSuccess) e = upload(&cv.b0, b0);
+    m->nnz.push_back(nnz0 * pixels);
+    // layers 1 .. n_conv-1: [F x n_taps*F] with K index = tap * F + input channel; centre tap: in group <= out group
+    const int k_chunks = cv.n_taps * kch;
+    for (int l = 1; l < cfg->n_conv && e == hipSuccess; ++l) {
+      const size_t n_w = (size_t)F * cv.n_taps * F;
+      std::vector<uint8_t> host(n_w * elem_size(m), 0);
+      int64_t nnz = 0;
+      for (int f = 0; f < F; ++f)
+        for (int t = 0; t < cv.n_taps; ++t)
+          for (int ci = 0; ci < F; ++ci) {
+            const bool centre = t == cv.n_taps - 1;
+            if (centre && !(grp[ci] <= grp[f])) continue;
+            const float v = W[l][((size_t)f * k * k + tap_kykx[t]) * F + ci];
+            const size_t off = m->dtype == MADE_BF16 ? frag_offset<bf16_t>(f, t * F + ci, k_chunks)
+                                                     : frag_offset<float>(f, t * F + ci, k_chunks);
+            if (m->dtype == MADE_BF16) ((uint16_t*)host.data())[off] = host_f32_to_bf16(v);
+            else ((float*)host.data())[off] = v;
+            nnz++;
+          }
+      void* dw = nullptr;
+      e = hipMalloc(&dw, host.size());
+      if (e == hipSuccess) e = hipMemcpy(dw, host.data(), host.size(), hipMemcpyHostToDevice);
+      cv.w.push_back(dw);
+      std::vector<float> hb(F, 0.f);
+      if (b && b[l]) hb.assign(b[l], b[l] + F);
+      float* db = nullptr;
+      if (e == hipSuccess) e = upload(&db, hb);
+      cv.bias.push_back(db);
+      m->nnz.push_back(nnz * pixels);
+    }
+    // head: rows c*256 + class read features of group <= c (a prefix, features are ordered by group)
+    if (e == hipSuccess) {
+      const int rows = 3 * CAT_C;
+      std::vector<uint8_t> host((size_t)rows * F * elem_size(m), 0);
+      std::vector<int> kend(rows / TILE, 0);
+      int64_t nnz = 0;
+      for (int r = 0; r < rows; ++r)
+        for (int f = 0; f < F; ++f) {
+          if (!(grp[f] <= r / CAT_C)) continue;
+          const float v = W[cfg->n_conv][(size_t)r * F + f];
+          const size_t off = m->dtype == MADE_BF16 ? frag_offset<bf16_t>(r, f, kch) : frag_offset<float>(r, f, kch);
+          if (m->dtype == MADE_BF16) ((uint16_t*)host.data())[off] = host_f32_to_bf16(v);
+          else ((float*)host.data())[off] = v;
+          kend[r / TILE] = std::max(kend[r / TILE], round_up(f + 1, kc));
+          nnz++;
+        }
+      e = hipMalloc(&cv.w_head, host.size());
+      if (e == hipSuccess) e = hipMemcpy(cv.w_head, host.data(), host.size(), hipMemcpyHostToDevice);
+      std::vector<float> hb(rows, 0.f);
+      if (b && b[cfg->n_conv]) hb.assign(b[cfg->n_conv], b[cfg->n_conv] + rows);
+      if (e == hipSuccess) e = upload(&cv.b_head, hb);
+      if (e == hipSuccess) e = upload(&cv.head_tile_kend, kend);
+      m->nnz.push_back(nnz * pixels);
+    }
+    if (e != hipSuccess)
+      rc = fail(e == hipErrorOutOfMemory ? MADE_ERR_NOMEM : MADE_ERR_HIP, "made_conv_init: upload failed: %s",
+                hipGetErrorString(e));
+  } catch (const std::bad_alloc&) {
+    rc = fail(MADE_ERR_NOMEM, "made_conv_init: host allocation failed");
+  }
+  if (rc != MADE_OK) {
+    made_free(m);
+    return rc;
+  }
+  m->prof_ms.assign(m->L + 2, 0.0);
+  m->prof_launches.assign(m->L + 2, 0);
+  *out = m;
+  return MADE_OK;
+}
+
 // ------------------------------------------------------------------------------------------------
 // launches
 // ------------------------------------------------------------------------------------------------
@@ -666,9 +870,124 @@ static int run_output_sample(made_model* m, const RowSet& rs, const SampleIO& io
   return MADE_OK;
 }
 
+// One pass of the convolutional network over ALL images of the batch (converged images are recomputed; their
+// symbols cannot change), then the fused head: Gumbel-max draw of the states in [state_lo, state_hi).
+static void launch_conv_trunk(made_model* m, const uint8_t* x, int N, hipStream_t s, const void** last_act) {
+  ConvNet& cv = m->conv;
+  const int kch = cv.F / chunk_elems(m);
+  const int ft = cv.F / 32;
+  ConvFirstArgs fa;
+  memset(&fa, 0, sizeof fa);
+  fa.x = x;
+  fa.w = cv.w0;
+  fa.bias = cv.b0;
+  fa.taps = cv.taps;
+  fa.n_taps = cv.n_taps;
+  fa.out = cv.act[0];
+  fa.out_chunks = kch;
+  fa.N = N;
+  fa.H = cv.H;
+  fa.F = cv.F;
+  prof_mark(m, 0, false, s);
+  if (m->dtype == MADE_BF16) {
+    if (ft == 4) hipLaunchKernelGGL((conv_first_kernel<bf16_t, 4>), dim3(N * cv.H), dim3(256), 0, s, fa);
+    else hipLaunchKernelGGL((conv_first_kernel<bf16_t, 2>), dim3(N * cv.H), dim3(256), 0, s, fa);
+  } else {
+    if (ft == 4) hipLaunchKernelGGL((conv_first_kernel<float, 4>), dim3(N * cv.H), dim3(256), 0, s, fa);
+    else hipLaunchKernelGGL((conv_first_kernel<float, 2>), dim3(N * cv.H), dim3(256), 0, s, fa);
+  }
+  prof_mark(m, 0, true, s);
+  m->stats[2]++;
+  const int kmid = cv.k / 2;
+  // input rows in fragment order; the epilogue re-uses the space for four 32 x 33 float patches
+  const size_t lds = std::max<size_t>((size_t)(CONV_ROWS + kmid) * kch * 256 * 16, (size_t)4 * TILE * (TILE + 1) * 4);
+  const int grid = N * ((cv.H + CONV_ROWS - 1) / CONV_ROWS);
+  int cur = 0;
+  for (int l = 1; l < cv.n_conv; ++l) {
+    ConvLayerArgs a;
+    memset(&a, 0, sizeof a);
+    a.in = cv.act[cur];
+    a.w = cv.w[l - 1];
+    a.bias = cv.bias[l - 1];
+    a.taps = cv.taps;
+    a.n_taps = cv.n_taps;
+    a.kmid = kmid;
+    a.out = cv.act[cur ^ 1];
+    a.N = N;
+    a.H = cv.H;
+    prof_mark(m, l, false, s);
+#define JM_LAUNCH_CONV(T, FT)                                                                                     \
+  do {                                                                                                            \
+    static size_t configured = 0;                                                                                 \
+    if (lds > configured) {                                                                                       \
+      (void)hipFuncSetAttribute((const void*)conv_layer_kernel<T, FT>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                (int)lds);                                                                        \
+      configured = lds;                                                                                           \
+    }                                                                                                             \
+    hipLaunchKernelGGL((conv_layer_kernel<T, FT>), dim3(grid), dim3(256), lds, s, a);                             \
+  } while (0)
+    if (m->dtype == MADE_BF16) {
+      if (ft == 4) JM_LAUNCH_CONV(bf16_t, 4); else JM_LAUNCH_CONV(bf16_t, 2);
+    } else {
+      if (ft == 4) JM_LAUNCH_CONV(float, 4); else JM_LAUNCH_CONV(float, 2);
+    }
+#undef JM_LAUNCH_CONV
+    prof_mark(m, l, true, s);
+    m->stats[2]++;
+    cur ^= 1;
+  }
+  *last_act = cv.act[cur];
+}
+
+static int run_conv_pass(made_model* m, int N, const SampleIO& io, hipStream_t s) {
+  ConvNet& cv = m->conv;
+  const void* last = nullptr;
+  launch_conv_trunk(m, io.x, N, s, &last);
+  CatArgs c;
+  memset(&c, 0, sizeof c);
+  c.A = last;
+  c.W = cv.w_head;
+  c.k_chunks = cv.F / chunk_elems(m);
+  c.bias = cv.b_head;
+  c.tile_kend = cv.head_tile_kend;
+  c.k_cap = cv.F;
+  c.rows = nullptr;
+  c.n_rows_ptr = nullptr;
+  c.n_rows = N * cv.H * 32;
+  c.noise = io.noise;
+  c.x = io.x;
+  c.enc = nullptr;
+  c.changed = m->ws.changed;
+  c.D = 3;
+  c.t_lo = 0;
+  c.t_hi = 3;
+  c.t_begin = 0;
+  c.n_pos = 3;
+  c.pair_tiles = (c.n_rows + 2 * TILE - 1) / (2 * TILE);
+  c.rows_per_image = cv.H * 32;
+  c.state_lo = io.t_lo;
+  c.state_hi = io.t_hi;
+  c.retire = io.retire;
+  prof_mark(m, m->L, false, s);
+  if (m->dtype == MADE_BF16)
+    hipLaunchKernelGGL((categorical_output_kernel<bf16_t>), dim3(c.n_pos * c.pair_tiles), dim3(CAT_WAVES * 64), 0, s, c);
+  else
+    hipLaunchKernelGGL((categorical_output_kernel<float>), dim3(c.n_pos * c.pair_tiles), dim3(CAT_WAVES * 64), 0, s, c);
+  prof_mark(m, m->L, true, s);
+  m->stats[2]++;
+  HIP_TRY(hipGetLastError());
+  return MADE_OK;
+}
+
 static int launch_init_state(made_model* m, const uint8_t* x_init, uint8_t* x, int N, hipStream_t s) {
   const size_t total = (size_t)N * m->D;
   const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
+  if (m->arch == 1) {   // the first convolution reads the symbols themselves
+    if (x) hipLaunchKernelGGL(copy_symbols_kernel, dim3(blocks), dim3(256), 0, s, x_init, x, total);
+    m->stats[2]++;
+    HIP_TRY(hipGetLastError());
+    return MADE_OK;
+  }
   if (m->dtype == MADE_BF16)
     hipLaunchKernelGGL((init_state_kernel<bf16_t>), dim3(blocks), dim3(256), 0, s, x_init, x, (bf16_t*)m->ws.enc,
                        m->layers[0].k_chunks, N, m->D, m->C);
@@ -699,6 +1018,32 @@ extern "C" int made_forward_logits(made_model* m, const uint8_t* x, int32_t N, f
   const bool was_profiling = m->profiling;
   m->profiling = false;  // this call does not wait for the stream, so it cannot read event times
   TRY(ensure_workspace(m, N, false));
+  if (m->arch == 1) {
+    const void* last = nullptr;
+    launch_conv_trunk(m, x, N, s, &last);
+    // the 1 x 1 head is a plain layer over pixels: logits[pixel][colour * 256 + class]
+    ConvNet& cv = m->conv;
+    LayerArgs a;
+    memset(&a, 0, sizeof a);
+    a.A = last;
+    a.W = cv.w_head;
+    a.k_chunks = cv.F / chunk_elems(m);
+    a.bias = cv.b_head;
+    a.tile_kend = cv.head_tile_kend;
+    a.k_cap = cv.F;
+    a.n_rows = N * cv.H * 32;
+    a.n_rows_pad = round_up(a.n_rows, 2 * TILE);
+    a.n_cols = 3 * CAT_C;
+    a.out = logits;
+    a.ldo = 3 * CAT_C;
+    const int big_saved = m->big_batch;
+    m->big_batch = 1 << 30;    // (the head has only 768 outputs: always the 32 x 32 tiles)
+    launch_layer<EPI_LOGITS>(m, m->L, a, 3 * CAT_C / TILE, (a.n_rows + TILE - 1) / TILE, s);
+    m->big_batch = big_saved;
+    m->profiling = was_profiling;
+    HIP_TRY(hipGetLastError());
+    return MADE_OK;
+  }
   TRY(launch_init_state(m, x, nullptr, N, s));
   RowSet rs{nullptr, nullptr, N};
   TRY(run_hidden(m, rs, nullptr, -1, s));
@@ -727,8 +1072,8 @@ static Block make_block(const made_model* m, int a, int b, int cap, bool limited
   blk.a = a;
   blk.b = b;
   blk.cap = cap;
-  blk.limited = limited;
-  if (limited) {
+  blk.limited = limited && m->arch == 0;
+  if (blk.limited) {
     // positions <= b (1-based) read last-layer units of degree < b; those read units of degree <= their own,
     // and inputs of index <= b - 1
     blk.hidden_limit.resize(m->L);
@@ -779,8 +1124,12 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
   } else {
     rs = RowSet{c.rows[0], nullptr, c.count};   // no stop test: every sample of the chain takes the pass
   }
-  TRY(run_hidden(m, rs, blk.limited ? blk.hidden_limit.data() : nullptr, blk.in_limit, s));
-  TRY(run_output_sample(m, rs, io, blk.whole_network, blk.out_k_limit, s));
+  if (m->arch == 1) {
+    TRY(run_conv_pass(m, c.count, io, s));
+  } else {
+    TRY(run_hidden(m, rs, blk.limited ? blk.hidden_limit.data() : nullptr, blk.in_limit, s));
+    TRY(run_output_sample(m, rs, io, blk.whole_network, blk.out_k_limit, s));
+  }
   c.k_enq = k;
   return MADE_OK;
 }
@@ -795,6 +1144,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
   Workspace& w = m->ws;
   // split the batch into chains of whole 32-sample tiles
   int want = std::max(1, std::min(m->n_chains, (N + TILE - 1) / TILE));
+  if (m->arch == 1) want = 1;   // the convolutional trunk always runs the whole batch
   const int per = round_up((N + want - 1) / want, TILE);
   const int n_chains = (N + per - 1) / per;
   int total_passes = 0;
@@ -922,7 +1272,7 @@ extern "C" int sequential_sample(made_model* m, const float* noise, int32_t N, i
 static int run_persistent(made_model* m, const float* noise, int N, const uint8_t* x_init, uint8_t* x, int block,
                           int cap, bool flag_unconverged, int32_t* iters_out, hipStream_t s, bool* done) {
   *done = false;
-  if (!m->use_persistent || m->persist_grid <= 0 || N > PERSIST_MAX_N) return MADE_OK;
+  if (m->arch != 0 || !m->use_persistent || m->persist_grid <= 0 || N > PERSIST_MAX_N) return MADE_OK;
   Workspace& w = m->ws;
   PersistArgs p;
   memset(&p, 0, sizeof p);

@@ -895,9 +895,10 @@ __global__ __launch_bounds__(NW * 64) void persistent_sampler_kernel(PersistArgs
 // exactly once (this layer is the model's HBM stream: 2 GiB dense for D = 1024, K = 4096, of which the
 // degree-sorted prefix structure lets it skip about half).  Each of the 4 waves owns 64 classes
 // (two 32-row weight tiles) against both 32-sample tiles: 4 accumulator tiles, no split of K, so the
-// sum order is fixed.  The MFMA takes the WEIGHTS as its row operand: an accumulator lane then holds
-// 16 classes of one sample, the 256-way argmax is 32 in-register compares, one cross-half shuffle and a
-// 4-entry combine through LDS.  Positions with the longest visible prefix are scheduled first.
+// sum order is fixed.  The MFMA takes the SAMPLES as its row operand: an accumulator lane then holds one
+// class of 16 samples, so the noise is read in whole 128-byte lines; the 256-way argmax is a compare of the
+// lane's two classes, a transposing butterfly over the 32 lanes of a half-wave and a 4-entry combine
+// through LDS.  Positions with the longest visible prefix are scheduled first.
 // ------------------------------------------------------------------------------------------------
 constexpr int CAT_C = 256;
 constexpr int CAT_WAVES = 4;
@@ -922,6 +923,11 @@ struct CatArgs {
   int t_lo, t_hi;        // positions whose symbol is re-drawn
   int t_begin, n_pos;    // positions this launch evaluates
   int pair_tiles;        // sample tiles of 64 this launch covers
+  // Convolutional model: operand rows are pixels, a "position" is a colour, D = 3.  rows_per_image > 0 then
+  // gives the pixels per image: changes are counted per image, and the states re-drawn are those with
+  // (pixel within its image) * 3 + colour in [state_lo, state_hi) instead of the t_lo / t_hi test.
+  int rows_per_image;
+  int state_lo, state_hi;
   RetireArgs retire;
 };
 
@@ -943,11 +949,11 @@ __device__ __forceinline__ void cat_group(const uint4* W0, const uint4* W1, cons
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int p = 0; p < CNT; ++p) {
-    mfma_chunk<T>(w0[p], a0[p], acc[0][0]);
-    mfma_chunk<T>(w1[p], a0[p], acc[1][0]);
+    mfma_chunk<T>(a0[p], w0[p], acc[0][0]);
+    mfma_chunk<T>(a0[p], w1[p], acc[1][0]);
     if (TWO) {
-      mfma_chunk<T>(w0[p], a1[p], acc[0][1]);
-      mfma_chunk<T>(w1[p], a1[p], acc[1][1]);
+      mfma_chunk<T>(a1[p], w0[p], acc[0][1]);
+      mfma_chunk<T>(a1[p], w1[p], acc[1][1]);
     }
   }
 }
@@ -997,62 +1003,268 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
     else
       cat_stream<T, false>(W0, W1, A0, A1, n_chunks, acc);
 
-    // acc[q][j][i]: class (wave*2 + q)*32 + 8*(i/4) + 4*h + i%4 of sample tile j's row r
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      if (j == 0 || two) {
-        const int sample = j ? n1 : n0;
-        const float* gp = a.noise + ((size_t)sample * a.D + t) * CAT_C;
-        const float* bp = a.bias + (size_t)t * CAT_C;
-        float best = -INFINITY;
-        int best_c = 0x7fffffff;
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-#pragma unroll
-          for (int i4 = 0; i4 < 4; ++i4) {
-            const int cb = (wave * 2 + q) * 32 + 8 * i4 + 4 * h;
-            const float4 gv = *(const float4*)(gp + cb);
-            const float4 bv = *(const float4*)(bp + cb);
-            const float v0 = (acc[q][j][i4 * 4 + 0] + bv.x) + gv.x;
-            const float v1 = (acc[q][j][i4 * 4 + 1] + bv.y) + gv.y;
-            const float v2 = (acc[q][j][i4 * 4 + 2] + bv.z) + gv.z;
-            const float v3 = (acc[q][j][i4 * 4 + 3] + bv.w) + gv.w;
-            // classes are visited in increasing order, so a strict compare keeps the lowest index of a tie
-            if (v0 > best) { best = v0; best_c = cb; }
-            if (v1 > best) { best = v1; best_c = cb + 1; }
-            if (v2 > best) { best = v2; best_c = cb + 2; }
-            if (v3 > best) { best = v3; best_c = cb + 3; }
-          }
+    // acc[q][j][i]: sample row 8*(i/4) + 4*h + i%4 of sample tile j, class (wave*2 + q)*32 + r.
+    // A lane's noise loads are then 4-byte reads that 32 lanes make to one 128-byte line (the noise is the
+    // larger stream of the convolutional model).  Element m = 16*j + i of a lane is one sample's best value
+    // among the lane's two classes; a transposing butterfly over the 32 lanes of a half-wave (each step the
+    // lanes of a pair split their elements between them and merge the partner's) leaves lane r with the
+    // half-wave's winner of element m = r.
+    const float b0 = a.bias[(size_t)t * CAT_C + wave * 64 + r];
+    const float b1 = a.bias[(size_t)t * CAT_C + wave * 64 + 32 + r];
+    float val[32];
+    int idx[32];
+    static_for<2>([&](auto J) {
+      constexpr int j = decltype(J)::value;
+      static_for<16>([&](auto I) {
+        constexpr int i = decltype(I)::value;
+        constexpr int m = 16 * j + i;
+        if (j == 0 || two) {
+          const int sample = __shfl(j ? n1 : n0, 8 * (i >> 2) + 4 * h + (i & 3));
+          const float* gp = a.noise + ((size_t)sample * a.D + t) * CAT_C + wave * 64 + r;
+          const float v0 = (acc[0][j][i] + b0) + gp[0];
+          const float v1 = (acc[1][j][i] + b1) + gp[32];
+          const bool second = v1 > v0;            // strict: the lower class keeps a tie
+          val[m] = second ? v1 : v0;
+          idx[m] = wave * 64 + r + (second ? 32 : 0);
+        } else {
+          val[m] = -INFINITY;
+          idx[m] = 0x7fffffff;
         }
-        const float ob = __shfl_xor(best, 32);
-        const int oc = __shfl_xor(best_c, 32);
-        if (ob > best || (ob == best && oc < best_c)) { best = ob; best_c = oc; }
-        if (h == 0) {
-          sm_val[wave][32 * j + r] = best;
-          sm_idx[wave][32 * j + r] = best_c;
-        }
-      }
+      });
+    });
+    static_for<5>([&](auto S) {
+      constexpr int bit = 16 >> decltype(S)::value;     // lane bit of this step; 2 * bit elements are left
+      const bool up = (r & bit) != 0;
+      static_for<bit>([&](auto K) {
+        constexpr int k = decltype(K)::value;
+        const float send_v = up ? val[k] : val[k + bit];
+        const int send_i = up ? idx[k] : idx[k + bit];
+        float keep_v = up ? val[k + bit] : val[k];
+        int keep_i = up ? idx[k + bit] : idx[k];
+        const float ov = __shfl_xor(send_v, bit);
+        const int oi = __shfl_xor(send_i, bit);
+        if (ov > keep_v || (ov == keep_v && oi < keep_i)) { keep_v = ov; keep_i = oi; }
+        val[k] = keep_v;
+        idx[k] = keep_i;
+      });
+    });
+    {
+      const int j = r >> 4, i = r & 15;
+      const int slot = 32 * j + 8 * (i >> 2) + 4 * h + (i & 3);
+      sm_val[wave][slot] = val[0];
+      sm_idx[wave][slot] = idx[0];
     }
     __syncthreads();
-    if (threadIdx.x < 64 && row0 + (int)threadIdx.x < n_rows && t >= a.t_lo && t < a.t_hi) {
+    if (threadIdx.x < 64) {   // (wave 0: one lane per sample row of the pair)
       const int sl = threadIdx.x;
-      float best = sm_val[0][sl];
-      int best_c = sm_idx[0][sl];
+      bool redraw = row0 + sl < n_rows;
+      if (redraw) {
+        if (a.rows_per_image > 0) {
+          const int st = ((row0 + sl) % a.rows_per_image) * 3 + t;
+          redraw = st >= a.state_lo && st < a.state_hi;
+        } else {
+          redraw = t >= a.t_lo && t < a.t_hi;
+        }
+      }
+      bool differs = false;
+      int sample = 0;
+      if (redraw) {
+        float best = sm_val[0][sl];
+        int best_c = sm_idx[0][sl];
 #pragma unroll
-      for (int w = 1; w < CAT_WAVES; ++w)
-        if (sm_val[w][sl] > best) { best = sm_val[w][sl]; best_c = sm_idx[w][sl]; }   // waves hold increasing classes
-      const int sample = a.rows ? a.rows[row0 + sl] : row0 + sl;
-      const size_t idx = (size_t)sample * a.D + t;
-      const uint8_t xn = (uint8_t)best_c;
-      if (xn != a.x[idx]) {
-        a.x[idx] = xn;
-        ((T*)a.enc)[frag_offset<T>(sample, t, a.enc_chunks)] =
-            Elem<T>::from_f32(((float)xn - 128.0f) * (1.0f / 128.0f));
+        for (int w = 1; w < CAT_WAVES; ++w)
+          if (sm_val[w][sl] > best) { best = sm_val[w][sl]; best_c = sm_idx[w][sl]; }   // waves hold increasing classes
+        sample = a.rows ? a.rows[row0 + sl] : row0 + sl;
+        const size_t idx = (size_t)sample * a.D + t;
+        const uint8_t xn = (uint8_t)best_c;
+        differs = xn != a.x[idx];
+        if (differs) {
+          a.x[idx] = xn;
+          if (a.enc)
+            ((T*)a.enc)[frag_offset<T>(sample, t, a.enc_chunks)] =
+                Elem<T>::from_f32(((float)xn - 128.0f) * (1.0f / 128.0f));
+        }
+      }
+      if (a.rows_per_image > 0) {
+        // the pixels of an image are consecutive rows: one counter update per image and workgroup (single
+        // updates of a handful of counters from every changed state serialise on one cache line)
+        const unsigned long long m = __ballot(differs);
+        const int img = (row0 + sl) / a.rows_per_image;
+        const int lo = max(img * a.rows_per_image - row0, 0);
+        const int hi = min((img + 1) * a.rows_per_image - row0, 64);
+        const unsigned long long mask = (hi >= 64 ? ~0ull : ((1ull << hi) - 1)) & ~((1ull << lo) - 1);
+        const int cnt = __popcll(m & mask);
+        if (sl == lo && cnt > 0) count_changed(&a.changed[img], cnt);
+      } else if (differs) {
         count_changed(&a.changed[sample], 1);
       }
     }
   }
   if (a.retire.enabled) finish_pass(a.retire, gridDim.x);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Masked convolutional model (images of width 32: one row of pixels is one 32-row operand group).
+// Activations are fragment-major with rows = pixels ((n*H + y)*32 + x) and K = feature channels.
+// ------------------------------------------------------------------------------------------------
+constexpr int CONV_MAX_K = 7;
+constexpr int CONV_ROWS = 4;             // image rows per workgroup of the k x k layers
+
+struct ConvFirstArgs {
+  const uint8_t* x;      // symbols [N, H, 32, 3]
+  const float* w;        // masked fp32 weights [F][n_taps][3] (live taps only)
+  const float* bias;     // [F]
+  const int* taps;       // [n_taps][2] = (dy, dx), dy <= 0
+  int n_taps;
+  void* out;             // activations, fragment-major, out_chunks chunks
+  int out_chunks;
+  int N, H, F;
+};
+
+// First layer (3 input channels, type A).  One workgroup per row of pixels; thread (pixel x, slice q) computes
+// F/8 consecutive channels of its pixel from the <= 3 * n_taps visible inputs, in fp32.  FT = F / 32.
+template <typename T, int FT>
+__global__ __launch_bounds__(256) void conv_first_kernel(ConvFirstArgs a) {
+  constexpr int P = 16 / (int)sizeof(T);
+  constexpr int PER = FT * 4;                // channels per thread (F / 8), a multiple of P
+  const int g = blockIdx.x;                  // group = (n, y)
+  const int n = g / a.H, y = g % a.H;
+  const int px = threadIdx.x & 31, q = threadIdx.x >> 5;
+  float acc[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) acc[i] = a.bias[q * PER + i];
+  for (int t = 0; t < a.n_taps; ++t) {
+    const int yy = y + a.taps[2 * t], xx = px + a.taps[2 * t + 1];
+    const bool ok = yy >= 0 && xx >= 0 && xx < 32;
+    const uint8_t* p = a.x + (((size_t)n * a.H + (ok ? yy : 0)) * 32 + (ok ? xx : 0)) * 3;
+    float in[3];
+#pragma unroll
+    for (int c = 0; c < 3; ++c) in[c] = ok ? ((float)p[c] - 128.0f) * (1.0f / 128.0f) : 0.f;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const float* w = a.w + ((size_t)(q * PER + i) * a.n_taps + t) * 3;
+      acc[i] += w[0] * in[0] + w[1] * in[1] + w[2] * in[2];
+    }
+  }
+#pragma unroll
+  for (int g8 = 0; g8 < PER / P; ++g8)
+    *(uint4*)((T*)a.out + frag_offset<T>(g * 32 + px, q * PER + g8 * P, a.out_chunks)) = Elem<T>::relu_piece(acc + g8 * P);
+}
+
+struct ConvLayerArgs {
+  const void* in;        // activations of the previous layer (fragment-major, F channels)
+  const void* w;         // masked weights as a [F x (n_taps * F)] matrix, tap-major K, fragment-major
+  const float* bias;
+  const int* taps;       // [n_taps][2] = (dy, dx) with dy <= 0
+  int n_taps;
+  int kmid;              // (k - 1) / 2: rows of halo above the workgroup's rows
+  void* out;
+  int N, H;
+};
+
+// k x k masked convolution F -> F as an implicit GEMM.  A workgroup owns CONV_ROWS image rows (128 pixels) of
+// one image and all F output channels.  The input rows it needs (its own and kmid rows above; taps below are
+// masked out) are copied into LDS once, in fragment order; a tap (dy, dx) then is the same LDS block read with
+// a row offset and a lane shift (lanes shifted out of the image read zero).  Weights stream from L2 straight
+// into registers, one visible tap and K chunk at a time, prefetched one step ahead.  FT = F / 32.
+template <typename T, int FT>
+__global__ __launch_bounds__(256) void conv_layer_kernel(ConvLayerArgs a) {
+  constexpr int KCH = FT * 32 / (2 * Elem<T>::EPL);     // K chunks per tap (= chunks per activation row group)
+  constexpr int CT = FT / 2;                            // output channel tiles per wave
+  constexpr int ROWBLK = KCH * 256;                     // uint4 per image row in LDS
+  extern __shared__ uint4 conv_lds[];                   // [(CONV_ROWS + kmid) rows][ROWBLK]
+  const int tiles_y = (a.H + CONV_ROWS - 1) / CONV_ROWS;
+  const int n = blockIdx.x / tiles_y, y0 = (blockIdx.x % tiles_y) * CONV_ROWS;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r = lane & 31, h = lane >> 5;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int lds_rows = CONV_ROWS + a.kmid;
+
+  // input rows y0 - kmid .. y0 + CONV_ROWS - 1 -> LDS (rows outside the image are zero)
+  for (int e = tid; e < lds_rows * ROWBLK; e += 256) {
+    const int lr = e / ROWBLK, off = e % ROWBLK;
+    const int y = y0 - a.kmid + lr;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (y >= 0 && y < a.H) v = ((const uint4*)a.in)[((size_t)n * a.H + y) * ROWBLK + off];
+    conv_lds[e] = v;
+  }
+  __syncthreads();
+
+  f32x16 acc[2][CT];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < CT; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  // weights: row group = output channel tile, chunk index = tap * KCH + c
+  const size_t wgroup = (size_t)a.n_taps * KCH * 256;
+  const uint4* Wp = (const uint4*)a.w + (size_t)(wn * CT) * wgroup + h * 32 + r;
+  const int n_steps = a.n_taps * KCH;
+  uint4 wcur[CT][4], wnext[CT][4];
+#pragma unroll
+  for (int j = 0; j < CT; ++j)
+#pragma unroll
+    for (int s = 0; s < 4; ++s) wcur[j][s] = Wp[(size_t)j * wgroup + s * 64];
+  for (int step = 0; step < n_steps; ++step) {
+    const int nxt = min(step + 1, n_steps - 1);          // (the last step re-reads itself: no branch)
+#pragma unroll
+    for (int j = 0; j < CT; ++j)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) wnext[j][s] = Wp[(size_t)j * wgroup + (size_t)nxt * 256 + s * 64];
+    const int tap = step / KCH, c = step % KCH;
+    const int dy = a.taps[2 * tap], dx = a.taps[2 * tap + 1];
+    const int xs = r + dx;
+    const bool x_ok = xs >= 0 && xs < 32;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int lr = wm * 2 + i + a.kmid + dy;            // LDS row holding image row y0 + 2*wm + i + dy
+      const uint4* row = conv_lds + (size_t)lr * ROWBLK + c * 256 + h * 32 + (x_ok ? xs : r);
+      uint4 af[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        af[s] = row[s * 64];
+        if (!x_ok) af[s] = make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int j = 0; j < CT; ++j) mfma_chunk<T>(af, wcur[j], acc[i][j]);
+    }
+#pragma unroll
+    for (int j = 0; j < CT; ++j)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) wcur[j][s] = wnext[j][s];
+  }
+  __syncthreads();                                        // the input tile is no longer needed
+
+  // epilogue through a wave-private LDS patch: lane = (pixel lane >> 1, 16 channels), 16-byte stores
+  constexpr int P = 16 / (int)sizeof(T);
+  float (*patch)[TILE + 1] = (float (*)[TILE + 1])((char*)conv_lds + wave * (TILE * (TILE + 1) * 4));
+  const int rr = lane >> 1, c16 = (lane & 1) * 16;
+  static_for<2>([&](auto I) {
+    constexpr int i = decltype(I)::value;
+    const int y = y0 + wm * 2 + i;
+    static_for<CT>([&](auto J) {
+      constexpr int j = decltype(J)::value;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) patch[8 * (e >> 2) + 4 * h + (e & 3)][r] = acc[i][j][e];
+      const int ch0 = (wn * CT + j) * TILE + c16;
+      float v[16];
+#pragma unroll
+      for (int cc = 0; cc < 16; ++cc) v[cc] = patch[rr][c16 + cc] + a.bias[ch0 + cc];
+      if (y < a.H) {
+        const int pixel = ((n * a.H) + y) * 32 + rr;
+#pragma unroll
+        for (int g = 0; g < 16 / P; ++g)
+          *(uint4*)((T*)a.out + frag_offset<T>(pixel, ch0 + g * P, KCH)) = Elem<T>::relu_piece(v + g * P);
+      }
+    });
+  });
+}
+
+__global__ void copy_symbols_kernel(const uint8_t* x_init, uint8_t* x, size_t total) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x)
+    x[i] = x_init ? x_init[i] : 0;
 }
 
 // Gumbel-max draw for categorical positions from logits held in memory:

@@ -268,7 +268,9 @@ class ConvWorkload:
 def conv_workload(name: str) -> ConvWorkload:
     table = {
         # 32 x 32 x 3 image, 256-way sub-pixels, 8 masked 5 x 5 layers of 128 channels, batch 32
-        "cfg5": ConvWorkload("cfg5", 32, 32, 256, 128, 5, 8, "bf16", 32, SEED_BASE + 5),
+        # (about half of a layer's taps are visible and ReLU halves the variance again: gain 2 keeps the scale from
+        # layer to layer; 2.3 gives logits of rms ~2, i.e. conditionals that are neither flat nor one-hot)
+        "cfg5": ConvWorkload("cfg5", 32, 32, 256, 128, 5, 8, "bf16", 32, SEED_BASE + 5, gain=2.3),
         # reduced shapes for the parity tests (the width stays 32: one row of pixels per 32-row operand group)
         "small_conv": ConvWorkload("small_conv", 3, 32, 256, 64, 5, 3, "bf16", 3, SEED_BASE + 21, gain=1.5),
         "small_conv_f32": ConvWorkload("small_conv_f32", 2, 32, 256, 64, 3, 2, "f32", 2, SEED_BASE + 22, gain=2.0),
