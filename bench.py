@@ -104,6 +104,8 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (supplementary sweeps)")
     ap.add_argument("--big-tile-batch", type=int, default=0,
                     help="batch size from which the 256 x 256 tile kernels are used (0 = library default)")
+    ap.add_argument("--conv-rows", type=int, default=0,
+                    help="image rows per workgroup of the conv model's k x k layers (0 = library default)")
     ap.add_argument("--chains", type=int, default=0, help="sub-batches on separate streams (0 = library default)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="no timing: run 20 device copies of 64 MiB (calibration of FETCH_SIZE / WRITE_SIZE), then "
@@ -135,6 +137,8 @@ def main() -> int:
     B.made_set_option(model, B.MADE_OPT_PERSISTENT, int(args.path == "persistent"))
     if args.chains > 0:
         B.made_set_option(model, B.MADE_OPT_CHAINS, args.chains)
+    if args.conv_rows > 0:
+        B.made_set_option(model, B.MADE_OPT_CONV_ROWS, args.conv_rows)
     if args.big_tile_batch > 0:
         B.made_set_option(model, B.MADE_OPT_BIG_TILE_BATCH, args.big_tile_batch)
     n_layers = (w.n_conv if conv else len(net.hidden)) + 1
@@ -171,7 +175,7 @@ def main() -> int:
     torch.cuda.synchronize()
 
     # ---- timed region (events off): whole-call throughput
-    it_sum, it_max, sample_passes, passes = 0.0, 0, 0, 0
+    it_sum, it_max, sample_passes, passes, conv_rows = 0.0, 0, 0, 0, 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -192,8 +196,10 @@ def main() -> int:
         st = B.made_last_stats(model)
         layer_ms += ms
         layer_launches += np.array(cnt)
-        # (the convolutional trunk evaluates every image of the batch in every pass)
-        layer_flops += flops_per_sample_pass * (N * st["passes"] if conv else st["sample_passes"]) * (np.array(cnt) > 0)
+        # (the convolutional trunk recomputes, per image, the rows below the first symbol that changed)
+        work = st["conv_rows"] / w.H if conv else st["sample_passes"]       # in whole-sample evaluations
+        layer_flops += flops_per_sample_pass * work * (np.array(cnt) > 0)
+        conv_rows += st.get("conv_rows", 0)
         sample_passes += st["sample_passes"]
         passes += st["passes"]
         itc = iters.cpu().numpy()
@@ -250,6 +256,7 @@ def main() -> int:
         "iters_mean": it_sum / args.steps,
         "iters_max": it_max,
         "passes_per_step": passes / args.steps,
+        **({"image_evaluations_per_step": conv_rows / w.H / args.steps} if conv else {}),
         "roofline": {
             "bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
             "traffic": measured_traffic(w.name, args.path, dom == n_layers - 1), "kernel": layer_name, "avg_launch_us": dom_avg_us,
@@ -261,7 +268,7 @@ def main() -> int:
                     "durations from HIP events around each launch on the launch stream (second pass over the "
                     "same steps)",
         },
-        "whole_call_tflops": 2.0 * sum(nnz) * (N * passes if conv else sample_passes) / elapsed_prof / 1e12,
+        "whole_call_tflops": 2.0 * sum(nnz) * (conv_rows / w.H if conv else sample_passes) / elapsed_prof / 1e12,
         "ms_per_step_with_events": elapsed_prof / args.steps * 1e3,
     }
 
@@ -273,7 +280,7 @@ def main() -> int:
         torch.cuda.synchronize()
         x_jac = x.clone()
         extras = {}
-        for mode, name in ((0, "sequential_whole_network"),) if conv else ((0, "sequential_whole_network"), (1, "sequential_lean")):
+        for mode, name in ((0, "sequential_whole_network"), (1, "sequential_lean")):
             B.sequential_sample(model, noises[0], N, mode, xq, stream)
             torch.cuda.synchronize()
             t0 = time.perf_counter()

@@ -81,7 +81,7 @@ int made_init(const made_config* cfg, const int32_t* const* degrees, const float
  * the same row to the left, are fully visible; taps below or to the right are not; at the centre tap an output
  * of group j sees inputs of group < j (type A; input colour c is group c) or <= j (type B).  The F features form
  * three groups of sizes ceil(F/3), ceil((F - s0)/2), rest; head rows of colour c are group c.
- * Supported: F in {64, 128}, k odd <= 7, n_conv >= 2.  The model works with made_forward_logits, jacobi_sample,
+ * Supported: F in {64, 128}, k odd with 3 <= k <= 7, n_conv >= 2.  The model works with made_forward_logits, jacobi_sample,
  * gs_jacobi_sample (blocks of consecutive states; every inner pass evaluates the whole network) and
  * sequential_sample (both modes evaluate the whole network at every step: no activation cache).
  */
@@ -156,6 +156,8 @@ int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, const uint8_t
  *   out[1] sum over passes of active samples (sample-passes; the unit of algorithmic work)
  *   out[2] kernels launched
  *   out[3] host waits on the device
+ *   out[4] convolutional model: image rows recomputed by the k x k layers, summed over passes and images (a pass
+ *          only recomputes the rows below the first symbol that changed in the pass before); 0 otherwise
  * n = number of int64 slots available in out (extra slots are left untouched).
  */
 int made_last_stats(const made_model* m, int64_t* out, int32_t n);
@@ -187,8 +189,10 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   MADE_OPT_BIG_TILE_BATCH (default 4096): batches (chains) of at least this many samples run the masked
  *   layers with 256 x 256 workgroup tiles staged through LDS instead of 32 x 32 tiles (on the D = 784,
  *   2 x 2000 network the two cross over near 5000 samples).
+ *   MADE_OPT_CONV_ROWS (default 4; 2 or 4): image rows per workgroup of the convolutional model's k x k layers.
  */
-enum { MADE_OPT_PERSISTENT = 1, MADE_OPT_FUSED_CATEGORICAL = 2, MADE_OPT_CHAINS = 3, MADE_OPT_BIG_TILE_BATCH = 4 };
+enum { MADE_OPT_PERSISTENT = 1, MADE_OPT_FUSED_CATEGORICAL = 2, MADE_OPT_CHAINS = 3, MADE_OPT_BIG_TILE_BATCH = 4,
+       MADE_OPT_CONV_ROWS = 5 };
 int made_set_option(made_model* m, int32_t option, int32_t value);
 
 /*

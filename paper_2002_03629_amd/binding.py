@@ -199,9 +199,10 @@ def gs_jacobi_sample(model: int, noise, N: int, x_init, block: int, x_out, iters
 
 
 def made_last_stats(model: int) -> dict:
-    buf = (C.c_int64 * 4)()
-    _check(lib().made_last_stats(model, buf, 4))
-    return {"passes": buf[0], "sample_passes": buf[1], "kernels": buf[2], "host_waits": buf[3]}
+    buf = (C.c_int64 * 5)()
+    _check(lib().made_last_stats(model, buf, 5))
+    return {"passes": buf[0], "sample_passes": buf[1], "kernels": buf[2], "host_waits": buf[3],
+            "conv_rows": buf[4]}
 
 
 def made_set_profiling(model: int, enable: bool) -> None:
@@ -212,6 +213,7 @@ MADE_OPT_PERSISTENT = 1
 MADE_OPT_FUSED_CATEGORICAL = 2
 MADE_OPT_CHAINS = 3
 MADE_OPT_BIG_TILE_BATCH = 4
+MADE_OPT_CONV_ROWS = 5
 
 
 def made_set_option(model: int, option: int, value: int) -> None:

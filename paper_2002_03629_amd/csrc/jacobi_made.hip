@@ -123,6 +123,7 @@ struct Workspace {
 // Masked convolutional model (arch 1): first layer 3 -> F (type A), n_conv - 1 layers F -> F (type B), 1 x 1 head.
 struct ConvNet {
   int H = 0, F = 0, k = 0, n_conv = 0, n_taps = 0;
+  int wg_rows = 4;                   // image rows per workgroup of the k x k layers: made_set_option(MADE_OPT_CONV_ROWS)
   int* taps = nullptr;               // device [n_taps][2] visible taps (dy, dx), the centre tap last
   float* w0 = nullptr;               // first layer, masked fp32 [F][n_taps][3]
   float* b0 = nullptr;
@@ -131,7 +132,11 @@ struct ConvNet {
   void* w_head = nullptr;            // [3*256 x F], fragment-major
   float* b_head = nullptr;
   int* head_tile_kend = nullptr;     // [3*8]
-  void* act[2] = {nullptr, nullptr}; // ping-pong activations for the current batch capacity
+  std::vector<void*> act;            // activations of every k x k layer for the current batch capacity (they
+                                     // persist between passes: see ConvWindow)
+  int* win = nullptr;                // [2 * n_pad + 1]: dirty_lo, first_changed, finished-workgroup counter
+  int win_pad = 0;
+  unsigned long long* rows_stat = nullptr;
 };
 
 struct made_model {
@@ -144,7 +149,7 @@ struct made_model {
   // degree, so these are prefix lengths
   std::vector<std::vector<int>> cnt_lt;
   Workspace ws;
-  int64_t stats[4] = {0, 0, 0, 0};
+  int64_t stats[5] = {0, 0, 0, 0, 0};
   // optional per-layer timing with HIP events on the caller's stream
   bool profiling = false;
   std::vector<hipEvent_t> ev_pool;            // pairs: [2i] before, [2i+1] after a layer launch
@@ -195,13 +200,19 @@ static int ensure_workspace(made_model* m, int N, bool need_z) {
     const int cap = std::max(N, w.N_cap);
     free_workspace(w);
     ConvNet& cv = m->conv;
-    for (int i = 0; i < 2; ++i) {
-      if (cv.act[i]) (void)hipFree(cv.act[i]);
-      cv.act[i] = nullptr;
+    for (void* p : cv.act)
+      if (p) (void)hipFree(p);
+    cv.act.assign(cv.n_conv, nullptr);
+    for (int i = 0; i < cv.n_conv; ++i) {
       const size_t bytes = (size_t)cap * cv.H * 32 * cv.F * elem_size(m);
       HIP_TRY(hipMalloc(&cv.act[i], bytes));
       HIP_TRY(hipMemset(cv.act[i], 0, bytes));
     }
+    if (cv.win) (void)hipFree(cv.win);
+    cv.win = nullptr;
+    cv.win_pad = round_up(cap, 2 * TILE);
+    HIP_TRY(hipMalloc((void**)&cv.win, (size_t)(2 * cv.win_pad + 1) * sizeof(int)));
+    if (!cv.rows_stat) HIP_TRY(hipMalloc((void**)&cv.rows_stat, sizeof(unsigned long long)));
     const int n_pad = round_up(cap, 2 * TILE);
     HIP_TRY(hipEventCreateWithFlags(&w.fork_ev, hipEventDisableTiming));
     HIP_TRY(hipMalloc((void**)&w.changed, (size_t)2 * n_pad * sizeof(int)));
@@ -278,12 +289,14 @@ extern "C" int made_free(made_model* m) {
   free_workspace(m->ws);
   {
     ConvNet& cv = m->conv;
-    void* ptrs[] = {cv.taps, cv.w0, cv.b0, cv.w_head, cv.b_head, cv.head_tile_kend, cv.act[0], cv.act[1]};
+    void* ptrs[] = {cv.taps, cv.w0, cv.b0, cv.w_head, cv.b_head, cv.head_tile_kend, cv.win, cv.rows_stat};
     for (void* p : ptrs)
       if (p) (void)hipFree(p);
     for (void* p : cv.w)
       if (p) (void)hipFree(p);
     for (float* p : cv.bias)
+      if (p) (void)hipFree(p);
+    for (void* p : cv.act)
       if (p) (void)hipFree(p);
   }
   for (hipEvent_t e : m->ev_pool) (void)hipEventDestroy(e);
@@ -295,7 +308,7 @@ extern "C" const char* made_last_error(void) { return g_last_error.c_str(); }
 
 extern "C" int made_last_stats(const made_model* m, int64_t* out, int32_t n) {
   if (!m || !out || n < 0) return fail(MADE_ERR_ARG, "made_last_stats: NULL argument");
-  for (int i = 0; i < n && i < 4; ++i) out[i] = m->stats[i];
+  for (int i = 0; i < n && i < 5; ++i) out[i] = m->stats[i];
   return MADE_OK;
 }
 
@@ -320,6 +333,11 @@ extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
   }
   if (option == MADE_OPT_FUSED_CATEGORICAL) {
     m->fused_categorical = value != 0;
+    return MADE_OK;
+  }
+  if (option == MADE_OPT_CONV_ROWS) {
+    if (value != 2 && value != 4) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_CONV_ROWS=%d, supported: 2, 4", value);
+    m->conv.wg_rows = value;
     return MADE_OK;
   }
   if (option == MADE_OPT_BIG_TILE_BATCH) {
@@ -538,7 +556,7 @@ extern "C" int made_conv_init(const made_conv_config* cfg, const float* const* W
   if (cfg->C != CAT_C) return fail(MADE_ERR_ARG, "made_conv_init: C=%d, only 256 classes are supported", cfg->C);
   if (cfg->dtype != MADE_F32 && cfg->dtype != MADE_BF16) return fail(MADE_ERR_ARG, "made_conv_init: unknown dtype %d", cfg->dtype);
   if (cfg->F != 64 && cfg->F != 128) return fail(MADE_ERR_ARG, "made_conv_init: F=%d, supported: 64, 128", cfg->F);
-  if (cfg->k < 1 || cfg->k > CONV_MAX_K || cfg->k % 2 == 0)
+  if (cfg->k < 3 || cfg->k > CONV_MAX_K || cfg->k % 2 == 0)
     return fail(MADE_ERR_ARG, "made_conv_init: k=%d must be odd and <= %d", cfg->k, CONV_MAX_K);
   if (cfg->n_conv < 2 || cfg->n_conv > 62) return fail(MADE_ERR_ARG, "made_conv_init: n_conv=%d out of range [2, 62]", cfg->n_conv);
   for (int l = 0; l <= cfg->n_conv; ++l)
@@ -872,77 +890,91 @@ static int run_output_sample(made_model* m, const RowSet& rs, const SampleIO& io
 
 // One pass of the convolutional network over ALL images of the batch (converged images are recomputed; their
 // symbols cannot change), then the fused head: Gumbel-max draw of the states in [state_lo, state_hi).
-static void launch_conv_trunk(made_model* m, const uint8_t* x, int N, hipStream_t s, const void** last_act) {
+static void launch_conv_trunk(made_model* m, const uint8_t* x, int N, const int* dirty_lo, int row_hi, hipStream_t s,
+                              const void** last_act) {
   ConvNet& cv = m->conv;
   const int kch = cv.F / chunk_elems(m);
   const int ft = cv.F / 32;
   ConvFirstArgs fa;
   memset(&fa, 0, sizeof fa);
+  fa.win = ConvWindow{dirty_lo, row_hi};
   fa.x = x;
   fa.w = cv.w0;
   fa.bias = cv.b0;
-  fa.taps = cv.taps;
-  fa.n_taps = cv.n_taps;
   fa.out = cv.act[0];
   fa.out_chunks = kch;
   fa.N = N;
   fa.H = cv.H;
-  fa.F = cv.F;
   prof_mark(m, 0, false, s);
-  if (m->dtype == MADE_BF16) {
-    if (ft == 4) hipLaunchKernelGGL((conv_first_kernel<bf16_t, 4>), dim3(N * cv.H), dim3(256), 0, s, fa);
-    else hipLaunchKernelGGL((conv_first_kernel<bf16_t, 2>), dim3(N * cv.H), dim3(256), 0, s, fa);
-  } else {
-    if (ft == 4) hipLaunchKernelGGL((conv_first_kernel<float, 4>), dim3(N * cv.H), dim3(256), 0, s, fa);
-    else hipLaunchKernelGGL((conv_first_kernel<float, 2>), dim3(N * cv.H), dim3(256), 0, s, fa);
+  {
+    const dim3 grid((N * cv.H + 1) / 2), block(512);
+#define JM_FIRST_K(T, FT)                                                                                 \
+  do {                                                                                                   \
+    if (cv.k == 3) hipLaunchKernelGGL((conv_first_kernel<T, FT, 3>), grid, block, 0, s, fa);             \
+    else if (cv.k == 5) hipLaunchKernelGGL((conv_first_kernel<T, FT, 5>), grid, block, 0, s, fa);        \
+    else hipLaunchKernelGGL((conv_first_kernel<T, FT, 7>), grid, block, 0, s, fa);                       \
+  } while (0)
+    if (m->dtype == MADE_BF16) {
+      if (ft == 4) JM_FIRST_K(bf16_t, 4); else JM_FIRST_K(bf16_t, 2);
+    } else {
+      if (ft == 4) JM_FIRST_K(float, 4); else JM_FIRST_K(float, 2);
+    }
+#undef JM_FIRST_K
   }
   prof_mark(m, 0, true, s);
   m->stats[2]++;
-  const int kmid = cv.k / 2;
-  // input rows in fragment order; the epilogue re-uses the space for four 32 x 33 float patches
-  const size_t lds = std::max<size_t>((size_t)(CONV_ROWS + kmid) * kch * 256 * 16, (size_t)4 * TILE * (TILE + 1) * 4);
-  const int grid = N * ((cv.H + CONV_ROWS - 1) / CONV_ROWS);
-  int cur = 0;
+  const int mid = cv.k / 2;
+  const int wg_rows = cv.wg_rows;
+  // padded input rows in fragment order; the epilogue re-uses the space for four 32 x 33 float patches
+  const size_t lds = std::max<size_t>((size_t)(wg_rows + mid) * kch * 8 * (32 + 2 * mid) * 16, (size_t)4 * TILE * (TILE + 1) * 4);
+  const int grid = N * ((cv.H + wg_rows - 1) / wg_rows);
   for (int l = 1; l < cv.n_conv; ++l) {
     ConvLayerArgs a;
     memset(&a, 0, sizeof a);
-    a.in = cv.act[cur];
+    a.win = ConvWindow{dirty_lo, row_hi};
+    a.in = cv.act[l - 1];
     a.w = cv.w[l - 1];
     a.bias = cv.bias[l - 1];
-    a.taps = cv.taps;
-    a.n_taps = cv.n_taps;
-    a.kmid = kmid;
-    a.out = cv.act[cur ^ 1];
+    a.out = cv.act[l];
     a.N = N;
     a.H = cv.H;
     prof_mark(m, l, false, s);
-#define JM_LAUNCH_CONV(T, FT)                                                                                     \
+#define JM_LAUNCH_CONV(T, FT, KS, WR)                                                                              \
   do {                                                                                                            \
     static size_t configured = 0;                                                                                 \
     if (lds > configured) {                                                                                       \
-      (void)hipFuncSetAttribute((const void*)conv_layer_kernel<T, FT>, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                (int)lds);                                                                        \
+      (void)hipFuncSetAttribute((const void*)conv_layer_kernel<T, FT, KS, WR>,                                    \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                            \
       configured = lds;                                                                                           \
     }                                                                                                             \
-    hipLaunchKernelGGL((conv_layer_kernel<T, FT>), dim3(grid), dim3(256), lds, s, a);                             \
+    hipLaunchKernelGGL((conv_layer_kernel<T, FT, KS, WR>), dim3(grid), dim3(256), lds, s, a);                     \
+  } while (0)
+#define JM_CONV_ROWS(T, FT, KS) do { if (wg_rows == 4) JM_LAUNCH_CONV(T, FT, KS, 4); else JM_LAUNCH_CONV(T, FT, KS, 2); } while (0)
+#define JM_CONV_K(T, FT)                                                                                           \
+  do {                                                                                                            \
+    if (cv.k == 3) JM_CONV_ROWS(T, FT, 3); else if (cv.k == 5) JM_CONV_ROWS(T, FT, 5); else JM_CONV_ROWS(T, FT, 7); \
   } while (0)
     if (m->dtype == MADE_BF16) {
-      if (ft == 4) JM_LAUNCH_CONV(bf16_t, 4); else JM_LAUNCH_CONV(bf16_t, 2);
+      if (ft == 4) JM_CONV_K(bf16_t, 4); else JM_CONV_K(bf16_t, 2);
     } else {
-      if (ft == 4) JM_LAUNCH_CONV(float, 4); else JM_LAUNCH_CONV(float, 2);
+      if (ft == 4) JM_CONV_K(float, 4); else JM_CONV_K(float, 2);
     }
+#undef JM_CONV_K
+#undef JM_CONV_ROWS
 #undef JM_LAUNCH_CONV
     prof_mark(m, l, true, s);
     m->stats[2]++;
-    cur ^= 1;
   }
-  *last_act = cv.act[cur];
+  *last_act = cv.act[cv.n_conv - 1];
 }
 
-static int run_conv_pass(made_model* m, int N, const SampleIO& io, hipStream_t s) {
+static int run_conv_pass(made_model* m, int N, const SampleIO& io, bool first_pass, bool whole_network,
+                         hipStream_t s) {
   ConvNet& cv = m->conv;
   const void* last = nullptr;
-  launch_conv_trunk(m, io.x, N, s, &last);
+  const int row_lo = io.t_lo / (32 * 3), row_hi = (io.t_hi - 1) / (32 * 3);   // rows holding the states drawn
+  int* dirty_lo = whole_network ? nullptr : cv.win;
+  launch_conv_trunk(m, io.x, N, dirty_lo, whole_network ? cv.H - 1 : row_hi, s, &last);
   CatArgs c;
   memset(&c, 0, sizeof c);
   c.A = last;
@@ -967,6 +999,17 @@ static int run_conv_pass(made_model* m, int N, const SampleIO& io, hipStream_t s
   c.rows_per_image = cv.H * 32;
   c.state_lo = io.t_lo;
   c.state_hi = io.t_hi;
+  if (!whole_network) {
+    c.dirty_lo = cv.win;
+    c.first_changed = cv.win + cv.win_pad;
+    c.win_done = cv.win + 2 * cv.win_pad;
+    c.rows_stat = cv.rows_stat;
+    c.row_lo = row_lo;
+    c.row_hi = row_hi;
+    c.first_pass = first_pass ? 1 : 0;
+    c.n_images = N;
+    c.img_rows = cv.H;
+  }
   c.retire = io.retire;
   prof_mark(m, m->L, false, s);
   if (m->dtype == MADE_BF16)
@@ -983,7 +1026,13 @@ static int launch_init_state(made_model* m, const uint8_t* x_init, uint8_t* x, i
   const size_t total = (size_t)N * m->D;
   const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
   if (m->arch == 1) {   // the first convolution reads the symbols themselves
-    if (x) hipLaunchKernelGGL(copy_symbols_kernel, dim3(blocks), dim3(256), 0, s, x_init, x, total);
+    if (x) {
+      ConvNet& cv = m->conv;
+      hipLaunchKernelGGL(copy_symbols_kernel, dim3(blocks), dim3(256), 0, s, x_init, x, total);
+      hipLaunchKernelGGL(conv_reset_window_kernel, dim3((N + 255) / 256), dim3(256), 0, s, cv.win,
+                         cv.win + cv.win_pad, N, cv.win + 2 * cv.win_pad, cv.rows_stat);
+      m->stats[2]++;
+    }
     m->stats[2]++;
     HIP_TRY(hipGetLastError());
     return MADE_OK;
@@ -1020,7 +1069,7 @@ extern "C" int made_forward_logits(made_model* m, const uint8_t* x, int32_t N, f
   TRY(ensure_workspace(m, N, false));
   if (m->arch == 1) {
     const void* last = nullptr;
-    launch_conv_trunk(m, x, N, s, &last);
+    launch_conv_trunk(m, x, N, nullptr, m->conv.H - 1, s, &last);
     // the 1 x 1 head is a plain layer over pixels: logits[pixel][colour * 256 + class]
     ConvNet& cv = m->conv;
     LayerArgs a;
@@ -1125,7 +1174,7 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
     rs = RowSet{c.rows[0], nullptr, c.count};   // no stop test: every sample of the chain takes the pass
   }
   if (m->arch == 1) {
-    TRY(run_conv_pass(m, c.count, io, s));
+    TRY(run_conv_pass(m, c.count, io, k == 1, blk.whole_network, s));
   } else {
     TRY(run_hidden(m, rs, blk.limited ? blk.hidden_limit.data() : nullptr, blk.in_limit, s));
     TRY(run_output_sample(m, rs, io, blk.whole_network, blk.out_k_limit, s));
@@ -1221,7 +1270,14 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
   }
   if (iters_out) HIP_TRY(hipMemcpyAsync(iters_out, w.iters, (size_t)N * sizeof(int), hipMemcpyDeviceToDevice, s));
   HIP_TRY(hipMemcpyAsync((void*)&w.h_pin[0], w.flags, sizeof(int), hipMemcpyDeviceToHost, s));
+  if (m->arch == 1)
+    HIP_TRY(hipMemcpyAsync((void*)&w.h_pin[2], m->conv.rows_stat, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipStreamSynchronize(s));
+  if (m->arch == 1) {
+    unsigned long long rows = 0;
+    memcpy(&rows, (const void*)&w.h_pin[2], sizeof rows);
+    m->stats[4] = (int64_t)rows;
+  }
   m->stats[3]++;
   prof_collect(m);
   // statistics from the chains' pass logs (complete now that everything has run)

@@ -928,6 +928,16 @@ struct CatArgs {
   // (pixel within its image) * 3 + colour in [state_lo, state_hi) instead of the t_lo / t_hi test.
   int rows_per_image;
   int state_lo, state_hi;
+  // Row window of the convolutional model (see ConvWindow); first_changed == NULL switches it off.  The head
+  // re-draws rows max(row_lo, dirty_lo[n]) .. row_hi (row_lo .. row_hi in the first pass of a block: its states
+  // have not been drawn against their final context yet); rows above have unchanged logits.  Every changed
+  // state lowers first_changed[image] to its row, and the last workgroup of the launch then sets
+  // dirty_lo[n] = min(first changed row, max(dirty_lo[n], row_hi + 1)) for the next pass.
+  int* dirty_lo;
+  int* first_changed;
+  int* win_done;                    // counter of finished workgroups (window tail)
+  unsigned long long* rows_stat;    // statistics: sum over passes and images of trunk rows recomputed
+  int row_lo, row_hi, first_pass, n_images, img_rows;
   RetireArgs retire;
 };
 
@@ -976,7 +986,20 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
   const int pos_i = blockIdx.x / a.pair_tiles, pair = blockIdx.x % a.pair_tiles;
   const int t = a.t_begin + a.n_pos - 1 - pos_i;
   const int row0 = pair * 64;
-  if (row0 < n_rows) {   // (uniform per workgroup)
+  bool active = true;
+  if (a.first_changed) {   // windowed pass of the convolutional model: two image rows per workgroup
+    active = false;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int g = pair * 2 + j;
+      if (g * 32 < n_rows) {
+        const int n = g / a.img_rows, y = g % a.img_rows;
+        const int lo = a.first_pass ? a.row_lo : max(a.row_lo, a.dirty_lo[n]);
+        active = active || (y >= lo && y <= a.row_hi);
+      }
+    }
+  }
+  if (row0 < n_rows && active) {   // (uniform per workgroup)
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, h = lane >> 5;
     const bool two = row0 + 32 < n_rows;
@@ -1094,13 +1117,54 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
         const int hi = min((img + 1) * a.rows_per_image - row0, 64);
         const unsigned long long mask = (hi >= 64 ? ~0ull : ((1ull << hi) - 1)) & ~((1ull << lo) - 1);
         const int cnt = __popcll(m & mask);
-        if (sl == lo && cnt > 0) count_changed(&a.changed[img], cnt);
+        if (sl == lo && cnt > 0) {
+          count_changed(&a.changed[img], cnt);
+          if (a.first_changed) {
+            const int pix = row0 + __builtin_ctzll(m & mask);          // lowest changed pixel of this image
+            const int old = __hip_atomic_fetch_min(&a.first_changed[img], (pix % a.rows_per_image) >> 5,
+                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            asm volatile("" ::"v"(old));                                // (performed before the tail counters)
+          }
+        }
       } else if (differs) {
         count_changed(&a.changed[sample], 1);
       }
     }
   }
+  if (a.first_changed) {   // window tail: the last workgroup to arrive updates the images' dirty rows
+    __shared__ int win_last_s;
+    __syncthreads();
+    if (threadIdx.x == 0)
+      win_last_s = (__hip_atomic_fetch_add(a.win_done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                    (int)gridDim.x - 1);
+    __syncthreads();
+    if (win_last_s) {
+      unsigned long long rows = 0;
+      for (int n = threadIdx.x; n < a.n_images; n += blockDim.x) {
+        const int fc = __hip_atomic_load(&a.first_changed[n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        a.first_changed[n] = 0x7fffffff;
+        const int d = a.dirty_lo[n];
+        rows += (unsigned long long)max(0, a.row_hi - d + 1);
+        a.dirty_lo[n] = min(fc, max(d, a.row_hi + 1));
+      }
+      if (rows) atomicAdd(a.rows_stat, rows);
+      if (threadIdx.x == 0) *a.win_done = 0;
+    }
+  }
   if (a.retire.enabled) finish_pass(a.retire, gridDim.x);
+}
+
+__global__ void conv_reset_window_kernel(int* dirty_lo, int* first_changed, int n, int* win_done,
+                                         unsigned long long* rows_stat) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) {
+    dirty_lo[i] = 0;
+    first_changed[i] = 0x7fffffff;
+  }
+  if (i == 0) {
+    *win_done = 0;
+    *rows_stat = 0;
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1110,156 +1174,279 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
 constexpr int CONV_MAX_K = 7;
 constexpr int CONV_ROWS = 4;             // image rows per workgroup of the k x k layers
 
+// Row window of a pass over the convolutional network.  The activations of every layer persist between passes
+// (one buffer per layer).  A state only depends on pixels above it and to its left, so as long as no symbol of
+// rows < d changed since they were computed, the activation rows < d of every layer are still those of the
+// current symbols: a pass only has to recompute rows d .. row_hi, where row_hi is the last row whose logits it
+// needs.  dirty_lo[n] holds d for image n and is maintained by the tail of the sampling kernel.
+struct ConvWindow {
+  const int* dirty_lo;   // NULL: recompute every row up to row_hi
+  int row_hi;
+};
+__device__ __forceinline__ bool conv_rows_active(const ConvWindow& w, int n, int y0, int rows) {
+  const int lo = w.dirty_lo ? w.dirty_lo[n] : 0;
+  return y0 + rows > lo && y0 <= w.row_hi;
+}
+
 struct ConvFirstArgs {
+  ConvWindow win;
   const uint8_t* x;      // symbols [N, H, 32, 3]
-  const float* w;        // masked fp32 weights [F][n_taps][3] (live taps only)
+  const float* w;        // masked fp32 weights [F][n_taps][3]: visible taps in row-major order, the centre last
   const float* bias;     // [F]
-  const int* taps;       // [n_taps][2] = (dy, dx), dy <= 0
-  int n_taps;
   void* out;             // activations, fragment-major, out_chunks chunks
   int out_chunks;
-  int N, H, F;
+  int N, H;
 };
 
-// First layer (3 input channels, type A).  One workgroup per row of pixels; thread (pixel x, slice q) computes
-// F/8 consecutive channels of its pixel from the <= 3 * n_taps visible inputs, in fp32.  FT = F / 32.
-template <typename T, int FT>
-__global__ __launch_bounds__(256) void conv_first_kernel(ConvFirstArgs a) {
+// First layer (3 input colours, type A), in fp32 FMAs.  A workgroup owns two rows of pixels (64 lanes = 64
+// pixels); wave q of its 8 waves computes channels q*F/8 .. of every pixel.  A wave's weights are the same for
+// all its lanes, so they come through the scalar unit (read only) and every FMA takes its weight from an
+// SGPR; a lane holds its <= 3 * n_taps visible inputs in registers.  FT = F / 32, KS = kernel size.
+template <typename T, int FT, int KS>
+__global__ __launch_bounds__(512) void conv_first_kernel(ConvFirstArgs a) {
+  constexpr int MID = KS / 2, NT = MID * KS + MID + 1;
   constexpr int P = 16 / (int)sizeof(T);
-  constexpr int PER = FT * 4;                // channels per thread (F / 8), a multiple of P
-  const int g = blockIdx.x;                  // group = (n, y)
-  const int n = g / a.H, y = g % a.H;
-  const int px = threadIdx.x & 31, q = threadIdx.x >> 5;
-  float acc[PER];
-#pragma unroll
-  for (int i = 0; i < PER; ++i) acc[i] = a.bias[q * PER + i];
-  for (int t = 0; t < a.n_taps; ++t) {
-    const int yy = y + a.taps[2 * t], xx = px + a.taps[2 * t + 1];
+  constexpr int PER = FT * 4;                // channels per wave (F / 8), a multiple of P
+  const int lane = threadIdx.x & 63, q = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int g = 2 * blockIdx.x + (lane >> 5), px = lane & 31;      // group = row of pixels (n, y)
+  const bool in_batch = g < a.N * a.H;
+  const int gl = in_batch ? g : 0;
+  const int n = gl / a.H, y = gl % a.H;
+  const bool live = in_batch && conv_rows_active(a.win, n, y, 1);
+  if (__ballot(live) == 0) return;
+  float in[NT][3];
+  static_for<NT>([&](auto TT) {
+    constexpr int t = decltype(TT)::value;
+    constexpr int dy = t / KS - MID, dx = t % KS - MID;            // (tap index = (dy + MID) * KS + dx + MID)
+    const int yy = y + dy, xx = px + dx;
     const bool ok = yy >= 0 && xx >= 0 && xx < 32;
+    // (the address is clamped, so the loads need no branch and all of them are in flight together)
     const uint8_t* p = a.x + (((size_t)n * a.H + (ok ? yy : 0)) * 32 + (ok ? xx : 0)) * 3;
-    float in[3];
+    const uint8_t v0 = p[0], v1 = p[1], v2 = p[2];
+    in[t][0] = ok ? ((float)v0 - 128.0f) * (1.0f / 128.0f) : 0.f;
+    in[t][1] = ok ? ((float)v1 - 128.0f) * (1.0f / 128.0f) : 0.f;
+    in[t][2] = ok ? ((float)v2 - 128.0f) * (1.0f / 128.0f) : 0.f;
+  });
+  float acc[PER];
+  static_for<PER>([&](auto II) {
+    constexpr int i = decltype(II)::value;
+    const float* w = a.w + (size_t)(q * PER + i) * NT * 3;         // (uniform over the wave)
+    float s = a.bias[q * PER + i];
 #pragma unroll
-    for (int c = 0; c < 3; ++c) in[c] = ok ? ((float)p[c] - 128.0f) * (1.0f / 128.0f) : 0.f;
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const float* w = a.w + ((size_t)(q * PER + i) * a.n_taps + t) * 3;
-      acc[i] += w[0] * in[0] + w[1] * in[1] + w[2] * in[2];
-    }
+      for (int c = 0; c < 3; ++c) s += w[t * 3 + c] * in[t][c];
+    acc[i] = s;
+  });
+  if (live) {
+#pragma unroll
+    for (int g8 = 0; g8 < PER / P; ++g8)
+      *(uint4*)((T*)a.out + frag_offset<T>(g * 32 + px, q * PER + g8 * P, a.out_chunks)) = Elem<T>::relu_piece(acc + g8 * P);
   }
-#pragma unroll
-  for (int g8 = 0; g8 < PER / P; ++g8)
-    *(uint4*)((T*)a.out + frag_offset<T>(g * 32 + px, q * PER + g8 * P, a.out_chunks)) = Elem<T>::relu_piece(acc + g8 * P);
 }
 
 struct ConvLayerArgs {
+  ConvWindow win;
   const void* in;        // activations of the previous layer (fragment-major, F channels)
   const void* w;         // masked weights as a [F x (n_taps * F)] matrix, tap-major K, fragment-major
   const float* bias;
-  const int* taps;       // [n_taps][2] = (dy, dx) with dy <= 0
-  int n_taps;
-  int kmid;              // (k - 1) / 2: rows of halo above the workgroup's rows
   void* out;
   int N, H;
 };
 
-// k x k masked convolution F -> F as an implicit GEMM.  A workgroup owns CONV_ROWS image rows (128 pixels) of
-// one image and all F output channels.  The input rows it needs (its own and kmid rows above; taps below are
-// masked out) are copied into LDS once, in fragment order; a tap (dy, dx) then is the same LDS block read with
-// a row offset and a lane shift (lanes shifted out of the image read zero).  Weights stream from L2 straight
-// into registers, one visible tap and K chunk at a time, prefetched one step ahead.  FT = F / 32.
-template <typename T, int FT>
+// k x k masked convolution F -> F as an implicit GEMM over the visible taps (rows above, and the same row up
+// to the centre).  A workgroup owns WG_ROWS image rows of one image and all F output channels; a wave owns one
+// 32-channel tile and RW of those rows (4 waves: F = 128 -> RW = WG_ROWS, F = 64 -> RW = WG_ROWS / 2).
+//
+// The input rows the workgroup needs (its own and MID = (k-1)/2 rows above; taps below are masked out) are
+// copied to LDS once, each 32-pixel run padded with MID zero entries on both sides, so the operand of tap
+// (dy, dx) is the same LDS data read at a row offset and an entry offset: no im2col buffer, no lane masks.
+// The loop runs over (dx, K chunk).  For one such step the weights of all visible dy (2 or 3 fragments of
+// 32 channels x 128 B) sit in registers while the wave walks down its RW + MID input rows: every input
+// fragment read from LDS feeds up to MID + 1 output rows (dy = input row - output row), which halves the LDS
+// traffic per MFMA, and a step is long enough (up to 12 x 4 MFMAs) to cover the L2 latency of the next
+// step's weights, which are requested at its start.
+template <typename T, int FT, int KS, int WG_ROWS>
 __global__ __launch_bounds__(256) void conv_layer_kernel(ConvLayerArgs a) {
+  constexpr int MID = KS / 2;
+  constexpr int NDY = MID + 1;
   constexpr int KCH = FT * 32 / (2 * Elem<T>::EPL);     // K chunks per tap (= chunks per activation row group)
-  constexpr int CT = FT / 2;                            // output channel tiles per wave
-  constexpr int ROWBLK = KCH * 256;                     // uint4 per image row in LDS
-  extern __shared__ uint4 conv_lds[];                   // [(CONV_ROWS + kmid) rows][ROWBLK]
-  const int tiles_y = (a.H + CONV_ROWS - 1) / CONV_ROWS;
-  const int n = blockIdx.x / tiles_y, y0 = (blockIdx.x % tiles_y) * CONV_ROWS;
+  constexpr int ROW_SPLIT = 4 / FT;                     // waves along the rows
+  constexpr int RW = WG_ROWS / ROW_SPLIT;               // output rows per wave
+  static_assert(RW >= 1 && RW * ROW_SPLIT == WG_ROWS, "rows must divide among the waves");
+  constexpr int PADW = 32 + 2 * MID;                    // entries per padded 32-pixel run
+  constexpr int ROWBLK = KCH * 8 * PADW;                // uint4 per image row in LDS
+  constexpr int LDS_ROWS = WG_ROWS + MID;
+  extern __shared__ uint4 conv_lds[];                   // [LDS_ROWS][KCH][slot*2 + half][PADW]
+  const int tiles_y = (a.H + WG_ROWS - 1) / WG_ROWS;
+  const int n = blockIdx.x / tiles_y, y0 = (blockIdx.x % tiles_y) * WG_ROWS;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 31, h = lane >> 5;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int lds_rows = CONV_ROWS + a.kmid;
+  const int ct = wave % FT;                             // channel tile of this wave
+  const int wrow = (wave / FT) * RW;                    // its first output row within the workgroup's rows
+  if (!conv_rows_active(a.win, n, y0, WG_ROWS)) return; // (uniform over the workgroup)
 
-  // input rows y0 - kmid .. y0 + CONV_ROWS - 1 -> LDS (rows outside the image are zero)
-  for (int e = tid; e < lds_rows * ROWBLK; e += 256) {
-    const int lr = e / ROWBLK, off = e % ROWBLK;
-    const int y = y0 - a.kmid + lr;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (y >= 0 && y < a.H) v = ((const uint4*)a.in)[((size_t)n * a.H + y) * ROWBLK + off];
-    conv_lds[e] = v;
+  // weights: row group = output channel tile, chunk index = tap * KCH + c, tap = (dy + MID) * KS + (dx + MID)
+  const size_t wgroup = (size_t)(MID * KS + MID + 1) * KCH * 256;
+  const uint4* Wp = (const uint4*)a.w + (size_t)ct * wgroup + h * 32 + r;
+  uint4 wc[NDY][4], wn[NDY][4];
+  auto load_weights = [&](int it, uint4 (&dst)[NDY][4]) {
+    const int dxi = it / KCH, c = it - dxi * KCH;
+    static_for<NDY>([&](auto D) {
+      constexpr int dyi = decltype(D)::value;
+      // (dy = 0 is invisible right of the centre: the slot then re-reads the row above and is not used)
+      const int dy_used = (dyi == MID && dxi > MID) ? MID - 1 : dyi;
+      const uint4* p = Wp + (size_t)((dy_used * KS + dxi) * KCH + c) * 256;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) dst[dyi][s] = p[s * 64];
+    });
+  };
+  // Steps (dx, chunk) come in two runs: dx <= 0 (MID + 1 visible dy each) and dx > 0 (MID visible dy), each a
+  // loop with a single straight-line body.  Within a run the workgroups start at different steps: all of them
+  // read the same few hundred KB of weights, and in lock-step they would all ask the same L2 channel for the
+  // same lines at the same time.
+  constexpr int N_A = (MID + 1) * KCH, N_B = MID * KCH, N_IT = N_A + N_B;
+  const int rot_a = (int)(blockIdx.x % N_A), rot_b = (int)(blockIdx.x % N_B);
+  auto step_of = [&](int p) {               // p-th step of this workgroup -> it = dxi * KCH + c
+    if (p >= N_IT) p = 0;                   // (prefetch past the end: any valid step)
+    if (p < N_A) { const int q = p + rot_a; return q < N_A ? q : q - N_A; }
+    const int q = p - N_A + rot_b;
+    return N_A + (q < N_B ? q : q - N_B);
+  };
+  // entry of pixel r + dx in the padded run of (input row wrow + j, chunk c, slot s, half h)
+  auto frag_ptr = [&](int it) {
+    const int dxi = it / KCH, c = it - dxi * KCH;
+    return conv_lds + ((size_t)(wrow * KCH + c) * 8 + h) * PADW + r + dxi;
+  };
+  JM_TSTAMP(0, 0);
+  load_weights(step_of(0), wc);
+  // the epilogue's lane = (pixel lane >> 1, 16 channels); its bias values are requested now
+  const int rr = lane >> 1, c16 = (lane & 1) * 16;
+  const int ch0 = ct * TILE + c16;
+  float4 bias4[4];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) bias4[g] = *(const float4*)(a.bias + ch0 + 4 * g);
+
+  // input rows y0 - MID .. y0 + WG_ROWS - 1 -> LDS (rows outside the image and the pads are zero); the loads of
+  // a batch are all issued before the first store so that their latencies overlap
+  constexpr int FILL = LDS_ROWS * KCH;                  // 16-byte pieces per thread
+  constexpr int FILL_BATCH = FILL < 12 ? FILL : 12;
+  static_for<(FILL + FILL_BATCH - 1) / FILL_BATCH>([&](auto B) {
+    constexpr int b0 = decltype(B)::value * FILL_BATCH;
+    constexpr int cnt = FILL - b0 < FILL_BATCH ? FILL - b0 : FILL_BATCH;
+    uint4 v[cnt];
+#pragma unroll
+    for (int i = 0; i < cnt; ++i) {
+      const int e = tid + (b0 + i) * 256;
+      const int lr = e / (KCH * 256), off = e % (KCH * 256);     // off = (c*8 + slot*2 + half)*32 + pixel
+      const int y = y0 - MID + lr;
+      const bool ok = y >= 0 && y < a.H;                          // (clamped address: a load without a branch)
+      v[i] = ((const uint4*)a.in)[((size_t)n * a.H + (ok ? y : 0)) * (KCH * 256) + off];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < cnt; ++i) {
+      const int e = tid + (b0 + i) * 256;
+      const int lr = e / (KCH * 256), off = e % (KCH * 256);
+      const int y = y0 - MID + lr;
+      const uint32_t keep = (y >= 0 && y < a.H) ? 0xffffffffu : 0u;
+      conv_lds[(lr * KCH * 8 + (off >> 5)) * PADW + MID + (off & 31)] =
+          make_uint4(v[i].x & keep, v[i].y & keep, v[i].z & keep, v[i].w & keep);
+    }
+  });
+  for (int e = tid; e < LDS_ROWS * KCH * 8 * 2 * MID; e += 256) {
+    const int run = e / (2 * MID), q = e % (2 * MID);
+    conv_lds[run * PADW + (q < MID ? q : 32 + q)] = make_uint4(0, 0, 0, 0);
   }
   __syncthreads();
+  JM_TSTAMP(1, 0);
 
-  f32x16 acc[2][CT];
+  f32x16 acc[RW];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int o = 0; o < RW; ++o)
 #pragma unroll
-    for (int j = 0; j < CT; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    for (int e = 0; e < 16; ++e) acc[o][e] = 0.f;
 
-  // weights: row group = output channel tile, chunk index = tap * KCH + c
-  const size_t wgroup = (size_t)a.n_taps * KCH * 256;
-  const uint4* Wp = (const uint4*)a.w + (size_t)(wn * CT) * wgroup + h * 32 + r;
-  const int n_steps = a.n_taps * KCH;
-  uint4 wcur[CT][4], wnext[CT][4];
+  // The first PRE input fragments of a step are read from LDS during the step before it, so that the MFMAs
+  // of a step do not start behind a burst of LDS reads of all four waves.
+  constexpr int NJ = RW + MID;                          // input rows a wave walks per step
+  constexpr int PRE = NJ < 2 ? NJ : 2;
+  uint4 pre[PRE][4];
+  {
+    const uint4* base = frag_ptr(step_of(0));
 #pragma unroll
-  for (int j = 0; j < CT; ++j)
+    for (int j = 0; j < PRE; ++j)
 #pragma unroll
-    for (int s = 0; s < 4; ++s) wcur[j][s] = Wp[(size_t)j * wgroup + s * 64];
-  for (int step = 0; step < n_steps; ++step) {
-    const int nxt = min(step + 1, n_steps - 1);          // (the last step re-reads itself: no branch)
-#pragma unroll
-    for (int j = 0; j < CT; ++j)
-#pragma unroll
-      for (int s = 0; s < 4; ++s) wnext[j][s] = Wp[(size_t)j * wgroup + (size_t)nxt * 256 + s * 64];
-    const int tap = step / KCH, c = step % KCH;
-    const int dy = a.taps[2 * tap], dx = a.taps[2 * tap + 1];
-    const int xs = r + dx;
-    const bool x_ok = xs >= 0 && xs < 32;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int lr = wm * 2 + i + a.kmid + dy;            // LDS row holding image row y0 + 2*wm + i + dy
-      const uint4* row = conv_lds + (size_t)lr * ROWBLK + c * 256 + h * 32 + (x_ok ? xs : r);
-      uint4 af[4];
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        af[s] = row[s * 64];
-        if (!x_ok) af[s] = make_uint4(0, 0, 0, 0);
-      }
-#pragma unroll
-      for (int j = 0; j < CT; ++j) mfma_chunk<T>(af, wcur[j], acc[i][j]);
-    }
-#pragma unroll
-    for (int j = 0; j < CT; ++j)
-#pragma unroll
-      for (int s = 0; s < 4; ++s) wcur[j][s] = wnext[j][s];
+      for (int s = 0; s < 4; ++s) pre[j][s] = base[(size_t)j * ROWBLK + s * 2 * PADW];
   }
-  __syncthreads();                                        // the input tile is no longer needed
+  auto run_steps = [&](auto NV, int p_begin, int p_end) {
+    constexpr int n_visible = decltype(NV)::value;             // visible dy of these steps
+    for (int p = p_begin; p < p_end; ++p) {
+      const int it_next = step_of(p + 1);
+      load_weights(it_next, wn);
+      const uint4* base = frag_ptr(step_of(p));
+      const uint4* base_next = frag_ptr(it_next);
+      uint4 af[NJ][4];
+#pragma unroll
+      for (int j = 0; j < PRE; ++j)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) af[j][s] = pre[j][s];
+#pragma unroll
+      for (int j = PRE; j < NJ; ++j)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) af[j][s] = base[(size_t)j * ROWBLK + s * 2 * PADW];
+      // (the scheduler otherwise sinks every load to just before its first use, to save registers, and the
+      // wave then waits out each L2 and LDS latency in turn)
+      __builtin_amdgcn_sched_barrier(0);
+      static_for<NJ>([&](auto J) {
+        constexpr int j = decltype(J)::value;                  // input row y0 + wrow - MID + j
+        if constexpr (j == (NJ > 2 ? NJ - 2 : 0)) {
+#pragma unroll
+          for (int jj = 0; jj < PRE; ++jj)
+#pragma unroll
+            for (int s = 0; s < 4; ++s) pre[jj][s] = base_next[(size_t)jj * ROWBLK + s * 2 * PADW];
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        static_for<n_visible>([&](auto D) {
+          constexpr int dyi = decltype(D)::value;              // dy = dyi - MID; output row o = j - dyi
+          constexpr int o = j - dyi;
+          if constexpr (o >= 0 && o < RW) mfma_chunk<T>(af[j], wc[dyi], acc[o]);
+        });
+      });
+#pragma unroll
+      for (int d = 0; d < NDY; ++d)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) wc[d][s] = wn[d][s];
+      if (p == 0) JM_TSTAMP(2, 0);
+      if (p == 4) JM_TSTAMP(3, 0);
+    }
+  };
+  run_steps(std::integral_constant<int, NDY>{}, 0, N_A);
+  run_steps(std::integral_constant<int, MID>{}, N_A, N_IT);
+  JM_TSTAMP(4, 0);
+  __syncthreads();                                        // the input rows are no longer needed
 
   // epilogue through a wave-private LDS patch: lane = (pixel lane >> 1, 16 channels), 16-byte stores
   constexpr int P = 16 / (int)sizeof(T);
   float (*patch)[TILE + 1] = (float (*)[TILE + 1])((char*)conv_lds + wave * (TILE * (TILE + 1) * 4));
-  const int rr = lane >> 1, c16 = (lane & 1) * 16;
-  static_for<2>([&](auto I) {
-    constexpr int i = decltype(I)::value;
-    const int y = y0 + wm * 2 + i;
-    static_for<CT>([&](auto J) {
-      constexpr int j = decltype(J)::value;
+  const float bias[16] = {bias4[0].x, bias4[0].y, bias4[0].z, bias4[0].w, bias4[1].x, bias4[1].y, bias4[1].z, bias4[1].w,
+                          bias4[2].x, bias4[2].y, bias4[2].z, bias4[2].w, bias4[3].x, bias4[3].y, bias4[3].z, bias4[3].w};
+  static_for<RW>([&](auto O) {
+    constexpr int o = decltype(O)::value;
+    const int y = y0 + wrow + o;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) patch[8 * (e >> 2) + 4 * h + (e & 3)][r] = acc[i][j][e];
-      const int ch0 = (wn * CT + j) * TILE + c16;
-      float v[16];
+    for (int e = 0; e < 16; ++e) patch[8 * (e >> 2) + 4 * h + (e & 3)][r] = acc[o][e];
+    float v[16];
 #pragma unroll
-      for (int cc = 0; cc < 16; ++cc) v[cc] = patch[rr][c16 + cc] + a.bias[ch0 + cc];
-      if (y < a.H) {
-        const int pixel = ((n * a.H) + y) * 32 + rr;
+    for (int cc = 0; cc < 16; ++cc) v[cc] = patch[rr][c16 + cc] + bias[cc];
+    if (y < a.H) {
+      const int pixel = ((n * a.H) + y) * 32 + rr;
 #pragma unroll
-        for (int g = 0; g < 16 / P; ++g)
-          *(uint4*)((T*)a.out + frag_offset<T>(pixel, ch0 + g * P, KCH)) = Elem<T>::relu_piece(v + g * P);
-      }
-    });
+      for (int g = 0; g < 16 / P; ++g)
+        *(uint4*)((T*)a.out + frag_offset<T>(pixel, ch0 + g * P, KCH)) = Elem<T>::relu_piece(v + g * P);
+    }
   });
+  JM_TSTAMP(5, 1);
 }
 
 __global__ void copy_symbols_kernel(const uint8_t* x_init, uint8_t* x, size_t total) {
