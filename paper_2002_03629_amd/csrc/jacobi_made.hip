@@ -125,7 +125,7 @@ struct ConvNet {
   int H = 0, F = 0, k = 0, n_conv = 0, n_taps = 0;
   int wg_rows = 4;                   // image rows per workgroup of the k x k layers: made_set_option(MADE_OPT_CONV_ROWS)
   int* taps = nullptr;               // device [n_taps][2] visible taps (dy, dx), the centre tap last
-  float* w0 = nullptr;               // first layer, masked fp32 [F][n_taps][3]
+  void* w0 = nullptr;                // first layer, masked [F x K0] (K = tap * 3 + colour), fragment-major
   float* b0 = nullptr;
   std::vector<void*> w;              // layers 1 .. n_conv-1: [F x n_taps*F] tap-major K, fragment-major
   std::vector<float*> bias;
@@ -600,19 +600,27 @@ extern "C" int made_conv_init(const made_conv_config* cfg, const float* const* W
   int rc = MADE_OK;
   try {
     e = upload(&cv.taps, taps);
-    // first layer: fp32 [F][n_taps][3]; centre tap: colour c visible iff c < group(f)
-    std::vector<float> w0((size_t)F * cv.n_taps * 3, 0.f), b0(F, 0.f);
+    // first layer: [F x K0] with K index = tap * 3 + colour, fragment-major; centre tap: colour c visible iff
+    // c < group(f)
+    const int k0_chunks = (cv.n_taps * 3 + kc - 1) / kc;
+    std::vector<uint8_t> w0((size_t)F * k0_chunks * kc * elem_size(m), 0);
+    std::vector<float> b0(F, 0.f);
     int64_t nnz0 = 0;
     for (int f = 0; f < F; ++f)
       for (int t = 0; t < cv.n_taps; ++t)
         for (int c = 0; c < 3; ++c) {
           const bool centre = t == cv.n_taps - 1;
           if (centre && !(c < grp[f])) continue;
-          w0[((size_t)f * cv.n_taps + t) * 3 + c] = W[0][((size_t)f * k * k + tap_kykx[t]) * 3 + c];
+          const float v = W[0][((size_t)f * k * k + tap_kykx[t]) * 3 + c];
+          const size_t off = m->dtype == MADE_BF16 ? frag_offset<bf16_t>(f, t * 3 + c, k0_chunks)
+                                                   : frag_offset<float>(f, t * 3 + c, k0_chunks);
+          if (m->dtype == MADE_BF16) ((uint16_t*)w0.data())[off] = host_f32_to_bf16(v);
+          else ((float*)w0.data())[off] = v;
           nnz0++;
         }
     if (b && b[0]) b0.assign(b[0], b[0] + F);
-    if (e == hipSuccess) e = upload(&cv.w0, w0);
+    if (e == hipSuccess) e = hipMalloc(&cv.w0, w0.size());
+    if (e == hipSuccess) e = hipMemcpy(cv.w0, w0.data(), w0.size(), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = upload(&cv.b0, b0);
     m->nnz.push_back(nnz0 * pixels);
     // layers 1 .. n_conv-1: [F x n_taps*F] with K index = tap * F + input channel; centre tap: in group <= out group
@@ -907,7 +915,7 @@ static void launch_conv_trunk(made_model* m, const uint8_t* x, int N, const int*
   fa.H = cv.H;
   prof_mark(m, 0, false, s);
   {
-    const dim3 grid((N * cv.H + 1) / 2), block(512);
+    const dim3 grid(N * cv.H), block(ft * 64);
 #define JM_FIRST_K(T, FT)                                                                                 \
   do {                                                                                                   \
     if (cv.k == 3) hipLaunchKernelGGL((conv_first_kernel<T, FT, 3>), grid, block, 0, s, fa);             \

@@ -1000,6 +1000,7 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
     }
   }
   if (row0 < n_rows && active) {   // (uniform per workgroup)
+    JM_TSTAMP(0, 0);
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, h = lane >> 5;
     const bool two = row0 + 32 < n_rows;
@@ -1026,6 +1027,7 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
     else
       cat_stream<T, false>(W0, W1, A0, A1, n_chunks, acc);
 
+    JM_TSTAMP(1, 1);
     // acc[q][j][i]: sample row 8*(i/4) + 4*h + i%4 of sample tile j, class (wave*2 + q)*32 + r.
     // A lane's noise loads are then 4-byte reads that 32 lanes make to one 128-byte line (the noise is the
     // larger stream of the convolutional model).  Element m = 16*j + i of a lane is one sample's best value
@@ -1055,6 +1057,7 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
         }
       });
     });
+    JM_TSTAMP(2, 1);
     static_for<5>([&](auto S) {
       constexpr int bit = 16 >> decltype(S)::value;     // lane bit of this step; 2 * bit elements are left
       const bool up = (r & bit) != 0;
@@ -1078,6 +1081,7 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
       sm_idx[wave][slot] = idx[0];
     }
     __syncthreads();
+    JM_TSTAMP(3, 1);
     if (threadIdx.x < 64) {   // (wave 0: one lane per sample row of the pair)
       const int sl = threadIdx.x;
       bool redraw = row0 + sl < n_rows;
@@ -1131,6 +1135,7 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
       }
     }
   }
+  JM_TSTAMP(4, 1);
   if (a.first_changed) {   // window tail: the last workgroup to arrive updates the images' dirty rows
     __shared__ int win_last_s;
     __syncthreads();
@@ -1191,58 +1196,93 @@ __device__ __forceinline__ bool conv_rows_active(const ConvWindow& w, int n, int
 struct ConvFirstArgs {
   ConvWindow win;
   const uint8_t* x;      // symbols [N, H, 32, 3]
-  const float* w;        // masked fp32 weights [F][n_taps][3]: visible taps in row-major order, the centre last
+  const void* w;         // masked weights as a [F x K0] matrix, fragment-major; K index = tap * 3 + colour with the
+                         // visible taps in row-major order (tap = (dy + MID) * KS + dx + MID), zero beyond 3 * n_taps
   const float* bias;     // [F]
   void* out;             // activations, fragment-major, out_chunks chunks
   int out_chunks;
   int N, H;
 };
 
-// First layer (3 input colours, type A), in fp32 FMAs.  A workgroup owns two rows of pixels (64 lanes = 64
-// pixels); wave q of its 8 waves computes channels q*F/8 .. of every pixel.  A wave's weights are the same for
-// all its lanes, so they come through the scalar unit (read only) and every FMA takes its weight from an
-// SGPR; a lane holds its <= 3 * n_taps visible inputs in registers.  FT = F / 32, KS = kernel size.
+// First layer (3 input colours, type A) as a small GEMM on the matrix cores: the inputs (v - 128) / 128 are
+// exact in bf16, so nothing is lost against fp32 FMAs.  A workgroup owns one row of 32 pixels; wave w owns
+// channel tile w (F / 32 waves).  The MID + 1 symbol rows the pixels can see are copied to LDS as bytes (zero
+// padded left and right); within one kernel row the K index tap * 3 + colour runs along consecutive bytes of
+// that copy, so the 32 x K0 operand is built in LDS, in fragment order, with one byte read per element.
 template <typename T, int FT, int KS>
-__global__ __launch_bounds__(512) void conv_first_kernel(ConvFirstArgs a) {
-  constexpr int MID = KS / 2, NT = MID * KS + MID + 1;
-  constexpr int P = 16 / (int)sizeof(T);
-  constexpr int PER = FT * 4;                // channels per wave (F / 8), a multiple of P
-  const int lane = threadIdx.x & 63, q = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int g = 2 * blockIdx.x + (lane >> 5), px = lane & 31;      // group = row of pixels (n, y)
-  const bool in_batch = g < a.N * a.H;
-  const int gl = in_batch ? g : 0;
-  const int n = gl / a.H, y = gl % a.H;
-  const bool live = in_batch && conv_rows_active(a.win, n, y, 1);
-  if (__ballot(live) == 0) return;
-  float in[NT][3];
-  static_for<NT>([&](auto TT) {
-    constexpr int t = decltype(TT)::value;
-    constexpr int dy = t / KS - MID, dx = t % KS - MID;            // (tap index = (dy + MID) * KS + dx + MID)
-    const int yy = y + dy, xx = px + dx;
-    const bool ok = yy >= 0 && xx >= 0 && xx < 32;
-    // (the address is clamped, so the loads need no branch and all of them are in flight together)
-    const uint8_t* p = a.x + (((size_t)n * a.H + (ok ? yy : 0)) * 32 + (ok ? xx : 0)) * 3;
-    const uint8_t v0 = p[0], v1 = p[1], v2 = p[2];
-    in[t][0] = ok ? ((float)v0 - 128.0f) * (1.0f / 128.0f) : 0.f;
-    in[t][1] = ok ? ((float)v1 - 128.0f) * (1.0f / 128.0f) : 0.f;
-    in[t][2] = ok ? ((float)v2 - 128.0f) * (1.0f / 128.0f) : 0.f;
-  });
-  float acc[PER];
-  static_for<PER>([&](auto II) {
-    constexpr int i = decltype(II)::value;
-    const float* w = a.w + (size_t)(q * PER + i) * NT * 3;         // (uniform over the wave)
-    float s = a.bias[q * PER + i];
+__global__ __launch_bounds__(FT * 64) void conv_first_kernel(ConvFirstArgs a) {
+  constexpr int MID = KS / 2, NT = MID * KS + MID + 1, K_LIVE = NT * 3;
+  constexpr int KC = 2 * Elem<T>::EPL, P = 16 / (int)sizeof(T);
+  constexpr int K0_CHUNKS = (K_LIVE + KC - 1) / KC, K0 = K0_CHUNKS * KC;
+  constexpr int ROWB = (32 + 2 * MID) * 3;          // bytes per padded symbol row
+  constexpr int NTHREADS = FT * 64;
+  __shared__ uint8_t xt[(MID + 1) * ROWB + 16];
+  __shared__ __align__(16) T a_lds[32 * K0];        // one row group of the operand, fragment-major
+  __shared__ float patch_lds[FT][TILE][TILE + 1];
+  const int g = blockIdx.x;                         // group = row of pixels (n, y)
+  const int n = g / a.H, y = g % a.H;
+  if (!conv_rows_active(a.win, n, y, 1)) return;    // (uniform over the workgroup)
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r = lane & 31, h = lane >> 5;
+
+  // this wave's weights: K0_CHUNKS chunks of channel tile `wave`
+  const uint4* Wp = (const uint4*)a.w + (size_t)wave * K0_CHUNKS * 256 + h * 32 + r;
+  uint4 wf[K0_CHUNKS][4];
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+  for (int c = 0; c < K0_CHUNKS; ++c)
 #pragma unroll
-      for (int c = 0; c < 3; ++c) s += w[t * 3 + c] * in[t][c];
-    acc[i] = s;
-  });
-  if (live) {
+    for (int s = 0; s < 4; ++s) wf[c][s] = Wp[(size_t)c * 256 + s * 64];
+  const int rr = lane >> 1, c16 = (lane & 1) * 16;
+  const int ch0 = wave * TILE + c16;
+  float4 bias4[4];
 #pragma unroll
-    for (int g8 = 0; g8 < PER / P; ++g8)
-      *(uint4*)((T*)a.out + frag_offset<T>(g * 32 + px, q * PER + g8 * P, a.out_chunks)) = Elem<T>::relu_piece(acc + g8 * P);
+  for (int q = 0; q < 4; ++q) bias4[q] = *(const float4*)(a.bias + ch0 + 4 * q);
+
+  // symbol rows y - MID .. y with MID pixels of padding on both sides
+  for (int e = tid; e < (MID + 1) * ROWB; e += NTHREADS) {
+    const int row = e / ROWB, col = e % ROWB;       // col = (pixel + MID) * 3 + colour
+    const int yy = y - MID + row, xb = col - 3 * MID;
+    const bool ok = yy >= 0 && xb >= 0 && xb < 96;
+    const uint8_t v = a.x[((size_t)n * a.H + (ok ? yy : 0)) * 96 + (ok ? xb : 0)];
+    xt[e] = ok ? v : (uint8_t)128;                  // 128 encodes the value 0
   }
+  __syncthreads();
+  // operand element (pixel, k): kernel row dyi = k / (3 KS), byte (pixel * 3 + k % (3 KS)) of that padded row
+  for (int e = tid; e < 32 * K0; e += NTHREADS) {
+    const int px = e & 31, k = e >> 5;
+    float v = 0.f;
+    if (k < K_LIVE) {
+      const int dyi = k / (3 * KS), rem = k - dyi * 3 * KS;
+      v = ((float)xt[dyi * ROWB + px * 3 + rem] - 128.0f) * (1.0f / 128.0f);
+    }
+    a_lds[frag_offset<T>(px, k, K0_CHUNKS)] = Elem<T>::from_f32(v);
+  }
+  __syncthreads();
+
+  f32x16 acc;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  const uint4* Ap = (const uint4*)a_lds + h * 32 + r;
+#pragma unroll
+  for (int c = 0; c < K0_CHUNKS; ++c) {
+    uint4 af[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) af[s] = Ap[c * 256 + s * 64];
+    mfma_chunk<T>(af, wf[c], acc);
+  }
+
+  float (*patch)[TILE + 1] = patch_lds[wave];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) patch[8 * (e >> 2) + 4 * h + (e & 3)][r] = acc[e];
+  const float bias[16] = {bias4[0].x, bias4[0].y, bias4[0].z, bias4[0].w, bias4[1].x, bias4[1].y, bias4[1].z, bias4[1].w,
+                          bias4[2].x, bias4[2].y, bias4[2].z, bias4[2].w, bias4[3].x, bias4[3].y, bias4[3].z, bias4[3].w};
+  float v[16];
+#pragma unroll
+  for (int cc = 0; cc < 16; ++cc) v[cc] = patch[rr][c16 + cc] + bias[cc];
+  const int pixel = g * 32 + rr;
+#pragma unroll
+  for (int q = 0; q < 16 / P; ++q)
+    *(uint4*)((T*)a.out + frag_offset<T>(pixel, ch0 + q * P, a.out_chunks)) = Elem<T>::relu_piece(v + q * P);
 }
 
 struct ConvLayerArgs {
@@ -1289,17 +1329,15 @@ __global__ __launch_bounds__(256) void conv_layer_kernel(ConvLayerArgs a) {
   // weights: row group = output channel tile, chunk index = tap * KCH + c, tap = (dy + MID) * KS + (dx + MID)
   const size_t wgroup = (size_t)(MID * KS + MID + 1) * KCH * 256;
   const uint4* Wp = (const uint4*)a.w + (size_t)ct * wgroup + h * 32 + r;
-  uint4 wc[NDY][4], wn[NDY][4];
-  auto load_weights = [&](int it, uint4 (&dst)[NDY][4]) {
+  // Two weight buffers: step p uses buffer p % 2, and as soon as the MFMAs of one dy are issued that dy's
+  // fragment of the buffer is re-requested for step p + 2, so a fragment has close to two steps to arrive.
+  uint4 wbuf[2][NDY][4];
+  auto load_weight_frag = [&](int it, auto D, uint4 (&dst)[4]) {
+    constexpr int dyi = decltype(D)::value;
     const int dxi = it / KCH, c = it - dxi * KCH;
-    static_for<NDY>([&](auto D) {
-      constexpr int dyi = decltype(D)::value;
-      // (dy = 0 is invisible right of the centre: the slot then re-reads the row above and is not used)
-      const int dy_used = (dyi == MID && dxi > MID) ? MID - 1 : dyi;
-      const uint4* p = Wp + (size_t)((dy_used * KS + dxi) * KCH + c) * 256;
+    const uint4* p = Wp + (size_t)((dyi * KS + dxi) * KCH + c) * 256;
 #pragma unroll
-      for (int s = 0; s < 4; ++s) dst[dyi][s] = p[s * 64];
-    });
+    for (int s = 0; s < 4; ++s) dst[s] = p[s * 64];
   };
   // Steps (dx, chunk) come in two runs: dx <= 0 (MID + 1 visible dy each) and dx > 0 (MID visible dy), each a
   // loop with a single straight-line body.  Within a run the workgroups start at different steps: all of them
@@ -1308,7 +1346,6 @@ __global__ __launch_bounds__(256) void conv_layer_kernel(ConvLayerArgs a) {
   constexpr int N_A = (MID + 1) * KCH, N_B = MID * KCH, N_IT = N_A + N_B;
   const int rot_a = (int)(blockIdx.x % N_A), rot_b = (int)(blockIdx.x % N_B);
   auto step_of = [&](int p) {               // p-th step of this workgroup -> it = dxi * KCH + c
-    if (p >= N_IT) p = 0;                   // (prefetch past the end: any valid step)
     if (p < N_A) { const int q = p + rot_a; return q < N_A ? q : q - N_A; }
     const int q = p - N_A + rot_b;
     return N_A + (q < N_B ? q : q - N_B);
@@ -1319,7 +1356,15 @@ __global__ __launch_bounds__(256) void conv_layer_kernel(ConvLayerArgs a) {
     return conv_lds + ((size_t)(wrow * KCH + c) * 8 + h) * PADW + r + dxi;
   };
   JM_TSTAMP(0, 0);
-  load_weights(step_of(0), wc);
+  static_for<2>([&](auto P) {
+    constexpr int p = decltype(P)::value;
+    if constexpr (p < N_IT) {
+      const int it = step_of(p);
+      static_for<NDY>([&](auto D) {
+        if (decltype(D)::value < MID || it < N_A) load_weight_frag(it, D, wbuf[p][decltype(D)::value]);
+      });
+    }
+  });
   // the epilogue's lane = (pixel lane >> 1, 16 channels); its bias values are requested now
   const int rr = lane >> 1, c16 = (lane & 1) * 16;
   const int ch0 = ct * TILE + c16;
@@ -1379,50 +1424,54 @@ __global__ __launch_bounds__(256) void conv_layer_kernel(ConvLayerArgs a) {
 #pragma unroll
       for (int s = 0; s < 4; ++s) pre[j][s] = base[(size_t)j * ROWBLK + s * 2 * PADW];
   }
-  auto run_steps = [&](auto NV, int p_begin, int p_end) {
-    constexpr int n_visible = decltype(NV)::value;             // visible dy of these steps
-    for (int p = p_begin; p < p_end; ++p) {
-      const int it_next = step_of(p + 1);
-      load_weights(it_next, wn);
-      const uint4* base = frag_ptr(step_of(p));
-      const uint4* base_next = frag_ptr(it_next);
-      uint4 af[NJ][4];
+  // one step: p = its index in this workgroup's order, BUF = p % 2
+  auto one_step = [&](auto NV, auto BUF, int p) {
+    constexpr int n_visible = decltype(NV)::value;             // visible dy of this step
+    constexpr int buf = decltype(BUF)::value;
+    const uint4* base = frag_ptr(step_of(p));
+    const uint4* base_next = frag_ptr(step_of(p + 1 < N_IT ? p + 1 : p));
+    const bool more = p + 2 < N_IT;
+    const int it_pre = step_of(more ? p + 2 : p);              // the step this buffer serves next
+    uint4 af[NJ][4];
 #pragma unroll
-      for (int j = 0; j < PRE; ++j)
+    for (int j = 0; j < PRE; ++j)
 #pragma unroll
-        for (int s = 0; s < 4; ++s) af[j][s] = pre[j][s];
+      for (int s = 0; s < 4; ++s) af[j][s] = pre[j][s];
 #pragma unroll
-      for (int j = PRE; j < NJ; ++j)
+    for (int j = PRE; j < NJ; ++j)
 #pragma unroll
-        for (int s = 0; s < 4; ++s) af[j][s] = base[(size_t)j * ROWBLK + s * 2 * PADW];
-      // (the scheduler otherwise sinks every load to just before its first use, to save registers, and the
-      // wave then waits out each L2 and LDS latency in turn)
-      __builtin_amdgcn_sched_barrier(0);
-      static_for<NJ>([&](auto J) {
-        constexpr int j = decltype(J)::value;                  // input row y0 + wrow - MID + j
-        if constexpr (j == (NJ > 2 ? NJ - 2 : 0)) {
-#pragma unroll
-          for (int jj = 0; jj < PRE; ++jj)
-#pragma unroll
-            for (int s = 0; s < 4; ++s) pre[jj][s] = base_next[(size_t)jj * ROWBLK + s * 2 * PADW];
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        static_for<n_visible>([&](auto D) {
-          constexpr int dyi = decltype(D)::value;              // dy = dyi - MID; output row o = j - dyi
-          constexpr int o = j - dyi;
-          if constexpr (o >= 0 && o < RW) mfma_chunk<T>(af[j], wc[dyi], acc[o]);
-        });
+      for (int s = 0; s < 4; ++s) af[j][s] = base[(size_t)j * ROWBLK + s * 2 * PADW];
+    // (the scheduler otherwise sinks every load to just before its first use, to save registers, and the
+    // wave then waits out each L2 and LDS latency in turn)
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<n_visible>([&](auto D) {
+      constexpr int dyi = decltype(D)::value;                  // dy = dyi - MID reads input row j = o + dyi
+      static_for<RW>([&](auto O) {
+        constexpr int o = decltype(O)::value;
+        mfma_chunk<T>(af[o + dyi], wbuf[buf][dyi], acc[o]);
       });
+      if constexpr (dyi == 0) {                                // first fragments of the next step's input
 #pragma unroll
-      for (int d = 0; d < NDY; ++d)
+        for (int jj = 0; jj < PRE; ++jj)
 #pragma unroll
-        for (int s = 0; s < 4; ++s) wc[d][s] = wn[d][s];
-      if (p == 0) JM_TSTAMP(2, 0);
-      if (p == 4) JM_TSTAMP(3, 0);
+          for (int s = 0; s < 4; ++s) pre[jj][s] = base_next[(size_t)jj * ROWBLK + s * 2 * PADW];
+      }
+      if (more && (dyi < MID || it_pre < N_A)) load_weight_frag(it_pre, D, wbuf[buf][dyi]);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    if (p == 0) JM_TSTAMP(2, 0);
+    if (p == 4) JM_TSTAMP(3, 0);
+  };
+  // run A: steps 0 .. N_A-1 (dx <= 0), run B: steps N_A .. N_IT-1 (dx > 0); buffers alternate throughout
+  auto run_steps = [&](auto NV, auto PARITY, int p_begin, int p_end) {
+    constexpr int par = decltype(PARITY)::value;
+    for (int p = p_begin; p < p_end; p += 2) {
+      one_step(NV, std::integral_constant<int, par>{}, p);
+      if (p + 1 < p_end) one_step(NV, std::integral_constant<int, 1 - par>{}, p + 1);
     }
   };
-  run_steps(std::integral_constant<int, NDY>{}, 0, N_A);
-  run_steps(std::integral_constant<int, MID>{}, N_A, N_IT);
+  run_steps(std::integral_constant<int, NDY>{}, std::integral_constant<int, 0>{}, 0, N_A);
+  run_steps(std::integral_constant<int, MID>{}, std::integral_constant<int, N_A % 2>{}, N_A, N_IT);
   JM_TSTAMP(4, 0);
   __syncthreads();                                        // the input rows are no longer needed
 
