@@ -983,30 +983,23 @@ static int run_conv_pass(made_model* m, int N, const SampleIO& io, bool first_pa
   const int row_lo = io.t_lo / (32 * 3), row_hi = (io.t_hi - 1) / (32 * 3);   // rows holding the states drawn
   int* dirty_lo = whole_network ? nullptr : cv.win;
   launch_conv_trunk(m, io.x, N, dirty_lo, whole_network ? cv.H - 1 : row_hi, s, &last);
-  CatArgs c;
+  ConvHeadArgs c;
   memset(&c, 0, sizeof c);
   c.A = last;
   c.W = cv.w_head;
-  c.k_chunks = cv.F / chunk_elems(m);
   c.bias = cv.b_head;
   c.tile_kend = cv.head_tile_kend;
-  c.k_cap = cv.F;
-  c.rows = nullptr;
-  c.n_rows_ptr = nullptr;
-  c.n_rows = N * cv.H * 32;
   c.noise = io.noise;
   c.x = io.x;
-  c.enc = nullptr;
   c.changed = m->ws.changed;
-  c.D = 3;
-  c.t_lo = 0;
-  c.t_hi = 3;
-  c.t_begin = 0;
-  c.n_pos = 3;
-  c.pair_tiles = (c.n_rows + 2 * TILE - 1) / (2 * TILE);
-  c.rows_per_image = cv.H * 32;
+  c.N = N;
+  c.H = cv.H;
   c.state_lo = io.t_lo;
   c.state_hi = io.t_hi;
+  // one workgroup per CU in all (3 colours x 85; the kernel runs one wave per SIMD); the 4 waves of workgroup
+  // (colour, group) walk over the pixel rows 4 * group + wave, + 4 * groups, ...
+  c.groups = std::max(1, std::min((N * cv.H + 3) / 4, 85));
+  const size_t head_lds = (size_t)(CAT_C / TILE) * (cv.F / chunk_elems(m)) * 256 * 16;   // one colour's weights
   if (!whole_network) {
     c.dirty_lo = cv.win;
     c.first_changed = cv.win + cv.win_pad;
@@ -1015,15 +1008,25 @@ static int run_conv_pass(made_model* m, int N, const SampleIO& io, bool first_pa
     c.row_lo = row_lo;
     c.row_hi = row_hi;
     c.first_pass = first_pass ? 1 : 0;
-    c.n_images = N;
-    c.img_rows = cv.H;
   }
   c.retire = io.retire;
   prof_mark(m, m->L, false, s);
-  if (m->dtype == MADE_BF16)
-    hipLaunchKernelGGL((categorical_output_kernel<bf16_t>), dim3(c.n_pos * c.pair_tiles), dim3(CAT_WAVES * 64), 0, s, c);
-  else
-    hipLaunchKernelGGL((categorical_output_kernel<float>), dim3(c.n_pos * c.pair_tiles), dim3(CAT_WAVES * 64), 0, s, c);
+#define JM_LAUNCH_HEAD(T, FT)                                                                                      \
+  do {                                                                                                            \
+    static bool configured = false;                                                                               \
+    if (!configured) {                                                                                            \
+      (void)hipFuncSetAttribute((const void*)conv_head_kernel<T, FT>, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                (int)head_lds);                                                                   \
+      configured = true;                                                                                          \
+    }                                                                                                             \
+    hipLaunchKernelGGL((conv_head_kernel<T, FT>), dim3(3 * c.groups), dim3(256), head_lds, s, c);                 \
+  } while (0)
+  if (m->dtype == MADE_BF16) {
+    if (cv.F == 128) JM_LAUNCH_HEAD(bf16_t, 4); else JM_LAUNCH_HEAD(bf16_t, 2);
+  } else {
+    if (cv.F == 128) JM_LAUNCH_HEAD(float, 4); else JM_LAUNCH_HEAD(float, 2);
+  }
+#undef JM_LAUNCH_HEAD
   prof_mark(m, m->L, true, s);
   m->stats[2]++;
   HIP_TRY(hipGetLastError());

@@ -923,21 +923,6 @@ struct CatArgs {
   int t_lo, t_hi;        // positions whose symbol is re-drawn
   int t_begin, n_pos;    // positions this launch evaluates
   int pair_tiles;        // sample tiles of 64 this launch covers
-  // Convolutional model: operand rows are pixels, a "position" is a colour, D = 3.  rows_per_image > 0 then
-  // gives the pixels per image: changes are counted per image, and the states re-drawn are those with
-  // (pixel within its image) * 3 + colour in [state_lo, state_hi) instead of the t_lo / t_hi test.
-  int rows_per_image;
-  int state_lo, state_hi;
-  // Row window of the convolutional model (see ConvWindow); first_changed == NULL switches it off.  The head
-  // re-draws rows max(row_lo, dirty_lo[n]) .. row_hi (row_lo .. row_hi in the first pass of a block: its states
-  // have not been drawn against their final context yet); rows above have unchanged logits.  Every changed
-  // state lowers first_changed[image] to its row, and the last workgroup of the launch then sets
-  // dirty_lo[n] = min(first changed row, max(dirty_lo[n], row_hi + 1)) for the next pass.
-  int* dirty_lo;
-  int* first_changed;
-  int* win_done;                    // counter of finished workgroups (window tail)
-  unsigned long long* rows_stat;    // statistics: sum over passes and images of trunk rows recomputed
-  int row_lo, row_hi, first_pass, n_images, img_rows;
   RetireArgs retire;
 };
 
@@ -986,21 +971,7 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
   const int pos_i = blockIdx.x / a.pair_tiles, pair = blockIdx.x % a.pair_tiles;
   const int t = a.t_begin + a.n_pos - 1 - pos_i;
   const int row0 = pair * 64;
-  bool active = true;
-  if (a.first_changed) {   // windowed pass of the convolutional model: two image rows per workgroup
-    active = false;
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int g = pair * 2 + j;
-      if (g * 32 < n_rows) {
-        const int n = g / a.img_rows, y = g % a.img_rows;
-        const int lo = a.first_pass ? a.row_lo : max(a.row_lo, a.dirty_lo[n]);
-        active = active || (y >= lo && y <= a.row_hi);
-      }
-    }
-  }
-  if (row0 < n_rows && active) {   // (uniform per workgroup)
-    JM_TSTAMP(0, 0);
+  if (row0 < n_rows) {   // (uniform per workgroup)
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, h = lane >> 5;
     const bool two = row0 + 32 < n_rows;
@@ -1027,7 +998,6 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
     else
       cat_stream<T, false>(W0, W1, A0, A1, n_chunks, acc);
 
-    JM_TSTAMP(1, 1);
     // acc[q][j][i]: sample row 8*(i/4) + 4*h + i%4 of sample tile j, class (wave*2 + q)*32 + r.
     // A lane's noise loads are then 4-byte reads that 32 lanes make to one 128-byte line (the noise is the
     // larger stream of the convolutional model).  Element m = 16*j + i of a lane is one sample's best value
@@ -1057,7 +1027,6 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
         }
       });
     });
-    JM_TSTAMP(2, 1);
     static_for<5>([&](auto S) {
       constexpr int bit = 16 >> decltype(S)::value;     // lane bit of this step; 2 * bit elements are left
       const bool up = (r & bit) != 0;
@@ -1081,18 +1050,9 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
       sm_idx[wave][slot] = idx[0];
     }
     __syncthreads();
-    JM_TSTAMP(3, 1);
     if (threadIdx.x < 64) {   // (wave 0: one lane per sample row of the pair)
       const int sl = threadIdx.x;
-      bool redraw = row0 + sl < n_rows;
-      if (redraw) {
-        if (a.rows_per_image > 0) {
-          const int st = ((row0 + sl) % a.rows_per_image) * 3 + t;
-          redraw = st >= a.state_lo && st < a.state_hi;
-        } else {
-          redraw = t >= a.t_lo && t < a.t_hi;
-        }
-      }
+      const bool redraw = row0 + sl < n_rows && t >= a.t_lo && t < a.t_hi;
       bool differs = false;
       int sample = 0;
       if (redraw) {
@@ -1112,48 +1072,7 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
                 Elem<T>::from_f32(((float)xn - 128.0f) * (1.0f / 128.0f));
         }
       }
-      if (a.rows_per_image > 0) {
-        // the pixels of an image are consecutive rows: one counter update per image and workgroup (single
-        // updates of a handful of counters from every changed state serialise on one cache line)
-        const unsigned long long m = __ballot(differs);
-        const int img = (row0 + sl) / a.rows_per_image;
-        const int lo = max(img * a.rows_per_image - row0, 0);
-        const int hi = min((img + 1) * a.rows_per_image - row0, 64);
-        const unsigned long long mask = (hi >= 64 ? ~0ull : ((1ull << hi) - 1)) & ~((1ull << lo) - 1);
-        const int cnt = __popcll(m & mask);
-        if (sl == lo && cnt > 0) {
-          count_changed(&a.changed[img], cnt);
-          if (a.first_changed) {
-            const int pix = row0 + __builtin_ctzll(m & mask);          // lowest changed pixel of this image
-            const int old = __hip_atomic_fetch_min(&a.first_changed[img], (pix % a.rows_per_image) >> 5,
-                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            asm volatile("" ::"v"(old));                                // (performed before the tail counters)
-          }
-        }
-      } else if (differs) {
-        count_changed(&a.changed[sample], 1);
-      }
-    }
-  }
-  JM_TSTAMP(4, 1);
-  if (a.first_changed) {   // window tail: the last workgroup to arrive updates the images' dirty rows
-    __shared__ int win_last_s;
-    __syncthreads();
-    if (threadIdx.x == 0)
-      win_last_s = (__hip_atomic_fetch_add(a.win_done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-                    (int)gridDim.x - 1);
-    __syncthreads();
-    if (win_last_s) {
-      unsigned long long rows = 0;
-      for (int n = threadIdx.x; n < a.n_images; n += blockDim.x) {
-        const int fc = __hip_atomic_load(&a.first_changed[n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        a.first_changed[n] = 0x7fffffff;
-        const int d = a.dirty_lo[n];
-        rows += (unsigned long long)max(0, a.row_hi - d + 1);
-        a.dirty_lo[n] = min(fc, max(d, a.row_hi + 1));
-      }
-      if (rows) atomicAdd(a.rows_stat, rows);
-      if (threadIdx.x == 0) *a.win_done = 0;
+      if (differs) count_changed(&a.changed[sample], 1);
     }
   }
   if (a.retire.enabled) finish_pass(a.retire, gridDim.x);
@@ -1496,6 +1415,208 @@ __global__ __launch_bounds__(256) void conv_layer_kernel(ConvLayerArgs a) {
     }
   });
   JM_TSTAMP(5, 1);
+}
+
+struct ConvHeadArgs {
+  const void* A;         // last k x k layer's activations (fragment-major, rows = pixels, F channels)
+  const void* W;         // head weights [3*256 x F], rows colour*256 + class (fragment-major)
+  const float* bias;     // [3*256]
+  const int* tile_kend;  // [3*8] visible K per 32-row weight tile; the 8 tiles of a colour share one value
+  const float* noise;    // g[pixel, colour, 256]
+  uint8_t* x;            // symbols [pixel, colour]
+  int* changed;          // per image: states changed in this pass
+  int N, H;
+  int state_lo, state_hi;   // states (pixel within its image * 3 + colour) that are re-drawn
+  int groups;               // workgroups per colour; workgroup (colour, group) walks rows group, group + groups, ...
+  // row window (see ConvWindow); first_changed == NULL: every row is evaluated and nothing is tracked
+  int* dirty_lo;
+  int* first_changed;
+  int* win_done;
+  unsigned long long* rows_stat;
+  int row_lo, row_hi, first_pass;
+  RetireArgs retire;
+};
+
+// 1 x 1 head + Gumbel-max draw + change detection of the convolutional model.  A workgroup is bound to one
+// colour and first copies that colour's 256 x F weight block (and bias) to LDS; after that its 4 waves work
+// independently: a wave takes one row of 32 pixels at a time (rows wave, wave + stride, ...) and multiplies it
+// with one 32-class tile after the other.  The classes are the MFMA's row operand, so lane (r, h) holds 16
+// classes of pixel r per tile: the 256-way argmax is a running (value, class) pair per lane plus one exchange
+// between the half-waves, and the lane's noise comes in 16-byte loads.  The noise is the large stream of this
+// launch (100 MB per pass at batch 32 against 8 MB of activations), and 16-byte loads are what the memory
+// system needs: measured on this access pattern 4.2 TB/s, against 1.5 TB/s for 4-byte loads of whole 128-byte
+// lines (pixels as row operand) and 5.5 TB/s for a plain linear read.  No barrier inside the loop.  FT = F / 32.
+template <typename T, int FT>
+__global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
+  constexpr int KC = 2 * Elem<T>::EPL;
+  constexpr int KCH = FT * 32 / KC;
+  constexpr int NCT = CAT_C / TILE;                     // class tiles
+  extern __shared__ uint4 head_w[];                     // [NCT][KCH][256] this colour's weights, fragment-major
+  __shared__ float4 bias_lds[CAT_C / 4];
+  const int t = blockIdx.x / a.groups, group = blockIdx.x % a.groups;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r = lane & 31, h = lane >> 5;
+  const int n_rows = a.N * a.H;
+
+  auto row_active = [&](int g) {
+    const int n = g / a.H, y = g % a.H;
+    if (y * 96 + 93 + t < a.state_lo || y * 96 + t >= a.state_hi) return false;   // no state of this row is drawn
+    if (!a.first_changed) return true;
+    const int lo = a.first_pass ? a.row_lo : max(a.row_lo, a.dirty_lo[n]);
+    return y >= lo && y <= a.row_hi;
+  };
+  const int stride = a.groups * 4;
+  auto next_active = [&](int g) {                       // first active row of this wave at or after g
+    while (g < n_rows && !row_active(g)) g += stride;
+    return g;
+  };
+  JM_TSTAMP(0, 0);
+  int n_done = 0;
+  int g = next_active(group * 4 + wave);
+  const bool wg_has_work = __syncthreads_or(g < n_rows);
+
+  // Noise registers: a ring of RING class tiles; slot ct % RING holds the lane's classes ct*32 + 8q + 4h .. + 3
+  // of pixel r.  As soon as a tile is consumed, the tile RING places further on (of this row or of the wave's
+  // next row) is requested into its slot, so RING tiles (2 KB per wave each) are always in flight.
+  auto load_noise = [&](int g_row, int ct, float4 (&dst)[4]) {
+    const float* nz = a.noise + ((size_t)(g_row * 32 + r) * 3 + t) * CAT_C + ct * TILE + 4 * h;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) dst[q] = *(const float4*)(nz + 8 * q);
+  };
+  constexpr int RING = 4;
+  static_assert(NCT % RING == 0, "a row must be a whole number of ring turns");
+  float4 gz[RING][4];
+  if (g < n_rows) {
+#pragma unroll
+    for (int ct = 0; ct < RING; ++ct) load_noise(g, ct, gz[ct]);
+  }
+
+  int k_end = a.tile_kend[t * NCT];
+  if (k_end > FT * 32) k_end = FT * 32;
+  const int n_chunks = (k_end + KC - 1) / KC;
+  if (wg_has_work) {
+    const uint4* Wsrc = (const uint4*)a.W + (size_t)t * NCT * KCH * 256;
+    constexpr int PIECES = NCT * KCH;                   // 16-byte pieces per thread
+    static_for<(PIECES + 7) / 8>([&](auto B) {
+      constexpr int b0 = decltype(B)::value * 8;
+      constexpr int cnt = PIECES - b0 < 8 ? PIECES - b0 : 8;
+      uint4 v[cnt];
+#pragma unroll
+      for (int i = 0; i < cnt; ++i) v[i] = Wsrc[(size_t)(b0 + i) * 256 + tid];
+#pragma unroll
+      for (int i = 0; i < cnt; ++i) head_w[(b0 + i) * 256 + tid] = v[i];
+    });
+    if (tid < CAT_C / 4) bias_lds[tid] = *(const float4*)(a.bias + t * CAT_C + 4 * tid);
+  }
+  __syncthreads();
+  JM_TSTAMP(1, 0);
+  int sink = 0;                                         // old values of the counter atomics (see below)
+
+  while (g < n_rows) {                                  // (uniform over the wave)
+    const int n = g / a.H, y = g % a.H;
+    const int g_next = next_active(g + stride);
+    const size_t xi = ((size_t)g * 32 + r) * 3 + t;     // lane (r, 0) finishes pixel r
+    const uint8_t x_old = a.x[xi];
+    uint4 af[KCH][4];
+    const uint4* A0 = (const uint4*)a.A + (size_t)g * KCH * 256 + h * 32 + r;
+#pragma unroll
+    for (int c = 0; c < KCH; ++c)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) af[c][s] = A0[c * 256 + s * 64];
+
+    float best = -INFINITY;
+    int best_c = 0;
+    static_for<NCT>([&](auto CT) {
+      constexpr int ct = decltype(CT)::value;
+      f32x16 acc;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+      const uint4* Wl = head_w + (size_t)ct * KCH * 256 + h * 32 + r;
+      static_for<KCH>([&](auto C) {
+        constexpr int c = decltype(C)::value;
+        if (c < n_chunks) {
+          uint4 wf[4];
+#pragma unroll
+          for (int s = 0; s < 4; ++s) wf[s] = Wl[c * 256 + s * 64];
+          mfma_chunk<T>(wf, af[c], acc);
+        }
+      });
+      // acc[4q + j]: class ct*32 + 8q + 4h + j of pixel r; classes ascend along (ct, q, j), so a strict compare
+      // keeps the lowest class of a tie
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int cb = ct * TILE + 8 * q + 4 * h;
+        const float4 bv = bias_lds[cb >> 2];
+        const float4 gv = gz[ct % RING][q];
+        const float v0 = (acc[4 * q + 0] + bv.x) + gv.x;
+        const float v1 = (acc[4 * q + 1] + bv.y) + gv.y;
+        const float v2 = (acc[4 * q + 2] + bv.z) + gv.z;
+        const float v3 = (acc[4 * q + 3] + bv.w) + gv.w;
+        if (v0 > best) { best = v0; best_c = cb; }
+        if (v1 > best) { best = v1; best_c = cb + 1; }
+        if (v2 > best) { best = v2; best_c = cb + 2; }
+        if (v3 > best) { best = v3; best_c = cb + 3; }
+      }
+      // (without this the compiler postpones the compare chains of all tiles to the end of the row and keeps
+      // every tile's sums and noise alive until then)
+      asm volatile("" : "+v"(best), "+v"(best_c));
+      if constexpr (ct + RING < NCT) load_noise(g, ct + RING, gz[ct % RING]);
+      else if (g_next < n_rows) load_noise(g_next, ct + RING - NCT, gz[ct % RING]);
+      __builtin_amdgcn_sched_barrier(0);          // (keeps the reload here instead of at its use much later)
+    });
+    {
+      const float ob = __shfl_xor(best, 32);
+      const int oc = __shfl_xor(best_c, 32);
+      if (ob > best || (ob == best && oc < best_c)) { best = ob; best_c = oc; }
+    }
+    bool differs = false;
+    if (h == 0) {
+      const int st = (y * 32 + r) * 3 + t;
+      if (st >= a.state_lo && st < a.state_hi) {
+        const uint8_t xn = (uint8_t)best_c;
+        differs = xn != x_old;
+        if (differs) a.x[xi] = xn;
+      }
+    }
+    const unsigned long long changed_mask = __ballot(differs);
+    if (lane == 0 && changed_mask != 0) {
+      // returning atomics, so that "the value came back" means "performed"; the values are only consumed
+      // after the loop (before the tail counters), so a row does not wait for them
+      sink += __hip_atomic_fetch_add(&a.changed[n], __popcll(changed_mask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (a.first_changed)
+        sink += __hip_atomic_fetch_min(&a.first_changed[n], y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    g = g_next;
+    if (n_done == 0) JM_TSTAMP(2, 0);
+    if (n_done == 1) JM_TSTAMP(3, 0);
+    ++n_done;
+  }
+  JM_TSTAMP(4, 0);
+  asm volatile("" ::"v"(sink));                         // every counter atomic of this thread has been performed
+
+  if (a.first_changed) {   // window tail: the last workgroup to arrive updates the images' dirty rows
+    __shared__ int win_last_s;
+    __syncthreads();
+    if (threadIdx.x == 0)
+      win_last_s = (__hip_atomic_fetch_add(a.win_done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                    (int)gridDim.x - 1);
+    __syncthreads();
+    if (win_last_s) {
+      unsigned long long rows = 0;
+      for (int n = threadIdx.x; n < a.N; n += blockDim.x) {
+        const int fc = __hip_atomic_load(&a.first_changed[n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        a.first_changed[n] = 0x7fffffff;
+        const int d = a.dirty_lo[n];
+        rows += (unsigned long long)max(0, a.row_hi - d + 1);
+        a.dirty_lo[n] = min(fc, max(d, a.row_hi + 1));
+      }
+      if (rows) atomicAdd(a.rows_stat, rows);
+      if (threadIdx.x == 0) *a.win_done = 0;
+    }
+  }
+  JM_TSTAMP(5, 1);
+  if (a.retire.enabled) finish_pass(a.retire, gridDim.x);
+  JM_TSTAMP(6, 1);
 }
 
 __global__ void copy_symbols_kernel(const uint8_t* x_init, uint8_t* x, size_t total) {
