@@ -79,9 +79,9 @@ def cpu_baseline_conv(w, net, noise, budget_s=12.0):
 def measured_traffic(workload: str, path: str, dom_is_output: bool):
     """HBM bytes per launch of the dominant kernel, as measured with rocprofv3 PMC counters in a separate run
     (counters cannot be read from inside this process); the summary under profiles/ holds the figure."""
-    if workload != "cfg2" or path != "layers" or not dom_is_output:
+    if workload not in ("cfg2", "cfg4") or path != "layers" or not dom_is_output:
         return None
-    fn = os.path.join(ROOT, "profiles", "cfg2_jacobi_pmc_traffic.txt")
+    fn = os.path.join(ROOT, "profiles", f"{workload}_jacobi_pmc_traffic.txt")
     try:
         for line in open(fn):
             if line.startswith("traffic_bytes_per_launch"):
@@ -209,6 +209,11 @@ def main() -> int:
     elapsed_prof = time.perf_counter() - t0
     B.made_set_profiling(model, False)
 
+    if conv:
+        # the k x k layers are launches of one kernel on one shape: fold their slots into slot 1
+        for arr in (layer_ms, layer_launches, layer_flops):
+            arr[1] = arr[1:n_layers - 1].sum()
+            arr[2:n_layers - 1] = 0
     dom = int(np.argmax(layer_ms))
     dom_avg_us = layer_ms[dom] / max(1, layer_launches[dom]) * 1e3
     es = 2 if w.dtype == "bf16" else 4
@@ -226,13 +231,16 @@ def main() -> int:
         peak, unit, bound = (PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_F32_TFLOPS), "TFLOP/s", "mfma"
     if conv:
         layer_name = ("conv_first_kernel" if dom == 0 else
-                      f"conv_layer_kernel layer {dom} (k x k masked convolution as implicit GEMM)" if dom < n_layers - 1
-                      else "categorical_output_kernel (1 x 1 head + Gumbel-max)")
+                      f"conv_layer_kernel (k x k masked convolution as implicit GEMM, all {n_layers - 2} such layers)"
+                      if dom < n_layers - 1 else "conv_head_kernel (1 x 1 head + Gumbel-max)")
     elif dom == n_layers:
         layer_name = "persistent_sampler_kernel (all passes of a call: hidden layers, output layer + sampling, stop test)"
     else:
-        layer_name = (f"masked_layer_kernel layer {dom} "
-                      f"({'output+sampling epilogue' if dom == n_layers - 1 else 'hidden'})")
+        if dom == n_layers - 1 and w.C == 256:
+            layer_name = "categorical_output_kernel (output layer + Gumbel-max draw + stop test)"
+        else:
+            layer_name = (f"masked_layer_kernel layer {dom} "
+                          f"({'output+sampling epilogue' if dom == n_layers - 1 else 'hidden'})")
 
     result = {
         "metric": "samples/s (Jacobi vs sequential, same output); iters to converge; MFMA util",
