@@ -285,6 +285,45 @@ def gs_jacobi_reference(model: MadeModel, noise: np.ndarray, block: int,
     return x, per_block.sum(axis=1).astype(np.int32), per_block, min_margin
 
 
+def jacobi_gs_reference(model: MadeModel, noise: np.ndarray, block: int,
+                        x_init: Optional[np.ndarray] = None, max_iters: Optional[int] = None):
+    """Algorithm 2 (Jacobi-GS), tolerance 0, per-sample stopping.  Returns (x, iters[N], done[N], min_margin[N]).
+
+    Iteration k: every block [a, b) -- all blocks "in parallel", i.e. all from the same s^{k-1} -- is walked
+    through position by position: s_j^k = h_j(u, s^{k-1}_{1:a-1}, s^k_{a:j-1}).  So position j of block i is
+    evaluated on the mixed vector (previous iterate before the block, current iterate inside it).  Stop at the
+    first k with s^k == s^{k-1} or at k = M (number of blocks), where the result is exact (Proposition 2).
+    """
+    N, D = noise.shape[0], model.D
+    parts = block_partition(D, block)
+    M = len(parts)
+    cap = M if (max_iters is None or max_iters <= 0) else min(max_iters, M)
+    x = np.zeros((N, D), dtype=np.uint8) if x_init is None else np.array(x_init, dtype=np.uint8)
+    iters = np.zeros(N, dtype=np.int32)
+    done = np.zeros(N, dtype=bool)
+    min_margin = np.full(N, np.inf)
+    k = 0
+    while not done.all() and k < cap:
+        k += 1
+        act = np.flatnonzero(~done)
+        prev = x[act]
+        new = prev.copy()
+        for (a, b) in parts:
+            mixed = prev.copy()                         # s^{k-1} everywhere ...
+            for j in range(a, b):                       # ... except the block's earlier positions
+                z_j = logits_at(model, mixed, j)
+                mixed[:, j], margin = decide(z_j, _noise_at(noise[act], j), model.C)
+                min_margin[act] = np.minimum(min_margin[act], margin)
+            new[:, a:b] = mixed[:, a:b]
+        same = (new == prev).all(axis=1)
+        x[act] = new
+        iters[act] = k
+        done[act[same]] = True
+        if k == M:
+            done[act] = True
+    return x, iters, done, min_margin
+
+
 # --------------------------------------------------------------------------------------
 # The joint distribution by enumeration (chain rule, Appendix A.3)
 # --------------------------------------------------------------------------------------

@@ -400,6 +400,64 @@ def test_gs_jacobi_chain_uses_block_size_iterations():
     assert (x == 1).all() and (per_block == np.array([5, 5, 2])[None, :]).all()
 
 
+# ------------------------------------------------------------------ Proposition 2 / Algorithm 2
+@pytest.mark.parametrize("name", ["cfg1", "small_f32", "small_cat_f32"])
+def test_jacobi_gs_exact_for_every_block_size(name):
+    w = S.workload(name)
+    net = S.make_network(w, with_bias=True)
+    model = _model(net)
+    noise = S.make_noise(w)
+    xs, _ = O.sequential_sample(model, noise)
+    xj, it_j, _, _, _ = O.jacobi_reference(model, noise)
+    for B in [1, 2, 7, 16, w.D - 1, w.D, w.D + 5]:
+        M = len(O.block_partition(w.D, B))
+        x, iters, done, _ = O.jacobi_gs_reference(model, noise, B)
+        assert (x == xs).all() and done.all()
+        assert (iters >= 1).all() and (iters <= M).all()             # Proposition 2: at most M iterations
+        if B == 1:
+            assert (iters == it_j).all()              # blocks of one position: Algorithm 1 itself
+        if B >= w.D:
+            assert (iters == 1).all()                 # one block: a single sweep is the feedforward computation
+        # proof of Proposition 2: after k iterations the first k blocks are final
+        for k in (1, 2, 3):
+            if k < M:
+                xk = O.jacobi_gs_reference(model, noise, B, max_iters=k)[0]
+                assert (xk[:, :k * B] == xs[:, :k * B]).all()
+    init = np.random.default_rng(5).integers(0, 2 if w.C == 1 else w.C, (w.N, w.D)).astype(np.uint8)
+    assert (O.jacobi_gs_reference(model, noise, 7, init)[0] == xs).all()
+
+
+def test_jacobi_gs_chain_needs_one_iteration_per_block():
+    """A chain that copies its predecessor (Section 4.1, Example 3) started from the wrong symbols: every
+    iteration of Algorithm 2 finalises exactly one more block, so M iterations are needed."""
+    T = 12
+    model = _model(S.copy_chain_network(T))
+    u = S.uniform_noise(2, T, 3) * 0.98 + 0.01
+    x, iters, done, _ = O.jacobi_gs_reference(model, u, 5)
+    assert (x == 1).all() and (iters == 3).all() and done.all()
+    x1 = O.jacobi_gs_reference(model, u, 5, max_iters=1)[0]
+    assert (x1[:, :5] == 1).all() and not (x1[:, 5:] == 1).all()
+
+
+def test_jacobi_gs_one_iteration_by_hand():
+    """One iteration of Algorithm 2 written out with the scalar evaluator: position j of block [a, b) sees the
+    previous iterate before a and this iteration's symbols in a .. j-1."""
+    net = small_net(7, 1, [9], seed=21)
+    model = _model(net)
+    u = S.uniform_noise(3, 7, 8)
+    prev = np.random.default_rng(2).integers(0, 2, (3, 7)).astype(np.uint8)
+    expect = prev.copy()
+    for n in range(3):
+        for (a, b) in [(0, 3), (3, 6), (6, 7)]:
+            mixed = [int(v) for v in prev[n]]
+            for j in range(a, b):
+                z = scalar_logits(net, mixed, j)[0]
+                mixed[j] = 1 if u[n, j] < 1.0 / (1.0 + math.exp(-z)) else 0
+            expect[n, a:b] = mixed[a:b]
+    got = O.jacobi_gs_reference(model, u, 3, prev, max_iters=1)[0]
+    assert (got == expect).all()
+
+
 # ------------------------------------------------------------------ bf16-activation mode
 def test_bf16_activation_mode_rounds_hidden_units_only():
     w = S.workload("small_bf16")
