@@ -315,6 +315,18 @@ def main() -> int:
                                            "iters_mean": float(itc.mean()), "iters_max": int(itc.max()),
                                            "batch_passes": int(st["passes"]),
                                            "same_output_as_jacobi": bool(torch.equal(xq, x_jac))}
+        if not conv and w.C == 1:
+            for blk in (w.block_sizes or []):           # Algorithm 2: one timed call per block size (it is slow)
+                B.jacobi_gs_sample(model, noises[0], N, None, blk, 0, xq, iters, stream)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                B.jacobi_gs_sample(model, noises[0], N, None, blk, 0, xq, iters, stream)
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t0
+                itc = iters.cpu().numpy()
+                extras[f"jacobi_gs_B{blk}"] = {"samples_per_s": N / dt, "ms_per_batch": dt * 1e3,
+                                               "iters_mean": float(itc.mean()), "iters_max": int(itc.max()),
+                                               "same_output_as_jacobi": bool(torch.equal(xq, x_jac))}
         result["extras"] = extras
 
     if not args.no_cpu_baseline and conv:

@@ -151,6 +151,24 @@ int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, const uint8_t
                      int32_t block, uint8_t* x_out, int32_t* iters_out, void* stream);
 
 /*
+ * jacobi_gs_sample -- Algorithm 2 (Jacobi-GS) with tolerance 0: in every iteration all blocks of `block`
+ * consecutive positions (the last one may be short) are processed "in parallel", each from the previous
+ * iterate, and inside a block the positions are drawn one after the other:
+ *     s_j^k = h_j(u, s^{k-1}_{1:a-1}, s^k_{a:j-1})   for j in block [a, b].
+ * Per sample the iteration stops at the first k with s^k == s^{k-1}, or at k = M (number of blocks), where the
+ * result is exact (Proposition 2).  One iteration costs `block` evaluations of the hidden layers on M copies
+ * of the batch (every block has its own mixed input), so on a masked MLP this solver is the most expensive of
+ * the family; it is here for completeness of the paper's solvers.
+ *   x_init    : device uint8 [N, D] or NULL (zeros).
+ *   max_iters : <= 0 or > M means M; a smaller limit makes the call return MADE_ERR_NOT_CONVERGED when a
+ *               sample was still changing in the last allowed iteration (x_out then holds that iterate).
+ *   iters_out : device int32 [N] or NULL; iterations per sample (including the confirming one).
+ * Supported: the masked MLP with Bernoulli positions (C = 1), M * round_up(N, 32) <= 2^22.
+ */
+int jacobi_gs_sample(made_model* m, const float* noise, int32_t N, const uint8_t* x_init, int32_t block,
+                     int32_t max_iters, uint8_t* x_out, int32_t* iters_out, void* stream);
+
+/*
  * made_last_stats -- counters of the most recent *_sample call on this model (host side):
  *   out[0] passes launched (network passes over the still-active part of the batch)
  *   out[1] sum over passes of active samples (sample-passes; the unit of algorithmic work)

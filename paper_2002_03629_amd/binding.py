@@ -18,7 +18,7 @@ MADE_OK, MADE_ERR_ARG, MADE_ERR_NOMEM, MADE_ERR_HIP, MADE_ERR_NOT_CONVERGED = 0,
 MADE_F32, MADE_BF16 = 0, 1
 
 EXPORTS = ["made_init", "made_conv_init", "made_free", "made_forward_logits", "sequential_sample", "jacobi_sample",
-           "gs_jacobi_sample", "made_last_stats", "made_set_profiling", "made_last_profile", "made_set_option",
+           "gs_jacobi_sample", "jacobi_gs_sample", "made_last_stats", "made_set_profiling", "made_last_profile", "made_set_option",
            "made_layer_nnz",
            "made_last_error"]
 
@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
         L.sequential_sample.argtypes = [vp, vp, i32, i32, vp, vp]
         L.jacobi_sample.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
         L.gs_jacobi_sample.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
+        L.jacobi_gs_sample.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, vp]
         L.made_last_stats.argtypes = [vp, i64p, i32]
         L.made_set_profiling.argtypes = [vp, i32]
         L.made_last_profile.argtypes = [vp, C.POINTER(C.c_double), i64p, i32]
@@ -195,6 +196,13 @@ def jacobi_sample(model: int, noise, N: int, x_init, max_iters: int, x_out, iter
 def gs_jacobi_sample(model: int, noise, N: int, x_init, block: int, x_out, iters_out=None, stream=None) -> None:
     import torch
     _check(lib().gs_jacobi_sample(model, _ptr(noise, torch.float32), N, _ptr(x_init, torch.uint8), block,
+                                  _ptr(x_out, torch.uint8), _ptr(iters_out, torch.int32), _stream(stream)))
+
+
+def jacobi_gs_sample(model: int, noise, N: int, x_init, block: int, max_iters: int, x_out, iters_out=None,
+                     stream=None) -> None:
+    import torch
+    _check(lib().jacobi_gs_sample(model, _ptr(noise, torch.float32), N, _ptr(x_init, torch.uint8), block, max_iters,
                                   _ptr(x_out, torch.uint8), _ptr(iters_out, torch.int32), _stream(stream)))
 
 

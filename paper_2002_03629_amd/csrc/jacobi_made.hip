@@ -150,6 +150,13 @@ struct made_model {
   std::vector<std::vector<int>> cnt_lt;
   Workspace ws;
   int64_t stats[5] = {0, 0, 0, 0, 0};
+  // Jacobi-GS (Algorithm 2): symbols of the virtual samples, per-sub-step position table, per-sample state
+  uint8_t* jgs_xv = nullptr;
+  size_t jgs_xv_cap = 0;
+  int* jgs_tab = nullptr;
+  size_t jgs_tab_cap = 0;
+  int* jgs_state = nullptr;                   // [N] stopped flags, then one counter of samples still iterating
+  size_t jgs_state_cap = 0;
   // optional per-layer timing with HIP events on the caller's stream
   bool profiling = false;
   std::vector<hipEvent_t> ev_pool;            // pairs: [2i] before, [2i+1] after a layer launch
@@ -287,6 +294,9 @@ extern "C" int made_free(made_model* m) {
     if (l.cnt_lt) (void)hipFree(l.cnt_lt);
   }
   free_workspace(m->ws);
+  if (m->jgs_xv) (void)hipFree(m->jgs_xv);
+  if (m->jgs_tab) (void)hipFree(m->jgs_tab);
+  if (m->jgs_state) (void)hipFree(m->jgs_state);
   {
     ConvNet& cv = m->conv;
     void* ptrs[] = {cv.taps, cv.w0, cv.b0, cv.w_head, cv.b_head, cv.head_tile_kend, cv.win, cv.rows_stat};
@@ -1444,6 +1454,125 @@ extern "C" int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, co
     blocks.push_back(make_block(m, a, b, b - a, true));
   }
   return run_chains(m, blocks, noise, x_init, x_out, N, false, iters_out, s);
+}
+
+template <typename P>
+static int grow(P** p, size_t* cap, size_t need_bytes) {
+  if (need_bytes <= *cap) return MADE_OK;
+  if (*p) (void)hipFree(*p);
+  *p = nullptr;
+  *cap = 0;
+  HIP_TRY(hipMalloc((void**)p, need_bytes));
+  *cap = need_bytes;
+  return MADE_OK;
+}
+
+// Algorithm 2.  Every block keeps its own copy of the state vector ("virtual sample" (block i, sample n) =
+// row i * np + n of a batch of M * np rows): it starts an iteration as the previous iterate and receives the
+// block's new symbols one position at a time.  Sub-step q of an iteration evaluates the hidden layers on all
+// virtual samples and then, in one launch, position a_i + q of every block i on that block's rows only.  After
+// |block| sub-steps the blocks' positions are collected, compared with the previous iterate (per sample) and
+// become the new iterate.
+extern "C" int jacobi_gs_sample(made_model* m, const float* noise, int32_t N, const uint8_t* x_init, int32_t block,
+                                int32_t max_iters, uint8_t* x_out, int32_t* iters_out, void* stream) {
+  TRY(check_call(m, noise, N, x_out, "jacobi_gs_sample"));
+  if (block < 1) return fail(MADE_ERR_ARG, "jacobi_gs_sample: block=%d must be >= 1", block);
+  if (m->arch != 0 || m->C != 1)
+    return fail(MADE_ERR_ARG, "jacobi_gs_sample: only the masked MLP with Bernoulli positions is supported");
+  if (N == 0) return MADE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  memset(m->stats, 0, sizeof m->stats);
+  m->ev_layer.clear();
+  const int D = m->D;
+  const int B = std::min(block, D);
+  const int M = (D + B - 1) / B;
+  const int np = round_up(N, TILE);
+  const int64_t V64 = (int64_t)M * np;
+  if (V64 > (1 << 22))
+    return fail(MADE_ERR_ARG, "jacobi_gs_sample: %d blocks x %d samples = %lld virtual samples exceed 2^22", M, np,
+                (long long)V64);
+  const int V = (int)V64;
+  const int row_tiles = V / TILE, tiles_per_block = np / TILE;
+  const int cap = (max_iters <= 0 || max_iters > M) ? M : max_iters;
+  TRY(ensure_workspace(m, V, false));
+  Workspace& w = m->ws;
+  TRY(grow(&m->jgs_xv, &m->jgs_xv_cap, (size_t)V * D));
+  TRY(grow(&m->jgs_tab, &m->jgs_tab_cap, (size_t)B * row_tiles * sizeof(int)));
+  TRY(grow(&m->jgs_state, &m->jgs_state_cap, (size_t)(N + 1) * sizeof(int)));
+  {   // position drawn by row tile rt in sub-step q: a_i + q for its block i, or -1 past the block's end
+    std::vector<int> tab((size_t)B * row_tiles);
+    for (int q = 0; q < B; ++q)
+      for (int rt = 0; rt < row_tiles; ++rt) {
+        const int i = rt / tiles_per_block, pos = i * B + q;
+        tab[(size_t)q * row_tiles + rt] = (pos < std::min((i + 1) * B, D)) ? pos : -1;
+      }
+    HIP_TRY(hipMemcpyAsync(m->jgs_tab, tab.data(), tab.size() * sizeof(int), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipStreamSynchronize(s));   // (tab is a local)
+  }
+  int* state = m->jgs_state;
+  int* n_active = m->jgs_state + N;
+  HIP_TRY(hipMemsetAsync(state, 0, (size_t)(N + 1) * sizeof(int), s));
+  HIP_TRY(hipMemsetAsync(w.flags, 0, sizeof(int), s));
+  HIP_TRY(hipMemsetAsync(w.iters, 0, (size_t)N * sizeof(int), s));
+  {   // x_out = initial iterate
+    const size_t total = (size_t)N * D;
+    const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
+    hipLaunchKernelGGL(copy_symbols_kernel, dim3(blocks), dim3(256), 0, s, x_init, x_out, total);
+    m->stats[2]++;
+  }
+  const RowSet rs{nullptr, nullptr, V};
+  const int fill_blocks = (int)std::min<size_t>(((size_t)V * D + 255) / 256, 8192);
+  int k = 0;
+  for (;;) {
+    ++k;
+    if (m->dtype == MADE_BF16)
+      hipLaunchKernelGGL((jgs_begin_kernel<bf16_t>), dim3(fill_blocks), dim3(256), 0, s, x_out, m->jgs_xv, (bf16_t*)w.enc,
+                         m->layers[0].k_chunks, N, np, M, D);
+    else
+      hipLaunchKernelGGL((jgs_begin_kernel<float>), dim3(fill_blocks), dim3(256), 0, s, x_out, m->jgs_xv, (float*)w.enc,
+                         m->layers[0].k_chunks, N, np, M, D);
+    m->stats[2]++;
+    for (int q = 0; q < B; ++q) {
+      TRY(run_hidden(m, rs, nullptr, -1, s));
+      LayerArgs a = base_args(m, m->L, w.act[m->L - 1], rs);
+      a.noise = noise;
+      a.x = m->jgs_xv;
+      a.enc = w.enc;
+      a.enc_chunks = m->layers[0].k_chunks;
+      a.changed = w.changed;
+      a.D = D;
+      a.diag_pos = m->jgs_tab + (size_t)q * row_tiles;
+      a.noise_mod = np;
+      a.noise_n = N;
+      a.n_launch_tiles = 1;
+      a.row_tiles = row_tiles;
+      prof_mark(m, m->L, false, s);
+      if (m->dtype == MADE_BF16)
+        hipLaunchKernelGGL((masked_layer_kernel<bf16_t, EPI_BERNOULLI>), dim3(row_tiles), dim3(NW * 64), 0, s, a);
+      else
+        hipLaunchKernelGGL((masked_layer_kernel<float, EPI_BERNOULLI>), dim3(row_tiles), dim3(NW * 64), 0, s, a);
+      prof_mark(m, m->L, true, s);
+      m->stats[2]++;
+    }
+    HIP_TRY(hipMemsetAsync(n_active, 0, sizeof(int), s));
+    hipLaunchKernelGGL(jgs_end_kernel, dim3(N), dim3(256), 0, s, x_out, m->jgs_xv, np, D, B, w.iters, state, k,
+                       (k == cap) ? 1 : 0, (cap < M) ? 1 : 0, n_active, w.flags);
+    m->stats[2]++;
+    HIP_TRY(hipMemcpyAsync((void*)&w.h_pin[1], n_active, sizeof(int), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    m->stats[3]++;
+    if (w.h_pin[1] == 0 || k == cap) break;
+  }
+  HIP_TRY(hipGetLastError());
+  if (iters_out) HIP_TRY(hipMemcpyAsync(iters_out, w.iters, (size_t)N * sizeof(int), hipMemcpyDeviceToDevice, s));
+  HIP_TRY(hipMemcpyAsync((void*)&w.h_pin[0], w.flags, sizeof(int), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  prof_collect(m);
+  m->stats[0] = k;
+  m->stats[1] = (int64_t)k * B * V;
+  if (w.h_pin[0] & 1)
+    return fail(MADE_ERR_NOT_CONVERGED, "samples were still changing after the last allowed iteration");
+  return MADE_OK;
 }
 
 #ifdef JM_TRACE

@@ -141,6 +141,12 @@ struct LayerArgs {
   int* changed;          // per-sample count of positions whose symbol changed
   int D;
   int t_lo, t_hi;        // only positions in [t_lo, t_hi) are re-drawn
+  // Jacobi-GS (Algorithm 2): the rows are "virtual samples" (block i, sample n) = row i * noise_mod + n, each
+  // block carrying its own mixed input.  diag_pos[row tile] is the one position that tile's block draws in
+  // this sub-step (-1: none), so the launch evaluates one unit tile per row tile; a virtual sample reads the
+  // noise of its real sample.  diag_pos == NULL: an ordinary launch.
+  const int* diag_pos;
+  int noise_mod, noise_n;
   RetireArgs retire;
 };
 
@@ -333,7 +339,8 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
       e_xold[j] = 0;
       if (col_live) {
         const size_t idx = (size_t)e_sample[j] * a.D + col;
-        e_noise[j] = a.noise[idx];
+        const int nrow = a.noise_mod > 0 ? min(e_sample[j] % a.noise_mod, a.noise_n - 1) : e_sample[j];
+        e_noise[j] = a.noise[(size_t)nrow * a.D + col];
         e_xold[j] = a.x[idx];
       }
     }
@@ -426,7 +433,15 @@ template <typename T, int EPI>
 __global__ __launch_bounds__(NW * 64) void masked_layer_kernel(LayerArgs a) {
   __shared__ float part[NW][TILE][TILE + 1];
   int rel_tile, row0;
-  if (item_to_tile(blockIdx.x, a.n_launch_tiles, a.row_tiles, rel_tile, row0)) {
+  if (EPI == EPI_BERNOULLI && a.diag_pos) {   // one unit tile per row tile (see LayerArgs::diag_pos)
+    const int j = a.diag_pos[blockIdx.x];
+    if (j >= 0) {
+      LayerArgs b = a;
+      b.t_lo = j;
+      b.t_hi = j + 1;
+      compute_tile<T, EPI, false>(b, j / TILE - a.tile_begin, blockIdx.x * TILE, a.rows, a.n_rows, part);
+    }
+  } else if (item_to_tile(blockIdx.x, a.n_launch_tiles, a.row_tiles, rel_tile, row0)) {
     const int n_rows = a.n_rows_ptr ? *a.n_rows_ptr : a.n_rows;
     if (row0 < n_rows) compute_tile<T, EPI, false>(a, rel_tile, row0, a.rows, n_rows, part);
   }
@@ -1674,6 +1689,47 @@ __global__ void init_state_kernel(const uint8_t* x_init, uint8_t* x, T* enc, int
     if (x) x[i] = v;
     const float e = (C == 1) ? (float)v : ((float)v - 128.0f) * (1.0f / 128.0f);
     enc[frag_offset<T>(n, t, enc_chunks)] = Elem<T>::from_f32(e);
+  }
+}
+
+// Jacobi-GS (Algorithm 2), start of an iteration: every block's virtual sample starts from the previous
+// iterate: xv[i * np + n] = x[n] for all blocks i, and the network input of the virtual samples is rebuilt.
+template <typename T>
+__global__ void jgs_begin_kernel(const uint8_t* x, uint8_t* xv, T* enc, int enc_chunks, int N, int np, int M, int D) {
+  const size_t total = (size_t)M * np * D;
+  for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+    const int v = (int)(e / D), t = (int)(e % D);
+    const int n = v % np;
+    const uint8_t val = n < N ? x[(size_t)n * D + t] : 0;
+    xv[e] = val;
+    enc[frag_offset<T>(v, t, enc_chunks)] = Elem<T>::from_f32((float)val);
+  }
+}
+
+// End of an iteration: block i's positions are taken from its virtual sample, compared with the previous
+// iterate (forward difference with tolerance 0, per sample) and stored.  One workgroup per sample.
+// state[n]: 0 = still iterating, 1 = stopped.  *n_active counts the samples that go on.
+__global__ void jgs_end_kernel(uint8_t* x, const uint8_t* xv, int np, int D, int block, int* iters, int* state,
+                               int k, int last, int flag_unconverged, int* n_active, int* flags) {
+  __shared__ int any_s;
+  const int n = blockIdx.x;
+  if (threadIdx.x == 0) any_s = 0;
+  __syncthreads();
+  int any = 0;
+  for (int t = threadIdx.x; t < D; t += blockDim.x) {
+    const uint8_t v = xv[((size_t)(t / block) * np + n) * D + t];
+    if (v != x[(size_t)n * D + t]) {
+      any = 1;
+      x[(size_t)n * D + t] = v;
+    }
+  }
+  if (any) any_s = 1;          // (benign race: every writer stores 1)
+  __syncthreads();
+  if (threadIdx.x == 0 && state[n] == 0) {
+    iters[n] = k;
+    if (!any_s || last) state[n] = 1;
+    else atomicAdd(n_active, 1);
+    if (any_s && last && flag_unconverged) atomicOr(flags, 1);   // still changing at a caller-given limit
   }
 }
 

@@ -84,6 +84,13 @@ class GpuModel:
         B.gs_jacobi_sample(self.h, dev(noise), N, None if x_init is None else dev(x_init), block, x, it)
         return x.cpu().numpy(), it.cpu().numpy()
 
+    def jacobi_gs(self, noise, block, x_init=None, max_iters=0):
+        N = noise.shape[0]
+        x = torch.empty((N, self.net.D), dtype=torch.uint8, device="cuda")
+        it = torch.empty((N,), dtype=torch.int32, device="cuda")
+        B.jacobi_gs_sample(self.h, dev(noise), N, None if x_init is None else dev(x_init), block, max_iters, x, it)
+        return x.cpu().numpy(), it.cpu().numpy()
+
     def sequential(self, noise, mode):
         N = noise.shape[0]
         x = torch.empty((N, self.net.D), dtype=torch.uint8, device="cuda")

@@ -82,6 +82,31 @@ def test_cfg4_categorical_full_size():
         assert_sample_parity(same, noise[:sub], xq[:sub], xs, mg)
 
 
+@pytest.mark.timeout(600)
+def test_cfg2_jacobi_gs_full_batch():
+    """Algorithm 2 on cfg2 at full batch: the result is certified for all 128 samples (one oracle pass), and a
+    sub-batch is compared with the oracle's Algorithm 2 run (iteration counts) and with its sequential run.
+    The virtual batch (13 blocks x 128 samples) goes through the hidden layers on the 32 x 32 tile kernels for
+    block 64 and on the 256 x 256 tile kernels for block 16 (49 x 128 = 6272 rows)."""
+    w = S.workload("cfg2")
+    net = S.make_network(w)
+    _, same = oracle_models(net)
+    noise = S.make_noise(w)
+    sub = 4
+    xs, mg = O.sequential_sample(same, noise[:sub])
+    with GpuModel(net) as g:
+        for block in (64, 16):
+            progress(f"cfg2 jacobi_gs block {block}")
+            x, it = g.jacobi_gs(noise, block)
+            st = g.stats()
+            assert_sample_parity(same, noise, x)
+            assert_sample_parity(same, noise[:sub], x[:sub], xs, mg)
+            ref = O.jacobi_gs_reference(same, noise[:sub], block)
+            clear = ref[3] >= MARGIN
+            assert (it[:sub][clear] == ref[1][clear]).all()
+            print(f"cfg2 jacobi_gs block {block}: iterations mean {it.mean():.2f} max {it.max()}, stats {st}")
+
+
 def test_cfg2_large_batch_vector_epilogue():
     """cfg2's network at batch 300: the 256 x 256 tile kernels with the 16-byte epilogue I/O (D % 16 == 0)."""
     import dataclasses

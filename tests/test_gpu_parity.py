@@ -9,7 +9,8 @@ from oracle import made_oracle as O
 from paper_2002_03629_amd import binding as B
 from paper_2002_03629_amd import synth as S
 
-from gpu_util import LOGIT_TOL, MARGIN, GpuModel, assert_logits_close, assert_sample_parity, dev, oracle_models
+from gpu_util import (LOGIT_TOL, MARGIN, GpuModel, assert_logits_close, assert_sample_parity, dev, oracle_models,
+                      progress)
 
 pytestmark = pytest.mark.gpu
 
@@ -113,6 +114,48 @@ def test_gs_jacobi_every_block_size(name):
         assert_sample_parity(same, noise, x, xs, margins)
         ref = O.gs_jacobi_reference(same, noise, 7, init)
         assert (it[ref[3] >= MARGIN] == ref[1][ref[3] >= MARGIN]).all()
+
+
+@pytest.mark.parametrize("name", ["cfg1", "small_f32", "small_bf16", "mid_bf16"])
+def test_jacobi_gs_every_block_size(name):
+    """Algorithm 2 against its oracle: same result as the sequential sampler, same iteration counts."""
+    w = S.workload(name)
+    net = S.make_network(w, with_bias=True)
+    _, same = oracle_models(net)
+    noise = S.make_noise(w)
+    xs, margins = O.sequential_sample(same, noise)
+    with GpuModel(net) as g:
+        for block in [1, 5, 16, 33, w.D - 1, w.D, w.D + 7]:
+            progress(f"jacobi_gs {name} block {block}")
+            x, it = g.jacobi_gs(noise, block)
+            assert_sample_parity(same, noise, x, xs, margins)
+            xr, it_ref, done, mm = O.jacobi_gs_reference(same, noise, block)
+            clear = mm >= MARGIN
+            assert (it[clear] == it_ref[clear]).all(), (block, it, it_ref)
+            M = -(-w.D // min(block, w.D))
+            assert (it >= 1).all() and (it <= M).all()
+            if block >= w.D:
+                assert (it == 1).all()
+        init = _symbols(w, np.random.default_rng(3), w.N)
+        x, it = g.jacobi_gs(noise, 7, init)
+        assert_sample_parity(same, noise, x, xs, margins)
+        ref = O.jacobi_gs_reference(same, noise, 7, init)
+        assert (it[ref[3] >= MARGIN] == ref[1][ref[3] >= MARGIN]).all()
+        # an iteration limit below M: the iterate after one iteration, and the not-converged status
+        ref1 = O.jacobi_gs_reference(same, noise, 7, None, 1)
+        if not ref1[2].all() and (ref1[3] >= MARGIN).all():
+            with pytest.raises(B.MadeError) as e:
+                g.jacobi_gs(noise, 7, None, 1)
+            assert e.value.code == B.MADE_ERR_NOT_CONVERGED
+
+
+def test_jacobi_gs_rejects_unsupported_models():
+    w = S.workload("small_cat_f32")
+    net = S.make_network(w)
+    with GpuModel(net) as g:
+        with pytest.raises(B.MadeError) as e:
+            g.jacobi_gs(S.make_noise(w), 4)
+        assert e.value.code == B.MADE_ERR_ARG
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
