@@ -300,7 +300,8 @@ def main() -> int:
             extras[name] = {"samples_per_s": N / dt, "ms_per_batch": dt * 1e3,
                             "same_output_as_jacobi": bool(torch.equal(xq, x_jac)),
                             "jacobi_speedup": (N * args.steps / elapsed) / (N / dt)}
-        for blk in ([] if conv else (w.block_sizes or [])):
+        # conv model: GS-Jacobi with blocks of whole image rows (4 / 8 / 16 rows of 96 states)
+        for blk in ([4 * 96, 8 * 96, 16 * 96] if conv else (w.block_sizes or [])):
             B.gs_jacobi_sample(model, noises[0], N, None, blk, xq, iters, stream)
             torch.cuda.synchronize()
             t0 = time.perf_counter()

@@ -35,6 +35,7 @@ class Workload:
     seed: int = SEED_BASE
     gain: float = 1.0           # extra factor on every weight (coupling strength sweeps)
     block_sizes: List[int] = field(default_factory=list)
+    real: bool = False          # continuous states with logistic conditionals (C = 2 outputs per position)
 
 
 def workload(name: str) -> Workload:
@@ -57,6 +58,13 @@ def workload(name: str) -> Workload:
                               gain=1.5),
         "small_cat_f32": Workload("small_cat_f32", 12, 5, [40], "f32", 7, "random", "fan_in", SEED_BASE + 15,
                                   gain=3.0),
+        # continuous states, logistic conditionals: the paper's own MADE (2 x 512 hidden, 100 images, T = 784)
+        "made_logistic": Workload("made_logistic", 784, 2, [512, 512], "bf16", 100, "random", "fan_in", SEED_BASE + 6,
+                                  real=True),
+        "small_real_f32": Workload("small_real_f32", 50, 2, [77, 45], "f32", 9, "random", "fan_in", SEED_BASE + 16,
+                                   gain=1.5, real=True),
+        "small_real_bf16": Workload("small_real_bf16", 100, 2, [203, 150], "bf16", 37, "random", "fan_in",
+                                    SEED_BASE + 17, gain=1.5, real=True),
     }
     return table[name]
 
@@ -166,6 +174,7 @@ class Network:
     degrees: List[np.ndarray]
     W: List[np.ndarray]
     b: List[Optional[np.ndarray]]
+    real: bool = False          # continuous states with logistic conditionals (then C = 2: mean and log-scale rows)
 
 
 def make_network(w: Workload, with_bias: bool = False) -> Network:
@@ -178,12 +187,20 @@ def make_network(w: Workload, with_bias: bool = False) -> Network:
         for W in Ws:
             b = (0.3 * g.standard_normal(size=W.shape[0])).astype(np.float32)
             bs.append(bf16_representable(b) if w.dtype == "bf16" else b)
-    return Network(w.D, w.C, list(w.hidden), w.dtype, degs, Ws, bs)
+    return Network(w.D, w.C, list(w.hidden), w.dtype, degs, Ws, bs, w.real)
+
+
+def logistic_noise(N: int, D: int, seed: int) -> np.ndarray:
+    """l[N, D] fp32 standard logistic variates log(u / (1 - u)), computed once in fp64 from clamped uniforms."""
+    u = np.clip(_rng(seed).random(size=(N, D)), 2.0 ** -24, 1.0 - 2.0 ** -24)
+    return np.log(u / (1.0 - u)).astype(np.float32)
 
 
 def make_noise(w: Workload, rep: int = 0, N: Optional[int] = None) -> np.ndarray:
     n = w.N if N is None else N
     seed = w.seed + 2 + 10 * rep
+    if w.real:
+        return logistic_noise(n, w.D, seed)
     return uniform_noise(n, w.D, seed) if w.C == 1 else gumbel_noise(n, w.D, w.C, seed)
 
 
