@@ -50,6 +50,32 @@ def cpu_baseline(w, net, noises, budget_s=12.0):
                       f"({done // sub} x {sub} of a batch of {noises[0].shape[0]}), {dt:.1f} s"}, xs0, sub
 
 
+def cpu_baseline_real(w, net, noises, budget_s=12.0):
+    """The logistic oracle's sequential sampler (Eq. 1) on whole batches until about budget_s seconds are spent."""
+    from oracle import logistic_oracle as LO
+    from oracle import made_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = 1
+    model = O.build_model(net.D, net.C, net.degrees, net.W, net.b, "bf16" if net.dtype == "bf16" else None)
+    LO.sequential_sample_real(model, noises[0][:1])
+    done, xs0 = 0, None
+    t0 = time.perf_counter()
+    for r in range(len(noises)):
+        xs = LO.sequential_sample_real(model, noises[r])
+        if r == 0:
+            xs0 = xs
+        done += noises[r].shape[0]
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    return {"value": done / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"oracle sequential_sample_real (numpy fp64, states and activations rounded as on the GPU) on "
+                      f"{done} samples, {dt:.1f} s"}, xs0, noises[0].shape[0]
+
+
 def cpu_baseline_conv(w, net, noise, budget_s=12.0):
     """The conv oracle's sequential sampler (Eq. 1) on a bounded sample: the first states of ONE image, one network
     evaluation per state exactly as conv_sequential_sample does it; every state costs the same, so the time per
@@ -106,6 +132,8 @@ def main() -> int:
                     help="batch size from which the 256 x 256 tile kernels are used (0 = library default)")
     ap.add_argument("--conv-rows", type=int, default=0,
                     help="image rows per workgroup of the conv model's k x k layers (0 = library default)")
+    ap.add_argument("--eps", type=float, default=0.0,
+                    help="forward-difference tolerance of Algorithm 1 (workloads with real states only)")
     ap.add_argument("--chains", type=int, default=0, help="sub-batches on separate streams (0 = library default)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="no timing: run 20 device copies of 64 MiB (calibration of FETCH_SIZE / WRITE_SIZE), then "
@@ -150,12 +178,16 @@ def main() -> int:
     n_noise = min(args.steps, 4 if conv else 32)
     noises_host = [S.make_conv_noise(w, rep=r) if conv else S.make_noise(w, rep=r) for r in range(n_noise)]
     noises = [torch.from_numpy(a).cuda() for a in noises_host]
-    x = torch.empty((N, D), dtype=torch.uint8, device="cuda")
+    real = (not conv) and w.real
+    x = torch.empty((N, D), dtype=torch.float32 if real else torch.uint8, device="cuda")
     iters = torch.empty((N,), dtype=torch.int32, device="cuda")
     stream = torch.cuda.current_stream()
 
     def step(i):
-        B.jacobi_sample(model, noises[i % n_noise], N, None, 0, x, iters, stream)
+        if real:
+            B.jacobi_sample_real(model, noises[i % n_noise], N, None, args.eps, 0, x, iters, stream)
+        else:
+            B.jacobi_sample(model, noises[i % n_noise], N, None, 0, x, iters, stream)
 
     if args.pmc_probe:
         src = torch.ones((16 << 20,), dtype=torch.float32, device="cuda")     # 64 MiB read + 64 MiB written per copy
@@ -258,6 +290,9 @@ def main() -> int:
         "config": {"workload": (f"{w.name}: masked conv net {w.H}x{w.W}x3 states, {w.n_conv} masked {w.k}x{w.k} layers of "
                                 f"{w.F} channels + 1x1 head, C={w.C}, batch={N}, Jacobi (Algorithm 1), seeded weights, "
                                 f"fixed Gumbel noise") if conv else
+                               (f"{w.name}: MADE D={D} hidden={w.hidden} real states, logistic conditionals, batch={N}, "
+                                f"Jacobi (Algorithm 1) with tolerance eps={args.eps}, seeded N(0,1/fan_in) weights, "
+                                f"random degrees, fixed logistic noise") if real else
                                (f"{w.name}: MADE D={D} hidden={w.hidden} C={w.C} batch={N} Jacobi (Algorithm 1), "
                                 f"seeded N(0,1/fan_in) weights, random degrees, fixed U(0,1) noise"),
                    "path": args.path},
@@ -282,7 +317,39 @@ def main() -> int:
 
     # ---- side measurements: on-GPU sequential sampler (speedup denominator) and GS-Jacobi
     x_jac = None
-    if not args.no_extras:
+    if not args.no_extras and real:
+        xq = torch.empty_like(x)
+        B.jacobi_sample_real(model, noises[0], N, None, 0.0, 0, x, iters, stream)
+        torch.cuda.synchronize()
+        x_jac = x.clone()
+        extras = {}
+        for mode, name in ((0, "sequential_whole_network"), (1, "sequential_lean")):
+            B.sequential_sample_real(model, noises[0], N, mode, xq, stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            reps = 3
+            for _ in range(reps):
+                B.sequential_sample_real(model, noises[0], N, mode, xq, stream)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / reps
+            extras[name] = {"samples_per_s": N / dt, "ms_per_batch": dt * 1e3,
+                            "max_abs_difference_to_jacobi_eps0": float((xq - x_jac).abs().max()),
+                            "jacobi_speedup": (N * args.steps / elapsed) / (N / dt)}
+        for eps in (0.0, 1e-3, 1e-2, 1e-1):               # the paper's trade of accuracy for iterations
+            B.jacobi_sample_real(model, noises[0], N, None, eps, 0, xq, iters, stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            reps = 20
+            for _ in range(reps):
+                B.jacobi_sample_real(model, noises[0], N, None, eps, 0, xq, iters, stream)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / reps
+            itc = iters.cpu().numpy()
+            extras[f"jacobi_eps{eps:g}"] = {"samples_per_s": N / dt, "ms_per_batch": dt * 1e3,
+                                           "iters_mean": float(itc.mean()), "iters_max": int(itc.max()),
+                                           "max_abs_difference_to_eps0": float((xq - x_jac).abs().max())}
+        result["extras"] = extras
+    elif not args.no_extras:
         xq = torch.empty_like(x)
         B.jacobi_sample(model, noises[0], N, None, 0, x, iters, stream)
         torch.cuda.synchronize()
@@ -337,6 +404,12 @@ def main() -> int:
             # early states depend on early states only: the oracle's first states are final
             result["cpu_baseline"]["gpu_matches_oracle_on_sample"] = bool(
                 np.array_equal(x_jac[:1, :n2].cpu().numpy(), xs))
+    elif not args.no_cpu_baseline and real:
+        base, xs, n2 = cpu_baseline_real(w, net, noises_host)
+        result["cpu_baseline"] = base
+        if x_jac is not None:
+            result["cpu_baseline"]["max_abs_difference_gpu_to_oracle_on_sample"] = float(
+                np.abs(x_jac[:n2].cpu().numpy() - xs).max())
     elif not args.no_cpu_baseline:
         base, xs, n2 = cpu_baseline(w, net, noises_host)
         result["cpu_baseline"] = base

@@ -50,6 +50,10 @@ typedef struct made_config {
   int32_t dtype;         /* MADE_F32: fp32 weights/activations; MADE_BF16: bf16 weights and
                             hidden activations (rounded to nearest even after bias+ReLU),
                             fp32 accumulation, fp32 logits                                */
+  int32_t real;          /* 0: discrete positions (above).  1: real-valued positions with logistic
+                            conditionals (the paper's own MADE, Appendix C.3); then C must be 2:
+                            output row 2t is the mean mu_t and row 2t+1 the log-scale a_t of
+                            position t, and the *_real entry points below are the ones to call */
 } made_config;
 
 /*
@@ -167,6 +171,26 @@ int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, const uint8_t
  */
 int jacobi_gs_sample(made_model* m, const float* noise, int32_t N, const uint8_t* x_init, int32_t block,
                      int32_t max_iters, uint8_t* x_out, int32_t* iters_out, void* stream);
+
+/*
+ * Models with real states (made_config.real = 1).  The recurrence (Eq. 1) is the inverse-CDF draw of a logistic
+ * conditional (Appendix A.3): s_t = mu_t + exp(clip(a_t, -6, 3)) * l_t, where (mu_t, a_t) are the network's two
+ * outputs for position t given s_{1:t-1} and l_t = log(u_t / (1 - u_t)) is the fixed noise (standard logistic
+ * variates).  A state enters the network as itself (rounded to bf16 with MADE_BF16).  Algorithm 1 / 3 run with
+ * the forward-difference tolerance eps of the paper (Sections 2.2, 4.2): per sample, the iteration (of a block)
+ * stops at the first k where no position moved by more than eps (max-norm), or at the proven bound.  eps = 0
+ * reproduces the sequential result of the same arithmetic exactly; eps > 0 trades accuracy for iterations.
+ *   noise  : device fp32 [N, D] standard logistic variates
+ *   x_init : device fp32 [N, D] or NULL (zeros);  x_out : device fp32 [N, D]
+ *   made_forward_params: params = device fp32 [N, D, 2] = (mu, a) of every position for the given states.
+ * Errors as for the discrete entry points (which refuse a model with real states, and vice versa).
+ */
+int made_forward_params(made_model* m, const float* x, int32_t N, float* params, void* stream);
+int sequential_sample_real(made_model* m, const float* noise, int32_t N, int32_t mode, float* x_out, void* stream);
+int jacobi_sample_real(made_model* m, const float* noise, int32_t N, const float* x_init, float eps,
+                       int32_t max_iters, float* x_out, int32_t* iters_out, void* stream);
+int gs_jacobi_sample_real(made_model* m, const float* noise, int32_t N, const float* x_init, int32_t block,
+                          float eps, float* x_out, int32_t* iters_out, void* stream);
 
 /*
  * made_last_stats -- counters of the most recent *_sample call on this model (host side):

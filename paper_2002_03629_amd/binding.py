@@ -18,7 +18,8 @@ MADE_OK, MADE_ERR_ARG, MADE_ERR_NOMEM, MADE_ERR_HIP, MADE_ERR_NOT_CONVERGED = 0,
 MADE_F32, MADE_BF16 = 0, 1
 
 EXPORTS = ["made_init", "made_conv_init", "made_free", "made_forward_logits", "sequential_sample", "jacobi_sample",
-           "gs_jacobi_sample", "jacobi_gs_sample", "made_last_stats", "made_set_profiling", "made_last_profile", "made_set_option",
+           "gs_jacobi_sample", "jacobi_gs_sample", "made_forward_params", "sequential_sample_real",
+           "jacobi_sample_real", "gs_jacobi_sample_real", "made_last_stats", "made_set_profiling", "made_last_profile", "made_set_option",
            "made_layer_nnz",
            "made_last_error"]
 
@@ -31,7 +32,7 @@ class MadeError(RuntimeError):
 
 class made_config(C.Structure):
     _fields_ = [("D", C.c_int32), ("C", C.c_int32), ("n_hidden", C.c_int32),
-                ("hidden", C.POINTER(C.c_int32)), ("dtype", C.c_int32)]
+                ("hidden", C.POINTER(C.c_int32)), ("dtype", C.c_int32), ("real", C.c_int32)]
 
 
 class made_conv_config(C.Structure):
@@ -64,6 +65,10 @@ def lib() -> C.CDLL:
         L.jacobi_sample.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
         L.gs_jacobi_sample.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
         L.jacobi_gs_sample.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, vp]
+        L.made_forward_params.argtypes = [vp, vp, i32, vp, vp]
+        L.sequential_sample_real.argtypes = [vp, vp, i32, i32, vp, vp]
+        L.jacobi_sample_real.argtypes = [vp, vp, i32, vp, C.c_float, i32, vp, vp, vp]
+        L.gs_jacobi_sample_real.argtypes = [vp, vp, i32, vp, i32, C.c_float, vp, vp, vp]
         L.made_last_stats.argtypes = [vp, i64p, i32]
         L.made_set_profiling.argtypes = [vp, i32]
         L.made_last_profile.argtypes = [vp, C.POINTER(C.c_double), i64p, i32]
@@ -105,11 +110,11 @@ def _stream(stream) -> Optional[int]:
 
 
 def made_init(D: int, Cn: int, hidden: Sequence[int], dtype: int, degrees: Sequence[np.ndarray],
-              W: Sequence[np.ndarray], b: Optional[Sequence[Optional[np.ndarray]]] = None) -> int:
+              W: Sequence[np.ndarray], b: Optional[Sequence[Optional[np.ndarray]]] = None, real: bool = False) -> int:
     """Returns the opaque model handle (an integer address)."""
     L = len(hidden)
     hid = np.ascontiguousarray(hidden, dtype=np.int32)
-    cfg = made_config(int(D), int(Cn), L, hid.ctypes.data_as(C.POINTER(C.c_int32)), int(dtype))
+    cfg = made_config(int(D), int(Cn), L, hid.ctypes.data_as(C.POINTER(C.c_int32)), int(dtype), 1 if real else 0)
     keep = []
     deg_arr = (C.POINTER(C.c_int32) * L)()
     for l in range(L):
@@ -206,6 +211,33 @@ def jacobi_gs_sample(model: int, noise, N: int, x_init, block: int, max_iters: i
                                   _ptr(x_out, torch.uint8), _ptr(iters_out, torch.int32), _stream(stream)))
 
 
+def made_forward_params(model: int, x, N: int, params, stream=None) -> None:
+    import torch
+    _check(lib().made_forward_params(model, _ptr(x, torch.float32), N, _ptr(params, torch.float32), _stream(stream)))
+
+
+def sequential_sample_real(model: int, noise, N: int, mode: int, x_out, stream=None) -> None:
+    import torch
+    _check(lib().sequential_sample_real(model, _ptr(noise, torch.float32), N, mode, _ptr(x_out, torch.float32),
+                                        _stream(stream)))
+
+
+def jacobi_sample_real(model: int, noise, N: int, x_init, eps: float, max_iters: int, x_out, iters_out=None,
+                       stream=None) -> None:
+    import torch
+    _check(lib().jacobi_sample_real(model, _ptr(noise, torch.float32), N, _ptr(x_init, torch.float32), float(eps),
+                                    max_iters, _ptr(x_out, torch.float32), _ptr(iters_out, torch.int32),
+                                    _stream(stream)))
+
+
+def gs_jacobi_sample_real(model: int, noise, N: int, x_init, block: int, eps: float, x_out, iters_out=None,
+                          stream=None) -> None:
+    import torch
+    _check(lib().gs_jacobi_sample_real(model, _ptr(noise, torch.float32), N, _ptr(x_init, torch.float32), block,
+                                       float(eps), _ptr(x_out, torch.float32), _ptr(iters_out, torch.int32),
+                                       _stream(stream)))
+
+
 def made_last_stats(model: int) -> dict:
     buf = (C.c_int64 * 5)()
     _check(lib().made_last_stats(model, buf, 5))
@@ -245,4 +277,4 @@ def made_layer_nnz(model: int, n_layers: int) -> List[int]:
 def model_from_network(net) -> int:
     """made_init from a synth.Network description."""
     return made_init(net.D, net.C, net.hidden, MADE_BF16 if net.dtype == "bf16" else MADE_F32, net.degrees, net.W,
-                     net.b)
+                     net.b, getattr(net, "real", False))

@@ -141,6 +141,8 @@ struct ConvNet {
 
 struct made_model {
   int arch = 0;                               // 0 masked MLP, 1 masked convolutional network
+  bool real = false;                          // MLP with real states and logistic conditionals (C = 2 rows per position)
+  float call_eps = 0.f;                       // forward-difference tolerance of the current *_real call
   ConvNet conv;
   int D = 0, C = 1, L = 0, dtype = MADE_F32, device = 0;
   std::vector<int> hidden;
@@ -378,6 +380,9 @@ static int validate_config(const made_config* cfg, const int32_t* const* degrees
     return fail(MADE_ERR_ARG, "made_init: n_hidden=%d out of range [1, 64] or hidden NULL", cfg->n_hidden);
   if (cfg->dtype != MADE_F32 && cfg->dtype != MADE_BF16) return fail(MADE_ERR_ARG, "made_init: unknown dtype %d", cfg->dtype);
   if ((int64_t)cfg->D * cfg->C > (int64_t)1 << 28) return fail(MADE_ERR_ARG, "made_init: D*C too large");
+  if (cfg->real != 0 && cfg->real != 1) return fail(MADE_ERR_ARG, "made_init: real=%d must be 0 or 1", cfg->real);
+  if (cfg->real && cfg->C != 2)
+    return fail(MADE_ERR_ARG, "made_init: a model with real states has C = 2 output rows per position, not %d", cfg->C);
   for (int l = 0; l < cfg->n_hidden; ++l) {
     if (cfg->hidden[l] < 1 || cfg->hidden[l] > (1 << 20))
       return fail(MADE_ERR_ARG, "made_init: hidden[%d]=%d out of range", l, cfg->hidden[l]);
@@ -399,6 +404,7 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
   if (!m) return fail(MADE_ERR_NOMEM, "made_init: host allocation failed");
   m->D = cfg->D;
   m->C = cfg->C;
+  m->real = cfg->real != 0;
   m->L = cfg->n_hidden;
   m->dtype = cfg->dtype;
   m->hidden.assign(cfg->hidden, cfg->hidden + cfg->n_hidden);
@@ -713,7 +719,7 @@ struct RowSet {            // which samples a pass covers
 
 struct SampleIO {          // what the sampling epilogue reads and writes
   const float* noise;
-  uint8_t* x;
+  uint8_t* x;              // symbols; for a model with real states this is a float [N, D] buffer
   int t_lo, t_hi;
   RetireArgs retire;       // retire.enabled = 0: no stop test after this pass (sequential sampling)
 };
@@ -841,7 +847,23 @@ static int run_output_sample(made_model* m, const RowSet& rs, const SampleIO& io
     tile_hi = (io.t_hi * C + TILE - 1) / TILE;
   }
   a.tile_begin = tile_lo;
-  if (C == 1) {
+  if (m->real) {
+    a.noise = io.noise;
+    a.xr = (float*)io.x;
+    a.eps = m->call_eps;
+    a.enc = m->ws.enc;
+    a.enc_chunks = m->layers[0].k_chunks;
+    a.changed = m->ws.changed;
+    a.D = m->D;
+    a.t_lo = io.t_lo;
+    a.t_hi = io.t_hi;
+    a.retire = io.retire;
+    prof_mark(m, m->L, false, s);
+    if (m->dtype == MADE_BF16) launch_layer_t<bf16_t, EPI_LOGISTIC>(a, tile_hi - tile_lo, row_tiles, s);
+    else launch_layer_t<float, EPI_LOGISTIC>(a, tile_hi - tile_lo, row_tiles, s);
+    prof_mark(m, m->L, true, s);
+    m->stats[2]++;
+  } else if (C == 1) {
     a.noise = io.noise;
     a.x = io.x;
     a.enc = m->ws.enc;
@@ -1058,6 +1080,17 @@ static int launch_init_state(made_model* m, const uint8_t* x_init, uint8_t* x, i
     HIP_TRY(hipGetLastError());
     return MADE_OK;
   }
+  if (m->real) {
+    if (m->dtype == MADE_BF16)
+      hipLaunchKernelGGL((init_state_real_kernel<bf16_t>), dim3(blocks), dim3(256), 0, s, (const float*)x_init, (float*)x,
+                         (bf16_t*)m->ws.enc, m->layers[0].k_chunks, N, m->D);
+    else
+      hipLaunchKernelGGL((init_state_real_kernel<float>), dim3(blocks), dim3(256), 0, s, (const float*)x_init, (float*)x,
+                         (float*)m->ws.enc, m->layers[0].k_chunks, N, m->D);
+    m->stats[2]++;
+    HIP_TRY(hipGetLastError());
+    return MADE_OK;
+  }
   if (m->dtype == MADE_BF16)
     hipLaunchKernelGGL((init_state_kernel<bf16_t>), dim3(blocks), dim3(256), 0, s, x_init, x, (bf16_t*)m->ws.enc,
                        m->layers[0].k_chunks, N, m->D, m->C);
@@ -1069,8 +1102,12 @@ static int launch_init_state(made_model* m, const uint8_t* x_init, uint8_t* x, i
   return MADE_OK;
 }
 
-static int check_call(made_model* m, const void* noise, int32_t N, const void* x_out, const char* who) {
+static int check_call(made_model* m, const void* noise, int32_t N, const void* x_out, const char* who,
+                      bool real_entry = false) {
   if (!m) return fail(MADE_ERR_ARG, "%s: model is NULL", who);
+  if (m->real != real_entry)
+    return fail(MADE_ERR_ARG, m->real ? "%s: the model has real states, use the *_real entry points"
+                                      : "%s: the model has discrete states", who);
   if (N < 0) return fail(MADE_ERR_ARG, "%s: N=%d is negative", who, N);
   if (N > (1 << 22)) return fail(MADE_ERR_ARG, "%s: N=%d exceeds 2^22", who, N);
   if (N > 0 && (!noise || !x_out)) return fail(MADE_ERR_ARG, "%s: NULL noise or output pointer", who);
@@ -1349,7 +1386,7 @@ extern "C" int sequential_sample(made_model* m, const float* noise, int32_t N, i
 static int run_persistent(made_model* m, const float* noise, int N, const uint8_t* x_init, uint8_t* x, int block,
                           int cap, bool flag_unconverged, int32_t* iters_out, hipStream_t s, bool* done) {
   *done = false;
-  if (m->arch != 0 || !m->use_persistent || m->persist_grid <= 0 || N > PERSIST_MAX_N) return MADE_OK;
+  if (m->arch != 0 || m->real || !m->use_persistent || m->persist_grid <= 0 || N > PERSIST_MAX_N) return MADE_OK;
   Workspace& w = m->ws;
   PersistArgs p;
   memset(&p, 0, sizeof p);
@@ -1454,6 +1491,90 @@ extern "C" int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, co
     blocks.push_back(make_block(m, a, b, b - a, true));
   }
   return run_chains(m, blocks, noise, x_init, x_out, N, false, iters_out, s);
+}
+
+// ------------------------------------------------------------------------------------------------
+// entry points of models with real states (logistic conditionals); same schedulers as above, the symbol
+// buffers are float [N, D] and a position counts as changed when it moved by more than eps
+// ------------------------------------------------------------------------------------------------
+extern "C" int made_forward_params(made_model* m, const float* x, int32_t N, float* params, void* stream) {
+  TRY(check_call(m, x, N, params, "made_forward_params", true));
+  if (N == 0) return MADE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  const bool was_profiling = m->profiling;
+  m->profiling = false;
+  TRY(ensure_workspace(m, N, false));
+  TRY(launch_init_state(m, (const uint8_t*)x, nullptr, N, s));
+  RowSet rs{nullptr, nullptr, N};
+  TRY(run_hidden(m, rs, nullptr, -1, s));
+  LayerArgs a = base_args(m, m->L, m->ws.act[m->L - 1], rs);
+  a.out = params;
+  a.ldo = m->D * m->C;
+  const int big_saved = m->big_batch;
+  m->big_batch = 1 << 30;
+  launch_layer<EPI_LOGITS>(m, m->L, a, m->layers[m->L].n_tiles, (N + TILE - 1) / TILE, s);
+  m->big_batch = big_saved;
+  m->profiling = was_profiling;
+  HIP_TRY(hipGetLastError());
+  return MADE_OK;
+}
+
+extern "C" int sequential_sample_real(made_model* m, const float* noise, int32_t N, int32_t mode, float* x_out,
+                                      void* stream) {
+  TRY(check_call(m, noise, N, x_out, "sequential_sample_real", true));
+  if (mode != 0 && mode != 1) return fail(MADE_ERR_ARG, "sequential_sample_real: mode=%d must be 0 or 1", mode);
+  if (N == 0) return MADE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  memset(m->stats, 0, sizeof m->stats);
+  m->ev_layer.clear();
+  m->call_eps = 0.f;
+  TRY(ensure_workspace(m, N, true));
+  std::vector<Block> blocks;
+  blocks.reserve(m->D);
+  for (int p = 0; p < m->D; ++p) {
+    Block blk = make_block(m, p, p + 1, 1, mode == 1);
+    blk.stop_test = false;
+    blk.whole_network = (mode == 0);
+    blocks.push_back(std::move(blk));
+  }
+  TRY(run_chains(m, blocks, noise, nullptr, (uint8_t*)x_out, N, false, nullptr, s));
+  m->stats[0] = m->D;
+  m->stats[1] = (int64_t)m->D * N;
+  return MADE_OK;
+}
+
+extern "C" int jacobi_sample_real(made_model* m, const float* noise, int32_t N, const float* x_init, float eps,
+                                  int32_t max_iters, float* x_out, int32_t* iters_out, void* stream) {
+  TRY(check_call(m, noise, N, x_out, "jacobi_sample_real", true));
+  if (!(eps >= 0.f)) return fail(MADE_ERR_ARG, "jacobi_sample_real: eps must be >= 0");
+  if (N == 0) return MADE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  memset(m->stats, 0, sizeof m->stats);
+  m->ev_layer.clear();
+  m->call_eps = eps;
+  TRY(ensure_workspace(m, N, true));
+  const int cap = (max_iters <= 0 || max_iters > m->D) ? m->D : max_iters;
+  std::vector<Block> blocks(1, make_block(m, 0, m->D, cap, false));
+  return run_chains(m, blocks, noise, (const uint8_t*)x_init, (uint8_t*)x_out, N, cap < m->D, iters_out, s);
+}
+
+extern "C" int gs_jacobi_sample_real(made_model* m, const float* noise, int32_t N, const float* x_init, int32_t block,
+                                     float eps, float* x_out, int32_t* iters_out, void* stream) {
+  TRY(check_call(m, noise, N, x_out, "gs_jacobi_sample_real", true));
+  if (block < 1) return fail(MADE_ERR_ARG, "gs_jacobi_sample_real: block=%d must be >= 1", block);
+  if (!(eps >= 0.f)) return fail(MADE_ERR_ARG, "gs_jacobi_sample_real: eps must be >= 0");
+  if (N == 0) return MADE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  memset(m->stats, 0, sizeof m->stats);
+  m->ev_layer.clear();
+  m->call_eps = eps;
+  TRY(ensure_workspace(m, N, true));
+  std::vector<Block> blocks;
+  for (int a = 0; a < m->D; a += block) {
+    const int b = std::min(a + block, m->D);
+    blocks.push_back(make_block(m, a, b, b - a, true));
+  }
+  return run_chains(m, blocks, noise, (const uint8_t*)x_init, (uint8_t*)x_out, N, false, iters_out, s);
 }
 
 template <typename P>

@@ -90,7 +90,8 @@ constexpr int PD = JM_PD;  // K chunks a wave keeps in flight (all their loads a
 static_assert(PD >= 1 && PD <= 8, "prefetch depth must be 1..8");
 constexpr int XCDS = 8;    // workgroup i is dispatched to XCD i % 8; each XCD has its own L2
 
-enum Epilogue { EPI_RELU = 0, EPI_LOGITS = 1, EPI_BERNOULLI = 2 };
+enum Epilogue { EPI_RELU = 0, EPI_LOGITS = 1, EPI_BERNOULLI = 2, EPI_LOGISTIC = 3 };
+constexpr float LOGISTIC_A_LO = -6.0f, LOGISTIC_A_HI = 3.0f;   // the log-scale output is clipped to this range
 
 // What the last workgroup of a pass's final kernel does once every workgroup is done: retire the
 // samples that did not change and tell the host how many are left (see retire_tail).
@@ -147,6 +148,11 @@ struct LayerArgs {
   // noise of its real sample.  diag_pos == NULL: an ordinary launch.
   const int* diag_pos;
   int noise_mod, noise_n;
+  // EPI_LOGISTIC (continuous states, logistic conditionals): output rows 2t / 2t+1 are the mean and the
+  // log-scale of position t; x_t = mean + exp(clip(log-scale)) * l_t with l = noise (standard logistic
+  // variates); a position counts as changed when it moved by more than eps.  t_lo / t_hi are positions.
+  float* xr;             // [sample, D] real states, updated in place
+  float eps;
   RetireArgs retire;
 };
 
@@ -331,7 +337,21 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
   }
   float e_noise[EPT];
   uint8_t e_xold[EPT];
-  const bool col_live = EPI == EPI_BERNOULLI && col >= a.t_lo && col < a.t_hi;
+  float e_xr[EPT];
+  const int pos = EPI == EPI_LOGISTIC ? (col >> 1) : col;     // the position this output column belongs to
+  const bool col_live = (EPI == EPI_BERNOULLI || EPI == EPI_LOGISTIC) && pos >= a.t_lo && pos < a.t_hi;
+  if (EPI == EPI_LOGISTIC) {
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+      e_noise[j] = 0.f;
+      e_xr[j] = 0.f;
+      if (col_live && (col & 1) == 0) {
+        const size_t idx = (size_t)e_sample[j] * a.D + pos;
+        e_noise[j] = a.noise[idx];
+        e_xr[j] = a.xr[idx];
+      }
+    }
+  }
   if (EPI == EPI_BERNOULLI) {
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
@@ -393,6 +413,24 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
       if (row_ok) publish<COH>((T*)a.out + frag_offset<T>(sample, col, a.out_chunks), Elem<T>::from_f32(fmaxf(v, 0.f)));
     } else if (EPI == EPI_LOGITS) {
       if (row_ok && col < a.n_cols) ((float*)a.out)[(size_t)sample * a.ldo + col] = v;
+    } else if (EPI == EPI_LOGISTIC) {
+      // even lane: mean of position `pos`, odd lane: its log-scale
+      const float a_log = __shfl_xor(v, 1);
+      int cnt = 0;
+      if (row_ok && col_live && (col & 1) == 0) {
+        const float xn = v + expf(fminf(fmaxf(a_log, LOGISTIC_A_LO), LOGISTIC_A_HI)) * e_noise[j];
+        if (xn != e_xr[j]) {
+          publish<COH>(a.xr + (size_t)sample * a.D + pos, xn);
+          publish<COH>((T*)a.enc + frag_offset<T>(sample, pos, a.enc_chunks), Elem<T>::from_f32(xn));
+        }
+        cnt = !(fabsf(xn - e_xr[j]) <= a.eps);     // (a NaN counts as changed)
+      }
+      cnt += __shfl_xor(cnt, 1);
+      cnt += __shfl_xor(cnt, 2);
+      cnt += __shfl_xor(cnt, 4);
+      cnt += __shfl_xor(cnt, 8);
+      cnt += __shfl_xor(cnt, 16);
+      if (cc == 0 && cnt > 0) count_changed(&a.changed[sample], cnt);
     } else {  // EPI_BERNOULLI: x_t = 1 iff u_t < sigmoid(z_t); count changes per sample
       int cnt = 0;
       if (row_ok && col_live) {
@@ -445,7 +483,7 @@ __global__ __launch_bounds__(NW * 64) void masked_layer_kernel(LayerArgs a) {
     const int n_rows = a.n_rows_ptr ? *a.n_rows_ptr : a.n_rows;
     if (row0 < n_rows) compute_tile<T, EPI, false>(a, rel_tile, row0, a.rows, n_rows, part);
   }
-  if (EPI == EPI_BERNOULLI && a.retire.enabled) finish_pass(a.retire, gridDim.x);
+  if ((EPI == EPI_BERNOULLI || EPI == EPI_LOGISTIC) && a.retire.enabled) finish_pass(a.retire, gridDim.x);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1730,6 +1768,19 @@ __global__ void jgs_end_kernel(uint8_t* x, const uint8_t* xv, int np, int D, int
     if (!any_s || last) state[n] = 1;
     else atomicAdd(n_active, 1);
     if (any_s && last && flag_unconverged) atomicOr(flags, 1);   // still changing at a caller-given limit
+  }
+}
+
+// Start of a call on a model with real states: x = x_init (or zeros) and the network input (the states
+// themselves, rounded to the model's element type).
+template <typename T>
+__global__ void init_state_real_kernel(const float* x_init, float* x, T* enc, int enc_chunks, int N, int D) {
+  const size_t total = (size_t)N * D;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int n = (int)(i / D), t = (int)(i % D);
+    const float v = x_init ? x_init[i] : 0.f;
+    if (x) x[i] = v;
+    enc[frag_offset<T>(n, t, enc_chunks)] = Elem<T>::from_f32(v);
   }
 }
 
