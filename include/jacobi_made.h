@@ -232,9 +232,12 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   layers with 256 x 256 workgroup tiles staged through LDS instead of 32 x 32 tiles (on the D = 784,
  *   2 x 2000 network the two cross over near 5000 samples).
  *   MADE_OPT_CONV_ROWS (default 4; 2 or 4): image rows per workgroup of the convolutional model's k x k layers.
+ *   MADE_OPT_PREFIX_CACHE (default 1): GS-Jacobi on the masked MLP keeps the activations of the hidden units whose
+ *   inputs all lie before the current block (degree <= block start: they are final) after the block's first
+ *   pass and only re-evaluates the units behind them; 0 re-evaluates every visible unit in every pass.
  */
 enum { MADE_OPT_PERSISTENT = 1, MADE_OPT_FUSED_CATEGORICAL = 2, MADE_OPT_CHAINS = 3, MADE_OPT_BIG_TILE_BATCH = 4,
-       MADE_OPT_CONV_ROWS = 5 };
+       MADE_OPT_CONV_ROWS = 5, MADE_OPT_PREFIX_CACHE = 6 };
 int made_set_option(made_model* m, int32_t option, int32_t value);
 
 /*

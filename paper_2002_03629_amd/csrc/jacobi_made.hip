@@ -167,6 +167,7 @@ struct made_model {
   std::vector<int64_t> prof_launches;         // [L+1]
   std::vector<int64_t> nnz;                   // [L+1] visible (mask = 1) weights per layer
   int persist_grid = 0;                       // workgroups of the persistent kernel (0 = not usable)
+  bool prefix_cache = true;                   // made_set_option(MADE_OPT_PREFIX_CACHE)
   int big_batch = 4096;                       // made_set_option(MADE_OPT_BIG_TILE_BATCH); measured crossover ~5000
   int n_chains = 1;                           // made_set_option(MADE_OPT_CHAINS)
   int fused_categorical = 1;                  // made_set_option(MADE_OPT_FUSED_CATEGORICAL)
@@ -345,6 +346,10 @@ extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
   }
   if (option == MADE_OPT_FUSED_CATEGORICAL) {
     m->fused_categorical = value != 0;
+    return MADE_OK;
+  }
+  if (option == MADE_OPT_PREFIX_CACHE) {
+    m->prefix_cache = value != 0;
     return MADE_OK;
   }
   if (option == MADE_OPT_CONV_ROWS) {
@@ -810,7 +815,10 @@ static LayerArgs base_args(const made_model* m, int l, const void* A, const RowS
 
 // Hidden layers for the samples of `rs`.  unit_limit[l] < 0 means the whole layer; otherwise only the
 // first unit_limit[l] (degree-sorted) units are evaluated, reading only the first in_limit inputs.
-static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, int in_limit0, hipStream_t s) {
+// unit_first (optional): units below unit_first[l] are frozen -- their inputs are final and their activations
+// are already in the layer's buffer from an earlier pass -- so only the tiles from there on are evaluated.
+static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, int in_limit0, hipStream_t s,
+                      const int* unit_first = nullptr) {
   const int row_tiles = (rs.n_rows + TILE - 1) / TILE;
   const int kc = chunk_elems(m);
   int in_limit = in_limit0;
@@ -822,8 +830,9 @@ static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, in
     int tiles = ly.n_tiles;
     if (unit_limit && unit_limit[l] >= 0) tiles = std::min(tiles, (unit_limit[l] + TILE - 1) / TILE);
     if (in_limit >= 0) a.k_cap = std::min(ly.in_pad, round_up(in_limit, kc));
-    if (tiles > 0) {
-      launch_layer<EPI_RELU>(m, l, a, tiles, row_tiles, s);
+    if (unit_first) a.tile_begin = std::min(tiles, unit_first[l] / TILE);
+    if (tiles - a.tile_begin > 0) {
+      launch_layer<EPI_RELU>(m, l, a, tiles - a.tile_begin, row_tiles, s);
       m->stats[2]++;
     }
     in_limit = (unit_limit && unit_limit[l] >= 0) ? unit_limit[l] : -1;
@@ -1171,6 +1180,8 @@ struct Block {
   bool whole_network = false;     // evaluate every output tile even though only [a, b) is re-drawn
   bool limited = false;           // evaluate only hidden units of degree < b (1-based), see run_hidden
   std::vector<int> hidden_limit;  // [L] when limited
+  std::vector<int> hidden_frozen; // [L] when limited: units of degree <= a, whose inputs are positions before
+                                  // the block: final, so their activations stay valid after the block's first pass
   int in_limit = -1, out_k_limit = -1;
 };
 
@@ -1185,6 +1196,8 @@ static Block make_block(const made_model* m, int a, int b, int cap, bool limited
     // and inputs of index <= b - 1
     blk.hidden_limit.resize(m->L);
     for (int l = 0; l < m->L; ++l) blk.hidden_limit[l] = m->cnt_lt[l][b];
+    blk.hidden_frozen.resize(m->L);
+    for (int l = 0; l < m->L; ++l) blk.hidden_frozen[l] = m->cnt_lt[l][std::min(a + 1, m->D)];
     blk.in_limit = b - 1;
     blk.out_k_limit = blk.hidden_limit[m->L - 1];
   }
@@ -1234,7 +1247,9 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
   if (m->arch == 1) {
     TRY(run_conv_pass(m, c.count, io, k == 1, blk.whole_network, s));
   } else {
-    TRY(run_hidden(m, rs, blk.limited ? blk.hidden_limit.data() : nullptr, blk.in_limit, s));
+    // (after a block's first pass the frozen prefix of every hidden layer is reused, not recomputed)
+    TRY(run_hidden(m, rs, blk.limited ? blk.hidden_limit.data() : nullptr, blk.in_limit, s,
+                   (blk.limited && k > 1 && m->prefix_cache) ? blk.hidden_frozen.data() : nullptr));
     TRY(run_output_sample(m, rs, io, blk.whole_network, blk.out_k_limit, s));
   }
   c.k_enq = k;

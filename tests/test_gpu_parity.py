@@ -114,6 +114,11 @@ def test_gs_jacobi_every_block_size(name):
         assert_sample_parity(same, noise, x, xs, margins)
         ref = O.gs_jacobi_reference(same, noise, 7, init)
         assert (it[ref[3] >= MARGIN] == ref[1][ref[3] >= MARGIN]).all()
+        # the frozen-prefix reuse changes no bit: same symbols and pass counts with it switched off
+        x_on, it_on = g.gs_jacobi(noise, 16)
+        B.made_set_option(g.h, B.MADE_OPT_PREFIX_CACHE, 0)
+        x_off, it_off = g.gs_jacobi(noise, 16)
+        assert (x_on == x_off).all() and (it_on == it_off).all()
 
 
 @pytest.mark.parametrize("name", ["cfg1", "small_f32", "small_bf16", "mid_bf16"])
