@@ -4,7 +4,7 @@ binary MADE (D = 784, 2 x 2000 hidden, bf16, batch 128), synthetic seeded weight
 
 One "step" = one jacobi_sample call on one batch whose noise is already resident in HBM: every
 pass of the whole masked network, the sampling epilogue, the per-sample stop test and the final
-synchronisation are inside the timed region.  Prints ONE JSON line (see README).
+synchronisation are inside the timed region.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -140,8 +140,8 @@ def main() -> int:
                          "20 steps; meant to run under `rocprofv3 --pmc ...`")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (samples are independent systems; see DESIGN.md "
-              "for how the path would shard). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on exactly one GPU (samples are independent systems, so a batch would "
+              "shard without any exchange). Run with --gpus 1.", file=sys.stderr)
         return 2
 
     import torch

@@ -3,7 +3,7 @@
 // One Jacobi pass (the loop body of Algorithm 1) is: every hidden masked layer, then the output
 // masked layer whose epilogue draws the symbols from the fixed noise (Appendix A.3) and counts,
 // per sample, how many positions changed (the forward difference of Section 2.2.1 with
-// tolerance 0).  A small kernel then retires unchanged samples from the active list.
+// tolerance 0).  The last workgroup of that kernel retires unchanged samples from the active list.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -302,8 +302,8 @@ __device__ __forceinline__ void chunk_group(const uint4* Ap, const uint4* Wp, in
 // per K chunk holds 64 bytes of each, the h-th half of the chunk.  The MFMA contracts lane-held K
 // slices of A against the same slices of B, so which physical K a slot carries does not matter as
 // long as both operands agree.  Both operands live in the fragment-major layout described at
-// frag_offset, so every wave-wide load is one contiguous kilobyte.  At batch sizes around 100 a tile's whole K range is only a few hundred KB, so the
-// work is bound by memory latency, not by bandwidth or MFMA rate: the waves of a workgroup take K
+// frag_offset, so every wave-wide load is one contiguous kilobyte.  At batch sizes around 100 a tile's whole K
+// range is only a few hundred KB, so the work is bound by memory latency, not by bandwidth or MFMA rate: the waves of a workgroup take K
 // chunks round-robin and each issues the loads of up to PD chunks before its first MFMA, which puts
 // most of the tile in flight at once.  Partial tiles are summed through LDS in a fixed order
 // (deterministic results).
@@ -948,10 +948,12 @@ __global__ __launch_bounds__(NW * 64) void persistent_sampler_kernel(PersistArgs
 // exactly once (this layer is the model's HBM stream: 2 GiB dense for D = 1024, K = 4096, of which the
 // degree-sorted prefix structure lets it skip about half).  Each of the 4 waves owns 64 classes
 // (two 32-row weight tiles) against both 32-sample tiles: 4 accumulator tiles, no split of K, so the
-// sum order is fixed.  The MFMA takes the SAMPLES as its row operand: an accumulator lane then holds one
-// class of 16 samples, so the noise is read in whole 128-byte lines; the 256-way argmax is a compare of the
-// lane's two classes, a transposing butterfly over the 32 lanes of a half-wave and a 4-entry combine
-// through LDS.  Positions with the longest visible prefix are scheduled first.
+// sum order is fixed.  The MFMA takes the WEIGHTS as its row operand: an accumulator lane then holds
+// 16 classes of one sample, the noise comes in 16-byte loads, and the 256-way argmax is 32 in-register
+// compares, one exchange between the half-waves and a 4-entry combine through LDS.  (With the samples as row
+// operand a lane holds one class of 16 samples and reads the noise 4 bytes at a time, whole 128-byte lines per
+// half-wave: measured 1.5 TB/s on the noise stream against 4.2 TB/s for the 16-byte pattern.)  Positions with
+// the longest visible prefix are scheduled first.
 // ------------------------------------------------------------------------------------------------
 constexpr int CAT_C = 256;
 constexpr int CAT_WAVES = 4;
@@ -997,11 +999,11 @@ __device__ __forceinline__ void cat_group(const uint4* W0, const uint4* W1, cons
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int p = 0; p < CNT; ++p) {
-    mfma_chunk<T>(a0[p], w0[p], acc[0][0]);
-    mfma_chunk<T>(a0[p], w1[p], acc[1][0]);
+    mfma_chunk<T>(w0[p], a0[p], acc[0][0]);
+    mfma_chunk<T>(w1[p], a0[p], acc[1][0]);
     if (TWO) {
-      mfma_chunk<T>(a1[p], w0[p], acc[0][1]);
-      mfma_chunk<T>(a1[p], w1[p], acc[1][1]);
+      mfma_chunk<T>(w0[p], a1[p], acc[0][1]);
+      mfma_chunk<T>(w1[p], a1[p], acc[1][1]);
     }
   }
 }
@@ -1051,56 +1053,41 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
     else
       cat_stream<T, false>(W0, W1, A0, A1, n_chunks, acc);
 
-    // acc[q][j][i]: sample row 8*(i/4) + 4*h + i%4 of sample tile j, class (wave*2 + q)*32 + r.
-    // A lane's noise loads are then 4-byte reads that 32 lanes make to one 128-byte line (the noise is the
-    // larger stream of the convolutional model).  Element m = 16*j + i of a lane is one sample's best value
-    // among the lane's two classes; a transposing butterfly over the 32 lanes of a half-wave (each step the
-    // lanes of a pair split their elements between them and merge the partner's) leaves lane r with the
-    // half-wave's winner of element m = r.
-    const float b0 = a.bias[(size_t)t * CAT_C + wave * 64 + r];
-    const float b1 = a.bias[(size_t)t * CAT_C + wave * 64 + 32 + r];
-    float val[32];
-    int idx[32];
-    static_for<2>([&](auto J) {
-      constexpr int j = decltype(J)::value;
-      static_for<16>([&](auto I) {
-        constexpr int i = decltype(I)::value;
-        constexpr int m = 16 * j + i;
-        if (j == 0 || two) {
-          const int sample = __shfl(j ? n1 : n0, 8 * (i >> 2) + 4 * h + (i & 3));
-          const float* gp = a.noise + ((size_t)sample * a.D + t) * CAT_C + wave * 64 + r;
-          const float v0 = (acc[0][j][i] + b0) + gp[0];
-          const float v1 = (acc[1][j][i] + b1) + gp[32];
-          const bool second = v1 > v0;            // strict: the lower class keeps a tie
-          val[m] = second ? v1 : v0;
-          idx[m] = wave * 64 + r + (second ? 32 : 0);
-        } else {
-          val[m] = -INFINITY;
-          idx[m] = 0x7fffffff;
+    // acc[q][j][i]: class (wave*2 + q)*32 + 8*(i/4) + 4*h + i%4 of sample tile j's row r
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      if (j == 0 || two) {
+        const int sample = j ? n1 : n0;
+        const float* gp = a.noise + ((size_t)sample * a.D + t) * CAT_C;
+        const float* bp = a.bias + (size_t)t * CAT_C;
+        float best = -INFINITY;
+        int best_c = 0x7fffffff;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+#pragma unroll
+          for (int i4 = 0; i4 < 4; ++i4) {
+            const int cb = (wave * 2 + q) * 32 + 8 * i4 + 4 * h;
+            const float4 gv = *(const float4*)(gp + cb);
+            const float4 bv = *(const float4*)(bp + cb);
+            const float v0 = (acc[q][j][i4 * 4 + 0] + bv.x) + gv.x;
+            const float v1 = (acc[q][j][i4 * 4 + 1] + bv.y) + gv.y;
+            const float v2 = (acc[q][j][i4 * 4 + 2] + bv.z) + gv.z;
+            const float v3 = (acc[q][j][i4 * 4 + 3] + bv.w) + gv.w;
+            // classes are visited in increasing order, so a strict compare keeps the lowest index of a tie
+            if (v0 > best) { best = v0; best_c = cb; }
+            if (v1 > best) { best = v1; best_c = cb + 1; }
+            if (v2 > best) { best = v2; best_c = cb + 2; }
+            if (v3 > best) { best = v3; best_c = cb + 3; }
+          }
         }
-      });
-    });
-    static_for<5>([&](auto S) {
-      constexpr int bit = 16 >> decltype(S)::value;     // lane bit of this step; 2 * bit elements are left
-      const bool up = (r & bit) != 0;
-      static_for<bit>([&](auto K) {
-        constexpr int k = decltype(K)::value;
-        const float send_v = up ? val[k] : val[k + bit];
-        const int send_i = up ? idx[k] : idx[k + bit];
-        float keep_v = up ? val[k + bit] : val[k];
-        int keep_i = up ? idx[k + bit] : idx[k];
-        const float ov = __shfl_xor(send_v, bit);
-        const int oi = __shfl_xor(send_i, bit);
-        if (ov > keep_v || (ov == keep_v && oi < keep_i)) { keep_v = ov; keep_i = oi; }
-        val[k] = keep_v;
-        idx[k] = keep_i;
-      });
-    });
-    {
-      const int j = r >> 4, i = r & 15;
-      const int slot = 32 * j + 8 * (i >> 2) + 4 * h + (i & 3);
-      sm_val[wave][slot] = val[0];
-      sm_idx[wave][slot] = idx[0];
+        const float ob = __shfl_xor(best, 32);
+        const int oc = __shfl_xor(best_c, 32);
+        if (ob > best || (ob == best && oc < best_c)) { best = ob; best_c = oc; }
+        if (h == 0) {
+          sm_val[wave][32 * j + r] = best;
+          sm_idx[wave][32 * j + r] = best_c;
+        }
+      }
     }
     __syncthreads();
     if (threadIdx.x < 64) {   // (wave 0: one lane per sample row of the pair)
