@@ -1477,15 +1477,16 @@ struct ConvHeadArgs {
   RetireArgs retire;
 };
 
+constexpr int HEAD_PATCH_PITCH = TILE + 4;   // floats per pixel row of the noise patch (16-byte reads of 16 lanes
+                                             // then cover all 64 banks)
+
 // 1 x 1 head + Gumbel-max draw + change detection of the convolutional model.  A workgroup is bound to one
 // colour and first copies that colour's 256 x F weight block (and bias) to LDS; after that its 4 waves work
 // independently: a wave takes one row of 32 pixels at a time (rows wave, wave + stride, ...) and multiplies it
 // with one 32-class tile after the other.  The classes are the MFMA's row operand, so lane (r, h) holds 16
 // classes of pixel r per tile: the 256-way argmax is a running (value, class) pair per lane plus one exchange
-// between the half-waves, and the lane's noise comes in 16-byte loads.  The noise is the large stream of this
-// launch (100 MB per pass at batch 32 against 8 MB of activations), and 16-byte loads are what the memory
-// system needs: measured on this access pattern 4.2 TB/s, against 1.5 TB/s for 4-byte loads of whole 128-byte
-// lines (pixels as row operand) and 5.5 TB/s for a plain linear read.  No barrier inside the loop.  FT = F / 32.
+// between the half-waves.  The noise is the large stream of this launch (100 MB per pass at batch 32 against
+// 8 MB of activations); see load_noise for how it is fetched.  No barrier inside the loop.  FT = F / 32.
 template <typename T, int FT>
 __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
   constexpr int KC = 2 * Elem<T>::EPL;
@@ -1493,6 +1494,7 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
   constexpr int NCT = CAT_C / TILE;                     // class tiles
   extern __shared__ uint4 head_w[];                     // [NCT][KCH][256] this colour's weights, fragment-major
   __shared__ float4 bias_lds[CAT_C / 4];
+  __shared__ __align__(16) float noise_patch[4][TILE * HEAD_PATCH_PITCH];
   const int t = blockIdx.x / a.groups, group = blockIdx.x % a.groups;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 31, h = lane >> 5;
@@ -1505,30 +1507,59 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
     const int lo = a.first_pass ? a.row_lo : max(a.row_lo, a.dirty_lo[n]);
     return y >= lo && y <= a.row_hi;
   };
+  // The wave's rows are wave, wave + stride, ...; which of them are active is decided up front, 64 rows at a time,
+  // so that no load (the images' dirty rows) is issued between the noise requests of the main loop: loads
+  // return in order, and waiting for a young one means waiting for every noise load before it.
   const int stride = a.groups * 4;
-  auto next_active = [&](int g) {                       // first active row of this wave at or after g
-    while (g < n_rows && !row_active(g)) g += stride;
-    return g;
+  const int g_first = group * 4 + wave;
+  int chunk = 0;                                        // rows g_first + (64 * chunk + k) * stride, k = 0..63
+  auto active_mask = [&](int ch) {
+    unsigned long long m = 0;
+    for (int k = 0; k < 64; ++k) {
+      const int gg = g_first + (64 * ch + k) * stride;
+      if (gg >= n_rows) break;
+      if (row_active(gg)) m |= 1ull << k;
+    }
+    return m;
   };
+  unsigned long long mask = active_mask(0);
+  // first active row at or after position k of the current chunk (moves on to later chunks when needed)
+  auto next_active = [&](int k) {
+    for (;;) {
+      const unsigned long long rest = k < 64 ? (mask >> k) << k : 0ull;
+      if (rest) return g_first + (64 * chunk + __builtin_ctzll(rest)) * stride;
+      if (g_first + (long long)(64 * (chunk + 1)) * stride >= n_rows) return n_rows;
+      ++chunk;
+      mask = active_mask(chunk);
+      k = 0;
+    }
+  };
+  auto slot_of = [&](int gg) { return (gg - g_first) / stride - 64 * chunk; };
   JM_TSTAMP(0, 0);
   int n_done = 0;
-  int g = next_active(group * 4 + wave);
+  int g = next_active(0);
   const bool wg_has_work = __syncthreads_or(g < n_rows);
 
-  // Noise registers: a ring of RING class tiles; slot ct % RING holds the lane's classes ct*32 + 8q + 4h .. + 3
-  // of pixel r.  As soon as a tile is consumed, the tile RING places further on (of this row or of the wave's
-  // next row) is requested into its slot, so RING tiles (2 KB per wave each) are always in flight.
-  auto load_noise = [&](int g_row, int ct, float4 (&dst)[4]) {
-    const float* nz = a.noise + ((size_t)(g_row * 32 + r) * 3 + t) * CAT_C + ct * TILE + 4 * h;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) dst[q] = *(const float4*)(nz + 8 * q);
+  // Noise: a ring of RING class tiles in registers.  A tile (32 pixels x 32 classes) is fetched by 4 loads in
+  // which 8 lanes cover one pixel's 128 bytes (lane = (pixel % 8, 4 classes)): whole cache lines per group of
+  // lanes, measured 5.6 TB/s on this stream like a linear read (4.2 TB/s when every lane fetches 16 bytes of
+  // its own pixel, 1.5 TB/s with 4-byte loads).  As soon as a tile is consumed, the tile RING places further
+  // on (of this row or of the wave's next row) is requested into its slot.  On consumption the tile is turned
+  // through a wave-private LDS patch into the accumulator layout (lane (r, h): classes 8q + 4h .. + 3 of
+  // pixel r for q = 0..3).
+  typedef __attribute__((__vector_size__(4 * sizeof(float)))) float vf4;   // (a native vector: stays in registers)
+  auto load_noise = [&](int g_row, int ct, vf4 (&dst)[4]) {
+    const float* nz = a.noise + ((size_t)(g_row * 32 + (lane >> 3)) * 3 + t) * CAT_C + ct * TILE + (lane & 7) * 4;
+    static_for<4>([&](auto I) {
+      constexpr int i = decltype(I)::value;
+      dst[i] = *(const vf4*)(nz + (size_t)i * 8 * 3 * CAT_C);
+    });
   };
   constexpr int RING = 4;
   static_assert(NCT % RING == 0, "a row must be a whole number of ring turns");
-  float4 gz[RING][4];
+  vf4 gz[RING][4];
   if (g < n_rows) {
-#pragma unroll
-    for (int ct = 0; ct < RING; ++ct) load_noise(g, ct, gz[ct]);
+    static_for<RING>([&](auto CT) { load_noise(g, decltype(CT)::value, gz[decltype(CT)::value]); });
   }
 
   int k_end = a.tile_kend[t * NCT];
@@ -1552,34 +1583,69 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
   JM_TSTAMP(1, 0);
   int sink = 0;                                         // old values of the counter atomics (see below)
 
+  // Activations and old symbols are requested one row ahead, and BEFORE the row's noise reloads: loads return in
+  // order, so a young activation load that is needed at once would make the wave wait for every noise load
+  // issued before it.
+  uint4 af_next[KCH][4];
+  uint8_t x_old_next = 0;
+  auto load_row_inputs = [&](int g_row) {
+    const uint4* A0 = (const uint4*)a.A + (size_t)g_row * KCH * 256 + h * 32 + r;
+    static_for<KCH>([&](auto C) {
+      constexpr int c = decltype(C)::value;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) af_next[c][s] = A0[c * 256 + s * 64];
+    });
+    x_old_next = a.x[((size_t)g_row * 32 + r) * 3 + t];
+  };
+  if (g < n_rows) load_row_inputs(g);
+  uint4 wf[2][KCH][4];
   while (g < n_rows) {                                  // (uniform over the wave)
     const int n = g / a.H, y = g % a.H;
-    const int g_next = next_active(g + stride);
+    const int g_next = next_active(slot_of(g) + 1);
     const size_t xi = ((size_t)g * 32 + r) * 3 + t;     // lane (r, 0) finishes pixel r
-    const uint8_t x_old = a.x[xi];
+    const uint8_t x_old = x_old_next;
     uint4 af[KCH][4];
-    const uint4* A0 = (const uint4*)a.A + (size_t)g * KCH * 256 + h * 32 + r;
 #pragma unroll
     for (int c = 0; c < KCH; ++c)
 #pragma unroll
-      for (int s = 0; s < 4; ++s) af[c][s] = A0[c * 256 + s * 64];
+      for (int s = 0; s < 4; ++s) af[c][s] = af_next[c][s];
+    if (g_next < n_rows) load_row_inputs(g_next);
+    __builtin_amdgcn_sched_barrier(0);
 
     float best = -INFINITY;
     int best_c = 0;
+    if (n_done == 0) {   // (first row of this wave: the first tile's weights)
+#pragma unroll
+      for (int c = 0; c < KCH; ++c)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) wf[0][c][s] = head_w[(size_t)c * 256 + s * 64 + h * 32 + r];
+    }
     static_for<NCT>([&](auto CT) {
       constexpr int ct = decltype(CT)::value;
       f32x16 acc;
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-      const uint4* Wl = head_w + (size_t)ct * KCH * 256 + h * 32 + r;
+      // this tile's weight fragments were read from LDS during the previous tile; request the next tile's now
       static_for<KCH>([&](auto C) {
         constexpr int c = decltype(C)::value;
-        if (c < n_chunks) {
-          uint4 wf[4];
+        const uint4* Wl = head_w + (size_t)((ct + 1) % NCT) * KCH * 256 + c * 256 + h * 32 + r;
 #pragma unroll
-          for (int s = 0; s < 4; ++s) wf[s] = Wl[c * 256 + s * 64];
-          mfma_chunk<T>(wf, af[c], acc);
-        }
+        for (int s = 0; s < 4; ++s) wf[(ct + 1) & 1][c][s] = Wl[s * 64];
+      });
+      static_for<KCH>([&](auto C) {
+        constexpr int c = decltype(C)::value;
+        if (c < n_chunks) mfma_chunk<T>(wf[ct & 1][c], af[c], acc);
+      });
+      // the tile's noise: from load layout (pixel 8i + lane/8, classes 4 (lane%8) ..) to accumulator layout
+      float* patch = noise_patch[wave];
+      static_for<4>([&](auto I) {
+        constexpr int i = decltype(I)::value;
+        *(vf4*)(patch + (8 * i + (lane >> 3)) * HEAD_PATCH_PITCH + (lane & 7) * 4) = gz[ct % RING][i];
+      });
+      vf4 gq[4];
+      static_for<4>([&](auto Q) {
+        constexpr int q = decltype(Q)::value;
+        gq[q] = *(const vf4*)(patch + r * HEAD_PATCH_PITCH + 8 * q + 4 * h);
       });
       // acc[4q + j]: class ct*32 + 8q + 4h + j of pixel r; classes ascend along (ct, q, j), so a strict compare
       // keeps the lowest class of a tie
@@ -1587,11 +1653,11 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
       for (int q = 0; q < 4; ++q) {
         const int cb = ct * TILE + 8 * q + 4 * h;
         const float4 bv = bias_lds[cb >> 2];
-        const float4 gv = gz[ct % RING][q];
-        const float v0 = (acc[4 * q + 0] + bv.x) + gv.x;
-        const float v1 = (acc[4 * q + 1] + bv.y) + gv.y;
-        const float v2 = (acc[4 * q + 2] + bv.z) + gv.z;
-        const float v3 = (acc[4 * q + 3] + bv.w) + gv.w;
+        const vf4 gv = gq[q];
+        const float v0 = (acc[4 * q + 0] + bv.x) + gv[0];
+        const float v1 = (acc[4 * q + 1] + bv.y) + gv[1];
+        const float v2 = (acc[4 * q + 2] + bv.z) + gv[2];
+        const float v3 = (acc[4 * q + 3] + bv.w) + gv[3];
         if (v0 > best) { best = v0; best_c = cb; }
         if (v1 > best) { best = v1; best_c = cb + 1; }
         if (v2 > best) { best = v2; best_c = cb + 2; }
