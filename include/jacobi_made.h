@@ -232,12 +232,20 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   layers with 256 x 256 workgroup tiles staged through LDS instead of 32 x 32 tiles (on the D = 784,
  *   2 x 2000 network the two cross over near 5000 samples).
  *   MADE_OPT_CONV_ROWS (default 4; 2 or 4): image rows per workgroup of the convolutional model's k x k layers.
+ *   MADE_OPT_RESIDENT (default 2; 0, 1 or 2): the sample-resident kernel serves jacobi_sample / gs_jacobi_sample of
+ *   Bernoulli models in ONE launch: a workgroup keeps 32 samples' iterate and hidden activations in its LDS for the
+ *   whole call, streams the masked weights from L2 and runs every pass (and block) without leaving the compute
+ *   unit.  It needs input plus hidden activations of 32 samples to fit 160 KB of LDS (e.g. D = 784 with 2 x 512
+ *   hidden units in bf16; not 2 x 2000).  0 = never; 1 = whenever the model fits; 2 = where it pays: always for
+ *   gs_jacobi_sample (short passes, otherwise dominated by launch gaps), for jacobi_sample only while a pass
+ *   streams at most 768 KB of visible weights (one compute unit streams them all).  Same symbols and pass counts
+ *   as the per-layer path except possibly where a decision margin vanishes (see resident.hpp).
  *   MADE_OPT_PREFIX_CACHE (default 1): GS-Jacobi on the masked MLP keeps the activations of the hidden units whose
  *   inputs all lie before the current block (degree <= block start: they are final) after the block's first
  *   pass and only re-evaluates the units behind them; 0 re-evaluates every visible unit in every pass.
  */
 enum { MADE_OPT_PERSISTENT = 1, MADE_OPT_FUSED_CATEGORICAL = 2, MADE_OPT_CHAINS = 3, MADE_OPT_BIG_TILE_BATCH = 4,
-       MADE_OPT_CONV_ROWS = 5, MADE_OPT_PREFIX_CACHE = 6 };
+       MADE_OPT_CONV_ROWS = 5, MADE_OPT_PREFIX_CACHE = 6, MADE_OPT_RESIDENT = 7 };
 int made_set_option(made_model* m, int32_t option, int32_t value);
 
 /*

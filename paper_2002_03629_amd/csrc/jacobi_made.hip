@@ -22,6 +22,7 @@
 #include <vector>
 
 #include "kernels.hpp"
+#include "resident.hpp"
 
 using namespace jm;
 
@@ -172,6 +173,13 @@ struct made_model {
   int n_chains = 1;                           // made_set_option(MADE_OPT_CHAINS)
   int fused_categorical = 1;                  // made_set_option(MADE_OPT_FUSED_CATEGORICAL)
   int use_persistent = 0;                     // made_set_option(MADE_OPT_PERSISTENT); off: measured slower, see header
+  // sample-resident kernel (resident_sampler_kernel): LDS layout, 0 bytes = this model does not fit
+  int use_resident = 2;                       // made_set_option(MADE_OPT_RESIDENT): 0 never, 1 whenever it fits, 2 where it pays
+  int64_t res_pass_bytes = 0;                 // visible weights one full pass streams, in bytes
+  int res_lds_bytes = 0, res_lds_enc = 0, res_lds_clear = 0;
+  std::vector<int> res_lds_out, res_lds_bias, res_lds_kend, res_lds_cnt;
+  unsigned long long* res_ctr = nullptr;      // device, 4 words, zero between calls
+  volatile unsigned long long* res_host = nullptr;   // pinned, 3 words
 };
 
 
@@ -312,6 +320,8 @@ extern "C" int made_free(made_model* m) {
     for (void* p : cv.act)
       if (p) (void)hipFree(p);
   }
+  if (m->res_ctr) (void)hipFree(m->res_ctr);
+  if (m->res_host) (void)hipHostFree((void*)m->res_host);
   for (hipEvent_t e : m->ev_pool) (void)hipEventDestroy(e);
   delete m;
   return MADE_OK;
@@ -346,6 +356,11 @@ extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
   }
   if (option == MADE_OPT_FUSED_CATEGORICAL) {
     m->fused_categorical = value != 0;
+    return MADE_OK;
+  }
+  if (option == MADE_OPT_RESIDENT) {
+    if (value < 0 || value > 2) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_RESIDENT=%d outside [0, 2]", value);
+    m->use_resident = value;
     return MADE_OK;
   }
   if (option == MADE_OPT_PREFIX_CACHE) {
@@ -544,6 +559,49 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
                ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, persistent_sampler_kernel<bf16_t>, NW * 64, 0)
                : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, persistent_sampler_kernel<float>, NW * 64, 0);
     if (pe == hipSuccess && coop && per_cu >= 1 && C == 1 && L + 1 <= PERSIST_MAX_LAYERS) m->persist_grid = cus;
+    (void)hipGetLastError();
+  }
+  // The sample-resident kernel keeps one 32-sample row group of the input and of every hidden layer, the biases
+  // and the mask tables in a workgroup's LDS, and the noise of up to RES_MAXT output tiles per wave in registers.
+  bool res_fits = C == 1 && !m->real && L + 1 <= PERSIST_MAX_LAYERS && m->layers[L].n_tiles <= RES_MAXT * RES_W;
+  for (int l = 0; l <= L; ++l) res_fits = res_fits && m->layers[l].n_tiles <= RES_TPW * RES_W;
+  if (res_fits) {
+    const int es = (int)elem_size(m);
+    auto up16 = [](int v) { return (v + 15) & ~15; };
+    int off = 0;
+    m->res_lds_out.assign(L + 1, 0);
+    m->res_lds_bias.assign(L + 1, 0);
+    m->res_lds_kend.assign(L + 1, 0);
+    m->res_lds_cnt.assign(L + 1, 0);
+    m->res_lds_enc = off;
+    off += m->layers[0].in_pad * RES_ROWS * es;
+    for (int l = 0; l < L; ++l) {
+      m->res_lds_out[l] = off;
+      off += m->layers[l + 1].in_pad * RES_ROWS * es;
+    }
+    m->res_lds_clear = off;
+    for (int l = 0; l <= L; ++l) {
+      m->res_lds_bias[l] = off;
+      off += m->layers[l].n_tiles * TILE * (int)sizeof(float);
+      m->res_lds_kend[l] = off;
+      off += up16(m->layers[l].n_tiles * (int)sizeof(int));
+      if (l < L) {
+        m->res_lds_cnt[l] = off;
+        off += up16((D + 1) * (int)sizeof(int));
+      }
+    }
+    const int statics = 2048;   // the kernel's own small LDS arrays
+    if (off + statics <= 160 * 1024) {   // LDS of a gfx950 compute unit
+      hipError_t le = m->dtype == MADE_BF16
+               ? hipFuncSetAttribute((const void*)resident_sampler_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize, off)
+               : hipFuncSetAttribute((const void*)resident_sampler_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize, off);
+      if (le == hipSuccess) le = hipMalloc((void**)&m->res_ctr, 4 * sizeof(unsigned long long));
+      if (le == hipSuccess) le = hipMemset(m->res_ctr, 0, 4 * sizeof(unsigned long long));
+      if (le == hipSuccess) le = hipHostMalloc((void**)&m->res_host, 4 * sizeof(unsigned long long), hipHostMallocDefault);
+      if (le == hipSuccess) m->res_lds_bytes = off;
+      m->res_pass_bytes = 0;
+      for (int l = 0; l <= L; ++l) m->res_pass_bytes += m->nnz[l] * es;
+    }
     (void)hipGetLastError();
   }
   *out = m;
@@ -1472,6 +1530,70 @@ static int run_persistent(made_model* m, const float* noise, int N, const uint8_
   return MADE_OK;
 }
 
+// The whole call in one launch of the sample-resident kernel (see resident_sampler_kernel): one workgroup per 32
+// samples.  Returns 1 in *done when the call was served this way.
+static int run_resident(made_model* m, const float* noise, int N, const uint8_t* x_init, uint8_t* x, int block,
+                        int cap, bool flag_unconverged, int32_t* iters_out, hipStream_t s, bool* done) {
+  *done = false;
+  if (m->arch != 0 || m->real || !m->use_resident || m->res_lds_bytes <= 0) return MADE_OK;
+  // One compute unit streams every visible weight of a pass (measured ~70 GB/s), against all of them in the
+  // per-layer launches (whose passes cost ~25 us in launch gaps at batch ~100): whole-network passes pay up to
+  // about 3/4 MB of visible weights, the short passes of GS-Jacobi blocks always.
+  if (m->use_resident == 2 && block >= m->D && m->res_pass_bytes > RES_AUTO_PASS_BYTES) return MADE_OK;
+  Workspace& w = m->ws;
+  ResidentArgs p;
+  memset(&p, 0, sizeof p);
+  for (int l = 0; l <= m->L; ++l) {
+    const Layer& ly = m->layers[l];
+    ResidentLayer& pl = p.layer[l];
+    pl.W = ly.W;
+    pl.bias = ly.bias;
+    pl.tile_kend = ly.tile_kend;
+    pl.cnt_lt = ly.cnt_lt;
+    pl.in_pad = ly.in_pad;
+    pl.k_chunks = ly.k_chunks;
+    pl.n_tiles = ly.n_tiles;
+    pl.out_dim = ly.out_dim;
+    pl.lds_out = m->res_lds_out[l];
+    pl.lds_bias = m->res_lds_bias[l];
+    pl.lds_kend = m->res_lds_kend[l];
+    pl.lds_cnt = m->res_lds_cnt[l];
+  }
+  p.L = m->L;
+  p.lds_enc = m->res_lds_enc;
+  p.lds_clear = m->res_lds_clear;
+  p.noise = noise;
+  p.x_init = x_init;
+  p.x = x;
+  p.N = N;
+  p.D = m->D;
+  p.block = std::min(block, m->D);
+  p.cap = cap;
+  p.flag_unconverged = flag_unconverged;
+  p.io_aligned = (m->D % 4 == 0) && ((uintptr_t)noise % 16 == 0);
+  p.iters = iters_out ? iters_out : w.iters;
+  p.ctr = m->res_ctr;
+  p.host = (unsigned long long*)m->res_host;
+  const int grid = (N + RES_ROWS - 1) / RES_ROWS;
+  prof_mark(m, m->L + 1, false, s);
+  if (m->dtype == MADE_BF16)
+    hipLaunchKernelGGL(resident_sampler_kernel<bf16_t>, dim3(grid), dim3(RES_W * 64), (size_t)m->res_lds_bytes, s, p);
+  else
+    hipLaunchKernelGGL(resident_sampler_kernel<float>, dim3(grid), dim3(RES_W * 64), (size_t)m->res_lds_bytes, s, p);
+  prof_mark(m, m->L + 1, true, s);
+  HIP_TRY(hipGetLastError());
+  m->stats[2] += 1;
+  HIP_TRY(hipStreamSynchronize(s));
+  m->stats[3] += 1;
+  prof_collect(m);
+  const unsigned long long flags = m->res_host[0];
+  m->stats[0] = (int64_t)m->res_host[1];
+  m->stats[1] = (int64_t)m->res_host[2];
+  *done = true;
+  if (flags & 1) return fail(MADE_ERR_NOT_CONVERGED, "samples were still changing after the last allowed pass");
+  return MADE_OK;
+}
+
 extern "C" int jacobi_sample(made_model* m, const float* noise, int32_t N, const uint8_t* x_init, int32_t max_iters,
                              uint8_t* x_out, int32_t* iters_out, void* stream) {
   TRY(check_call(m, noise, N, x_out, "jacobi_sample"));
@@ -1483,6 +1605,8 @@ extern "C" int jacobi_sample(made_model* m, const float* noise, int32_t N, const
   const int cap = (max_iters <= 0 || max_iters > m->D) ? m->D : max_iters;
   bool done = false;
   TRY(run_persistent(m, noise, N, x_init, x_out, m->D, cap, cap < m->D, iters_out, s, &done));
+  if (done) return MADE_OK;
+  TRY(run_resident(m, noise, N, x_init, x_out, m->D, cap, cap < m->D, iters_out, s, &done));
   if (done) return MADE_OK;
   std::vector<Block> blocks(1, make_block(m, 0, m->D, cap, false));
   return run_chains(m, blocks, noise, x_init, x_out, N, cap < m->D, iters_out, s);
@@ -1499,6 +1623,8 @@ extern "C" int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, co
   TRY(ensure_workspace(m, N, true));
   bool done = false;
   TRY(run_persistent(m, noise, N, x_init, x_out, block, m->D, false, iters_out, s, &done));
+  if (done) return MADE_OK;
+  TRY(run_resident(m, noise, N, x_init, x_out, block, m->D, false, iters_out, s, &done));
   if (done) return MADE_OK;
   std::vector<Block> blocks;
   for (int a = 0; a < m->D; a += block) {

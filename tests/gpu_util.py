@@ -38,6 +38,7 @@ def oracle_models(net):
 
 
 PERSISTENT = False     # execution path the models below are switched to (the tests run both)
+RESIDENT = 0           # sample-resident kernel: 0 never, 1 whenever the model fits it (2, the library's default, = where it pays)
 FUSED_CATEGORICAL = True
 CHAINS = 4
 
@@ -47,6 +48,7 @@ class GpuModel:
         self.net = net
         self.h = B.model_from_network(net)
         B.made_set_option(self.h, B.MADE_OPT_PERSISTENT, int(PERSISTENT if persistent is None else persistent))
+        B.made_set_option(self.h, B.MADE_OPT_RESIDENT, int(RESIDENT))
         B.made_set_option(self.h, B.MADE_OPT_FUSED_CATEGORICAL, int(FUSED_CATEGORICAL))
         B.made_set_option(self.h, B.MADE_OPT_CHAINS, CHAINS)
         if big_tile_batch is not None:

@@ -15,7 +15,8 @@ from gpu_util import (LOGIT_TOL, MARGIN, GpuModel, assert_logits_close, assert_s
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=["per-layer launches", "single chain", "persistent", "unfused categorical"])
+@pytest.fixture(autouse=True, params=["per-layer launches", "single chain", "persistent", "sample-resident",
+                                      "unfused categorical"])
 def execution_path(request):
     """Every test runs on every execution path of the library (they must all agree with the oracle)."""
     import gpu_util
@@ -23,11 +24,17 @@ def execution_path(request):
         name = getattr(request.node, "callspec", None) and request.node.callspec.params.get("name")
         if name != "small_cat":
             pytest.skip("only the 256-class workload has a fused and an unfused output path")
+    if request.param == "sample-resident":
+        name = getattr(request.node, "callspec", None) and request.node.callspec.params.get("name")
+        if name in ("small_cat", "small_cat_f32"):
+            pytest.skip("the sample-resident kernel serves Bernoulli models only")
     gpu_util.PERSISTENT = request.param == "persistent"
+    gpu_util.RESIDENT = int(request.param == "sample-resident")
     gpu_util.FUSED_CATEGORICAL = request.param != "unfused categorical"
     gpu_util.CHAINS = 1 if request.param == "single chain" else 4
     yield
     gpu_util.PERSISTENT = False
+    gpu_util.RESIDENT = 0
     gpu_util.FUSED_CATEGORICAL = True
     gpu_util.CHAINS = 4
 
