@@ -1460,6 +1460,7 @@ static int run_persistent(made_model* m, const float* noise, int N, const uint8_
                           int cap, bool flag_unconverged, int32_t* iters_out, hipStream_t s, bool* done) {
   *done = false;
   if (m->arch != 0 || m->real || !m->use_persistent || m->persist_grid <= 0 || N > PERSIST_MAX_N) return MADE_OK;
+  if ((uintptr_t)x % 4 != 0) return MADE_OK;   // the kernel re-reads symbols through their aligned 32-bit words
   Workspace& w = m->ws;
   PersistArgs p;
   memset(&p, 0, sizeof p);

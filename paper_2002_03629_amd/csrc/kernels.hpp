@@ -278,7 +278,18 @@ __device__ unsigned long long g_tile_trace[1024 * 8];
 
 // CNT chunks c0, c0 + NW, ... of one wave: every load is issued before the first MFMA.  Ap / Wp point at
 // the lane's 16 bytes of slot 0 in chunk 0 of its row group; a chunk is 256 uint4, a slot 64 uint4.
-template <typename T, int CNT>
+// 16 bytes that another workgroup of the SAME kernel may have written (through publish<true>) before the last
+// grid barrier: device-scope loads, which are served coherently without this XCD's caches having been
+// invalidated as a whole (that would also drop the weights every layer re-reads).
+template <bool COH>
+__device__ __forceinline__ uint4 load_shared16(const uint4* p) {
+  if (!COH) return *p;
+  const unsigned long long lo = __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const unsigned long long hi = __hip_atomic_load((const unsigned long long*)p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_uint4((unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32));
+}
+
+template <typename T, int CNT, bool COH>
 __device__ __forceinline__ void chunk_group(const uint4* Ap, const uint4* Wp, int c0, f32x16& acc) {
   static_assert(CNT >= 1 && CNT <= PD, "group larger than the prefetch depth");
   uint4 av[CNT][4], bv[CNT][4];
@@ -287,7 +298,7 @@ __device__ __forceinline__ void chunk_group(const uint4* Ap, const uint4* Wp, in
     const uint4* ap = Ap + (size_t)(c0 + p * NW) * 256;
     const uint4* wp = Wp + (size_t)(c0 + p * NW) * 256;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) { av[p][s] = ap[s * 64]; bv[p][s] = wp[s * 64]; }
+    for (int s = 0; s < 4; ++s) { av[p][s] = load_shared16<COH>(ap + s * 64); bv[p][s] = wp[s * 64]; }
   }
   // keep the scheduler from sinking loads between the MFMAs to save registers: the point is to have
   // every load of the group in flight at once
@@ -361,7 +372,13 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
         const size_t idx = (size_t)e_sample[j] * a.D + col;
         const int nrow = a.noise_mod > 0 ? min(e_sample[j] % a.noise_mod, a.noise_n - 1) : e_sample[j];
         e_noise[j] = a.noise[(size_t)nrow * a.D + col];
-        e_xold[j] = a.x[idx];
+        if (COH) {   // (see load_shared16) the aligned word that holds the symbol
+          const unsigned word = __hip_atomic_load((const unsigned*)((uintptr_t)(a.x + idx) & ~(uintptr_t)3), __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT);
+          e_xold[j] = (uint8_t)(word >> (8 * (unsigned)((uintptr_t)(a.x + idx) & 3)));
+        } else {
+          e_xold[j] = a.x[idx];
+        }
       }
     }
   }
@@ -380,15 +397,15 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
   const int n_chunks = (k_end + KC - 1) / KC;
   const int n_mine = (n_chunks - wave + NW - 1) / NW;   // wave-uniform (scalar)
   int base = 0;
-  for (; base + PD <= n_mine; base += PD) chunk_group<T, PD>(Ap, Wp, base * NW + wave, acc);
+  for (; base + PD <= n_mine; base += PD) chunk_group<T, PD, COH>(Ap, Wp, base * NW + wave, acc);
   switch (n_mine - base) {
-    case 7: chunk_group<T, (PD > 7 ? 7 : 1)>(Ap, Wp, base * NW + wave, acc); break;
-    case 6: chunk_group<T, (PD > 6 ? 6 : 1)>(Ap, Wp, base * NW + wave, acc); break;
-    case 5: chunk_group<T, (PD > 5 ? 5 : 1)>(Ap, Wp, base * NW + wave, acc); break;
-    case 4: chunk_group<T, (PD > 4 ? 4 : 1)>(Ap, Wp, base * NW + wave, acc); break;
-    case 3: chunk_group<T, (PD > 3 ? 3 : 1)>(Ap, Wp, base * NW + wave, acc); break;
-    case 2: chunk_group<T, (PD > 2 ? 2 : 1)>(Ap, Wp, base * NW + wave, acc); break;
-    case 1: chunk_group<T, 1>(Ap, Wp, base * NW + wave, acc); break;
+    case 7: chunk_group<T, (PD > 7 ? 7 : 1), COH>(Ap, Wp, base * NW + wave, acc); break;
+    case 6: chunk_group<T, (PD > 6 ? 6 : 1), COH>(Ap, Wp, base * NW + wave, acc); break;
+    case 5: chunk_group<T, (PD > 5 ? 5 : 1), COH>(Ap, Wp, base * NW + wave, acc); break;
+    case 4: chunk_group<T, (PD > 4 ? 4 : 1), COH>(Ap, Wp, base * NW + wave, acc); break;
+    case 3: chunk_group<T, (PD > 3 ? 3 : 1), COH>(Ap, Wp, base * NW + wave, acc); break;
+    case 2: chunk_group<T, (PD > 2 ? 2 : 1), COH>(Ap, Wp, base * NW + wave, acc); break;
+    case 1: chunk_group<T, 1, COH>(Ap, Wp, base * NW + wave, acc); break;
     default: break;
   }
 
@@ -738,9 +755,11 @@ struct PersistArgs {
 
 // Grid-wide barrier for a cooperative (co-resident) launch.  Everything a workgroup wrote for others went
 // out through publish<true> (write-through, device scope); each thread waits until its stores are
-// acknowledged, then thread 0 arrives and polls until all workgroups have arrived, and a device-scope acquire
-// drops this XCD's possibly stale cached copies.  (A device-scope release fence instead would write back the
-// whole L2 once per arriving workgroup, 32 times per XCD and barrier, stalling the workgroups still at work.)
+// acknowledged, then thread 0 arrives and polls until all workgroups have arrived.  Readers use device-scope
+// loads (load_shared16 and the like) for whatever another workgroup may have written, so no cache is written
+// back or invalidated here.  (A device-scope release fence instead would write back the whole L2 once per
+// arriving workgroup, 32 times per XCD and barrier, stalling the workgroups still at work; an acquire fence
+// would drop the weights the next layer re-reads.)
 // The wait is bounded: on timeout bit 1 of *flags is set and every workgroup leaves the kernel at its next
 // check, so the grid always drains.
 #ifndef JM_SLEEP
@@ -781,7 +800,7 @@ __device__ __forceinline__ bool grid_barrier(unsigned* bar, unsigned& epoch, int
       }
     }
     JM_STAMP(4);
-#ifndef JM_NO_ACQUIRE   // (timing experiments only: without it other workgroups' writes may be read stale)
+#ifdef JM_BARRIER_ACQUIRE   // (not needed: everything read across the barrier is read with device-scope loads)
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 #endif
     JM_STAMP(5);
