@@ -332,3 +332,61 @@ def make_conv_network(w: ConvWorkload, with_bias: bool = False) -> ConvNetwork:
 def make_conv_noise(w: ConvWorkload, rep: int = 0, N: Optional[int] = None) -> np.ndarray:
     n = w.N if N is None else N
     return gumbel_noise(n, w.H * w.W * 3, w.C, w.seed + 2 + 10 * rep)
+
+
+# ------------------------------------------------------------------------------------------------
+# recurrent network of Section 5.1 (backward pass by Jacobi iteration)
+# ------------------------------------------------------------------------------------------------
+@dataclass
+class RnnWorkload:
+    """One-layer RNN fitted to pixel sequences (Section 5.1, Appendix C.1)."""
+    name: str
+    B: int                      # sequences handled in parallel (the paper trains with batch size 1)
+    T: int                      # time steps = pixels of one flattened image
+    H: int                      # hidden units
+    I: int                      # inputs per step
+    seed: int = SEED_BASE + 40
+    w_std: float = 0.1          # all weights N(0, w_std^2), biases zero (Appendix C.1)
+
+
+def rnn_workload(name: str) -> RnnWorkload:
+    table = {
+        # the paper's shape: 10 x 10 images read pixel by pixel, 128 hidden units, batch 1
+        "rnn_paper": RnnWorkload("rnn_paper", 1, 100, 128, 1, SEED_BASE + 41),
+        # the same network on a batch that fills the GPU (one sequence per workgroup)
+        "rnn_batch": RnnWorkload("rnn_batch", 256, 100, 128, 1, SEED_BASE + 42),
+        # reduced, ragged shapes for the tests (nothing a multiple of 32)
+        "rnn_small": RnnWorkload("rnn_small", 5, 37, 40, 3, SEED_BASE + 43, w_std=0.2),
+        "rnn_wide": RnnWorkload("rnn_wide", 3, 70, 100, 2, SEED_BASE + 44, w_std=0.12),
+    }
+    return table[name]
+
+
+def make_rnn_params(w: RnnWorkload):
+    """(W [H, H], U [H, I], b [H]) as float32."""
+    r = _rng(w.seed)
+    W = (r.standard_normal((w.H, w.H)) * w.w_std).astype(np.float32)
+    U = (r.standard_normal((w.H, w.I)) * w.w_std).astype(np.float32)
+    b = np.zeros((w.H,), dtype=np.float32)
+    return W, U, b
+
+
+def make_rnn_inputs(w: RnnWorkload, rep: int = 0):
+    """(x [B, T, I], y [B, T, H]) as float32: x are flattened blob images with values in [0, 1] (stand-ins for the
+    resized digits; for I > 1 the channels are shifted copies), y are the per-step targets of the squared loss the
+    benchmark and the tests put on the hidden state."""
+    r = _rng(w.seed + 1000 * (rep + 1))
+    side = int(np.ceil(np.sqrt(w.T)))
+    yy, xx = np.mgrid[0:side, 0:side].astype(np.float64)
+    x = np.zeros((w.B, w.T, w.I), dtype=np.float64)
+    for bi in range(w.B):
+        img = np.zeros((side, side))
+        for _ in range(2):
+            cy, cx = r.uniform(0.2, 0.8, size=2) * (side - 1)
+            s = r.uniform(0.8, 2.0)
+            img += np.exp(-((yy - cy) ** 2 + (xx - cx) ** 2) / (2 * s * s))
+        flat = np.clip(img, 0.0, 1.0).reshape(-1)[:w.T]
+        for c in range(w.I):
+            x[bi, :, c] = np.roll(flat, c)
+    y = r.uniform(0.3, 1.2, size=(w.B, w.T, w.H))
+    return x.astype(np.float32), y.astype(np.float32)
