@@ -21,6 +21,7 @@ EXPORTS = ["made_init", "made_conv_init", "made_free", "made_forward_logits", "s
            "gs_jacobi_sample", "jacobi_gs_sample", "made_forward_params", "sequential_sample_real",
            "jacobi_sample_real", "gs_jacobi_sample_real", "made_last_stats", "made_set_profiling", "made_last_profile", "made_set_option",
            "made_layer_nnz",
+           "rnn_forward", "rnn_backward_sequential", "rnn_backward_jacobi", "rnn_jacobi_max_steps", "rnn_param_grads",
            "made_last_error"]
 
 
@@ -74,6 +75,11 @@ def lib() -> C.CDLL:
         L.made_last_profile.argtypes = [vp, C.POINTER(C.c_double), i64p, i32]
         L.made_layer_nnz.argtypes = [vp, i64p, i32]
         L.made_set_option.argtypes = [vp, i32, i32]
+        L.rnn_forward.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
+        L.rnn_backward_sequential.argtypes = [vp, vp, vp, i32, i32, i32, vp, vp]
+        L.rnn_backward_jacobi.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, C.c_float, vp, vp, vp, vp]
+        L.rnn_jacobi_max_steps.argtypes = [i32]
+        L.rnn_param_grads.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
         L.made_last_error.argtypes = []
         L.made_last_error.restype = C.c_char_p
         for name in EXPORTS[:-1]:
@@ -280,3 +286,39 @@ def model_from_network(net) -> int:
     """made_init from a synth.Network description."""
     return made_init(net.D, net.C, net.hidden, MADE_BF16 if net.dtype == "bf16" else MADE_F32, net.degrees, net.W,
                      net.b, getattr(net, "real", False))
+
+
+# ------------------------------------------------------------------------------------------------
+# recurrent network: backward pass by Jacobi iteration (include/jacobi_rnn.h); all tensors are float32 on the device
+# ------------------------------------------------------------------------------------------------
+def rnn_forward(W, U, b, x, h0, B: int, T: int, H: int, I: int, z, h, stream=None) -> None:
+    import torch
+    f = torch.float32
+    _check(lib().rnn_forward(_ptr(W, f), _ptr(U, f), _ptr(b, f), _ptr(x, f), _ptr(h0, f), B, T, H, I, _ptr(z, f), _ptr(h, f),
+                             _stream(stream)))
+
+
+def rnn_backward_sequential(W, z, g, B: int, T: int, H: int, d, stream=None) -> None:
+    import torch
+    f = torch.float32
+    _check(lib().rnn_backward_sequential(_ptr(W, f), _ptr(z, f), _ptr(g, f), B, T, H, _ptr(d, f), _stream(stream)))
+
+
+def rnn_backward_jacobi(W, z, g, d_init, B: int, T: int, H: int, n_iters: int, eps: float, d, iters_out=None,
+                        converged_out=None, stream=None) -> None:
+    import torch
+    f = torch.float32
+    _check(lib().rnn_backward_jacobi(_ptr(W, f), _ptr(z, f), _ptr(g, f), _ptr(d_init, f), B, T, H, int(n_iters), float(eps),
+                                     _ptr(d, f), _ptr(iters_out, torch.int32), _ptr(converged_out, torch.int32),
+                                     _stream(stream)))
+
+
+def rnn_jacobi_max_steps(H: int) -> int:
+    return int(lib().rnn_jacobi_max_steps(int(H)))
+
+
+def rnn_param_grads(z, h, x, d, h0, B: int, T: int, H: int, I: int, dW, dU, db, stream=None) -> None:
+    import torch
+    f = torch.float32
+    _check(lib().rnn_param_grads(_ptr(z, f), _ptr(h, f), _ptr(x, f), _ptr(d, f), _ptr(h0, f), B, T, H, I, _ptr(dW, f),
+                                 _ptr(dU, f), _ptr(db, f), _stream(stream)))

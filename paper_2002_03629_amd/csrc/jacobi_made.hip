@@ -1850,3 +1850,8 @@ extern "C" int jm_debug_read_tile_trace(unsigned long long* out) {
   return hipMemcpyFromSymbol(out, HIP_SYMBOL(jm::g_tile_trace), sizeof(unsigned long long) * 1024 * 8) == hipSuccess ? 0 : -1;
 }
 #endif
+
+// ------------------------------------------------------------------------------------------------
+// recurrent network: backward pass by Jacobi iteration
+// ------------------------------------------------------------------------------------------------
+#include "rnn_entry.hpp"

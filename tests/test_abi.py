@@ -11,9 +11,14 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "jacobi_made.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = re.findall(r"^\s*(?:const\s+char\s*\*|int)\s+(\w+)\s*\(", text, flags=re.M)
+    names = []
+    inc = os.path.join(ROOT, "include")
+    for fn in sorted(os.listdir(inc)):
+        if not fn.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"^\s*(?:const\s+char\s*\*|int)\s+(\w+)\s*\(", text, flags=re.M)
     return sorted(set(names))
 
 
@@ -41,3 +46,11 @@ def test_argument_errors_need_no_gpu():
     assert L.made_forward_logits(None, None, 4, None, None) == binding.MADE_ERR_ARG
     with pytest.raises(binding.MadeError):
         binding._check(L.made_last_stats(None, None, 4))
+    # recurrent-network entry points: shape and NULL checks come before any device work
+    assert L.rnn_backward_jacobi(None, None, None, None, 1, 10, 16, 0, 0.0, None, None, None, None) == binding.MADE_ERR_ARG
+    assert L.rnn_backward_sequential(None, None, None, 1, 10, 200, None, None) == binding.MADE_ERR_ARG
+    assert "128" in binding.made_last_error()
+    assert L.rnn_forward(None, None, None, None, None, 1, 0, 16, 1, None, None, None) == binding.MADE_ERR_ARG
+    assert L.rnn_param_grads(None, None, None, None, None, 1, 10, 16, 1, None, None, None, None) == binding.MADE_ERR_ARG
+    assert binding.rnn_jacobi_max_steps(128) == 128 and binding.rnn_jacobi_max_steps(64) == 256
+    assert binding.rnn_jacobi_max_steps(20) == 512 and binding.rnn_jacobi_max_steps(129) == 0
