@@ -117,6 +117,90 @@ def measured_traffic(workload: str, path: str, dom_is_output: bool):
     return None
 
 
+def bench_rnn(args, torch, B, S) -> int:
+    """Backward pass of the paper's RNN (Section 5.1) by Jacobi_n: one step = one rnn_backward_jacobi call on a
+    resident batch of sequences; side measurements: the standard backward pass, other n, the truncation error."""
+    import dataclasses
+    w = S.rnn_workload(args.workload)
+    if args.batch > 0:
+        w = dataclasses.replace(w, B=args.batch)
+    Bn, T, H, I = w.B, w.T, w.H, w.I
+    Wh, Uh, bh = S.make_rnn_params(w)
+    W, U, b = (torch.from_numpy(a).cuda() for a in (Wh, Uh, bh))
+    n_in = 4
+    stream = torch.cuda.current_stream()
+    zs, gs = [], []
+    for r in range(n_in):          # forward pass on the GPU; the loss is 0.5 |h_t - y_t|^2, so g = h - y
+        xh, yh = S.make_rnn_inputs(w, r)
+        x, y = torch.from_numpy(xh).cuda(), torch.from_numpy(yh).cuda()
+        z = torch.empty((Bn, T, H), dtype=torch.float32, device="cuda")
+        h = torch.empty_like(z)
+        B.rnn_forward(W, U, b, x, None, Bn, T, H, I, z, h, stream)
+        zs.append(z)
+        gs.append(h - y)
+    d = torch.empty((Bn, T, H), dtype=torch.float32, device="cuda")
+    d_seq = torch.empty_like(d)
+    iters = torch.empty((Bn,), dtype=torch.int32, device="cuda")
+    n = args.jacobi_n if 0 < args.jacobi_n <= T else T
+
+    def timed(fn, steps, warmup):
+        for i in range(warmup):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for i in range(steps):
+            fn(i)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps, e0.elapsed_time(e1) * 1e-3 / steps
+
+    jac = lambda i: B.rnn_backward_jacobi(W, zs[i % n_in], gs[i % n_in], None, Bn, T, H, n, 0.0, d, iters, None, stream)
+    seq = lambda i: B.rnn_backward_sequential(W, zs[i % n_in], gs[i % n_in], Bn, T, H, d_seq, stream)
+    wall, dev_s = timed(jac, args.steps, args.warmup)
+    result = {
+        "metric": "sequences/s (backward pass of the RNN by Jacobi_n, Section 5.1)", "value": Bn / wall, "unit": "sequences/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32 (matrix products as three bf16 MFMAs on split operands)",
+        "data": "synthetic", "config": {"workload": w.name, "sequences": Bn, "steps_T": T, "hidden": H, "jacobi_n": n},
+    }
+    # the one kernel of a call does n passes of a [T, H] x [H, H] product per sequence (algorithmic flops: one
+    # product per pass; the split into bf16 parts makes the hardware do three)
+    flops = 2.0 * T * H * H * n * Bn
+    ach = flops / dev_s / 1e12
+    result["roofline"] = {"bound": "mfma", "achieved": ach, "peak": 2500.0, "unit": "TFLOP/s", "frac": ach / 2500.0, "traffic": None,
+                          "kernel": "rnn_jacobi_kernel (all passes of a call)", "avg_launch_us": dev_s * 1e6, "launches": args.steps}
+    if not args.no_extras:
+        extras = {}
+        sw, sd = timed(seq, args.steps, args.warmup)
+        extras["standard_backward_ms"] = sw * 1e3
+        extras["speedup_vs_standard_backward"] = sw / wall
+        seq(0)
+        torch.cuda.synchronize()
+        ref_scale = float(d_seq.abs().max())
+        sweep = {}
+        for nn in sorted({1, 2, 5, 10, 20, 50, T}):
+            f = lambda i, nn=nn: B.rnn_backward_jacobi(W, zs[0], gs[0], None, Bn, T, H, nn, 0.0, d, iters, None, stream)
+            ww, _ = timed(f, max(10, args.steps // 4), 3)
+            sweep[str(nn)] = {"ms": ww * 1e3, "rel_err_vs_standard": float((d - d_seq).abs().max()) / ref_scale}
+        extras["jacobi_n_sweep"] = sweep
+        result["extras"] = extras
+    if not args.no_cpu_baseline:
+        from oracle import rnn_oracle as R
+        z64, g64 = zs[0].cpu().numpy().astype(np.float64), gs[0].cpu().numpy().astype(np.float64)
+        W64 = Wh.astype(np.float64)
+        reps, t0 = 0, time.perf_counter()
+        while time.perf_counter() - t0 < 10.0:
+            R.backprop_sequential(W64, z64, g64)
+            reps += 1
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": reps * Bn / dt, "unit": "sequences/s", "cores": os.cpu_count(), "kind": "oracle",
+                                  "sample": f"{reps} standard backward passes (numpy fp64) over the same {Bn} sequences, {dt:.1f} s"}
+    print(json.dumps(result))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -135,6 +219,8 @@ def main() -> int:
     ap.add_argument("--eps", type=float, default=0.0,
                     help="forward-difference tolerance of Algorithm 1 (workloads with real states only)")
     ap.add_argument("--chains", type=int, default=0, help="sub-batches on separate streams (0 = library default)")
+    ap.add_argument("--jacobi-n", type=int, default=10,
+                    help="pass limit n of Jacobi_n (Section 5.1; workloads rnn_paper / rnn_batch only)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="no timing: run 20 device copies of 64 MiB (calibration of FETCH_SIZE / WRITE_SIZE), then "
                          "20 steps; meant to run under `rocprofv3 --pmc ...`")
@@ -152,6 +238,8 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     import dataclasses
+    if args.workload.startswith("rnn"):
+        return bench_rnn(args, torch, B, S)
     conv = args.workload in ("cfg5", "small_conv", "small_conv_f32")
     w = S.conv_workload(args.workload) if conv else S.workload(args.workload)
     if args.batch > 0:

@@ -36,24 +36,29 @@ struct RnnJacobiArgs {
   float eps;
 };
 
-// fp32 value = hi + lo + O(2^-17 |value|), both parts bf16
+// fp32 value = hi + lo + O(2^-17 |value|), both parts bf16 (round to nearest even; gfx950 converts in hardware)
 __device__ __forceinline__ void split_bf16(float v, bf16_t& hi, bf16_t& lo) {
-  hi = f32_to_bf16(v);
-  lo = f32_to_bf16(v - bf16_to_f32(hi));
+  const __bf16 h = (__bf16)v;
+  const __bf16 l = (__bf16)(v - (float)h);
+  hi = __builtin_bit_cast(bf16_t, h);
+  lo = __builtin_bit_cast(bf16_t, l);
 }
 
 // One pass is D_new = G + X W with X[t] = sigmoid(z[t+1]) * D_old[t+1]: a [Tp, Hp] x [Hp, Hp] product, Tp / Hp
 // = T / H rounded up to 32.  gfx950 has no fast fp32 matrix path (fp32 MFMA runs at 1/16 of the bf16 rate), so
 // both operands are split into two bf16 parts and a product is three bf16 MFMAs with fp32 accumulation
 // (hi*hi + hi*lo + lo*hi; the dropped lo*lo term and the split residuals are ~2^-16 of a product).
-// Wave w owns column tile w % CT for good: its two W panels (hi, lo) stay in registers, as do G, sigmoid(z) and
-// the current iterate of the (at most two) 32 x 32 tiles it owns.  X lives in LDS as two bf16 arrays and is
-// updated in place: all waves read (MFMA phase), barrier, all waves write, barrier.
+// Wave w owns column tile (32 units) w % CT for good: its two W panels (hi, lo) stay in registers, as do G,
+// sigmoid(z) and the current iterate of the (at most two) 32 x 32 tiles it owns.  The MFMA takes W^T as its row
+// operand, so a lane holds 4 runs of 4 consecutive units of ONE time step: inputs come in 16-byte loads and the
+// new X goes back to LDS in 8-byte pieces.  X lives in LDS as two bf16 arrays [time][unit] and is updated in
+// place: all waves read (MFMA phase), barrier, all waves write, barrier.
 template <int CT>
 __global__ __launch_bounds__(RNN_WAVES * 64) void rnn_jacobi_kernel(RnnJacobiArgs a) {
   constexpr int Hp = 32 * CT;
   constexpr int KB = Hp / 16;            // MFMA K blocks (16 wide) per tile
   constexpr int LDX = Hp + 8;            // row pitch of X in bf16 elements (16 bytes of padding)
+  constexpr int TW = RNN_TILES_PER_WAVE;
   extern __shared__ __align__(16) unsigned char rnn_lds[];
   __shared__ unsigned diff_s[2];
   const int T = a.T, H = a.H;
@@ -64,56 +69,86 @@ __global__ __launch_bounds__(RNN_WAVES * 64) void rnn_jacobi_kernel(RnnJacobiArg
   const int cl = lane & 31, hh = lane >> 5;
   const int seq = blockIdx.x;
   const size_t base = (size_t)seq * T * H;
+  const bool vec_ok = (H % 4 == 0) && (((uintptr_t)a.g | (uintptr_t)a.z | (uintptr_t)a.d | (uintptr_t)a.d_init) % 16 == 0);
 
   const int c = wave % CT, q = wave / CT, nq = (RNN_WAVES - c + CT - 1) / CT;   // waves q = 0 .. nq-1 share column tile c
-  const int col = c * 32 + cl;
-  const bool col_ok = col < H;
 
-  // W panels: for K block m the lane holds W[k][col], k = hh * Hp/2 + 8 m .. + 8 (any assignment of K to lanes
-  // works as long as the X reads below use the same one)
+  // W panels: for K block m the lane holds W[k][unit], unit = 32 c + cl, k = hh * Hp/2 + 8 m .. + 8 (any
+  // assignment of K to lanes works as long as the X reads below use the same one)
   uint4 whi[KB], wlo[KB];
+  {
+    const int unit = c * 32 + cl;
 #pragma unroll
-  for (int m = 0; m < KB; ++m) {
-    bf16_t h8[8], l8[8];
+    for (int m = 0; m < KB; ++m) {
+      bf16_t h8[8], l8[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int k = hh * (Hp / 2) + 8 * m + i;
-      const float w = (k < H && col_ok) ? a.W[(size_t)k * H + col] : 0.0f;
-      split_bf16(w, h8[i], l8[i]);
+      for (int i = 0; i < 8; ++i) {
+        const int k = hh * (Hp / 2) + 8 * m + i;
+        const float w = (k < H && unit < H) ? a.W[(size_t)k * H + unit] : 0.0f;
+        split_bf16(w, h8[i], l8[i]);
+      }
+      whi[m] = make_uint4(h8[0] | (h8[1] << 16), h8[2] | (h8[3] << 16), h8[4] | (h8[5] << 16), h8[6] | (h8[7] << 16));
+      wlo[m] = make_uint4(l8[0] | (l8[1] << 16), l8[2] | (l8[3] << 16), l8[4] | (l8[5] << 16), l8[6] | (l8[7] << 16));
     }
-    whi[m] = make_uint4(h8[0] | (h8[1] << 16), h8[2] | (h8[3] << 16), h8[4] | (h8[5] << 16), h8[6] | (h8[7] << 16));
-    wlo[m] = make_uint4(l8[0] | (l8[1] << 16), l8[2] | (l8[3] << 16), l8[4] | (l8[5] << 16), l8[6] | (l8[7] << 16));
   }
 
-  // this wave's tiles: row tiles q, q + nq; element e of a tile is (row = 32 r + 8 (e / 4) + 4 hh + e % 4, col)
-  float G[RNN_TILES_PER_WAVE][16], S[RNN_TILES_PER_WAVE][16], D[RNN_TILES_PER_WAVE][16];
-  bool tile_ok[RNN_TILES_PER_WAVE];
+  // this wave's tiles: row (time) tiles q, q + nq.  Accumulator element e = 4 jj + i of a tile is
+  // (unit = 32 c + 8 jj + 4 hh + i, time = 32 r + cl).
+  float G[TW][16], S[TW][16], D[TW][16];
+  bool tile_ok[TW];
+  auto load4f = [&](const float* p, size_t idx, int u0, bool row_ok, float (&o)[4]) {
+    if (row_ok && vec_ok && u0 + 3 < H) {
+      const float4 v = *(const float4*)(p + idx);
+      o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+    } else {
 #pragma unroll
-  for (int i = 0; i < RNN_TILES_PER_WAVE; ++i) {
+      for (int i = 0; i < 4; ++i) o[i] = (row_ok && u0 + i < H) ? p[idx + i] : 0.0f;
+    }
+  };
+#pragma unroll
+  for (int i = 0; i < TW; ++i) {
     const int r = q + i * nq;
     tile_ok[i] = r < RT;
+    const int t = 32 * r + cl;
+    const bool row_ok = tile_ok[i] && t < T;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int row = 32 * r + 8 * (e >> 2) + 4 * hh + (e & 3);
-      const bool ok = tile_ok[i] && row < T && col_ok;
-      const size_t idx = base + (size_t)row * H + col;
-      G[i][e] = ok ? a.g[idx] : 0.0f;
-      S[i][e] = ok ? rnn_sigmoid(a.z[idx]) : 0.0f;
-      D[i][e] = (ok && a.d_init) ? a.d_init[idx] : 0.0f;
+    for (int jj = 0; jj < 4; ++jj) {
+      const int u0 = 32 * c + 8 * jj + 4 * hh;
+      const size_t idx = base + (size_t)t * H + u0;
+      float gv[4], zv[4], dv[4] = {0.f, 0.f, 0.f, 0.f};
+      load4f(a.g, idx, u0, row_ok, gv);
+      load4f(a.z, idx, u0, row_ok, zv);
+      if (a.d_init) load4f(a.d_init, idx, u0, row_ok, dv);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        G[i][4 * jj + e] = gv[e];
+        S[i][4 * jj + e] = (row_ok && u0 + e < H) ? rnn_sigmoid(zv[e]) : 0.0f;
+        D[i][4 * jj + e] = dv[e];
+      }
     }
   }
+  // X[t-1][unit .. unit+3] = S[t] * D[t], both bf16 parts, 8 bytes each
+  auto store_x = [&](int i, int jj) {
+    const int t = 32 * (q + i * nq) + cl;
+    if (t >= 1 && t < T) {
+      bf16_t h4[4], l4[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) split_bf16(S[i][4 * jj + e] * D[i][4 * jj + e], h4[e], l4[e]);
+      const int off = (t - 1) * LDX + 32 * c + 8 * jj + 4 * hh;
+      *(uint2*)(Xhi + off) = make_uint2(h4[0] | (h4[1] << 16), h4[2] | (h4[3] << 16));
+      *(uint2*)(Xlo + off) = make_uint2(l4[0] | (l4[1] << 16), l4[2] | (l4[3] << 16));
+    }
+  };
 
-  // X = 0, then X[t-1] = S[t] * D[t] for the initial iterate
   for (int i = threadIdx.x; i < Tp * LDX / 2; i += RNN_WAVES * 64) ((unsigned*)rnn_lds)[i] = 0u, ((unsigned*)Xlo)[i] = 0u;
   if (threadIdx.x < 2) diff_s[threadIdx.x] = 0u;
   __syncthreads();
   if (a.d_init) {
 #pragma unroll
-    for (int i = 0; i < RNN_TILES_PER_WAVE; ++i)
+    for (int i = 0; i < TW; ++i)
+      if (tile_ok[i]) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = 32 * (q + i * nq) + 8 * (e >> 2) + 4 * hh + (e & 3);
-        if (tile_ok[i] && row >= 1 && row < T) split_bf16(S[i][e] * D[i][e], Xhi[(row - 1) * LDX + col], Xlo[(row - 1) * LDX + col]);
+        for (int jj = 0; jj < 4; ++jj) store_x(i, jj);
       }
   }
   __syncthreads();
@@ -121,10 +156,10 @@ __global__ __launch_bounds__(RNN_WAVES * 64) void rnn_jacobi_kernel(RnnJacobiArg
   int k = 0, conv = 0;
   while (k < a.cap) {
     ++k;
-    // ---- MFMA phase: acc = X W for the wave's tiles
-    f32x16 acc[RNN_TILES_PER_WAVE];
+    // ---- MFMA phase: acc^T = W^T X^T for the wave's tiles
+    f32x16 acc[TW];
 #pragma unroll
-    for (int i = 0; i < RNN_TILES_PER_WAVE; ++i) {
+    for (int i = 0; i < TW; ++i) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][e] = 0.0f;
       if (tile_ok[i]) {
@@ -133,9 +168,9 @@ __global__ __launch_bounds__(RNN_WAVES * 64) void rnn_jacobi_kernel(RnnJacobiArg
         for (int m = 0; m < KB; ++m) {
           const bf16x8 xh = __builtin_bit_cast(bf16x8, *(const uint4*)(Xhi + xoff + 8 * m));
           const bf16x8 xl = __builtin_bit_cast(bf16x8, *(const uint4*)(Xlo + xoff + 8 * m));
-          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl, __builtin_bit_cast(bf16x8, whi[m]), acc[i], 0, 0, 0);
-          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, __builtin_bit_cast(bf16x8, wlo[m]), acc[i], 0, 0, 0);
-          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh, __builtin_bit_cast(bf16x8, whi[m]), acc[i], 0, 0, 0);
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, whi[m]), xl, acc[i], 0, 0, 0);
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wlo[m]), xh, acc[i], 0, 0, 0);
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, whi[m]), xh, acc[i], 0, 0, 0);
         }
       }
     }
@@ -143,16 +178,18 @@ __global__ __launch_bounds__(RNN_WAVES * 64) void rnn_jacobi_kernel(RnnJacobiArg
     // ---- update phase: D = G + acc, forward difference, X[t-1] = S[t] * D[t]
     float diff = 0.0f;
 #pragma unroll
-    for (int i = 0; i < RNN_TILES_PER_WAVE; ++i) {
+    for (int i = 0; i < TW; ++i) {
       if (tile_ok[i]) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int row = 32 * (q + i * nq) + 8 * (e >> 2) + 4 * hh + (e & 3);
-          const float dn = G[i][e] + acc[i][e];
-          const float df = fabsf(dn - D[i][e]);
-          diff = fmaxf(diff, df == df ? df : __builtin_inff());       // (a NaN never counts as converged)
-          D[i][e] = dn;
-          if (row >= 1 && row < T) split_bf16(S[i][e] * dn, Xhi[(row - 1) * LDX + col], Xlo[(row - 1) * LDX + col]);
+        for (int jj = 0; jj < 4; ++jj) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const float dn = G[i][4 * jj + e] + acc[i][4 * jj + e];
+            const float df = fabsf(dn - D[i][4 * jj + e]);
+            diff = fmaxf(diff, df == df ? df : __builtin_inff());       // (a NaN never counts as converged)
+            D[i][4 * jj + e] = dn;
+          }
+          store_x(i, jj);
         }
       }
     }
@@ -168,12 +205,23 @@ __global__ __launch_bounds__(RNN_WAVES * 64) void rnn_jacobi_kernel(RnnJacobiArg
   }
 
 #pragma unroll
-  for (int i = 0; i < RNN_TILES_PER_WAVE; ++i)
+  for (int i = 0; i < TW; ++i) {
+    const int t = 32 * (q + i * nq) + cl;
+    if (tile_ok[i] && t < T) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int row = 32 * (q + i * nq) + 8 * (e >> 2) + 4 * hh + (e & 3);
-      if (tile_ok[i] && row < T && col_ok) a.d[base + (size_t)row * H + col] = D[i][e];
+      for (int jj = 0; jj < 4; ++jj) {
+        const int u0 = 32 * c + 8 * jj + 4 * hh;
+        float* dst = a.d + base + (size_t)t * H + u0;
+        if (vec_ok && u0 + 3 < H) {
+          *(float4*)dst = make_float4(D[i][4 * jj], D[i][4 * jj + 1], D[i][4 * jj + 2], D[i][4 * jj + 3]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (u0 + e < H) dst[e] = D[i][4 * jj + e];
+        }
+      }
     }
+  }
   if (threadIdx.x == 0) {
     if (a.iters) a.iters[seq] = k;
     if (a.converged) a.converged[seq] = conv;
