@@ -68,17 +68,19 @@ class MadeModel:
                                 # float32 is kept as float32 (an exact copy; all arithmetic on it is float64)
     b: List[np.ndarray]         # L+1 biases, float64
     act_round: Optional[str]    # None, or "bf16": round every hidden activation to bfloat16
+    onehot: bool = False        # categorical symbols enter as one-hot vectors (D * C inputs) instead of one scalar each
 
 
-def masks_from_degrees(D: int, C: int, degrees: Sequence[np.ndarray]) -> List[np.ndarray]:
+def masks_from_degrees(D: int, C: int, degrees: Sequence[np.ndarray], onehot: bool = False) -> List[np.ndarray]:
     """Autoregressive masks of the masked MLP (the MADE construction cited in Section 5.3).
 
     Input position d (1-based) carries degree d.  A hidden unit of degree m may read a
     unit (or input) of degree <= m.  Output row (t, c) may read last-layer units of
     degree < t, strictly, so that the logits of position t are a function of x_{1:t-1}
     only -- the triangular structure of Eq. 5.  There are no direct input->output links.
+    With one-hot input, position d owns the C inputs d*C .. d*C + C - 1, all of degree d.
     """
-    prev = np.arange(1, D + 1)
+    prev = np.repeat(np.arange(1, D + 1), C) if onehot else np.arange(1, D + 1)
     masks = []
     for m in degrees:
         m = np.asarray(m, dtype=np.int64)
@@ -90,8 +92,9 @@ def masks_from_degrees(D: int, C: int, degrees: Sequence[np.ndarray]) -> List[np
 
 
 def build_model(D: int, C: int, degrees: Sequence[np.ndarray], W: Sequence[np.ndarray],
-                b: Sequence[Optional[np.ndarray]], act_round: Optional[str] = None) -> MadeModel:
-    masks = masks_from_degrees(D, C, degrees)
+                b: Sequence[Optional[np.ndarray]], act_round: Optional[str] = None, onehot: bool = False) -> MadeModel:
+    assert not onehot or C > 1
+    masks = masks_from_degrees(D, C, degrees, onehot)
     assert len(W) == len(masks) == len(b)
     WM, bb = [], []
     for Wl, Ml, bl in zip(W, masks, b):
@@ -106,13 +109,20 @@ def build_model(D: int, C: int, degrees: Sequence[np.ndarray], W: Sequence[np.nd
         WM.append(masked)
         bb.append(np.zeros(Wl.shape[0]) if bl is None else np.asarray(bl, dtype=np.float64))
     assert act_round in (None, "bf16")
-    return MadeModel(D, C, masks, WM, bb, act_round)
+    return MadeModel(D, C, masks, WM, bb, act_round, onehot)
 
 
-def encode(x: np.ndarray, C: int) -> np.ndarray:
+def encode(x: np.ndarray, C: int, onehot: bool = False) -> np.ndarray:
     """Network input for symbol values x: Bernoulli positions enter as 0/1, categorical
     positions as the scalar (x - 128) / 128 (one input per position, as in the paper's MADE
-    whose states are scalar pixel intensities, Appendix C.3)."""
+    whose states are scalar pixel intensities, Appendix C.3) -- or, in the one-hot reading, as the
+    indicator vector of the symbol: input t*C + c is 1 iff x_t = c."""
+    if onehot:
+        x = np.asarray(x, dtype=np.int64)
+        N, D = x.shape
+        e = np.zeros((N, D * C))
+        e[np.arange(N)[:, None], np.arange(D)[None, :] * C + x] = 1.0
+        return e
     x = np.asarray(x, dtype=np.float64)
     return x if C == 1 else (x - 128.0) / 128.0
 
@@ -131,7 +141,7 @@ def affine(h: np.ndarray, WM: np.ndarray, b: np.ndarray) -> np.ndarray:
 
 def last_hidden(model: MadeModel, x: np.ndarray) -> np.ndarray:
     """h_L for a batch of symbol vectors x[N, D]: h_l = ReLU((W_l * M_l) h_{l-1} + b_l)."""
-    h = encode(x, model.C)
+    h = encode(x, model.C, model.onehot)
     for WM, b in zip(model.WM[:-1], model.b[:-1]):
         h = np.maximum(affine(h, WM, b), 0.0)
         if model.act_round == "bf16":

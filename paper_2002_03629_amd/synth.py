@@ -36,6 +36,7 @@ class Workload:
     gain: float = 1.0           # extra factor on every weight (coupling strength sweeps)
     block_sizes: List[int] = field(default_factory=list)
     real: bool = False          # continuous states with logistic conditionals (C = 2 outputs per position)
+    onehot: bool = False        # categorical symbols enter the network as one-hot vectors (D * C inputs)
 
 
 def workload(name: str) -> Workload:
@@ -58,6 +59,15 @@ def workload(name: str) -> Workload:
                               gain=1.5),
         "small_cat_f32": Workload("small_cat_f32", 12, 5, [40], "f32", 7, "random", "fan_in", SEED_BASE + 15,
                                   gain=3.0),
+        # the same categorical models with one-hot input (the alternative reading of the input encoding)
+        "cfg4_onehot": Workload("cfg4_onehot", 1024, 256, [4096, 4096], "bf16", 64, "random", "fan_in", SEED_BASE + 7,
+                                onehot=True),
+        "small_cat_onehot": Workload("small_cat_onehot", 24, 256, [96, 80], "bf16", 10, "random", "fan_in",
+                                     SEED_BASE + 18, gain=1.5, onehot=True),
+        "small_cat_onehot_f32": Workload("small_cat_onehot_f32", 12, 5, [40], "f32", 7, "random", "fan_in",
+                                         SEED_BASE + 19, gain=3.0, onehot=True),
+        "mid_cat_onehot": Workload("mid_cat_onehot", 70, 7, [300, 130], "bf16", 45, "random", "fan_in",
+                                   SEED_BASE + 21, gain=2.5, onehot=True),
         # continuous states, logistic conditionals: the paper's own MADE (2 x 512 hidden, 100 images, T = 784)
         "made_logistic": Workload("made_logistic", 784, 2, [512, 512], "bf16", 100, "random", "fan_in", SEED_BASE + 6,
                                   real=True),
@@ -113,18 +123,19 @@ def hidden_degrees(rule: str, D: int, widths: List[int], seed: int) -> List[np.n
 
 
 def dense_weights(D: int, C: int, widths: List[int], rule: str, seed: int, gain: float = 1.0,
-                  bf16: bool = False) -> List[np.ndarray]:
+                  bf16: bool = False, onehot: bool = False) -> List[np.ndarray]:
     """Unmasked fp32 weight matrices, row-major [out, in], one per layer (L hidden + output).
 
     "std0.1": every entry N(0, 0.1^2).  "fan_in": N(0, 1/fan_in) with fan_in the dense
-    input width of the layer.  The output layer has D*C rows, row index t*C + c.
+    input width of the layer.  The output layer has D*C rows, row index t*C + c.  With one-hot input
+    the first layer has D*C columns (column t*C + c) of which D are active at a time: its fan_in is D.
     """
     g = _rng(seed)
-    dims = [D] + list(widths) + [D * C]
+    dims = [D * C if onehot else D] + list(widths) + [D * C]
     Ws = []
     for l in range(len(dims) - 1):
         fan_in, fan_out = dims[l], dims[l + 1]
-        std = 0.1 if rule == "std0.1" else (1.0 / np.sqrt(fan_in))
+        std = 0.1 if rule == "std0.1" else (1.0 / np.sqrt(D if (onehot and l == 0) else fan_in))
         scale = np.float32(std * gain)
         if fan_out * fan_in <= (1 << 26):
             w = g.standard_normal(size=(fan_out, fan_in), dtype=np.float32)
@@ -175,11 +186,12 @@ class Network:
     W: List[np.ndarray]
     b: List[Optional[np.ndarray]]
     real: bool = False          # continuous states with logistic conditionals (then C = 2: mean and log-scale rows)
+    onehot: bool = False        # W[0] is [hidden[0], D * C]: symbols enter as one-hot vectors
 
 
 def make_network(w: Workload, with_bias: bool = False) -> Network:
     degs = hidden_degrees(w.degree_rule, w.D, w.hidden, w.seed + 1)
-    Ws = dense_weights(w.D, w.C, w.hidden, w.weight_rule, w.seed, w.gain, bf16=(w.dtype == "bf16"))
+    Ws = dense_weights(w.D, w.C, w.hidden, w.weight_rule, w.seed, w.gain, bf16=(w.dtype == "bf16"), onehot=w.onehot)
     bs: List[Optional[np.ndarray]] = [None] * len(Ws)
     if with_bias:
         g = _rng(w.seed + 3)
@@ -187,7 +199,7 @@ def make_network(w: Workload, with_bias: bool = False) -> Network:
         for W in Ws:
             b = (0.3 * g.standard_normal(size=W.shape[0])).astype(np.float32)
             bs.append(bf16_representable(b) if w.dtype == "bf16" else b)
-    return Network(w.D, w.C, list(w.hidden), w.dtype, degs, Ws, bs, w.real)
+    return Network(w.D, w.C, list(w.hidden), w.dtype, degs, Ws, bs, w.real, w.onehot)
 
 
 def logistic_noise(N: int, D: int, seed: int) -> np.ndarray:

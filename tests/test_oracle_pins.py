@@ -18,7 +18,7 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
 def _model(net, act_round=None):
-    return O.build_model(net.D, net.C, net.degrees, net.W, net.b, act_round)
+    return O.build_model(net.D, net.C, net.degrees, net.W, net.b, act_round, net.onehot)
 
 
 # ------------------------------------------------------------------ a scalar evaluator
@@ -30,6 +30,9 @@ def scalar_logits(net, x, t):
     C = net.C
     prev_deg = list(range(1, net.D + 1))
     h = [float(v) if C == 1 else (float(v) - 128.0) / 128.0 for v in x]
+    if net.onehot:      # input t*C + c is the indicator of x_t = c and carries the degree of position t
+        prev_deg = [d for d in range(1, net.D + 1) for _ in range(C)]
+        h = [1.0 if int(x[i // C]) == i % C else 0.0 for i in range(net.D * C)]
     for l, deg in enumerate(net.degrees):
         W, b = net.W[l], net.b[l]
         nh = []
@@ -52,8 +55,8 @@ def scalar_logits(net, x, t):
     return out
 
 
-def small_net(D, C, hidden, seed, gain=3.0, bias=True, rule="random"):
-    w = S.Workload("t", D, C, hidden, "f32", 4, rule, "fan_in", seed, gain)
+def small_net(D, C, hidden, seed, gain=3.0, bias=True, rule="random", onehot=False):
+    w = S.Workload("t", D, C, hidden, "f32", 4, rule, "fan_in", seed, gain, onehot=onehot)
     return S.make_network(w, with_bias=bias)
 
 
@@ -471,3 +474,68 @@ def test_bf16_activation_mode_rounds_hidden_units_only():
     noise = S.make_noise(w)
     xs, _ = O.sequential_sample(rounded, noise)
     assert (O.jacobi_reference(rounded, noise)[0] == xs).all()
+
+
+# ------------------------------------------------------------------ one-hot categorical input
+def test_onehot_masks_by_hand():
+    # D = 3, C = 2, hidden degrees [1, 2]: unit of degree m reads the C inputs of every position d <= m
+    masks = O.masks_from_degrees(3, 2, [np.array([1, 2])], onehot=True)
+    m1 = np.array([[1, 1, 0, 0, 0, 0], [1, 1, 1, 1, 0, 0]], bool)
+    assert (masks[0] == m1).all() and masks[1].shape == (6, 2)
+    e = O.encode(np.array([[1, 0, 1]]), 2, onehot=True)
+    assert (e == np.array([[0, 1, 1, 0, 0, 1]])).all()
+
+
+def test_onehot_logits_match_scalar_definition_and_are_autoregressive():
+    net = small_net(6, 4, [9, 7], seed=61, onehot=True)
+    model = _model(net)
+    rng = np.random.default_rng(0)
+    x = rng.integers(0, 4, size=(5, 6)).astype(np.uint8)
+    z = O.logits_all(model, x)
+    for n in range(5):
+        for t in range(6):
+            assert np.allclose(z[n, t], scalar_logits(net, x[n], t), rtol=1e-12, atol=1e-12)
+    # position t reads x_{<t} only; and it does read them (every symbol value gives different logits somewhere)
+    for t in range(6):
+        y = x.copy()
+        y[:, t:] = rng.integers(0, 4, size=(5, 6 - t))
+        assert np.array_equal(O.logits_all(model, y)[:, :t + 1], z[:, :t + 1])
+    y = x.copy()
+    y[:, 0] = (y[:, 0] + 1) % 4
+    assert np.abs(O.logits_all(model, y)[:, 1:] - z[:, 1:]).max() > 1e-3
+    # the first layer is a sum of one weight column per position: h1 = relu(b + sum_t W[:, t*C + x_t] * mask)
+    vis = net.degrees[0][:, None] >= np.arange(1, 7)[None, :]
+    for n in range(5):
+        pre = net.b[0].astype(np.float64) + sum(net.W[0][:, t * 4 + int(x[n, t])].astype(np.float64) * vis[:, t] for t in range(6))
+        h1 = np.maximum(pre, 0.0)
+        assert np.allclose(O.affine(O.encode(x[n:n + 1], 4, True), model.WM[0], model.b[0])[0], pre, rtol=1e-12, atol=1e-14)
+        assert np.allclose(np.maximum(O.affine(O.encode(x[n:n + 1], 4, True), model.WM[0], model.b[0])[0], 0.0), h1)
+
+
+def test_onehot_sequential_sampler_distribution():
+    D, C = 4, 3
+    net = small_net(D, C, [12], seed=63, gain=2.5, rule="cyclic", onehot=True)
+    model = _model(net)
+    states, p = O.joint_bruteforce(model)
+    ref = brute_joint(net)
+    assert np.allclose(p, [ref[tuple(int(v) for v in s)] for s in states], rtol=1e-10)
+    assert p.sum() == pytest.approx(1.0, abs=1e-12)
+    n = 200000
+    x, _ = O.sequential_sample(model, S.gumbel_noise(n, D, C, 779))
+    code = (x.astype(np.int64) * (C ** np.arange(D - 1, -1, -1))).sum(axis=1)
+    counts = np.bincount(code, minlength=C ** D).astype(np.float64)
+    assert _chi2(counts, p) > 1e-3
+    assert p.max() / p.min() > 20
+
+
+@pytest.mark.parametrize("name", ["small_cat_onehot_f32", "mid_cat_onehot"])
+def test_onehot_jacobi_and_gs_jacobi_equal_sequential(name):
+    w = S.workload(name)
+    net = S.make_network(w, with_bias=True)
+    model = _model(net)
+    noise = S.make_noise(w)
+    xs, _ = O.sequential_sample(model, noise)
+    xj, it, done, _, _ = O.jacobi_reference(model, noise)
+    assert (xj == xs).all() and done.all() and (it <= w.D).all()
+    xg, _, _, _ = O.gs_jacobi_reference(model, noise, 5)
+    assert (xg == xs).all()
