@@ -54,6 +54,11 @@ typedef struct made_config {
                             conditionals (the paper's own MADE, Appendix C.3); then C must be 2:
                             output row 2t is the mean mu_t and row 2t+1 the log-scale a_t of
                             position t, and the *_real entry points below are the ones to call */
+  int32_t onehot;        /* 0: a categorical symbol enters the network as the scalar (x - 128) / 128 and W[0]
+                            is [hidden[0], D].  1 (C >= 2 only): it enters as a one-hot vector, W[0] is
+                            [hidden[0], D*C] with column t*C + c the weight of "x_t = c"; the first layer is
+                            then b + the sum over visible positions t of column t*C + x_t (the other reading
+                            of a categorical model's input; a gather instead of a matrix product)        */
 } made_config;
 
 /*

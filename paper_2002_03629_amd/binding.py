@@ -33,7 +33,7 @@ class MadeError(RuntimeError):
 
 class made_config(C.Structure):
     _fields_ = [("D", C.c_int32), ("C", C.c_int32), ("n_hidden", C.c_int32),
-                ("hidden", C.POINTER(C.c_int32)), ("dtype", C.c_int32), ("real", C.c_int32)]
+                ("hidden", C.POINTER(C.c_int32)), ("dtype", C.c_int32), ("real", C.c_int32), ("onehot", C.c_int32)]
 
 
 class made_conv_config(C.Structure):
@@ -116,11 +116,13 @@ def _stream(stream) -> Optional[int]:
 
 
 def made_init(D: int, Cn: int, hidden: Sequence[int], dtype: int, degrees: Sequence[np.ndarray],
-              W: Sequence[np.ndarray], b: Optional[Sequence[Optional[np.ndarray]]] = None, real: bool = False) -> int:
+              W: Sequence[np.ndarray], b: Optional[Sequence[Optional[np.ndarray]]] = None, real: bool = False,
+              onehot: bool = False) -> int:
     """Returns the opaque model handle (an integer address)."""
     L = len(hidden)
     hid = np.ascontiguousarray(hidden, dtype=np.int32)
-    cfg = made_config(int(D), int(Cn), L, hid.ctypes.data_as(C.POINTER(C.c_int32)), int(dtype), 1 if real else 0)
+    cfg = made_config(int(D), int(Cn), L, hid.ctypes.data_as(C.POINTER(C.c_int32)), int(dtype), 1 if real else 0,
+                      1 if onehot else 0)
     keep = []
     deg_arr = (C.POINTER(C.c_int32) * L)()
     for l in range(L):
@@ -129,7 +131,7 @@ def made_init(D: int, Cn: int, hidden: Sequence[int], dtype: int, degrees: Seque
             raise ValueError("degrees[%d] has shape %s" % (l, a.shape))
         keep.append(a)
         deg_arr[l] = a.ctypes.data_as(C.POINTER(C.c_int32))
-    dims = [D] + list(hidden) + [D * Cn]
+    dims = [D * Cn if onehot else D] + list(hidden) + [D * Cn]
     W_arr = (C.POINTER(C.c_float) * (L + 1))()
     b_arr = (C.POINTER(C.c_float) * (L + 1))()
     for l in range(L + 1):
@@ -285,7 +287,7 @@ def made_layer_nnz(model: int, n_layers: int) -> List[int]:
 def model_from_network(net) -> int:
     """made_init from a synth.Network description."""
     return made_init(net.D, net.C, net.hidden, MADE_BF16 if net.dtype == "bf16" else MADE_F32, net.degrees, net.W,
-                     net.b, getattr(net, "real", False))
+                     net.b, getattr(net, "real", False), getattr(net, "onehot", False))
 
 
 # ------------------------------------------------------------------------------------------------

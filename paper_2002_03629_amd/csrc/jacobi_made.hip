@@ -23,6 +23,7 @@
 
 #include "kernels.hpp"
 #include "resident.hpp"
+#include "onehot.hpp"
 
 using namespace jm;
 
@@ -143,6 +144,8 @@ struct ConvNet {
 struct made_model {
   int arch = 0;                               // 0 masked MLP, 1 masked convolutional network
   bool real = false;                          // MLP with real states and logistic conditionals (C = 2 rows per position)
+  bool onehot = false;                        // categorical symbols enter as one-hot vectors: the first layer is a sum of
+                                              // one weight row per position (layers[0].W is [D][C][out_pad], see made_init)
   float call_eps = 0.f;                       // forward-difference tolerance of the current *_real call
   ConvNet conv;
   int D = 0, C = 1, L = 0, dtype = MADE_F32, device = 0;
@@ -403,6 +406,9 @@ static int validate_config(const made_config* cfg, const int32_t* const* degrees
   if (cfg->real != 0 && cfg->real != 1) return fail(MADE_ERR_ARG, "made_init: real=%d must be 0 or 1", cfg->real);
   if (cfg->real && cfg->C != 2)
     return fail(MADE_ERR_ARG, "made_init: a model with real states has C = 2 output rows per position, not %d", cfg->C);
+  if (cfg->onehot != 0 && cfg->onehot != 1) return fail(MADE_ERR_ARG, "made_init: onehot=%d must be 0 or 1", cfg->onehot);
+  if (cfg->onehot && (cfg->C < 2 || cfg->real))
+    return fail(MADE_ERR_ARG, "made_init: one-hot input is for categorical positions (C >= 2, discrete states)");
   for (int l = 0; l < cfg->n_hidden; ++l) {
     if (cfg->hidden[l] < 1 || cfg->hidden[l] > (1 << 20))
       return fail(MADE_ERR_ARG, "made_init: hidden[%d]=%d out of range", l, cfg->hidden[l]);
@@ -425,6 +431,7 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
   m->D = cfg->D;
   m->C = cfg->C;
   m->real = cfg->real != 0;
+  m->onehot = cfg->onehot != 0;
   m->L = cfg->n_hidden;
   m->dtype = cfg->dtype;
   m->hidden.assign(cfg->hidden, cfg->hidden + cfg->n_hidden);
@@ -485,10 +492,31 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
         te = std::max(te, round_up(klen[j], kc));
       }
 
-      const size_t n_w = (size_t)ly.out_pad * ly.in_pad;
+      const bool gather = (l == 0 && m->onehot);
+      if (gather) {
+        // every visible position contributes exactly one weight per unit and sample
+        m->nnz.back() = 0;
+        for (int j = 0; j < ly.out_dim; ++j) m->nnz.back() += out_deg[j];
+      }
+      const size_t n_w = gather ? (size_t)D * C * ly.out_pad : (size_t)ly.out_pad * ly.in_pad;
       const size_t es = elem_size(m);
       std::vector<uint8_t> host(n_w * es, 0);
       const float* Wl = W[l];
+      // One-hot first layer: the caller's W[0] is [hidden[0], D*C] (column t*C + c = symbol c at position t).  It is
+      // stored as [D][C][out_pad]: the row of (t, c) holds that column for all units in degree order, zero for
+      // the units that may not see position t (degree <= t, 0-based t: a prefix of the row).
+      auto fill_gather = [&](int t0, int t1) {
+        for (int t = t0; t < t1; ++t)
+          for (int c2 = 0; c2 < C; ++c2) {
+            const size_t row = ((size_t)t * C + c2) * ly.out_pad;
+            for (int j = 0; j < ly.out_dim; ++j) {
+              if (out_deg[j] < t + 1) continue;
+              const float v = Wl[(size_t)perm[j] * ((size_t)D * C) + (size_t)t * C + c2];
+              if (m->dtype == MADE_BF16) ((uint16_t*)host.data())[row + j] = host_f32_to_bf16(v);
+              else ((float*)host.data())[row + j] = v;
+            }
+          }
+      };
       // mask, permute, convert and lay out in fragment-major order; rows are independent, so large layers
       // (the 2 GiB output layer of a 256-class model) are filled by several host threads
       auto fill_rows = [&](int j0, int j1) {
@@ -505,7 +533,15 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
         }
       };
       const int n_threads = n_w > ((size_t)1 << 24) ? 16 : 1;
-      if (n_threads == 1) {
+      if (gather) {
+        std::vector<std::thread> pool;
+        const int per = (D + n_threads - 1) / n_threads;
+        for (int i = 0; i < n_threads; ++i) {
+          const int t0 = std::min(D, i * per), t1 = std::min(D, (i + 1) * per);
+          if (t0 < t1) pool.emplace_back(fill_gather, t0, t1);
+        }
+        for (std::thread& th : pool) th.join();
+      } else if (n_threads == 1) {
         fill_rows(0, ly.out_dim);
       } else {
         std::vector<std::thread> pool;
@@ -778,6 +814,7 @@ struct RowSet {            // which samples a pass covers
   const int* rows;         // device list or NULL (identity)
   const int* n_rows_ptr;   // device count or NULL
   int n_rows;              // host-side upper bound (grid size) and value when n_rows_ptr is NULL
+  const uint8_t* x = nullptr;   // current symbols [N, D]: what a one-hot first layer reads instead of the scalar encoding
 };
 
 struct SampleIO {          // what the sampling epilogue reads and writes
@@ -889,7 +926,36 @@ static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, in
     if (unit_limit && unit_limit[l] >= 0) tiles = std::min(tiles, (unit_limit[l] + TILE - 1) / TILE);
     if (in_limit >= 0) a.k_cap = std::min(ly.in_pad, round_up(in_limit, kc));
     if (unit_first) a.tile_begin = std::min(tiles, unit_first[l] / TILE);
-    if (tiles - a.tile_begin > 0) {
+    if (l == 0 && m->onehot) {
+      if (!rs.x) return fail(MADE_ERR_ARG, "internal: a one-hot first layer needs the symbols");
+      if (rs.n_rows > 65535) return fail(MADE_ERR_ARG, "one-hot input: at most 65535 samples per call");
+      if (tiles - a.tile_begin > 0) {
+        OnehotArgs g;
+        g.Wg = ly.W;
+        g.bias = ly.bias;
+        g.x = rs.x;
+        g.rows = rs.rows;
+        g.n_rows_ptr = rs.n_rows_ptr;
+        g.n_rows = rs.n_rows;
+        g.cnt_lt = ly.cnt_lt;
+        g.D = m->D;
+        g.C = m->C;
+        g.pitch = ly.out_pad;
+        g.t_end = in_limit >= 0 ? std::min(in_limit, m->D) : m->D;
+        g.unit_begin = a.tile_begin * TILE;
+        g.unit_end = tiles * TILE;
+        g.out = a.out;
+        g.out_chunks = a.out_chunks;
+        const int chunks = (g.unit_end - g.unit_begin + ONEHOT_UNITS - 1) / ONEHOT_UNITS;
+        prof_mark(m, 0, false, s);
+        if (m->dtype == MADE_BF16)
+          hipLaunchKernelGGL(onehot_first_layer_kernel<bf16_t>, dim3(chunks, std::max(rs.n_rows, 1)), dim3(ONEHOT_THREADS), 0, s, g);
+        else
+          hipLaunchKernelGGL(onehot_first_layer_kernel<float>, dim3(chunks, std::max(rs.n_rows, 1)), dim3(ONEHOT_THREADS), 0, s, g);
+        prof_mark(m, 0, true, s);
+        m->stats[2]++;
+      }
+    } else if (tiles - a.tile_begin > 0) {
       launch_layer<EPI_RELU>(m, l, a, tiles - a.tile_begin, row_tiles, s);
       m->stats[2]++;
     }
@@ -1219,7 +1285,7 @@ extern "C" int made_forward_logits(made_model* m, const uint8_t* x, int32_t N, f
     return MADE_OK;
   }
   TRY(launch_init_state(m, x, nullptr, N, s));
-  RowSet rs{nullptr, nullptr, N};
+  RowSet rs{nullptr, nullptr, N, x};
   TRY(run_hidden(m, rs, nullptr, -1, s));
   LayerArgs a = base_args(m, m->L, m->ws.act[m->L - 1], rs);
   a.out = logits;
@@ -1280,7 +1346,7 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
   }
   const int k = c.k_enq + 1;
   const int in = (k - 1) & 1, out = k & 1;
-  RowSet rs{c.rows[in], c.n_rows[in], c.count};
+  RowSet rs{c.rows[in], c.n_rows[in], c.count, x};
   SampleIO io{noise, x, blk.a, blk.b, RetireArgs{}};
   if (blk.stop_test) {
     const int slot = (int)c.log_first.size();
@@ -1300,7 +1366,7 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
     io.retire.enabled = 1;
     c.log_first.push_back(k == 1);
   } else {
-    rs = RowSet{c.rows[0], nullptr, c.count};   // no stop test: every sample of the chain takes the pass
+    rs = RowSet{c.rows[0], nullptr, c.count, x};   // no stop test: every sample of the chain takes the pass
   }
   if (m->arch == 1) {
     TRY(run_conv_pass(m, c.count, io, k == 1, blk.whole_network, s));

@@ -31,7 +31,7 @@ def dev(a):
 
 def oracle_models(net):
     """(exact fp64 model, model whose hidden activations are rounded like the library's)."""
-    exact = O.build_model(net.D, net.C, net.degrees, net.W, net.b, None)
+    exact = O.build_model(net.D, net.C, net.degrees, net.W, net.b, None, getattr(net, "onehot", False))
     # the two differ only in the activation-rounding switch; share the (possibly multi-GiB) arrays
     same = dataclasses.replace(exact, act_round="bf16") if net.dtype == "bf16" else exact
     return exact, same

@@ -82,6 +82,38 @@ def test_cfg4_categorical_full_size():
         assert_sample_parity(same, noise[:sub], xq[:sub], xs, mg)
 
 
+@pytest.mark.timeout(900)
+def test_cfg4_onehot_full_size_certificate():
+    """cfg4 with one-hot input at full size (first layer = gather over a 4096 x 262144 weight matrix): the Jacobi
+    result of all 64 samples is certified as the fixed point of the oracle's network (one oracle evaluation of
+    every position from the GPU's output; exact except where the oracle's margin is below 1e-3), the logits of
+    two samples are compared, and GS-Jacobi and the lean sequential mode must reach the same certificate."""
+    w = S.workload("cfg4_onehot")
+    progress("cfg4_onehot: weights")
+    net = S.make_network(w)
+    progress("cfg4_onehot: building the oracle models")
+    exact, same = oracle_models(net)
+    noise = S.make_noise(w)
+    progress("cfg4_onehot: made_init")
+    with GpuModel(net) as g:
+        progress("cfg4_onehot: jacobi on the GPU, then the oracle certificate")
+        x, it = g.jacobi(noise)
+        exempt, _ = assert_sample_parity(same, noise, x)
+        assert (it >= 2).all() and (it <= w.D).all()
+        print(f"cfg4_onehot jacobi: passes mean {it.mean():.2f} max {it.max()}, exempt positions {exempt}, stats {g.stats()}")
+        z = g.logits(x[:2])
+        assert_logits_close(z, O.logits_all(exact, x[:2]), LOGIT_TOL["bf16"])
+        progress("cfg4_onehot: gs-jacobi, sequential")
+        xb, _ = g.gs_jacobi(noise, 128)
+        assert_sample_parity(same, noise, xb)
+        xq = g.sequential(noise[:8], 1)
+        assert_sample_parity(same, noise[:8], xq)
+        # the three solvers agree with each other wherever the oracle's margins are clear
+        ok, margin = O.fixed_point_check(same, x, noise)
+        clear = (margin >= MARGIN).all(axis=1)
+        assert (xb[clear] == x[clear]).all() and (xq[clear[:8]] == x[:8][clear[:8]]).all()
+
+
 @pytest.mark.timeout(600)
 def test_cfg2_jacobi_gs_full_batch():
     """Algorithm 2 on cfg2 at full batch: the result is certified for all 128 samples (one oracle pass), and a

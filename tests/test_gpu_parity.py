@@ -22,11 +22,11 @@ def execution_path(request):
     import gpu_util
     if request.param == "unfused categorical":
         name = getattr(request.node, "callspec", None) and request.node.callspec.params.get("name")
-        if name != "small_cat":
-            pytest.skip("only the 256-class workload has a fused and an unfused output path")
+        if name not in ("small_cat", "small_cat_onehot"):
+            pytest.skip("only the 256-class workloads have a fused and an unfused output path")
     if request.param == "sample-resident":
         name = getattr(request.node, "callspec", None) and request.node.callspec.params.get("name")
-        if name in ("small_cat", "small_cat_f32"):
+        if name is not None and "cat" in name:
             pytest.skip("the sample-resident kernel serves Bernoulli models only")
     gpu_util.PERSISTENT = request.param == "persistent"
     gpu_util.RESIDENT = int(request.param == "sample-resident")
@@ -39,7 +39,8 @@ def execution_path(request):
     gpu_util.CHAINS = 4
 
 
-SMALL = ["cfg1", "small_f32", "small_bf16", "mid_bf16", "small_cat", "small_cat_f32"]
+SMALL = ["cfg1", "small_f32", "small_bf16", "mid_bf16", "small_cat", "small_cat_f32", "small_cat_onehot",
+         "small_cat_onehot_f32", "mid_cat_onehot"]
 
 
 def _symbols(w, rng, N):
