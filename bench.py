@@ -32,7 +32,8 @@ def cpu_baseline(w, net, noises, budget_s=12.0):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = 1
-    model = O.build_model(net.D, net.C, net.degrees, net.W, net.b, "bf16" if net.dtype == "bf16" else None)
+    model = O.build_model(net.D, net.C, net.degrees, net.W, net.b, "bf16" if net.dtype == "bf16" else None,
+                          getattr(net, "onehot", False))
     sub = noises[0].shape[0] if net.D * net.C < (1 << 16) else min(8, noises[0].shape[0])   # huge models: 8 samples
     O.sequential_sample(model, noises[0][:1])              # warm the BLAS threads
     done, xs0 = 0, None
@@ -195,7 +196,12 @@ def bench_rnn(args, torch, B, S) -> int:
             R.backprop_sequential(W64, z64, g64)
             reps += 1
         dt = time.perf_counter() - t0
-        result["cpu_baseline"] = {"value": reps * Bn / dt, "unit": "sequences/s", "cores": os.cpu_count(), "kind": "oracle",
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = 1
+        result["cpu_baseline"] = {"value": reps * Bn / dt, "unit": "sequences/s", "cores": int(cores), "kind": "oracle",
                                   "sample": f"{reps} standard backward passes (numpy fp64) over the same {Bn} sequences, {dt:.1f} s"}
     print(json.dumps(result))
     return 0
