@@ -113,6 +113,7 @@ struct Workspace {
   float* zbuf = nullptr;             // categorical only: logits [N, D*C]
   int* changed = nullptr;
   int* iters = nullptr;
+  int* call_iters = nullptr;         // where the current call counts passes per sample: the caller's iters_out, else `iters`
   int* flags = nullptr;
   int n_pad = 0;
   std::vector<Chain> chains;         // independent sub-batches, each on its own stream
@@ -1198,7 +1199,11 @@ static int run_conv_pass(made_model* m, int N, const SampleIO& io, bool first_pa
   return MADE_OK;
 }
 
-static int launch_init_state(made_model* m, const uint8_t* x_init, uint8_t* x, int N, hipStream_t s) {
+static int launch_init_state(made_model* m, const uint8_t* x_init, uint8_t* x, int N, hipStream_t s,
+                             const CallReset* reset_in = nullptr) {
+  CallReset reset;
+  memset(&reset, 0, sizeof reset);
+  if (reset_in) reset = *reset_in;
   const size_t total = (size_t)N * m->D;
   const int blocks = (int)std::min<size_t>((total + 255) / 256, 4096);
   if (m->arch == 1) {   // the first convolution reads the symbols themselves
@@ -1216,20 +1221,20 @@ static int launch_init_state(made_model* m, const uint8_t* x_init, uint8_t* x, i
   if (m->real) {
     if (m->dtype == MADE_BF16)
       hipLaunchKernelGGL((init_state_real_kernel<bf16_t>), dim3(blocks), dim3(256), 0, s, (const float*)x_init, (float*)x,
-                         (bf16_t*)m->ws.enc, m->layers[0].k_chunks, N, m->D);
+                         (bf16_t*)m->ws.enc, m->layers[0].k_chunks, N, m->D, reset);
     else
       hipLaunchKernelGGL((init_state_real_kernel<float>), dim3(blocks), dim3(256), 0, s, (const float*)x_init, (float*)x,
-                         (float*)m->ws.enc, m->layers[0].k_chunks, N, m->D);
+                         (float*)m->ws.enc, m->layers[0].k_chunks, N, m->D, reset);
     m->stats[2]++;
     HIP_TRY(hipGetLastError());
     return MADE_OK;
   }
   if (m->dtype == MADE_BF16)
     hipLaunchKernelGGL((init_state_kernel<bf16_t>), dim3(blocks), dim3(256), 0, s, x_init, x, (bf16_t*)m->ws.enc,
-                       m->layers[0].k_chunks, N, m->D, m->C);
+                       m->layers[0].k_chunks, N, m->D, m->C, reset);
   else
     hipLaunchKernelGGL((init_state_kernel<float>), dim3(blocks), dim3(256), 0, s, x_init, x, (float*)m->ws.enc,
-                       m->layers[0].k_chunks, N, m->D, m->C);
+                       m->layers[0].k_chunks, N, m->D, m->C, reset);
   m->stats[2]++;
   HIP_TRY(hipGetLastError());
   return MADE_OK;
@@ -1338,7 +1343,7 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
     if (blk.stop_test || !c.iters_cleared) {
       const int padded = round_up(c.count, 2 * TILE);   // <= c.rows_cap
       hipLaunchKernelGGL(reset_rows_kernel, dim3((padded + 255) / 256), dim3(256), 0, s, c.rows[0], c.n_rows[0],
-                         c.first, c.count, padded, w.changed, c.iters_cleared ? nullptr : w.iters, c.done_ctr);
+                         c.first, c.count, padded, w.changed, c.iters_cleared ? nullptr : w.call_iters, c.done_ctr);
       m->stats[2]++;
       c.iters_cleared = true;
     }
@@ -1350,17 +1355,18 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
   SampleIO io{noise, x, blk.a, blk.b, RetireArgs{}};
   if (blk.stop_test) {
     const int slot = (int)c.log_first.size();
-    if (slot >= c.pin_len) return fail(MADE_ERR_HIP, "internal: pass log overflow");
+    if (slot >= c.pin_len - 1) return fail(MADE_ERR_HIP, "internal: pass log overflow");   // (the last word mirrors the flags)
     c.h_pin[slot] = -1;
     io.retire.rows_in = c.rows[in];
     io.retire.n_in = c.n_rows[in];
     io.retire.rows_out = c.rows[out];
     io.retire.n_out = c.n_rows[out];
     io.retire.changed = w.changed;
-    io.retire.iters = w.iters;
+    io.retire.iters = w.call_iters;
     io.retire.flags = w.flags;
     io.retire.done_ctr = c.done_ctr;
     io.retire.host_slot = c.d_pin + slot;
+    io.retire.host_flags = c.d_pin + (c.pin_len - 1);
     io.retire.last_pass = (k == blk.cap);
     io.retire.flag_unconverged = flag_unconverged;
     io.retire.enabled = 1;
@@ -1406,8 +1412,29 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
     c.log_first.clear();
     c.stream = n_chains == 1 ? s : c.own_stream;   // a single chain needs no fork and join
   }
-  TRY(launch_init_state(m, x_init, x, N, s));
-  HIP_TRY(hipMemsetAsync(w.flags, 0, sizeof(int), s));
+  w.call_iters = iters_out ? iters_out : w.iters;
+  for (int i = 0; i < n_chains; ++i) w.chains[i].h_pin[w.chains[i].pin_len - 1] = 0;
+  if (n_chains == 1 && m->arch == 0) {
+    // one chain on the caller's stream: the kernel that sets up the iterate also resets the chain's list and counters
+    Chain& c = w.chains[0];
+    CallReset r;
+    r.enabled = 1;
+    r.rows = c.rows[0];
+    r.n_rows = c.n_rows[0];
+    r.first = c.first;
+    r.count = c.count;
+    r.padded = round_up(c.count, 2 * TILE);
+    r.changed = w.changed;
+    r.iters = w.call_iters;
+    r.done_ctr = c.done_ctr;
+    r.flags = w.flags;
+    TRY(launch_init_state(m, x_init, x, N, s, &r));
+    c.block_started = true;
+    c.iters_cleared = true;
+  } else {
+    TRY(launch_init_state(m, x_init, x, N, s));
+    HIP_TRY(hipMemsetAsync(w.flags, 0, sizeof(int), s));
+  }
   if (n_chains > 1) {
     HIP_TRY(hipEventRecord(w.fork_ev, s));
     for (int i = 0; i < n_chains; ++i) HIP_TRY(hipStreamWaitEvent(w.chains[i].stream, w.fork_ev, 0));
@@ -1465,11 +1492,12 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
       return fail(MADE_ERR_HIP, "device did not report the stop test of a pass within 30 s");
     }
   }
-  if (iters_out) HIP_TRY(hipMemcpyAsync(iters_out, w.iters, (size_t)N * sizeof(int), hipMemcpyDeviceToDevice, s));
-  HIP_TRY(hipMemcpyAsync((void*)&w.h_pin[0], w.flags, sizeof(int), hipMemcpyDeviceToHost, s));
+  // (pass counts went straight to iters_out, the flags come through the chains' pinned words: no copies)
   if (m->arch == 1)
     HIP_TRY(hipMemcpyAsync((void*)&w.h_pin[2], m->conv.rows_stat, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipStreamSynchronize(s));
+  int call_flags = 0;
+  for (int i = 0; i < n_chains; ++i) call_flags |= w.chains[i].h_pin[w.chains[i].pin_len - 1];
   if (m->arch == 1) {
     unsigned long long rows = 0;
     memcpy(&rows, (const void*)&w.h_pin[2], sizeof rows);
@@ -1492,7 +1520,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
     }
     m->stats[0] = std::max(m->stats[0], passes);
   }
-  if (w.h_pin[0] & 1)
+  if (call_flags & 1)
     return fail(MADE_ERR_NOT_CONVERGED, "samples were still changing after the last allowed pass");
   return MADE_OK;
 }

@@ -105,6 +105,8 @@ struct RetireArgs {
   int* flags;            // bit 0: some sample was still changing after the last allowed pass
   int* done_ctr;         // workgroups finished so far in this kernel (cleared here)
   int* host_slot;        // device-visible pinned host word receiving the new active count
+  int* host_flags;       // device-visible pinned host word mirroring *flags (the host reads it after the call's last
+                         // kernel has finished)
   int last_pass;
   int flag_unconverged;
   int enabled;
@@ -212,7 +214,10 @@ __device__ __forceinline__ void retire_tail(const RetireArgs& r) {
       r.changed[sample] = 0;
       r.iters[sample] += 1;
       keep = (c > 0) && !r.last_pass;
-      if (c > 0 && r.last_pass && r.flag_unconverged) atomicOr(r.flags, 1);
+      if (c > 0 && r.last_pass && r.flag_unconverged) {
+        atomicOr(r.flags, 1);
+        if (r.host_flags) __hip_atomic_store(r.host_flags, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      }
     }
     const unsigned long long mask = __ballot(keep);
     const int before = __popcll(mask & ((1ull << lane) - 1ull));
@@ -1790,8 +1795,40 @@ __global__ __launch_bounds__(256) void gumbel_argmax_kernel(const float* __restr
 }
 
 // Start of a call: x = x_init (or zeros), enc = network input of x, bookkeeping cleared.
+// What the first kernel of a call also does when the whole batch is one chain: the chain's active list becomes
+// its whole sample range, the per-sample counters and the call's flags are cleared (otherwise reset_rows_kernel
+// and a memset do it: two more operations on the stream, each as long as a layer at batch ~100).
+struct CallReset {
+  int enabled;
+  int* rows;
+  int* n_rows;
+  int first, count, padded;
+  int* changed;
+  int* iters;
+  int* done_ctr;
+  int* flags;
+};
+
+__device__ __forceinline__ void call_reset(const CallReset& r) {
+  if (!r.enabled) return;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < (size_t)r.padded; i += stride) {
+    r.rows[i] = (int)i < r.count ? r.first + (int)i : r.first;
+    if ((int)i < r.count) {
+      r.changed[r.first + i] = 0;
+      r.iters[r.first + i] = 0;
+    }
+    if (i == 0) {
+      *r.n_rows = r.count;
+      *r.done_ctr = 0;
+      *r.flags = 0;
+    }
+  }
+}
+
 template <typename T>
-__global__ void init_state_kernel(const uint8_t* x_init, uint8_t* x, T* enc, int enc_chunks, int N, int D, int C) {
+__global__ void init_state_kernel(const uint8_t* x_init, uint8_t* x, T* enc, int enc_chunks, int N, int D, int C, CallReset reset) {
+  call_reset(reset);
   const size_t total = (size_t)N * D;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     const int n = (int)(i / D), t = (int)(i % D);
@@ -1846,7 +1883,8 @@ __global__ void jgs_end_kernel(uint8_t* x, const uint8_t* xv, int np, int D, int
 // Start of a call on a model with real states: x = x_init (or zeros) and the network input (the states
 // themselves, rounded to the model's element type).
 template <typename T>
-__global__ void init_state_real_kernel(const float* x_init, float* x, T* enc, int enc_chunks, int N, int D) {
+__global__ void init_state_real_kernel(const float* x_init, float* x, T* enc, int enc_chunks, int N, int D, CallReset reset) {
+  call_reset(reset);
   const size_t total = (size_t)N * D;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     const int n = (int)(i / D), t = (int)(i % D);
