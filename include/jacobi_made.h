@@ -15,9 +15,12 @@
  *   - "host" pointers are ordinary CPU memory, read during the call only.
  *   - "device" pointers are HIP device memory on the device that was current in
  *     made_init; they stay owned by the caller and are never freed or retained.
- *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  The
- *     *_sample calls synchronise `stream` before returning (their stop test needs the
- *     device's answer); made_forward_logits only enqueues work.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Results are
+ *     ordered on `stream` like those of a kernel launch: read them from work enqueued on the
+ *     same stream, or after synchronising it.  The *_sample calls with a stop test wait for
+ *     the device's answer (they return once the result is final and the status is known), but
+ *     a few empty launches they enqueued ahead of that answer may still be draining when they
+ *     return; sequential_sample and made_forward_logits only enqueue work.
  *   - one model must not be used from two host threads at once (it owns scratch memory).
  */
 #ifndef JACOBI_MADE_H

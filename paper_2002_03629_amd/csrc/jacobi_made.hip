@@ -86,6 +86,8 @@ struct Chain {
   volatile int* h_pin = nullptr;     // pinned, device-visible: [i] = active count after this chain's i-th pass
   int* d_pin = nullptr;              // the same memory as the device addresses it
   int pin_len = 0, rows_cap = 0;
+  int pin_half = 0, pin_base = 0;    // the pass log alternates between the two halves of the pinned words from call to
+  unsigned calls = 0;                // call: kernels a call leaves behind (see run_chains) may still report into its half
   // per call
   int first = 0, count = 0;
   size_t block = 0;                  // index into the call's block list
@@ -114,6 +116,8 @@ struct Workspace {
   int* changed = nullptr;
   int* iters = nullptr;
   int* call_iters = nullptr;         // where the current call counts passes per sample: the caller's iters_out, else `iters`
+  bool pending = false;              // the last call returned with (empty, speculative) kernels still queued on
+  hipStream_t pending_stream = nullptr;   // this stream: a call on another stream, or a reallocation, waits for them
   int* flags = nullptr;
   int n_pad = 0;
   std::vector<Chain> chains;         // independent sub-batches, each on its own stream
@@ -215,8 +219,21 @@ static void free_workspace(Workspace& w) {
   w = Workspace();
 }
 
+// Work a previous call left queued only touches the model's scratch memory.  It is ordered before anything a new
+// call enqueues on the same stream; a call on a different stream has to wait for it.
+static int settle(made_model* m, hipStream_t s) {
+  Workspace& w = m->ws;
+  if (w.pending && w.pending_stream != s) HIP_TRY(hipStreamSynchronize(w.pending_stream));
+  if (w.pending && w.pending_stream != s) w.pending = false;
+  return MADE_OK;
+}
+
 static int ensure_workspace(made_model* m, int N, bool need_z) {
   Workspace& w = m->ws;
+  if (w.pending && (N > w.N_cap || (need_z && m->C > 1 && !w.zbuf))) {   // about to free memory queued kernels may use
+    HIP_TRY(hipDeviceSynchronize());
+    w.pending = false;
+  }
   if (m->arch == 1) {
     if (N <= w.N_cap) return MADE_OK;
     const int cap = std::max(N, w.N_cap);
@@ -282,6 +299,10 @@ static int ensure_chain(made_model* m, size_t i, int rows_cap, int pin_len) {
   if (w.chains.size() <= i) w.chains.resize(i + 1);
   Chain& c = w.chains[i];
   if (c.own_stream && c.rows_cap >= rows_cap && c.pin_len >= pin_len) return MADE_OK;
+  if (w.pending) {
+    HIP_TRY(hipDeviceSynchronize());
+    w.pending = false;
+  }
   free_chain(c);
   rows_cap = round_up(rows_cap, 2 * TILE);
   HIP_TRY(hipStreamCreateWithFlags(&c.own_stream, hipStreamNonBlocking));
@@ -302,6 +323,7 @@ static int ensure_chain(made_model* m, size_t i, int rows_cap, int pin_len) {
 
 extern "C" int made_free(made_model* m) {
   if (!m) return MADE_OK;
+  if (m->ws.pending) (void)hipDeviceSynchronize();
   for (Layer& l : m->layers) {
     if (l.W) (void)hipFree(l.W);
     if (l.bias) (void)hipFree(l.bias);
@@ -1262,6 +1284,7 @@ extern "C" int made_forward_logits(made_model* m, const uint8_t* x, int32_t N, f
   hipStream_t s = (hipStream_t)stream;
   const bool was_profiling = m->profiling;
   m->profiling = false;  // this call does not wait for the stream, so it cannot read event times
+  TRY(settle(m, s));
   TRY(ensure_workspace(m, N, false));
   if (m->arch == 1) {
     const void* last = nullptr;
@@ -1355,8 +1378,8 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
   SampleIO io{noise, x, blk.a, blk.b, RetireArgs{}};
   if (blk.stop_test) {
     const int slot = (int)c.log_first.size();
-    if (slot >= c.pin_len - 1) return fail(MADE_ERR_HIP, "internal: pass log overflow");   // (the last word mirrors the flags)
-    c.h_pin[slot] = -1;
+    if (slot >= c.pin_half - 1) return fail(MADE_ERR_HIP, "internal: pass log overflow");   // (the half's last word mirrors the flags)
+    c.h_pin[c.pin_base + slot] = -1;
     io.retire.rows_in = c.rows[in];
     io.retire.n_in = c.n_rows[in];
     io.retire.rows_out = c.rows[out];
@@ -1365,8 +1388,8 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
     io.retire.iters = w.call_iters;
     io.retire.flags = w.flags;
     io.retire.done_ctr = c.done_ctr;
-    io.retire.host_slot = c.d_pin + slot;
-    io.retire.host_flags = c.d_pin + (c.pin_len - 1);
+    io.retire.host_slot = c.d_pin + c.pin_base + slot;
+    io.retire.host_flags = c.d_pin + c.pin_base + (c.pin_half - 1);
     io.retire.last_pass = (k == blk.cap);
     io.retire.flag_unconverged = flag_unconverged;
     io.retire.enabled = 1;
@@ -1402,8 +1425,10 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
   int total_passes = 0;
   for (const Block& b : blocks) total_passes += b.cap;
   for (int i = 0; i < n_chains; ++i) {
-    TRY(ensure_chain(m, (size_t)i, per, total_passes + 8));
+    TRY(ensure_chain(m, (size_t)i, per, 2 * (total_passes + 8)));
     Chain& c = w.chains[i];
+    c.pin_half = c.pin_len / 2;
+    c.pin_base = (int)(c.calls++ & 1u) * c.pin_half;
     c.first = i * per;
     c.count = std::min(per, N - c.first);
     c.block = 0;
@@ -1413,7 +1438,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
     c.stream = n_chains == 1 ? s : c.own_stream;   // a single chain needs no fork and join
   }
   w.call_iters = iters_out ? iters_out : w.iters;
-  for (int i = 0; i < n_chains; ++i) w.chains[i].h_pin[w.chains[i].pin_len - 1] = 0;
+  for (int i = 0; i < n_chains; ++i) w.chains[i].h_pin[w.chains[i].pin_base + w.chains[i].pin_half - 1] = 0;
   if (n_chains == 1 && m->arch == 0) {
     // one chain on the caller's stream: the kernel that sets up the iterate also resets the chain's list and counters
     Chain& c = w.chains[0];
@@ -1461,7 +1486,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
         // look (without blocking) at the oldest unconfirmed pass of this block
         if (c.k_conf < c.k_enq) {
           const int slot = (int)c.log_first.size() - (c.k_enq - c.k_conf);
-          const int left = c.h_pin[slot];
+          const int left = c.h_pin[c.pin_base + slot];
           if (left >= 0) {
             c.k_conf++;
             progressed = true;
@@ -1492,20 +1517,47 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
       return fail(MADE_ERR_HIP, "device did not report the stop test of a pass within 30 s");
     }
   }
-  // (pass counts went straight to iters_out, the flags come through the chains' pinned words: no copies)
+  // Pass counts went straight to iters_out and the flags come through the chains' pinned words, so nothing is
+  // copied back.  The call does not wait for the stream to drain either: it returns once the device has reported
+  // every pass whose result matters.  What may still be queued are passes enqueued speculatively behind the one
+  // that left no sample active: they find an empty list, touch nothing but the model's scratch memory, and are
+  // ordered before whatever the caller enqueues next on this stream.
+  const bool must_sync = m->arch == 1 || m->profiling;
   if (m->arch == 1)
     HIP_TRY(hipMemcpyAsync((void*)&w.h_pin[2], m->conv.rows_stat, sizeof(unsigned long long), hipMemcpyDeviceToHost, s));
-  HIP_TRY(hipStreamSynchronize(s));
+  if (must_sync) {
+    HIP_TRY(hipStreamSynchronize(s));
+    w.pending = false;
+    m->stats[3]++;
+  } else {
+    const auto t0 = std::chrono::steady_clock::now();
+    for (int i = 0; i < n_chains; ++i) {
+      const Chain& c = w.chains[i];
+      bool drained = false;             // a pass of this block has reported an empty list
+      for (size_t j = 0; j < c.log_first.size(); ++j) {
+        if (c.log_first[j]) drained = false;
+        if (drained) continue;
+        uint64_t polls = 0;
+        while (c.h_pin[c.pin_base + j] < 0) {
+          if ((++polls & 0xfff) == 0 &&
+              std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() > 30.0)
+            return fail(MADE_ERR_HIP, "device did not report the stop test of a pass within 30 s");
+        }
+        if (c.h_pin[c.pin_base + j] == 0) drained = true;
+      }
+    }
+    w.pending = true;
+    w.pending_stream = s;
+  }
   int call_flags = 0;
-  for (int i = 0; i < n_chains; ++i) call_flags |= w.chains[i].h_pin[w.chains[i].pin_len - 1];
+  for (int i = 0; i < n_chains; ++i) call_flags |= w.chains[i].h_pin[w.chains[i].pin_base + w.chains[i].pin_half - 1];
   if (m->arch == 1) {
     unsigned long long rows = 0;
     memcpy(&rows, (const void*)&w.h_pin[2], sizeof rows);
     m->stats[4] = (int64_t)rows;
   }
-  m->stats[3]++;
   prof_collect(m);
-  // statistics from the chains' pass logs (complete now that everything has run)
+  // statistics from the chains' pass logs
   for (int i = 0; i < n_chains; ++i) {
     const Chain& c = w.chains[i];
     int64_t passes = 0;
@@ -1516,7 +1568,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
         passes++;
         m->stats[1] += active_in;
       }
-      active_in = c.h_pin[j];
+      active_in = std::max(0, (int)c.h_pin[c.pin_base + j]);   // (an unreported pass is one that found the list empty)
     }
     m->stats[0] = std::max(m->stats[0], passes);
   }
@@ -1533,6 +1585,7 @@ extern "C" int sequential_sample(made_model* m, const float* noise, int32_t N, i
   hipStream_t s = (hipStream_t)stream;
   memset(m->stats, 0, sizeof m->stats);
   m->ev_layer.clear();
+  TRY(settle(m, s));
   TRY(ensure_workspace(m, N, true));
   std::vector<Block> blocks;
   blocks.reserve(m->D);
@@ -1696,6 +1749,7 @@ extern "C" int jacobi_sample(made_model* m, const float* noise, int32_t N, const
   hipStream_t s = (hipStream_t)stream;
   memset(m->stats, 0, sizeof m->stats);
   m->ev_layer.clear();
+  TRY(settle(m, s));
   TRY(ensure_workspace(m, N, true));
   const int cap = (max_iters <= 0 || max_iters > m->D) ? m->D : max_iters;
   bool done = false;
@@ -1715,6 +1769,7 @@ extern "C" int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, co
   hipStream_t s = (hipStream_t)stream;
   memset(m->stats, 0, sizeof m->stats);
   m->ev_layer.clear();
+  TRY(settle(m, s));
   TRY(ensure_workspace(m, N, true));
   bool done = false;
   TRY(run_persistent(m, noise, N, x_init, x_out, block, m->D, false, iters_out, s, &done));
@@ -1739,6 +1794,7 @@ extern "C" int made_forward_params(made_model* m, const float* x, int32_t N, flo
   hipStream_t s = (hipStream_t)stream;
   const bool was_profiling = m->profiling;
   m->profiling = false;
+  TRY(settle(m, s));
   TRY(ensure_workspace(m, N, false));
   TRY(launch_init_state(m, (const uint8_t*)x, nullptr, N, s));
   RowSet rs{nullptr, nullptr, N};
@@ -1764,6 +1820,7 @@ extern "C" int sequential_sample_real(made_model* m, const float* noise, int32_t
   memset(m->stats, 0, sizeof m->stats);
   m->ev_layer.clear();
   m->call_eps = 0.f;
+  TRY(settle(m, s));
   TRY(ensure_workspace(m, N, true));
   std::vector<Block> blocks;
   blocks.reserve(m->D);
@@ -1788,6 +1845,7 @@ extern "C" int jacobi_sample_real(made_model* m, const float* noise, int32_t N, 
   memset(m->stats, 0, sizeof m->stats);
   m->ev_layer.clear();
   m->call_eps = eps;
+  TRY(settle(m, s));
   TRY(ensure_workspace(m, N, true));
   const int cap = (max_iters <= 0 || max_iters > m->D) ? m->D : max_iters;
   std::vector<Block> blocks(1, make_block(m, 0, m->D, cap, false));
@@ -1804,6 +1862,7 @@ extern "C" int gs_jacobi_sample_real(made_model* m, const float* noise, int32_t 
   memset(m->stats, 0, sizeof m->stats);
   m->ev_layer.clear();
   m->call_eps = eps;
+  TRY(settle(m, s));
   TRY(ensure_workspace(m, N, true));
   std::vector<Block> blocks;
   for (int a = 0; a < m->D; a += block) {
@@ -1851,6 +1910,7 @@ extern "C" int jacobi_gs_sample(made_model* m, const float* noise, int32_t N, co
   const int V = (int)V64;
   const int row_tiles = V / TILE, tiles_per_block = np / TILE;
   const int cap = (max_iters <= 0 || max_iters > M) ? M : max_iters;
+  TRY(settle(m, s));
   TRY(ensure_workspace(m, V, false));
   Workspace& w = m->ws;
   TRY(grow(&m->jgs_xv, &m->jgs_xv_cap, (size_t)V * D));
