@@ -244,10 +244,11 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   Bernoulli models in ONE launch: a workgroup keeps 32 samples' iterate and hidden activations in its LDS for the
  *   whole call, streams the masked weights from L2 and runs every pass (and block) without leaving the compute
  *   unit.  It needs input plus hidden activations of 32 samples to fit 160 KB of LDS (e.g. D = 784 with 2 x 512
- *   hidden units in bf16; not 2 x 2000).  0 = never; 1 = whenever the model fits; 2 = where it pays: always for
- *   gs_jacobi_sample (short passes, otherwise dominated by launch gaps), for jacobi_sample only while a pass
- *   streams at most 768 KB of visible weights (one compute unit streams them all).  Same symbols and pass counts
- *   as the per-layer path except possibly where a decision margin vanishes (see resident.hpp).
+ *   hidden units in bf16; not 2 x 2000).  0 = never; 1 = whenever the model fits; 2 = where it pays: for
+ *   gs_jacobi_sample (short passes, otherwise dominated by dependent launches: 2x and more), not for jacobi_sample
+ *   (a whole-network pass streams every visible weight through one compute unit: at best even with the per-layer
+ *   launches that use all of them).  Same symbols and pass counts as the per-layer path except possibly where a
+ *   decision margin vanishes (see resident.hpp).
  *   MADE_OPT_PREFIX_CACHE (default 1): GS-Jacobi on the masked MLP keeps the activations of the hidden units whose
  *   inputs all lie before the current block (degree <= block start: they are final) after the block's first
  *   pass and only re-evaluates the units behind them; 0 re-evaluates every visible unit in every pass.

@@ -183,7 +183,6 @@ struct made_model {
   int use_persistent = 0;                     // made_set_option(MADE_OPT_PERSISTENT); off: measured slower, see header
   // sample-resident kernel (resident_sampler_kernel): LDS layout, 0 bytes = this model does not fit
   int use_resident = 2;                       // made_set_option(MADE_OPT_RESIDENT): 0 never, 1 whenever it fits, 2 where it pays
-  int64_t res_pass_bytes = 0;                 // visible weights one full pass streams, in bytes
   int res_lds_bytes = 0, res_lds_enc = 0, res_lds_clear = 0;
   std::vector<int> res_lds_out, res_lds_bias, res_lds_kend, res_lds_cnt;
   unsigned long long* res_ctr = nullptr;      // device, 4 words, zero between calls
@@ -658,8 +657,6 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
       if (le == hipSuccess) le = hipMemset(m->res_ctr, 0, 4 * sizeof(unsigned long long));
       if (le == hipSuccess) le = hipHostMalloc((void**)&m->res_host, 4 * sizeof(unsigned long long), hipHostMallocDefault);
       if (le == hipSuccess) m->res_lds_bytes = off;
-      m->res_pass_bytes = 0;
-      for (int l = 0; l <= L; ++l) m->res_pass_bytes += m->nnz[l] * es;
     }
     (void)hipGetLastError();
   }
@@ -1685,9 +1682,10 @@ static int run_resident(made_model* m, const float* noise, int N, const uint8_t*
   *done = false;
   if (m->arch != 0 || m->real || !m->use_resident || m->res_lds_bytes <= 0) return MADE_OK;
   // One compute unit streams every visible weight of a pass (measured ~70 GB/s), against all of them in the
-  // per-layer launches (whose passes cost ~25 us in launch gaps at batch ~100): whole-network passes pay up to
-  // about 3/4 MB of visible weights, the short passes of GS-Jacobi blocks always.
-  if (m->use_resident == 2 && block >= m->D && m->res_pass_bytes > RES_AUTO_PASS_BYTES) return MADE_OK;
+  // per-layer launches, whose passes cost ~20 us in dependent launches at batch ~100: the short passes of
+  // GS-Jacobi blocks are where the resident kernel pays (2x and more); whole-network Jacobi passes are at best
+  // even (0.116 vs 0.113 ms on a 196 / 2 x 500 network, 0.146 vs 0.097 ms on 784 / 2 x 512).
+  if (m->use_resident == 2 && block >= m->D) return MADE_OK;
   Workspace& w = m->ws;
   ResidentArgs p;
   memset(&p, 0, sizeof p);

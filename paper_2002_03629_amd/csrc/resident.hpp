@@ -23,7 +23,6 @@ constexpr int RES_W = 8;       // waves per workgroup; each owns whole unit tile
 constexpr int RES_R = JM_RES_R;       // weight chunks a wave keeps in flight (ring of register slots)
 constexpr int RES_MAXT = 4;    // output tiles a wave can own (their noise stays in registers)
 constexpr int RES_ROWS = 32;   // samples per workgroup (one MFMA tile)
-constexpr long long RES_AUTO_PASS_BYTES = 768 * 1024;   // whole-network passes are served up to this many visible weight bytes
 
 struct ResidentLayer {
   const void* W;
