@@ -267,3 +267,57 @@ def test_large_batch_uses_big_tiles(name, N):
         assert_sample_parity(same, noise, xb, xs, margins)
         xq = g.sequential(noise, 1)
         assert_sample_parity(same, noise, xq, xs, margins)
+
+
+@pytest.mark.parametrize("name", ["small_bf16", "mid_bf16", "small_cat_f32"])
+def test_back_to_back_calls_without_synchronisation(name):
+    """The sampling calls return before the stream has drained (a speculative, empty pass may still be queued).
+    Many calls in a row, on one stream and alternating between two, with different noise, batch sizes and initial
+    iterates and no synchronisation in between, must each give the result they give on their own."""
+    w = S.workload(name)
+    net = S.make_network(w, with_bias=True)
+    _, same = oracle_models(net)
+    hi = 2 if w.C == 1 else w.C
+    cases = []
+    for r in range(12):
+        N = [w.N, 5, 33, w.N, 1, 64][r % 6]
+        noise = S.make_noise(w, rep=r, N=N)
+        init = None if r % 3 else np.random.default_rng(r).integers(0, hi, (N, w.D)).astype(np.uint8)
+        cases.append((N, noise, init))
+    with GpuModel(net) as g:
+        alone = []
+        for N, noise, init in cases:                      # every call on its own, synchronised
+            x, it = g.jacobi(noise, init)
+            assert_sample_parity(same, noise, x)
+            alone.append((x, it))
+        side = torch.cuda.Stream()
+        for streams in ([None] * len(cases), [None if i % 2 else side for i in range(len(cases))]):
+            outs = []
+            for (N, noise, init), st in zip(cases, streams):
+                un, xin = dev(noise), (None if init is None else dev(init))
+                x = torch.empty((N, w.D), dtype=torch.uint8, device="cuda")
+                it = torch.empty((N,), dtype=torch.int32, device="cuda")
+                if st is not None:
+                    st.wait_stream(torch.cuda.current_stream())      # the inputs were uploaded on the current stream
+                B.jacobi_sample(g.h, un, N, xin, 0, x, it, st)
+                outs.append((x, it, un, xin))
+            torch.cuda.synchronize()
+            for (x, it, _, _), (xa, ita) in zip(outs, alone):
+                assert (x.cpu().numpy() == xa).all() and (it.cpu().numpy() == ita).all()
+        # GS-Jacobi and the sequential sampler interleaved with Jacobi, same stream, one synchronisation at the end
+        N, noise, _ = cases[0]
+        un = dev(noise)
+        res = []
+        for call in ("gs", "jacobi", "seq", "gs", "jacobi"):
+            x = torch.empty((N, w.D), dtype=torch.uint8, device="cuda")
+            it = torch.zeros((N,), dtype=torch.int32, device="cuda")
+            if call == "gs":
+                B.gs_jacobi_sample(g.h, un, N, None, 7, x, it)
+            elif call == "jacobi":
+                B.jacobi_sample(g.h, un, N, None, 0, x, it)
+            else:
+                B.sequential_sample(g.h, un, N, 1, x)
+            res.append(x)
+        torch.cuda.synchronize()
+        for x in res:
+            assert (x.cpu().numpy() == alone[0][0]).all()
