@@ -253,7 +253,7 @@ static int ensure_workspace(made_model* m, int N, bool need_z) {
     if (!cv.rows_stat) HIP_TRY(hipMalloc((void**)&cv.rows_stat, sizeof(unsigned long long)));
     const int n_pad = round_up(cap, 2 * TILE);
     HIP_TRY(hipEventCreateWithFlags(&w.fork_ev, hipEventDisableTiming));
-    HIP_TRY(hipMalloc((void**)&w.changed, (size_t)2 * n_pad * sizeof(int)));
+    HIP_TRY(hipMalloc((void**)&w.changed, (size_t)2 * n_pad * CHG * sizeof(int)));   // one counter per 128-byte line
     w.n_pad = n_pad;
     HIP_TRY(hipMalloc((void**)&w.iters, (size_t)n_pad * sizeof(int)));
     HIP_TRY(hipMalloc((void**)&w.flags, sizeof(int)));
@@ -281,7 +281,7 @@ static int ensure_workspace(made_model* m, int N, bool need_z) {
     HIP_TRY(hipMalloc((void**)&w.zbuf, (size_t)cap * m->D * m->C * sizeof(float)));
   }
   HIP_TRY(hipEventCreateWithFlags(&w.fork_ev, hipEventDisableTiming));
-  HIP_TRY(hipMalloc((void**)&w.changed, (size_t)2 * n_pad * sizeof(int)));
+  HIP_TRY(hipMalloc((void**)&w.changed, (size_t)2 * n_pad * CHG * sizeof(int)));   // one counter per 128-byte line
   w.n_pad = n_pad;
   HIP_TRY(hipMalloc((void**)&w.bar, sizeof(unsigned)));
   HIP_TRY(hipMalloc((void**)&w.dev_stats, 2 * sizeof(long long)));
@@ -1385,6 +1385,7 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
     io.retire.iters = w.call_iters;
     io.retire.flags = w.flags;
     io.retire.done_ctr = c.done_ctr;
+    io.retire.n_max = c.count;
     io.retire.host_slot = c.d_pin + c.pin_base + slot;
     io.retire.host_flags = c.d_pin + c.pin_base + (c.pin_half - 1);
     io.retire.last_pass = (k == blk.cap);

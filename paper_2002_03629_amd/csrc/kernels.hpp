@@ -91,6 +91,10 @@ static_assert(PD >= 1 && PD <= 8, "prefetch depth must be 1..8");
 constexpr int XCDS = 8;    // workgroup i is dispatched to XCD i % 8; each XCD has its own L2
 
 enum Epilogue { EPI_RELU = 0, EPI_LOGITS = 1, EPI_BERNOULLI = 2, EPI_LOGISTIC = 3 };
+// Per-sample changed counters sit one per 128-byte line (index sample * CHG): every workgroup that redraws
+// positions of a sample adds to its counter, and atomics on one line are performed one after the other (~1.3 ns
+// each), so 128 counters packed into four lines made the ~3000 atomics of a cfg2 pass queue up for a microsecond.
+constexpr int CHG = 32;
 constexpr float LOGISTIC_A_LO = -6.0f, LOGISTIC_A_HI = 3.0f;   // the log-scale output is clipped to this range
 
 // What the last workgroup of a pass's final kernel does once every workgroup is done: retire the
@@ -105,6 +109,7 @@ struct RetireArgs {
   int* flags;            // bit 0: some sample was still changing after the last allowed pass
   int* done_ctr;         // workgroups finished so far in this kernel (cleared here)
   int* host_slot;        // device-visible pinned host word receiving the new active count
+  int n_max;             // upper bound of *n_in known to the host (the chain's size): bounds the early read of rows_in
   int* host_flags;       // device-visible pinned host word mirroring *flags (the host reads it after the call's last
                          // kernel has finished)
   int last_pass;
@@ -192,15 +197,28 @@ __device__ __forceinline__ void mfma_chunk<float>(const uint4 (&a)[4], const uin
   }
 }
 
+#ifdef JM_TRACE
+__device__ unsigned long long g_tile_trace[1024 * 8];
+#define JM_TSTAMP(i, drain)                                                           \
+  do {                                                                                \
+    if (drain) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");            \
+    if (threadIdx.x == 0 && blockIdx.x < 1024) g_tile_trace[blockIdx.x * 8 + (i)] = wall_clock64(); \
+  } while (0)
+#else
+#define JM_TSTAMP(i, drain) do { } while (0)
+#endif
+
 // Stop test and compaction (the forward-difference test of Algorithm 1 with tolerance 0, per
 // sample): every active sample took one more pass; those whose symbols changed stay active, in
 // order, unless this was the last allowed pass.  Runs in ONE workgroup, after all others finished.
-__device__ __forceinline__ void retire_tail(const RetireArgs& r) {
+// pre_n / pre_row: *r.n_in and r.rows_in[threadIdx.x], read by every workgroup before it reported in (neither
+// changes during the kernel), so that the one that runs this is a memory round trip shorter.
+__device__ __forceinline__ void retire_tail(const RetireArgs& r, int pre_n, int pre_row) {
   __shared__ int wave_total[NW];
   __shared__ int base_s;
   const int nthreads = blockDim.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = nthreads >> 6;
-  const int n_rows = *r.n_in;
+  const int n_rows = pre_n;
   if (threadIdx.x == 0) base_s = 0;
   __syncthreads();
   for (int start = 0; start < n_rows; start += nthreads) {
@@ -208,10 +226,10 @@ __device__ __forceinline__ void retire_tail(const RetireArgs& r) {
     int sample = -1;
     bool keep = false;
     if (rix < n_rows) {
-      sample = r.rows_in[rix];
+      sample = start == 0 ? pre_row : r.rows_in[rix];
       // counters were built with device-scope atomics by workgroups on other XCDs: read them the same way
-      const int c = __hip_atomic_load(&r.changed[sample], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      r.changed[sample] = 0;
+      const int c = __hip_atomic_load(&r.changed[(size_t)sample * CHG], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      r.changed[(size_t)sample * CHG] = 0;
       r.iters[sample] += 1;
       keep = (c > 0) && !r.last_pass;
       if (c > 0 && r.last_pass && r.flag_unconverged) {
@@ -262,27 +280,25 @@ __device__ __forceinline__ void count_changed(int* counter, int cnt) {
 // its own counter atomics return before it bumps done_ctr, so no cache write-back is needed here.
 __device__ __forceinline__ void finish_pass(const RetireArgs& r, int total_workgroups) {
   __shared__ int is_last_s;
+  const int pre_n = *r.n_in;
+  const int pre_row = (int)threadIdx.x < r.n_max ? r.rows_in[threadIdx.x] : 0;
   __syncthreads();
+  JM_TSTAMP(6, 0);
   if (threadIdx.x == 0)
     is_last_s = (__hip_atomic_fetch_add(r.done_ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
                  total_workgroups - 1);
   __syncthreads();
-  if (is_last_s) retire_tail(r);
+  JM_TSTAMP(7, 0);
+  if (is_last_s) {
+    retire_tail(r, pre_n, pre_row);
+#ifdef JM_TRACE
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    if (threadIdx.x == 0) g_tile_trace[1023 * 8] = wall_clock64();
+#endif
+  }
 }
 
-#ifdef JM_TRACE
-__device__ unsigned long long g_tile_trace[1024 * 8];
-#define JM_TSTAMP(i, drain)                                                           \
-  do {                                                                                \
-    if (drain) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");            \
-    if (threadIdx.x == 0 && blockIdx.x < 1024) g_tile_trace[blockIdx.x * 8 + (i)] = wall_clock64(); \
-  } while (0)
-#else
-#define JM_TSTAMP(i, drain) do { } while (0)
-#endif
 
-// CNT chunks c0, c0 + NW, ... of one wave: every load is issued before the first MFMA.  Ap / Wp point at
-// the lane's 16 bytes of slot 0 in chunk 0 of its row group; a chunk is 256 uint4, a slot 64 uint4.
 // 16 bytes that another workgroup of the SAME kernel may have written (through publish<true>) before the last
 // grid barrier: device-scope loads, which are served coherently without this XCD's caches having been
 // invalidated as a whole (that would also drop the weights every layer re-reads).
@@ -294,6 +310,8 @@ __device__ __forceinline__ uint4 load_shared16(const uint4* p) {
   return make_uint4((unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32));
 }
 
+// CNT chunks c0, c0 + NW, ... of one wave: every load is issued before the first MFMA.  Ap / Wp point at
+// the lane's 16 bytes of slot 0 in chunk 0 of its row group; a chunk is 256 uint4, a slot 64 uint4.
 template <typename T, int CNT, bool COH>
 __device__ __forceinline__ void chunk_group(const uint4* Ap, const uint4* Wp, int c0, f32x16& acc) {
   static_assert(CNT >= 1 && CNT <= PD, "group larger than the prefetch depth");
@@ -421,6 +439,12 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
   __syncthreads();
   JM_TSTAMP(3, 1);
 
+  // The changed-count atomics of the EPT rows are issued without waiting for one another; their old values are
+  // waited for once, behind the loop (every atomic must have been performed before this workgroup reports in:
+  // see finish_pass).  One wait instead of EPT dependent round trips of ~1.2 us each.
+  int count_old[EPT];
+#pragma unroll
+  for (int j = 0; j < EPT; ++j) count_old[j] = 0;
 #pragma unroll
   for (int j = 0; j < EPT; ++j) {
     const int rr = (threadIdx.x >> 5) + j * (NW * 2);
@@ -452,7 +476,8 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
       cnt += __shfl_xor(cnt, 4);
       cnt += __shfl_xor(cnt, 8);
       cnt += __shfl_xor(cnt, 16);
-      if (cc == 0 && cnt > 0) count_changed(&a.changed[sample], cnt);
+      if (cc == 0 && cnt > 0)
+        count_old[j] = __hip_atomic_fetch_add(&a.changed[(size_t)sample * CHG], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     } else {  // EPI_BERNOULLI: x_t = 1 iff u_t < sigmoid(z_t); count changes per sample
       int cnt = 0;
       if (row_ok && col_live) {
@@ -470,8 +495,13 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
       cnt += __shfl_xor(cnt, 4);
       cnt += __shfl_xor(cnt, 8);
       cnt += __shfl_xor(cnt, 16);
-      if (cc == 0 && cnt > 0) count_changed(&a.changed[sample], cnt);
+      if (cc == 0 && cnt > 0)
+        count_old[j] = __hip_atomic_fetch_add(&a.changed[(size_t)sample * CHG], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
+  }
+  if (EPI == EPI_BERNOULLI || EPI == EPI_LOGISTIC) {
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) asm volatile("" ::"v"(count_old[j]));
   }
   JM_TSTAMP(4, 0);
   JM_TSTAMP(5, 1);
@@ -709,7 +739,7 @@ __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
       });
       if (EPI == EPI_BERNOULLI) {   // the two lanes of a row
         cnt += __shfl_xor(cnt, 1);
-        if ((lane & 1) == 0 && cnt > 0) count_changed(&a.changed[sample], cnt);
+        if ((lane & 1) == 0 && cnt > 0) count_changed(&a.changed[(size_t)sample * CHG], cnt);
       }
     });
   }
@@ -834,7 +864,7 @@ __global__ __launch_bounds__(NW * 64) void persistent_sampler_kernel(PersistArgs
   }
   if (blockIdx.x == 0) {
     for (int i = threadIdx.x; i < N; i += NT) p.iters[i] = 0;
-    for (int i = threadIdx.x; i < 2 * p.n_pad; i += NT) publish<true>(p.changed + i, 0);
+    for (int i = threadIdx.x; i < 2 * p.n_pad; i += NT) publish<true>(p.changed + (size_t)i * CHG, 0);
   }
   if (!grid_barrier(p.bar, epoch, p.flags, p.spin_limit)) return;
 
@@ -851,7 +881,7 @@ __global__ __launch_bounds__(NW * 64) void persistent_sampler_kernel(PersistArgs
     const int cap = gs ? (b0 - a0) : p.cap;
     for (int k = 1; k <= cap && n_rows > 0; ++k) {
       const int row_tiles = (n_rows + TILE - 1) / TILE;
-      int* changed = p.changed + parity * p.n_pad;
+      int* changed = p.changed + (size_t)parity * p.n_pad * CHG;
       // ---- hidden layers (GS: only units of degree < b0 matter to positions <= b0)
       int in_limit = gs ? b0 - 1 : -1;
       for (int l = 0; l < L; ++l) {
@@ -933,7 +963,7 @@ __global__ __launch_bounds__(NW * 64) void persistent_sampler_kernel(PersistArgs
         bool keep = false;
         if (rix < n_rows) {
           sample = rows_s[rix];
-          const int c = __hip_atomic_load(&changed[sample], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const int c = __hip_atomic_load(&changed[(size_t)sample * CHG], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           keep = (c > 0) && !last_pass;
           if (blockIdx.x == 0) {
             p.iters[sample] += 1;
@@ -951,8 +981,8 @@ __global__ __launch_bounds__(NW * 64) void persistent_sampler_kernel(PersistArgs
         __syncthreads();
       }
       if (blockIdx.x == 0) {
-        int* other = p.changed + (parity ^ 1) * p.n_pad;
-        for (int i = threadIdx.x; i < N; i += NT) publish<true>(other + i, 0);
+        int* other = p.changed + (size_t)(parity ^ 1) * p.n_pad * CHG;
+        for (int i = threadIdx.x; i < N; i += NT) publish<true>(other + (size_t)i * CHG, 0);
       }
       n_rows = new_n;
       parity ^= 1;
@@ -1136,7 +1166,7 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
                 Elem<T>::from_f32(((float)xn - 128.0f) * (1.0f / 128.0f));
         }
       }
-      if (differs) count_changed(&a.changed[sample], 1);
+      if (differs) count_changed(&a.changed[(size_t)sample * CHG], 1);
     }
   }
   if (a.retire.enabled) finish_pass(a.retire, gridDim.x);
@@ -1712,7 +1742,7 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
     if (lane == 0 && changed_mask != 0) {
       // returning atomics, so that "the value came back" means "performed"; the values are only consumed
       // after the loop (before the tail counters), so a row does not wait for them
-      sink += __hip_atomic_fetch_add(&a.changed[n], __popcll(changed_mask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      sink += __hip_atomic_fetch_add(&a.changed[(size_t)n * CHG], __popcll(changed_mask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (a.first_changed)
         sink += __hip_atomic_fetch_min(&a.first_changed[n], y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -1786,7 +1816,7 @@ __global__ __launch_bounds__(256) void gumbel_argmax_kernel(const float* __restr
   if (lane == 0) {
     const size_t idx = (size_t)sample * D + t;
     const uint8_t xn = (uint8_t)best_c;
-    if (xn != x[idx]) count_changed(&changed[sample], 1);
+    if (xn != x[idx]) count_changed(&changed[(size_t)sample * CHG], 1);
     x[idx] = xn;
     enc[frag_offset<T>(sample, t, enc_chunks)] = Elem<T>::from_f32(((float)xn - 128.0f) * (1.0f / 128.0f));
   }
@@ -1815,7 +1845,7 @@ __device__ __forceinline__ void call_reset(const CallReset& r) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < (size_t)r.padded; i += stride) {
     r.rows[i] = (int)i < r.count ? r.first + (int)i : r.first;
     if ((int)i < r.count) {
-      r.changed[r.first + i] = 0;
+      r.changed[(size_t)(r.first + i) * CHG] = 0;
       r.iters[r.first + i] = 0;
     }
     if (i == 0) {
@@ -1903,7 +1933,7 @@ __global__ void reset_rows_kernel(int* rows, int* n_rows, int first, int count, 
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < padded) rows[i] = i < count ? first + i : first;
   if (i < count) {
-    changed[first + i] = 0;
+    changed[(size_t)(first + i) * CHG] = 0;
     if (iters) iters[first + i] = 0;
   }
   if (i == 0) {
