@@ -835,6 +835,7 @@ struct RowSet {            // which samples a pass covers
   const int* n_rows_ptr;   // device count or NULL
   int n_rows;              // host-side upper bound (grid size) and value when n_rows_ptr is NULL
   const uint8_t* x = nullptr;   // current symbols [N, D]: what a one-hot first layer reads instead of the scalar encoding
+  int pos_base = 0;             // first sample of the chain the list belongs to (see LayerArgs::pos_base)
 };
 
 struct SampleIO {          // what the sampling epilogue reads and writes
@@ -925,6 +926,7 @@ static LayerArgs base_args(const made_model* m, int l, const void* A, const RowS
   a.n_rows = rs.n_rows;
   a.n_rows_pad = round_up(std::max(rs.n_rows, 1), 2 * TILE);
   a.n_cols = ly.out_dim;
+  a.pos_base = rs.pos_base;
   return a;
 }
 
@@ -932,8 +934,15 @@ static LayerArgs base_args(const made_model* m, int l, const void* A, const RowS
 // first unit_limit[l] (degree-sorted) units are evaluated, reading only the first in_limit inputs.
 // unit_first (optional): units below unit_first[l] are frozen -- their inputs are final and their activations
 // are already in the layer's buffer from an earlier pass -- so only the tiles from there on are evaluated.
+// by_pos: hidden activations are stored by position in the active list (see LayerArgs::a_by_pos); the caller
+// then runs the output layer the same way.  Only for whole-layer passes on the 32 x 32 tile kernels.
+static bool hidden_by_position(const made_model* m, const RowSet& rs, bool limited) {
+  return m->arch == 0 && !limited && !m->onehot && (m->C == 1 || m->real) && rs.rows != nullptr &&
+         rs.n_rows < m->big_batch;
+}
+
 static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, int in_limit0, hipStream_t s,
-                      const int* unit_first = nullptr) {
+                      const int* unit_first = nullptr, bool by_pos = false) {
   const int row_tiles = (rs.n_rows + TILE - 1) / TILE;
   const int kc = chunk_elems(m);
   int in_limit = in_limit0;
@@ -946,6 +955,8 @@ static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, in
     if (unit_limit && unit_limit[l] >= 0) tiles = std::min(tiles, (unit_limit[l] + TILE - 1) / TILE);
     if (in_limit >= 0) a.k_cap = std::min(ly.in_pad, round_up(in_limit, kc));
     if (unit_first) a.tile_begin = std::min(tiles, unit_first[l] / TILE);
+    a.a_by_pos = by_pos && l > 0;
+    a.out_by_pos = by_pos;
     if (l == 0 && m->onehot) {
       if (!rs.x) return fail(MADE_ERR_ARG, "internal: a one-hot first layer needs the symbols");
       if (rs.n_rows > 65535) return fail(MADE_ERR_ARG, "one-hot input: at most 65535 samples per call");
@@ -987,11 +998,12 @@ static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, in
 
 // Output layer + draw for positions [t_lo, t_hi).  whole = evaluate every output tile regardless.
 static int run_output_sample(made_model* m, const RowSet& rs, const SampleIO& io, bool whole, int k_limit,
-                             hipStream_t s) {
+                             hipStream_t s, bool by_pos = false) {
   const Layer& ly = m->layers[m->L];
   const int row_tiles = (rs.n_rows + TILE - 1) / TILE;
   const int kc = chunk_elems(m);
   LayerArgs a = base_args(m, m->L, m->ws.act[m->L - 1], rs);
+  a.a_by_pos = by_pos;
   if (k_limit >= 0) a.k_cap = std::min(ly.in_pad, round_up(k_limit, kc));
   const int C = m->C;
   int tile_lo = 0, tile_hi = ly.n_tiles;
@@ -1371,7 +1383,7 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
   }
   const int k = c.k_enq + 1;
   const int in = (k - 1) & 1, out = k & 1;
-  RowSet rs{c.rows[in], c.n_rows[in], c.count, x};
+  RowSet rs{c.rows[in], c.n_rows[in], c.count, x, c.first};
   SampleIO io{noise, x, blk.a, blk.b, RetireArgs{}};
   if (blk.stop_test) {
     const int slot = (int)c.log_first.size();
@@ -1393,15 +1405,16 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
     io.retire.enabled = 1;
     c.log_first.push_back(k == 1);
   } else {
-    rs = RowSet{c.rows[0], nullptr, c.count, x};   // no stop test: every sample of the chain takes the pass
+    rs = RowSet{c.rows[0], nullptr, c.count, x, c.first};   // no stop test: every sample of the chain takes the pass
   }
   if (m->arch == 1) {
     TRY(run_conv_pass(m, c.count, io, k == 1, blk.whole_network, s));
   } else {
     // (after a block's first pass the frozen prefix of every hidden layer is reused, not recomputed)
+    const bool by_pos = hidden_by_position(m, rs, blk.limited);
     TRY(run_hidden(m, rs, blk.limited ? blk.hidden_limit.data() : nullptr, blk.in_limit, s,
-                   (blk.limited && k > 1 && m->prefix_cache) ? blk.hidden_frozen.data() : nullptr));
-    TRY(run_output_sample(m, rs, io, blk.whole_network, blk.out_k_limit, s));
+                   (blk.limited && k > 1 && m->prefix_cache) ? blk.hidden_frozen.data() : nullptr, by_pos));
+    TRY(run_output_sample(m, rs, io, blk.whole_network, blk.out_k_limit, s, by_pos));
   }
   c.k_enq = k;
   return MADE_OK;

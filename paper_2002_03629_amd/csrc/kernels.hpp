@@ -136,6 +136,12 @@ struct LayerArgs {
   const int* n_rows_ptr;
   int n_rows;
   int n_rows_pad;        // entries the list `rows` holds (reads past the active count stay inside it)
+  // Activations that live only inside one pass can be stored by POSITION in the active list instead of by
+  // sample: the layer that reads them then needs no look-up in `rows` before it can request its operands (one
+  // dependent memory round trip less per kernel).  a_by_pos: rows of A are list positions; out_by_pos: EPI_RELU
+  // writes row (list position) instead of row (sample).
+  int a_by_pos, out_by_pos;
+  int pos_base;          // first row of this chain's positions (chains run concurrently on disjoint row ranges)
   // EPI_RELU: out = next layer's activations (fragment-major, out_chunks chunks).  EPI_LOGITS: float [sample, ldo]
   void* out;
   int ldo;
@@ -211,9 +217,10 @@ __device__ unsigned long long g_tile_trace[1024 * 8];
 // Stop test and compaction (the forward-difference test of Algorithm 1 with tolerance 0, per
 // sample): every active sample took one more pass; those whose symbols changed stay active, in
 // order, unless this was the last allowed pass.  Runs in ONE workgroup, after all others finished.
-// pre_n / pre_row: *r.n_in and r.rows_in[threadIdx.x], read by every workgroup before it reported in (neither
-// changes during the kernel), so that the one that runs this is a memory round trip shorter.
-__device__ __forceinline__ void retire_tail(const RetireArgs& r, int pre_n, int pre_row) {
+// pre_n / pre_row / pre_iters: *r.n_in, r.rows_in[threadIdx.x] and that sample's pass count, read by every
+// workgroup before it reported in (none of them changes during the kernel), so that the one that runs this is
+// two dependent memory round trips shorter.
+__device__ __forceinline__ void retire_tail(const RetireArgs& r, int pre_n, int pre_row, int pre_iters) {
   __shared__ int wave_total[NW];
   __shared__ int base_s;
   const int nthreads = blockDim.x;
@@ -230,7 +237,7 @@ __device__ __forceinline__ void retire_tail(const RetireArgs& r, int pre_n, int 
       // counters were built with device-scope atomics by workgroups on other XCDs: read them the same way
       const int c = __hip_atomic_load(&r.changed[(size_t)sample * CHG], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       r.changed[(size_t)sample * CHG] = 0;
-      r.iters[sample] += 1;
+      r.iters[sample] = (start == 0 ? pre_iters : r.iters[sample]) + 1;
       keep = (c > 0) && !r.last_pass;
       if (c > 0 && r.last_pass && r.flag_unconverged) {
         atomicOr(r.flags, 1);
@@ -282,6 +289,7 @@ __device__ __forceinline__ void finish_pass(const RetireArgs& r, int total_workg
   __shared__ int is_last_s;
   const int pre_n = *r.n_in;
   const int pre_row = (int)threadIdx.x < r.n_max ? r.rows_in[threadIdx.x] : 0;
+  const int pre_iters = (int)threadIdx.x < r.n_max ? r.iters[pre_row] : 0;   // (only the retire step writes iters)
   __syncthreads();
   JM_TSTAMP(6, 0);
   if (threadIdx.x == 0)
@@ -290,7 +298,7 @@ __device__ __forceinline__ void finish_pass(const RetireArgs& r, int total_workg
   __syncthreads();
   JM_TSTAMP(7, 0);
   if (is_last_s) {
-    retire_tail(r, pre_n, pre_row);
+    retire_tail(r, pre_n, pre_row, pre_iters);
 #ifdef JM_TRACE
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     if (threadIdx.x == 0) g_tile_trace[1023 * 8] = wall_clock64();
@@ -360,7 +368,7 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
   JM_TSTAMP(0, 0);
   // Everything that does not depend on other loads is requested up front, so a tile is a chain of only
   // three memory round trips (bookkeeping, operands, results).
-  const int my_sample = rows ? rows[row0 + r] : (row0 + r < a.n_rows ? row0 + r : 0);
+  const int my_sample = a.a_by_pos ? a.pos_base + row0 + r : (rows ? rows[row0 + r] : (row0 + r < a.n_rows ? row0 + r : 0));
   int k_end = a.tile_kend[tile];
   const float bias = a.bias[col];
   int e_sample[EPT];
@@ -456,7 +464,9 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
     v += bias;
 
     if (EPI == EPI_RELU) {
-      if (row_ok) publish<COH>((T*)a.out + frag_offset<T>(sample, col, a.out_chunks), Elem<T>::from_f32(fmaxf(v, 0.f)));
+      if (row_ok)
+        publish<COH>((T*)a.out + frag_offset<T>(a.out_by_pos ? a.pos_base + row0 + rr : sample, col, a.out_chunks),
+                     Elem<T>::from_f32(fmaxf(v, 0.f)));
     } else if (EPI == EPI_LOGITS) {
       if (row_ok && col < a.n_cols) ((float*)a.out)[(size_t)sample * a.ldo + col] = v;
     } else if (EPI == EPI_LOGISTIC) {
