@@ -1374,8 +1374,12 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
     // the active list restarts as the chain's whole range (blocks without a stop test never shrink it)
     if (blk.stop_test || !c.iters_cleared) {
       const int padded = round_up(c.count, 2 * TILE);   // <= c.rows_cap
-      hipLaunchKernelGGL(reset_rows_kernel, dim3((padded + 255) / 256), dim3(256), 0, s, c.rows[0], c.n_rows[0],
-                         c.first, c.count, padded, w.changed, c.iters_cleared ? nullptr : w.call_iters, c.done_ctr);
+      // (the call's first reset also fills the second list with valid ids: a tile past the active count reads
+      // list entries before it learns the count, and what an earlier, larger call left there would point
+      // outside this call's buffers)
+      hipLaunchKernelGGL(reset_rows_kernel, dim3((padded + 255) / 256), dim3(256), 0, s, c.rows[0],
+                         c.iters_cleared ? nullptr : c.rows[1], c.n_rows[0], c.first, c.count, padded, w.changed,
+                         c.iters_cleared ? nullptr : w.call_iters, c.done_ctr);
       m->stats[2]++;
       c.iters_cleared = true;
     }
@@ -1456,6 +1460,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
     CallReset r;
     r.enabled = 1;
     r.rows = c.rows[0];
+    r.rows_other = c.rows[1];
     r.n_rows = c.n_rows[0];
     r.first = c.first;
     r.count = c.count;

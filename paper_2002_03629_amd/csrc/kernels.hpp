@@ -415,6 +415,7 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
   }
 
   JM_TSTAMP(1, 1);
+  if (row0 >= n_rows) return;      // a tile past the active list (uniform; everything read so far was in bounds)
   const uint4* Ap = (const uint4*)a.A + (size_t)(my_sample >> 5) * a.k_chunks * 256 + h * 32 + (my_sample & 31);
   const uint4* Wp = (const uint4*)a.W + (size_t)tile * a.k_chunks * 256 + h * 32 + r;
   if (k_end > a.k_cap) k_end = a.k_cap;
@@ -542,8 +543,10 @@ __global__ __launch_bounds__(NW * 64) void masked_layer_kernel(LayerArgs a) {
       compute_tile<T, EPI, false>(b, j / TILE - a.tile_begin, blockIdx.x * TILE, a.rows, a.n_rows, part);
     }
   } else if (item_to_tile(blockIdx.x, a.n_launch_tiles, a.row_tiles, rel_tile, row0)) {
+    // (the active count is requested here but first looked at inside compute_tile, after the tile's other
+    // bookkeeping loads are on their way: one dependent memory round trip less than testing it first)
     const int n_rows = a.n_rows_ptr ? *a.n_rows_ptr : a.n_rows;
-    if (row0 < n_rows) compute_tile<T, EPI, false>(a, rel_tile, row0, a.rows, n_rows, part);
+    compute_tile<T, EPI, false>(a, rel_tile, row0, a.rows, n_rows, part);
   }
   if ((EPI == EPI_BERNOULLI || EPI == EPI_LOGISTIC) && a.retire.enabled) finish_pass(a.retire, gridDim.x);
 }
@@ -1841,6 +1844,7 @@ __global__ __launch_bounds__(256) void gumbel_argmax_kernel(const float* __restr
 struct CallReset {
   int enabled;
   int* rows;
+  int* rows_other;       // the chain's second list: filled with valid ids too (tiles past the active count read it)
   int* n_rows;
   int first, count, padded;
   int* changed;
@@ -1854,6 +1858,7 @@ __device__ __forceinline__ void call_reset(const CallReset& r) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < (size_t)r.padded; i += stride) {
     r.rows[i] = (int)i < r.count ? r.first + (int)i : r.first;
+    r.rows_other[i] = r.first;
     if ((int)i < r.count) {
       r.changed[(size_t)(r.first + i) * CHG] = 0;
       r.iters[r.first + i] = 0;
@@ -1938,10 +1943,11 @@ __global__ void init_state_real_kernel(const float* x_init, float* x, T* enc, in
 // a GS-Jacobi block).
 // Entries past the count, up to the list's padded length, are read as sample ids by the tile kernels (their
 // results are discarded), so they are set to a valid id of this call as well.
-__global__ void reset_rows_kernel(int* rows, int* n_rows, int first, int count, int padded, int* changed, int* iters,
-                                  int* done_ctr) {
+__global__ void reset_rows_kernel(int* rows, int* rows_other, int* n_rows, int first, int count, int padded, int* changed,
+                                  int* iters, int* done_ctr) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < padded) rows[i] = i < count ? first + i : first;
+  if (i < padded && rows_other) rows_other[i] = first;   // (only needed once per call: see enqueue_pass)
   if (i < count) {
     changed[(size_t)(first + i) * CHG] = 0;
     if (iters) iters[first + i] = 0;
