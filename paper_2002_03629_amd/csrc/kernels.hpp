@@ -289,7 +289,8 @@ __device__ __forceinline__ void finish_pass(const RetireArgs& r, int total_workg
   __shared__ int is_last_s;
   const int pre_n = *r.n_in;
   const int pre_row = (int)threadIdx.x < r.n_max ? r.rows_in[threadIdx.x] : 0;
-  const int pre_iters = (int)threadIdx.x < r.n_max ? r.iters[pre_row] : 0;   // (only the retire step writes iters)
+  // (only the retire step writes iters; an empty list reads none: iters may be the caller's memory)
+  const int pre_iters = (int)threadIdx.x < min(pre_n, r.n_max) ? r.iters[pre_row] : 0;
   __syncthreads();
   JM_TSTAMP(6, 0);
   if (threadIdx.x == 0)
@@ -377,6 +378,10 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
     const int rr = (threadIdx.x >> 5) + j * (NW * 2);
     e_sample[j] = rows ? rows[row0 + rr] : (row0 + rr < a.n_rows ? row0 + rr : 0);
   }
+  // A tile past the active list ends here (uniform).  The count was requested together with the loads above, so
+  // looking at it now costs no round trip of its own; and nothing of the caller's memory (noise, symbols) has
+  // been touched yet: a pass enqueued speculatively that finds the list empty reads the model's own memory only.
+  if (row0 >= n_rows) return;
   float e_noise[EPT];
   uint8_t e_xold[EPT];
   float e_xr[EPT];
@@ -415,7 +420,6 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
   }
 
   JM_TSTAMP(1, 1);
-  if (row0 >= n_rows) return;      // a tile past the active list (uniform; everything read so far was in bounds)
   const uint4* Ap = (const uint4*)a.A + (size_t)(my_sample >> 5) * a.k_chunks * 256 + h * 32 + (my_sample & 31);
   const uint4* Wp = (const uint4*)a.W + (size_t)tile * a.k_chunks * 256 + h * 32 + r;
   if (k_end > a.k_cap) k_end = a.k_cap;
