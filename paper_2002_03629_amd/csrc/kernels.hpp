@@ -228,16 +228,17 @@ __device__ __forceinline__ void retire_tail(const RetireArgs& r, int pre_n, int 
   const int n_rows = pre_n;
   if (threadIdx.x == 0) base_s = 0;
   __syncthreads();
-  for (int start = 0; start < n_rows; start += nthreads) {
-    const int rix = start + threadIdx.x;
+  if (n_rows <= nthreads) {
+    // ---- one row per thread (batches up to a workgroup's size: the latency-critical case)
+    const int rix = threadIdx.x;
     int sample = -1;
     bool keep = false;
     if (rix < n_rows) {
-      sample = start == 0 ? pre_row : r.rows_in[rix];
+      sample = pre_row;
       // counters were built with device-scope atomics by workgroups on other XCDs: read them the same way
       const int c = __hip_atomic_load(&r.changed[(size_t)sample * CHG], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       r.changed[(size_t)sample * CHG] = 0;
-      r.iters[sample] = (start == 0 ? pre_iters : r.iters[sample]) + 1;
+      r.iters[sample] = pre_iters + 1;
       keep = (c > 0) && !r.last_pass;
       if (c > 0 && r.last_pass && r.flag_unconverged) {
         atomicOr(r.flags, 1);
@@ -248,15 +249,81 @@ __device__ __forceinline__ void retire_tail(const RetireArgs& r, int pre_n, int 
     const int before = __popcll(mask & ((1ull << lane) - 1ull));
     if (lane == 0) wave_total[wave] = __popcll(mask);
     __syncthreads();
-    int off = base_s;
+    int off = 0;
     for (int w = 0; w < wave; ++w) off += wave_total[w];
     if (keep) r.rows_out[off + before] = sample;
-    __syncthreads();
     if (threadIdx.x == 0) {
       int tot = 0;
       for (int w = 0; w < nwaves; ++w) tot += wave_total[w];
-      base_s += tot;
+      base_s = tot;
     }
+    __syncthreads();
+  } else {
+    // ---- large lists: every thread owns a contiguous run of up to 64 rows per round (one round covers
+    // 64 * nthreads rows), reads its rows' counters in groups of independent loads, and the kept rows are
+    // placed by a prefix sum over the threads' counts: order kept, and the work is spread over the workgroup
+    // instead of one dependent round trip per nthreads rows (measured 263 us for 32768 rows that way).
+    constexpr int G = 8;
+    int base = 0;
+    bool unconverged = false;
+    for (int s0 = 0; s0 < n_rows; s0 += 64 * nthreads) {
+      const int n_here = min(n_rows - s0, 64 * nthreads);
+      const int per = (n_here + nthreads - 1) / nthreads;            // <= 64
+      const int i0 = min(s0 + n_here, s0 + (int)threadIdx.x * per), i1 = min(s0 + n_here, i0 + per);
+      unsigned long long keep = 0;
+      for (int g = i0; g < i1; g += G) {
+        int sample[G], c[G], itv[G];
+#pragma unroll
+        for (int q = 0; q < G; ++q) sample[q] = g + q < i1 ? r.rows_in[g + q] : -1;
+#pragma unroll
+        for (int q = 0; q < G; ++q) {
+          c[q] = 0;
+          itv[q] = 0;
+          if (sample[q] >= 0) {
+            c[q] = __hip_atomic_load(&r.changed[(size_t)sample[q] * CHG], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            itv[q] = r.iters[sample[q]];
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < G; ++q) {
+          if (sample[q] >= 0) {
+            r.changed[(size_t)sample[q] * CHG] = 0;
+            r.iters[sample[q]] = itv[q] + 1;
+            if (c[q] > 0 && !r.last_pass) keep |= 1ull << (g - i0 + q);
+            if (c[q] > 0 && r.last_pass && r.flag_unconverged) unconverged = true;
+          }
+        }
+      }
+      const int cnt = __popcll(keep);
+      int incl = cnt;                                               // inclusive prefix over the wave's lanes
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int v = __shfl_up(incl, d);
+        if (lane >= d) incl += v;
+      }
+      if (lane == 63) wave_total[wave] = incl;
+      __syncthreads();
+      int off = base + incl - cnt, tot = 0;
+      for (int w = 0; w < nwaves; ++w) {
+        if (w < wave) off += wave_total[w];
+        tot += wave_total[w];
+      }
+      for (int g = i0; g < i1; g += G) {
+        int sample[G];
+#pragma unroll
+        for (int q = 0; q < G; ++q) sample[q] = (g + q < i1 && ((keep >> (g - i0 + q)) & 1ull)) ? r.rows_in[g + q] : -1;
+#pragma unroll
+        for (int q = 0; q < G; ++q)
+          if (sample[q] >= 0) r.rows_out[off++] = sample[q];
+      }
+      base += tot;
+      __syncthreads();                                              // wave_total is reused by the next round
+    }
+    if (unconverged) {
+      atomicOr(r.flags, 1);
+      if (r.host_flags) __hip_atomic_store(r.host_flags, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    if (threadIdx.x == 0) base_s = base;
     __syncthreads();
   }
   // the next pass reads whole tiles of the new list: pad it with a valid id of this call (anything older

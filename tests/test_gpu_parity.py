@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.fixture(autouse=True, params=["per-layer launches", "single chain", "persistent", "sample-resident",
-                                      "unfused categorical"])
+                                      "library defaults", "unfused categorical"])
 def execution_path(request):
     """Every test runs on every execution path of the library (they must all agree with the oracle)."""
     import gpu_util
@@ -29,9 +29,9 @@ def execution_path(request):
         if name is not None and "cat" in name:
             pytest.skip("the sample-resident kernel serves Bernoulli models only")
     gpu_util.PERSISTENT = request.param == "persistent"
-    gpu_util.RESIDENT = int(request.param == "sample-resident")
+    gpu_util.RESIDENT = 1 if request.param == "sample-resident" else (2 if request.param == "library defaults" else 0)
     gpu_util.FUSED_CATEGORICAL = request.param != "unfused categorical"
-    gpu_util.CHAINS = 1 if request.param == "single chain" else 4
+    gpu_util.CHAINS = 1 if request.param in ("single chain", "library defaults") else 4
     yield
     gpu_util.PERSISTENT = False
     gpu_util.RESIDENT = 0
