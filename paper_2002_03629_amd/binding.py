@@ -264,6 +264,7 @@ MADE_OPT_BIG_TILE_BATCH = 4
 MADE_OPT_CONV_ROWS = 5
 MADE_OPT_PREFIX_CACHE = 6
 MADE_OPT_RESIDENT = 7
+MADE_OPT_RETIRE_SPLIT = 8
 
 
 def made_set_option(model: int, option: int, value: int) -> None:

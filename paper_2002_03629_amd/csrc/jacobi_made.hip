@@ -179,6 +179,7 @@ struct made_model {
   bool prefix_cache = true;                   // made_set_option(MADE_OPT_PREFIX_CACHE)
   int big_batch = 4096;                       // made_set_option(MADE_OPT_BIG_TILE_BATCH); measured crossover ~5000
   int n_chains = 1;                           // made_set_option(MADE_OPT_CHAINS)
+  int retire_split = 4096;                    // made_set_option(MADE_OPT_RETIRE_SPLIT)
   int fused_categorical = 1;                  // made_set_option(MADE_OPT_FUSED_CATEGORICAL)
   int use_persistent = 0;                     // made_set_option(MADE_OPT_PERSISTENT); off: measured slower, see header
   // sample-resident kernel (resident_sampler_kernel): LDS layout, 0 bytes = this model does not fit
@@ -311,8 +312,9 @@ static int ensure_chain(made_model* m, size_t i, int rows_cap, int pin_len) {
     HIP_TRY(hipMemset(c.rows[b], 0, (size_t)rows_cap * sizeof(int)));   // kernels may read past the active count
     HIP_TRY(hipMalloc((void**)&c.n_rows[b], sizeof(int)));
   }
-  HIP_TRY(hipMalloc((void**)&c.done_ctr, sizeof(int)));
-  HIP_TRY(hipMemset(c.done_ctr, 0, sizeof(int)));
+  // (the retire kernel's list cursor lives RETIRE_CURSOR words behind the counter)
+  HIP_TRY(hipMalloc((void**)&c.done_ctr, (size_t)2 * RETIRE_CURSOR * sizeof(int)));
+  HIP_TRY(hipMemset(c.done_ctr, 0, (size_t)2 * RETIRE_CURSOR * sizeof(int)));
   HIP_TRY(hipHostMalloc((void**)&c.h_pin, (size_t)pin_len * sizeof(int), hipHostMallocMapped));
   HIP_TRY(hipHostGetDevicePointer((void**)&c.d_pin, (void*)c.h_pin, 0));
   c.rows_cap = rows_cap;
@@ -400,6 +402,11 @@ extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
   if (option == MADE_OPT_BIG_TILE_BATCH) {
     if (value < 1) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_BIG_TILE_BATCH=%d must be >= 1", value);
     m->big_batch = value;
+    return MADE_OK;
+  }
+  if (option == MADE_OPT_RETIRE_SPLIT) {
+    if (value < 1) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_RETIRE_SPLIT=%d must be >= 1", value);
+    m->retire_split = value;
     return MADE_OK;
   }
   if (option == MADE_OPT_CHAINS) {
@@ -1418,7 +1425,17 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
     const bool by_pos = hidden_by_position(m, rs, blk.limited);
     TRY(run_hidden(m, rs, blk.limited ? blk.hidden_limit.data() : nullptr, blk.in_limit, s,
                    (blk.limited && k > 1 && m->prefix_cache) ? blk.hidden_frozen.data() : nullptr, by_pos));
+    // a long list is retired by a kernel of its own, spread over the chip, instead of by the output kernel's
+    // last workgroup
+    const RetireArgs retire = io.retire;
+    const bool split_retire = retire.enabled && c.count >= m->retire_split;
+    if (split_retire) io.retire.enabled = 0;
     TRY(run_output_sample(m, rs, io, blk.whole_network, blk.out_k_limit, s, by_pos));
+    if (split_retire) {
+      hipLaunchKernelGGL(retire_kernel, dim3((c.count + RETIRE_WG_ROWS - 1) / RETIRE_WG_ROWS), dim3(256), 0, s, retire);
+      HIP_TRY(hipGetLastError());
+      m->stats[2]++;
+    }
   }
   c.k_enq = k;
   return MADE_OK;

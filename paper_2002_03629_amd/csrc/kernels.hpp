@@ -341,6 +341,88 @@ __device__ __forceinline__ void retire_tail(const RetireArgs& r, int pre_n, int 
   }
 }
 
+// The retire step as a kernel of its own, for lists too long for one workgroup to go through quickly (one
+// compute unit handles the scattered counter reads of 32768 rows in ~180 us; spread over the chip they take a
+// few us, which repays the extra launch).  Every workgroup takes RETIRE_WG_ROWS consecutive list entries, keeps
+// their order, and claims its place in the new list with one atomic add on a cursor: the order of the
+// workgroups' runs in the new list is that of their arrival, which no result depends on (every sample's
+// arithmetic is independent of its place in the list).  The last workgroup to finish pads and publishes the list.
+// cursor = r.done_ctr + RETIRE_CURSOR (a line of its own); both are zero on entry and on exit.
+constexpr int RETIRE_WG_ROWS = 1024;
+constexpr int RETIRE_CURSOR = 32;
+__global__ __launch_bounds__(256) void retire_kernel(RetireArgs r) {
+  __shared__ int wave_total[4];
+  __shared__ int base_s;
+  __shared__ int is_last_s;
+  constexpr int Q = RETIRE_WG_ROWS / 256;
+  const int n_rows = min(*r.n_in, r.n_max);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int first = blockIdx.x * RETIRE_WG_ROWS + wave * (Q * 64) + lane;   // a wave owns Q * 64 consecutive rows
+  int* cursor = r.done_ctr + RETIRE_CURSOR;
+  int sample[Q], c[Q], itv[Q];
+#pragma unroll
+  for (int q = 0; q < Q; ++q) sample[q] = first + q * 64 < n_rows ? r.rows_in[first + q * 64] : -1;
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    c[q] = 0;
+    itv[q] = 0;
+    if (sample[q] >= 0) {
+      c[q] = __hip_atomic_load(&r.changed[(size_t)sample[q] * CHG], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      itv[q] = r.iters[sample[q]];
+    }
+  }
+  bool unconverged = false;
+  int pos[Q], wave_count = 0;
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    bool keep = false;
+    if (sample[q] >= 0) {
+      r.changed[(size_t)sample[q] * CHG] = 0;
+      r.iters[sample[q]] = itv[q] + 1;
+      keep = c[q] > 0 && !r.last_pass;
+      unconverged |= c[q] > 0 && r.last_pass && r.flag_unconverged;
+    }
+    const unsigned long long mask = __ballot(keep);
+    pos[q] = keep ? wave_count + __popcll(mask & ((1ull << lane) - 1ull)) : -1;
+    wave_count += __popcll(mask);
+  }
+  if (lane == 0) wave_total[wave] = wave_count;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int tot = wave_total[0] + wave_total[1] + wave_total[2] + wave_total[3];
+    base_s = tot ? __hip_atomic_fetch_add(cursor, tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+  }
+  __syncthreads();
+  int off = base_s;
+  for (int w = 0; w < wave; ++w) off += wave_total[w];
+#pragma unroll
+  for (int q = 0; q < Q; ++q)
+    if (pos[q] >= 0) r.rows_out[off + pos[q]] = sample[q];
+  if (unconverged) {
+    atomicOr(r.flags, 1);
+    if (r.host_flags) __hip_atomic_store(r.host_flags, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  }
+  // (thread 0 has its cursor atomic's result, so the atomic below is performed after it; the list entries
+  // themselves are read by the next kernel only)
+  if (threadIdx.x == 0)
+    is_last_s = (__hip_atomic_fetch_add(r.done_ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (int)gridDim.x - 1);
+  __syncthreads();
+  if (!is_last_s) return;
+  const int new_n = __hip_atomic_load(cursor, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (n_rows > 0) {
+    // whole tiles of the new list are read by the next pass: pad with a valid id of this call (no other
+    // workgroup writes at or behind new_n)
+    const int fill = r.rows_in[0];
+    for (int i = new_n + threadIdx.x; i < ((new_n + 63) & ~63); i += blockDim.x) r.rows_out[i] = fill;
+  }
+  if (threadIdx.x == 0) {
+    *r.n_out = new_n;
+    __hip_atomic_store(cursor, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(r.done_ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(r.host_slot, new_n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  }
+}
+
 // Add to a per-sample changed counter and wait until the atomic has been performed (its old value
 // came back), so that a later atomic on done_ctr is ordered after it without a memory fence.
 __device__ __forceinline__ void count_changed(int* counter, int cnt) {
@@ -1937,6 +2019,7 @@ __device__ __forceinline__ void call_reset(const CallReset& r) {
     if (i == 0) {
       *r.n_rows = r.count;
       *r.done_ctr = 0;
+      r.done_ctr[RETIRE_CURSOR] = 0;
       *r.flags = 0;
     }
   }
@@ -2026,6 +2109,7 @@ __global__ void reset_rows_kernel(int* rows, int* rows_other, int* n_rows, int f
   if (i == 0) {
     *n_rows = count;
     *done_ctr = 0;
+    done_ctr[RETIRE_CURSOR] = 0;
   }
 }
 

@@ -41,6 +41,7 @@ PERSISTENT = False     # execution path the models below are switched to (the te
 RESIDENT = 0           # sample-resident kernel: 0 never, 1 whenever the model fits it (2, the library's default, = where it pays)
 FUSED_CATEGORICAL = True
 CHAINS = 4
+RETIRE_SPLIT = None   # None: the library's default; 1: the stop test always runs as a kernel of its own
 
 
 class GpuModel:
@@ -51,6 +52,8 @@ class GpuModel:
         B.made_set_option(self.h, B.MADE_OPT_RESIDENT, int(RESIDENT))
         B.made_set_option(self.h, B.MADE_OPT_FUSED_CATEGORICAL, int(FUSED_CATEGORICAL))
         B.made_set_option(self.h, B.MADE_OPT_CHAINS, CHAINS)
+        if RETIRE_SPLIT is not None:
+            B.made_set_option(self.h, B.MADE_OPT_RETIRE_SPLIT, RETIRE_SPLIT)
         if big_tile_batch is not None:
             B.made_set_option(self.h, B.MADE_OPT_BIG_TILE_BATCH, big_tile_batch)
 

@@ -158,3 +158,38 @@ def test_cfg2_large_batch_vector_epilogue():
         assert_logits_close(z, O.logits_all(exact, x), LOGIT_TOL["bf16"])
         xb, _ = g.gs_jacobi(noise, 196)
         assert_sample_parity(same, noise, xb)
+
+
+def test_cfg2_batch_8192_stop_test_as_its_own_kernel():
+    """cfg2's network at batch 8192, one chain, library defaults: lists this long are retired by a kernel of their own
+    (MADE_OPT_RETIRE_SPLIT).  Whole batch by the fixed-point certificate, a sub-batch against the oracle's sequential
+    run, and symbols and pass counts identical to the run that keeps the stop test inside the output kernel."""
+    import dataclasses
+    import gpu_util
+    w = dataclasses.replace(S.workload("cfg2"), N=8192)
+    net = S.make_network(w)
+    _, same = oracle_models(net)
+    noise = S.make_noise(w)
+    sub = 4
+    xs, mg = O.sequential_sample(same, noise[:sub])
+    ref = O.jacobi_reference(same, noise[:64])
+    results = []
+    old = gpu_util.CHAINS, gpu_util.RETIRE_SPLIT
+    try:
+        for split in (None, 1 << 30):
+            gpu_util.CHAINS, gpu_util.RETIRE_SPLIT = 1, split
+            progress(f"cfg2 batch 8192, retire split {split}")
+            with GpuModel(net) as g:
+                x, it = g.jacobi(noise)
+                xb, itb = g.gs_jacobi(noise, 196)
+            results.append((x, it, xb, itb))
+    finally:
+        gpu_util.CHAINS, gpu_util.RETIRE_SPLIT = old
+    x, it, xb, itb = results[0]
+    assert_sample_parity(same, noise, x)
+    assert_sample_parity(same, noise[:sub], x[:sub], xs, mg)
+    assert_sample_parity(same, noise, xb)
+    clear = ref[4] >= MARGIN
+    assert (it[:64][clear] == ref[1][clear]).all()
+    for a, b in zip(results[0], results[1]):
+        assert (a == b).all()

@@ -32,7 +32,9 @@ def execution_path(request):
     gpu_util.RESIDENT = 1 if request.param == "sample-resident" else (2 if request.param == "library defaults" else 0)
     gpu_util.FUSED_CATEGORICAL = request.param != "unfused categorical"
     gpu_util.CHAINS = 1 if request.param in ("single chain", "library defaults") else 4
+    gpu_util.RETIRE_SPLIT = 1 if request.param == "single chain" else None   # (the stop test as its own kernel)
     yield
+    gpu_util.RETIRE_SPLIT = None
     gpu_util.PERSISTENT = False
     gpu_util.RESIDENT = 0
     gpu_util.FUSED_CATEGORICAL = True
