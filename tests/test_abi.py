@@ -54,3 +54,24 @@ def test_argument_errors_need_no_gpu():
     assert L.rnn_param_grads(None, None, None, None, None, 1, 10, 16, 1, None, None, None, None) == binding.MADE_ERR_ARG
     assert binding.rnn_jacobi_max_steps(128) == 128 and binding.rnn_jacobi_max_steps(64) == 256
     assert binding.rnn_jacobi_max_steps(20) == 512 and binding.rnn_jacobi_max_steps(129) == 0
+
+
+def test_header_constants_match_the_binding():
+    """Every enumerator the headers define (status codes, dtypes, options) has the same value in the binding."""
+    inc = os.path.join(ROOT, "include")
+    found = {}
+    for fn in sorted(os.listdir(inc)):
+        if not fn.endswith(".h"):
+            continue
+        text = re.sub(r"/\*.*?\*/", "", open(os.path.join(inc, fn)).read(), flags=re.S)
+        for body in re.findall(r"enum\s*\w*\s*\{(.*?)\}", text, flags=re.S):
+            for name, value in re.findall(r"(\w+)\s*=\s*(-?\d+)", body):
+                found[name] = int(value)
+    assert found, "no enumerators parsed"
+    missing = [n for n in found if not hasattr(binding, n)]
+    assert not missing, missing
+    for name, value in found.items():
+        assert getattr(binding, name) == value, name
+    # an option the library does not know is an argument error, also without a GPU
+    L = binding.lib()
+    assert L.made_set_option(None, binding.MADE_OPT_RETIRE_SPLIT, 1) == binding.MADE_ERR_ARG
