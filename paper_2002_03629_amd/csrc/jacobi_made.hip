@@ -890,19 +890,13 @@ static void prof_collect(made_model* m) {
 
 template <typename T, int EPI>
 static void launch_big_t(LayerArgs a, int n_tiles, int n_rows_max, hipStream_t s) {
-  static bool configured = false;   // (per instantiation) allow 128 KB of dynamic LDS
-  if (!configured) {
-    (void)hipFuncSetAttribute((const void*)masked_layer_big_kernel<T, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              BIG_LDS_BYTES);
-    configured = true;
-  }
   a.n_launch_tiles = n_tiles;
   a.row_tiles = (n_rows_max + BIG_ROWS - 1) / BIG_ROWS;
   const int big_cols = (n_tiles + BIG_T - 1) / BIG_T;
   a.big_by_rows = a.row_tiles >= big_cols;
   const int groups = ((a.big_by_rows ? a.row_tiles : big_cols) + XCDS - 1) / XCDS;
   const int other = a.big_by_rows ? big_cols : a.row_tiles;
-  hipLaunchKernelGGL((masked_layer_big_kernel<T, EPI>), dim3(groups * XCDS * other), dim3(256), BIG_LDS_BYTES, s, a);
+  hipLaunchKernelGGL((masked_layer_big_kernel<T, EPI>), dim3(groups * XCDS * other), dim3(256), 0, s, a);   // (128 KB of static LDS)
 }
 
 template <int EPI>

@@ -61,6 +61,37 @@ template <> struct Elem<float> {
   }
 };
 
+// Four consecutive elements (dst aligned to them) from four floats: 8 bytes in bf16, 16 in fp32.  bf16 through
+// the hardware's conversion (round to nearest even like f32_to_bf16, one instruction per pair instead of six per
+// element: at 64 K outputs per workgroup the epilogue of the 256 x 256 kernel is bound by such arithmetic).
+template <typename T>
+__device__ __forceinline__ void store_quad(T* dst, float a, float b, float c, float d);
+template <>
+__device__ __forceinline__ void store_quad<bf16_t>(bf16_t* dst, float a, float b, float c, float d) {
+  typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+  typedef float f32x4_t __attribute__((ext_vector_type(4)));
+  const f32x4_t f = {a, b, c, d};
+  *(bf16x4_t*)dst = __builtin_convertvector(f, bf16x4_t);
+}
+template <>
+__device__ __forceinline__ void store_quad<float>(float* dst, float a, float b, float c, float d) {
+  *(float4*)dst = make_float4(a, b, c, d);
+}
+
+// frag_offset(row, k) = frag_row_offset(row) + frag_col_offset(k): for code that stores many (row, k) pairs
+template <typename T>
+__device__ __forceinline__ size_t frag_row_offset(int row, int k_chunks) {
+  constexpr int KC = 2 * Elem<T>::EPL, P = 16 / (int)sizeof(T);
+  return (size_t)(row >> 5) * k_chunks * (size_t)(KC * 32) + (size_t)((row & 31) * P);
+}
+template <typename T>
+__device__ __forceinline__ uint32_t frag_col_offset(int k) {
+  constexpr int EPL = Elem<T>::EPL, KC = 2 * EPL, P = 16 / (int)sizeof(T);
+  const int c = k / KC, kk = k % KC;
+  const int h = kk / EPL, s = (kk % EPL) / P, i = kk % P;
+  return (uint32_t)c * (uint32_t)(KC * 32) + (uint32_t)(((s * 2 + h) * 32) * P + i);
+}
+
 // Fragment-major layout of every MFMA operand matrix (masked weights, network input, hidden activations).
 //
 // A [rows, K] matrix is cut into groups of 32 rows and chunks of KC = 2 * EPL columns (128 bytes per row).
@@ -717,7 +748,32 @@ __global__ __launch_bounds__(NW * 64) void masked_layer_kernel(LayerArgs a) {
 constexpr int BIG_W = 4;                 // MFMA tiles per wave and dimension
 constexpr int BIG_T = 2 * BIG_W;         // tiles per workgroup and dimension (2 x 2 waves)
 constexpr int BIG_ROWS = BIG_T * TILE;   // 256
-constexpr int BIG_LDS_BYTES = 2 * 2 * BIG_T * 256 * 16;   // 2 stages x (8 + 8) blocks x 4 KB = 128 KB
+constexpr int BIG_HALF = 128;            // 16-byte pieces of one block in half a chunk (2 of its 4 MFMA steps)
+constexpr int BIG_STAGE = 2 * BIG_T * BIG_HALF;   // pieces per ring stage: (8 + 8) blocks x 2 KB = 32 KB
+
+// Workgroup barrier that orders LDS traffic only.  (__syncthreads also waits for every outstanding global load
+// of the wave, i.e. it would drain a prefetch ring at every use.)
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// One wave copies 64 x 16 bytes from global memory (one address per lane) straight into LDS at
+// lds_byte_address + 16 * lane (wave-uniform address, handed to the instruction in M0).  Written as assembly
+// rather than through the compiler's builtin on purpose: the compiler orders every later LDS read behind ALL
+// outstanding copies of this kind that it knows of (vmcnt(0)), which serialises a ring of several stages; this
+// way it knows of none, and the caller waits (s_waitcnt vmcnt(n), then a barrier) for exactly the stage it reads.
+__device__ __forceinline__ void load_to_lds16(const void* src, uint32_t lds_byte_address) {
+  uint32_t saved_m0;   // (M0 is the compiler's to use: put it back)
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(saved_m0)
+               : "v"(src), "s"(lds_byte_address)
+               : "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
 
 template <typename T>
 __device__ __forceinline__ void mfma_step(const uint4& a, const uint4& b, f32x16& acc);
@@ -736,7 +792,11 @@ __device__ __forceinline__ void mfma_step<float>(const uint4& a, const uint4& b,
 template <typename T, int EPI>
 __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
   constexpr int KC = 2 * Elem<T>::EPL;
-  extern __shared__ uint4 big_lds[];     // [stage][block 0..7 = samples, 8..15 = units][256]
+  // ring stages, [block 0..7 = samples, 8..15 = units][128] each (separate arrays: see the main loop)
+  __shared__ uint4 big_s0[BIG_STAGE];
+  __shared__ uint4 big_s1[BIG_STAGE];
+  __shared__ uint4 big_s2[BIG_STAGE];
+  __shared__ uint4 big_s3[BIG_STAGE];
   const int n_rows = a.n_rows_ptr ? *a.n_rows_ptr : a.n_rows;
   const int big_cols = (a.n_launch_tiles + BIG_T - 1) / BIG_T;
   // Workgroup i runs on XCD i % 8.  An XCD should own whichever operand is larger (it then streams only
@@ -754,7 +814,7 @@ __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
   if (wg_n < big_cols && wg_m < a.row_tiles && row0 < n_rows) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 31, h = lane >> 5;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave >> 1, wn = wave & 1, wave_in_sub = wave & 1;
     const int rel_tile0 = wg_n * BIG_T;
     const int tile0 = a.tile_begin + rel_tile0;
     const int live_tiles = min(BIG_T, a.n_launch_tiles - rel_tile0);
@@ -766,21 +826,27 @@ __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
     const size_t group = (size_t)a.k_chunks * 256;
 
     // Operand blocks go from global memory straight into LDS (global_load_lds_dwordx4: lane i of a wave
-    // deposits its 16 bytes at the wave's LDS base + 16 i), so a chunk in flight costs no registers.  Two
-    // stages: the next chunk lands while the current one is multiplied.  (A four-stage ring of half chunks
-    // was measured and is not faster: the loop is bound by the MFMA/LDS issue rate of one wave per SIMD, not
-    // by memory latency.)  This thread copies element `tid` of each of the 16 blocks of a chunk; offsets are
-    // in 16-byte units (the host refuses operand buffers of 64 GiB and more).
-    uint32_t offA[BIG_T];
+    // deposits its 16 bytes at the wave's LDS base + 16 i), so data in flight costs no registers.  A chunk is
+    // moved in two halves (MFMA steps 0-1 and 2-3 of all 16 blocks: 32 KB) through a ring of four stages, three
+    // halves in flight while one is multiplied: a load has three halves' worth of MFMA time (~1.3 us) to
+    // arrive.  The stages are four DISTINCT LDS arrays on purpose: the compiler orders every LDS read behind all
+    // outstanding LDS-bound loads it cannot prove to target other memory (with one array it put a full
+    // vmcnt(0) in front of each half's first read, right behind the prefetch it had just issued: load and
+    // multiply never overlapped, 2.4 us per chunk instead of <1).  Each thread copies 8 pieces of 16 bytes per
+    // half: element e = half * 128 + (tid & 127) of blocks 2 q + (tid >> 7); offsets in 16-byte units (the host
+    // refuses operand buffers of 64 GiB and more).
+    const int sub = wave >> 1, e_lo = tid & 127;             // (sub: wave-uniform)
+    uint32_t offA[BIG_W];
 #pragma unroll
-    for (int q = 0; q < BIG_T; ++q) {
-      const int row = row0 + q * TILE + (tid & 31);
+    for (int q = 0; q < BIG_W; ++q) {
+      const int row = row0 + (2 * q + sub) * TILE + (tid & 31);
       const int sample = a.rows ? a.rows[min(row, a.n_rows_pad - 1)] : (row < a.n_rows ? row : 0);
-      offA[q] = (uint32_t)((size_t)(sample >> 5) * group) + (tid & ~31) + (sample & 31);
+      offA[q] = (uint32_t)((size_t)(sample >> 5) * group) + (e_lo & ~31) + (sample & 31);
     }
     const uint4* Abase = (const uint4*)a.A;
-    const uint4* Wbase = (const uint4*)a.W + (size_t)tile0 * group + tid;
+    const uint4* Wbase = (const uint4*)a.W + (size_t)tile0 * group + e_lo;
     const int last_live = live_tiles - 1;                     // tiles past the layer's end repeat the last one
+    const int n_half = 2 * n_chunks;
 
     f32x16 acc[BIG_W][BIG_W];
 #pragma unroll
@@ -790,124 +856,186 @@ __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    typedef __attribute__((address_space(1))) const void gptr_t;
-    typedef __attribute__((address_space(3))) void lptr_t;
-    auto issue_chunk = [&](int c, int stage) {
-      const uint32_t co = (uint32_t)c * 256;
-      uint4* dst = big_lds + stage * (2 * BIG_T * 256) + wave * 64;
+    // half hc (clamped to the last one: the ring is always kept full, so that the number of loads in flight is
+    // the same at every wait; the surplus copies land in stages nobody reads any more) -> stage array dst
+    auto issue_half = [&](int hc, uint4* dst) {
+      hc = min(hc, n_half - 1);
+      const uint32_t co = (uint32_t)(hc >> 1) * 256 + (uint32_t)(hc & 1) * 128;
+      const uint32_t d = lds_address(dst + sub * BIG_HALF + wave_in_sub * 64);
 #pragma unroll
-      for (int q = 0; q < BIG_T; ++q) {
-        __builtin_amdgcn_global_load_lds((gptr_t*)(Abase + offA[q] + co), (lptr_t*)(dst + q * 256), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((gptr_t*)(Wbase + (size_t)min(q, last_live) * group + co),
-                                         (lptr_t*)(dst + (BIG_T + q) * 256), 16, 0, 0);
+      for (int q = 0; q < BIG_W; ++q) {
+        load_to_lds16(Abase + offA[q] + co, d + 2 * q * BIG_HALF * 16);
+        load_to_lds16(Wbase + (size_t)min(2 * q + sub, last_live) * group + co, d + (BIG_T + 2 * q) * BIG_HALF * 16);
       }
     };
-    if (n_chunks > 0) issue_chunk(0, 0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    for (int c = 0; c < n_chunks; ++c) {
-      const uint4* cur = big_lds + (c & 1) * (2 * BIG_T * 256);
-      if (c + 1 < n_chunks) issue_chunk(c + 1, (c + 1) & 1);   // lands while this chunk is consumed
+    auto multiply_half = [&](const uint4* cur) {
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
+      for (int sl = 0; sl < 2; ++sl) {
         uint4 af[BIG_W], bf[BIG_W];
 #pragma unroll
-        for (int i = 0; i < BIG_W; ++i) af[i] = cur[(wm * BIG_W + i) * 256 + s * 64 + lane];
+        for (int i = 0; i < BIG_W; ++i) af[i] = cur[(wm * BIG_W + i) * BIG_HALF + sl * 64 + lane];
 #pragma unroll
-        for (int j = 0; j < BIG_W; ++j) bf[j] = cur[(BIG_T + wn * BIG_W + j) * 256 + s * 64 + lane];
+        for (int j = 0; j < BIG_W; ++j) bf[j] = cur[(BIG_T + wn * BIG_W + j) * BIG_HALF + sl * 64 + lane];
 #pragma unroll
         for (int i = 0; i < BIG_W; ++i)
 #pragma unroll
-          for (int j = 0; j < BIG_W; ++j) mfma_step<T>(af[i], bf[j], acc[i][j]);
+          for (int j = 0; j < BIG_W; ++j) mfma_step<T>(bf[j], af[i], acc[i][j]);   // (units = rows of the result)
       }
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the next chunk has arrived in the other stage
-      __syncthreads();
+    };
+    // one ring step: this wave's copies of half hc have landed (the 2 x 8 younger ones may still fly), then
+    // everybody's have and everybody is done reading the stage that half hc + 3 goes to
+    auto ring_step = [&](int hc, const uint4* cur, uint4* refill) {
+      // (no fence here on purpose: a release fence on LDS makes the compiler wait for ALL LDS-bound loads, the
+      // younger halves included.  The memory clobber keeps the compiler from moving LDS reads across; the stage
+      // that is refilled below was last read by MFMAs issued before this point, whose operands had arrived.)
+      asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
+      issue_half(hc + 3, refill);
+      multiply_half(cur);
+    };
+    JM_TSTAMP(EPI == EPI_RELU ? 0 : 3, 0);
+#ifdef JM_TRACE
+    if (threadIdx.x == 0 && blockIdx.x < 1024) g_tile_trace[blockIdx.x * 8 + (EPI == EPI_RELU ? 6 : 7)] = n_chunks;
+#endif
+    if (n_half > 0) {
+      issue_half(0, big_s0);
+      issue_half(1, big_s1);
+      issue_half(2, big_s2);
+      for (int hc = 0; hc < n_half; hc += 4) {                // n_half is even
+        ring_step(hc, big_s0, big_s3);
+        ring_step(hc + 1, big_s1, big_s0);
+        if (hc + 2 < n_half) {
+          ring_step(hc + 2, big_s2, big_s1);
+          ring_step(hc + 3, big_s3, big_s2);
+        }
+      }
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // surplus copies: the epilogue reuses stage 0
+    __syncthreads();
+    // New names for the accumulators from here on: the (long, fully unrolled) epilogue's register needs then do
+    // not reach back into the main loop (without this the compiler moved accumulators between register files
+    // and reloaded spilled ones inside the loop of the sampling variant).
+#pragma unroll
+    for (int i = 0; i < BIG_W; ++i)
+#pragma unroll
+      for (int j = 0; j < BIG_W; ++j) asm volatile("" : "+a"(acc[i][j]));
 
-    // ---- epilogue.  acc[i][j][e]: row = row0 + (wm*4 + i)*32 + 8*(e/4) + 4*h + e%4, unit = (tile0 + wn*4 + j)*32 + r.
-    // The operand stages are free now.  The workgroup's 256 sample ids go through LDS, and every 32 x 32
-    // accumulator tile is turned through a wave-private LDS patch so that a lane ends up with 16 consecutive
-    // units of ONE sample: results, noise and symbols then move in 16-byte pieces.
-    int* ids = (int*)big_lds;
-    float (*patch)[TILE + 1] = (float (*)[TILE + 1])((char*)big_lds + 1024 + wave * (TILE * (TILE + 1) * 4));
+    JM_TSTAMP(EPI == EPI_RELU ? 1 : 4, 0);
+    // ---- epilogue.  The weights were the MFMA's row operand, so lane (r, h) holds ONE sample per sample tile and
+    // runs of four consecutive units: acc[i][j][e] belongs to sample row0 + (wm*4 + i)*32 + r and unit
+    // (tile0 + wn*4 + j)*32 + 8*(e/4) + 4*h + e%4.  Four units of a sample are contiguous in every array the
+    // epilogue touches (bias, noise, symbols, and the fragment-major activations: half of a 16-byte piece in
+    // bf16, a whole one in fp32), so results leave the registers in 8- and 16-byte pieces without a transposition
+    // through LDS.  The operand stages are free now: the workgroup's 256 sample ids go through stage 0.
+    int* ids = (int*)big_s0;
     {
       const int row = row0 + tid;
       ids[tid] = row < n_rows ? (a.rows ? a.rows[row] : row) : -1;
     }
     __syncthreads();
-    constexpr int P = 16 / (int)sizeof(T);          // elements per 16-byte piece of the fragment layout
-    const int rr = lane >> 1, c16 = (lane & 1) * 16;  // this lane's row and first column inside a tile
-    const bool vec_io = a.io_aligned != 0;            // 16-byte reads of noise / symbols need aligned rows
+    const bool vec_io = a.io_aligned != 0;            // 16-byte reads of noise, 4-byte symbol words: aligned rows
+    // Everything the epilogue reads is requested before anything is stored: the compiler must keep a load behind
+    // every earlier store it cannot prove to be to other memory, and loads waited for one at a time cost a memory
+    // round trip each (64 per wave: that was most of the epilogue's time).  Bias: once for all sample tiles.
+    int col_of[BIG_W];                                 // first unit of this lane in unit tile j (+ 8 g per run of four)
+    bool tile_ok[BIG_W];
+    float4 b4[BIG_W][4];
+    uint32_t frag_col[BIG_W][4];                       // the runs' places inside a row of the fragment-major output
+#pragma unroll
+    for (int j = 0; j < BIG_W; ++j) {
+      const int rel_tile = rel_tile0 + wn * BIG_W + j;
+      col_of[j] = (a.tile_begin + min(rel_tile, a.n_launch_tiles - 1)) * TILE + 4 * h;
+      tile_ok[j] = rel_tile < a.n_launch_tiles;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        b4[j][g] = *(const float4*)(a.bias + col_of[j] + 8 * g);
+        frag_col[j][g] = frag_col_offset<T>(col_of[j] + 8 * g);
+      }
+    }
     static_for<BIG_W>([&](auto I) {
       constexpr int i = decltype(I)::value;
-      const int sample = ids[(wm * BIG_W + i) * TILE + rr];
+      const int sample = ids[(wm * BIG_W + i) * TILE + r];
+      const size_t frag_row = frag_row_offset<T>(max(sample, 0), EPI == EPI_RELU ? a.out_chunks : a.enc_chunks);
       int cnt = 0;
+      // sampling: a run of four positions that is wholly inside the window and the row takes the fast path
+      // (one 16-byte read of noise, one word of symbols); its inputs are requested here for all 16 runs
+      bool fast[BIG_W][4];
+      float4 u4[BIG_W][4];
+      uint32_t xo[BIG_W][4];
+      if (EPI == EPI_BERNOULLI) {
+#pragma unroll
+        for (int j = 0; j < BIG_W; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int col0 = col_of[j] + 8 * g;
+            fast[j][g] = tile_ok[j] && sample >= 0 && vec_io && col0 >= a.t_lo && col0 + 4 <= min(a.t_hi, a.D);
+            u4[j][g] = make_float4(2.f, 2.f, 2.f, 2.f);
+            xo[j][g] = 0;
+            if (fast[j][g]) {
+              const size_t idx = (size_t)sample * a.D + col0;
+              u4[j][g] = *(const float4*)(a.noise + idx);
+              xo[j][g] = *(const uint32_t*)(a.x + idx);
+            }
+          }
+      }
       static_for<BIG_W>([&](auto J) {
         constexpr int j = decltype(J)::value;
-        const int rel_tile = rel_tile0 + wn * BIG_W + j;
-        const int col0 = (a.tile_begin + min(rel_tile, a.n_launch_tiles - 1)) * TILE + c16;
-        const bool ok = rel_tile < a.n_launch_tiles && sample >= 0;
+        const bool ok = tile_ok[j] && sample >= 0;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) patch[8 * (e >> 2) + 4 * h + (e & 3)][r] = acc[i][j][e];
-        // (same wave wrote and reads the patch: the compiler's LDS counter wait orders them)
-        float v[16];
+        for (int g = 0; g < 4; ++g) {
+          const int col0 = col_of[j] + 8 * g;                      // this lane's units col0 .. col0 + 3
+          const float v[4] = {acc[i][j][4 * g + 0] + b4[j][g].x, acc[i][j][4 * g + 1] + b4[j][g].y,
+                              acc[i][j][4 * g + 2] + b4[j][g].z, acc[i][j][4 * g + 3] + b4[j][g].w};
+          if (EPI == EPI_RELU) {
+            if (ok) store_quad<T>((T*)a.out + (frag_row + frag_col[j][g]), fmaxf(v[0], 0.f),
+                                  fmaxf(v[1], 0.f), fmaxf(v[2], 0.f), fmaxf(v[3], 0.f));
+          } else if (EPI == EPI_LOGITS) {
+            if (ok) {
 #pragma unroll
-        for (int c = 0; c < 16; ++c) v[c] = patch[rr][c16 + c] + a.bias[col0 + c];
-        if (EPI == EPI_RELU) {
-          if (ok) {
-#pragma unroll
-            for (int g = 0; g < 16 / P; ++g)
-              *(uint4*)((T*)a.out + frag_offset<T>(sample, col0 + g * P, a.out_chunks)) = Elem<T>::relu_piece(v + g * P);
-          }
-        } else if (EPI == EPI_LOGITS) {
-          if (ok) {
-#pragma unroll
-            for (int c = 0; c < 16; ++c)
-              if (col0 + c < a.n_cols) ((float*)a.out)[(size_t)sample * a.ldo + col0 + c] = v[c];
-          }
-        } else if (ok && col0 < a.t_hi && col0 + 16 > a.t_lo) {
-          const size_t idx = (size_t)sample * a.D + col0;
-          float u[16];
-          uint8_t xo[16];
-          if (vec_io && col0 + 16 <= a.D) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-              const float4 t4 = *(const float4*)(a.noise + idx + 4 * g);
-              u[4 * g + 0] = t4.x;
-              u[4 * g + 1] = t4.y;
-              u[4 * g + 2] = t4.z;
-              u[4 * g + 3] = t4.w;
+              for (int c = 0; c < 4; ++c)
+                if (col0 + c < a.n_cols) ((float*)a.out)[(size_t)sample * a.ldo + col0 + c] = v[c];
             }
-            const uint4 xw = *(const uint4*)(a.x + idx);
-            const uint32_t xws[4] = {xw.x, xw.y, xw.z, xw.w};
+          } else if (fast[j][g]) {
+            // all four positions are the lane's to update: one word of symbols and one piece of the encoded
+            // input instead of a byte and an element per changed position (the first pass from zeros changes
+            // every other position: 26 M single stores at batch 32768)
+            const size_t idx = (size_t)sample * a.D + col0;
+            const float u[4] = {u4[j][g].x, u4[j][g].y, u4[j][g].z, u4[j][g].w};
+            uint32_t xn = 0;
 #pragma unroll
-            for (int c = 0; c < 16; ++c) xo[c] = (uint8_t)((xws[c >> 2] >> (8 * (c & 3))) & 0xffu);
-          } else {
-#pragma unroll
-            for (int c = 0; c < 16; ++c) {
-              const bool in = col0 + c < a.D;
-              u[c] = in ? a.noise[idx + c] : 2.0f;
-              xo[c] = in ? a.x[idx + c] : 0;
+            for (int c = 0; c < 4; ++c) xn |= (u[c] < 1.0f / (1.0f + expf(-v[c])) ? 1u : 0u) << (8 * c);
+            if (xn != xo[j][g]) {
+              uint32_t d = xn ^ xo[j][g];                          // differing positions: one bit per non-zero byte
+              d |= d >> 4;
+              d |= d >> 2;
+              d |= d >> 1;
+              cnt += __popc(d & 0x01010101u);
+              *(uint32_t*)(a.x + idx) = xn;
+              store_quad<T>((T*)a.enc + (frag_row + frag_col[j][g]), (float)(xn & 1u),
+                            (float)((xn >> 8) & 1u), (float)((xn >> 16) & 1u), (float)(xn >> 24));
             }
-          }
+          } else if (ok && col0 < a.t_hi && col0 + 4 > a.t_lo && col0 < a.D) {
+            const size_t idx = (size_t)sample * a.D + col0;
 #pragma unroll
-          for (int c = 0; c < 16; ++c) {
-            const int col = col0 + c;
-            const float p = 1.0f / (1.0f + expf(-v[c]));
-            const uint8_t xn = u[c] < p ? 1 : 0;
-            if (col >= a.t_lo && col < a.t_hi && xn != xo[c]) {
-              cnt++;
-              a.x[idx + c] = xn;
-              ((T*)a.enc)[frag_offset<T>(sample, col, a.enc_chunks)] = Elem<T>::from_f32((float)xn);
+            for (int c = 0; c < 4; ++c) {
+              const int col = col0 + c;
+              if (col >= a.t_lo && col < a.t_hi && col < a.D) {
+                const uint8_t xn = a.noise[idx + c] < 1.0f / (1.0f + expf(-v[c])) ? 1 : 0;
+                if (xn != a.x[idx + c]) {
+                  cnt++;
+                  a.x[idx + c] = xn;
+                  ((T*)a.enc)[frag_offset<T>(sample, col, a.enc_chunks)] = Elem<T>::from_f32((float)xn);
+                }
+              }
             }
           }
         }
       });
-      if (EPI == EPI_BERNOULLI) {   // the two lanes of a row
-        cnt += __shfl_xor(cnt, 1);
-        if ((lane & 1) == 0 && cnt > 0) count_changed(&a.changed[(size_t)sample * CHG], cnt);
+      if (EPI == EPI_BERNOULLI) {   // the two lanes of a sample
+        cnt += __shfl_xor(cnt, 32);
+        if (h == 0 && cnt > 0) count_changed(&a.changed[(size_t)sample * CHG], cnt);
       }
     });
+    JM_TSTAMP(EPI == EPI_RELU ? 2 : 5, 1);
   }
   if (EPI == EPI_BERNOULLI && a.retire.enabled) finish_pass(a.retire, gridDim.x);
 }

@@ -97,14 +97,6 @@ struct ResCtx {
 #define RES_STAMP(pass, i) do { } while (0)
 #endif
 
-// Workgroup barrier that orders LDS traffic only.  (__syncthreads also waits for every outstanding global load
-// of the wave, i.e. it would drain the weight prefetch ring at every layer boundary.)
-__device__ __forceinline__ void lds_barrier() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-  __builtin_amdgcn_s_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
 __device__ __forceinline__ int snake_j(int m, int wave) { return (m & 1) ? (m + 1) * RES_W - 1 - wave : m * RES_W + wave; }
 
 __device__ __forceinline__ void cursor_load(TileCursor& c, const ResCtx& x, int bit) {
