@@ -38,6 +38,13 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest ev
 }
 __device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
 
+// P(x = 1) = 1 / (1 + exp(-v)) of a binary state (the conditional a draw u < P is taken from), evaluated with the
+// hardware's exp2 and reciprocal: within 1e-6 of the exact value (|v| log2(e) 2^-24 relative in the exponential,
+// scaled by P (1 - P) <= 1/4, plus an ulp each for exp2 and the reciprocal), 0 and 1 at the extremes.  Every
+// kernel that draws binary states from logits uses this one expression, so a draw does not depend on which of
+// them made it.  (The library's full-precision expf and division cost ~80 instructions per draw.)
+__device__ __forceinline__ float bernoulli_probability(float v) { return __builtin_amdgcn_rcpf(1.0f + __expf(-v)); }
+
 template <typename T> struct Elem;
 template <> struct Elem<bf16_t> {
   static constexpr int EPL = 32;  // elements one lane loads per K chunk (64 bytes)
@@ -676,7 +683,7 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
     } else {  // EPI_BERNOULLI: x_t = 1 iff u_t < sigmoid(z_t); count changes per sample
       int cnt = 0;
       if (row_ok && col_live) {
-        const float p = 1.0f / (1.0f + expf(-v));
+        const float p = bernoulli_probability(v);
         const uint8_t xn = e_noise[j] < p ? 1 : 0;
         cnt = (xn != e_xold[j]);
         if (cnt) {   // an unchanged symbol (and its encoding) is already in place
@@ -1002,7 +1009,7 @@ __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
             const float u[4] = {u4[j][g].x, u4[j][g].y, u4[j][g].z, u4[j][g].w};
             uint32_t xn = 0;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) xn |= (u[c] < 1.0f / (1.0f + expf(-v[c])) ? 1u : 0u) << (8 * c);
+            for (int c = 0; c < 4; ++c) xn |= (u[c] < bernoulli_probability(v[c]) ? 1u : 0u) << (8 * c);
             if (xn != xo[j][g]) {
               uint32_t d = xn ^ xo[j][g];                          // differing positions: one bit per non-zero byte
               d |= d >> 4;
@@ -1019,7 +1026,7 @@ __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
             for (int c = 0; c < 4; ++c) {
               const int col = col0 + c;
               if (col >= a.t_lo && col < a.t_hi && col < a.D) {
-                const uint8_t xn = a.noise[idx + c] < 1.0f / (1.0f + expf(-v[c])) ? 1 : 0;
+                const uint8_t xn = a.noise[idx + c] < bernoulli_probability(v[c]) ? 1 : 0;
                 if (xn != a.x[idx + c]) {
                   cnt++;
                   a.x[idx + c] = xn;
