@@ -927,22 +927,20 @@ __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
       for (int j = 0; j < BIG_W; ++j) asm volatile("" : "+a"(acc[i][j]));
 
     JM_TSTAMP(EPI == EPI_RELU ? 1 : 4, 0);
-    // ---- epilogue.  The weights were the MFMA's row operand, so lane (r, h) holds ONE sample per sample tile and
-    // runs of four consecutive units: acc[i][j][e] belongs to sample row0 + (wm*4 + i)*32 + r and unit
-    // (tile0 + wn*4 + j)*32 + 8*(e/4) + 4*h + e%4.  Four units of a sample are contiguous in every array the
-    // epilogue touches (bias, noise, symbols, and the fragment-major activations: half of a 16-byte piece in
-    // bf16, a whole one in fp32), so results leave the registers in 8- and 16-byte pieces without a transposition
-    // through LDS.  The operand stages are free now: the workgroup's 256 sample ids go through stage 0.
+    // ---- epilogue.  Four units of a sample are contiguous in every array it touches (noise, symbols, and the
+    // fragment-major activations: half of a 16-byte piece in bf16, a whole one in fp32), so results leave the
+    // registers in 8- and 16-byte pieces without a transposition through LDS.  The operand stages are free now: the
+    // workgroup's 256 sample ids go through stage 0.
     int* ids = (int*)big_s0;
     {
       const int row = row0 + tid;
       ids[tid] = row < n_rows ? (a.rows ? a.rows[row] : row) : -1;
     }
     __syncthreads();
-    const bool vec_io = a.io_aligned != 0;            // 16-byte reads of noise, 4-byte symbol words: aligned rows
-    // Everything the epilogue reads is requested before anything is stored: the compiler must keep a load behind
-    // every earlier store it cannot prove to be to other memory, and loads waited for one at a time cost a memory
-    // round trip each (64 per wave: that was most of the epilogue's time).  Bias: once for all sample tiles.
+    // The weights were the MFMA's row operand, so lane (r, h) holds ONE sample per sample tile and runs of four
+    // consecutive units: acc[i][j][e] belongs to sample row0 + (wm*4 + i)*32 + r and unit
+    // (tile0 + wn*4 + j)*32 + 8*(e/4) + 4*h + e%4.  Everything the epilogue reads is requested before anything is
+    // stored where possible (the bias: here, once for all sample tiles).
     int col_of[BIG_W];                                 // first unit of this lane in unit tile j (+ 8 g per run of four)
     bool tile_ok[BIG_W];
     float4 b4[BIG_W][4];
@@ -958,69 +956,61 @@ __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
         frag_col[j][g] = frag_col_offset<T>(col_of[j] + 8 * g);
       }
     }
-    static_for<BIG_W>([&](auto I) {
-      constexpr int i = decltype(I)::value;
-      const int sample = ids[(wm * BIG_W + i) * TILE + r];
-      const size_t frag_row = frag_row_offset<T>(max(sample, 0), EPI == EPI_RELU ? a.out_chunks : a.enc_chunks);
+    if constexpr (EPI == EPI_BERNOULLI) {
+      // Sampling, in 8 batches of two unit tiles (8 runs of four positions per lane).  A run that lies wholly inside
+      // the window and the row takes the fast path: one 16-byte read of noise, one word of symbols in, one out, one
+      // piece of the encoded input (instead of a byte and an element per changed position: the first pass from
+      // zeros changes every other one, 26 M single stores at batch 32768).  The inputs of batch b + 1 are requested
+      // before the results of batch b are stored: the compiler keeps a load behind every earlier store it cannot
+      // prove to be to other memory, and a batch's loads waited for on their own cost a memory round trip each.
+      const bool vec_io = a.io_aligned != 0;           // 16-byte reads of noise, 4-byte symbol words: aligned rows
+      constexpr int NB = 2 * BIG_W;
+      bool fast[2][8];
+      float4 u4[2][8];
+      uint32_t xo[2][8];
+      int old_count[BIG_W];                            // what the counter atomics returned: waited for once, at the end
+      auto request = [&](int b, bool (&f)[8], float4 (&u)[8], uint32_t (&x)[8]) {
+        const int sample = ids[(wm * BIG_W + (b >> 1)) * TILE + r];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          const int j = 2 * (b & 1) + (q >> 2), col0 = col_of[j] + 8 * (q & 3);
+          f[q] = tile_ok[j] && sample >= 0 && vec_io && col0 >= a.t_lo && col0 + 4 <= min(a.t_hi, a.D);
+          // (unconditional loads from an address that is always valid: a load inside a branch is waited for there)
+          const size_t idx = f[q] ? (size_t)sample * a.D + col0 : 0;
+          u[q] = *(const float4*)(a.noise + idx);
+          x[q] = *(const uint32_t*)(a.x + idx);
+        }
+      };
+      request(0, fast[0], u4[0], xo[0]);
       int cnt = 0;
-      // sampling: a run of four positions that is wholly inside the window and the row takes the fast path
-      // (one 16-byte read of noise, one word of symbols); its inputs are requested here for all 16 runs
-      bool fast[BIG_W][4];
-      float4 u4[BIG_W][4];
-      uint32_t xo[BIG_W][4];
-      if (EPI == EPI_BERNOULLI) {
-#pragma unroll
-        for (int j = 0; j < BIG_W; ++j)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const int col0 = col_of[j] + 8 * g;
-            fast[j][g] = tile_ok[j] && sample >= 0 && vec_io && col0 >= a.t_lo && col0 + 4 <= min(a.t_hi, a.D);
-            u4[j][g] = make_float4(2.f, 2.f, 2.f, 2.f);
-            xo[j][g] = 0;
-            if (fast[j][g]) {
-              const size_t idx = (size_t)sample * a.D + col0;
-              u4[j][g] = *(const float4*)(a.noise + idx);
-              xo[j][g] = *(const uint32_t*)(a.x + idx);
-            }
-          }
-      }
-      static_for<BIG_W>([&](auto J) {
-        constexpr int j = decltype(J)::value;
-        const bool ok = tile_ok[j] && sample >= 0;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int col0 = col_of[j] + 8 * g;                      // this lane's units col0 .. col0 + 3
+      static_for<NB>([&](auto Bt) {
+        constexpr int b = decltype(Bt)::value, i = b >> 1;
+        const int sample = ids[(wm * BIG_W + i) * TILE + r];
+        const size_t frag_row = frag_row_offset<T>(max(sample, 0), a.enc_chunks);
+        if (b + 1 < NB) request(b + 1, fast[(b + 1) & 1], u4[(b + 1) & 1], xo[(b + 1) & 1]);
+        if ((b & 1) == 0) cnt = 0;
+        static_for<8>([&](auto Qt) {
+          constexpr int q = decltype(Qt)::value, j = 2 * (b & 1) + (q >> 2), g = q & 3;
+          const int col0 = col_of[j] + 8 * g;
           const float v[4] = {acc[i][j][4 * g + 0] + b4[j][g].x, acc[i][j][4 * g + 1] + b4[j][g].y,
                               acc[i][j][4 * g + 2] + b4[j][g].z, acc[i][j][4 * g + 3] + b4[j][g].w};
-          if (EPI == EPI_RELU) {
-            if (ok) store_quad<T>((T*)a.out + (frag_row + frag_col[j][g]), fmaxf(v[0], 0.f),
-                                  fmaxf(v[1], 0.f), fmaxf(v[2], 0.f), fmaxf(v[3], 0.f));
-          } else if (EPI == EPI_LOGITS) {
-            if (ok) {
-#pragma unroll
-              for (int c = 0; c < 4; ++c)
-                if (col0 + c < a.n_cols) ((float*)a.out)[(size_t)sample * a.ldo + col0 + c] = v[c];
-            }
-          } else if (fast[j][g]) {
-            // all four positions are the lane's to update: one word of symbols and one piece of the encoded
-            // input instead of a byte and an element per changed position (the first pass from zeros changes
-            // every other position: 26 M single stores at batch 32768)
+          if (fast[b & 1][q]) {
             const size_t idx = (size_t)sample * a.D + col0;
-            const float u[4] = {u4[j][g].x, u4[j][g].y, u4[j][g].z, u4[j][g].w};
+            const float u[4] = {u4[b & 1][q].x, u4[b & 1][q].y, u4[b & 1][q].z, u4[b & 1][q].w};
             uint32_t xn = 0;
 #pragma unroll
             for (int c = 0; c < 4; ++c) xn |= (u[c] < bernoulli_probability(v[c]) ? 1u : 0u) << (8 * c);
-            if (xn != xo[j][g]) {
-              uint32_t d = xn ^ xo[j][g];                          // differing positions: one bit per non-zero byte
+            if (xn != xo[b & 1][q]) {
+              uint32_t d = xn ^ xo[b & 1][q];                      // differing positions: one bit per non-zero byte
               d |= d >> 4;
               d |= d >> 2;
               d |= d >> 1;
               cnt += __popc(d & 0x01010101u);
               *(uint32_t*)(a.x + idx) = xn;
-              store_quad<T>((T*)a.enc + (frag_row + frag_col[j][g]), (float)(xn & 1u),
-                            (float)((xn >> 8) & 1u), (float)((xn >> 16) & 1u), (float)(xn >> 24));
+              store_quad<T>((T*)a.enc + (frag_row + frag_col[j][g]), (float)(xn & 1u), (float)((xn >> 8) & 1u),
+                            (float)((xn >> 16) & 1u), (float)(xn >> 24));
             }
-          } else if (ok && col0 < a.t_hi && col0 + 4 > a.t_lo && col0 < a.D) {
+          } else if (tile_ok[j] && sample >= 0 && col0 < a.t_hi && col0 + 4 > a.t_lo && col0 < a.D) {
             const size_t idx = (size_t)sample * a.D + col0;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -1035,13 +1025,45 @@ __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
               }
             }
           }
+        });
+        if (b & 1) {   // the sample tile is done: one counter update by the first of the sample's two lanes
+          cnt += __shfl_xor(cnt, 32);
+          old_count[i] = 0;
+          if (h == 0 && cnt > 0 && sample >= 0)
+            old_count[i] = __hip_atomic_fetch_add(&a.changed[(size_t)sample * CHG], cnt, __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT);
         }
       });
-      if (EPI == EPI_BERNOULLI) {   // the two lanes of a sample
-        cnt += __shfl_xor(cnt, 32);
-        if (h == 0 && cnt > 0) count_changed(&a.changed[(size_t)sample * CHG], cnt);
-      }
-    });
+      // (the atomics have been performed once their old values are here: see count_changed)
+#pragma unroll
+      for (int i = 0; i < BIG_W; ++i) asm volatile("" ::"v"(old_count[i]));
+    } else {
+      static_for<BIG_W>([&](auto I) {
+        constexpr int i = decltype(I)::value;
+        const int sample = ids[(wm * BIG_W + i) * TILE + r];
+        const size_t frag_row = frag_row_offset<T>(max(sample, 0), a.out_chunks);
+        static_for<BIG_W>([&](auto J) {
+          constexpr int j = decltype(J)::value;
+          const bool ok = tile_ok[j] && sample >= 0;
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int col0 = col_of[j] + 8 * g;                    // this lane's units col0 .. col0 + 3
+            const float v[4] = {acc[i][j][4 * g + 0] + b4[j][g].x, acc[i][j][4 * g + 1] + b4[j][g].y,
+                                acc[i][j][4 * g + 2] + b4[j][g].z, acc[i][j][4 * g + 3] + b4[j][g].w};
+            if (EPI == EPI_RELU) {
+              if (ok) store_quad<T>((T*)a.out + (frag_row + frag_col[j][g]), fmaxf(v[0], 0.f), fmaxf(v[1], 0.f),
+                                    fmaxf(v[2], 0.f), fmaxf(v[3], 0.f));
+            } else {
+              if (ok) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                  if (col0 + c < a.n_cols) ((float*)a.out)[(size_t)sample * a.ldo + col0 + c] = v[c];
+              }
+            }
+          }
+        });
+      });
+    }
     JM_TSTAMP(EPI == EPI_RELU ? 2 : 5, 1);
   }
   if (EPI == EPI_BERNOULLI && a.retire.enabled) finish_pass(a.retire, gridDim.x);
