@@ -92,6 +92,8 @@ struct Chain {
   int first = 0, count = 0;
   size_t block = 0;                  // index into the call's block list
   int k_enq = 0, k_conf = 0;         // passes of the current block enqueued / whose result the host has seen
+  int bound = 0;                     // upper limit of the active count in the current block: the chain's size, then
+                                     // what the latest confirmed pass left (the list only shrinks inside a block)
   bool block_started = false, finished = false, iters_cleared = false;
   std::vector<char> log_first;       // per enqueued pass: was it the first of its block
 };
@@ -1385,10 +1387,14 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
       c.iters_cleared = true;
     }
     c.block_started = true;
+    c.bound = c.count;
   }
   const int k = c.k_enq + 1;
   const int in = (k - 1) & 1, out = k & 1;
-  RowSet rs{c.rows[in], c.n_rows[in], c.count, x, c.first};
+  // (grids, tile shapes and the place of the stop test are chosen for at most c.bound active samples: late passes
+  // of a large batch run on a fraction of it)
+  const int n_bound = std::max(1, std::min(c.bound, c.count));
+  RowSet rs{c.rows[in], c.n_rows[in], n_bound, x, c.first};
   SampleIO io{noise, x, blk.a, blk.b, RetireArgs{}};
   if (blk.stop_test) {
     const int slot = (int)c.log_first.size();
@@ -1402,7 +1408,7 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
     io.retire.iters = w.call_iters;
     io.retire.flags = w.flags;
     io.retire.done_ctr = c.done_ctr;
-    io.retire.n_max = c.count;
+    io.retire.n_max = n_bound;
     io.retire.host_slot = c.d_pin + c.pin_base + slot;
     io.retire.host_flags = c.d_pin + c.pin_base + (c.pin_half - 1);
     io.retire.last_pass = (k == blk.cap);
@@ -1422,11 +1428,11 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
     // a long list is retired by a kernel of its own, spread over the chip, instead of by the output kernel's
     // last workgroup
     const RetireArgs retire = io.retire;
-    const bool split_retire = retire.enabled && c.count >= m->retire_split;
+    const bool split_retire = retire.enabled && n_bound >= m->retire_split;
     if (split_retire) io.retire.enabled = 0;
     TRY(run_output_sample(m, rs, io, blk.whole_network, blk.out_k_limit, s, by_pos));
     if (split_retire) {
-      hipLaunchKernelGGL(retire_kernel, dim3((c.count + RETIRE_WG_ROWS - 1) / RETIRE_WG_ROWS), dim3(256), 0, s, retire);
+      hipLaunchKernelGGL(retire_kernel, dim3((n_bound + RETIRE_WG_ROWS - 1) / RETIRE_WG_ROWS), dim3(256), 0, s, retire);
       HIP_TRY(hipGetLastError());
       m->stats[2]++;
     }
@@ -1459,6 +1465,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
     c.count = std::min(per, N - c.first);
     c.block = 0;
     c.k_enq = c.k_conf = 0;
+    c.bound = c.count;
     c.block_started = c.finished = c.iters_cleared = false;
     c.log_first.clear();
     c.stream = n_chains == 1 ? s : c.own_stream;   // a single chain needs no fork and join
@@ -1516,6 +1523,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
           const int left = c.h_pin[c.pin_base + slot];
           if (left >= 0) {
             c.k_conf++;
+            c.bound = std::min(c.bound, left);
             progressed = true;
             if (left == 0) block_done = true;
           }
