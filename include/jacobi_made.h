@@ -238,7 +238,7 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   MI355X that costs more than the overlap gains, hence the default of a single chain.
  *   MADE_OPT_BIG_TILE_BATCH (default 4096): batches (chains) of at least this many samples run the masked
  *   layers with 256 x 256 workgroup tiles staged through LDS instead of 32 x 32 tiles (on the D = 784,
- *   2 x 2000 network the two cross over near 5000 samples).
+ *   2 x 2000 network the two cross over near 3500 samples).
  *   MADE_OPT_CONV_ROWS (default 4; 2 or 4): image rows per workgroup of the convolutional model's k x k layers.
  *   MADE_OPT_RESIDENT (default 2; 0, 1 or 2): the sample-resident kernel serves jacobi_sample / gs_jacobi_sample of
  *   Bernoulli models in ONE launch: a workgroup keeps 32 samples' iterate and hidden activations in its LDS for the

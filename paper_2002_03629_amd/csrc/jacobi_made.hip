@@ -179,7 +179,7 @@ struct made_model {
   std::vector<int64_t> nnz;                   // [L+1] visible (mask = 1) weights per layer
   int persist_grid = 0;                       // workgroups of the persistent kernel (0 = not usable)
   bool prefix_cache = true;                   // made_set_option(MADE_OPT_PREFIX_CACHE)
-  int big_batch = 4096;                       // made_set_option(MADE_OPT_BIG_TILE_BATCH); measured crossover ~5000
+  int big_batch = 4096;                       // made_set_option(MADE_OPT_BIG_TILE_BATCH); measured crossover ~3500
   int n_chains = 1;                           // made_set_option(MADE_OPT_CHAINS)
   int retire_split = 4096;                    // made_set_option(MADE_OPT_RETIRE_SPLIT)
   int fused_categorical = 1;                  // made_set_option(MADE_OPT_FUSED_CATEGORICAL)
