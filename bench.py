@@ -489,6 +489,31 @@ def main() -> int:
                 extras[f"jacobi_gs_B{blk}"] = {"samples_per_s": N / dt, "ms_per_batch": dt * 1e3,
                                                "iters_mean": float(itc.mean()), "iters_max": int(itc.max()),
                                                "same_output_as_jacobi": bool(torch.equal(xq, x_jac))}
+        if not conv and w.C == 1 and not getattr(net, "onehot", False) and not args.batch:
+            # the same network on larger batches (supplementary: throughput once the layers are real GEMMs); the
+            # noise recipe is the workload's, so the first N samples are the headline batch again
+            sweep = {}
+            for nb in (2048, 8192, 32768):
+                wb = dataclasses.replace(w, N=nb)
+                ub = torch.from_numpy(S.make_noise(wb, rep=0)).cuda()
+                xb = torch.empty((nb, w.D), dtype=torch.uint8, device="cuda")
+                ib = torch.empty((nb,), dtype=torch.int32, device="cuda")
+                for _ in range(2):
+                    B.jacobi_sample(model, ub, nb, None, 0, xb, ib, stream)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                reps = 5
+                for _ in range(reps):
+                    B.jacobi_sample(model, ub, nb, None, 0, xb, ib, stream)
+                torch.cuda.synchronize()
+                dt = (time.perf_counter() - t0) / reps
+                same_noise = bool(torch.equal(ub[:N], noises[0]))
+                sweep[str(nb)] = {"samples_per_s": nb / dt, "ms_per_batch": dt * 1e3,
+                                  "iters_mean": float(ib.float().mean().item()),
+                                  "positions_differing_from_headline_batch":
+                                      int((xb[:N] != x_jac).sum().item()) if same_noise else None}
+                del ub, xb, ib
+            extras["batch_sweep"] = sweep
         result["extras"] = extras
 
     if not args.no_cpu_baseline and conv:
