@@ -158,6 +158,10 @@ def test_cfg2_large_batch_vector_epilogue():
         assert_logits_close(z, O.logits_all(exact, x), LOGIT_TOL["bf16"])
         xb, _ = g.gs_jacobi(noise, 196)
         assert_sample_parity(same, noise, xb)
+        # a block size that is no multiple of four: windows cut the epilogue's runs of four positions
+        xc, _ = g.gs_jacobi(noise, 50)
+        assert_sample_parity(same, noise, xc)
+        assert_sample_parity(same, noise[:sub], xc[:sub], xs, mg)
 
 
 def test_cfg2_batch_8192_stop_test_as_its_own_kernel():
