@@ -893,9 +893,11 @@ __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
     // everybody's have and everybody is done reading the stage that half hc + 3 goes to
     auto ring_step = [&](int hc, const uint4* cur, uint4* refill) {
       // (no fence here on purpose: a release fence on LDS makes the compiler wait for ALL LDS-bound loads, the
-      // younger halves included.  The memory clobber keeps the compiler from moving LDS reads across; the stage
-      // that is refilled below was last read by MFMAs issued before this point, whose operands had arrived.)
-      asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");
+      // younger halves included.  The memory clobber keeps the compiler from moving LDS reads across.  lgkmcnt(0):
+      // the stage that is refilled below was read in the previous step, and the compiler may have left the last of
+      // those reads in flight with its MFMAs behind this point; every wave's reads have returned before any wave
+      // passes the barrier and requests the refill.)
+      asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
       issue_half(hc + 3, refill);
       multiply_half(cur);
     };
