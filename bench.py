@@ -220,6 +220,8 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (supplementary sweeps)")
     ap.add_argument("--big-tile-batch", type=int, default=0,
                     help="batch size from which the 256 x 256 tile kernels are used (0 = library default)")
+    ap.add_argument("--mid-tile-batch", type=int, default=0,
+                    help="batch size from which the 128 x 128 tile kernels are used (0 = library default)")
     ap.add_argument("--conv-rows", type=int, default=0,
                     help="image rows per workgroup of the conv model's k x k layers (0 = library default)")
     ap.add_argument("--eps", type=float, default=0.0,
@@ -263,6 +265,8 @@ def main() -> int:
         B.made_set_option(model, B.MADE_OPT_CONV_ROWS, args.conv_rows)
     if args.big_tile_batch > 0:
         B.made_set_option(model, B.MADE_OPT_BIG_TILE_BATCH, args.big_tile_batch)
+    if args.mid_tile_batch > 0:
+        B.made_set_option(model, B.MADE_OPT_MID_TILE_BATCH, args.mid_tile_batch)
     n_layers = (w.n_conv if conv else len(net.hidden)) + 1
     nnz = B.made_layer_nnz(model, n_layers)
     n_slots = n_layers + 1                     # per-layer kernels + the persistent whole-call kernel

@@ -265,6 +265,7 @@ MADE_OPT_CONV_ROWS = 5
 MADE_OPT_PREFIX_CACHE = 6
 MADE_OPT_RESIDENT = 7
 MADE_OPT_RETIRE_SPLIT = 8
+MADE_OPT_MID_TILE_BATCH = 9
 
 
 def made_set_option(model: int, option: int, value: int) -> None:

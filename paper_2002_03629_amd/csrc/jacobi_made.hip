@@ -179,7 +179,10 @@ struct made_model {
   std::vector<int64_t> nnz;                   // [L+1] visible (mask = 1) weights per layer
   int persist_grid = 0;                       // workgroups of the persistent kernel (0 = not usable)
   bool prefix_cache = true;                   // made_set_option(MADE_OPT_PREFIX_CACHE)
-  int big_batch = 4096;                       // made_set_option(MADE_OPT_BIG_TILE_BATCH); measured crossover ~3500
+  int big_batch = 1 << 30;                    // made_set_option(MADE_OPT_BIG_TILE_BATCH): 256 x 256 tiles from here on (off:
+                                              // slower than 128 x 128 at every batch measured, up to 32768)
+  int mid_batch = 1280;                       // made_set_option(MADE_OPT_MID_TILE_BATCH): 128 x 128 tiles from here up to
+                                              // big_batch; measured crossover with the 32 x 32 tiles between 1024 and 1536
   int n_chains = 1;                           // made_set_option(MADE_OPT_CHAINS)
   int retire_split = 4096;                    // made_set_option(MADE_OPT_RETIRE_SPLIT)
   int fused_categorical = 1;                  // made_set_option(MADE_OPT_FUSED_CATEGORICAL)
@@ -404,6 +407,11 @@ extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
   if (option == MADE_OPT_BIG_TILE_BATCH) {
     if (value < 1) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_BIG_TILE_BATCH=%d must be >= 1", value);
     m->big_batch = value;
+    return MADE_OK;
+  }
+  if (option == MADE_OPT_MID_TILE_BATCH) {
+    if (value < 1) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_MID_TILE_BATCH=%d must be >= 1", value);
+    m->mid_batch = value;
     return MADE_OK;
   }
   if (option == MADE_OPT_RETIRE_SPLIT) {
@@ -890,25 +898,30 @@ static void prof_collect(made_model* m) {
   m->ev_layer.clear();
 }
 
-template <typename T, int EPI>
+template <typename T, int EPI, int W>
 static void launch_big_t(LayerArgs a, int n_tiles, int n_rows_max, hipStream_t s) {
+  constexpr int BIG_T = 2 * W, BIG_ROWS = BIG_T * TILE;   // tiles / samples per workgroup and dimension
   a.n_launch_tiles = n_tiles;
   a.row_tiles = (n_rows_max + BIG_ROWS - 1) / BIG_ROWS;
   const int big_cols = (n_tiles + BIG_T - 1) / BIG_T;
   a.big_by_rows = a.row_tiles >= big_cols;
   const int groups = ((a.big_by_rows ? a.row_tiles : big_cols) + XCDS - 1) / XCDS;
   const int other = a.big_by_rows ? big_cols : a.row_tiles;
-  hipLaunchKernelGGL((masked_layer_big_kernel<T, EPI>), dim3(groups * XCDS * other), dim3(256), 0, s, a);   // (128 KB of static LDS)
+  hipLaunchKernelGGL((masked_layer_big_kernel<T, EPI, W>), dim3(groups * XCDS * other), dim3(256), 0, s, a);   // (static LDS: 128 / 64 KB)
 }
 
 template <int EPI>
 static void launch_layer(made_model* m, int layer, const LayerArgs& a, int n_tiles, int row_tiles, hipStream_t s) {
   prof_mark(m, layer, false, s);
-  const bool big = a.n_rows >= m->big_batch;
+  const bool big = a.n_rows >= m->big_batch, mid = !big && a.n_rows >= m->mid_batch;
   if (m->dtype == MADE_BF16) {
-    if (big) launch_big_t<bf16_t, EPI>(a, n_tiles, a.n_rows, s); else launch_layer_t<bf16_t, EPI>(a, n_tiles, row_tiles, s);
+    if (big) launch_big_t<bf16_t, EPI, 4>(a, n_tiles, a.n_rows, s);
+    else if (mid) launch_big_t<bf16_t, EPI, 2>(a, n_tiles, a.n_rows, s);
+    else launch_layer_t<bf16_t, EPI>(a, n_tiles, row_tiles, s);
   } else {
-    if (big) launch_big_t<float, EPI>(a, n_tiles, a.n_rows, s); else launch_layer_t<float, EPI>(a, n_tiles, row_tiles, s);
+    if (big) launch_big_t<float, EPI, 4>(a, n_tiles, a.n_rows, s);
+    else if (mid) launch_big_t<float, EPI, 2>(a, n_tiles, a.n_rows, s);
+    else launch_layer_t<float, EPI>(a, n_tiles, row_tiles, s);
   }
   prof_mark(m, layer, true, s);
 }
@@ -941,7 +954,7 @@ static LayerArgs base_args(const made_model* m, int l, const void* A, const RowS
 // then runs the output layer the same way.  Only for whole-layer passes on the 32 x 32 tile kernels.
 static bool hidden_by_position(const made_model* m, const RowSet& rs, bool limited) {
   return m->arch == 0 && !limited && !m->onehot && (m->C == 1 || m->real) && rs.rows != nullptr &&
-         rs.n_rows < m->big_batch;
+         rs.n_rows < std::min(m->big_batch, m->mid_batch);
 }
 
 static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, int in_limit0, hipStream_t s,
@@ -1316,10 +1329,11 @@ extern "C" int made_forward_logits(made_model* m, const uint8_t* x, int32_t N, f
     a.n_cols = 3 * CAT_C;
     a.out = logits;
     a.ldo = 3 * CAT_C;
-    const int big_saved = m->big_batch;
-    m->big_batch = 1 << 30;    // (the head has only 768 outputs: always the 32 x 32 tiles)
+    const int big_saved = m->big_batch, mid_saved = m->mid_batch;
+    m->big_batch = m->mid_batch = 1 << 30;    // (the head has only 768 outputs: always the 32 x 32 tiles)
     launch_layer<EPI_LOGITS>(m, m->L, a, 3 * CAT_C / TILE, (a.n_rows + TILE - 1) / TILE, s);
     m->big_batch = big_saved;
+    m->mid_batch = mid_saved;
     m->profiling = was_profiling;
     HIP_TRY(hipGetLastError());
     return MADE_OK;
@@ -1838,10 +1852,11 @@ extern "C" int made_forward_params(made_model* m, const float* x, int32_t N, flo
   LayerArgs a = base_args(m, m->L, m->ws.act[m->L - 1], rs);
   a.out = params;
   a.ldo = m->D * m->C;
-  const int big_saved = m->big_batch;
-  m->big_batch = 1 << 30;
+  const int big_saved = m->big_batch, mid_saved = m->mid_batch;
+  m->big_batch = m->mid_batch = 1 << 30;
   launch_layer<EPI_LOGITS>(m, m->L, a, m->layers[m->L].n_tiles, (N + TILE - 1) / TILE, s);
   m->big_batch = big_saved;
+  m->mid_batch = mid_saved;
   m->profiling = was_profiling;
   HIP_TRY(hipGetLastError());
   return MADE_OK;

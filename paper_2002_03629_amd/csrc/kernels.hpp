@@ -752,11 +752,7 @@ __global__ __launch_bounds__(NW * 64) void masked_layer_kernel(LayerArgs a) {
 // there: 512 FLOP per byte fetched from L2.  Because global memory already holds both operands in
 // fragment order, the LDS image is a plain copy and every ds_read_b128 is conflict free.
 // ------------------------------------------------------------------------------------------------
-constexpr int BIG_W = 4;                 // MFMA tiles per wave and dimension
-constexpr int BIG_T = 2 * BIG_W;         // tiles per workgroup and dimension (2 x 2 waves)
-constexpr int BIG_ROWS = BIG_T * TILE;   // 256
 constexpr int BIG_HALF = 128;            // 16-byte pieces of one block in half a chunk (2 of its 4 MFMA steps)
-constexpr int BIG_STAGE = 2 * BIG_T * BIG_HALF;   // pieces per ring stage: (8 + 8) blocks x 2 KB = 32 KB
 
 // Workgroup barrier that orders LDS traffic only.  (__syncthreads also waits for every outstanding global load
 // of the wave, i.e. it would drain a prefetch ring at every use.)
@@ -796,8 +792,12 @@ __device__ __forceinline__ void mfma_step<float>(const uint4& a, const uint4& b,
   acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
 }
 
-template <typename T, int EPI>
-__global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
+// W = MFMA tiles per wave and dimension: 4 (256 x 256 per workgroup, one workgroup per compute unit) or 2 (128 x 128:
+// a quarter of the LDS and accumulators, two workgroups per compute unit; for batches that would leave most of the
+// chip idle on 256-row tiles).
+template <typename T, int EPI, int W>
+__global__ __launch_bounds__(256, W == 2 ? 2 : 1) void masked_layer_big_kernel(LayerArgs a) {
+  constexpr int BIG_W = W, BIG_T = 2 * W, BIG_ROWS = BIG_T * TILE, BIG_STAGE = 2 * BIG_T * BIG_HALF;
   constexpr int KC = 2 * Elem<T>::EPL;
   // ring stages, [block 0..7 = samples, 8..15 = units][128] each (separate arrays: see the main loop)
   __shared__ uint4 big_s0[BIG_STAGE];
@@ -897,7 +897,9 @@ __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
       // the stage that is refilled below was read in the previous step, and the compiler may have left the last of
       // those reads in flight with its MFMAs behind this point; every wave's reads have returned before any wave
       // passes the barrier and requests the refill.)
-      asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      // (two younger halves of 2 W copies per wave each)
+      if constexpr (W == 4) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
       issue_half(hc + 3, refill);
       multiply_half(cur);
     };
@@ -936,7 +938,7 @@ __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
     int* ids = (int*)big_s0;
     {
       const int row = row0 + tid;
-      ids[tid] = row < n_rows ? (a.rows ? a.rows[row] : row) : -1;
+      if (tid < BIG_ROWS) ids[tid] = row < n_rows ? (a.rows ? a.rows[row] : row) : -1;
     }
     __syncthreads();
     // The weights were the MFMA's row operand, so lane (r, h) holds ONE sample per sample tile and runs of four
@@ -966,16 +968,16 @@ __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
       // before the results of batch b are stored: the compiler keeps a load behind every earlier store it cannot
       // prove to be to other memory, and a batch's loads waited for on their own cost a memory round trip each.
       const bool vec_io = a.io_aligned != 0;           // 16-byte reads of noise, 4-byte symbol words: aligned rows
-      constexpr int NB = 2 * BIG_W;
+      constexpr int PAIRS = BIG_W / 2, NB = BIG_W * PAIRS;   // unit-tile pairs per sample tile; batches
       bool fast[2][8];
       float4 u4[2][8];
       uint32_t xo[2][8];
       int old_count[BIG_W];                            // what the counter atomics returned: waited for once, at the end
       auto request = [&](int b, bool (&f)[8], float4 (&u)[8], uint32_t (&x)[8]) {
-        const int sample = ids[(wm * BIG_W + (b >> 1)) * TILE + r];
+        const int sample = ids[(wm * BIG_W + b / PAIRS) * TILE + r];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-          const int j = 2 * (b & 1) + (q >> 2), col0 = col_of[j] + 8 * (q & 3);
+          const int j = 2 * (b % PAIRS) + (q >> 2), col0 = col_of[j] + 8 * (q & 3);
           f[q] = tile_ok[j] && sample >= 0 && vec_io && col0 >= a.t_lo && col0 + 4 <= min(a.t_hi, a.D);
           // (unconditional loads from an address that is always valid: a load inside a branch is waited for there)
           const size_t idx = f[q] ? (size_t)sample * a.D + col0 : 0;
@@ -986,13 +988,13 @@ __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
       request(0, fast[0], u4[0], xo[0]);
       int cnt = 0;
       static_for<NB>([&](auto Bt) {
-        constexpr int b = decltype(Bt)::value, i = b >> 1;
+        constexpr int b = decltype(Bt)::value, i = b / PAIRS, pair = b % PAIRS;
         const int sample = ids[(wm * BIG_W + i) * TILE + r];
         const size_t frag_row = frag_row_offset<T>(max(sample, 0), a.enc_chunks);
         if (b + 1 < NB) request(b + 1, fast[(b + 1) & 1], u4[(b + 1) & 1], xo[(b + 1) & 1]);
-        if ((b & 1) == 0) cnt = 0;
+        if (pair == 0) cnt = 0;
         static_for<8>([&](auto Qt) {
-          constexpr int q = decltype(Qt)::value, j = 2 * (b & 1) + (q >> 2), g = q & 3;
+          constexpr int q = decltype(Qt)::value, j = 2 * pair + (q >> 2), g = q & 3;
           const int col0 = col_of[j] + 8 * g;
           const float v[4] = {acc[i][j][4 * g + 0] + b4[j][g].x, acc[i][j][4 * g + 1] + b4[j][g].y,
                               acc[i][j][4 * g + 2] + b4[j][g].z, acc[i][j][4 * g + 3] + b4[j][g].w};
@@ -1028,7 +1030,7 @@ __global__ __launch_bounds__(256) void masked_layer_big_kernel(LayerArgs a) {
             }
           }
         });
-        if (b & 1) {   // the sample tile is done: one counter update by the first of the sample's two lanes
+        if (pair == PAIRS - 1) {   // the sample tile is done: one counter update by the first of the sample's two lanes
           cnt += __shfl_xor(cnt, 32);
           old_count[i] = 0;
           if (h == 0 && cnt > 0 && sample >= 0)

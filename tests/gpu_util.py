@@ -45,7 +45,7 @@ RETIRE_SPLIT = None   # None: the library's default; 1: the stop test always run
 
 
 class GpuModel:
-    def __init__(self, net, persistent=None, big_tile_batch=None):
+    def __init__(self, net, persistent=None, big_tile_batch=None, mid_tile_batch=None):
         self.net = net
         self.h = B.model_from_network(net)
         B.made_set_option(self.h, B.MADE_OPT_PERSISTENT, int(PERSISTENT if persistent is None else persistent))
@@ -56,6 +56,8 @@ class GpuModel:
             B.made_set_option(self.h, B.MADE_OPT_RETIRE_SPLIT, RETIRE_SPLIT)
         if big_tile_batch is not None:
             B.made_set_option(self.h, B.MADE_OPT_BIG_TILE_BATCH, big_tile_batch)
+        if mid_tile_batch is not None:
+            B.made_set_option(self.h, B.MADE_OPT_MID_TILE_BATCH, mid_tile_batch)
 
     def close(self):
         if self.h:

@@ -139,8 +139,9 @@ def test_cfg2_jacobi_gs_full_batch():
             print(f"cfg2 jacobi_gs block {block}: iterations mean {it.mean():.2f} max {it.max()}, stats {st}")
 
 
-def test_cfg2_large_batch_vector_epilogue():
-    """cfg2's network at batch 300: the 256 x 256 tile kernels with the 16-byte epilogue I/O (D % 16 == 0)."""
+@pytest.mark.parametrize("tile", [256, 128])
+def test_cfg2_large_batch_vector_epilogue(tile):
+    """cfg2's network at batch 300: the 256 x 256 / 128 x 128 tile kernels with the 16-byte epilogue I/O (D % 16 == 0)."""
     import dataclasses
     w = dataclasses.replace(S.workload("cfg2"), N=300)
     net = S.make_network(w)
@@ -149,7 +150,7 @@ def test_cfg2_large_batch_vector_epilogue():
     sub = 4
     xs, mg = O.sequential_sample(same, noise[:sub])
     ref = O.jacobi_reference(same, noise)
-    with GpuModel(net, big_tile_batch=256) as g:
+    with GpuModel(net, big_tile_batch=256 if tile == 256 else 1 << 30, mid_tile_batch=128 if tile == 128 else None) as g:
         x, it = g.jacobi(noise)
         assert_sample_parity(same, noise, x)
         assert_sample_parity(same, noise[:sub], x[:sub], xs, mg)

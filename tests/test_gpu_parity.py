@@ -246,10 +246,11 @@ def test_edge_cases():
         B.made_init(4, 1, [3], B.MADE_F32, [np.array([1, 2, 4], np.int32)], [np.zeros((3, 4)), np.zeros((4, 3))])
 
 
+@pytest.mark.parametrize("tile", [256, 128])
 @pytest.mark.parametrize("name,N", [("mid_bf16", 700), ("small_f32", 300), ("small_bf16", 515)])
-def test_large_batch_uses_big_tiles(name, N):
-    """Large batches run the layers with 256 x 256 workgroup tiles (the threshold is lowered to 256 samples here
-    so that the oracle stays cheap); same parity bar."""
+def test_large_batch_uses_big_tiles(name, N, tile):
+    """Large batches run the layers with 256 x 256 (or, below that threshold, 128 x 128) workgroup tiles (the
+    thresholds are lowered to 256 / 128 samples here so that the oracle stays cheap); same parity bar."""
     import dataclasses
     w = dataclasses.replace(S.workload(name), N=N)
     net = S.make_network(w, with_bias=True)
@@ -258,7 +259,7 @@ def test_large_batch_uses_big_tiles(name, N):
     x0 = _symbols(w, np.random.default_rng(4), N)
     xs, margins = O.sequential_sample(same, noise)
     ref = O.jacobi_reference(same, noise)
-    with GpuModel(net, big_tile_batch=256) as g:
+    with GpuModel(net, big_tile_batch=256 if tile == 256 else 1 << 30, mid_tile_batch=128 if tile == 128 else None) as g:
         z = g.logits(x0)
         assert_logits_close(z, O.logits_all(exact, x0), LOGIT_TOL[w.dtype])
         x, it = g.jacobi(noise)
