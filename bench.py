@@ -222,6 +222,8 @@ def main() -> int:
                     help="batch size from which the 256 x 256 tile kernels are used (0 = library default)")
     ap.add_argument("--mid-tile-batch", type=int, default=0,
                     help="batch size from which the 128 x 128 tile kernels are used (0 = library default)")
+    ap.add_argument("--retire-split", type=int, default=0,
+                    help="active-list length from which the stop test runs as a kernel of its own (0 = library default)")
     ap.add_argument("--conv-rows", type=int, default=0,
                     help="image rows per workgroup of the conv model's k x k layers (0 = library default)")
     ap.add_argument("--eps", type=float, default=0.0,
@@ -267,6 +269,8 @@ def main() -> int:
         B.made_set_option(model, B.MADE_OPT_BIG_TILE_BATCH, args.big_tile_batch)
     if args.mid_tile_batch > 0:
         B.made_set_option(model, B.MADE_OPT_MID_TILE_BATCH, args.mid_tile_batch)
+    if args.retire_split > 0:
+        B.made_set_option(model, B.MADE_OPT_RETIRE_SPLIT, args.retire_split)
     n_layers = (w.n_conv if conv else len(net.hidden)) + 1
     nnz = B.made_layer_nnz(model, n_layers)
     n_slots = n_layers + 1                     # per-layer kernels + the persistent whole-call kernel

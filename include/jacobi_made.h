@@ -255,7 +255,7 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   MADE_OPT_PREFIX_CACHE (default 1): GS-Jacobi on the masked MLP keeps the activations of the hidden units whose
  *   inputs all lie before the current block (degree <= block start: they are final) after the block's first
  *   pass and only re-evaluates the units behind them; 0 re-evaluates every visible unit in every pass.
- *   MADE_OPT_RETIRE_SPLIT (default 4096, >= 1): the stop test of a pass (which samples changed, the new active
+ *   MADE_OPT_RETIRE_SPLIT (default 2048, >= 1): the stop test of a pass (which samples changed, the new active
  *   list) runs inside the pass's last kernel, in the workgroup that finishes last; batches (chains) of at least
  *   this many samples run it as a kernel of its own spread over the chip (one workgroup needs ~180 us for 32768
  *   samples; the extra launch costs a few us).  Masked-MLP models only.  The active list's internal order may

@@ -184,7 +184,7 @@ struct made_model {
   int mid_batch = 1280;                       // made_set_option(MADE_OPT_MID_TILE_BATCH): 128 x 128 tiles from here up to
                                               // big_batch; measured crossover with the 32 x 32 tiles between 1024 and 1536
   int n_chains = 1;                           // made_set_option(MADE_OPT_CHAINS)
-  int retire_split = 4096;                    // made_set_option(MADE_OPT_RETIRE_SPLIT)
+  int retire_split = 2048;                    // made_set_option(MADE_OPT_RETIRE_SPLIT); +4 % at batch 2048, +9 % at 4096 over the fused tail
   int fused_categorical = 1;                  // made_set_option(MADE_OPT_FUSED_CATEGORICAL)
   int use_persistent = 0;                     // made_set_option(MADE_OPT_PERSISTENT); off: measured slower, see header
   // sample-resident kernel (resident_sampler_kernel): LDS layout, 0 bytes = this model does not fit
