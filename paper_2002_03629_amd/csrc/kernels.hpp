@@ -743,14 +743,16 @@ __global__ __launch_bounds__(NW * 64) void masked_layer_kernel(LayerArgs a) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// Large-batch variant of the masked layer: 256 samples x 256 units per workgroup.
+// Large-batch variant of the masked layer: 128 x 128 or 256 x 256 (samples x units) per workgroup.
 //
-// With hundreds of active samples a layer is a real GEMM and the 32 x 32 tiles above would re-read
-// every operand byte from L2 (16 FLOP per byte).  Here 4 waves each own 128 x 128 outputs (4 x 4 MFMA
-// tiles, 256 accumulator registers); per K chunk the workgroup copies 8 sample blocks and 8 weight
-// blocks (4 KB each) into LDS once, double buffered, and every wave reads its 4 + 4 fragments from
-// there: 512 FLOP per byte fetched from L2.  Because global memory already holds both operands in
-// fragment order, the LDS image is a plain copy and every ds_read_b128 is conflict free.
+// With a thousand and more active samples a layer is a real GEMM and the 32 x 32 tiles above would re-read
+// every operand byte from L2 (16 FLOP per byte).  Here 4 waves (2 x 2) each own W x W MFMA tiles (W = 2: 64 x 64
+// outputs, 64 accumulator registers; W = 4: 128 x 128, 256 registers); per half K chunk the workgroup copies 2 W
+// sample blocks and 2 W weight blocks (2 KB each) into one stage of an LDS ring, and every wave reads its W + W
+// fragments per MFMA step from there: 256 resp. 512 FLOP per byte fetched from L2.  Because global memory already
+// holds both operands in fragment order, the LDS image is a plain copy and every ds_read_b128 is conflict free.
+// W = 2 leaves room for two workgroups per compute unit (64 KB of LDS, ~200 registers), which fill each other's
+// barrier, LDS and epilogue waits; it is the faster shape at every batch measured.
 // ------------------------------------------------------------------------------------------------
 constexpr int BIG_HALF = 128;            // 16-byte pieces of one block in half a chunk (2 of its 4 MFMA steps)
 
