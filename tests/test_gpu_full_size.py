@@ -198,3 +198,34 @@ def test_cfg2_batch_8192_stop_test_as_its_own_kernel():
     assert (it[:64][clear] == ref[1][clear]).all()
     for a, b in zip(results[0], results[1]):
         assert (a == b).all()
+
+
+@pytest.mark.parametrize("N", [1279, 1280, 1281, 2047, 2048, 2049, 2600])
+def test_batches_around_the_tile_and_stop_test_thresholds(N):
+    """Library defaults on batches just below, at and above the sizes where the layers move to the LDS-staged
+    128 x 128 tiles (1280) and the stop test becomes a kernel of its own (2048); late passes of the same call fall
+    back below both.  Whole batch by the fixed-point certificate; pass counts against a run that stays on the
+    32 x 32 tiles with the fused stop test."""
+    import dataclasses
+    import gpu_util
+    w = dataclasses.replace(S.workload("mid_bf16"), N=N)
+    net = S.make_network(w, with_bias=True)
+    _, same = oracle_models(net)
+    noise = S.make_noise(w)
+    old = gpu_util.CHAINS, gpu_util.RETIRE_SPLIT
+    try:
+        gpu_util.CHAINS, gpu_util.RETIRE_SPLIT = 1, None
+        with GpuModel(net) as g:
+            x, it = g.jacobi(noise)
+            xb, _ = g.gs_jacobi(noise, 50)
+        gpu_util.RETIRE_SPLIT = 1 << 30
+        with GpuModel(net, mid_tile_batch=1 << 30) as g:
+            x_small, it_small = g.jacobi(noise)
+    finally:
+        gpu_util.CHAINS, gpu_util.RETIRE_SPLIT = old
+    assert_sample_parity(same, noise, x)
+    assert_sample_parity(same, noise, xb)
+    assert_sample_parity(same, noise, x_small)
+    rows_equal = (x == x_small).all(axis=1)
+    assert rows_equal.mean() > 0.99                      # (the two tile shapes sum in different orders: near-ties may flip)
+    assert (it[rows_equal] == it_small[rows_equal]).all()
