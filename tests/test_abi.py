@@ -75,3 +75,13 @@ def test_header_constants_match_the_binding():
     # an option the library does not know is an argument error, also without a GPU
     L = binding.lib()
     assert L.made_set_option(None, binding.MADE_OPT_RETIRE_SPLIT, 1) == binding.MADE_ERR_ARG
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits (before it touches any GPU)."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
