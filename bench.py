@@ -516,8 +516,11 @@ def main() -> int:
                 torch.cuda.synchronize()
                 dt = (time.perf_counter() - t0) / reps
                 same_noise = bool(torch.equal(ub[:N], noises[0]))
+                stb = B.made_last_stats(model)
+                tfl = 2.0 * sum(nnz) * stb["sample_passes"] / dt / 1e12      # algorithmic: masked weights, active samples
                 sweep[str(nb)] = {"samples_per_s": nb / dt, "ms_per_batch": dt * 1e3,
                                   "iters_mean": float(ib.float().mean().item()),
+                                  "algorithmic_tflops": tfl, "frac_of_bf16_mfma_peak": tfl / 2500.0,
                                   "positions_differing_from_headline_batch":
                                       int((xb[:N] != x_jac).sum().item()) if same_noise else None}
                 del ub, xb, ib
