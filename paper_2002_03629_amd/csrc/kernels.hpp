@@ -1554,13 +1554,12 @@ struct ConvFirstArgs {
 template <typename T, int FT, int KS>
 __global__ __launch_bounds__(FT * 64) void conv_first_kernel(ConvFirstArgs a) {
   constexpr int MID = KS / 2, NT = MID * KS + MID + 1, K_LIVE = NT * 3;
-  constexpr int KC = 2 * Elem<T>::EPL, P = 16 / (int)sizeof(T);
+  constexpr int KC = 2 * Elem<T>::EPL;
   constexpr int K0_CHUNKS = (K_LIVE + KC - 1) / KC, K0 = K0_CHUNKS * KC;
   constexpr int ROWB = (32 + 2 * MID) * 3;          // bytes per padded symbol row
   constexpr int NTHREADS = FT * 64;
   __shared__ uint8_t xt[(MID + 1) * ROWB + 16];
   __shared__ __align__(16) T a_lds[32 * K0];        // one row group of the operand, fragment-major
-  __shared__ float patch_lds[FT][TILE][TILE + 1];
   const int g = blockIdx.x;                         // group = row of pixels (n, y)
   const int n = g / a.H, y = g % a.H;
   if (!conv_rows_active(a.win, n, y, 1)) return;    // (uniform over the workgroup)
@@ -1574,11 +1573,12 @@ __global__ __launch_bounds__(FT * 64) void conv_first_kernel(ConvFirstArgs a) {
   for (int c = 0; c < K0_CHUNKS; ++c)
 #pragma unroll
     for (int s = 0; s < 4; ++s) wf[c][s] = Wp[(size_t)c * 256 + s * 64];
-  const int rr = lane >> 1, c16 = (lane & 1) * 16;
-  const int ch0 = wave * TILE + c16;
+  // the weights are the MFMA's row operand, so lane (r, h) ends up with pixel r and the runs of four channels
+  // 8 q + 4 h .. + 3 of its channel tile: its bias values are requested now
+  const int ch0 = wave * TILE + 4 * h;
   float4 bias4[4];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) bias4[q] = *(const float4*)(a.bias + ch0 + 4 * q);
+  for (int q = 0; q < 4; ++q) bias4[q] = *(const float4*)(a.bias + ch0 + 8 * q);
 
   // symbol rows y - MID .. y with MID pixels of padding on both sides
   for (int e = tid; e < (MID + 1) * ROWB; e += NTHREADS) {
@@ -1610,21 +1610,17 @@ __global__ __launch_bounds__(FT * 64) void conv_first_kernel(ConvFirstArgs a) {
     uint4 af[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) af[s] = Ap[c * 256 + s * 64];
-    mfma_chunk<T>(af, wf[c], acc);
+    mfma_chunk<T>(wf[c], af, acc);                  // (channels = rows of the result)
   }
 
-  float (*patch)[TILE + 1] = patch_lds[wave];
+  // acc[4 q + c] = channel ch0 + 8 q + c of pixel r: four consecutive channels are half a 16-byte piece (bf16) or a
+  // whole one (fp32) of the fragment-major activations, stored straight from the registers
+  const size_t out_row = frag_row_offset<T>(g * 32 + r, a.out_chunks);
 #pragma unroll
-  for (int e = 0; e < 16; ++e) patch[8 * (e >> 2) + 4 * h + (e & 3)][r] = acc[e];
-  const float bias[16] = {bias4[0].x, bias4[0].y, bias4[0].z, bias4[0].w, bias4[1].x, bias4[1].y, bias4[1].z, bias4[1].w,
-                          bias4[2].x, bias4[2].y, bias4[2].z, bias4[2].w, bias4[3].x, bias4[3].y, bias4[3].z, bias4[3].w};
-  float v[16];
-#pragma unroll
-  for (int cc = 0; cc < 16; ++cc) v[cc] = patch[rr][c16 + cc] + bias[cc];
-  const int pixel = g * 32 + rr;
-#pragma unroll
-  for (int q = 0; q < 16 / P; ++q)
-    *(uint4*)((T*)a.out + frag_offset<T>(pixel, ch0 + q * P, a.out_chunks)) = Elem<T>::relu_piece(v + q * P);
+  for (int q = 0; q < 4; ++q)
+    store_quad<T>((T*)a.out + (out_row + frag_col_offset<T>(ch0 + 8 * q)), fmaxf(acc[4 * q + 0] + bias4[q].x, 0.f),
+                  fmaxf(acc[4 * q + 1] + bias4[q].y, 0.f), fmaxf(acc[4 * q + 2] + bias4[q].z, 0.f),
+                  fmaxf(acc[4 * q + 3] + bias4[q].w, 0.f));
 }
 
 struct ConvLayerArgs {
@@ -1707,12 +1703,12 @@ __global__ __launch_bounds__(256) void conv_layer_kernel(ConvLayerArgs a) {
       });
     }
   });
-  // the epilogue's lane = (pixel lane >> 1, 16 channels); its bias values are requested now
-  const int rr = lane >> 1, c16 = (lane & 1) * 16;
-  const int ch0 = ct * TILE + c16;
+  // the weights are the MFMA's row operand, so lane (r, h) ends up with pixel r and the runs of four channels
+  // 8 g + 4 h .. + 3 of its channel tile: its bias values are requested now
+  const int ch0 = ct * TILE + 4 * h;
   float4 bias4[4];
 #pragma unroll
-  for (int g = 0; g < 4; ++g) bias4[g] = *(const float4*)(a.bias + ch0 + 4 * g);
+  for (int g = 0; g < 4; ++g) bias4[g] = *(const float4*)(a.bias + ch0 + 8 * g);
 
   // input rows y0 - MID .. y0 + WG_ROWS - 1 -> LDS (rows outside the image and the pads are zero); the loads of
   // a batch are all issued before the first store so that their latencies overlap
@@ -1790,7 +1786,7 @@ __global__ __launch_bounds__(256) void conv_layer_kernel(ConvLayerArgs a) {
       constexpr int dyi = decltype(D)::value;                  // dy = dyi - MID reads input row j = o + dyi
       static_for<RW>([&](auto O) {
         constexpr int o = decltype(O)::value;
-        mfma_chunk<T>(af[o + dyi], wbuf[buf][dyi], acc[o]);
+        mfma_chunk<T>(wbuf[buf][dyi], af[o + dyi], acc[o]);   // (channels = rows of the result)
       });
       if constexpr (dyi == 0) {                                // first fragments of the next step's input
 #pragma unroll
@@ -1815,26 +1811,24 @@ __global__ __launch_bounds__(256) void conv_layer_kernel(ConvLayerArgs a) {
   run_steps(std::integral_constant<int, NDY>{}, std::integral_constant<int, 0>{}, 0, N_A);
   run_steps(std::integral_constant<int, MID>{}, std::integral_constant<int, N_A % 2>{}, N_A, N_IT);
   JM_TSTAMP(4, 0);
-  __syncthreads();                                        // the input rows are no longer needed
 
-  // epilogue through a wave-private LDS patch: lane = (pixel lane >> 1, 16 channels), 16-byte stores
-  constexpr int P = 16 / (int)sizeof(T);
-  float (*patch)[TILE + 1] = (float (*)[TILE + 1])((char*)conv_lds + wave * (TILE * (TILE + 1) * 4));
-  const float bias[16] = {bias4[0].x, bias4[0].y, bias4[0].z, bias4[0].w, bias4[1].x, bias4[1].y, bias4[1].z, bias4[1].w,
-                          bias4[2].x, bias4[2].y, bias4[2].z, bias4[2].w, bias4[3].x, bias4[3].y, bias4[3].z, bias4[3].w};
+  // epilogue: acc[o][4 g + c] = channel ch0 + 8 g + c of pixel r in output row o.  Four consecutive channels are
+  // half a 16-byte piece (bf16) or a whole one (fp32) of the fragment-major activations: stored straight from the
+  // registers, converted by the hardware (the first version turned every tile through an LDS patch to get
+  // 16-byte stores, which took longer than the stores saved).
+  uint32_t out_col[4];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) out_col[g] = frag_col_offset<T>(ch0 + 8 * g);
   static_for<RW>([&](auto O) {
     constexpr int o = decltype(O)::value;
     const int y = y0 + wrow + o;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) patch[8 * (e >> 2) + 4 * h + (e & 3)][r] = acc[o][e];
-    float v[16];
-#pragma unroll
-    for (int cc = 0; cc < 16; ++cc) v[cc] = patch[rr][c16 + cc] + bias[cc];
     if (y < a.H) {
-      const int pixel = ((n * a.H) + y) * 32 + rr;
+      const size_t out_row = frag_row_offset<T>(((n * a.H) + y) * 32 + r, KCH);
 #pragma unroll
-      for (int g = 0; g < 16 / P; ++g)
-        *(uint4*)((T*)a.out + frag_offset<T>(pixel, ch0 + g * P, KCH)) = Elem<T>::relu_piece(v + g * P);
+      for (int g = 0; g < 4; ++g)
+        store_quad<T>((T*)a.out + (out_row + out_col[g]), fmaxf(acc[o][4 * g + 0] + bias4[g].x, 0.f),
+                      fmaxf(acc[o][4 * g + 1] + bias4[g].y, 0.f), fmaxf(acc[o][4 * g + 2] + bias4[g].z, 0.f),
+                      fmaxf(acc[o][4 * g + 3] + bias4[g].w, 0.f));
     }
   });
   JM_TSTAMP(5, 1);
