@@ -229,3 +229,27 @@ def test_batches_around_the_tile_and_stop_test_thresholds(N):
     rows_equal = (x == x_small).all(axis=1)
     assert rows_equal.mean() > 0.99                      # (the two tile shapes sum in different orders: near-ties may flip)
     assert (it[rows_equal] == it_small[rows_equal]).all()
+
+
+def test_four_chains_of_large_sub_batches():
+    """8200 samples cut into four chains on their own streams: each chain runs the 128 x 128 tiles and its own
+    stand-alone stop test concurrently with the others.  Whole batch by the fixed-point certificate, pass counts
+    against the single-chain run."""
+    import dataclasses
+    import gpu_util
+    w = dataclasses.replace(S.workload("mid_bf16"), N=8200)
+    net = S.make_network(w, with_bias=True)
+    _, same = oracle_models(net)
+    noise = S.make_noise(w)
+    old = gpu_util.CHAINS, gpu_util.RETIRE_SPLIT
+    try:
+        out = []
+        for chains in (4, 1):
+            gpu_util.CHAINS, gpu_util.RETIRE_SPLIT = chains, None
+            with GpuModel(net) as g:
+                out.append(g.jacobi(noise))
+    finally:
+        gpu_util.CHAINS, gpu_util.RETIRE_SPLIT = old
+    (x4, it4), (x1, it1) = out
+    assert_sample_parity(same, noise, x4)
+    assert (x4 == x1).all() and (it4 == it1).all()
