@@ -181,8 +181,8 @@ struct made_model {
   bool prefix_cache = true;                   // made_set_option(MADE_OPT_PREFIX_CACHE)
   int big_batch = 1 << 30;                    // made_set_option(MADE_OPT_BIG_TILE_BATCH): 256 x 256 tiles from here on (off:
                                               // slower than 128 x 128 at every batch measured, up to 32768)
-  int mid_batch = 1280;                       // made_set_option(MADE_OPT_MID_TILE_BATCH): 128 x 128 tiles from here up to
-                                              // big_batch; measured crossover with the 32 x 32 tiles between 1024 and 1536
+  int mid_batch = 1536;                       // made_set_option(MADE_OPT_MID_TILE_BATCH): 128 x 128 tiles from here up to
+                                              // big_batch; measured crossover with the 32 x 32 tiles near 1536
   int n_chains = 1;                           // made_set_option(MADE_OPT_CHAINS)
   int retire_split = 2048;                    // made_set_option(MADE_OPT_RETIRE_SPLIT); +4 % at batch 2048, +9 % at 4096 over the fused tail
   int fused_categorical = 1;                  // made_set_option(MADE_OPT_FUSED_CATEGORICAL)

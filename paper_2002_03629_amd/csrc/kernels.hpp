@@ -121,10 +121,12 @@ constexpr int TILE = 32;   // output tile: 32 samples x 32 units per workgroup
 #define JM_NW 8
 #endif
 #ifndef JM_PD
-#define JM_PD 4
+#define JM_PD 2
 #endif
 constexpr int NW = JM_NW;  // waves per workgroup; they split the K range between them
-constexpr int PD = JM_PD;  // K chunks a wave keeps in flight (all their loads are issued before the first MFMA); <= 8
+constexpr int PD = JM_PD;  // K chunks a wave keeps in flight (all their loads are issued before the first MFMA); <= 8.
+                           // 2: ~110 registers, so two workgroups share a compute unit (4 needs ~170: one); equal at
+                           // batch 128 (one workgroup per unit anyway), +15-18 % at batches 512-1024
 static_assert(PD >= 1 && PD <= 8, "prefetch depth must be 1..8");
 constexpr int XCDS = 8;    // workgroup i is dispatched to XCD i % 8; each XCD has its own L2
 

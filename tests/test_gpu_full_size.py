@@ -208,10 +208,10 @@ def test_cfg2_batch_8192_stop_test_as_its_own_kernel():
         assert (ia[rows_equal] != io[rows_equal]).mean() < 1e-3     # (a near-tie in an intermediate pass costs a pass)
 
 
-@pytest.mark.parametrize("N", [1279, 1280, 1281, 2047, 2048, 2049, 2600])
+@pytest.mark.parametrize("N", [1535, 1536, 1537, 2047, 2048, 2049, 2600])
 def test_batches_around_the_tile_and_stop_test_thresholds(N):
     """Library defaults on batches just below, at and above the sizes where the layers move to the LDS-staged
-    128 x 128 tiles (1280) and the stop test becomes a kernel of its own (2048); late passes of the same call fall
+    128 x 128 tiles (1536) and the stop test becomes a kernel of its own (2048); late passes of the same call fall
     back below both.  Whole batch by the fixed-point certificate; pass counts against a run that stays on the
     32 x 32 tiles with the fused stop test."""
     import dataclasses
