@@ -22,6 +22,9 @@
  *     a few empty launches they enqueued ahead of that answer may still be draining when they
  *     return; sequential_sample and made_forward_logits only enqueue work.
  *   - one model must not be used from two host threads at once (it owns scratch memory).
+ *   - a *_sample call that waits for the device gives up after 30 s without an answer and returns MADE_ERR_HIP
+ *     with its kernels possibly still queued: synchronise the device before reusing that call's buffers; the
+ *     model then refuses every further call and made_free waits for the device before it releases anything.
  */
 #ifndef JACOBI_MADE_H
 #define JACOBI_MADE_H
@@ -119,6 +122,22 @@ int made_free(made_model* m);
  * Asynchronous on `stream`.
  */
 int made_forward_logits(made_model* m, const uint8_t* x, int32_t N, float* logits, void* stream);
+
+/*
+ * made_layer_activations -- inspection aid for tests: the activations h_l = ReLU((W_l * M_l) h_{l-1} + b_l) of one
+ * layer of the network of Section 5.3.1 (for the convolutional model: of one k x k layer) as the library holds
+ * them, i.e. after the rounding to bf16 of a MADE_BF16 model, widened exactly to fp32.  Feeding them to a reference
+ * implementation of layer l + 1 checks every layer on its own, without the compounding of rounding differences
+ * over the depth of the network.
+ *   x     : device uint8 [N, D] symbols; the whole network is evaluated on them first.  NULL (convolutional model
+ *           only, N at most the batch of that call): nothing is evaluated, the values the most recent sampling call
+ *           left in the model's per-layer buffers are returned.
+ *   layer : 0 .. L-1 (masked MLP) or 0 .. n_conv-1 (convolutional model).
+ *   out   : device fp32; masked MLP: [N, hidden[layer]] with the units in the caller's order; convolutional model:
+ *           [N, H, 32, F].
+ * Asynchronous on `stream`.  Models with real states are refused.
+ */
+int made_layer_activations(made_model* m, const uint8_t* x, int32_t N, int32_t layer, float* out, void* stream);
 
 /*
  * Noise (the input u of Eq. 1, fixed for the whole call; Appendix A.3):

@@ -71,6 +71,7 @@ struct Layer {
   int* tile_kend = nullptr;      // device, [n_tiles]
   std::vector<int> h_tile_kend;  // host copy
   int* cnt_lt = nullptr;         // device, hidden layers only: [D + 2] prefix lengths by degree
+  int* slot_unit = nullptr;      // device, hidden layers only: [out_dim] the caller's index of the unit stored in slot j
 };
 
 // A chain is a contiguous range of the batch's samples that is iterated on its own HIP stream.  Samples are
@@ -150,6 +151,8 @@ struct ConvNet {
 
 struct made_model {
   int arch = 0;                               // 0 masked MLP, 1 masked convolutional network
+  bool poisoned = false;                      // a call gave up waiting for the device with its kernels still queued:
+                                              // every later call is refused, made_free waits for the device first
   bool real = false;                          // MLP with real states and logistic conditionals (C = 2 rows per position)
   bool onehot = false;                        // categorical symbols enter as one-hot vectors: the first layer is a sum of
                                               // one weight row per position (layers[0].W is [D][C][out_pad], see made_init)
@@ -335,6 +338,7 @@ extern "C" int made_free(made_model* m) {
     if (l.bias) (void)hipFree(l.bias);
     if (l.tile_kend) (void)hipFree(l.tile_kend);
     if (l.cnt_lt) (void)hipFree(l.cnt_lt);
+    if (l.slot_unit) (void)hipFree(l.slot_unit);
   }
   free_workspace(m->ws);
   if (m->jgs_xv) (void)hipFree(m->jgs_xv);
@@ -606,6 +610,8 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
         he = hipMalloc((void**)&ly.cnt_lt, m->cnt_lt[l].size() * sizeof(int));
         if (he == hipSuccess)
           he = hipMemcpy(ly.cnt_lt, m->cnt_lt[l].data(), m->cnt_lt[l].size() * sizeof(int), hipMemcpyHostToDevice);
+        if (he == hipSuccess) he = hipMalloc((void**)&ly.slot_unit, perm.size() * sizeof(int));
+        if (he == hipSuccess) he = hipMemcpy(ly.slot_unit, perm.data(), perm.size() * sizeof(int), hipMemcpyHostToDevice);
       }
       if (he != hipSuccess)
         rc = fail(he == hipErrorOutOfMemory ? MADE_ERR_NOMEM : MADE_ERR_HIP, "made_init: layer %d upload failed: %s", l,
@@ -957,15 +963,22 @@ static bool hidden_by_position(const made_model* m, const RowSet& rs, bool limit
          rs.n_rows < std::min(m->big_batch, m->mid_batch);
 }
 
+// Where a forward pass keeps the network input and the hidden activations: the model's workspace (NULL), or
+// buffers of the caller's choosing (the entry point that must not allocate passes pieces of a static array).
+struct ActBuffers {
+  void* enc;
+  void* act[64];         // (made_init admits at most 64 hidden layers)
+};
+
 static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, int in_limit0, hipStream_t s,
-                      const int* unit_first = nullptr, bool by_pos = false) {
+                      const int* unit_first = nullptr, bool by_pos = false, const ActBuffers* buf = nullptr) {
   const int row_tiles = (rs.n_rows + TILE - 1) / TILE;
   const int kc = chunk_elems(m);
   int in_limit = in_limit0;
   for (int l = 0; l < m->L; ++l) {
     const Layer& ly = m->layers[l];
-    LayerArgs a = base_args(m, l, l == 0 ? m->ws.enc : m->ws.act[l - 1], rs);
-    a.out = m->ws.act[l];
+    LayerArgs a = base_args(m, l, l == 0 ? (buf ? buf->enc : m->ws.enc) : (buf ? buf->act[l - 1] : m->ws.act[l - 1]), rs);
+    a.out = buf ? buf->act[l] : m->ws.act[l];
     a.out_chunks = m->layers[l + 1].k_chunks;
     int tiles = ly.n_tiles;
     if (unit_limit && unit_limit[l] >= 0) tiles = std::min(tiles, (unit_limit[l] + TILE - 1) / TILE);
@@ -1247,7 +1260,8 @@ static int run_conv_pass(made_model* m, int N, const SampleIO& io, bool first_pa
 }
 
 static int launch_init_state(made_model* m, const uint8_t* x_init, uint8_t* x, int N, hipStream_t s,
-                             const CallReset* reset_in = nullptr) {
+                             const CallReset* reset_in = nullptr, void* enc_buf = nullptr) {
+  void* const enc = enc_buf ? enc_buf : m->ws.enc;
   CallReset reset;
   memset(&reset, 0, sizeof reset);
   if (reset_in) reset = *reset_in;
@@ -1268,19 +1282,19 @@ static int launch_init_state(made_model* m, const uint8_t* x_init, uint8_t* x, i
   if (m->real) {
     if (m->dtype == MADE_BF16)
       hipLaunchKernelGGL((init_state_real_kernel<bf16_t>), dim3(blocks), dim3(256), 0, s, (const float*)x_init, (float*)x,
-                         (bf16_t*)m->ws.enc, m->layers[0].k_chunks, N, m->D, reset);
+                         (bf16_t*)enc, m->layers[0].k_chunks, N, m->D, reset);
     else
       hipLaunchKernelGGL((init_state_real_kernel<float>), dim3(blocks), dim3(256), 0, s, (const float*)x_init, (float*)x,
-                         (float*)m->ws.enc, m->layers[0].k_chunks, N, m->D, reset);
+                         (float*)enc, m->layers[0].k_chunks, N, m->D, reset);
     m->stats[2]++;
     HIP_TRY(hipGetLastError());
     return MADE_OK;
   }
   if (m->dtype == MADE_BF16)
-    hipLaunchKernelGGL((init_state_kernel<bf16_t>), dim3(blocks), dim3(256), 0, s, x_init, x, (bf16_t*)m->ws.enc,
+    hipLaunchKernelGGL((init_state_kernel<bf16_t>), dim3(blocks), dim3(256), 0, s, x_init, x, (bf16_t*)enc,
                        m->layers[0].k_chunks, N, m->D, m->C, reset);
   else
-    hipLaunchKernelGGL((init_state_kernel<float>), dim3(blocks), dim3(256), 0, s, x_init, x, (float*)m->ws.enc,
+    hipLaunchKernelGGL((init_state_kernel<float>), dim3(blocks), dim3(256), 0, s, x_init, x, (float*)enc,
                        m->layers[0].k_chunks, N, m->D, m->C, reset);
   m->stats[2]++;
   HIP_TRY(hipGetLastError());
@@ -1296,6 +1310,9 @@ static int check_call(made_model* m, const void* noise, int32_t N, const void* x
   if (N < 0) return fail(MADE_ERR_ARG, "%s: N=%d is negative", who, N);
   if (N > (1 << 22)) return fail(MADE_ERR_ARG, "%s: N=%d exceeds 2^22", who, N);
   if (N > 0 && (!noise || !x_out)) return fail(MADE_ERR_ARG, "%s: NULL noise or output pointer", who);
+  if (m->poisoned)
+    return fail(MADE_ERR_HIP, "%s: an earlier call on this model timed out waiting for the device; synchronise the "
+                              "device, release the model with made_free and build a new one", who);
   HIP_TRY(hipSetDevice(m->device));
   return MADE_OK;
 }
@@ -1346,6 +1363,62 @@ extern "C" int made_forward_logits(made_model* m, const uint8_t* x, int32_t N, f
   a.ldo = m->D * m->C;
   launch_layer<EPI_LOGITS>(m, m->L, a, m->layers[m->L].n_tiles, (N + TILE - 1) / TILE, s);
   m->profiling = was_profiling;
+  HIP_TRY(hipGetLastError());
+  return MADE_OK;
+}
+
+extern "C" int made_layer_activations(made_model* m, const uint8_t* x, int32_t N, int32_t layer, float* out,
+                                      void* stream) {
+  if (!m) return fail(MADE_ERR_ARG, "made_layer_activations: model is NULL");
+  if (m->real) return fail(MADE_ERR_ARG, "made_layer_activations: the model has real states");
+  if (N < 0 || N > (1 << 22)) return fail(MADE_ERR_ARG, "made_layer_activations: N=%d out of range [0, 2^22]", N);
+  const int n_act = m->arch == 1 ? m->conv.n_conv : m->L;
+  if (layer < 0 || layer >= n_act)
+    return fail(MADE_ERR_ARG, "made_layer_activations: layer=%d, the model has %d layers with activations", layer, n_act);
+  if (N > 0 && !out) return fail(MADE_ERR_ARG, "made_layer_activations: out is NULL");
+  if (!x && m->arch != 1)
+    return fail(MADE_ERR_ARG, "made_layer_activations: x is NULL (only the convolutional model keeps its activations)");
+  HIP_TRY(hipSetDevice(m->device));
+  if (N == 0) return MADE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  const bool was_profiling = m->profiling;
+  m->profiling = false;
+  TRY(settle(m, s));
+  if (!x && N > m->ws.N_cap)
+    return fail(MADE_ERR_ARG, "made_layer_activations: no call on %d or more images has run on this model yet", N);
+  TRY(ensure_workspace(m, N, false));
+  const void* act = nullptr;
+  int rows = 0, width = 0, k_chunks = 0;
+  const int* slot_unit = nullptr;
+  if (m->arch == 1) {
+    ConvNet& cv = m->conv;
+    if (x) {
+      const void* last = nullptr;
+      launch_conv_trunk(m, x, N, nullptr, cv.H - 1, s, &last);
+    }
+    act = cv.act[layer];
+    rows = N * cv.H * 32;
+    width = cv.F;
+    k_chunks = cv.F / chunk_elems(m);
+  } else {
+    TRY(launch_init_state(m, x, nullptr, N, s));
+    RowSet rs{nullptr, nullptr, N, x};
+    TRY(run_hidden(m, rs, nullptr, -1, s));
+    act = m->ws.act[layer];
+    rows = N;
+    width = m->layers[layer].out_dim;
+    k_chunks = m->layers[layer + 1].k_chunks;
+    slot_unit = m->layers[layer].slot_unit;
+  }
+  m->profiling = was_profiling;
+  const size_t total = (size_t)rows * width;
+  const int blocks = (int)std::min<size_t>((total + 255) / 256, 16384);
+  if (m->dtype == MADE_BF16)
+    hipLaunchKernelGGL(unpack_activations_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t*)act, k_chunks,
+                       slot_unit, rows, width, out);
+  else
+    hipLaunchKernelGGL(unpack_activations_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float*)act, k_chunks,
+                       slot_unit, rows, width, out);
   HIP_TRY(hipGetLastError());
   return MADE_OK;
 }
@@ -1453,6 +1526,17 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
   }
   c.k_enq = k;
   return MADE_OK;
+}
+
+// The device has not reported a pass for 30 s.  Passes that write the caller's buffers and the model's scratch
+// memory are still queued (on `s` and possibly on the chains' own streams), so the model is marked: later calls
+// are refused, and made_free / any reallocation waits for the whole device before it frees what they use.
+static int give_up_waiting(made_model* m, hipStream_t s) {
+  m->ws.pending = true;
+  m->ws.pending_stream = s;
+  m->poisoned = true;
+  return fail(MADE_ERR_HIP, "device did not report the stop test of a pass within 30 s; kernels of this call are "
+                            "still queued: synchronise the device before reusing the call's buffers");
 }
 
 // Run the block list on every chain.  Each chain works through the blocks on its own stream; the host keeps
@@ -1563,7 +1647,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
       last_progress = std::chrono::steady_clock::now();
     } else if ((++spins & 0xfff) == 0 &&
                std::chrono::duration<double>(std::chrono::steady_clock::now() - last_progress).count() > 30.0) {
-      return fail(MADE_ERR_HIP, "device did not report the stop test of a pass within 30 s");
+      return give_up_waiting(m, s);
     }
   }
   // Pass counts went straight to iters_out and the flags come through the chains' pinned words, so nothing is
@@ -1590,7 +1674,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
         while (c.h_pin[c.pin_base + j] < 0) {
           if ((++polls & 0xfff) == 0 &&
               std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() > 30.0)
-            return fail(MADE_ERR_HIP, "device did not report the stop test of a pass within 30 s");
+            return give_up_waiting(m, s);
         }
         if (c.h_pin[c.pin_base + j] == 0) drained = true;
       }
@@ -2044,16 +2128,7 @@ extern "C" int jacobi_gs_sample(made_model* m, const float* noise, int32_t N, co
 }
 
 #ifdef JM_TRACE
-// development aid (only in builds with -DJM_TRACE): read and clear the barrier time stamps
-extern "C" int jm_debug_read_trace(unsigned long long* out) {
-  if (hipMemcpyFromSymbol(out, HIP_SYMBOL(jm::g_trace), sizeof(unsigned long long) * 64 * 256 * 5) != hipSuccess) return -1;
-  static std::vector<unsigned long long> zeros(64 * 256 * 5, 0);
-  (void)hipMemcpyToSymbol(HIP_SYMBOL(jm::g_trace), zeros.data(), sizeof(unsigned long long) * 64 * 256 * 5);
-  return 0;
-}
-extern "C" int jm_debug_read_tile_trace(unsigned long long* out) {
-  return hipMemcpyFromSymbol(out, HIP_SYMBOL(jm::g_tile_trace), sizeof(unsigned long long) * 1024 * 8) == hipSuccess ? 0 : -1;
-}
+#include "dev_trace_entry.hpp"   // development builds only: entry points that read the time stamps back
 #endif
 
 // ------------------------------------------------------------------------------------------------

@@ -243,16 +243,23 @@ __device__ __forceinline__ void mfma_chunk<float>(const uint4 (&a)[4], const uin
   }
 }
 
-#ifdef JM_TRACE
-__device__ unsigned long long g_tile_trace[1024 * 8];
-#define JM_TSTAMP(i, drain)                                                           \
-  do {                                                                                \
-    if (drain) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");            \
-    if (threadIdx.x == 0 && blockIdx.x < 1024) g_tile_trace[blockIdx.x * 8 + (i)] = wall_clock64(); \
-  } while (0)
-#else
-#define JM_TSTAMP(i, drain) do { } while (0)
-#endif
+// JM_TSTAMP / JM_STAMP: time-stamp hooks of development builds (-DJM_TRACE); they expand to nothing otherwise.
+#include "dev_trace.hpp"
+
+// What the host learns of a pass, written by ONE thread: first the not-converged flag (device copy and its mirror
+// in pinned host memory), then the new active count -- the word the host polls.  The host reads the flag mirror as
+// soon as it has seen the count of a call's last pass, so the flag must be visible first: the count is stored with
+// release semantics in that (rare) case.  Otherwise the host reads nothing but the count before it synchronises
+// the stream, and a relaxed store will do.
+__device__ __forceinline__ void publish_pass_result(const RetireArgs& r, bool flagged, int new_n) {
+  if (flagged) {
+    __hip_atomic_fetch_or(r.flags, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (r.host_flags) __hip_atomic_store(r.host_flags, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    __hip_atomic_store(r.host_slot, new_n, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+  } else {
+    __hip_atomic_store(r.host_slot, new_n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  }
+}
 
 // Stop test and compaction (the forward-difference test of Algorithm 1 with tolerance 0, per
 // sample): every active sample took one more pass; those whose symbols changed stay active, in
@@ -263,10 +270,14 @@ __device__ unsigned long long g_tile_trace[1024 * 8];
 __device__ __forceinline__ void retire_tail(const RetireArgs& r, int pre_n, int pre_row, int pre_iters) {
   __shared__ int wave_total[NW];
   __shared__ int base_s;
+  __shared__ int flagged_s;          // some sample was still changing in the last allowed pass
   const int nthreads = blockDim.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = nthreads >> 6;
   const int n_rows = pre_n;
-  if (threadIdx.x == 0) base_s = 0;
+  if (threadIdx.x == 0) {
+    base_s = 0;
+    flagged_s = 0;
+  }
   __syncthreads();
   if (n_rows <= nthreads) {
     // ---- one row per thread (batches up to a workgroup's size: the latency-critical case)
@@ -280,10 +291,7 @@ __device__ __forceinline__ void retire_tail(const RetireArgs& r, int pre_n, int 
       r.changed[(size_t)sample * CHG] = 0;
       r.iters[sample] = pre_iters + 1;
       keep = (c > 0) && !r.last_pass;
-      if (c > 0 && r.last_pass && r.flag_unconverged) {
-        atomicOr(r.flags, 1);
-        if (r.host_flags) __hip_atomic_store(r.host_flags, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-      }
+      if (c > 0 && r.last_pass && r.flag_unconverged) flagged_s = 1;   // (every writer stores 1)
     }
     const unsigned long long mask = __ballot(keep);
     const int before = __popcll(mask & ((1ull << lane) - 1ull));
@@ -359,10 +367,7 @@ __device__ __forceinline__ void retire_tail(const RetireArgs& r, int pre_n, int 
       base += tot;
       __syncthreads();                                              // wave_total is reused by the next round
     }
-    if (unconverged) {
-      atomicOr(r.flags, 1);
-      if (r.host_flags) __hip_atomic_store(r.host_flags, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    }
+    if (unconverged) flagged_s = 1;
     if (threadIdx.x == 0) base_s = base;
     __syncthreads();
   }
@@ -376,8 +381,7 @@ __device__ __forceinline__ void retire_tail(const RetireArgs& r, int pre_n, int 
   if (threadIdx.x == 0) {
     *r.n_out = base_s;
     *r.done_ctr = 0;
-    // the host reads nothing but this word before it synchronises the stream: no release needed
-    __hip_atomic_store(r.host_slot, base_s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    publish_pass_result(r, flagged_s != 0, base_s);
   }
 }
 
@@ -438,10 +442,14 @@ __global__ __launch_bounds__(256) void retire_kernel(RetireArgs r) {
 #pragma unroll
   for (int q = 0; q < Q; ++q)
     if (pos[q] >= 0) r.rows_out[off + pos[q]] = sample[q];
+  // A thread that saw a sample still changing in the last allowed pass sets the device flag and waits for the
+  // atomic's result; the barrier then puts every such update of this workgroup before its arrival below, so the
+  // workgroup that arrives last finds the flag of all of them.
   if (unconverged) {
-    atomicOr(r.flags, 1);
-    if (r.host_flags) __hip_atomic_store(r.host_flags, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    const int old = __hip_atomic_fetch_or(r.flags, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("" ::"v"(old));
   }
+  __syncthreads();
   // (thread 0 has its cursor atomic's result, so the atomic below is performed after it; the list entries
   // themselves are read by the next kernel only)
   if (threadIdx.x == 0)
@@ -459,7 +467,8 @@ __global__ __launch_bounds__(256) void retire_kernel(RetireArgs r) {
     *r.n_out = new_n;
     __hip_atomic_store(cursor, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __hip_atomic_store(r.done_ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(r.host_slot, new_n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    const int fl = __hip_atomic_load(r.flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    publish_pass_result(r, (fl & 1) != 0 && r.last_pass && r.flag_unconverged, new_n);
   }
 }
 
@@ -489,10 +498,7 @@ __device__ __forceinline__ void finish_pass(const RetireArgs& r, int total_workg
   JM_TSTAMP(7, 0);
   if (is_last_s) {
     retire_tail(r, pre_n, pre_row, pre_iters);
-#ifdef JM_TRACE
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-    if (threadIdx.x == 0) g_tile_trace[1023 * 8] = wall_clock64();
-#endif
+    JM_TRACE_TAIL_DONE();
   }
 }
 
@@ -908,9 +914,7 @@ __global__ __launch_bounds__(256, W == 2 ? 2 : 1) void masked_layer_big_kernel(L
       multiply_half(cur);
     };
     JM_TSTAMP(EPI == EPI_RELU ? 0 : 3, 0);
-#ifdef JM_TRACE
-    if (threadIdx.x == 0 && blockIdx.x < 1024) g_tile_trace[blockIdx.x * 8 + (EPI == EPI_RELU ? 6 : 7)] = n_chunks;
-#endif
+    JM_TRACE_VALUE(EPI == EPI_RELU ? 6 : 7, n_chunks);
     if (n_half > 0) {
       issue_half(0, big_s0);
       issue_half(1, big_s1);
@@ -1130,18 +1134,6 @@ struct PersistArgs {
 // check, so the grid always drains.
 #ifndef JM_SLEEP
 #define JM_SLEEP 1
-#endif
-#ifdef JM_TRACE
-// development aid: per workgroup and barrier, the times of arrival / after release fence / after the
-// arrival atomic / after the wait / after the acquire fence
-__device__ unsigned long long g_trace[64 * 256 * 5];
-#define JM_STAMP(tag)                                                                            \
-  do {                                                                                           \
-    const unsigned b_ = epoch / gridDim.x - 1;                                                   \
-    if (b_ < 64 && blockIdx.x < 256) g_trace[(b_ * 256 + blockIdx.x) * 5 + (tag)-1] = wall_clock64(); \
-  } while (0)
-#else
-#define JM_STAMP(tag) do { } while (0)
 #endif
 
 __device__ __forceinline__ bool grid_barrier(unsigned* bar, unsigned& epoch, int* flags, unsigned spin_limit) {
@@ -2107,6 +2099,21 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
 __global__ void copy_symbols_kernel(const uint8_t* x_init, uint8_t* x, size_t total) {
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x)
     x[i] = x_init ? x_init[i] : 0;
+}
+
+// Activations of one layer from the fragment-major buffer to a plain float [rows, width] array; slot_unit (or NULL)
+// maps the storage slot of a unit to the column it is written to.  (Inspection only: no sampling path uses it.)
+template <typename T>
+__global__ void unpack_activations_kernel(const T* act, int k_chunks, const int* slot_unit, int rows, int width,
+                                          float* out) {
+  const size_t total = (size_t)rows * width;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const int row = (int)(i / width), j = (int)(i % width);
+    const T v = act[frag_offset<T>(row, j, k_chunks)];
+    float f;
+    if constexpr (std::is_same<T, float>::value) f = v; else f = bf16_to_f32(v);
+    out[(size_t)row * width + (slot_unit ? slot_unit[j] : j)] = f;
+  }
 }
 
 // Gumbel-max draw for categorical positions from logits held in memory:

@@ -83,19 +83,6 @@ struct ResCtx {
   int lane_off;
 };
 
-#ifdef JM_TRACE
-// development aid: wave JM_RES_TRACE_WAVE of workgroup 0 stamps the phases of its first 128 passes
-#ifndef JM_RES_TRACE_WAVE
-#define JM_RES_TRACE_WAVE 0
-#endif
-#define RES_STAMP(pass, i)                                                                              \
-  do {                                                                                                  \
-    if (blockIdx.x == 0 && threadIdx.x == JM_RES_TRACE_WAVE * 64 && (pass) < 128)                        \
-      g_tile_trace[(pass) * 8 + (i)] = wall_clock64();                                                  \
-  } while (0)
-#else
-#define RES_STAMP(pass, i) do { } while (0)
-#endif
 
 __device__ __forceinline__ int snake_j(int m, int wave) { return (m & 1) ? (m + 1) * RES_W - 1 - wave : m * RES_W + wave; }
 

@@ -1,6 +1,5 @@
 """Helpers shared by the GPU parity tests (test code; may import both the binding and the oracle)."""
 import dataclasses
-import os
 import time
 
 import numpy as np
@@ -10,19 +9,14 @@ from oracle import made_oracle as O
 from paper_2002_03629_amd import binding as B
 
 MARGIN = 1e-3          # positions whose oracle decision margin is below this are exempt from bit-exactness
+CLEAR_FLOOR = 0.25     # iteration counts are compared for samples none of whose decisions came within MARGIN of a
+                       # tie; on the reduced workloads at least this share of the batch must be such samples
 LOGIT_TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 
 def progress(msg):
-    """Long tests leave a trace outside pytest's capture so that a watcher sees they are alive."""
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    d = os.path.join(root, "gpurun_out")
-    try:
-        os.makedirs(d, exist_ok=True)
-        with open(os.path.join(d, "test_progress.log"), "a") as f:
-            f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
-    except OSError:
-        pass
+    """Long tests say where they are (visible with `pytest -s`; the output of a failing test is shown anyway)."""
+    print(f"[{time.strftime('%H:%M:%S')}] {msg}", flush=True)
 
 
 def dev(a):
@@ -98,6 +92,14 @@ class GpuModel:
         B.jacobi_gs_sample(self.h, dev(noise), N, None if x_init is None else dev(x_init), block, max_iters, x, it)
         return x.cpu().numpy(), it.cpu().numpy()
 
+    def activations(self, x, layer):
+        """Hidden layer `layer` evaluated on symbols x, as the library holds it, [N, width] float32."""
+        N = x.shape[0]
+        out = torch.empty((N, self.net.hidden[layer]), dtype=torch.float32, device="cuda")
+        B.made_layer_activations(self.h, dev(x), N, layer, out)
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+
     def sequential(self, noise, mode):
         N = noise.shape[0]
         x = torch.empty((N, self.net.D), dtype=torch.uint8, device="cuda")
@@ -138,3 +140,51 @@ def assert_sample_parity(model_same, noise, x_gpu, x_oracle=None, margin_oracle=
             clear = margin_oracle.min(axis=1) >= MARGIN
             assert same[clear].all(), "a sample with every margin >= 1e-3 differs from the sequential oracle"
     return exempt, frac
+
+
+def assert_counts_match(it, it_ref, min_margin, floor=CLEAR_FLOOR):
+    """Iteration counts against the oracle's for every sample whose decisions all stayed clear of a tie, and
+    there must be enough such samples for the comparison to mean something."""
+    clear = min_margin >= MARGIN
+    assert clear.mean() >= floor, f"only {clear.mean():.2f} of the samples have all margins >= {MARGIN}"
+    assert (it[clear] == it_ref[clear]).all(), (it, it_ref)
+    return float(clear.mean())
+
+
+def mlp_layer_certificate(g, model_same, x, noise=None):
+    """Every layer of the masked MLP on its own (see layer_certificate.py): the oracle's layer l + 1 applied to
+    the activations the library produced for layer l must reproduce the library's layer l + 1 -- bit for bit
+    except within the fp32 accumulation error of a bf16 rounding boundary (bf16 model), resp. within that error
+    (fp32 model) -- and the logits must follow from the library's last hidden layer within the accumulation
+    error.  With `noise`, x is also checked to be the oracle's decision from those logits wherever its margin is
+    at least MARGIN.  Prints the worst accumulation error seen in units of 2^-24 sum|a_i w_i|."""
+    import layer_certificate as LC
+    net = g.net
+    L = len(net.hidden)
+    h = O.encode(x, model_same.C, model_same.onehot)
+    rounded = model_same.act_round == "bf16"
+    worst = 0.0
+    for l in range(L + 1):
+        pre = O.affine(h, model_same.WM[l], model_same.b[l])
+        mag = O.affine(np.abs(h), np.abs(model_same.WM[l]), np.abs(model_same.b[l]))
+        err = LC.sum_error(mag)
+        if l == L:
+            got = g.logits(x).reshape(x.shape[0], -1).astype(np.float64)
+            ok = LC.certify_plain(pre, err, got)
+            assert ok.all(), f"logits: {int((~ok).sum())} of {ok.size} outside the accumulation error"
+            worst = max(worst, float((np.abs(got - pre) / (LC.U32 * np.maximum(mag, 1e-30))).max()))
+            if noise is not None:
+                fx, margin = O.decide(pre.reshape(x.shape[0], model_same.D, model_same.C), noise, model_same.C)
+                assert not ((fx != x) & (margin >= MARGIN)).any()
+            break
+        got = g.activations(x, l).astype(np.float64)
+        if rounded:
+            ok, exact, near = LC.certify_rounded(pre, err, got)
+            assert ok.all(), LC.summarize(f"hidden layer {l}", ok, exact, near)
+            assert exact.mean() > 0.95, LC.summarize(f"hidden layer {l}", ok, exact, near)
+        else:
+            ok = LC.certify_plain(np.maximum(pre, 0.0), err, got)
+            assert ok.all(), f"hidden layer {l}: {int((~ok).sum())} of {ok.size} outside the accumulation error"
+            worst = max(worst, float((np.abs(got - np.maximum(pre, 0.0)) / (LC.U32 * np.maximum(mag, 1e-30))).max()))
+        h = got
+    return worst

@@ -9,6 +9,7 @@ from oracle import conv_oracle as CO
 from paper_2002_03629_amd import binding as B
 from paper_2002_03629_amd import synth as S
 
+import layer_certificate as LC
 from gpu_util import LOGIT_TOL, MARGIN, assert_logits_close, dev, progress
 
 pytestmark = pytest.mark.gpu
@@ -47,6 +48,15 @@ class ConvGpu:
         torch.cuda.synchronize()
         return out.cpu().numpy()
 
+    def activations(self, x, layer, N=None):
+        """k x k layer `layer` as the library holds it, [N, H, 32, F] float32: evaluated on symbols x, or (x = None)
+        whatever the most recent sampling call left in the model's per-layer buffers."""
+        N = x.shape[0] if x is not None else N
+        out = torch.empty((N, self.net.H, 32, self.net.F), dtype=torch.float32, device="cuda")
+        B.made_layer_activations(self.h, None if x is None else dev(x), N, layer, out)
+        torch.cuda.synchronize()
+        return out.cpu().numpy()
+
     def run(self, what, noise, *args, x_init=None):
         N = noise.shape[0]
         x = torch.empty((N, self.net.D), dtype=torch.uint8, device="cuda")
@@ -59,6 +69,52 @@ class ConvGpu:
         else:
             B.sequential_sample(self.h, dev(noise), N, args[0], x)
         return x.cpu().numpy(), it.cpu().numpy()
+
+
+def conv_layer_certificate(g, same, x, noise, from_buffers=False, label=""):
+    """Every kernel of the convolutional model on its own (see layer_certificate.py).  For l = 1 .. n_conv the
+    oracle's layer l applied to the activations the library holds for layer l - 1 must reproduce the library's
+    layer l: bit for bit except within the fp32 accumulation error of a bf16 rounding boundary, where the
+    neighbouring bf16 value is accepted (fp32 models: within the accumulation error).  The head's logits must follow
+    from the library's last layer within the accumulation error, and every symbol of x must be the oracle's
+    Gumbel-max decision from those logits unless its margin is below MARGIN -- the parity bar, applied to each
+    kernel separately instead of to the composition of nine of them.
+    from_buffers: take the activations a sampling call left behind (they must equal a fresh evaluation on x)."""
+    net = g.net
+    N = x.shape[0]
+    n_conv = len(same.WM) - 1
+    rounded = same.act_round == "bf16"
+    a = (x.astype(np.float64).reshape(N, net.H, net.W, 3) - 128.0) / 128.0
+    stats = []
+    # (read what the sampling call left behind BEFORE any fresh evaluation overwrites the buffers)
+    kept = [g.activations(None, l, N) for l in range(n_conv)] if from_buffers else None
+    for l in range(n_conv):
+        got = g.activations(x, l).astype(np.float64)
+        if from_buffers:
+            assert (kept[l] == got).all(), f"{label} layer {l}: the buffers a sampling call left differ from a fresh evaluation"
+        pre = CO.conv_layer(a, same.WM[l], same.b[l])
+        err = LC.sum_error(CO.conv_layer(np.abs(a), np.abs(same.WM[l]), np.abs(same.b[l])))
+        if rounded:
+            ok, exact, near = LC.certify_rounded(pre, err, got)
+            assert ok.all(), LC.summarize(f"{label} layer {l}", ok, exact, near)
+            assert exact.mean() > 0.95, LC.summarize(f"{label} layer {l}", ok, exact, near)
+            stats.append((float(exact.mean()), float(near.mean())))
+        else:
+            ok = LC.certify_plain(np.maximum(pre, 0.0), err, got)
+            assert ok.all(), f"{label} layer {l}: {int((~ok).sum())} of {ok.size} outside the accumulation error"
+        a = got
+    z_ref = CO.conv_layer(a, same.WM[-1], same.b[-1])
+    mag = CO.conv_layer(np.abs(a), np.abs(same.WM[-1]), np.abs(same.b[-1]))
+    z = g.logits(x).astype(np.float64).reshape(z_ref.shape)
+    ok = LC.certify_plain(z_ref, LC.sum_error(mag), z)
+    assert ok.all(), f"{label} head: {int((~ok).sum())} of {ok.size} logits outside the accumulation error"
+    worst = float((np.abs(z - z_ref) / (LC.U32 * np.maximum(mag, 1e-30))).max())
+    fx, margin = CO.decide(z_ref.reshape(N, same.D, same.C), noise, same.C)
+    wrong = (fx != x) & (margin >= MARGIN)
+    assert not wrong.any(), f"{label}: {int(wrong.sum())} states are not the oracle's decision at margin >= {MARGIN}"
+    return {"exempt_states": int((fx != x).sum()), "worst_logit_error_in_u_sum_abs": worst,
+            "bit_identical_per_layer": [round(e, 5) for e, _ in stats],
+            "near_boundary_per_layer": [round(n, 5) for _, n in stats]}
 
 
 @pytest.mark.parametrize("name", ["small_conv", "small_conv_f32"])
@@ -90,9 +146,13 @@ def test_conv_parity(name):
             xq, _ = g.run("seq", noise, mode)
             certify(same, noise, xq, xs, margins)
         # Jacobi only recomputes the image rows below the first symbol that changed in the pass before
-        g.run("jacobi", noise)
+        xj, _ = g.run("jacobi", noise)
         st = B.made_last_stats(g.h)
         assert 0 < st["conv_rows"] <= st["passes"] * w.N * net.H
+        if net.H > 2:                                    # (with two rows nothing is ever final before the last pass)
+            assert st["conv_rows"] < st["passes"] * w.N * net.H
+        # every kernel on its own, on the activations the call left in the per-layer buffers
+        print(conv_layer_certificate(g, same, xj, noise, from_buffers=True, label=name))
         with pytest.raises(B.MadeError) as e:
             g.run("jacobi", noise, 1)
         assert e.value.code == B.MADE_ERR_NOT_CONVERGED
@@ -119,23 +179,20 @@ def test_cfg5_shape_f32_certificate():
         print(f"cfg5 shape fp32: passes {it}, {int((fx != x).sum())} states differ (all with margin < {MARGIN})")
 
 
-@pytest.mark.timeout(900)
+@pytest.mark.timeout(1500)
 def test_cfg5_full_size_certificate():
-    """cfg5 as benchmarked: bf16 weights and activations, batch 32.  A sequential oracle run would be 3072 network
-    passes, so the batch is certified by one oracle pass at the GPU's result.
+    """cfg5 as benchmarked: bf16 weights and activations, batch 32, Jacobi and GS-Jacobi (blocks of 4 / 8 / 16 image
+    rows).  A sequential oracle run would be 3072 network passes per image, so the results are certified at the
+    library's own output.
 
-    Tolerances.  Every layer rounds its activations to bf16 (relative step 2^-8).  An activation that lies next
-    to a rounding boundary rounds the other way when the fp32 sum is taken in another order than the oracle's
-    fp64 sum, and every such one-step difference moves a share of the next layer's activations across their own
-    boundaries: after eight layers about one activation in six differs by one step (the same happens between
-    two CPU evaluations that differ only in summation order).  The logits of the two sides therefore differ by
-    rounding noise of the size the rounding itself introduces: relative rms 2^-9/sqrt(3) per layer, summed in
-    quadrature over 8 layers = 3.2e-3 of rms; the test allows 1.5 x that in the rms norm and 5e-2 of rms at the
-    worst of the 25 M elements.  Decisions: two logit vectors within eps of each other can only pick different
-    classes where the best two perturbed logits are within 2 eps, so a differing state must have an oracle
-    margin below 2 * 5e-2 * rms, differing states must be rare (< 0.5 %), and -- the exact part -- every state
-    is the argmax of the GPU's own logits, i.e. the result is the fixed point (= sequential sample) of the
-    network as the GPU evaluates it."""
+    Grading.  Two correct evaluations of this network disagree END TO END by far more than the parity bar's
+    margin: every layer rounds to bf16, a value next to a rounding boundary rounds the other way under another
+    summation order, and each such flip perturbs the next layer (tests/test_bf16_cascade.py shows it between two
+    CPU evaluations).  The bar is therefore applied LAYER BY LAYER (conv_layer_certificate): each of the nine
+    kernels, fed the library's own input, must reproduce the oracle's layer bit for bit except within the fp32
+    accumulation error of a rounding boundary, the logits must follow from the last layer within that error, and
+    every drawn state must be the oracle's decision from those logits unless its margin is below 1e-3.  The
+    end-to-end figures are kept as a secondary, looser check in the rms norm and are printed."""
     w = S.conv_workload("cfg5")
     progress("cfg5: drawing network and noise")
     net = S.make_conv_network(w)
@@ -145,27 +202,46 @@ def test_cfg5_full_size_certificate():
         progress("cfg5: jacobi on the GPU")
         x, it = g.run("jacobi", noise)
         st = B.made_last_stats(g.h)
+        assert 0 < st["conv_rows"] < st["passes"] * w.N * net.H      # row windows: strictly fewer rows than passes x rows
+        progress("cfg5: layer-by-layer certificate of the Jacobi result (32 images)")
+        cert = conv_layer_certificate(g, same, x, noise, from_buffers=True, label="cfg5 jacobi")
+        print(f"cfg5 jacobi: passes mean {it.mean():.2f} max {it.max()}, stats {st}; certificate {cert}")
+        # secondary: end to end against the oracle's own chain of layers, in the rms norm (see the docstring)
         z = g.logits(x)
-        progress("cfg5: oracle pass over 32 images")
+        progress("cfg5: end-to-end oracle pass over 32 images")
         zs = CO.conv_logits_all(same, x)
         rms = float(np.sqrt(np.mean(zs ** 2)))
         err_max = float(np.abs(z - zs).max())
         err_rms = float(np.sqrt(np.mean((z - zs) ** 2)))
         fx, margin = CO.decide(zs, noise, w.C)
         differ = fx != x
-        print(f"cfg5 jacobi: passes mean {it.mean():.2f} max {it.max()}, stats {st}; logits rms {rms:.3f}, "
-              f"error rms {err_rms:.2e} max {err_max:.2e}; {int(differ.sum())} of {differ.size} states differ from "
-              f"the oracle's decision, largest margin among them {margin[differ].max() if differ.any() else 0:.2e}")
-        assert err_rms <= 1.5 * 3.2e-3 * rms
-        assert err_max <= 5e-2 * rms
-        assert not (differ & (margin >= 2 * 5e-2 * rms)).any()
+        print(f"cfg5 end to end: logits rms {rms:.3f}, error rms {err_rms:.2e} max {err_max:.2e}; {int(differ.sum())} of "
+              f"{differ.size} states differ from the decision of the oracle's own chain, largest margin among them "
+              f"{margin[differ].max() if differ.any() else 0:.2e}")
+        assert err_rms <= 1.5 * 3.2e-3 * rms                    # (rms norm; the max norm is printed, not graded)
         assert differ.mean() < 5e-3
-        # the GPU's result is the argmax of the GPU's own logits (the sampling kernel and the logits kernel share
-        # the trunk bit for bit and differ only in the fp32 summation order of the 1 x 1 head)
-        own, own_margin = CO.decide(z.astype(np.float64), noise, w.C)
-        assert not ((own != x) & (own_margin >= 1e-4)).any()
         ze = CO.conv_logits_all(exact, x[:2])
-        assert np.sqrt(np.mean((z[:2] - ze) ** 2)) <= LOGIT_TOL["bf16"] * np.sqrt(np.mean(ze ** 2))
+        assert np.sqrt(np.mean((z[:2] - ze) ** 2)) <= LOGIT_TOL["bf16"] * np.sqrt(np.mean(ze ** 2))   # (rms norm)
+        # GS-Jacobi with blocks of whole image rows: same certificate; images whose result equals the Jacobi one
+        # are covered by the certificate above, the others are certified themselves
+        full_rows = None
+        for rows in (8, 4, 16):
+            progress(f"cfg5: gs-jacobi, blocks of {rows} rows")
+            xb, itb = g.run("gs", noise, rows * 96)
+            stb = B.made_last_stats(g.h)
+            other = np.flatnonzero((xb != x).any(axis=1))
+            print(f"cfg5 gs-jacobi {rows} rows: inner passes mean {itb.mean():.1f}, stats {stb}, "
+                  f"{other.size} images differ from the Jacobi result")
+            assert (itb >= net.H // rows).all() and (itb <= net.D).all()
+            # a block only evaluates the rows up to its own last row, and not the rows that are already final
+            if full_rows is None:
+                full_rows = stb["passes"] * w.N * net.H
+            assert 0 < stb["conv_rows"] < stb["passes"] * w.N * net.H
+            if rows == 8 or other.size:
+                sel = np.arange(w.N) if rows == 8 else other
+                # (the buffers hold the last block's window only for the rows it evaluated: fresh evaluation)
+                sub = conv_layer_certificate(_Subset(g, sel), same, xb[sel], noise[sel], label=f"cfg5 gs {rows} rows")
+                print(f"  certificate on {sel.size} images: {sub}")
     # same network on 2-row images: full sequential oracle
     progress("cfg5: 2-row images against the sequential oracle")
     w2 = dataclasses.replace(w, H=2, N=4)
@@ -176,3 +252,40 @@ def test_cfg5_full_size_certificate():
     with ConvGpu(net2) as g:
         x, it = g.run("jacobi", noise2)
         certify(same2, noise2, x, xs, margins)
+
+
+class _Subset:
+    """A ConvGpu seen through a subset of its batch (fresh evaluations only)."""
+
+    def __init__(self, g, sel):
+        self.g, self.net = g, g.net
+
+    def activations(self, x, layer, N=None):
+        return self.g.activations(x, layer)
+
+    def logits(self, x):
+        return self.g.logits(x)
+
+
+@pytest.mark.timeout(900)
+def test_taller_reduced_shape_against_the_sequential_oracle():
+    """8-row images (768 states) of a reduced network against the oracle's full sequential run at the ordinary bar
+    (bit-exact unless a margin is below 1e-3), Jacobi and GS-Jacobi with blocks of 2 and 3 rows, plus the
+    layer-by-layer certificate."""
+    w = dataclasses.replace(S.conv_workload("small_conv"), H=8, N=2)
+    net = S.make_conv_network(w, with_bias=True)
+    _, same = models(net)
+    noise = S.make_conv_noise(w)
+    progress("8-row images: sequential oracle")
+    xs, margins = CO.conv_sequential_sample(same, noise)
+    with ConvGpu(net) as g:
+        x, it = g.run("jacobi", noise)
+        certify(same, noise, x, xs, margins)
+        st = B.made_last_stats(g.h)
+        assert 0 < st["conv_rows"] < st["passes"] * w.N * net.H
+        print(conv_layer_certificate(g, same, x, noise, from_buffers=True, label="8 rows"))
+        for rows in (2, 3):
+            xb, _ = g.run("gs", noise, rows * 96)
+            certify(same, noise, xb, xs, margins)
+            stb = B.made_last_stats(g.h)
+            assert 0 < stb["conv_rows"] < stb["passes"] * w.N * net.H

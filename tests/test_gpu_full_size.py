@@ -9,8 +9,24 @@ import pytest
 from oracle import made_oracle as O
 from paper_2002_03629_amd import synth as S
 
-from gpu_util import (LOGIT_TOL, MARGIN, GpuModel, assert_logits_close, assert_sample_parity, oracle_models,
-                      progress)
+from gpu_util import (LOGIT_TOL, MARGIN, GpuModel, assert_logits_close, assert_sample_parity, mlp_layer_certificate,
+                      oracle_models, progress)
+
+
+def assert_counts_close(it, it_ref, min_margin, x, x_ref, same_floor):
+    """Iteration counts at full size.  Nearly every sample of a large network meets SOME decision within 1e-3 of a
+    tie in one of its passes (cfg2: 784 positions x 3-4 passes), so the strict comparison -- equal counts where
+    every margin is clear -- covers only a few samples.  Therefore, for EVERY sample: the count is within one pass
+    of the oracle's (a near-tie that falls the other way in an intermediate pass costs or saves one pass), and
+    the count is equal wherever the final symbols are the oracle's; and the share of samples whose symbols are
+    identical to the oracle's own Jacobi run has a floor."""
+    clear = min_margin >= MARGIN
+    assert (it[clear] == it_ref[clear]).all()
+    assert (np.abs(it - it_ref) <= 1).all(), (it, it_ref)
+    same = (x == x_ref).all(axis=1)
+    assert same.mean() >= same_floor, f"only {same.mean():.3f} of the samples equal the oracle's Jacobi result"
+    assert (it[same] != it_ref[same]).mean() <= 0.05
+    return float(clear.mean()), float(same.mean()), float((it == it_ref).mean())
 
 pytestmark = pytest.mark.gpu
 
@@ -28,11 +44,13 @@ def test_cfg2_jacobi_and_gs_jacobi_full_batch(persistent):
         x, it = g.jacobi(noise)
         exempt, _ = assert_sample_parity(same, noise, x)
         assert_sample_parity(same, noise[:sub], x[:sub], xs, mg)
-        assert (it[mm >= MARGIN] == it_ref[mm >= MARGIN]).all()
-        print(f"cfg2 jacobi: passes mean {it.mean():.2f} max {it.max()}, exempt positions {exempt}, "
-              f"identical to oracle jacobi: {(x == xr).all(axis=1).mean():.3f}")
+        clear, same_frac, equal_counts = assert_counts_close(it, it_ref, mm, x, xr, same_floor=0.85)
+        print(f"cfg2 jacobi: passes mean {it.mean():.2f} max {it.max()}, exempt positions {exempt}, samples with all "
+              f"margins clear {clear:.3f}, identical to oracle jacobi {same_frac:.3f}, equal pass counts {equal_counts:.3f}")
         z = g.logits(x[:16])
         assert_logits_close(z, O.logits_all(exact, x[:16]), LOGIT_TOL["bf16"])
+        worst = mlp_layer_certificate(g, same, x, noise)
+        print(f"cfg2 layer certificate at the Jacobi result: worst logit accumulation error {worst:.2f} x 2^-24 sum|a w|")
         for block in w.block_sizes:
             xb, itb = g.gs_jacobi(noise, block)
             assert_sample_parity(same, noise, xb)
@@ -40,6 +58,8 @@ def test_cfg2_jacobi_and_gs_jacobi_full_batch(persistent):
             ref = O.gs_jacobi_reference(same, noise[:sub], block)
             clear = ref[3] >= MARGIN
             assert (itb[:sub][clear] == ref[1][clear]).all()
+            # every sample of the sub-batch: a block's inner loop may take one pass more or less per near-tie
+            assert (np.abs(itb[:sub] - ref[1]) <= 2).all(), (block, itb[:sub], ref[1])
         for mode in (0, 1):
             xq = g.sequential(noise, mode)
             assert_sample_parity(same, noise, xq)
@@ -71,6 +91,9 @@ def test_cfg4_categorical_full_size():
         ref = O.jacobi_reference(same, noise[:8])
         clear = ref[4] >= MARGIN
         assert (it[:8][clear] == ref[1][clear]).all()
+        assert (np.abs(it[:8] - ref[1]) <= 1).all(), (it[:8], ref[1])
+        print(f"cfg4 jacobi vs oracle jacobi on 8 samples: clear {clear.mean():.2f}, equal counts {(it[:8] == ref[1]).mean():.2f}, "
+              f"identical symbols {(x[:8] == ref[0]).all(axis=1).mean():.2f}")
         z = g.logits(x[:2])
         assert_logits_close(z, O.logits_all(exact, x[:2]), LOGIT_TOL["bf16"])
         progress("cfg4: gs-jacobi, sequential")
@@ -154,7 +177,7 @@ def test_cfg2_large_batch_vector_epilogue(tile):
         x, it = g.jacobi(noise)
         assert_sample_parity(same, noise, x)
         assert_sample_parity(same, noise[:sub], x[:sub], xs, mg)
-        assert (it[ref[4] >= MARGIN] == ref[1][ref[4] >= MARGIN]).all()
+        assert_counts_close(it, ref[1], ref[4], x, ref[0], same_floor=0.85)
         z = g.logits(x[:300])
         assert_logits_close(z, O.logits_all(exact, x), LOGIT_TOL["bf16"])
         xb, _ = g.gs_jacobi(noise, 196)
@@ -194,8 +217,7 @@ def test_cfg2_batch_8192_stop_test_as_its_own_kernel():
     assert_sample_parity(same, noise, x)
     assert_sample_parity(same, noise[:sub], x[:sub], xs, mg)
     assert_sample_parity(same, noise, xb)
-    clear = ref[4] >= MARGIN
-    assert (it[:64][clear] == ref[1][clear]).all()
+    assert_counts_close(it[:64], ref[1], ref[4], x[:64], ref[0], same_floor=0.85)
     # the other run: same symbols and pass counts, except where a draw lies within rounding of its threshold (which
     # tile shape a late pass runs on depends on the active count the host had seen when it enqueued the pass, and
     # the shapes sum in different orders)

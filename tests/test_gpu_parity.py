@@ -9,8 +9,8 @@ from oracle import made_oracle as O
 from paper_2002_03629_amd import binding as B
 from paper_2002_03629_amd import synth as S
 
-from gpu_util import (LOGIT_TOL, MARGIN, GpuModel, assert_logits_close, assert_sample_parity, dev, oracle_models,
-                      progress)
+from gpu_util import (LOGIT_TOL, MARGIN, GpuModel, assert_counts_match, assert_logits_close, assert_sample_parity, dev,
+                      mlp_layer_certificate, oracle_models, progress)
 
 pytestmark = pytest.mark.gpu
 
@@ -64,6 +64,19 @@ def test_forward_logits(name):
 
 
 @pytest.mark.parametrize("name", SMALL)
+def test_every_layer_on_its_own(name):
+    """The layer-by-layer certificate: each masked layer, fed the library's own previous layer, against the oracle's
+    layer -- bit-exact bf16 activations except within the fp32 accumulation error of a rounding boundary."""
+    w = S.workload(name)
+    net = S.make_network(w, with_bias=True)
+    _, same = oracle_models(net)
+    x = _symbols(w, np.random.default_rng(7), w.N)
+    with GpuModel(net) as g:
+        worst = mlp_layer_certificate(g, same, x)
+    print(f"{name}: worst accumulation error {worst:.2f} x 2^-24 sum|a w|")
+
+
+@pytest.mark.parametrize("name", SMALL)
 def test_jacobi_matches_sequential_oracle(name):
     w = S.workload(name)
     net = S.make_network(w, with_bias=True)
@@ -81,12 +94,10 @@ def test_jacobi_matches_sequential_oracle(name):
             xi, iti = g.jacobi(noise, init)
             assert_sample_parity(same, noise, xi, xs, margins)
             ref_i = O.jacobi_reference(same, noise, init)
-            clear = ref_i[4] >= MARGIN
-            assert (iti[clear] == ref_i[1][clear]).all()
+            assert_counts_match(iti, ref_i[1], ref_i[4])
     assert_sample_parity(same, noise, x, xs, margins)
     assert (it >= 1).all() and (it <= w.D).all()
-    clear = mm >= MARGIN
-    assert (it[clear] == it_ref[clear]).all()
+    assert_counts_match(it, it_ref, mm)
     assert st["passes"] == it.max() and st["sample_passes"] == it.sum()
 
 
@@ -115,15 +126,14 @@ def test_gs_jacobi_every_block_size(name):
             x, it = g.gs_jacobi(noise, block)
             assert_sample_parity(same, noise, x, xs, margins)
             xr, it_ref, per_block, mm = O.gs_jacobi_reference(same, noise, block)
-            clear = mm >= MARGIN
-            assert (it[clear] == it_ref[clear]).all(), (block, it, it_ref)
+            assert_counts_match(it, it_ref, mm)
             if block == 1:
                 assert (it == w.D).all()
         init = _symbols(w, np.random.default_rng(3), w.N)
         x, it = g.gs_jacobi(noise, 7, init)
         assert_sample_parity(same, noise, x, xs, margins)
         ref = O.gs_jacobi_reference(same, noise, 7, init)
-        assert (it[ref[3] >= MARGIN] == ref[1][ref[3] >= MARGIN]).all()
+        assert_counts_match(it, ref[1], ref[3])
         # the frozen-prefix reuse changes no bit: same symbols and pass counts with it switched off
         x_on, it_on = g.gs_jacobi(noise, 16)
         B.made_set_option(g.h, B.MADE_OPT_PREFIX_CACHE, 0)
@@ -145,8 +155,7 @@ def test_jacobi_gs_every_block_size(name):
             x, it = g.jacobi_gs(noise, block)
             assert_sample_parity(same, noise, x, xs, margins)
             xr, it_ref, done, mm = O.jacobi_gs_reference(same, noise, block)
-            clear = mm >= MARGIN
-            assert (it[clear] == it_ref[clear]).all(), (block, it, it_ref)
+            assert_counts_match(it, it_ref, mm)
             M = -(-w.D // min(block, w.D))
             assert (it >= 1).all() and (it <= M).all()
             if block >= w.D:
@@ -155,7 +164,7 @@ def test_jacobi_gs_every_block_size(name):
         x, it = g.jacobi_gs(noise, 7, init)
         assert_sample_parity(same, noise, x, xs, margins)
         ref = O.jacobi_gs_reference(same, noise, 7, init)
-        assert (it[ref[3] >= MARGIN] == ref[1][ref[3] >= MARGIN]).all()
+        assert_counts_match(it, ref[1], ref[3])
         # an iteration limit below M: the iterate after one iteration, and the not-converged status
         ref1 = O.jacobi_gs_reference(same, noise, 7, None, 1)
         if not ref1[2].all() and (ref1[3] >= MARGIN).all():
@@ -264,8 +273,7 @@ def test_large_batch_uses_big_tiles(name, N, tile):
         assert_logits_close(z, O.logits_all(exact, x0), LOGIT_TOL[w.dtype])
         x, it = g.jacobi(noise)
         assert_sample_parity(same, noise, x, xs, margins)
-        clear = ref[4] >= MARGIN
-        assert (it[clear] == ref[1][clear]).all()
+        assert_counts_match(it, ref[1], ref[4])
         xb, itb = g.gs_jacobi(noise, 33)
         assert_sample_parity(same, noise, xb, xs, margins)
         xq = g.sequential(noise, 1)
