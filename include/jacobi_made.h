@@ -124,6 +124,20 @@ int made_free(made_model* m);
 int made_forward_logits(made_model* m, const uint8_t* x, int32_t N, float* logits, void* stream);
 
 /*
+ * made_forward_logits_noalloc -- made_forward_logits for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and bit-identical
+ * logits; the network input and the hidden activations of the pass live in a static device array of 8 MiB (one copy
+ * per GPU, held until the process ends) instead of the model's workspace, and the call neither allocates, frees nor
+ * waits for the device.  Only work on `stream` is enqueued (a clearing kernel, then the pass).
+ *   Limit: round_up(N, 64) * (sum over the layers of their input width padded to a multiple of 64) * element size
+ *   must fit the 8 MiB (D = 784 with 2 x 2000 hidden units in bf16: 832 samples per call); beyond that the call
+ *   returns MADE_ERR_ARG and the message states the limit for the model.  Masked MLPs with discrete states only.
+ *   All calls on one GPU share that GPU's array, whatever the model: calls that overlap in time (different streams,
+ *   or graphs replayed concurrently) race on it and must be serialised by the caller.
+ */
+int made_forward_logits_noalloc(made_model* m, const uint8_t* x, int32_t N, float* logits, void* stream);
+
+/*
  * made_layer_activations -- inspection aid for tests: the activations h_l = ReLU((W_l * M_l) h_{l-1} + b_l) of one
  * layer of the network of Section 5.3.1 (for the convolutional model: of one k x k layer) as the library holds
  * them, i.e. after the rounding to bf16 of a MADE_BF16 model, widened exactly to fp32.  Feeding them to a reference

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libjacobi_m
 MADE_OK, MADE_ERR_ARG, MADE_ERR_NOMEM, MADE_ERR_HIP, MADE_ERR_NOT_CONVERGED = 0, -1, -2, -3, -4
 MADE_F32, MADE_BF16 = 0, 1
 
-EXPORTS = ["made_init", "made_conv_init", "made_free", "made_forward_logits", "made_layer_activations", "sequential_sample", "jacobi_sample",
+EXPORTS = ["made_init", "made_conv_init", "made_free", "made_forward_logits", "made_forward_logits_noalloc", "made_layer_activations", "sequential_sample", "jacobi_sample",
            "gs_jacobi_sample", "jacobi_gs_sample", "made_forward_params", "sequential_sample_real",
            "jacobi_sample_real", "gs_jacobi_sample_real", "made_last_stats", "made_set_profiling", "made_last_profile", "made_set_option",
            "made_layer_nnz",
@@ -62,6 +62,7 @@ def lib() -> C.CDLL:
                                      C.POINTER(C.POINTER(C.c_float)), C.POINTER(vp)]
         L.made_free.argtypes = [vp]
         L.made_forward_logits.argtypes = [vp, vp, i32, vp, vp]
+        L.made_forward_logits_noalloc.argtypes = [vp, vp, i32, vp, vp]
         L.made_layer_activations.argtypes = [vp, vp, i32, i32, vp, vp]
         L.sequential_sample.argtypes = [vp, vp, i32, i32, vp, vp]
         L.jacobi_sample.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp]
@@ -193,6 +194,12 @@ def made_free(model: Optional[int]) -> None:
 def made_forward_logits(model: int, x, N: int, logits, stream=None) -> None:
     import torch
     _check(lib().made_forward_logits(model, _ptr(x, torch.uint8), N, _ptr(logits, torch.float32), _stream(stream)))
+
+
+def made_forward_logits_noalloc(model: int, x, N: int, logits, stream=None) -> None:
+    import torch
+    _check(lib().made_forward_logits_noalloc(model, _ptr(x, torch.uint8), N, _ptr(logits, torch.float32),
+                                             _stream(stream)))
 
 
 def made_layer_activations(model: int, x, N: int, layer: int, out, stream=None) -> None:

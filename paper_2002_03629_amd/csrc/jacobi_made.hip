@@ -15,6 +15,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <numeric>
 #include <string>
@@ -26,6 +27,32 @@
 #include "onehot.hpp"
 
 using namespace jm;
+
+// ------------------------------------------------------------------------------------------------
+// Static scratch memory of made_forward_logits_noalloc (the entry point for callers that cannot allocate).
+// `scratch` is a host-side stand-in, not a device address: host code only ever uses the address that
+// hipGetSymbolAddress returned for the device at hand (every device holds its own copy of the array).
+// ------------------------------------------------------------------------------------------------
+constexpr size_t NOALLOC_SCRATCH_BYTES = (size_t)8 << 20;   // 8 MiB per device, held until the process ends
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static void* g_scratch_ptr[NOALLOC_MAX_DEVICES] = {nullptr};
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on `device`, which must be the current device.  Looked up once per device.
+static hipError_t scratch_address(int device, void** out) {
+  *out = nullptr;
+  if (device < 0 || device >= NOALLOC_MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    g_scratch_ptr[device] = ptr;
+  }
+  *out = g_scratch_ptr[device];
+  return hipSuccess;
+}
 
 // ------------------------------------------------------------------------------------------------
 // errors
@@ -482,6 +509,15 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
   if (e != hipSuccess) {
     delete m;
     return fail(MADE_ERR_HIP, "hipGetDevice failed: %s", hipGetErrorString(e));
+  }
+
+  {   // the static scratch array's address on this device (see made_forward_logits_noalloc)
+    void* sp = nullptr;
+    e = scratch_address(m->device, &sp);
+    if (e != hipSuccess) {
+      delete m;
+      return fail(MADE_ERR_HIP, "made_init: hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+    }
   }
 
   const int L = m->L, D = m->D, C = m->C;
@@ -1363,6 +1399,67 @@ extern "C" int made_forward_logits(made_model* m, const uint8_t* x, int32_t N, f
   a.ldo = m->D * m->C;
   launch_layer<EPI_LOGITS>(m, m->L, a, m->layers[m->L].n_tiles, (N + TILE - 1) / TILE, s);
   m->profiling = was_profiling;
+  HIP_TRY(hipGetLastError());
+  return MADE_OK;
+}
+
+// One pass over the whole network like made_forward_logits, for callers that cannot allocate: network input and
+// hidden activations live in this device's copy of the static `scratch` array instead of the model's workspace,
+// and nothing here calls hipMalloc / hipFree or waits for the device.  The used part of the array is cleared
+// first (by a kernel, so that the call may be captured into a graph): the masked weights are zero in the K
+// padding of a layer, but what an earlier call of another model left there could be Inf or NaN.
+extern "C" int made_forward_logits_noalloc(made_model* m, const uint8_t* x, int32_t N, float* logits, void* stream) {
+  if (!m) return fail(MADE_ERR_ARG, "made_forward_logits_noalloc: model is NULL");
+  if (m->arch != 0 || m->real)
+    return fail(MADE_ERR_ARG, "made_forward_logits_noalloc: only masked MLPs with discrete states are supported");
+  if (N < 0) return fail(MADE_ERR_ARG, "made_forward_logits_noalloc: N=%d is negative", N);
+  if (N > 0 && (!x || !logits)) return fail(MADE_ERR_ARG, "made_forward_logits_noalloc: NULL symbols or logits pointer");
+  if (m->poisoned) return fail(MADE_ERR_HIP, "made_forward_logits_noalloc: an earlier call on this model timed out");
+  if (N == 0) return MADE_OK;
+  // layout: [enc | act 0 | ... | act L-1], each n_pad rows of the layer's padded input width, 256-byte aligned
+  const size_t es = elem_size(m);
+  const size_t n_pad = (size_t)round_up(N, 2 * TILE);
+  size_t per_row = 0;
+  for (int l = 0; l <= m->L; ++l) per_row += (size_t)m->layers[l].in_pad * es;
+  const size_t need = n_pad * per_row;                     // (every piece is a multiple of 64 rows x 128 bytes)
+  if (need > NOALLOC_SCRATCH_BYTES)
+    return fail(MADE_ERR_ARG, "made_forward_logits_noalloc: N=%d needs %zu bytes of scratch memory, the static array "
+                              "holds %zu (at most %zu samples of this model per call)", N, need, NOALLOC_SCRATCH_BYTES,
+                (NOALLOC_SCRATCH_BYTES / per_row) / (2 * TILE) * (2 * TILE));
+  HIP_TRY(hipSetDevice(m->device));
+  void* base = nullptr;
+  {
+    const hipError_t e = scratch_address(m->device, &base);   // (looked up in made_init; a table read here)
+    if (e != hipSuccess) return fail(MADE_ERR_HIP, "hipGetSymbolAddress(scratch) failed: %s", hipGetErrorString(e));
+  }
+  hipStream_t s = (hipStream_t)stream;
+  ActBuffers buf;
+  memset(&buf, 0, sizeof buf);
+  size_t off = 0;
+  buf.enc = (unsigned char*)base + off;
+  off += n_pad * m->layers[0].in_pad * es;
+  for (int l = 0; l < m->L; ++l) {
+    buf.act[l] = (unsigned char*)base + off;
+    off += n_pad * m->layers[l + 1].in_pad * es;
+  }
+  const bool was_profiling = m->profiling;
+  m->profiling = false;
+  {
+    const size_t n16 = need / 16;
+    const int blocks = (int)std::min<size_t>((n16 + 255) / 256, 2048);
+    hipLaunchKernelGGL(zero_fill_kernel, dim3(blocks), dim3(256), 0, s, (uint4*)base, n16);
+  }
+  int rc = launch_init_state(m, x, nullptr, N, s, nullptr, buf.enc);
+  RowSet rs{nullptr, nullptr, N, x};
+  if (rc == MADE_OK) rc = run_hidden(m, rs, nullptr, -1, s, nullptr, false, &buf);
+  if (rc == MADE_OK) {
+    LayerArgs a = base_args(m, m->L, buf.act[m->L - 1], rs);
+    a.out = logits;
+    a.ldo = m->D * m->C;
+    launch_layer<EPI_LOGITS>(m, m->L, a, m->layers[m->L].n_tiles, (N + TILE - 1) / TILE, s);
+  }
+  m->profiling = was_profiling;
+  if (rc != MADE_OK) return rc;
   HIP_TRY(hipGetLastError());
   return MADE_OK;
 }

@@ -2101,6 +2101,12 @@ __global__ void copy_symbols_kernel(const uint8_t* x_init, uint8_t* x, size_t to
     x[i] = x_init ? x_init[i] : 0;
 }
 
+// Clear n pieces of 16 bytes (a kernel rather than a memset so that a caller may capture it into a graph).
+__global__ void zero_fill_kernel(uint4* p, size_t n) {
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = make_uint4(0, 0, 0, 0);
+}
+
 // Activations of one layer from the fragment-major buffer to a plain float [rows, width] array; slot_unit (or NULL)
 // maps the storage slot of a unit to the column it is written to.  (Inspection only: no sampling path uses it.)
 template <typename T>
