@@ -51,6 +51,49 @@ def cpu_baseline(w, net, noises, budget_s=12.0):
                       f"({done // sub} x {sub} of a batch of {noises[0].shape[0]}), {dt:.1f} s"}, xs0, sub
 
 
+def coupling_sweep(w, torch, B, S, stream):
+    """Supplementary (not a benchmark configuration): how the number of Jacobi passes, and with it the speed-up over
+    the sequential sampler, depends on how strongly the states are coupled (Section 4.1: learned weights leave few
+    long dependency chains; these random ones are scaled up instead).  The workload's network with every weight
+    multiplied by gamma, and the Markov copy chain of Section 4.1's third example (exactly T passes) at T = D."""
+    import dataclasses
+    out = {}
+    cases = [(f"gamma{g:g}", dataclasses.replace(w, gain=w.gain * g), None) for g in (1.0, 4.0, 16.0, 64.0)]
+    cases.append(("copy_chain_T%d" % w.D, None, S.copy_chain_network(w.D, dtype=w.dtype)))
+    for name, wg, net in cases:
+        if net is None:
+            net = S.make_network(wg)
+            u = torch.from_numpy(S.make_noise(wg)).cuda()
+        else:
+            u = torch.from_numpy(S.uniform_noise(w.N, w.D, w.seed + 2) * 0.98 + 0.01).cuda()
+        h = B.model_from_network(net)
+        try:
+            x = torch.empty((w.N, w.D), dtype=torch.uint8, device="cuda")
+            xq = torch.empty_like(x)
+            it = torch.empty((w.N,), dtype=torch.int32, device="cuda")
+            B.jacobi_sample(h, u, w.N, None, 0, x, it, stream)
+            torch.cuda.synchronize()
+            reps = 5
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                B.jacobi_sample(h, u, w.N, None, 0, x, it, stream)
+            torch.cuda.synchronize()
+            dt = (time.perf_counter() - t0) / reps
+            B.sequential_sample(h, u, w.N, 1, xq, stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            B.sequential_sample(h, u, w.N, 1, xq, stream)
+            torch.cuda.synchronize()
+            ds = time.perf_counter() - t0
+            itc = it.cpu().numpy()
+            out[name] = {"jacobi_ms": dt * 1e3, "iters_mean": float(itc.mean()), "iters_max": int(itc.max()),
+                         "sequential_lean_ms": ds * 1e3, "jacobi_speedup_vs_lean_sequential": ds / dt,
+                         "same_output_as_sequential": bool(torch.equal(x, xq))}
+        finally:
+            B.made_free(h)
+    return out
+
+
 def cpu_baseline_real(w, net, noises, budget_s=12.0):
     """The logistic oracle's sequential sampler (Eq. 1) on whole batches until about budget_s seconds are spent."""
     from oracle import logistic_oracle as LO
@@ -116,6 +159,28 @@ def measured_traffic(workload: str, path: str, dom_is_output: bool):
     except OSError:
         pass
     return None
+
+
+def measured_mfma(workload: str):
+    """MFMA counters of the workload's kernels from a separate `rocprofv3 --pmc` run, as summarised under profiles/
+    (lines `name: value` after the marker `bench_fields:`); None when no such summary exists."""
+    fn = os.path.join(ROOT, "profiles", f"{workload}_pmc_mfma.txt")
+    try:
+        lines = open(fn).read().splitlines()
+    except OSError:
+        return None
+    out, on = {"source": f"profiles/{workload}_pmc_mfma.txt"}, False
+    for line in lines:
+        if line.startswith("bench_fields:"):
+            on = True
+            continue
+        if on and ":" in line:
+            k, v = line.split(":", 1)
+            try:
+                out[k.strip()] = float(v)
+            except ValueError:
+                out[k.strip()] = v.strip()
+    return out if len(out) > 1 else None
 
 
 def bench_rnn(args, torch, B, S) -> int:
@@ -207,7 +272,7 @@ def bench_rnn(args, torch, B, S) -> int:
     return 0
 
 
-def main() -> int:
+def parse_args(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
@@ -234,26 +299,24 @@ def main() -> int:
     ap.add_argument("--pmc-probe", action="store_true",
                     help="no timing: run 20 device copies of 64 MiB (calibration of FETCH_SIZE / WRITE_SIZE), then "
                          "20 steps; meant to run under `rocprofv3 --pmc ...`")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (samples are independent systems, so a batch would "
-              "shard without any exchange). Run with --gpus 1.", file=sys.stderr)
-        return 2
+    ap.add_argument("--single", action="store_true",
+                    help="time only --workload (default: the cfg2 run also times cfg1, cfg4 and cfg5 and reports all "
+                         "five configurations in the one JSON line)")
+    ap.add_argument("--gain", type=float, default=0.0,
+                    help="scale every weight of the workload by this factor (coupling-strength sweeps; 0 = as defined)")
+    return ap.parse_args(argv)
 
-    import torch
-    from paper_2002_03629_amd import binding as B
-    from paper_2002_03629_amd import synth as S
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 3
+def run_one(args, torch, B, S, light=False):
+    """Time one workload; returns the result dict of the JSON line.  light: the short form used for the other
+    configurations of the default run (no Jacobi-GS, no batch sweep, a shorter CPU baseline)."""
     import dataclasses
-    if args.workload.startswith("rnn"):
-        return bench_rnn(args, torch, B, S)
     conv = args.workload in ("cfg5", "small_conv", "small_conv_f32")
     w = S.conv_workload(args.workload) if conv else S.workload(args.workload)
     if args.batch > 0:
         w = dataclasses.replace(w, N=args.batch)
+    if args.gain > 0:
+        w = dataclasses.replace(w, gain=w.gain * args.gain)
     if conv:
         net = S.make_conv_network(w)
         model = B.conv_model_from_network(net)
@@ -301,8 +364,7 @@ def main() -> int:
             step(i)
         torch.cuda.synchronize()
         B.made_free(model)
-        print(json.dumps({"pmc_probe": True, "copy_bytes_read": 64 << 20, "copy_bytes_written": 64 << 20}))
-        return 0
+        return {"pmc_probe": True, "copy_bytes_read": 64 << 20, "copy_bytes_written": 64 << 20}
 
     for i in range(args.warmup):
         step(i)
@@ -343,9 +405,26 @@ def main() -> int:
     elapsed_prof = time.perf_counter() - t0
     B.made_set_profiling(model, False)
 
+    # ---- one pass on the FULL batch (pass limit 1) with events: the launch a kernel's roofline is best quoted on
+    # (later passes of a call run on fewer samples or fewer image rows, and the last launch finds an empty list)
+    first_ms = np.zeros(n_slots)
+    first_launches = np.zeros(n_slots, dtype=np.int64)
+    if not real:
+        B.made_set_profiling(model, True)
+        for i in range(5):
+            try:
+                B.jacobi_sample(model, noises[i % n_noise], N, None, 1, x, iters, stream)
+            except B.MadeError as e:                       # one pass does not converge: that is the point
+                if e.code != B.MADE_ERR_NOT_CONVERGED:
+                    raise
+            ms, cnt = B.made_last_profile(model, n_slots)
+            first_ms += ms
+            first_launches += np.array(cnt)
+        B.made_set_profiling(model, False)
+
     if conv:
         # the k x k layers are launches of one kernel on one shape: fold their slots into slot 1
-        for arr in (layer_ms, layer_launches, layer_flops):
+        for arr in (layer_ms, layer_launches, layer_flops, first_ms, first_launches):
             arr[1] = arr[1:n_layers - 1].sum()
             arr[2:n_layers - 1] = 0
     dom = int(np.argmax(layer_ms))
@@ -357,7 +436,9 @@ def main() -> int:
     if hbm_bound:
         noise_bytes = 4.0 * D * w.C * (w.C > 1) + 4.0 * D * (w.C == 1)       # per active sample
         act_bytes = es * (w.hidden[-1] if dom == n_layers - 1 else 0)
-        dom_bytes = layer_launches[dom] * nnz[dom] * es + sample_passes * (noise_bytes + act_bytes)
+        # weights are charged only to launches that found a non-empty list (`passes`); the speculative launch behind
+        # the converged pass reads nothing, but its duration stays in the denominator (it is a launch of this kernel)
+        dom_bytes = passes * nnz[dom] * es + sample_passes * (noise_bytes + act_bytes)
         achieved = dom_bytes / (layer_ms[dom] * 1e-3) / 1e9
         peak, unit, bound = 8000.0, "GB/s", "hbm"
     else:
@@ -375,6 +456,20 @@ def main() -> int:
         else:
             layer_name = (f"masked_layer_kernel layer {dom} "
                           f"({'output+sampling epilogue' if dom == n_layers - 1 else 'hidden'})")
+
+    # the dominant kernel on a full batch
+    full = None
+    if first_launches[dom] > 0 and dom < n_layers:
+        full_us = first_ms[dom] / first_launches[dom] * 1e3
+        if hbm_bound:
+            full_ach = (nnz[dom] * es + N * (noise_bytes + act_bytes)) / (full_us * 1e-6) / 1e9
+        else:
+            # (for the convolutional model slot 1 holds the launches of all k x k layers: one layer's work each)
+            full_ach = flops_per_sample_pass[dom] * N / (full_us * 1e-6) / 1e12
+        full = {"avg_launch_us": full_us, "achieved": full_ach, "frac": full_ach / peak,
+                "launches": int(first_launches[dom]),
+                "what": "the same kernel on a pass over the full batch (first pass of a call with pass limit 1)"}
+    pmc = measured_mfma(w.name)
 
     result = {
         "metric": "samples/s (Jacobi vs sequential, same output); iters to converge; MFMA util",
@@ -408,10 +503,16 @@ def main() -> int:
             "launches": int(layer_launches[dom]),
             "per_slot_avg_us": [float(m / max(1, c) * 1e3) for m, c in zip(layer_ms, layer_launches)],
             "mfma_tflops": layer_flops[dom] / (layer_ms[dom] * 1e-3) / 1e12 if layer_ms[dom] > 0 else 0.0,
-            "note": "algorithmic flops = 2*nnz(W*mask) per active sample per pass; algorithmic bytes (hbm bound) = "
-                    "visible weights once per launch + noise and last-hidden activations per active sample; "
-                    "durations from HIP events around each launch on the launch stream (second pass over the "
-                    "same steps)",
+            "full_batch_launch": full,
+            "traffic_source": "profiles/%s_jacobi_pmc_traffic.txt (two separate rocprofv3 --pmc runs)" % w.name,
+            "rocprof": pmc,
+            "note": "frac uses durations from HIP events around each launch on the launch stream, measured live in a "
+                    "second pass over the same steps, averaged over ALL launches of the kernel in a call (late "
+                    "passes on few samples and the final launch on an empty list included); full_batch_launch is "
+                    "the same kernel on a whole batch.  algorithmic flops = 2*nnz(W*mask) per active sample per pass; "
+                    "algorithmic bytes (hbm bound) = visible weights once per launch on a non-empty list + noise and "
+                    "last-hidden activations per active sample.  rocprof: figures of separate rocprofv3 runs "
+                    "(kernel-trace duration, MFMA counters) read from the named summaries under profiles/",
         },
         "whole_call_tflops": 2.0 * sum(nnz) * (conv_rows / w.H if conv else sample_passes) / elapsed_prof / 1e12,
         "ms_per_step_with_events": elapsed_prof / args.steps * 1e3,
@@ -485,7 +586,7 @@ def main() -> int:
                                            "iters_mean": float(itc.mean()), "iters_max": int(itc.max()),
                                            "batch_passes": int(st["passes"]),
                                            "same_output_as_jacobi": bool(torch.equal(xq, x_jac))}
-        if not conv and w.C == 1:
+        if not conv and w.C == 1 and not light:
             for blk in (w.block_sizes or []):           # Algorithm 2: one timed call per block size (it is slow)
                 B.jacobi_gs_sample(model, noises[0], N, None, blk, 0, xq, iters, stream)
                 torch.cuda.synchronize()
@@ -497,7 +598,9 @@ def main() -> int:
                 extras[f"jacobi_gs_B{blk}"] = {"samples_per_s": N / dt, "ms_per_batch": dt * 1e3,
                                                "iters_mean": float(itc.mean()), "iters_max": int(itc.max()),
                                                "same_output_as_jacobi": bool(torch.equal(xq, x_jac))}
-        if not conv and w.C == 1 and not getattr(net, "onehot", False) and not args.batch:
+        if not conv and w.C == 1 and not light and not args.batch and not args.gain and w.name == "cfg2":
+            extras["coupling_sweep"] = coupling_sweep(w, torch, B, S, stream)
+        if not conv and w.C == 1 and not getattr(net, "onehot", False) and not args.batch and not light:
             # the same network on larger batches (supplementary: throughput once the layers are real GEMMs); the
             # noise recipe is the workload's, so the first N samples are the headline batch again
             sweep = {}
@@ -528,7 +631,7 @@ def main() -> int:
         result["extras"] = extras
 
     if not args.no_cpu_baseline and conv:
-        base, xs, n2 = cpu_baseline_conv(w, net, noises_host[0])
+        base, xs, n2 = cpu_baseline_conv(w, net, noises_host[0], 6.0 if light else 12.0)
         result["cpu_baseline"] = base
         if x_jac is not None:
             # early states depend on early states only: the oracle's first states are final
@@ -545,7 +648,7 @@ def main() -> int:
         # hours, not seconds; the scalar-input workload of the same shape (cfg4) carries the CPU baseline
         result["cpu_baseline"] = None
     elif not args.no_cpu_baseline:
-        base, xs, n2 = cpu_baseline(w, net, noises_host)
+        base, xs, n2 = cpu_baseline(w, net, noises_host, 6.0 if light else 12.0)
         result["cpu_baseline"] = base
         if x_jac is not None:
             result["cpu_baseline"]["gpu_matches_oracle_on_sample"] = bool(
@@ -554,6 +657,90 @@ def main() -> int:
         result["cpu_baseline"] = None
 
     B.made_free(model)
+    return result
+
+
+def summary_of(r):
+    """The figures of one configuration that go into the multi-configuration line."""
+    ex = r.get("extras") or {}
+    out = {"workload": r["config"]["workload"], "dtype": r["dtype"], "steps": r["steps"],
+           "samples_per_s": r["value"], "ms_per_step": r["ms_per_step"],
+           "iters_mean": r["iters_mean"], "iters_max": r["iters_max"], "passes_per_step": r["passes_per_step"]}
+    for key in ("sequential_whole_network", "sequential_lean"):
+        if key in ex:
+            out[key] = {"ms_per_batch": ex[key]["ms_per_batch"], "jacobi_speedup": ex[key]["jacobi_speedup"],
+                        "same_output_as_jacobi": ex[key].get("same_output_as_jacobi")}
+    gs = {k: v for k, v in ex.items() if k.startswith("gs_jacobi_B")}
+    if gs:
+        out["gs_jacobi"] = gs
+    rf = r["roofline"]
+    out["roofline"] = {k: rf[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "kernel",
+                                          "avg_launch_us", "launches", "full_batch_launch", "rocprof")}
+    out["whole_call_tflops"] = r["whole_call_tflops"]
+    out["cpu_baseline"] = r.get("cpu_baseline")
+    return out
+
+
+def main() -> int:
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (samples are independent systems, so a batch would "
+              "shard without any exchange). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2002_03629_amd import binding as B
+    from paper_2002_03629_amd import synth as S
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    if args.workload.startswith("rnn"):
+        return bench_rnn(args, torch, B, S)
+    result = run_one(args, torch, B, S)
+    multi = (args.workload == "cfg2" and not args.single and not args.pmc_probe and not args.batch and not args.gain
+             and args.path == "layers" and not args.no_extras)
+    if multi:
+        # The headline (`value`, `roofline`, `cpu_baseline`) is cfg2, the configuration of the paper's MADE
+        # experiment; the other benchmark configurations are timed in the same run, each as its own model.
+        import copy
+        configs = {"cfg1": None, "cfg2": summary_of(result)}
+        gs = configs["cfg2"].pop("gs_jacobi", {})
+        seq = configs["cfg2"].get("sequential_whole_network", {}).get("ms_per_batch")
+        configs["cfg3"] = {"workload": "cfg2's network, GS-Jacobi (Algorithm 3) with blocks of 16 / 64 / 196 positions, batch 128",
+                           **{k: dict(v, speedup_vs_sequential_whole_network=(seq / v["ms_per_batch"] if seq else None))
+                              for k, v in gs.items()}}
+        for name in ("cfg1", "cfg4", "cfg5"):
+            sub = copy.copy(args)
+            sub.workload = name
+            sub.steps = args.steps if name == "cfg1" else min(args.steps, 20)
+            sub.warmup = min(args.warmup, 5) if name != "cfg1" else args.warmup
+            sub.no_cpu_baseline = args.no_cpu_baseline
+            t0 = time.perf_counter()
+            r = run_one(sub, torch, B, S, light=True)
+            configs[name] = summary_of(r)
+            configs[name]["bench_wall_s"] = time.perf_counter() - t0
+            torch.cuda.empty_cache()
+        result["configs"] = configs
+        # flat copies of the main figures (scalars survive any truncation of nested values)
+        flat = {}
+        for name, c in configs.items():
+            if name == "cfg3":
+                for k, v in c.items():
+                    if isinstance(v, dict):
+                        flat[f"cfg3_{k}_samples_per_s"] = v["samples_per_s"]
+                        flat[f"cfg3_{k}_iters_mean"] = v["iters_mean"]
+                continue
+            flat[f"{name}_samples_per_s"] = c["samples_per_s"]
+            flat[f"{name}_ms_per_step"] = c["ms_per_step"]
+            flat[f"{name}_iters_mean"] = c["iters_mean"]
+            flat[f"{name}_speedup_vs_seq"] = (c.get("sequential_whole_network") or {}).get("jacobi_speedup")
+            flat[f"{name}_roofline_bound"] = c["roofline"]["bound"]
+            flat[f"{name}_roofline_frac"] = c["roofline"]["frac"]
+            fb = c["roofline"].get("full_batch_launch")
+            flat[f"{name}_full_batch_frac"] = fb["frac"] if fb else None
+            flat[f"{name}_cpu_oracle_samples_per_s"] = (c.get("cpu_baseline") or {}).get("value")
+        result["config"].update(flat)
     print(json.dumps(result))
     return 0
 
