@@ -4,10 +4,9 @@
 #pragma once
 
 #ifdef JM_TRACE
-namespace jm {
+// (included from inside namespace jm)
 __device__ unsigned long long g_tile_trace[1024 * 8];      // [workgroup][stamp 0..7]
 __device__ unsigned long long g_trace[64 * 256 * 5];        // persistent kernel: [barrier][workgroup][stage 1..5]
-}  // namespace jm
 #define JM_TSTAMP(i, drain)                                                           \
   do {                                                                                \
     if (drain) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");            \

@@ -1661,9 +1661,10 @@ __global__ __launch_bounds__(256) void conv_layer_kernel(ConvLayerArgs a) {
   // weights: row group = output channel tile, chunk index = tap * KCH + c, tap = (dy + MID) * KS + (dx + MID)
   const size_t wgroup = (size_t)(MID * KS + MID + 1) * KCH * 256;
   const uint4* Wp = (const uint4*)a.w + (size_t)ct * wgroup + h * 32 + r;
-  // Two weight buffers: step p uses buffer p % 2, and as soon as the MFMAs of one dy are issued that dy's
-  // fragment of the buffer is re-requested for step p + 2, so a fragment has close to two steps to arrive.
-  uint4 wbuf[2][NDY][4];
+  // Three weight buffers: step p uses buffer p % 3; at its start the fragments of step p + 2 are requested into the
+  // buffer step p - 1 has just finished with, so a fragment has two whole steps (> 1 us) to arrive from L2.
+  constexpr int NBUF = 3;
+  uint4 wbuf[NBUF][NDY][4];
   auto load_weight_frag = [&](int it, auto D, uint4 (&dst)[4]) {
     constexpr int dyi = decltype(D)::value;
     const int dxi = it / KCH, c = it - dxi * KCH;
@@ -1744,66 +1745,73 @@ __global__ __launch_bounds__(256) void conv_layer_kernel(ConvLayerArgs a) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[o][e] = 0.f;
 
-  // The first PRE input fragments of a step are read from LDS during the step before it, so that the MFMAs
-  // of a step do not start behind a burst of LDS reads of all four waves.
-  constexpr int NJ = RW + MID;                          // input rows a wave walks per step
-  constexpr int PRE = NJ < 2 ? NJ : 2;
-  uint4 pre[PRE][4];
+  // A step walks down the wave's input rows j = 0 .. RW + (visible dy) - 2 (LDS row j holds image row
+  // y0 + wrow - MID + j): the fragment of row j feeds the output rows o = j - dyi of every visible dy, i.e. up to
+  // MID + 1 MFMA groups, and is then dead.  Fragments are read from LDS AHEAD input rows before they are used,
+  // through a ring of AHEAD + 1 register sets, continuing across step boundaries, so that the LDS latency is
+  // covered by the MFMAs of the rows in between and only AHEAD + 1 fragments are live at a time (holding all
+  // RW + MID fragments of a step at once cost 64 registers more and left their reads exposed at every step's
+  // start).  A step has NJP row slots, NJ = RW + MID rounded up to a multiple of the ring size, so that slot j
+  // always uses register set j % RING; slots without a row do nothing but the reads ahead.
+  constexpr int NJ = RW + MID;
+  constexpr int AHEAD = 2, RING = AHEAD + 1;
+  constexpr int NJP = (NJ + RING - 1) / RING * RING;
+  static_assert(NJP >= AHEAD, "a step must have room for the reads ahead");
+  uint4 af[RING][4];
+  auto read_row = [&](const uint4* base, int j, uint4 (&dst)[4]) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) dst[s] = base[(size_t)j * ROWBLK + s * 2 * PADW];
+  };
   {
     const uint4* base = frag_ptr(step_of(0));
-#pragma unroll
-    for (int j = 0; j < PRE; ++j)
-#pragma unroll
-      for (int s = 0; s < 4; ++s) pre[j][s] = base[(size_t)j * ROWBLK + s * 2 * PADW];
+    static_for<AHEAD>([&](auto J) { read_row(base, decltype(J)::value, af[decltype(J)::value]); });
   }
-  // one step: p = its index in this workgroup's order, BUF = p % 2
+  // one step: p = its index in this workgroup's order, BUF = p % NBUF
   auto one_step = [&](auto NV, auto BUF, int p) {
     constexpr int n_visible = decltype(NV)::value;             // visible dy of this step
     constexpr int buf = decltype(BUF)::value;
+    constexpr int rows_used = RW + n_visible - 1;              // input rows this step reads
     const uint4* base = frag_ptr(step_of(p));
     const uint4* base_next = frag_ptr(step_of(p + 1 < N_IT ? p + 1 : p));
-    const bool more = p + 2 < N_IT;
-    const int it_pre = step_of(more ? p + 2 : p);              // the step this buffer serves next
-    uint4 af[NJ][4];
-#pragma unroll
-    for (int j = 0; j < PRE; ++j)
-#pragma unroll
-      for (int s = 0; s < 4; ++s) af[j][s] = pre[j][s];
-#pragma unroll
-    for (int j = PRE; j < NJ; ++j)
-#pragma unroll
-      for (int s = 0; s < 4; ++s) af[j][s] = base[(size_t)j * ROWBLK + s * 2 * PADW];
+    if (p + 2 < N_IT) {                                        // weights of step p + 2
+      const int it2 = step_of(p + 2);
+      static_for<NDY>([&](auto D) {
+        if (decltype(D)::value < MID || it2 < N_A) load_weight_frag(it2, D, wbuf[(buf + 2) % NBUF][decltype(D)::value]);
+      });
+    }
     // (the scheduler otherwise sinks every load to just before its first use, to save registers, and the
     // wave then waits out each L2 and LDS latency in turn)
     __builtin_amdgcn_sched_barrier(0);
-    static_for<n_visible>([&](auto D) {
-      constexpr int dyi = decltype(D)::value;                  // dy = dyi - MID reads input row j = o + dyi
-      static_for<RW>([&](auto O) {
-        constexpr int o = decltype(O)::value;
-        mfma_chunk<T>(wbuf[buf][dyi], af[o + dyi], acc[o]);   // (channels = rows of the result)
-      });
-      if constexpr (dyi == 0) {                                // first fragments of the next step's input
-#pragma unroll
-        for (int jj = 0; jj < PRE; ++jj)
-#pragma unroll
-          for (int s = 0; s < 4; ++s) pre[jj][s] = base_next[(size_t)jj * ROWBLK + s * 2 * PADW];
+    static_for<NJP>([&](auto J) {
+      constexpr int j = decltype(J)::value;
+      constexpr int ja = j + AHEAD;                            // the row read now, used AHEAD slots later
+      if constexpr (ja < NJP) {
+        if constexpr (ja < rows_used) read_row(base, ja, af[ja % RING]);
+      } else {
+        read_row(base_next, ja - NJP, af[(ja - NJP) % RING]);  // (rows 0 .. AHEAD-1 exist in every step)
       }
-      if (more && (dyi < MID || it_pre < N_A)) load_weight_frag(it_pre, D, wbuf[buf][dyi]);
+      if constexpr (j < rows_used) {
+        static_for<n_visible>([&](auto D) {
+          constexpr int dyi = decltype(D)::value, o = j - dyi;  // dy = dyi - MID reads input row j = o + dyi
+          if constexpr (o >= 0 && o < RW) mfma_chunk<T>(wbuf[buf][dyi], af[j % RING], acc[o]);   // (channels = rows of the result)
+        });
+      }
       __builtin_amdgcn_sched_barrier(0);
     });
     if (p == 0) JM_TSTAMP(2, 0);
     if (p == 4) JM_TSTAMP(3, 0);
   };
-  // run A: steps 0 .. N_A-1 (dx <= 0), run B: steps N_A .. N_IT-1 (dx > 0); buffers alternate throughout
-  auto run_steps = [&](auto NV, auto PARITY, int p_begin, int p_end) {
-    constexpr int par = decltype(PARITY)::value;
-    for (int p = p_begin; p < p_end; p += 2) {
-      one_step(NV, std::integral_constant<int, par>{}, p);
-      if (p + 1 < p_end) one_step(NV, std::integral_constant<int, 1 - par>{}, p + 1);
+  // run A: steps 0 .. N_A-1 (dx <= 0), run B: steps N_A .. N_IT-1 (dx > 0); buffers rotate throughout
+  auto run_steps = [&](auto NV, auto PHASE, int p_begin, int p_end) {
+    constexpr int ph = decltype(PHASE)::value;
+    for (int p = p_begin; p < p_end; p += NBUF) {
+      one_step(NV, std::integral_constant<int, ph>{}, p);
+      if (p + 1 < p_end) one_step(NV, std::integral_constant<int, (ph + 1) % NBUF>{}, p + 1);
+      if (p + 2 < p_end) one_step(NV, std::integral_constant<int, (ph + 2) % NBUF>{}, p + 2);
     }
   };
   run_steps(std::integral_constant<int, NDY>{}, std::integral_constant<int, 0>{}, 0, N_A);
-  run_steps(std::integral_constant<int, MID>{}, std::integral_constant<int, N_A % 2>{}, N_A, N_IT);
+  run_steps(std::integral_constant<int, MID>{}, std::integral_constant<int, N_A % NBUF>{}, N_A, N_IT);
   JM_TSTAMP(4, 0);
 
   // epilogue: acc[o][4 g + c] = channel ch0 + 8 g + c of pixel r in output row o.  Four consecutive channels are
