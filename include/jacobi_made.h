@@ -287,7 +287,16 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   decision margin vanishes (see resident.hpp).
  *   MADE_OPT_PREFIX_CACHE (default 1): GS-Jacobi on the masked MLP keeps the activations of the hidden units whose
  *   inputs all lie before the current block (degree <= block start: they are final) after the block's first
- *   pass and only re-evaluates the units behind them; 0 re-evaluates every visible unit in every pass.
+ *   pass and only re-evaluates the units behind them (1); 0 re-evaluates every visible unit in every pass.  2: in
+ *   addition, on batches (chains) of at least MADE_OPT_PARTIAL_SUM_BATCH samples (default 1024) and Bernoulli
+ *   models, the contribution of the frozen inputs to the units that are still evaluated -- a sum that no longer
+ *   changes inside the block -- is computed once, in the block's second pass, and later passes only multiply the
+ *   inputs that can still change and add it (the caching argument the paper makes for its hybrid solvers, Section
+ *   4.2).  The split changes the order of the fp32 sums, so a decision within rounding of its threshold may fall
+ *   the other way than with 0 or 1.  Measured on the D = 784, 2 x 2000 network it does not pay at any batch up to
+ *   32768 (blocks of 16: 20.1 ms against 11.5 ms with 1 and 15.6 ms with 0): a block takes about three passes, the
+ *   slice of units that is still evaluated is one or two tiles wide, and its launches are bound by their fixed
+ *   costs, not by the length of the sums -- hence the default of 1.
  *   MADE_OPT_RETIRE_SPLIT (default 2048, >= 1): the stop test of a pass (which samples changed, the new active
  *   list) runs inside the pass's last kernel, in the workgroup that finishes last; batches (chains) of at least
  *   this many samples run it as a kernel of its own spread over the chip (one workgroup needs ~180 us for 32768
@@ -296,7 +305,7 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  */
 enum { MADE_OPT_PERSISTENT = 1, MADE_OPT_FUSED_CATEGORICAL = 2, MADE_OPT_CHAINS = 3, MADE_OPT_BIG_TILE_BATCH = 4,
        MADE_OPT_CONV_ROWS = 5, MADE_OPT_PREFIX_CACHE = 6, MADE_OPT_RESIDENT = 7, MADE_OPT_RETIRE_SPLIT = 8,
-       MADE_OPT_MID_TILE_BATCH = 9 };
+       MADE_OPT_MID_TILE_BATCH = 9, MADE_OPT_PARTIAL_SUM_BATCH = 10 };
 int made_set_option(made_model* m, int32_t option, int32_t value);
 
 /*

@@ -120,6 +120,7 @@ struct Chain {
   int first = 0, count = 0;
   size_t block = 0;                  // index into the call's block list
   int k_enq = 0, k_conf = 0;         // passes of the current block enqueued / whose result the host has seen
+  int bound_at_block_start = 0;      // the chain's size (a block restarts the list with every sample of the chain)
   int bound = 0;                     // upper limit of the active count in the current block: the chain's size, then
                                      // what the latest confirmed pass left (the list only shrinks inside a block)
   bool block_started = false, finished = false, iters_cleared = false;
@@ -143,6 +144,9 @@ struct Workspace {
   void* enc = nullptr;               // [N_pad, D_pad] network input of the current iterate
   std::vector<void*> act;            // hidden activations, [N_pad, pad(H_l)]
   float* zbuf = nullptr;             // categorical only: logits [N, D*C]
+  std::vector<float*> partial;       // GS-Jacobi partial-sum cache: per layer 0 .. L, [n_pad, out_pad] fp32 (allocated on
+  int partial_cap = 0;               // first use, for partial_cap samples)
+  float* zero_bias = nullptr;        // [largest out_pad] zeros: the launches that fill `partial` add no bias
   int* changed = nullptr;
   int* iters = nullptr;
   int* call_iters = nullptr;         // where the current call counts passes per sample: the caller's iters_out, else `iters`
@@ -208,7 +212,10 @@ struct made_model {
   std::vector<int64_t> prof_launches;         // [L+1]
   std::vector<int64_t> nnz;                   // [L+1] visible (mask = 1) weights per layer
   int persist_grid = 0;                       // workgroups of the persistent kernel (0 = not usable)
-  bool prefix_cache = true;                   // made_set_option(MADE_OPT_PREFIX_CACHE)
+  int prefix_cache = 1;                       // made_set_option(MADE_OPT_PREFIX_CACHE): 0 off, 1 frozen units' activations,
+                                              // 2 also the frozen inputs' partial sums, for lists of partial_batch samples on
+                                              // (measured slower than 1 at every batch up to 32768: not the default)
+  int partial_batch = 1024;                   // made_set_option(MADE_OPT_PARTIAL_SUM_BATCH)
   int big_batch = 1 << 30;                    // made_set_option(MADE_OPT_BIG_TILE_BATCH): 256 x 256 tiles from here on (off:
                                               // slower than 128 x 128 at every batch measured, up to 32768)
   int mid_batch = 1536;                       // made_set_option(MADE_OPT_MID_TILE_BATCH): 128 x 128 tiles from here up to
@@ -242,6 +249,9 @@ static void free_workspace(Workspace& w) {
   for (void* p : w.act)
     if (p) (void)hipFree(p);
   if (w.zbuf) (void)hipFree(w.zbuf);
+  for (float* p : w.partial)
+    if (p) (void)hipFree(p);
+  if (w.zero_bias) (void)hipFree(w.zero_bias);
   for (Chain& c : w.chains) free_chain(c);
   w.chains.clear();
   if (w.fork_ev) (void)hipEventDestroy(w.fork_ev);
@@ -427,7 +437,13 @@ extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
     return MADE_OK;
   }
   if (option == MADE_OPT_PREFIX_CACHE) {
-    m->prefix_cache = value != 0;
+    if (value < 0 || value > 2) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_PREFIX_CACHE=%d outside [0, 2]", value);
+    m->prefix_cache = value;
+    return MADE_OK;
+  }
+  if (option == MADE_OPT_PARTIAL_SUM_BATCH) {
+    if (value < 1) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_PARTIAL_SUM_BATCH=%d must be >= 1", value);
+    m->partial_batch = value;
     return MADE_OK;
   }
   if (option == MADE_OPT_CONV_ROWS) {
@@ -955,7 +971,10 @@ static void launch_big_t(LayerArgs a, int n_tiles, int n_rows_max, hipStream_t s
 template <int EPI>
 static void launch_layer(made_model* m, int layer, const LayerArgs& a, int n_tiles, int row_tiles, hipStream_t s) {
   prof_mark(m, layer, false, s);
-  const bool big = a.n_rows >= m->big_batch, mid = !big && a.n_rows >= m->mid_batch;
+  // (launches that start behind cached partial sums cover few units: they stay on the 32 x 32 tiles, whose grids are
+  // the larger ones there, and only that kernel takes k_begin / partial)
+  const bool small_only = a.partial != nullptr || a.k_begin > 0;
+  const bool big = !small_only && a.n_rows >= m->big_batch, mid = !small_only && !big && a.n_rows >= m->mid_batch;
   if (m->dtype == MADE_BF16) {
     if (big) launch_big_t<bf16_t, EPI, 4>(a, n_tiles, a.n_rows, s);
     else if (mid) launch_big_t<bf16_t, EPI, 2>(a, n_tiles, a.n_rows, s);
@@ -1006,8 +1025,16 @@ struct ActBuffers {
   void* act[64];         // (made_init admits at most 64 hidden layers)
 };
 
+// Cached partial sums of a GS-Jacobi block (see enqueue_pass): layer l multiplies only the inputs from k_first[l] on
+// and adds sums[l] (fp32 [sample, out_pad]) for the inputs before them.  Index L is the output layer.
+struct PartialSums {
+  const int* k_first;
+  float* const* sums;
+};
+
 static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, int in_limit0, hipStream_t s,
-                      const int* unit_first = nullptr, bool by_pos = false, const ActBuffers* buf = nullptr) {
+                      const int* unit_first = nullptr, bool by_pos = false, const ActBuffers* buf = nullptr,
+                      const PartialSums* ps = nullptr) {
   const int row_tiles = (rs.n_rows + TILE - 1) / TILE;
   const int kc = chunk_elems(m);
   int in_limit = in_limit0;
@@ -1020,6 +1047,11 @@ static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, in
     if (unit_limit && unit_limit[l] >= 0) tiles = std::min(tiles, (unit_limit[l] + TILE - 1) / TILE);
     if (in_limit >= 0) a.k_cap = std::min(ly.in_pad, round_up(in_limit, kc));
     if (unit_first) a.tile_begin = std::min(tiles, unit_first[l] / TILE);
+    if (ps && ps->k_first[l] > 0) {
+      a.k_begin = ps->k_first[l];
+      a.partial = ps->sums[l];
+      a.ld_partial = ly.out_pad;
+    }
     a.a_by_pos = by_pos && l > 0;
     a.out_by_pos = by_pos;
     if (l == 0 && m->onehot) {
@@ -1063,7 +1095,7 @@ static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, in
 
 // Output layer + draw for positions [t_lo, t_hi).  whole = evaluate every output tile regardless.
 static int run_output_sample(made_model* m, const RowSet& rs, const SampleIO& io, bool whole, int k_limit,
-                             hipStream_t s, bool by_pos = false) {
+                             hipStream_t s, bool by_pos = false, const PartialSums* ps = nullptr) {
   const Layer& ly = m->layers[m->L];
   const int row_tiles = (rs.n_rows + TILE - 1) / TILE;
   const int kc = chunk_elems(m);
@@ -1104,6 +1136,11 @@ static int run_output_sample(made_model* m, const RowSet& rs, const SampleIO& io
     a.t_hi = io.t_hi;
     a.retire = io.retire;
     a.io_aligned = (m->D % 16 == 0) && ((uintptr_t)io.noise % 16 == 0) && ((uintptr_t)io.x % 16 == 0);
+    if (ps && ps->k_first[m->L] > 0) {
+      a.k_begin = ps->k_first[m->L];
+      a.partial = ps->sums[m->L];
+      a.ld_partial = ly.out_pad;
+    }
     launch_layer<EPI_BERNOULLI>(m, m->L, a, tile_hi - tile_lo, row_tiles, s);
     m->stats[2]++;
   } else if (C == CAT_C && m->fused_categorical) {
@@ -1531,6 +1568,8 @@ struct Block {
   std::vector<int> hidden_frozen; // [L] when limited: units of degree <= a, whose inputs are positions before
                                   // the block: final, so their activations stay valid after the block's first pass
   int in_limit = -1, out_k_limit = -1;
+  std::vector<int> k_first;       // [L + 1] when limited: the inputs of layer l before k_first[l] (chunk-rounded) are
+                                  // frozen in this block: positions before a, resp. units of degree <= a
 };
 
 static Block make_block(const made_model* m, int a, int b, int cap, bool limited) {
@@ -1548,8 +1587,64 @@ static Block make_block(const made_model* m, int a, int b, int cap, bool limited
     for (int l = 0; l < m->L; ++l) blk.hidden_frozen[l] = m->cnt_lt[l][std::min(a + 1, m->D)];
     blk.in_limit = b - 1;
     blk.out_k_limit = blk.hidden_limit[m->L - 1];
+    const int kc = chunk_elems(m);
+    blk.k_first.resize(m->L + 1);
+    blk.k_first[0] = m->onehot ? 0 : a / kc * kc;      // (a one-hot first layer is a gather, not a product)
+    for (int l = 1; l <= m->L; ++l) blk.k_first[l] = blk.hidden_frozen[l - 1] / kc * kc;
   }
   return blk;
+}
+
+// The sums over a block's frozen inputs, for every layer and every unit that later passes of the block still
+// evaluate: P_l[sample, unit] = sum over the inputs i < k_first[l] of W_l[unit, i] * h_{l-1}[sample, i], from the
+// activations the block's first pass has left (frozen units are final after it).  Plain launches of the layer
+// kernels with the fp32 epilogue, K cut off at k_first[l], no bias, into one [n_pad, out_pad] buffer per layer.
+static int fill_partial_sums(made_model* m, const RowSet& rs, const Block& blk, hipStream_t s) {
+  Workspace& w = m->ws;
+  if ((int)w.partial.size() != m->L + 1 || w.partial_cap < w.n_pad) {
+    if (w.pending) {                                   // (queued kernels of an earlier call may still read the old buffers)
+      HIP_TRY(hipDeviceSynchronize());
+      w.pending = false;
+    }
+    for (float* p : w.partial)
+      if (p) (void)hipFree(p);
+    w.partial.assign(m->L + 1, nullptr);
+    int widest = 0;
+    for (int l = 0; l <= m->L; ++l) {
+      HIP_TRY(hipMalloc((void**)&w.partial[l], (size_t)w.n_pad * m->layers[l].out_pad * sizeof(float)));
+      widest = std::max(widest, m->layers[l].out_pad);
+    }
+    if (!w.zero_bias) {
+      HIP_TRY(hipMalloc((void**)&w.zero_bias, (size_t)widest * sizeof(float)));
+      HIP_TRY(hipMemset(w.zero_bias, 0, (size_t)widest * sizeof(float)));
+    }
+    w.partial_cap = w.n_pad;
+  }
+  const int row_tiles = (rs.n_rows + TILE - 1) / TILE;
+  for (int l = 0; l <= m->L; ++l) {
+    if (blk.k_first[l] <= 0) continue;
+    const Layer& ly = m->layers[l];
+    LayerArgs a = base_args(m, l, l == 0 ? w.enc : w.act[l - 1], rs);
+    a.bias = w.zero_bias;
+    a.k_cap = std::min(ly.in_pad, blk.k_first[l]);
+    a.out = w.partial[l];
+    a.ldo = ly.out_pad;
+    a.n_cols = ly.out_pad;
+    int tile_lo, tile_hi;
+    if (l < m->L) {
+      tile_hi = std::min(ly.n_tiles, (blk.hidden_limit[l] + TILE - 1) / TILE);
+      tile_lo = std::min(tile_hi, blk.hidden_frozen[l] / TILE);
+    } else {
+      tile_lo = (blk.a * m->C) / TILE;
+      tile_hi = (blk.b * m->C + TILE - 1) / TILE;
+    }
+    a.tile_begin = tile_lo;
+    if (tile_hi - tile_lo <= 0) continue;
+    launch_layer<EPI_LOGITS>(m, l, a, tile_hi - tile_lo, row_tiles, s);
+    m->stats[2]++;
+  }
+  HIP_TRY(hipGetLastError());
+  return MADE_OK;
 }
 
 // Enqueue the next pass of chain c's current block on the chain's stream.
@@ -1573,6 +1668,7 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
     c.block_started = true;
     c.bound = c.count;
   }
+  c.bound_at_block_start = c.count;
   const int k = c.k_enq + 1;
   const int in = (k - 1) & 1, out = k & 1;
   // (grids, tile shapes and the place of the stop test are chosen for at most c.bound active samples: late passes
@@ -1607,14 +1703,22 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
   } else {
     // (after a block's first pass the frozen prefix of every hidden layer is reused, not recomputed)
     const bool by_pos = hidden_by_position(m, rs, blk.limited);
+    // Partial-sum cache (GS-Jacobi on long lists): from a block's second pass on, a layer multiplies only the inputs
+    // that can still change and adds the sum over the frozen ones, which the block's second pass computes once
+    // (from the activations its first pass left) for the units that are still evaluated.
+    const bool cached = blk.limited && k > 1 && m->prefix_cache;
+    const bool use_partial = cached && m->prefix_cache == 2 && m->C == 1 && !m->real &&
+                             c.bound_at_block_start >= m->partial_batch && blk.cap > 2;
+    PartialSums ps{blk.k_first.data(), w.partial.data()};
+    if (use_partial && k == 2) TRY(fill_partial_sums(m, rs, blk, s));
     TRY(run_hidden(m, rs, blk.limited ? blk.hidden_limit.data() : nullptr, blk.in_limit, s,
-                   (blk.limited && k > 1 && m->prefix_cache) ? blk.hidden_frozen.data() : nullptr, by_pos));
+                   cached ? blk.hidden_frozen.data() : nullptr, by_pos, nullptr, use_partial ? &ps : nullptr));
     // a long list is retired by a kernel of its own, spread over the chip, instead of by the output kernel's
     // last workgroup
     const RetireArgs retire = io.retire;
     const bool split_retire = retire.enabled && n_bound >= m->retire_split;
     if (split_retire) io.retire.enabled = 0;
-    TRY(run_output_sample(m, rs, io, blk.whole_network, blk.out_k_limit, s, by_pos));
+    TRY(run_output_sample(m, rs, io, blk.whole_network, blk.out_k_limit, s, by_pos, use_partial ? &ps : nullptr));
     if (split_retire) {
       hipLaunchKernelGGL(retire_kernel, dim3((n_bound + RETIRE_WG_ROWS - 1) / RETIRE_WG_ROWS), dim3(256), 0, s, retire);
       HIP_TRY(hipGetLastError());

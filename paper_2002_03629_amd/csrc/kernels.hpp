@@ -166,6 +166,10 @@ struct LayerArgs {
   const float* bias;     // [out_pad]
   const int* tile_kend;  // per 32-unit tile: K extent that holds non-zero (visible) weights, chunk-rounded
   int k_cap;             // additional upper limit on K (chunk-rounded)
+  int k_begin;           // first K element this launch multiplies (chunk-rounded; 32 x 32 tile kernel only).  The
+                         // contribution of the inputs before it comes from `partial`:
+  const float* partial;  // [sample, ld_partial] fp32 sums over the inputs [0, k_begin) of every unit of the layer, added
+  int ld_partial;        // to the tile's own sum before bias and activation; NULL: nothing to add
   int tile_begin;        // first unit tile this launch covers
   int n_launch_tiles;    // unit tiles this launch covers
   int row_tiles;         // sample tiles this launch covers (upper bound; tiles beyond n_rows idle)
@@ -573,6 +577,10 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
     const int rr = (threadIdx.x >> 5) + j * (NW * 2);
     e_sample[j] = rows ? rows[row0 + rr] : (row0 + rr < a.n_rows ? row0 + rr : 0);
   }
+  float e_partial[EPT];
+#pragma unroll
+  for (int j = 0; j < EPT; ++j)
+    e_partial[j] = a.partial ? a.partial[(size_t)e_sample[j] * a.ld_partial + col] : 0.f;
   // A tile past the active list ends here (uniform).  The count was requested together with the loads above, so
   // looking at it now costs no round trip of its own; and nothing of the caller's memory (noise, symbols) has
   // been touched yet: a pass enqueued speculatively that finds the list empty reads the model's own memory only.
@@ -625,18 +633,20 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
 
   // Chunks wave, wave + NW, ... belong to this wave.  They are taken in straight-line groups: all loads of
   // a group are issued before its first MFMA (no branches inside a group, so nothing forces an early wait).
-  const int n_chunks = (k_end + KC - 1) / KC;
+  // (a launch may start behind the inputs whose contribution is cached: see LayerArgs::k_begin)
+  const int c_first = a.k_begin / KC;
+  const int n_chunks = max((k_end + KC - 1) / KC - c_first, 0);
   const int n_mine = (n_chunks - wave + NW - 1) / NW;   // wave-uniform (scalar)
   int base = 0;
-  for (; base + PD <= n_mine; base += PD) chunk_group<T, PD, COH>(Ap, Wp, base * NW + wave, acc);
+  for (; base + PD <= n_mine; base += PD) chunk_group<T, PD, COH>(Ap, Wp, c_first + base * NW + wave, acc);
   switch (n_mine - base) {
-    case 7: chunk_group<T, (PD > 7 ? 7 : 1), COH>(Ap, Wp, base * NW + wave, acc); break;
-    case 6: chunk_group<T, (PD > 6 ? 6 : 1), COH>(Ap, Wp, base * NW + wave, acc); break;
-    case 5: chunk_group<T, (PD > 5 ? 5 : 1), COH>(Ap, Wp, base * NW + wave, acc); break;
-    case 4: chunk_group<T, (PD > 4 ? 4 : 1), COH>(Ap, Wp, base * NW + wave, acc); break;
-    case 3: chunk_group<T, (PD > 3 ? 3 : 1), COH>(Ap, Wp, base * NW + wave, acc); break;
-    case 2: chunk_group<T, (PD > 2 ? 2 : 1), COH>(Ap, Wp, base * NW + wave, acc); break;
-    case 1: chunk_group<T, 1, COH>(Ap, Wp, base * NW + wave, acc); break;
+    case 7: chunk_group<T, (PD > 7 ? 7 : 1), COH>(Ap, Wp, c_first + base * NW + wave, acc); break;
+    case 6: chunk_group<T, (PD > 6 ? 6 : 1), COH>(Ap, Wp, c_first + base * NW + wave, acc); break;
+    case 5: chunk_group<T, (PD > 5 ? 5 : 1), COH>(Ap, Wp, c_first + base * NW + wave, acc); break;
+    case 4: chunk_group<T, (PD > 4 ? 4 : 1), COH>(Ap, Wp, c_first + base * NW + wave, acc); break;
+    case 3: chunk_group<T, (PD > 3 ? 3 : 1), COH>(Ap, Wp, c_first + base * NW + wave, acc); break;
+    case 2: chunk_group<T, (PD > 2 ? 2 : 1), COH>(Ap, Wp, c_first + base * NW + wave, acc); break;
+    case 1: chunk_group<T, 1, COH>(Ap, Wp, c_first + base * NW + wave, acc); break;
     default: break;
   }
 
@@ -661,6 +671,7 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
     float v = 0.f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) v += part[w][rr][cc];
+    v += e_partial[j];
     v += bias;
 
     if (EPI == EPI_RELU) {

@@ -135,10 +135,22 @@ def test_gs_jacobi_every_block_size(name):
         ref = O.gs_jacobi_reference(same, noise, 7, init)
         assert_counts_match(it, ref[1], ref[3])
         # the frozen-prefix reuse changes no bit: same symbols and pass counts with it switched off
+        B.made_set_option(g.h, B.MADE_OPT_PREFIX_CACHE, 1)
         x_on, it_on = g.gs_jacobi(noise, 16)
         B.made_set_option(g.h, B.MADE_OPT_PREFIX_CACHE, 0)
         x_off, it_off = g.gs_jacobi(noise, 16)
         assert (x_on == x_off).all() and (it_on == it_off).all()
+        # the partial-sum cache (forced on at this small batch) re-orders fp32 sums: same parity bar as every path
+        if w.C == 1:
+            B.made_set_option(g.h, B.MADE_OPT_PREFIX_CACHE, 2)
+            B.made_set_option(g.h, B.MADE_OPT_PARTIAL_SUM_BATCH, 1)
+            for block in (5, 16, 33, w.D - 1):
+                x, it = g.gs_jacobi(noise, block)
+                assert_sample_parity(same, noise, x, xs, margins)
+                ref = O.gs_jacobi_reference(same, noise, block)
+                assert_counts_match(it, ref[1], ref[3])
+            xi, iti = g.gs_jacobi(noise, 7, init)
+            assert_sample_parity(same, noise, xi, xs, margins)
 
 
 @pytest.mark.parametrize("name", ["cfg1", "small_f32", "small_bf16", "mid_bf16"])
