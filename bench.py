@@ -149,7 +149,7 @@ def cpu_baseline_conv(w, net, noise, budget_s=12.0):
 def measured_traffic(workload: str, path: str, dom_is_output: bool):
     """HBM bytes per launch of the dominant kernel, as measured with rocprofv3 PMC counters in a separate run
     (counters cannot be read from inside this process); the summary under profiles/ holds the figure."""
-    if workload not in ("cfg2", "cfg4") or path != "layers" or not dom_is_output:
+    if workload not in ("cfg2", "cfg4") or path == "persistent" or not dom_is_output:
         return None
     fn = os.path.join(ROOT, "profiles", f"{workload}_jacobi_pmc_traffic.txt")
     try:
@@ -280,8 +280,9 @@ def parse_args(argv=None):
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip sequential / GS-Jacobi side measurements")
-    ap.add_argument("--path", choices=["persistent", "layers"], default="layers",
-                    help="persistent: one cooperative launch per call; layers: one launch per layer and pass")
+    ap.add_argument("--path", choices=["persistent", "layers", "default"], default="default",
+                    help="persistent: one cooperative launch per call; layers: one launch per layer and pass; default: "
+                         "the library's own choice (small Bernoulli batches: one launch per call, XCD by XCD)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (supplementary sweeps)")
     ap.add_argument("--big-tile-batch", type=int, default=0,
                     help="batch size from which the 256 x 256 tile kernels are used (0 = library default)")
@@ -324,6 +325,8 @@ def run_one(args, torch, B, S, light=False):
         net = S.make_network(w)
         model = B.model_from_network(net)
     B.made_set_option(model, B.MADE_OPT_PERSISTENT, int(args.path == "persistent"))
+    if args.path == "layers":
+        B.made_set_option(model, B.MADE_OPT_XCD_RESIDENT, 0)
     if args.chains > 0:
         B.made_set_option(model, B.MADE_OPT_CHAINS, args.chains)
     if args.conv_rows > 0:
@@ -449,7 +452,8 @@ def run_one(args, torch, B, S, light=False):
                       f"conv_layer_kernel (k x k masked convolution as implicit GEMM, all {n_layers - 2} such layers)"
                       if dom < n_layers - 1 else "conv_head_kernel (1 x 1 head + Gumbel-max)")
     elif dom == n_layers:
-        layer_name = "persistent_sampler_kernel (all passes of a call: hidden layers, output layer + sampling, stop test)"
+        layer_name = ("persistent_sampler_kernel" if args.path == "persistent" else "xcd_sampler_kernel") + \
+                     " (all passes of a call in one launch: hidden layers, output layer + sampling, stop test)"
     else:
         if dom == n_layers - 1 and w.C == 256:
             layer_name = "categorical_output_kernel (output layer + Gumbel-max draw + stop test)"
@@ -699,7 +703,7 @@ def main() -> int:
         return bench_rnn(args, torch, B, S)
     result = run_one(args, torch, B, S)
     multi = (args.workload == "cfg2" and not args.single and not args.pmc_probe and not args.batch and not args.gain
-             and args.path == "layers" and not args.no_extras)
+             and args.path == "default" and not args.no_extras)
     if multi:
         # The headline (`value`, `roofline`, `cpu_baseline`) is cfg2, the configuration of the paper's MADE
         # experiment; the other benchmark configurations are timed in the same run, each as its own model.

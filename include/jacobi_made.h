@@ -261,6 +261,14 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   batch <= 2048 from ONE cooperative launch that keeps a workgroup per CU resident and separates layers by
  *   a grid-wide barrier; 0 = one kernel launch per layer and pass.  Same results either way; on MI355X the
  *   per-layer launches are currently the faster of the two at batch 128, hence the default.
+ *   MADE_OPT_XCD_RESIDENT (default 1; 0, 1 or 2): jacobi_sample / gs_jacobi_sample of Bernoulli models in ONE launch in
+ *   which every XCD (a group of compute units with an L2 of its own) iterates its own eighth of the samples through
+ *   all passes, synchronising only among its own workgroups and through its own L2 -- samples are independent
+ *   systems, so nothing has to cross the chip.  0 = never; 1 = where it was measured faster than one launch per layer
+ *   and pass: gs_jacobi_sample up to 1024 samples (1.5-2x), jacobi_sample up to 512 samples on models whose layers are
+ *   at most 1024 units wide (1.2-1.3x; on wider layers a phase of this kernel costs more than a launch); 2 = whenever
+ *   the batch fits (2048 samples).  Same symbols and pass counts as the per-layer launches.  The kernel checks that its workgroups sit on the XCDs it assumes and are
+ *   all resident; if not it backs out, and this and every later call on the model take the per-layer launches.
  *   MADE_OPT_FUSED_CATEGORICAL (default 1): for C = 256, draw the Gumbel-max symbols inside the output layer's
  *   kernel (logits stay in registers); 0 = write the logits to scratch memory and draw in a second kernel, as
  *   models with other C always do.
@@ -305,7 +313,7 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  */
 enum { MADE_OPT_PERSISTENT = 1, MADE_OPT_FUSED_CATEGORICAL = 2, MADE_OPT_CHAINS = 3, MADE_OPT_BIG_TILE_BATCH = 4,
        MADE_OPT_CONV_ROWS = 5, MADE_OPT_PREFIX_CACHE = 6, MADE_OPT_RESIDENT = 7, MADE_OPT_RETIRE_SPLIT = 8,
-       MADE_OPT_MID_TILE_BATCH = 9, MADE_OPT_PARTIAL_SUM_BATCH = 10 };
+       MADE_OPT_MID_TILE_BATCH = 9, MADE_OPT_PARTIAL_SUM_BATCH = 10, MADE_OPT_XCD_RESIDENT = 11 };
 int made_set_option(made_model* m, int32_t option, int32_t value);
 
 /*

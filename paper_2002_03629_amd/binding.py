@@ -281,6 +281,7 @@ MADE_OPT_RESIDENT = 7
 MADE_OPT_RETIRE_SPLIT = 8
 MADE_OPT_MID_TILE_BATCH = 9
 MADE_OPT_PARTIAL_SUM_BATCH = 10
+MADE_OPT_XCD_RESIDENT = 11
 
 
 def made_set_option(model: int, option: int, value: int) -> None:

@@ -159,6 +159,9 @@ struct Workspace {
   unsigned* bar = nullptr;           // persistent kernel: grid barrier counter
   long long* dev_stats = nullptr;    // persistent kernel: [passes, sample-passes]
   volatile int* h_pin = nullptr;     // pinned host words: [0] flags copy, [2..5] persistent kernel's statistics
+  volatile int* xcd_report = nullptr;     // pinned, device-visible: what xcd_sampler_kernel reports (8 words per XCD + flags)
+  int* xcd_report_dev = nullptr;     // the same memory as the device addresses it
+  unsigned xcd_calls = 0;            // calls served by xcd_sampler_kernel on this workspace
 };
 
 // Masked convolutional model (arch 1): first layer 3 -> F (type A), n_conv - 1 layers F -> F (type B), 1 x 1 head.
@@ -223,7 +226,10 @@ struct made_model {
   int n_chains = 1;                           // made_set_option(MADE_OPT_CHAINS)
   int retire_split = 2048;                    // made_set_option(MADE_OPT_RETIRE_SPLIT); +4 % at batch 2048, +9 % at 4096 over the fused tail
   int fused_categorical = 1;                  // made_set_option(MADE_OPT_FUSED_CATEGORICAL)
-  int use_persistent = 0;                     // made_set_option(MADE_OPT_PERSISTENT); off: measured slower, see header
+  int use_persistent = 0;                     // made_set_option(MADE_OPT_PERSISTENT): 1 = the device-wide cooperative kernel
+                                              // (measured slower, see header)
+  int use_xcd = 1;                            // made_set_option(MADE_OPT_XCD_RESIDENT): 0 never, 1 where it pays, 2 whenever possible
+  int xcd_grid = 0;                           // workgroups of xcd_sampler_kernel (0 = not usable on this device / model)
   // sample-resident kernel (resident_sampler_kernel): LDS layout, 0 bytes = this model does not fit
   int use_resident = 2;                       // made_set_option(MADE_OPT_RESIDENT): 0 never, 1 whenever it fits, 2 where it pays
   int res_lds_bytes = 0, res_lds_enc = 0, res_lds_clear = 0;
@@ -261,6 +267,7 @@ static void free_workspace(Workspace& w) {
   if (w.iters) (void)hipFree(w.iters);
   if (w.flags) (void)hipFree(w.flags);
   if (w.h_pin) (void)hipHostFree((void*)w.h_pin);
+  if (w.xcd_report) (void)hipHostFree((void*)w.xcd_report);
   w = Workspace();
 }
 
@@ -329,11 +336,19 @@ static int ensure_workspace(made_model* m, int N, bool need_z) {
   HIP_TRY(hipEventCreateWithFlags(&w.fork_ev, hipEventDisableTiming));
   HIP_TRY(hipMalloc((void**)&w.changed, (size_t)2 * n_pad * CHG * sizeof(int)));   // one counter per 128-byte line
   w.n_pad = n_pad;
-  HIP_TRY(hipMalloc((void**)&w.bar, sizeof(unsigned)));
-  HIP_TRY(hipMalloc((void**)&w.dev_stats, 2 * sizeof(long long)));
+  // (xcd_sampler_kernel: per XCD a flag array for its barrier and a counter for the registration of its workgroups,
+  // and the word in which it keeps counting its barriers from call to call)
+  HIP_TRY(hipMalloc((void**)&w.bar, (size_t)(2 * XCDS * XCD_LINE + XCDS * 32) * sizeof(unsigned)));
+  HIP_TRY(hipMemset(w.bar, 0, (size_t)(2 * XCDS * XCD_LINE + XCDS * 32) * sizeof(unsigned)));
+  HIP_TRY(hipHostMalloc((void**)&w.xcd_report, (size_t)(8 * XCDS + 8) * sizeof(int), hipHostMallocMapped));
+  HIP_TRY(hipHostGetDevicePointer((void**)&w.xcd_report_dev, (void*)w.xcd_report, 0));
+  for (int i = 0; i < 8 * XCDS + 8; ++i) w.xcd_report[i] = 0;
+  w.xcd_calls = 0;
+  HIP_TRY(hipMalloc((void**)&w.dev_stats, (size_t)2 * XCDS * sizeof(long long)));
   HIP_TRY(hipMalloc((void**)&w.iters, (size_t)n_pad * sizeof(int)));
   HIP_TRY(hipMalloc((void**)&w.flags, sizeof(int)));
-  HIP_TRY(hipHostMalloc((void**)&w.h_pin, 8 * sizeof(int), hipHostMallocDefault));
+  HIP_TRY(hipMemset(w.flags, 0, sizeof(int)));
+  HIP_TRY(hipHostMalloc((void**)&w.h_pin, (8 + 4 * XCDS) * sizeof(int), hipHostMallocDefault));
   w.N_cap = cap;
   return MADE_OK;
 }
@@ -425,6 +440,11 @@ extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
   if (!m) return fail(MADE_ERR_ARG, "made_set_option: model is NULL");
   if (option == MADE_OPT_PERSISTENT) {
     m->use_persistent = value != 0;
+    return MADE_OK;
+  }
+  if (option == MADE_OPT_XCD_RESIDENT) {
+    if (value < 0 || value > 2) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_XCD_RESIDENT=%d outside [0, 2]", value);
+    m->use_xcd = value;
     return MADE_OK;
   }
   if (option == MADE_OPT_FUSED_CATEGORICAL) {
@@ -692,6 +712,15 @@ extern "C" int made_init(const made_config* cfg, const int32_t* const* degrees, 
                ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, persistent_sampler_kernel<bf16_t>, NW * 64, 0)
                : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, persistent_sampler_kernel<float>, NW * 64, 0);
     if (pe == hipSuccess && coop && per_cu >= 1 && C == 1 && L + 1 <= PERSIST_MAX_LAYERS) m->persist_grid = cus;
+    // The XCD-local kernel wants two workgroups per compute unit resident at once on a chip of 8 XCDs.
+    int per_cu_x = 0;
+    if (pe == hipSuccess)
+      pe = m->dtype == MADE_BF16
+               ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_x, xcd_sampler_kernel<bf16_t>, NW * 64, 0)
+               : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_x, xcd_sampler_kernel<float>, NW * 64, 0);
+    if (pe == hipSuccess && per_cu_x >= 1 && cus >= XCDS && cus % XCDS == 0 && C == 1 && !m->real &&
+        L + 1 <= PERSIST_MAX_LAYERS)
+      m->xcd_grid = std::min(cus * std::min(per_cu_x, 2), XCDS * XCD_LINE);
     (void)hipGetLastError();
   }
   // The sample-resident kernel keeps one 32-sample row group of the input and of every hidden layer, the biases
@@ -2012,6 +2041,127 @@ static int run_persistent(made_model* m, const float* noise, int N, const uint8_
   return MADE_OK;
 }
 
+// The whole call in one launch, each XCD iterating its own share of the samples (see xcd_sampler_kernel).  *done = true
+// when the call was served this way; when the kernel backs out (workgroups not on the expected XCD, or not
+// co-resident) the path is switched off for this model and the caller takes the per-layer launches.
+static int run_xcd(made_model* m, const float* noise, int N, const uint8_t* x_init, uint8_t* x, int block,
+                   int cap, bool flag_unconverged, int32_t* iters_out, hipStream_t s, bool* done) {
+  *done = false;
+  if (m->arch != 0 || m->real || m->C != 1 || !m->use_xcd || m->xcd_grid <= 0) return MADE_OK;
+  const int per = (N + XCDS - 1) / XCDS;
+  if (per > XCD_MAX_ROWS) return MADE_OK;
+  // Where it pays (use_xcd = 1), measured on MI355X against the per-layer launches: the short passes of GS-Jacobi
+  // blocks up to 1024 samples (D = 784, 2 x 2000: 1.2 against 2.3 ms for blocks of 16 at batch 128, 2.3 against 3.4 ms
+  // at 1024); whole-network Jacobi passes only while a layer is at most 32 unit tiles wide and the batch at most 512
+  // (196 / 2 x 500: 0.075 against 0.098 ms; 784 / 2 x 2000: 0.124 against 0.105 ms -- there a phase of this kernel,
+  // with its device-scope operand loads and its barrier, costs more than a launch).
+  if (m->use_xcd == 1) {
+    int widest = 0;
+    for (int l = 0; l <= m->L; ++l) widest = std::max(widest, m->layers[l].n_tiles);
+    const bool gs = block < m->D;
+    if (gs ? N > 1024 : (N > 512 || widest > 32)) return MADE_OK;
+  }
+  Workspace& w = m->ws;
+  PersistArgs p;
+  memset(&p, 0, sizeof p);
+  for (int l = 0; l <= m->L; ++l) {
+    const Layer& ly = m->layers[l];
+    PersistLayer& pl = p.layer[l];
+    pl.W = ly.W;
+    pl.bias = ly.bias;
+    pl.tile_kend = ly.tile_kend;
+    pl.cnt_lt = ly.cnt_lt;
+    pl.out = l < m->L ? w.act[l] : nullptr;
+    pl.in_pad = ly.in_pad;
+    pl.k_chunks = ly.k_chunks;
+    pl.n_tiles = ly.n_tiles;
+    pl.out_dim = ly.out_dim;
+    pl.out_chunks = l < m->L ? m->layers[l + 1].k_chunks : 0;
+  }
+  p.L = m->L;
+  p.enc = w.enc;
+  p.enc_chunks = m->layers[0].k_chunks;
+  p.noise = noise;
+  p.x_init = x_init;
+  p.x = x;
+  p.N = N;
+  p.D = m->D;
+  p.block = block;
+  p.cap = cap;
+  p.flag_unconverged = flag_unconverged;
+  p.changed = w.changed;
+  p.n_pad = w.n_pad;
+  p.iters = iters_out ? iters_out : w.iters;
+  p.flags = w.flags;
+  p.bar = w.bar;
+  p.stats = w.dev_stats;
+  p.spin_limit = 1u << 20;
+  p.reg_base = w.xcd_calls * (unsigned)(m->xcd_grid / XCDS);
+  p.call_id = (int)(++w.xcd_calls);
+  p.host_report = w.xcd_report_dev;
+  // The device flags are only ever set when the kernel backs out (after which this path is switched off), but the
+  // per-layer scheduler and the persistent kernel share the word: the stream-ordered clear costs one small memset.
+  HIP_TRY(hipMemsetAsync(w.flags, 0, sizeof(int), s));
+  prof_mark(m, m->L + 1, false, s);
+  if (m->dtype == MADE_BF16)
+    hipLaunchKernelGGL(xcd_sampler_kernel<bf16_t>, dim3(m->xcd_grid), dim3(NW * 64), 0, s, p);
+  else
+    hipLaunchKernelGGL(xcd_sampler_kernel<float>, dim3(m->xcd_grid), dim3(NW * 64), 0, s, p);
+  prof_mark(m, m->L + 1, true, s);
+  HIP_TRY(hipGetLastError());
+  m->stats[2] += 1;
+  // Every XCD's first workgroup reports into pinned memory once its share of the batch is done; the call returns
+  // when all have (results stay ordered on the stream like those of any launch).
+  const auto t0 = std::chrono::steady_clock::now();
+  uint64_t polls = 0;
+  bool backed_out = false;
+  for (;;) {
+    if (w.xcd_report[64] != 0) { backed_out = true; break; }
+    int n_done = 0;
+    for (int g = 0; g < XCDS; ++g) n_done += (w.xcd_report[g * 8 + 5] == p.call_id);
+    if (n_done == XCDS) break;
+    if ((++polls & 0xfff) == 0 && std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() > 30.0)
+      return give_up_waiting(m, s);
+  }
+  if (m->profiling || backed_out) {
+    HIP_TRY(hipStreamSynchronize(s));
+    m->stats[3] += 1;
+    w.pending = false;
+  } else {
+    w.pending = true;                // (workgroups may still be leaving the kernel; they touch nothing any more)
+    w.pending_stream = s;
+  }
+  prof_collect(m);
+  if (backed_out || w.xcd_report[64] != 0) {     // results are incomplete: take the other path from now on
+    const int flags = w.xcd_report[64];
+    unsigned counters[2 * XCDS * XCD_LINE];
+    memset(counters, 0, sizeof counters);
+    (void)hipMemcpy(counters, w.bar, sizeof counters, hipMemcpyDeviceToHost);
+    char detail[256];
+    int off = 0;
+    for (int g = 0; g < XCDS; ++g)
+      off += snprintf(detail + off, sizeof detail - off, " %u", counters[(XCDS + g) * XCD_LINE] - p.reg_base);
+    (void)fail(MADE_OK, "xcd_sampler_kernel backed out (flags %d: 4 = more workgroups on an XCD than expected, 2 = a "
+                        "barrier's wait ran out; workgroups registered per XCD:%s; expected %d each); per-layer launches "
+                        "serve this model from now on", flags, detail, m->xcd_grid / XCDS);
+    m->xcd_grid = 0;
+    m->stats[2] = 0;
+    w.xcd_report[64] = 0;
+    return MADE_OK;
+  }
+  int call_flags = 0;
+  for (int g = 0; g < XCDS; ++g) {
+    const volatile int* r = w.xcd_report + g * 8;
+    const int64_t passes = ((int64_t)r[1] << 32) | (uint32_t)r[0], sp = ((int64_t)r[3] << 32) | (uint32_t)r[2];
+    m->stats[0] = std::max<int64_t>(m->stats[0], passes);
+    m->stats[1] += sp;
+    call_flags |= r[4];
+  }
+  *done = true;
+  if (call_flags & 1) return fail(MADE_ERR_NOT_CONVERGED, "samples were still changing after the last allowed pass");
+  return MADE_OK;
+}
+
 // The whole call in one launch of the sample-resident kernel (see resident_sampler_kernel): one workgroup per 32
 // samples.  Returns 1 in *done when the call was served this way.
 static int run_resident(made_model* m, const float* noise, int N, const uint8_t* x_init, uint8_t* x, int block,
@@ -2090,7 +2240,11 @@ extern "C" int jacobi_sample(made_model* m, const float* noise, int32_t N, const
   bool done = false;
   TRY(run_persistent(m, noise, N, x_init, x_out, m->D, cap, cap < m->D, iters_out, s, &done));
   if (done) return MADE_OK;
+  if (N <= 256) TRY(run_xcd(m, noise, N, x_init, x_out, m->D, cap, cap < m->D, iters_out, s, &done));
+  if (done) return MADE_OK;
   TRY(run_resident(m, noise, N, x_init, x_out, m->D, cap, cap < m->D, iters_out, s, &done));
+  if (done) return MADE_OK;
+  if (N > 256) TRY(run_xcd(m, noise, N, x_init, x_out, m->D, cap, cap < m->D, iters_out, s, &done));
   if (done) return MADE_OK;
   std::vector<Block> blocks(1, make_block(m, 0, m->D, cap, false));
   return run_chains(m, blocks, noise, x_init, x_out, N, cap < m->D, iters_out, s);
@@ -2109,7 +2263,13 @@ extern "C" int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, co
   bool done = false;
   TRY(run_persistent(m, noise, N, x_init, x_out, block, m->D, false, iters_out, s, &done));
   if (done) return MADE_OK;
+  // (measured: the XCD-resident kernel is the faster of the two whole-call kernels up to ~256 samples, the
+  // sample-resident one -- where the model fits it -- beyond)
+  if (N <= 256) TRY(run_xcd(m, noise, N, x_init, x_out, block, m->D, false, iters_out, s, &done));
+  if (done) return MADE_OK;
   TRY(run_resident(m, noise, N, x_init, x_out, block, m->D, false, iters_out, s, &done));
+  if (done) return MADE_OK;
+  if (N > 256) TRY(run_xcd(m, noise, N, x_init, x_out, block, m->D, false, iters_out, s, &done));
   if (done) return MADE_OK;
   std::vector<Block> blocks;
   for (int a = 0; a < m->D; a += block) {

@@ -553,7 +553,10 @@ __device__ __forceinline__ void chunk_group(const uint4* Ap, const uint4* Wp, in
 // rows/n_rows: the active-sample list (global or LDS memory) and its length; entries past n_rows are
 // stale but valid sample ids.  `part` is the workgroup's LDS scratch.  All threads of the workgroup
 // call this together; the tile (rel_tile, row0) is uniform.
-template <typename T, int EPI, bool COH>
+// XCD_LOCAL: every workgroup that touches this sample's counters runs on the same XCD (see xcd_sampler_kernel), so
+// the counter atomics need not leave that XCD's L2: workgroup-scope atomics (atomics are always performed in the
+// L2, and all of these workgroups share one) instead of device-scope ones, which go to the memory side.
+template <typename T, int EPI, bool COH, bool XCD_LOCAL = false>
 __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, int row0, const int* rows, int n_rows,
                                              float (*part)[TILE][TILE + 1]) {
   constexpr int EPL = Elem<T>::EPL;
@@ -676,7 +679,7 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
 
     if (EPI == EPI_RELU) {
       if (row_ok)
-        publish<COH>((T*)a.out + frag_offset<T>(a.out_by_pos ? a.pos_base + row0 + rr : sample, col, a.out_chunks),
+        publish<COH && !XCD_LOCAL>((T*)a.out + frag_offset<T>(a.out_by_pos ? a.pos_base + row0 + rr : sample, col, a.out_chunks),
                      Elem<T>::from_f32(fmaxf(v, 0.f)));
     } else if (EPI == EPI_LOGITS) {
       if (row_ok && col < a.n_cols) ((float*)a.out)[(size_t)sample * a.ldo + col] = v;
@@ -687,8 +690,8 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
       if (row_ok && col_live && (col & 1) == 0) {
         const float xn = v + expf(fminf(fmaxf(a_log, LOGISTIC_A_LO), LOGISTIC_A_HI)) * e_noise[j];
         if (xn != e_xr[j]) {
-          publish<COH>(a.xr + (size_t)sample * a.D + pos, xn);
-          publish<COH>((T*)a.enc + frag_offset<T>(sample, pos, a.enc_chunks), Elem<T>::from_f32(xn));
+          publish<COH && !XCD_LOCAL>(a.xr + (size_t)sample * a.D + pos, xn);
+          publish<COH && !XCD_LOCAL>((T*)a.enc + frag_offset<T>(sample, pos, a.enc_chunks), Elem<T>::from_f32(xn));
         }
         cnt = !(fabsf(xn - e_xr[j]) <= a.eps);     // (a NaN counts as changed)
       }
@@ -706,8 +709,8 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
         const uint8_t xn = e_noise[j] < p ? 1 : 0;
         cnt = (xn != e_xold[j]);
         if (cnt) {   // an unchanged symbol (and its encoding) is already in place
-          publish<COH>(a.x + (size_t)sample * a.D + col, xn);
-          publish<COH>((T*)a.enc + frag_offset<T>(sample, col, a.enc_chunks), Elem<T>::from_f32((float)xn));
+          publish<COH && !XCD_LOCAL>(a.x + (size_t)sample * a.D + col, xn);
+          publish<COH && !XCD_LOCAL>((T*)a.enc + frag_offset<T>(sample, col, a.enc_chunks), Elem<T>::from_f32((float)xn));
         }
       }
       // the 32 lanes of a half-wave hold one sample row of the tile
@@ -716,8 +719,12 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
       cnt += __shfl_xor(cnt, 4);
       cnt += __shfl_xor(cnt, 8);
       cnt += __shfl_xor(cnt, 16);
-      if (cc == 0 && cnt > 0)
-        count_old[j] = __hip_atomic_fetch_add(&a.changed[(size_t)sample * CHG], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (cc == 0 && cnt > 0) {
+        if constexpr (XCD_LOCAL)
+          count_old[j] = __hip_atomic_fetch_add(&a.changed[(size_t)sample * CHG], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        else
+          count_old[j] = __hip_atomic_fetch_add(&a.changed[(size_t)sample * CHG], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
     }
   }
   if (EPI == EPI_BERNOULLI || EPI == EPI_LOGISTIC) {
@@ -1132,6 +1139,14 @@ struct PersistArgs {
   unsigned* bar;         // grid barrier arrival counter (zero at launch)
   long long* stats;      // [0] passes, [1] sample-passes
   unsigned spin_limit;   // barrier gives up after this many polls (never reached unless the launch was not co-resident)
+  // xcd_sampler_kernel: nothing is reset between calls.  Barrier numbers continue where the XCD's previous call
+  // left them (a word behind the flag and registration arrays), registration counts continue from reg_base = calls
+  // so far x workgroups per XCD, and each XCD reports into its own 8 words of pinned host memory: [0..1] passes,
+  // [2..3] sample-passes (64 bit each), [4] flags, [5] = call_id once the rest is written; word 64 collects the
+  // back-out flags (2, 4) of all XCDs.
+  unsigned reg_base;
+  int call_id;
+  int* host_report;
 };
 
 // Grid-wide barrier for a cooperative (co-resident) launch.  Everything a workgroup wrote for others went
@@ -1325,6 +1340,252 @@ __global__ __launch_bounds__(NW * 64) void persistent_sampler_kernel(PersistArgs
   if (blockIdx.x == 0 && threadIdx.x == 0) {
     p.stats[0] = n_passes;
     p.stats[1] = n_sample_passes;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Whole call in one launch, XCD by XCD.
+//
+// Samples are independent systems, so nothing forces the workgroups of a whole-call kernel to synchronise across
+// the chip: XCD g (its 32 compute units share one L2) takes the samples [g * per, (g + 1) * per) through every
+// pass of Algorithm 1 / every block of Algorithm 3 on its own.  What its workgroups exchange -- activations,
+// symbols, changed counters -- is written by ordinary stores (the vector L1 writes through to the L2) and made
+// visible by waiting for those stores and a barrier among the XCD's workgroups on flag words that only they touch;
+// readers fetch it with device-scope loads, which go past their unit's L1 and are served by the L2 the writers
+// share with them.  (Two cheaper-looking ways to keep stale L1 lines out were tried: invalidating the L1 at every
+// barrier with workgroup scope does nothing on this chip outside threadgroup-split mode -- results went wrong --
+// and with device scope it made a phase cost 20 us.)  Nothing crosses to another XCD's L2, which is what made
+// each phase of the device-wide persistent kernel cost 10-15 us; here a phase is ~7 us on the D = 784, 2 x 2000
+// network (against 4.5-8 us for a launch of the per-layer kernels) and ~4 us on small ones.  A workgroup learns its XCD from the hardware's XCC id; the scheme
+// needs gridDim / 8 workgroups on each of the 8 XCDs, all resident at once.  If that does not hold the whole grid
+// backs out (flag 4: surplus workgroup on an XCD; flag 2: a barrier's bounded wait ran out), so the grid always
+// drains, and the host takes the per-layer path instead.
+// ------------------------------------------------------------------------------------------------
+constexpr int XCD_MAX_ROWS = 256;        // samples one XCD takes (its active list is kept in LDS)
+constexpr int XCD_LINE = 64;             // words per XCD in the barrier's flag array (one per workgroup of the XCD) and in the
+                                         // registration array: two cache lines that only this XCD's workgroups touch
+
+// Barrier among the n_group workgroups of one XCD.  Every workgroup owns one word of the XCD's flag array and
+// stores the number of the barrier it has reached there (after its threads' earlier stores have reached the L2);
+// the first wave of every workgroup then reads all the words with ONE load per poll (device-scope loads, served
+// by the L2 past this unit's L1) until none is behind.  No read-modify-write is involved, so arrivals and polls
+// do not queue up behind each other on one cache line as they do with a shared counter (measured: 64 workgroups
+// polling a counter with atomics took ~20 us per barrier).  The wait is bounded (see the kernel's comment).
+__device__ __forceinline__ bool xcd_barrier(unsigned* slots, int rank, unsigned& epoch, int n_group, int* flags,
+                                            unsigned spin_limit, int* host_flags) {
+  __shared__ int ok_s;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this thread's stores have reached the L2
+  __syncthreads();
+  epoch += 1;
+  if (threadIdx.x < 64) {
+    if (threadIdx.x == 0) slots[rank] = epoch;
+    int ok = 1;
+    unsigned spins = 0;
+    const int lane = threadIdx.x;
+    for (;;) {
+      const unsigned v = lane < n_group ? __hip_atomic_load(slots + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : epoch;
+      if (__all((int)(v - epoch) >= 0)) break;
+      __builtin_amdgcn_s_sleep(JM_SLEEP);
+      if (++spins > spin_limit ||
+          ((spins & 255) == 0 && (__hip_atomic_load(flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & 6))) {
+        if (lane == 0) {
+          __hip_atomic_fetch_or(flags, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_fetch_or(host_flags, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+        ok = 0;
+        break;
+      }
+    }
+    if (lane == 0) ok_s = ok;
+  }
+  __syncthreads();
+  return ok_s != 0;
+}
+
+// (second launch bound = waves per SIMD: two workgroups of 8 waves per compute unit, i.e. at most 128 registers)
+template <typename T>
+__global__ __launch_bounds__(NW * 64, 4) void xcd_sampler_kernel(PersistArgs p) {
+  __shared__ float part[NW][TILE][TILE + 1];
+  __shared__ int rows_s[XCD_MAX_ROWS];
+  __shared__ int wave_total[NW];
+  __shared__ int xcc_s, rank_s, unconverged_s;
+  constexpr int NT = NW * 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // Which XCD this workgroup runs on is read from the hardware; its rank among the XCD's workgroups is the order
+  // of arrival at a counter only they touch.  The dispatcher deals workgroups round-robin over the XCDs, so each is
+  // expected to receive gridDim / 8 of them: a surplus workgroup backs out here (flag 4), a missing one makes the
+  // first barrier's bounded wait run out (flag 2); either way the whole grid drains and the host falls back.
+  const int n_group = gridDim.x / XCDS;
+  if (threadIdx.x == 0) {
+    unsigned id;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(id));
+    id &= 0xf;
+    xcc_s = (int)id;
+    unconverged_s = 0;
+    rank_s = id < XCDS ? (int)(__hip_atomic_fetch_add(p.bar + (size_t)(XCDS + id) * XCD_LINE, 1u, __ATOMIC_RELAXED,
+                                                      __HIP_MEMORY_SCOPE_WORKGROUP) - p.reg_base)
+                       : n_group;
+  }
+  __syncthreads();
+  const int group = xcc_s, rank = rank_s;
+  if (group >= XCDS || rank < 0 || rank >= n_group) {
+    if (threadIdx.x == 0) {
+      __hip_atomic_fetch_or(p.flags, 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_fetch_or(p.host_report + 64, 4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    return;
+  }
+  const int N = p.N, D = p.D, L = p.L;
+  const int per = (N + XCDS - 1) / XCDS;                 // <= XCD_MAX_ROWS (host)
+  const int first = group * per, count = max(0, min(per, N - first));
+  int* report = p.host_report + group * 8;
+  if (count == 0) {                      // (barriers are per XCD: nobody waits for this one)
+    if (rank == 0 && threadIdx.x == 0) {
+      for (int i = 0; i < 5; ++i) __hip_atomic_store(report + i, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      __hip_atomic_store(report + 5, p.call_id, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    return;
+  }
+  unsigned* slots = p.bar + (size_t)group * XCD_LINE;
+  unsigned* epoch_word = p.bar + (size_t)2 * XCDS * XCD_LINE + group * 32;     // (a cache line per XCD)
+  unsigned epoch = *epoch_word;          // where this XCD's previous call stopped counting its barriers
+
+  // x = x_init (or zeros) and its network encoding, for this XCD's samples
+  for (size_t i = (size_t)rank * NT + threadIdx.x; i < (size_t)count * D; i += (size_t)n_group * NT) {
+    const int n = first + (int)(i / D), t = (int)(i % D);
+    const uint8_t v = p.x_init ? p.x_init[(size_t)n * D + t] : 0;
+    p.x[(size_t)n * D + t] = v;
+    ((T*)p.enc)[frag_offset<T>(n, t, p.enc_chunks)] = Elem<T>::from_f32((float)v);
+  }
+  if (rank == 0) {
+    for (int i = threadIdx.x; i < count; i += NT) {
+      p.iters[first + i] = 0;
+      p.changed[(size_t)(first + i) * CHG] = 0;
+      p.changed[(size_t)(p.n_pad + first + i) * CHG] = 0;
+    }
+  }
+  if (!xcd_barrier(slots, rank, epoch, n_group, p.flags, p.spin_limit, p.host_report + 64)) return;
+
+  long long n_passes = 0, n_sample_passes = 0;
+  int parity = 0;
+  const bool gs = p.block < D;
+  for (int a0 = 0; a0 < D; a0 += p.block) {
+    const int b0 = min(a0 + p.block, D);          // block = 0-based positions [a0, b0)
+    // entries past the active count are read as sample ids too (their results are discarded)
+    for (int i = threadIdx.x; i < XCD_MAX_ROWS; i += NT) rows_s[i] = first + (i < count ? i : 0);
+    int n_rows = count;
+    __syncthreads();
+    const int cap = gs ? (b0 - a0) : p.cap;
+    for (int k = 1; k <= cap && n_rows > 0; ++k) {
+      const int row_tiles = (n_rows + TILE - 1) / TILE;
+      int* changed = p.changed + (size_t)parity * p.n_pad * CHG;
+      int in_limit = gs ? b0 - 1 : -1;
+      for (int l = 0; l < L; ++l) {
+        const PersistLayer& ly = p.layer[l];
+        LayerArgs a = {};
+        a.A = l == 0 ? p.enc : p.layer[l - 1].out;
+        a.W = ly.W;
+        a.k_chunks = ly.k_chunks;
+        a.bias = ly.bias;
+        a.tile_kend = ly.tile_kend;
+        a.k_cap = ly.in_pad;
+        if (in_limit >= 0) a.k_cap = min(ly.in_pad, (in_limit + 2 * Elem<T>::EPL - 1) / (2 * Elem<T>::EPL) * (2 * Elem<T>::EPL));
+        a.n_rows = N;
+        a.out = ly.out;
+        a.out_chunks = ly.out_chunks;
+        a.n_cols = ly.out_dim;
+        int tiles = ly.n_tiles;
+        if (gs) {
+          const int lim = ly.cnt_lt[b0];
+          tiles = min(tiles, (lim + TILE - 1) / TILE);
+          in_limit = lim;
+        }
+        for (int item = rank; item < tiles * row_tiles; item += n_group) {
+          compute_tile<T, EPI_RELU, true, true>(a, item / row_tiles, (item % row_tiles) * TILE, rows_s, n_rows, part);
+          __syncthreads();   // `part` is reused by the next item
+        }
+        if (!xcd_barrier(slots, rank, epoch, n_group, p.flags, p.spin_limit, p.host_report + 64)) return;
+      }
+      {
+        const PersistLayer& ly = p.layer[L];
+        LayerArgs a = {};
+        a.A = p.layer[L - 1].out;
+        a.W = ly.W;
+        a.k_chunks = ly.k_chunks;
+        a.bias = ly.bias;
+        a.tile_kend = ly.tile_kend;
+        a.k_cap = ly.in_pad;
+        if (in_limit >= 0) a.k_cap = min(ly.in_pad, (in_limit + 2 * Elem<T>::EPL - 1) / (2 * Elem<T>::EPL) * (2 * Elem<T>::EPL));
+        a.tile_begin = a0 / TILE;
+        a.n_rows = N;
+        a.n_cols = ly.out_dim;
+        a.noise = p.noise;
+        a.x = p.x;
+        a.enc = p.enc;
+        a.enc_chunks = p.enc_chunks;
+        a.changed = changed;
+        a.D = D;
+        a.t_lo = a0;
+        a.t_hi = b0;
+        const int tiles = (b0 + TILE - 1) / TILE - a.tile_begin;
+        for (int item = rank; item < tiles * row_tiles; item += n_group) {
+          compute_tile<T, EPI_BERNOULLI, true, true>(a, item / row_tiles, (item % row_tiles) * TILE, rows_s, n_rows, part);
+          __syncthreads();
+        }
+        if (!xcd_barrier(slots, rank, epoch, n_group, p.flags, p.spin_limit, p.host_report + 64)) return;
+      }
+      // stop test and compaction, recomputed identically by every workgroup of the XCD; its first workgroup also keeps
+      // the pass counts and clears the counters the pass after next will use
+      n_passes += 1;
+      n_sample_passes += n_rows;
+      const bool last_pass = (k == cap);
+      int new_n = 0;
+      for (int start = 0; start < n_rows; start += NT) {
+        const int rix = start + threadIdx.x;
+        int sample = -1;
+        bool keep = false;
+        if (rix < n_rows) {
+          sample = rows_s[rix];
+          // (whatever other compute units wrote is read past this unit's L1: device-scope loads)
+          const int c = __hip_atomic_load(&changed[(size_t)sample * CHG], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          keep = (c > 0) && !last_pass;
+          if (rank == 0) {
+            p.iters[sample] = __hip_atomic_load(&p.iters[sample], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) + 1;
+            if (c > 0 && last_pass && p.flag_unconverged) unconverged_s = 1;     // (every writer stores 1)
+          }
+        }
+        const unsigned long long mask = __ballot(keep);
+        const int before = __popcll(mask & ((1ull << lane) - 1ull));
+        if (lane == 0) wave_total[wave] = __popcll(mask);
+        __syncthreads();
+        int off = new_n;
+        for (int w = 0; w < wave; ++w) off += wave_total[w];
+        if (keep) rows_s[off + before] = sample;
+        for (int w = 0; w < NW; ++w) new_n += wave_total[w];
+        __syncthreads();
+      }
+      if (rank == 0) {
+        int* other = p.changed + (size_t)(parity ^ 1) * p.n_pad * CHG;
+        for (int i = threadIdx.x; i < count; i += NT) other[(size_t)(first + i) * CHG] = 0;
+      }
+      n_rows = new_n;
+      parity ^= 1;
+    }
+  }
+  // The XCD's first workgroup reports.  Its own stores (pass counts) and, through the last barrier, everybody
+  // else's (symbols) have reached the L2; the release store of the call's id orders the report words before it.
+  if (rank == 0) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      *epoch_word = epoch;
+      __hip_atomic_store(report + 0, (int)(n_passes & 0xffffffff), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      __hip_atomic_store(report + 1, (int)(n_passes >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      __hip_atomic_store(report + 2, (int)(n_sample_passes & 0xffffffff), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      __hip_atomic_store(report + 3, (int)(n_sample_passes >> 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      __hip_atomic_store(report + 4, unconverged_s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      __hip_atomic_store(report + 5, p.call_id, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
   }
 }
 

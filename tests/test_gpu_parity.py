@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.fixture(autouse=True, params=["per-layer launches", "single chain", "persistent", "sample-resident",
-                                      "library defaults", "unfused categorical"])
+                                      "library defaults", "unfused categorical", "xcd-resident"])
 def execution_path(request):
     """Every test runs on every execution path of the library (they must all agree with the oracle)."""
     import gpu_util
@@ -24,16 +24,18 @@ def execution_path(request):
         name = getattr(request.node, "callspec", None) and request.node.callspec.params.get("name")
         if name not in ("small_cat", "small_cat_onehot"):
             pytest.skip("only the 256-class workloads have a fused and an unfused output path")
-    if request.param == "sample-resident":
+    if request.param in ("sample-resident", "xcd-resident"):
         name = getattr(request.node, "callspec", None) and request.node.callspec.params.get("name")
         if name is not None and "cat" in name:
-            pytest.skip("the sample-resident kernel serves Bernoulli models only")
+            pytest.skip("the sample-resident and XCD-resident kernels serve Bernoulli models only")
     gpu_util.PERSISTENT = request.param == "persistent"
     gpu_util.RESIDENT = 1 if request.param == "sample-resident" else (2 if request.param == "library defaults" else 0)
     gpu_util.FUSED_CATEGORICAL = request.param != "unfused categorical"
     gpu_util.CHAINS = 1 if request.param in ("single chain", "library defaults") else 4
     gpu_util.RETIRE_SPLIT = 1 if request.param == "single chain" else None   # (the stop test as its own kernel)
+    gpu_util.XCD = 2 if request.param == "xcd-resident" else (None if request.param == "library defaults" else 0)
     yield
+    gpu_util.XCD = 0
     gpu_util.RETIRE_SPLIT = None
     gpu_util.PERSISTENT = False
     gpu_util.RESIDENT = 0
@@ -344,3 +346,27 @@ def test_back_to_back_calls_without_synchronisation(name):
         torch.cuda.synchronize()
         for x in res:
             assert (x.cpu().numpy() == alone[0][0]).all()
+
+
+def test_xcd_resident_kernel_serves_the_call():
+    """With MADE_OPT_XCD_RESIDENT = 2 a Bernoulli call is ONE launch, not three launches per pass: the kernel did not back out, and its results are those of the per-layer launches bit for bit."""
+    import gpu_util
+    if gpu_util.XCD != 2:
+        pytest.skip("runs once, on the XCD-resident execution path")
+    for name in ("mid_bf16", "small_f32", "cfg1"):
+        w = S.workload(name)
+        net = S.make_network(w, with_bias=True)
+        noise = S.make_noise(w)
+        with GpuModel(net) as g:
+            x, it = g.jacobi(noise)
+            st = g.stats()
+            assert st["kernels"] == 1, (st, B.made_last_error())
+            xb, itb = g.gs_jacobi(noise, 16)
+            assert g.stats()["kernels"] == 1
+            B.made_set_option(g.h, B.MADE_OPT_XCD_RESIDENT, 0)
+            B.made_set_option(g.h, B.MADE_OPT_RESIDENT, 0)
+            x2, it2 = g.jacobi(noise)
+            assert g.stats()["kernels"] > 1
+            xb2, itb2 = g.gs_jacobi(noise, 16)
+            assert (x == x2).all() and (it == it2).all() and st["passes"] == it.max() and st["sample_passes"] == it.sum()
+            assert (xb == xb2).all() and (itb == itb2).all()
