@@ -168,3 +168,43 @@ def conv_jacobi_reference(model: ConvModel, noise: np.ndarray, x_init: Optional[
         if k == D:
             done[act] = True
     return x, iters, done, min_margin
+
+
+def conv_jacobi_gs_reference(model: ConvModel, noise: np.ndarray, block: int, x_init: Optional[np.ndarray] = None,
+                             max_iters: Optional[int] = None):
+    """Algorithm 2 (Jacobi-GS) on the convolutional model, tolerance 0, per-image stopping.
+    Returns (x, iters[N], done[N], min_margin[N]).
+
+    The states are cut into consecutive blocks of `block` states (the last may be short).  Iteration k: every block
+    [a, b) starts from the previous iterate s^{k-1} and is walked through state by state,
+    s_j^k = h_j(u, s^{k-1}_{1:a-1}, s^k_{a:j-1}) -- the blocks independently of each other ("in parallel") -- and the
+    blocks' new states together form s^k.  An image stops at the first k with s^k == s^{k-1} or at k = M (number of
+    blocks), where the result is exact (Proposition 2).  The count includes the confirming iteration."""
+    N, D = noise.shape[0], model.D
+    parts = [(a, min(a + block, D)) for a in range(0, D, block)]
+    M = len(parts)
+    cap = M if (max_iters is None or max_iters <= 0) else min(max_iters, M)
+    x = np.zeros((N, D), dtype=np.uint8) if x_init is None else np.array(x_init, dtype=np.uint8)
+    iters = np.zeros(N, dtype=np.int32)
+    done = np.zeros(N, dtype=bool)
+    min_margin = np.full(N, np.inf)
+    k = 0
+    while not done.all() and k < cap:
+        k += 1
+        act = np.flatnonzero(~done)
+        prev = x[act]
+        new = prev.copy()
+        for (a, b) in parts:
+            mixed = prev.copy()                         # s^{k-1} everywhere, then the block's own new states
+            for j in range(a, b):
+                z_j = conv_logits_all(model, mixed)[:, j]
+                mixed[:, j], margin = decide(z_j, noise[act][:, j], model.C)
+                min_margin[act] = np.minimum(min_margin[act], margin)
+            new[:, a:b] = mixed[:, a:b]
+        same = (new == prev).all(axis=1)
+        x[act] = new
+        iters[act] = k
+        done[act[same]] = True
+        if k == M:
+            done[act] = True
+    return x, iters, done, min_margin

@@ -159,3 +159,37 @@ def test_jacobi_equals_sequential(act_round):
     bad = xs.copy()
     bad[:, 0] ^= 1
     assert not CO.conv_fixed_point_check(model, bad, noise)[0].all()
+
+
+def test_conv_jacobi_gs_equals_sequential_and_one_iteration_by_hand():
+    """Algorithm 2 on the convolutional model: exact in at most M iterations for every block size (Proposition 2),
+    one block = the sequential sampler in one iteration, and one iteration written out with the scalar evaluator."""
+    net = tiny(2, 2, 3, 4, 3, 2, seed=12)
+    model = model_of(net)
+    N, D, C = 2, net.D, net.C
+    noise = S.gumbel_noise(N, D, C, 91)
+    xs, _ = CO.conv_sequential_sample(model, noise)
+    for block in (1, 2, 3, 5, D, D + 4):
+        x, iters, done, _ = CO.conv_jacobi_gs_reference(model, noise, block)
+        M = -(-D // min(block, D))
+        assert (x == xs).all() and done.all() and (iters >= 1).all() and (iters <= M).all(), block
+        if block >= D:
+            assert (iters == 1).all()
+    # one iteration from a random iterate, by hand: state j of block [a, b) sees the previous iterate before a and
+    # this iteration's states in a .. j-1
+    prev = np.random.default_rng(4).integers(0, C, (N, D)).astype(np.uint8)
+    expect = prev.copy()
+    block = 5
+    for n in range(N):
+        for a in range(0, D, block):
+            mixed = [int(v) for v in prev[n]]
+            for j in range(a, min(a + block, D)):
+                z = scalar_conv_logits(net, mixed, j)
+                s = [z[c] + float(noise[n, j, c]) for c in range(C)]
+                mixed[j] = s.index(max(s))
+            expect[n, a:a + block] = mixed[a:a + block]
+    got = CO.conv_jacobi_gs_reference(model, noise, block, prev, max_iters=1)[0]
+    assert (got == expect).all()
+    # an iteration limit below M leaves the image unconverged and says so
+    lim = CO.conv_jacobi_gs_reference(model, noise, 2, None, max_iters=1)
+    assert (lim[1] == 1).all() and not lim[2].all()

@@ -163,6 +163,35 @@ def test_conv_jacobi_reference_min_margin():
         assert _close(mm[n], smallest), (n, mm[n], smallest)
 
 
+def test_conv_jacobi_gs_reference_min_margin():
+    net = tiny(2, 2, 3, 4, 3, 2, seed=9)
+    model = model_of(net)
+    N, D, C = 2, net.D, net.C
+    noise = S.gumbel_noise(N, D, C, 83)
+    block = 5
+    M = -(-D // block)
+    x, iters, done, mm = CO.conv_jacobi_gs_reference(model, noise, block)
+    for n in range(N):
+        prev = [0] * D
+        smallest, k = math.inf, 0
+        while True:
+            k += 1
+            new = list(prev)
+            for a in range(0, D, block):
+                mixed = list(prev)
+                for j in range(a, min(a + block, D)):
+                    sym, m = scalar_decide(scalar_conv_logits(net, mixed, j), noise[n, j], C)
+                    mixed[j] = sym
+                    smallest = min(smallest, m)
+                new[a:a + block] = mixed[a:a + block]
+            same = new == prev
+            prev = new
+            if same or k == M:
+                break
+        assert k == iters[n] and prev == [int(v) for v in x[n]]
+        assert _close(mm[n], smallest), (n, mm[n], smallest)
+
+
 def test_a_planted_mistake_in_min_margin_is_caught():
     """The pins above have teeth: a min over the batch axis, or a min over the last pass only, is rejected."""
     D = 6
