@@ -590,6 +590,19 @@ def run_one(args, torch, B, S, light=False):
                                            "iters_mean": float(itc.mean()), "iters_max": int(itc.max()),
                                            "batch_passes": int(st["passes"]),
                                            "same_output_as_jacobi": bool(torch.equal(xq, x_jac))}
+        if conv:
+            for rows in (1, 2):                         # Algorithm 2 with blocks of whole image rows: one timed call each
+                blk = rows * 96
+                B.jacobi_gs_sample(model, noises[0], N, None, blk, 0, xq, iters, stream)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                B.jacobi_gs_sample(model, noises[0], N, None, blk, 0, xq, iters, stream)
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t0
+                itc = iters.cpu().numpy()
+                extras[f"jacobi_gs_B{blk}"] = {"samples_per_s": N / dt, "ms_per_batch": dt * 1e3,
+                                               "iters_mean": float(itc.mean()), "iters_max": int(itc.max()),
+                                               "same_output_as_jacobi": bool(torch.equal(xq, x_jac))}
         if not conv and w.C == 1 and not light:
             for blk in (w.block_sizes or []):           # Algorithm 2: one timed call per block size (it is slow)
                 B.jacobi_gs_sample(model, noises[0], N, None, blk, 0, xq, iters, stream)

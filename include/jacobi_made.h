@@ -208,7 +208,10 @@ int gs_jacobi_sample(made_model* m, const float* noise, int32_t N, const uint8_t
  *   max_iters : <= 0 or > M means M; a smaller limit makes the call return MADE_ERR_NOT_CONVERGED when a
  *               sample was still changing in the last allowed iteration (x_out then holds that iterate).
  *   iters_out : device int32 [N] or NULL; iterations per sample (including the confirming one).
- * Supported: the masked MLP with Bernoulli positions (C = 1), M * round_up(N, 32) <= 2^22.
+ * Supported: the masked MLP with Bernoulli positions (C = 1), M * round_up(N, 32) <= 2^22; and the convolutional model
+ * (blocks of consecutive sub-pixel states, e.g. 96 = one image row; Section 5.3.2 runs this solver with blocks of one
+ * row): there every block works on a copy of the image of its own, M * N copies in all, whose per-layer activations
+ * must fit 64 GB, and an iteration costs `block` launches of the layer stack on about one image row per copy.
  */
 int jacobi_gs_sample(made_model* m, const float* noise, int32_t N, const uint8_t* x_init, int32_t block,
                      int32_t max_iters, uint8_t* x_out, int32_t* iters_out, void* stream);

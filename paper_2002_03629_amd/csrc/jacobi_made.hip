@@ -1227,13 +1227,13 @@ static int run_output_sample(made_model* m, const RowSet& rs, const SampleIO& io
 // One pass of the convolutional network over ALL images of the batch (converged images are recomputed; their
 // symbols cannot change), then the fused head: Gumbel-max draw of the states in [state_lo, state_hi).
 static void launch_conv_trunk(made_model* m, const uint8_t* x, int N, const int* dirty_lo, int row_hi, hipStream_t s,
-                              const void** last_act) {
+                              const void** last_act, const int* row_hi_of = nullptr) {
   ConvNet& cv = m->conv;
   const int kch = cv.F / chunk_elems(m);
   const int ft = cv.F / 32;
   ConvFirstArgs fa;
   memset(&fa, 0, sizeof fa);
-  fa.win = ConvWindow{dirty_lo, row_hi};
+  fa.win = ConvWindow{dirty_lo, row_hi, row_hi_of};
   fa.x = x;
   fa.w = cv.w0;
   fa.bias = cv.b0;
@@ -1267,7 +1267,7 @@ static void launch_conv_trunk(made_model* m, const uint8_t* x, int N, const int*
   for (int l = 1; l < cv.n_conv; ++l) {
     ConvLayerArgs a;
     memset(&a, 0, sizeof a);
-    a.win = ConvWindow{dirty_lo, row_hi};
+    a.win = ConvWindow{dirty_lo, row_hi, row_hi_of};
     a.in = cv.act[l - 1];
     a.w = cv.w[l - 1];
     a.bias = cv.bias[l - 1];
@@ -1304,6 +1304,8 @@ static void launch_conv_trunk(made_model* m, const uint8_t* x, int N, const int*
   *last_act = cv.act[cv.n_conv - 1];
 }
 
+static void launch_conv_head(made_model* m, const ConvHeadArgs& c, hipStream_t s);
+
 static int run_conv_pass(made_model* m, int N, const SampleIO& io, bool first_pass, bool whole_network,
                          hipStream_t s) {
   ConvNet& cv = m->conv;
@@ -1327,7 +1329,6 @@ static int run_conv_pass(made_model* m, int N, const SampleIO& io, bool first_pa
   // one workgroup per CU in all (3 colours x 85; the kernel runs one wave per SIMD); the 4 waves of workgroup
   // (colour, group) walk over the pixel rows 4 * group + wave, + 4 * groups, ...
   c.groups = std::max(1, std::min((N * cv.H + 3) / 4, 85));
-  const size_t head_lds = (size_t)(CAT_C / TILE) * (cv.F / chunk_elems(m)) * 256 * 16;   // one colour's weights
   if (!whole_network) {
     c.dirty_lo = cv.win;
     c.first_changed = cv.win + cv.win_pad;
@@ -1338,6 +1339,14 @@ static int run_conv_pass(made_model* m, int N, const SampleIO& io, bool first_pa
     c.first_pass = first_pass ? 1 : 0;
   }
   c.retire = io.retire;
+  launch_conv_head(m, c, s);
+  HIP_TRY(hipGetLastError());
+  return MADE_OK;
+}
+
+static void launch_conv_head(made_model* m, const ConvHeadArgs& c, hipStream_t s) {
+  ConvNet& cv = m->conv;
+  const size_t head_lds = (size_t)(CAT_C / TILE) * (cv.F / chunk_elems(m)) * 256 * 16;   // one colour's weights
   prof_mark(m, m->L, false, s);
 #define JM_LAUNCH_HEAD(T, FT)                                                                                      \
   do {                                                                                                            \
@@ -1357,8 +1366,6 @@ static int run_conv_pass(made_model* m, int N, const SampleIO& io, bool first_pa
 #undef JM_LAUNCH_HEAD
   prof_mark(m, m->L, true, s);
   m->stats[2]++;
-  HIP_TRY(hipGetLastError());
-  return MADE_OK;
 }
 
 static int launch_init_state(made_model* m, const uint8_t* x_init, uint8_t* x, int N, hipStream_t s,
@@ -2379,6 +2386,109 @@ static int grow(P** p, size_t* cap, size_t need_bytes) {
   return MADE_OK;
 }
 
+// Algorithm 2 on the convolutional model.  Block i gets a copy of every image of its own ("virtual image" i * N + n,
+// with its own symbols and its own per-layer activations), because inside an iteration the blocks' mixed state
+// vectors differ: copy i holds the previous iterate everywhere except in block i, where the new states appear one
+// by one.  An iteration: (1) all copies' symbols = previous iterate; one evaluation of the N real images, whose
+// activations are then copied to every block's copies (rows above a block never change inside an iteration, so
+// they are valid for all of them); (2) sub-steps q = 0 .. |block| - 1: every copy recomputes, in every layer, only
+// the image rows between the state it drew last and the one it draws now, and the head draws that one state from
+// the noise of the copy's real image; (3) the blocks' states are collected per real image, compared with the
+// previous iterate (stop test) and become the new one.  One iteration costs |block| launches of the whole layer
+// stack, each on about one row per block and image: with states that are expensive to evaluate this solver cannot
+// compete with Algorithm 1 (which does the same work in one pass), it is here to complete the paper's family.
+static int jacobi_gs_conv(made_model* m, const float* noise, int N, const uint8_t* x_init, int block, int max_iters,
+                          uint8_t* x_out, int32_t* iters_out, hipStream_t s) {
+  ConvNet& cv = m->conv;
+  const int D = m->D;
+  const int B = std::min(block, D);
+  const int M = (D + B - 1) / B;
+  const int64_t V64 = (int64_t)M * N;
+  const size_t per_image = (size_t)cv.H * 32 * cv.F * elem_size(m);
+  if (V64 > (1 << 20) || (double)V64 * per_image * cv.n_conv > 64e9)
+    return fail(MADE_ERR_ARG, "jacobi_gs_sample: %d blocks x %d images = %lld copies of the image need more than 64 GB of "
+                              "activations", M, N, (long long)V64);
+  const int V = (int)V64;
+  const int cap = (max_iters <= 0 || max_iters > M) ? M : max_iters;
+  TRY(settle(m, s));
+  TRY(ensure_workspace(m, V, false));
+  Workspace& w = m->ws;
+  TRY(grow(&m->jgs_xv, &m->jgs_xv_cap, (size_t)V * D));
+  TRY(grow(&m->jgs_state, &m->jgs_state_cap, (size_t)(N + 1 + V) * sizeof(int)));
+  int* state = m->jgs_state;
+  int* n_active = m->jgs_state + N;
+  int* state_one = m->jgs_state + N + 1;
+  int* dirty_lo = cv.win;                  // [V]
+  int* row_hi_of = cv.win + cv.win_pad;    // [V]
+  HIP_TRY(hipMemsetAsync(state, 0, (size_t)(N + 1) * sizeof(int), s));
+  HIP_TRY(hipMemsetAsync(w.flags, 0, sizeof(int), s));
+  HIP_TRY(hipMemsetAsync(w.iters, 0, (size_t)N * sizeof(int), s));
+  {
+    const size_t total = (size_t)N * D;
+    hipLaunchKernelGGL(copy_symbols_kernel, dim3((int)std::min<size_t>((total + 255) / 256, 4096)), dim3(256), 0, s, x_init,
+                       x_out, total);
+    m->stats[2]++;
+  }
+  ConvHeadArgs c;
+  memset(&c, 0, sizeof c);
+  c.W = cv.w_head;
+  c.bias = cv.b_head;
+  c.tile_kend = cv.head_tile_kend;
+  c.noise = noise;
+  c.x = m->jgs_xv;
+  c.changed = w.changed;
+  c.N = V;
+  c.H = cv.H;
+  c.state_lo = 0;
+  c.state_hi = D;
+  c.groups = std::max(1, std::min((V * cv.H + 3) / 4, 85));
+  c.state_one = state_one;
+  c.noise_images = N;
+  const size_t n16 = (size_t)N * per_image / 16;
+  int k = 0;
+  for (;;) {
+    ++k;
+    hipLaunchKernelGGL(jgs_conv_begin_kernel, dim3((int)std::min<size_t>(((size_t)V * D + 255) / 256, 8192)), dim3(256), 0, s,
+                       x_out, m->jgs_xv, N, M, D);
+    m->stats[2]++;
+    const void* last = nullptr;
+    launch_conv_trunk(m, m->jgs_xv, N, nullptr, cv.H - 1, s, &last);      // the previous iterate, every row
+    if (M > 1)
+      for (int l = 0; l < cv.n_conv; ++l) {
+        hipLaunchKernelGGL(jgs_conv_broadcast_kernel, dim3((int)std::min<size_t>((n16 * (M - 1) + 255) / 256, 16384)), dim3(256),
+                           0, s, (uint4*)cv.act[l], n16, M);
+        m->stats[2]++;
+      }
+    for (int q = 0; q < B; ++q) {
+      hipLaunchKernelGGL(jgs_conv_window_kernel, dim3((V + 255) / 256), dim3(256), 0, s, dirty_lo, row_hi_of, state_one, N, M,
+                         D, B, q);
+      m->stats[2]++;
+      launch_conv_trunk(m, m->jgs_xv, V, dirty_lo, 0, s, &last, row_hi_of);
+      c.A = last;
+      launch_conv_head(m, c, s);
+    }
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemsetAsync(n_active, 0, sizeof(int), s));
+    hipLaunchKernelGGL(jgs_end_kernel, dim3(N), dim3(256), 0, s, x_out, m->jgs_xv, N, D, B, w.iters, state, k,
+                       (k == cap) ? 1 : 0, (cap < M) ? 1 : 0, n_active, w.flags);
+    m->stats[2]++;
+    HIP_TRY(hipMemcpyAsync((void*)&w.h_pin[1], n_active, sizeof(int), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    m->stats[3]++;
+    if (w.h_pin[1] == 0 || k == cap) break;
+  }
+  HIP_TRY(hipGetLastError());
+  if (iters_out) HIP_TRY(hipMemcpyAsync(iters_out, w.iters, (size_t)N * sizeof(int), hipMemcpyDeviceToDevice, s));
+  HIP_TRY(hipMemcpyAsync((void*)&w.h_pin[0], w.flags, sizeof(int), hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  prof_collect(m);
+  m->stats[0] = k;
+  m->stats[1] = (int64_t)k * B * V;
+  if (w.h_pin[0] & 1)
+    return fail(MADE_ERR_NOT_CONVERGED, "images were still changing after the last allowed iteration");
+  return MADE_OK;
+}
+
 // Algorithm 2.  Every block keeps its own copy of the state vector ("virtual sample" (block i, sample n) =
 // row i * np + n of a batch of M * np rows): it starts an iteration as the previous iterate and receives the
 // block's new symbols one position at a time.  Sub-step q of an iteration evaluates the hidden layers on all
@@ -2389,12 +2499,13 @@ extern "C" int jacobi_gs_sample(made_model* m, const float* noise, int32_t N, co
                                 int32_t max_iters, uint8_t* x_out, int32_t* iters_out, void* stream) {
   TRY(check_call(m, noise, N, x_out, "jacobi_gs_sample"));
   if (block < 1) return fail(MADE_ERR_ARG, "jacobi_gs_sample: block=%d must be >= 1", block);
-  if (m->arch != 0 || m->C != 1)
-    return fail(MADE_ERR_ARG, "jacobi_gs_sample: only the masked MLP with Bernoulli positions is supported");
+  if (m->arch == 0 && m->C != 1)
+    return fail(MADE_ERR_ARG, "jacobi_gs_sample: of the masked MLPs only those with Bernoulli positions are supported");
   if (N == 0) return MADE_OK;
   hipStream_t s = (hipStream_t)stream;
   memset(m->stats, 0, sizeof m->stats);
   m->ev_layer.clear();
+  if (m->arch == 1) return jacobi_gs_conv(m, noise, N, x_init, block, max_iters, x_out, iters_out, s);
   const int D = m->D;
   const int B = std::min(block, D);
   const int M = (D + B - 1) / B;

@@ -1795,10 +1795,13 @@ constexpr int CONV_ROWS = 4;             // image rows per workgroup of the k x 
 struct ConvWindow {
   const int* dirty_lo;   // NULL: recompute every row up to row_hi
   int row_hi;
+  const int* row_hi_of;  // per image instead of the common row_hi (NULL: row_hi).  Algorithm 2 gives every block a
+                         // copy of the image of its own, and each copy only needs the rows of its block's current state
 };
 __device__ __forceinline__ bool conv_rows_active(const ConvWindow& w, int n, int y0, int rows) {
   const int lo = w.dirty_lo ? w.dirty_lo[n] : 0;
-  return y0 + rows > lo && y0 <= w.row_hi;
+  const int hi = w.row_hi_of ? w.row_hi_of[n] : w.row_hi;
+  return y0 + rows > lo && y0 <= hi;
 }
 
 struct ConvFirstArgs {
@@ -1947,9 +1950,11 @@ __global__ __launch_bounds__(256) void conv_layer_kernel(ConvLayerArgs a) {
   // Steps (dx, chunk) come in two runs: dx <= 0 (MID + 1 visible dy each) and dx > 0 (MID visible dy), each a
   // loop with a single straight-line body.  Within a run the workgroups start at different steps: all of them
   // read the same few hundred KB of weights, and in lock-step they would all ask the same L2 channel for the
-  // same lines at the same time.
+  // same lines at the same time.  The starting step fixes the order of the fp32 additions, so it is taken from
+  // the rows' place in the image alone: an image's activations are the same bits wherever it sits in the batch
+  // (Algorithm 2 evaluates copies of an image at other batch positions and must reach the same fixed point).
   constexpr int N_A = (MID + 1) * KCH, N_B = MID * KCH, N_IT = N_A + N_B;
-  const int rot_a = (int)(blockIdx.x % N_A), rot_b = (int)(blockIdx.x % N_B);
+  const int rot_a = (y0 / WG_ROWS) % N_A, rot_b = (y0 / WG_ROWS) % N_B;
   auto step_of = [&](int p) {               // p-th step of this workgroup -> it = dxi * KCH + c
     if (p < N_A) { const int q = p + rot_a; return q < N_A ? q : q - N_A; }
     const int q = p - N_A + rot_b;
@@ -2125,6 +2130,10 @@ struct ConvHeadArgs {
   int* win_done;
   unsigned long long* rows_stat;
   int row_lo, row_hi, first_pass;
+  // Algorithm 2 (virtual images, see jacobi_gs_sample): image n draws the ONE state state_one[n] (or none if negative)
+  // and reads the noise of image n % noise_images; nothing is counted or tracked.  NULL: the windows above apply.
+  const int* state_one;
+  int noise_images;
   RetireArgs retire;
 };
 
@@ -2153,6 +2162,10 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
 
   auto row_active = [&](int g) {
     const int n = g / a.H, y = g % a.H;
+    if (a.state_one) {
+      const int st = a.state_one[n];
+      return st >= 0 && st % 3 == t && st / 96 == y;
+    }
     if (y * 96 + 93 + t < a.state_lo || y * 96 + t >= a.state_hi) return false;   // no state of this row is drawn
     if (!a.first_changed) return true;
     const int lo = a.first_pass ? a.row_lo : max(a.row_lo, a.dirty_lo[n]);
@@ -2200,6 +2213,7 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
   // pixel r for q = 0..3).
   typedef __attribute__((__vector_size__(4 * sizeof(float)))) float vf4;   // (a native vector: stays in registers)
   auto load_noise = [&](int g_row, int ct, vf4 (&dst)[4]) {
+    if (a.state_one) g_row = ((g_row / a.H) % a.noise_images) * a.H + g_row % a.H;   // (a virtual image: its real image's noise)
     const float* nz = a.noise + ((size_t)(g_row * 32 + (lane >> 3)) * 3 + t) * CAT_C + ct * TILE + (lane & 7) * 4;
     static_for<4>([&](auto I) {
       constexpr int i = decltype(I)::value;
@@ -2329,14 +2343,14 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
     bool differs = false;
     if (h == 0) {
       const int st = (y * 32 + r) * 3 + t;
-      if (st >= a.state_lo && st < a.state_hi) {
+      if (a.state_one ? st == a.state_one[n] : (st >= a.state_lo && st < a.state_hi)) {
         const uint8_t xn = (uint8_t)best_c;
         differs = xn != x_old;
         if (differs) a.x[xi] = xn;
       }
     }
     const unsigned long long changed_mask = __ballot(differs);
-    if (lane == 0 && changed_mask != 0) {
+    if (lane == 0 && changed_mask != 0 && !a.state_one) {
       // returning atomics, so that "the value came back" means "performed"; the values are only consumed
       // after the loop (before the tail counters), so a row does not wait for them
       sink += __hip_atomic_fetch_add(&a.changed[(size_t)n * CHG], __popcll(changed_mask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -2502,6 +2516,34 @@ __global__ void jgs_begin_kernel(const uint8_t* x, uint8_t* xv, T* enc, int enc_
     xv[e] = val;
     enc[frag_offset<T>(v, t, enc_chunks)] = Elem<T>::from_f32((float)val);
   }
+}
+
+// Algorithm 2 on the convolutional model: the N real images' symbols to all M * N virtual images (block-major:
+// virtual image i * N + n is block i's copy of image n).
+__global__ void jgs_conv_begin_kernel(const uint8_t* x, uint8_t* xv, int N, int M, int D) {
+  const size_t per = (size_t)N * D, total = per * M;
+  for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x)
+    xv[e] = x[e % per];
+}
+
+// The activations of the N real images (the first N virtual images hold them: one evaluation of the previous iterate)
+// to the other blocks' copies: per layer, n16 pieces of 16 bytes per batch of N images.
+__global__ void jgs_conv_broadcast_kernel(uint4* act, size_t n16, int M) {
+  const size_t total = n16 * (size_t)(M - 1);
+  for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x)
+    act[n16 + e] = act[e % n16];
+}
+
+// Sub-step q of an iteration: block i's copies draw state a_i + q (none past the block's end) and need the image rows
+// from the row of the state drawn before (its symbol is new) to the row of this state.
+__global__ void jgs_conv_window_kernel(int* dirty_lo, int* row_hi_of, int* state_one, int N, int M, int D, int block, int q) {
+  const int v = blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= N * M) return;
+  const int i = v / N, a = i * block, st = a + q;
+  const bool live = st < min(a + block, D);
+  state_one[v] = live ? st : -1;
+  dirty_lo[v] = live ? (q > 0 ? (st - 1) / 96 : st / 96) : 0x3fffffff;
+  row_hi_of[v] = live ? st / 96 : -1;
 }
 
 // End of an iteration: block i's positions are taken from its virtual sample, compared with the previous

@@ -242,6 +242,20 @@ def test_cfg5_full_size_certificate():
                 # (the buffers hold the last block's window only for the rows it evaluated: fresh evaluation)
                 sub = conv_layer_certificate(_Subset(g, sel), same, xb[sel], noise[sel], label=f"cfg5 gs {rows} rows")
                 print(f"  certificate on {sel.size} images: {sub}")
+        # Algorithm 2 with blocks of one image row (the block size of the paper's CIFAR-10 run, Section 5.3.2): 32 blocks
+        # x 32 images = 1024 copies of the image
+        progress("cfg5: jacobi-gs, blocks of one row")
+        xg = torch.empty((w.N, net.D), dtype=torch.uint8, device="cuda")
+        itg = torch.empty((w.N,), dtype=torch.int32, device="cuda")
+        B.jacobi_gs_sample(g.h, dev(noise), w.N, None, 96, 0, xg, itg)
+        xg, itg = xg.cpu().numpy(), itg.cpu().numpy()
+        other = np.flatnonzero((xg != x).any(axis=1))
+        print(f"cfg5 jacobi-gs, one row per block: iterations mean {itg.mean():.1f} max {itg.max()}, stats "
+              f"{B.made_last_stats(g.h)}, {other.size} images differ from the Jacobi result")
+        assert (itg >= 1).all() and (itg <= 32).all()
+        # the copies sit at other batch positions than their images; the kernels' sums do not depend on the position,
+        # so Algorithm 2 iterates the very same function and reaches the very same fixed point
+        assert other.size == 0, f"{other.size} images differ from the Jacobi result"
     # same network on 2-row images: full sequential oracle
     progress("cfg5: 2-row images against the sequential oracle")
     w2 = dataclasses.replace(w, H=2, N=4)
@@ -289,3 +303,50 @@ def test_taller_reduced_shape_against_the_sequential_oracle():
             certify(same, noise, xb, xs, margins)
             stb = B.made_last_stats(g.h)
             assert 0 < stb["conv_rows"] < stb["passes"] * w.N * net.H
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["small_conv", "small_conv_f32", "small_conv/8 rows"])
+def test_conv_jacobi_gs(name):
+    """Algorithm 2 on the convolutional model against its oracle: the sequential result, the oracle's iteration
+    counts, blocks that are whole rows, cut rows, a single block, and an iteration limit; on 8-row images (two
+    workgroups' rows per image and layer) blocks of one row and of two rows and a bit."""
+    tall = name.endswith("/8 rows")
+    w = S.conv_workload(name.split("/")[0])
+    if tall:
+        w = dataclasses.replace(w, H=8, N=2)
+    net = S.make_conv_network(w, with_bias=True)
+    _, same = models(net)
+    noise = S.make_conv_noise(w)
+    xs, margins = CO.conv_sequential_sample(same, noise)
+    D = net.D
+
+    def run(block, max_iters=0, x_init=None):
+        x = torch.empty((w.N, D), dtype=torch.uint8, device="cuda")
+        it = torch.empty((w.N,), dtype=torch.int32, device="cuda")
+        B.jacobi_gs_sample(g.h, dev(noise), w.N, None if x_init is None else dev(x_init), block, max_iters, x, it)
+        return x.cpu().numpy(), it.cpu().numpy()
+
+    with ConvGpu(net) as g:
+        for block in ((96, 200) if tall else (96, 50, 192, D, D + 5)):
+            progress(f"{name}: jacobi-gs, blocks of {block} states")
+            x, it = run(block)
+            certify(same, noise, x, xs, margins)
+            ref = CO.conv_jacobi_gs_reference(same, noise, block)
+            clear = ref[3] >= MARGIN
+            assert (it[clear] == ref[1][clear]).all(), (block, it, ref[1])
+            M = -(-D // min(block, D))
+            assert (it >= 1).all() and (it <= M).all()
+            if block >= D:
+                assert (it == 1).all()
+        init = np.random.default_rng(5).integers(0, 256, size=(w.N, D)).astype(np.uint8)
+        x, it = run(96, 0, init)
+        certify(same, noise, x, xs, margins)
+        ref1 = CO.conv_jacobi_gs_reference(same, noise, 96, None, 1)
+        if not ref1[2].all():
+            with pytest.raises(B.MadeError) as e:
+                run(96, 1)
+            assert e.value.code == B.MADE_ERR_NOT_CONVERGED
+        # Jacobi still works on the model afterwards (the workspace has grown to the copies' size)
+        xj, _ = g.run("jacobi", noise)
+        certify(same, noise, xj, xs, margins)
