@@ -350,3 +350,24 @@ def test_conv_jacobi_gs(name):
         # Jacobi still works on the model afterwards (the workspace has grown to the copies' size)
         xj, _ = g.run("jacobi", noise)
         certify(same, noise, xj, xs, margins)
+
+
+def test_an_image_gets_the_same_bits_at_any_batch_position():
+    """The benchmark's network on a batch and on the same batch in another order: symbols, iteration counts and every
+    layer's activations are those of the image, not of its place in the batch (the order of the fp32 additions in
+    the kernels must not depend on the workgroup's index).  Algorithm 2 relies on it: its copies of an image sit
+    at other batch positions and have to iterate the same function."""
+    w = dataclasses.replace(S.conv_workload("cfg5"), N=7)
+    net = S.make_conv_network(w)
+    noise = S.make_conv_noise(w)
+    perm = np.array([3, 6, 0, 5, 1, 4, 2])
+    with ConvGpu(net) as g:
+        x1, it1 = g.run("jacobi", noise)
+        a1 = [g.activations(None, l, w.N) for l in range(w.n_conv)]
+        x2, it2 = g.run("jacobi", noise[perm])
+        a2 = [g.activations(None, l, w.N) for l in range(w.n_conv)]
+        assert (x2 == x1[perm]).all() and (it2 == it1[perm]).all()
+        for l in range(w.n_conv):
+            assert (a2[l] == a1[l][perm]).all(), f"layer {l}"
+        z1, z2 = g.logits(x1), g.logits(x1[perm])
+        assert (z2 == z1[perm]).all()
