@@ -280,12 +280,14 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   chains' dependent kernel launches can overlap.  The caller's stream waits for all of them before the call
  *   returns.  With one host thread enqueuing, more chains mean proportionally more launches; at batch 128 on
  *   MI355X that costs more than the overlap gains, hence the default of a single chain.
- *   MADE_OPT_MID_TILE_BATCH (default 1536, >= 1) and MADE_OPT_BIG_TILE_BATCH (default: off, >= 1): batches (chains)
- *   of at least MID samples run the masked layers with 128 x 128 workgroup tiles staged through LDS instead of
- *   32 x 32 tiles, those of at least BIG samples with 256 x 256 tiles (the same kernel with four times the
- *   accumulators and LDS, one workgroup per compute unit instead of two).  On the D = 784, 2 x 2000 network the
- *   32 x 32 and 128 x 128 tiles cross over near 1536 samples, and the 128 x 128 tiles are faster than
- *   the 256 x 256 ones at every batch measured (12.6 against 10.0 M samples/s at 8192, 17.0 against 14.7 at 32768).
+ *   MADE_OPT_MID_TILE_BATCH (default 1536, >= 1) and MADE_OPT_BIG_TILE_BATCH (>= 1): batches (chains) of at least
+ *   MID samples run the masked layers with 128 x 128 workgroup tiles staged through LDS instead of 32 x 32 tiles,
+ *   those of at least BIG samples with 256 x 256 tiles (the same kernel with four times the accumulators and LDS,
+ *   one workgroup per compute unit instead of two).  On the D = 784, 2 x 2000 network the 32 x 32 and 128 x 128
+ *   tiles cross over near 1536 samples.  By default the hidden layers take the 256 x 256 tiles from 16384 samples on
+ *   (measured 5-12 % faster there, up to 2.5x slower below 8192, where they leave compute units idle) and the
+ *   sampling layer never does (slower at every batch: 0.196 against 0.175 ms at 32768); setting
+ *   MADE_OPT_BIG_TILE_BATCH applies the given threshold to every layer.
  *   MADE_OPT_CONV_ROWS (default 4; 2 or 4): image rows per workgroup of the convolutional model's k x k layers.
  *   MADE_OPT_RESIDENT (default 2; 0, 1 or 2): the sample-resident kernel serves jacobi_sample / gs_jacobi_sample of
  *   Bernoulli models in ONE launch: a workgroup keeps 32 samples' iterate and hidden activations in its LDS for the

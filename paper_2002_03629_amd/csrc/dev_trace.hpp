@@ -16,6 +16,11 @@ __device__ unsigned long long g_trace[64 * 256 * 5];        // persistent kernel
   do {                                                                                \
     if (threadIdx.x == 0 && blockIdx.x < 1024) g_tile_trace[blockIdx.x * 8 + (i)] = (v); \
   } while (0)
+// time a wave spends inside a wait (summed over a loop; reported next to a count in one trace word)
+#define JM_WAIT_DECL() unsigned long long jm_wait_sum_ = 0, jm_wait_t0_ = 0
+#define JM_WAIT_BEGIN() jm_wait_t0_ = wall_clock64()
+#define JM_WAIT_END() jm_wait_sum_ += wall_clock64() - jm_wait_t0_
+#define JM_WAIT_PACK(count) ((unsigned long long)(count) | (jm_wait_sum_ << 16))
 #define JM_TRACE_TAIL_DONE()                                                          \
   do {                                                                                \
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");                       \
@@ -41,6 +46,10 @@ __device__ unsigned long long g_trace[64 * 256 * 5];        // persistent kernel
 #define RES_STAMP(pass, i) do { } while (0)
 #define JM_TSTAMP(i, drain) do { } while (0)
 #define JM_TRACE_VALUE(i, v) do { } while (0)
+#define JM_WAIT_DECL() do { } while (0)
+#define JM_WAIT_BEGIN() do { } while (0)
+#define JM_WAIT_END() do { } while (0)
+#define JM_WAIT_PACK(count) (count)
 #define JM_TRACE_TAIL_DONE() do { } while (0)
 #define JM_STAMP(tag) do { } while (0)
 #endif

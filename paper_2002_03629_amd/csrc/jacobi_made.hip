@@ -219,8 +219,11 @@ struct made_model {
                                               // 2 also the frozen inputs' partial sums, for lists of partial_batch samples on
                                               // (measured slower than 1 at every batch up to 32768: not the default)
   int partial_batch = 1024;                   // made_set_option(MADE_OPT_PARTIAL_SUM_BATCH)
-  int big_batch = 1 << 30;                    // made_set_option(MADE_OPT_BIG_TILE_BATCH): 256 x 256 tiles from here on (off:
-                                              // slower than 128 x 128 at every batch measured, up to 32768)
+  int big_batch = 16384;                      // 256 x 256 tiles from here on: measured 5-12 % faster than 128 x 128 on the
+                                              // hidden layers from 16384 samples on, slower below (too few workgroups) and
+  bool big_output = false;                    // slower at every batch on the sampling layer (its epilogue needs a second
+                                              // workgroup on the compute unit to hide behind), which therefore stays on
+                                              // 128 x 128 unless made_set_option(MADE_OPT_BIG_TILE_BATCH) names a batch
   int mid_batch = 1536;                       // made_set_option(MADE_OPT_MID_TILE_BATCH): 128 x 128 tiles from here up to
                                               // big_batch; measured crossover with the 32 x 32 tiles near 1536
   int n_chains = 1;                           // made_set_option(MADE_OPT_CHAINS)
@@ -474,6 +477,7 @@ extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
   if (option == MADE_OPT_BIG_TILE_BATCH) {
     if (value < 1) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_BIG_TILE_BATCH=%d must be >= 1", value);
     m->big_batch = value;
+    m->big_output = true;
     return MADE_OK;
   }
   if (option == MADE_OPT_MID_TILE_BATCH) {
@@ -991,9 +995,10 @@ static void launch_big_t(LayerArgs a, int n_tiles, int n_rows_max, hipStream_t s
   a.n_launch_tiles = n_tiles;
   a.row_tiles = (n_rows_max + BIG_ROWS - 1) / BIG_ROWS;
   const int big_cols = (n_tiles + BIG_T - 1) / BIG_T;
-  a.big_by_rows = a.row_tiles >= big_cols;
-  const int groups = ((a.big_by_rows ? a.row_tiles : big_cols) + XCDS - 1) / XCDS;
-  const int other = a.big_by_rows ? big_cols : a.row_tiles;
+  const int pair_cols = (big_cols + 1) / 2;                // a workgroup takes a long and a short column of unit tiles
+  a.big_by_rows = a.row_tiles >= pair_cols;
+  const int groups = ((a.big_by_rows ? a.row_tiles : pair_cols) + XCDS - 1) / XCDS;
+  const int other = a.big_by_rows ? pair_cols : a.row_tiles;
   hipLaunchKernelGGL((masked_layer_big_kernel<T, EPI, W>), dim3(groups * XCDS * other), dim3(256), 0, s, a);   // (static LDS: 128 / 64 KB)
 }
 
@@ -1003,7 +1008,8 @@ static void launch_layer(made_model* m, int layer, const LayerArgs& a, int n_til
   // (launches that start behind cached partial sums cover few units: they stay on the 32 x 32 tiles, whose grids are
   // the larger ones there, and only that kernel takes k_begin / partial)
   const bool small_only = a.partial != nullptr || a.k_begin > 0;
-  const bool big = !small_only && a.n_rows >= m->big_batch, mid = !small_only && !big && a.n_rows >= m->mid_batch;
+  const bool big = !small_only && a.n_rows >= m->big_batch && (EPI == EPI_RELU || m->big_output);
+  const bool mid = !small_only && !big && a.n_rows >= m->mid_batch;
   if (m->dtype == MADE_BF16) {
     if (big) launch_big_t<bf16_t, EPI, 4>(a, n_tiles, a.n_rows, s);
     else if (mid) launch_big_t<bf16_t, EPI, 2>(a, n_tiles, a.n_rows, s);

@@ -828,26 +828,35 @@ __global__ __launch_bounds__(256, W == 2 ? 2 : 1) void masked_layer_big_kernel(L
   constexpr int BIG_W = W, BIG_T = 2 * W, BIG_ROWS = BIG_T * TILE, BIG_STAGE = 2 * BIG_T * BIG_HALF;
   constexpr int KC = 2 * Elem<T>::EPL;
   // ring stages, [block 0..7 = samples, 8..15 = units][128] each (separate arrays: see the main loop)
-  __shared__ uint4 big_s0[BIG_STAGE];
-  __shared__ uint4 big_s1[BIG_STAGE];
-  __shared__ uint4 big_s2[BIG_STAGE];
-  __shared__ uint4 big_s3[BIG_STAGE];
+  __shared__ uint4 big_ring[4 * BIG_STAGE];
   const int n_rows = a.n_rows_ptr ? *a.n_rows_ptr : a.n_rows;
   const int big_cols = (a.n_launch_tiles + BIG_T - 1) / BIG_T;
+  // The visible K grows about linearly with the unit index (units are laid out by degree, positions in order): the
+  // last column of unit tiles costs several times the first.  A workgroup therefore takes TWO columns of its sample
+  // tile, c from the end and c from the start, one after the other: every workgroup then has about the same work
+  // (with one column each and four workgroups per compute unit the slowest unit took 1.45x the average).
+  const int pair_cols = (big_cols + 1) / 2;
   // Workgroup i runs on XCD i % 8.  An XCD should own whichever operand is larger (it then streams only
   // the smaller one through its L2): sample tiles when samples outnumber units, unit tiles otherwise.
   const int xcd = blockIdx.x % XCDS, slot = blockIdx.x / XCDS;
-  int wg_m, wg_n;                                           // row_tiles counts 256-sample tiles here
+  int wg_m, wg_p;                                           // row_tiles counts 256-sample tiles here
   if (a.big_by_rows) {
-    wg_n = slot % big_cols;
-    wg_m = (slot / big_cols) * XCDS + xcd;
+    wg_p = slot % pair_cols;
+    wg_m = (slot / pair_cols) * XCDS + xcd;
   } else {
     wg_m = slot % a.row_tiles;
-    wg_n = (slot / a.row_tiles) * XCDS + xcd;
+    wg_p = (slot / a.row_tiles) * XCDS + xcd;
   }
   const int row0 = wg_m * BIG_ROWS;
-  if (wg_n < big_cols && wg_m < a.row_tiles && row0 < n_rows) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  if (wg_p < pair_cols && wg_m < a.row_tiles && row0 < n_rows) {
+   for (int part = 0; part < 2; ++part) {
+    const int wg_n = part == 0 ? big_cols - 1 - wg_p : wg_p;
+    if (part == 1 && wg_n >= big_cols - 1 - wg_p) break;     // (an odd number of columns: the middle one is part 0's)
+    // (the thread index is made opaque per part: otherwise everything the epilogue derives from it alone is computed
+    // once, ahead of the first part, and kept in registers through both main loops, which then spill)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r = lane & 31, h = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1, wave_in_sub = wave & 1;
     const int rel_tile0 = wg_n * BIG_T;
@@ -903,48 +912,55 @@ __global__ __launch_bounds__(256, W == 2 ? 2 : 1) void masked_layer_big_kernel(L
         load_to_lds16(Wbase + (size_t)min(2 * q + sub, last_live) * group + co, d + (BIG_T + 2 * q) * BIG_HALF * 16);
       }
     };
-    auto multiply_half = [&](const uint4* cur) {
+    // A half is multiplied in two sub-steps (MFMA step sl = 0, 1 of its blocks).  The fragments of a sub-step are
+    // read from LDS one sub-step ahead, into the register set the sub-step before last has finished with, so the
+    // matrix cores always have a sub-step's worth of MFMAs (2 W^2 of them) whose operands are already in registers
+    // while the next reads are under way -- with one wave per SIMD nothing else would cover the LDS latency:
+    //   read set 1 <- half h, sl 1 | MFMAs on set 0 (half h, sl 0) | barrier, refill, read set 0 <- half h + 1, sl 0 |
+    //   MFMAs on set 1
+    JM_WAIT_DECL();
+    uint4 fa0[BIG_W], fb0[BIG_W], fa1[BIG_W], fb1[BIG_W];
+    auto read_frags = [&](const uint4* cur, int sl, uint4 (&fa)[BIG_W], uint4 (&fb)[BIG_W]) {
 #pragma unroll
-      for (int sl = 0; sl < 2; ++sl) {
-        uint4 af[BIG_W], bf[BIG_W];
+      for (int i = 0; i < BIG_W; ++i) fa[i] = cur[(wm * BIG_W + i) * BIG_HALF + sl * 64 + lane];
 #pragma unroll
-        for (int i = 0; i < BIG_W; ++i) af[i] = cur[(wm * BIG_W + i) * BIG_HALF + sl * 64 + lane];
-#pragma unroll
-        for (int j = 0; j < BIG_W; ++j) bf[j] = cur[(BIG_T + wn * BIG_W + j) * BIG_HALF + sl * 64 + lane];
-#pragma unroll
-        for (int i = 0; i < BIG_W; ++i)
-#pragma unroll
-          for (int j = 0; j < BIG_W; ++j) mfma_step<T>(bf[j], af[i], acc[i][j]);   // (units = rows of the result)
-      }
+      for (int j = 0; j < BIG_W; ++j) fb[j] = cur[(BIG_T + wn * BIG_W + j) * BIG_HALF + sl * 64 + lane];
     };
-    // one ring step: this wave's copies of half hc have landed (the 2 x 8 younger ones may still fly), then
-    // everybody's have and everybody is done reading the stage that half hc + 3 goes to
-    auto ring_step = [&](int hc, const uint4* cur, uint4* refill) {
-      // (no fence here on purpose: a release fence on LDS makes the compiler wait for ALL LDS-bound loads, the
-      // younger halves included.  The memory clobber keeps the compiler from moving LDS reads across.  lgkmcnt(0):
-      // the stage that is refilled below was read in the previous step, and the compiler may have left the last of
-      // those reads in flight with its MFMAs behind this point; every wave's reads have returned before any wave
-      // passes the barrier and requests the refill.)
-      // (two younger halves of 2 W copies per wave each)
+    auto multiply = [&](const uint4 (&fa)[BIG_W], const uint4 (&fb)[BIG_W]) {
+#pragma unroll
+      for (int i = 0; i < BIG_W; ++i)
+#pragma unroll
+        for (int j = 0; j < BIG_W; ++j) mfma_step<T>(fb[j], fa[i], acc[i][j]);   // (units = rows of the result)
+    };
+    // One half.  On entry its sl-0 fragments are on their way into set 0.  The barrier in the middle says: this
+    // wave's copies of half hc + 1 have landed (the 2 x 2 W younger ones may still fly), everybody's have, and
+    // everybody has read all it needs of half hc (lgkmcnt(0): both of its fragment sets have arrived), so half
+    // hc + 4 can be requested into its stage.
+    // (no fence there on purpose: a release fence on LDS makes the compiler wait for ALL LDS-bound loads, the
+    // younger halves included.  The memory clobber keeps the compiler from moving LDS reads across.)
+    auto half_step = [&](int hc, uint4* cur, const uint4* next) {
+      read_frags(cur, 1, fa1, fb1);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(fa0, fb0);
+      __builtin_amdgcn_sched_barrier(0);
+      JM_WAIT_BEGIN();
       if constexpr (W == 4) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
       else asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-      issue_half(hc + 3, refill);
-      multiply_half(cur);
+      JM_WAIT_END();
+      issue_half(hc + 4, cur);
+      read_frags(next, 0, fa0, fb0);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(fa1, fb1);
+      __builtin_amdgcn_sched_barrier(0);
     };
     JM_TSTAMP(EPI == EPI_RELU ? 0 : 3, 0);
-    JM_TRACE_VALUE(EPI == EPI_RELU ? 6 : 7, n_chunks);
     if (n_half > 0) {
-      issue_half(0, big_s0);
-      issue_half(1, big_s1);
-      issue_half(2, big_s2);
-      for (int hc = 0; hc < n_half; hc += 4) {                // n_half is even
-        ring_step(hc, big_s0, big_s3);
-        ring_step(hc + 1, big_s1, big_s0);
-        if (hc + 2 < n_half) {
-          ring_step(hc + 2, big_s2, big_s1);
-          ring_step(hc + 3, big_s3, big_s2);
-        }
-      }
+      for (int hc = 0; hc < 4; ++hc) issue_half(hc, big_ring + hc * BIG_STAGE);
+      if constexpr (W == 4) asm volatile("s_waitcnt vmcnt(24)\n\ts_barrier" ::: "memory");   // half 0 is there
+      else asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");
+      read_frags(big_ring, 0, fa0, fb0);
+      for (int hc = 0; hc < n_half; ++hc)
+        half_step(hc, big_ring + (hc & 3) * BIG_STAGE, big_ring + ((hc + 1) & 3) * BIG_STAGE);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // surplus copies: the epilogue reuses stage 0
     __syncthreads();
@@ -957,11 +973,12 @@ __global__ __launch_bounds__(256, W == 2 ? 2 : 1) void masked_layer_big_kernel(L
       for (int j = 0; j < BIG_W; ++j) asm volatile("" : "+a"(acc[i][j]));
 
     JM_TSTAMP(EPI == EPI_RELU ? 1 : 4, 0);
+    JM_TRACE_VALUE(EPI == EPI_RELU ? 6 : 7, JM_WAIT_PACK(n_chunks));
     // ---- epilogue.  Four units of a sample are contiguous in every array it touches (noise, symbols, and the
     // fragment-major activations: half of a 16-byte piece in bf16, a whole one in fp32), so results leave the
     // registers in 8- and 16-byte pieces without a transposition through LDS.  The operand stages are free now: the
     // workgroup's 256 sample ids go through stage 0.
-    int* ids = (int*)big_s0;
+    int* ids = (int*)big_ring;
     {
       const int row = row0 + tid;
       if (tid < BIG_ROWS) ids[tid] = row < n_rows ? (a.rows ? a.rows[row] : row) : -1;
@@ -1095,6 +1112,8 @@ __global__ __launch_bounds__(256, W == 2 ? 2 : 1) void masked_layer_big_kernel(L
       });
     }
     JM_TSTAMP(EPI == EPI_RELU ? 2 : 5, 1);
+    __syncthreads();                                           // (the sample ids in stage 0 make way for operands)
+   }
   }
   if (EPI == EPI_BERNOULLI && a.retire.enabled) finish_pass(a.retire, gridDim.x);
 }
