@@ -33,6 +33,25 @@ def build_library(verbose: bool = True, out_path: str = LIB_PATH, defines=()) ->
     return out_path
 
 
+PROBES = os.path.join(HERE, "probes")
+
+
+def build_probes(verbose: bool = True) -> None:
+    """The stand-alone measurement probes (probes/*.hip -> probes/bin/<name>): what plain loops of the kernels' shape
+    reach on the chip.  The library does not use them; profiles/ quotes their output next to the kernels' figures."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    os.makedirs(os.path.join(PROBES, "bin"), exist_ok=True)
+    for name in sorted(f[:-4] for f in os.listdir(PROBES) if f.endswith(".hip")):
+        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               os.path.join(PROBES, name + ".hip"), "-o", os.path.join(PROBES, "bin", name)]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if proc.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + proc.stdout)
+
+
 if __name__ == "__main__":
     build_library()
+    build_probes()
     sys.exit(0)
