@@ -1375,8 +1375,9 @@ __global__ __launch_bounds__(NW * 64) void persistent_sampler_kernel(PersistArgs
 // barrier with workgroup scope does nothing on this chip outside threadgroup-split mode -- results went wrong --
 // and with device scope it made a phase cost 20 us.)  Nothing crosses to another XCD's L2, which is what made
 // each phase of the device-wide persistent kernel cost 10-15 us; here a phase is ~7 us on the D = 784, 2 x 2000
-// network (against 4.5-8 us for a launch of the per-layer kernels) and ~4 us on small ones.  A workgroup learns its XCD from the hardware's XCC id; the scheme
-// needs gridDim / 8 workgroups on each of the 8 XCDs, all resident at once.  If that does not hold the whole grid
+// network (against 4.5-8 us for a launch of the per-layer kernels) and ~4 us on small ones.  A workgroup learns
+// its XCD from the hardware's XCC id; the scheme needs gridDim / 8 workgroups on each of the 8 XCDs, all
+// resident at once.  If that does not hold the whole grid
 // backs out (flag 4: surplus workgroup on an XCD; flag 2: a barrier's bounded wait ran out), so the grid always
 // drains, and the host takes the per-layer path instead.
 // ------------------------------------------------------------------------------------------------
