@@ -288,6 +288,8 @@ def parse_args(argv=None):
                     help="batch size from which the 256 x 256 tile kernels are used (0 = library default)")
     ap.add_argument("--mid-tile-batch", type=int, default=0,
                     help="batch size from which the 128 x 128 tile kernels are used (0 = library default)")
+    ap.add_argument("--lazy-stop-test", type=int, default=-1, choices=[-1, 0, 1],
+                    help="MADE_OPT_LAZY_STOP_TEST (-1 = library default)")
     ap.add_argument("--retire-split", type=int, default=0,
                     help="active-list length from which the stop test runs as a kernel of its own (0 = library default)")
     ap.add_argument("--conv-rows", type=int, default=0,
@@ -337,6 +339,8 @@ def run_one(args, torch, B, S, light=False):
         B.made_set_option(model, B.MADE_OPT_MID_TILE_BATCH, args.mid_tile_batch)
     if args.retire_split > 0:
         B.made_set_option(model, B.MADE_OPT_RETIRE_SPLIT, args.retire_split)
+    if args.lazy_stop_test >= 0 and not conv:
+        B.made_set_option(model, B.MADE_OPT_LAZY_STOP_TEST, args.lazy_stop_test)
     n_layers = (w.n_conv if conv else len(net.hidden)) + 1
     nnz = B.made_layer_nnz(model, n_layers)
     n_slots = n_layers + 1                     # per-layer kernels + the persistent whole-call kernel

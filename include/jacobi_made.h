@@ -244,6 +244,7 @@ int gs_jacobi_sample_real(made_model* m, const float* noise, int32_t N, const fl
  *   out[3] host waits on the device
  *   out[4] convolutional model: image rows recomputed by the k x k layers, summed over passes and images (a pass
  *          only recomputes the rows below the first symbol that changed in the pass before); 0 otherwise
+ *   out[5] passes whose stop test had no tail (MADE_OPT_LAZY_STOP_TEST: the next pass derived its list itself)
  * n = number of int64 slots available in out (extra slots are left untouched).
  */
 int made_last_stats(const made_model* m, int64_t* out, int32_t n);
@@ -264,6 +265,11 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   batch <= 2048 from ONE cooperative launch that keeps a workgroup per CU resident and separates layers by
  *   a grid-wide barrier; 0 = one kernel launch per layer and pass.  Same results either way; on MI355X the
  *   per-layer launches are currently the faster of the two at batch 128, hence the default.
+ *   MADE_OPT_LAZY_STOP_TEST (default 1; 0 or 1): jacobi_sample of a Bernoulli model on at most 256 samples (per-layer
+ *   launches): the sampling kernel of a pass only records which samples changed, and every workgroup of the next
+ *   pass's first kernel derives that pass's list of active samples from the record -- in the memory round trip in
+ *   which it would otherwise read the list -- instead of the previous pass's last workgroup compacting it in a tail
+ *   of three dependent round trips.  Same results and pass counts; 0 keeps the tail.
  *   MADE_OPT_XCD_RESIDENT (default 1; 0, 1 or 2): jacobi_sample / gs_jacobi_sample of Bernoulli models in ONE launch in
  *   which every XCD (a group of compute units with an L2 of its own) iterates its own eighth of the samples through
  *   all passes, synchronising only among its own workgroups and through its own L2 -- samples are independent
@@ -318,7 +324,8 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  */
 enum { MADE_OPT_PERSISTENT = 1, MADE_OPT_FUSED_CATEGORICAL = 2, MADE_OPT_CHAINS = 3, MADE_OPT_BIG_TILE_BATCH = 4,
        MADE_OPT_CONV_ROWS = 5, MADE_OPT_PREFIX_CACHE = 6, MADE_OPT_RESIDENT = 7, MADE_OPT_RETIRE_SPLIT = 8,
-       MADE_OPT_MID_TILE_BATCH = 9, MADE_OPT_PARTIAL_SUM_BATCH = 10, MADE_OPT_XCD_RESIDENT = 11 };
+       MADE_OPT_MID_TILE_BATCH = 9, MADE_OPT_PARTIAL_SUM_BATCH = 10, MADE_OPT_XCD_RESIDENT = 11,
+       MADE_OPT_LAZY_STOP_TEST = 12 };
 int made_set_option(made_model* m, int32_t option, int32_t value);
 
 /*

@@ -124,6 +124,7 @@ struct Chain {
   int bound = 0;                     // upper limit of the active count in the current block: the chain's size, then
                                      // what the latest confirmed pass left (the list only shrinks inside a block)
   bool block_started = false, finished = false, iters_cleared = false;
+  bool lazy = false;                 // this call's passes use the tail-less stop test (see DeriveArgs)
   std::vector<char> log_first;       // per enqueued pass: was it the first of its block
 };
 
@@ -148,6 +149,7 @@ struct Workspace {
   int partial_cap = 0;               // first use, for partial_cap samples)
   float* zero_bias = nullptr;        // [largest out_pad] zeros: the launches that fill `partial` add no bias
   int* changed = nullptr;
+  unsigned* lazy_masks = nullptr;    // [3 * DERIVE_WORDS] changed-row bits of the tail-less stop test (see DeriveArgs)
   int* iters = nullptr;
   int* call_iters = nullptr;         // where the current call counts passes per sample: the caller's iters_out, else `iters`
   bool pending = false;              // the last call returned with (empty, speculative) kernels still queued on
@@ -199,7 +201,7 @@ struct made_model {
   // degree, so these are prefix lengths
   std::vector<std::vector<int>> cnt_lt;
   Workspace ws;
-  int64_t stats[5] = {0, 0, 0, 0, 0};
+  int64_t stats[6] = {0, 0, 0, 0, 0, 0};
   // Jacobi-GS (Algorithm 2): symbols of the virtual samples, per-sub-step position table, per-sample state
   uint8_t* jgs_xv = nullptr;
   size_t jgs_xv_cap = 0;
@@ -231,6 +233,8 @@ struct made_model {
   int fused_categorical = 1;                  // made_set_option(MADE_OPT_FUSED_CATEGORICAL)
   int use_persistent = 0;                     // made_set_option(MADE_OPT_PERSISTENT): 1 = the device-wide cooperative kernel
                                               // (measured slower, see header)
+  int lazy_retire = 1;                        // made_set_option(MADE_OPT_LAZY_STOP_TEST): 1 = Jacobi on lists of up to 256 samples
+                                              // derives a pass's list in its first kernel instead of in the previous one's tail
   int use_xcd = 1;                            // made_set_option(MADE_OPT_XCD_RESIDENT): 0 never, 1 where it pays, 2 whenever possible
   int xcd_grid = 0;                           // workgroups of xcd_sampler_kernel (0 = not usable on this device / model)
   // sample-resident kernel (resident_sampler_kernel): LDS layout, 0 bytes = this model does not fit
@@ -267,6 +271,7 @@ static void free_workspace(Workspace& w) {
   if (w.bar) (void)hipFree(w.bar);
   if (w.dev_stats) (void)hipFree(w.dev_stats);
   if (w.changed) (void)hipFree(w.changed);
+  if (w.lazy_masks) (void)hipFree(w.lazy_masks);
   if (w.iters) (void)hipFree(w.iters);
   if (w.flags) (void)hipFree(w.flags);
   if (w.h_pin) (void)hipHostFree((void*)w.h_pin);
@@ -338,6 +343,8 @@ static int ensure_workspace(made_model* m, int N, bool need_z) {
   }
   HIP_TRY(hipEventCreateWithFlags(&w.fork_ev, hipEventDisableTiming));
   HIP_TRY(hipMalloc((void**)&w.changed, (size_t)2 * n_pad * CHG * sizeof(int)));   // one counter per 128-byte line
+  HIP_TRY(hipMalloc((void**)&w.lazy_masks, (size_t)64 * sizeof(unsigned)));
+  HIP_TRY(hipMemset(w.lazy_masks, 0, (size_t)64 * sizeof(unsigned)));
   w.n_pad = n_pad;
   // (xcd_sampler_kernel: per XCD a flag array for its barrier and a counter for the registration of its workgroups,
   // and the word in which it keeps counting its barriers from call to call)
@@ -422,7 +429,7 @@ extern "C" const char* made_last_error(void) { return g_last_error.c_str(); }
 
 extern "C" int made_last_stats(const made_model* m, int64_t* out, int32_t n) {
   if (!m || !out || n < 0) return fail(MADE_ERR_ARG, "made_last_stats: NULL argument");
-  for (int i = 0; i < n && i < 5; ++i) out[i] = m->stats[i];
+  for (int i = 0; i < n && i < 6; ++i) out[i] = m->stats[i];
   return MADE_OK;
 }
 
@@ -443,6 +450,11 @@ extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
   if (!m) return fail(MADE_ERR_ARG, "made_set_option: model is NULL");
   if (option == MADE_OPT_PERSISTENT) {
     m->use_persistent = value != 0;
+    return MADE_OK;
+  }
+  if (option == MADE_OPT_LAZY_STOP_TEST) {
+    if (value != 0 && value != 1) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_LAZY_STOP_TEST=%d must be 0 or 1", value);
+    m->lazy_retire = value;
     return MADE_OK;
   }
   if (option == MADE_OPT_XCD_RESIDENT) {
@@ -951,6 +963,8 @@ struct SampleIO {          // what the sampling epilogue reads and writes
   uint8_t* x;              // symbols; for a model with real states this is a float [N, D] buffer
   int t_lo, t_hi;
   RetireArgs retire;       // retire.enabled = 0: no stop test after this pass (sequential sampling)
+  unsigned* lazy_mask = nullptr;   // Bernoulli MLP: changed rows go here as bits and the next pass derives its list from
+                                   // them (see DeriveArgs); retire.enabled is 0 then
 };
 
 template <typename T, int EPI>
@@ -1069,7 +1083,7 @@ struct PartialSums {
 
 static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, int in_limit0, hipStream_t s,
                       const int* unit_first = nullptr, bool by_pos = false, const ActBuffers* buf = nullptr,
-                      const PartialSums* ps = nullptr) {
+                      const PartialSums* ps = nullptr, const DeriveArgs* derive = nullptr) {
   const int row_tiles = (rs.n_rows + TILE - 1) / TILE;
   const int kc = chunk_elems(m);
   int in_limit = in_limit0;
@@ -1089,6 +1103,7 @@ static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, in
     }
     a.a_by_pos = by_pos && l > 0;
     a.out_by_pos = by_pos;
+    if (l == 0 && derive) a.derive = *derive;
     if (l == 0 && m->onehot) {
       if (!rs.x) return fail(MADE_ERR_ARG, "internal: a one-hot first layer needs the symbols");
       if (rs.n_rows > 65535) return fail(MADE_ERR_ARG, "one-hot input: at most 65535 samples per call");
@@ -1170,6 +1185,7 @@ static int run_output_sample(made_model* m, const RowSet& rs, const SampleIO& io
     a.t_lo = io.t_lo;
     a.t_hi = io.t_hi;
     a.retire = io.retire;
+    a.lazy_mask = io.lazy_mask;
     a.io_aligned = (m->D % 16 == 0) && ((uintptr_t)io.noise % 16 == 0) && ((uintptr_t)io.x % 16 == 0);
     if (ps && ps->k_first[m->L] > 0) {
       a.k_begin = ps->k_first[m->L];
@@ -1718,6 +1734,28 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
   const int n_bound = std::max(1, std::min(c.bound, c.count));
   RowSet rs{c.rows[in], c.n_rows[in], n_bound, x, c.first};
   SampleIO io{noise, x, blk.a, blk.b, RetireArgs{}};
+  // Tail-less stop test (see DeriveArgs): pass k only records which rows changed; pass k + 1's first kernel derives
+  // its list from that, reports pass k's result and counts it.  The last allowed pass keeps the ordinary tail (no
+  // pass follows it), and so does everything the conditions below exclude.
+  const bool lazy_out = c.lazy && k < blk.cap;
+  const bool derive_in = c.lazy && k > 1;
+  DeriveArgs dv;
+  memset(&dv, 0, sizeof dv);
+  if (derive_in) {
+    // pass k - 1 read list (k - 2) & 1 and left its bits in set (k - 1) % 3; this pass's list goes where the
+    // tail of pass k - 1 would have put it
+    dv.enabled = 1;
+    dv.rows_in = c.rows[k & 1];
+    dv.n_in = c.n_rows[k & 1];
+    dv.rows_out = c.rows[in];
+    dv.n_out = c.n_rows[in];
+    dv.mask_in = w.lazy_masks + ((k - 1) % 3) * DERIVE_WORDS;
+    dv.mask_clear = w.lazy_masks + ((k + 1) % 3) * DERIVE_WORDS;
+    dv.iters = w.call_iters;
+    dv.pass = k - 1;
+    dv.n_max = std::max(1, std::min(c.count, DERIVE_MAX_ROWS));
+    dv.host_slot = c.d_pin + c.pin_base + ((int)c.log_first.size() - 1);
+  }
   if (blk.stop_test) {
     const int slot = (int)c.log_first.size();
     if (slot >= c.pin_half - 1) return fail(MADE_ERR_HIP, "internal: pass log overflow");   // (the half's last word mirrors the flags)
@@ -1735,7 +1773,11 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
     io.retire.host_flags = c.d_pin + c.pin_base + (c.pin_half - 1);
     io.retire.last_pass = (k == blk.cap);
     io.retire.flag_unconverged = flag_unconverged;
-    io.retire.enabled = 1;
+    io.retire.enabled = lazy_out ? 0 : 1;
+    if (lazy_out) {
+      io.lazy_mask = w.lazy_masks + (k % 3) * DERIVE_WORDS;
+      m->stats[5]++;
+    }
     c.log_first.push_back(k == 1);
   } else {
     rs = RowSet{c.rows[0], nullptr, c.count, x, c.first};   // no stop test: every sample of the chain takes the pass
@@ -1754,7 +1796,8 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
     PartialSums ps{blk.k_first.data(), w.partial.data()};
     if (use_partial && k == 2) TRY(fill_partial_sums(m, rs, blk, s));
     TRY(run_hidden(m, rs, blk.limited ? blk.hidden_limit.data() : nullptr, blk.in_limit, s,
-                   cached ? blk.hidden_frozen.data() : nullptr, by_pos, nullptr, use_partial ? &ps : nullptr));
+                   cached ? blk.hidden_frozen.data() : nullptr, by_pos, nullptr, use_partial ? &ps : nullptr,
+                   derive_in ? &dv : nullptr));
     // a long list is retired by a kernel of its own, spread over the chip, instead of by the output kernel's
     // last workgroup
     const RetireArgs retire = io.retire;
@@ -1808,6 +1851,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
     c.k_enq = c.k_conf = 0;
     c.bound = c.count;
     c.block_started = c.finished = c.iters_cleared = false;
+    c.lazy = false;
     c.log_first.clear();
     c.stream = n_chains == 1 ? s : c.own_stream;   // a single chain needs no fork and join
   }
@@ -1828,6 +1872,11 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
     r.iters = w.call_iters;
     r.done_ctr = c.done_ctr;
     r.flags = w.flags;
+    // (conditions of the tail-less stop test: Algorithm 1 of a Bernoulli MLP on one chain whose list fits one
+    // workgroup's threads and whose layers run on the 32 x 32 tile kernel)
+    c.lazy = m->lazy_retire && m->C == 1 && !m->real && blocks.size() == 1 && blocks[0].stop_test && !blocks[0].limited &&
+             c.count <= DERIVE_MAX_ROWS && c.count < std::min(m->mid_batch, m->big_batch) && c.count < m->retire_split;
+    r.lazy_masks = c.lazy ? w.lazy_masks : nullptr;
     TRY(launch_init_state(m, x_init, x, N, s, &r));
     c.block_started = true;
     c.iters_cleared = true;

@@ -157,6 +157,32 @@ struct RetireArgs {
   int enabled;
 };
 
+// Stop test without a tail (short lists, at most DERIVE_MAX_ROWS samples).  retire_tail above costs the pass's last
+// kernel three dependent memory round trips after its arithmetic is done (counter atomics performed -> arrival
+// counter -> the last workgroup reads the counters).  Instead, the sampling kernel of pass k only ORs one bit per
+// changed row into a word per row tile (`LayerArgs::lazy_mask`, by position in pass k's list), and EVERY workgroup
+// of the next pass's first kernel derives pass k + 1's list for itself, in LDS, from pass k's list and those words
+// -- the same memory round trip in which it would otherwise read the list.  Workgroup 0 also stores the new list and
+// count for the pass's other kernels, records the pass counts, clears the mask words of the pass after next and
+// reports to the host.  Three sets of mask words rotate: pass k writes set k % 3, pass k + 1 reads it and clears
+// set (k + 2) % 3, which was last read a whole pass earlier.
+constexpr int DERIVE_MAX_ROWS = 256;
+constexpr int DERIVE_WORDS = DERIVE_MAX_ROWS / 32;
+static_assert(NW * 64 >= DERIVE_MAX_ROWS + 64, "one thread per list entry, padding included");
+struct DeriveArgs {
+  int enabled;
+  const int* rows_in;       // the previous pass's list and count
+  const int* n_in;
+  int* rows_out;            // this pass's list and count (written by workgroup 0)
+  int* n_out;
+  const unsigned* mask_in;  // [DERIVE_WORDS] bit r of word t: row 32 t + r of rows_in changed in the previous pass
+  unsigned* mask_clear;     // [DERIVE_WORDS] the set the pass after this one will write
+  int* iters;               // per-sample pass counts: the samples of rows_in took pass `pass`
+  int pass;
+  int n_max;                // upper bound of *n_in known to the host
+  int* host_slot;           // pinned host word receiving this pass's active count (= what the previous pass left)
+};
+
 struct LayerArgs {
   // operands, both in fragment-major layout with k_chunks chunks per row group:
   // A = activations [sample, K], W = masked weights [unit, K]
@@ -211,6 +237,8 @@ struct LayerArgs {
   float* xr;             // [sample, D] real states, updated in place
   float eps;
   RetireArgs retire;
+  unsigned* lazy_mask;   // EPI_BERNOULLI: changed rows are recorded as bits here instead of in `changed` (see DeriveArgs)
+  DeriveArgs derive;     // EPI_RELU, first layer of a pass: the list comes from the previous pass's mask words
 };
 
 // Store that other workgroups of the SAME kernel will read after a grid barrier.  COH = true writes through to
@@ -654,6 +682,8 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
   }
 
   JM_TSTAMP(2, 1);
+  __shared__ unsigned tile_mask_s;     // rows of this tile with a changed symbol (lazy stop test)
+  if (EPI == EPI_BERNOULLI && threadIdx.x == 0) tile_mask_s = 0;
   // acc[i] is the tile element (row = 8*(i/4) + 4*h + i%4, col = r): rows come from A = samples
 #pragma unroll
   for (int i = 0; i < 16; ++i) part[wave][(i >> 2) * 8 + h * 4 + (i & 3)][r] = acc[i];
@@ -722,6 +752,8 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
       if (cc == 0 && cnt > 0) {
         if constexpr (XCD_LOCAL)
           count_old[j] = __hip_atomic_fetch_add(&a.changed[(size_t)sample * CHG], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        else if (a.lazy_mask)
+          atomicOr(&tile_mask_s, 1u << rr);
         else
           count_old[j] = __hip_atomic_fetch_add(&a.changed[(size_t)sample * CHG], cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
@@ -730,6 +762,13 @@ __device__ __forceinline__ void compute_tile(const LayerArgs& a, int rel_tile, i
   if (EPI == EPI_BERNOULLI || EPI == EPI_LOGISTIC) {
 #pragma unroll
     for (int j = 0; j < EPT; ++j) asm volatile("" ::"v"(count_old[j]));
+  }
+  if constexpr (EPI == EPI_BERNOULLI && !XCD_LOCAL) {
+    if (a.lazy_mask) {   // (uniform) one update per tile; the next kernel reads it, so nobody waits for it here
+      __syncthreads();
+      if (threadIdx.x == 0 && tile_mask_s)
+        __hip_atomic_fetch_or(&a.lazy_mask[row0 / TILE], tile_mask_s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
   }
   JM_TSTAMP(4, 0);
   JM_TSTAMP(5, 1);
@@ -759,6 +798,42 @@ __global__ __launch_bounds__(NW * 64) void masked_layer_kernel(LayerArgs a) {
       b.t_hi = j + 1;
       compute_tile<T, EPI, false>(b, j / TILE - a.tile_begin, blockIdx.x * TILE, a.rows, a.n_rows, part);
     }
+  } else if (EPI == EPI_RELU && a.derive.enabled) {
+    // this pass's list, derived by every workgroup for itself (see DeriveArgs); NW * 64 >= DERIVE_MAX_ROWS threads
+    __shared__ int drv_rows[DERIVE_MAX_ROWS + 64];
+    __shared__ int drv_wave[NW];
+    const DeriveArgs& d = a.derive;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int n_prev = min(*d.n_in, d.n_max);
+    const int sample = t < d.n_max ? d.rows_in[t] : 0;                 // (the list is padded with valid ids)
+    const unsigned word = t < DERIVE_MAX_ROWS ? d.mask_in[t >> 5] : 0u;
+    const int fill = d.rows_in[0];
+    const bool keep = t < n_prev && ((word >> (t & 31)) & 1u);
+    const unsigned long long m = __ballot(keep);
+    if (lane == 0) drv_wave[wave] = __popcll(m);
+    if (t < DERIVE_MAX_ROWS + 64) drv_rows[t] = fill;                  // whole tiles of the list are read
+    __syncthreads();
+    int off = 0, new_n = 0;
+    for (int w = 0; w < NW; ++w) {
+      if (w < wave) off += drv_wave[w];
+      new_n += drv_wave[w];
+    }
+    const int pos = off + __popcll(m & ((1ull << lane) - 1ull));
+    if (keep) drv_rows[pos] = sample;
+    const int padded = (new_n + 63) & ~63;
+    if (blockIdx.x == 0) {
+      if (keep) d.rows_out[pos] = sample;
+      if (t >= new_n && t < padded) d.rows_out[t] = fill;
+      if (t < n_prev) d.iters[sample] = d.pass;
+      if (t < DERIVE_WORDS) d.mask_clear[t] = 0u;
+      if (t == 0) {
+        *d.n_out = new_n;
+        __hip_atomic_store(d.host_slot, new_n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+      }
+    }
+    __syncthreads();
+    if (item_to_tile(blockIdx.x, a.n_launch_tiles, a.row_tiles, rel_tile, row0))
+      compute_tile<T, EPI, false>(a, rel_tile, row0, drv_rows, new_n, part);
   } else if (item_to_tile(blockIdx.x, a.n_launch_tiles, a.row_tiles, rel_tile, row0)) {
     // (the active count is requested here but first looked at inside compute_tile, after the tile's other
     // bookkeeping loads are on their way: one dependent memory round trip less than testing it first)
@@ -2490,6 +2565,7 @@ struct CallReset {
   int* iters;
   int* done_ctr;
   int* flags;
+  unsigned* lazy_masks;  // [3 * DERIVE_WORDS] (see DeriveArgs), or NULL
 };
 
 __device__ __forceinline__ void call_reset(const CallReset& r) {
@@ -2502,6 +2578,7 @@ __device__ __forceinline__ void call_reset(const CallReset& r) {
       r.changed[(size_t)(r.first + i) * CHG] = 0;
       r.iters[r.first + i] = 0;
     }
+    if (r.lazy_masks && i < 3 * DERIVE_WORDS) r.lazy_masks[i] = 0u;
     if (i == 0) {
       *r.n_rows = r.count;
       *r.done_ctr = 0;

@@ -36,6 +36,7 @@ RESIDENT = 0           # sample-resident kernel: 0 never, 1 whenever the model f
 FUSED_CATEGORICAL = True
 CHAINS = 4
 RETIRE_SPLIT = None   # None: the library's default; 1: the stop test always runs as a kernel of its own
+LAZY = None           # stop test without a tail (Jacobi, Bernoulli, one chain of up to 256 samples): None = library default (on)
 XCD = 0               # whole-call kernel with one share of the batch per XCD: 0 never, 2 whenever the batch fits, None: library default
 
 
@@ -51,6 +52,8 @@ class GpuModel:
             B.made_set_option(self.h, B.MADE_OPT_RETIRE_SPLIT, RETIRE_SPLIT)
         if XCD is not None:
             B.made_set_option(self.h, B.MADE_OPT_XCD_RESIDENT, XCD)
+        if LAZY is not None:
+            B.made_set_option(self.h, B.MADE_OPT_LAZY_STOP_TEST, LAZY)
         if big_tile_batch is not None:
             B.made_set_option(self.h, B.MADE_OPT_BIG_TILE_BATCH, big_tile_batch)
         if mid_tile_batch is not None:

@@ -16,7 +16,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.fixture(autouse=True, params=["per-layer launches", "single chain", "persistent", "sample-resident",
-                                      "library defaults", "unfused categorical", "xcd-resident"])
+                                      "library defaults", "unfused categorical", "xcd-resident", "tail-less stop test"])
 def execution_path(request):
     """Every test runs on every execution path of the library (they must all agree with the oracle)."""
     import gpu_util
@@ -24,17 +24,20 @@ def execution_path(request):
         name = getattr(request.node, "callspec", None) and request.node.callspec.params.get("name")
         if name not in ("small_cat", "small_cat_onehot"):
             pytest.skip("only the 256-class workloads have a fused and an unfused output path")
-    if request.param in ("sample-resident", "xcd-resident"):
+    if request.param in ("sample-resident", "xcd-resident", "tail-less stop test"):
         name = getattr(request.node, "callspec", None) and request.node.callspec.params.get("name")
         if name is not None and "cat" in name:
-            pytest.skip("the sample-resident and XCD-resident kernels serve Bernoulli models only")
+            pytest.skip("the sample-resident and XCD-resident kernels and the tail-less stop test serve Bernoulli models only")
     gpu_util.PERSISTENT = request.param == "persistent"
     gpu_util.RESIDENT = 1 if request.param == "sample-resident" else (2 if request.param == "library defaults" else 0)
     gpu_util.FUSED_CATEGORICAL = request.param != "unfused categorical"
-    gpu_util.CHAINS = 1 if request.param in ("single chain", "library defaults") else 4
+    gpu_util.CHAINS = 1 if request.param in ("single chain", "library defaults", "tail-less stop test") else 4
+    # (the list of a pass derived by its own first kernel: Jacobi on one chain of per-layer launches)
+    gpu_util.LAZY = 1 if request.param == "tail-less stop test" else (None if request.param == "library defaults" else 0)
     gpu_util.RETIRE_SPLIT = 1 if request.param == "single chain" else None   # (the stop test as its own kernel)
     gpu_util.XCD = 2 if request.param == "xcd-resident" else (None if request.param == "library defaults" else 0)
     yield
+    gpu_util.LAZY = None
     gpu_util.XCD = 0
     gpu_util.RETIRE_SPLIT = None
     gpu_util.PERSISTENT = False
@@ -370,3 +373,43 @@ def test_xcd_resident_kernel_serves_the_call():
             xb2, itb2 = g.gs_jacobi(noise, 16)
             assert (x == x2).all() and (it == it2).all() and st["passes"] == it.max() and st["sample_passes"] == it.sum()
             assert (xb == xb2).all() and (itb == itb2).all()
+
+
+def test_tail_less_stop_test_serves_the_call_and_changes_nothing():
+    """MADE_OPT_LAZY_STOP_TEST = 1: every pass but a call's last allowed one has no tail (the next pass derives its
+    list), and symbols, per-sample pass counts and the call's statistics are those of the tail, bit for bit -- from
+    zeros, from a random start, and when the pass limit cuts the call short."""
+    import gpu_util
+    if gpu_util.LAZY != 1:
+        pytest.skip("runs once, on the tail-less execution path")
+    for name in ("mid_bf16", "small_f32", "small_bf16", "cfg1"):
+        w = S.workload(name)
+        net = S.make_network(w, with_bias=True)
+        noise = S.make_noise(w)
+        x0 = _symbols(w, np.random.default_rng(9), w.N)
+        with GpuModel(net) as g:
+            for init, limit in ((None, 0), (x0, 0), (None, 2), (x0, 3)):
+                res = {}
+                for lazy in (1, 0):
+                    B.made_set_option(g.h, B.MADE_OPT_LAZY_STOP_TEST, lazy)
+                    x = torch.empty((w.N, w.D), dtype=torch.uint8, device="cuda")
+                    it = torch.full((w.N,), -7, dtype=torch.int32, device="cuda")
+                    code = 0
+                    try:
+                        B.jacobi_sample(g.h, dev(noise), w.N, None if init is None else dev(init), limit, x, it)
+                    except B.MadeError as e:
+                        code = e.code
+                    torch.cuda.synchronize()
+                    st = g.stats()
+                    res[lazy] = (x.cpu().numpy(), it.cpu().numpy(), code, st)
+                    if lazy and limit == 0:
+                        assert st["tail_less_passes"] >= st["passes"] >= 1, st     # (every pass, the speculative one included)
+                    elif lazy:
+                        assert 0 < st["tail_less_passes"] <= limit - 1, st        # (the last allowed pass keeps its tail)
+                    else:
+                        assert st["tail_less_passes"] == 0
+                a, b = res[1], res[0]
+                assert (a[0] == b[0]).all() and (a[1] == b[1]).all() and a[2] == b[2], (name, limit)
+                assert a[3]["passes"] == b[3]["passes"] and a[3]["sample_passes"] == b[3]["sample_passes"]
+                if limit:
+                    assert a[2] in (0, B.MADE_ERR_NOT_CONVERGED)
