@@ -23,7 +23,7 @@ PEAK_BF16_TFLOPS = 2500.0       # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3
 
 
-def cpu_baseline(w, net, noises, budget_s=12.0):
+def cpu_baseline(w, net, noises, budget_s=12.0, single_thread_s=0.0):
     """The numpy oracle's sequential sampler, as it stands, on a bounded sample of the workload: whole batches
     (different noise each) until about budget_s seconds of CPU work are done, at least one batch."""
     from oracle import made_oracle as O
@@ -46,9 +46,26 @@ def cpu_baseline(w, net, noises, budget_s=12.0):
         if time.perf_counter() - t0 > budget_s:
             break
     dt = time.perf_counter() - t0
-    return {"value": done / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+    base = {"value": done / dt, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
             "sample": f"oracle sequential_sample (numpy fp64, activations rounded as on the GPU) on {done} samples "
-                      f"({done // sub} x {sub} of a batch of {noises[0].shape[0]}), {dt:.1f} s"}, xs0, sub
+                      f"({done // sub} x {sub} of a batch of {noises[0].shape[0]}), {dt:.1f} s"}
+    if single_thread_s > 0:
+        # the same oracle held to one thread (the other mode a CPU baseline is usually quoted in), on a smaller sample
+        try:
+            from threadpoolctl import threadpool_limits
+            n1 = max(1, min(sub, 16))
+            with threadpool_limits(limits=1):
+                t1 = time.perf_counter()
+                reps1 = 0
+                while reps1 == 0 or time.perf_counter() - t1 < single_thread_s:
+                    O.sequential_sample(model, noises[0][:n1])
+                    reps1 += 1
+                d1 = time.perf_counter() - t1
+            base["single_thread"] = {"value": reps1 * n1 / d1, "unit": "samples/s", "cores": 1,
+                                     "sample": f"{reps1} x {n1} samples, {d1:.1f} s"}
+        except Exception as e:   # (threadpoolctl missing: the figure is left out)
+            base["single_thread"] = {"error": str(e)}
+    return base, xs0, sub
 
 
 def coupling_sweep(w, torch, B, S, stream):
@@ -669,7 +686,7 @@ def run_one(args, torch, B, S, light=False):
         # hours, not seconds; the scalar-input workload of the same shape (cfg4) carries the CPU baseline
         result["cpu_baseline"] = None
     elif not args.no_cpu_baseline:
-        base, xs, n2 = cpu_baseline(w, net, noises_host, 6.0 if light else 12.0)
+        base, xs, n2 = cpu_baseline(w, net, noises_host, 6.0 if light else 12.0, 0.0 if light else 4.0)
         result["cpu_baseline"] = base
         if x_jac is not None:
             result["cpu_baseline"]["gpu_matches_oracle_on_sample"] = bool(
