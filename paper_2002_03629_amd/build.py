@@ -19,9 +19,10 @@ FLAGS = [
 ]
 
 
-def build_library(verbose: bool = True, out_path: str = LIB_PATH, defines=()) -> str:
+def build_library(verbose: bool = True, out_path: str = LIB_PATH, defines=(), extra_flags=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS + ["-D" + d for d in defines] + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", out_path]
+    cmd = ([hipcc] + FLAGS + list(extra_flags) + ["-D" + d for d in defines] + [os.path.join(CSRC, s) for s in SOURCES] +
+           ["-o", out_path])
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
