@@ -31,8 +31,25 @@ def assert_counts_close(it, it_ref, min_margin, x, x_ref, same_floor):
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture
+def library_defaults():
+    """The models of a test run with the options the library itself defaults to (what bench.py times): one chain, the
+    tail-less stop test, the one-launch kernels where the library chooses them."""
+    import gpu_util
+    old = (gpu_util.CHAINS, gpu_util.RESIDENT, gpu_util.XCD, gpu_util.LAZY, gpu_util.RETIRE_SPLIT)
+    gpu_util.CHAINS, gpu_util.RESIDENT, gpu_util.XCD, gpu_util.LAZY, gpu_util.RETIRE_SPLIT = 1, 2, None, None, None
+    yield
+    gpu_util.CHAINS, gpu_util.RESIDENT, gpu_util.XCD, gpu_util.LAZY, gpu_util.RETIRE_SPLIT = old
+
+
+def test_cfg2_full_batch_as_benchmarked(library_defaults):
+    """cfg2 in the launch configuration bench.py times (library defaults): Jacobi on per-layer launches with the
+    tail-less stop test, GS-Jacobi in the one-launch kernel."""
+    test_cfg2_jacobi_and_gs_jacobi_full_batch(False, expect_default_paths=True)
+
+
 @pytest.mark.parametrize("persistent", [True, False])
-def test_cfg2_jacobi_and_gs_jacobi_full_batch(persistent):
+def test_cfg2_jacobi_and_gs_jacobi_full_batch(persistent, expect_default_paths=False):
     w = S.workload("cfg2")
     net = S.make_network(w)
     exact, same = oracle_models(net)
@@ -42,6 +59,9 @@ def test_cfg2_jacobi_and_gs_jacobi_full_batch(persistent):
     xr, it_ref, _, _, mm = O.jacobi_reference(same, noise)
     with GpuModel(net, persistent) as g:
         x, it = g.jacobi(noise)
+        if expect_default_paths:
+            st = g.stats()
+            assert st["tail_less_passes"] >= st["passes"] > 0 and st["kernels"] > 3, st
         exempt, _ = assert_sample_parity(same, noise, x)
         assert_sample_parity(same, noise[:sub], x[:sub], xs, mg)
         clear, same_frac, equal_counts = assert_counts_close(it, it_ref, mm, x, xr, same_floor=0.85)
@@ -53,6 +73,8 @@ def test_cfg2_jacobi_and_gs_jacobi_full_batch(persistent):
         print(f"cfg2 layer certificate at the Jacobi result: worst logit accumulation error {worst:.2f} x 2^-24 sum|a w|")
         for block in w.block_sizes:
             xb, itb = g.gs_jacobi(noise, block)
+            if expect_default_paths:
+                assert g.stats()["kernels"] == 1, g.stats()      # (the whole call in one launch)
             assert_sample_parity(same, noise, xb)
             assert_sample_parity(same, noise[:sub], xb[:sub], xs, mg)
             ref = O.gs_jacobi_reference(same, noise[:sub], block)
@@ -67,7 +89,7 @@ def test_cfg2_jacobi_and_gs_jacobi_full_batch(persistent):
 
 
 @pytest.mark.timeout(900)
-def test_cfg4_categorical_full_size():
+def test_cfg4_categorical_full_size(library_defaults):
     """D = 1024 positions x 256 classes, 2 x 4096 hidden, 2 GiB output layer, batch 64.  The whole batch is
     certified with one oracle pass per sample; a sub-batch is compared with the oracle's sequential run."""
     w = S.workload("cfg4")
@@ -106,7 +128,7 @@ def test_cfg4_categorical_full_size():
 
 
 @pytest.mark.timeout(900)
-def test_cfg4_onehot_full_size_certificate():
+def test_cfg4_onehot_full_size_certificate(library_defaults):
     """cfg4 with one-hot input at full size (first layer = gather over a 4096 x 262144 weight matrix): the Jacobi
     result of all 64 samples is certified as the fixed point of the oracle's network (one oracle evaluation of
     every position from the GPU's output; exact except where the oracle's margin is below 1e-3), the logits of
