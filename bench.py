@@ -305,6 +305,8 @@ def parse_args(argv=None):
                     help="batch size from which the 256 x 256 tile kernels are used (0 = library default)")
     ap.add_argument("--mid-tile-batch", type=int, default=0,
                     help="batch size from which the 128 x 128 tile kernels are used (0 = library default)")
+    ap.add_argument("--frozen-positions", type=int, default=-1, choices=[-1, 0, 1],
+                    help="MADE_OPT_FROZEN_POSITIONS (-1 = library default)")
     ap.add_argument("--lazy-stop-test", type=int, default=-1, choices=[-1, 0, 1],
                     help="MADE_OPT_LAZY_STOP_TEST (-1 = library default)")
     ap.add_argument("--retire-split", type=int, default=0,
@@ -356,6 +358,8 @@ def run_one(args, torch, B, S, light=False):
         B.made_set_option(model, B.MADE_OPT_MID_TILE_BATCH, args.mid_tile_batch)
     if args.retire_split > 0:
         B.made_set_option(model, B.MADE_OPT_RETIRE_SPLIT, args.retire_split)
+    if args.frozen_positions >= 0 and not conv:
+        B.made_set_option(model, B.MADE_OPT_FROZEN_POSITIONS, args.frozen_positions)
     if args.lazy_stop_test >= 0 and not conv:
         B.made_set_option(model, B.MADE_OPT_LAZY_STOP_TEST, args.lazy_stop_test)
     n_layers = (w.n_conv if conv else len(net.hidden)) + 1
@@ -396,6 +400,7 @@ def run_one(args, torch, B, S, light=False):
 
     # ---- timed region (events off): whole-call throughput
     it_sum, it_max, sample_passes, passes, conv_rows = 0.0, 0, 0, 0, 0
+    out_weights, out_draws = 0, 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -422,6 +427,8 @@ def run_one(args, torch, B, S, light=False):
         conv_rows += st.get("conv_rows", 0)
         sample_passes += st["sample_passes"]
         passes += st["passes"]
+        out_weights += st.get("output_weights_evaluated", 0)
+        out_draws += st.get("output_draws_evaluated", 0)
         itc = iters.cpu().numpy()
         it_sum += itc.mean()
         it_max = max(it_max, int(itc.max()))
@@ -463,6 +470,10 @@ def run_one(args, torch, B, S, light=False):
         # weights are charged only to launches that found a non-empty list (`passes`); the speculative launch behind
         # the converged pass reads nothing, but its duration stays in the denominator (it is a launch of this kernel)
         dom_bytes = passes * nnz[dom] * es + sample_passes * (noise_bytes + act_bytes)
+        if dom == n_layers - 1 and out_weights > 0:
+            # the 256-class output kernel skips the positions that cannot change: charge what the passes did read
+            # (visible weights of the evaluated positions, 1 KB of noise per evaluated (sample, position))
+            dom_bytes = out_weights * es + out_draws * 4.0 * w.C + sample_passes * act_bytes
         achieved = dom_bytes / (layer_ms[dom] * 1e-3) / 1e9
         peak, unit, bound = 8000.0, "GB/s", "hbm"
     else:
@@ -536,7 +547,8 @@ def run_one(args, torch, B, S, light=False):
                     "passes on few samples and the final launch on an empty list included); full_batch_launch is "
                     "the same kernel on a whole batch.  algorithmic flops = 2*nnz(W*mask) per active sample per pass; "
                     "algorithmic bytes (hbm bound) = visible weights once per launch on a non-empty list + noise and "
-                    "last-hidden activations per active sample.  rocprof: figures of separate rocprofv3 runs "
+                    "last-hidden activations per active sample; the 256-class output kernel is charged what its passes "
+                    "read after skipping the positions that cannot change (made_last_stats).  rocprof: figures of separate rocprofv3 runs "
                     "(kernel-trace duration, MFMA counters) read from the named summaries under profiles/",
         },
         "whole_call_tflops": 2.0 * sum(nnz) * (conv_rows / w.H if conv else sample_passes) / elapsed_prof / 1e12,

@@ -245,6 +245,10 @@ int gs_jacobi_sample_real(made_model* m, const float* noise, int32_t N, const fl
  *   out[4] convolutional model: image rows recomputed by the k x k layers, summed over passes and images (a pass
  *          only recomputes the rows below the first symbol that changed in the pass before); 0 otherwise
  *   out[5] passes whose stop test had no tail (MADE_OPT_LAZY_STOP_TEST: the next pass derived its list itself)
+ *   out[6] jacobi_sample of a 256-class model: visible output-layer weights the call's passes multiplied per sample
+ *          (a pass skips the positions below the first one its predecessor changed: MADE_OPT_FROZEN_POSITIONS);
+ *          0 otherwise
+ *   out[7] the same call: (sample, position) pairs its passes evaluated in the output layer (each reads 1 KB of noise)
  * n = number of int64 slots available in out (extra slots are left untouched).
  */
 int made_last_stats(const made_model* m, int64_t* out, int32_t n);
@@ -265,6 +269,11 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   batch <= 2048 from ONE cooperative launch that keeps a workgroup per CU resident and separates layers by
  *   a grid-wide barrier; 0 = one kernel launch per layer and pass.  Same results either way; on MI355X the
  *   per-layer launches are currently the faster of the two at batch 128, hence the default.
+ *   MADE_OPT_FROZEN_POSITIONS (default 1; 0 or 1): models with 256 classes per position (fused output kernel): a pass
+ *   of jacobi_sample / gs_jacobi_sample evaluates only the output positions behind the lowest position that the
+ *   pass before changed in any sample still active.  The positions up to there read the inputs they read in that
+ *   pass and would draw the same symbols (Proposition 1's frozen prefix, measured per pass instead of bounded by the
+ *   pass count): same results, same pass counts, fewer of the output layer's weights streamed in the late passes.
  *   MADE_OPT_LAZY_STOP_TEST (default 1; 0 or 1): jacobi_sample of a Bernoulli model on at most 256 samples (per-layer
  *   launches): the sampling kernel of a pass only records which samples changed, and every workgroup of the next
  *   pass's first kernel derives that pass's list of active samples from the record -- in the memory round trip in
@@ -325,7 +334,7 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
 enum { MADE_OPT_PERSISTENT = 1, MADE_OPT_FUSED_CATEGORICAL = 2, MADE_OPT_CHAINS = 3, MADE_OPT_BIG_TILE_BATCH = 4,
        MADE_OPT_CONV_ROWS = 5, MADE_OPT_PREFIX_CACHE = 6, MADE_OPT_RESIDENT = 7, MADE_OPT_RETIRE_SPLIT = 8,
        MADE_OPT_MID_TILE_BATCH = 9, MADE_OPT_PARTIAL_SUM_BATCH = 10, MADE_OPT_XCD_RESIDENT = 11,
-       MADE_OPT_LAZY_STOP_TEST = 12 };
+       MADE_OPT_LAZY_STOP_TEST = 12, MADE_OPT_FROZEN_POSITIONS = 13 };
 int made_set_option(made_model* m, int32_t option, int32_t value);
 
 /*

@@ -261,10 +261,11 @@ def gs_jacobi_sample_real(model: int, noise, N: int, x_init, block: int, eps: fl
 
 
 def made_last_stats(model: int) -> dict:
-    buf = (C.c_int64 * 6)()
-    _check(lib().made_last_stats(model, buf, 6))
+    buf = (C.c_int64 * 8)()
+    _check(lib().made_last_stats(model, buf, 8))
     return {"passes": buf[0], "sample_passes": buf[1], "kernels": buf[2], "host_waits": buf[3],
-            "conv_rows": buf[4], "tail_less_passes": buf[5]}
+            "conv_rows": buf[4], "tail_less_passes": buf[5], "output_weights_evaluated": buf[6],
+            "output_draws_evaluated": buf[7]}
 
 
 def made_set_profiling(model: int, enable: bool) -> None:
@@ -283,6 +284,7 @@ MADE_OPT_MID_TILE_BATCH = 9
 MADE_OPT_PARTIAL_SUM_BATCH = 10
 MADE_OPT_XCD_RESIDENT = 11
 MADE_OPT_LAZY_STOP_TEST = 12
+MADE_OPT_FROZEN_POSITIONS = 13
 
 
 def made_set_option(model: int, option: int, value: int) -> None:

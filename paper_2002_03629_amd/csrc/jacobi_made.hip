@@ -104,6 +104,7 @@ struct Layer {
 // A chain is a contiguous range of the batch's samples that is iterated on its own HIP stream.  Samples are
 // independent systems (each has its own noise), so chains never exchange anything; running several of them
 // concurrently overlaps the dispatch latency of one chain's dependent kernels with another chain's work.
+constexpr int FROZEN_WORDS = 48;     // the frozen-position words' place in a chain's counter block (see CallReset)
 struct Chain {
   hipStream_t own_stream = nullptr;  // created with the chain
   hipStream_t stream = nullptr;      // the stream this call runs the chain on (the caller's when there is one chain)
@@ -125,6 +126,7 @@ struct Chain {
                                      // what the latest confirmed pass left (the list only shrinks inside a block)
   bool block_started = false, finished = false, iters_cleared = false;
   bool lazy = false;                 // this call's passes use the tail-less stop test (see DeriveArgs)
+  bool frozen = false;               // this call's passes skip the output positions that cannot change (CatArgs::t_first_ptr)
   std::vector<char> log_first;       // per enqueued pass: was it the first of its block
 };
 
@@ -201,7 +203,7 @@ struct made_model {
   // degree, so these are prefix lengths
   std::vector<std::vector<int>> cnt_lt;
   Workspace ws;
-  int64_t stats[6] = {0, 0, 0, 0, 0, 0};
+  int64_t stats[8] = {0, 0, 0, 0, 0, 0, 0, 0};
   // Jacobi-GS (Algorithm 2): symbols of the virtual samples, per-sub-step position table, per-sample state
   uint8_t* jgs_xv = nullptr;
   size_t jgs_xv_cap = 0;
@@ -233,6 +235,8 @@ struct made_model {
   int fused_categorical = 1;                  // made_set_option(MADE_OPT_FUSED_CATEGORICAL)
   int use_persistent = 0;                     // made_set_option(MADE_OPT_PERSISTENT): 1 = the device-wide cooperative kernel
                                               // (measured slower, see header)
+  int frozen_positions = 1;                   // made_set_option(MADE_OPT_FROZEN_POSITIONS): 256-class output kernel skips the
+                                              // positions below the first one that changed in the pass before
   int lazy_retire = 1;                        // made_set_option(MADE_OPT_LAZY_STOP_TEST): 1 = Jacobi on lists of up to 256 samples
                                               // derives a pass's list in its first kernel instead of in the previous one's tail
   int use_xcd = 1;                            // made_set_option(MADE_OPT_XCD_RESIDENT): 0 never, 1 where it pays, 2 whenever possible
@@ -385,7 +389,8 @@ static int ensure_chain(made_model* m, size_t i, int rows_cap, int pin_len) {
   // (the retire kernel's list cursor lives RETIRE_CURSOR words behind the counter)
   HIP_TRY(hipMalloc((void**)&c.done_ctr, (size_t)2 * RETIRE_CURSOR * sizeof(int)));
   HIP_TRY(hipMemset(c.done_ctr, 0, (size_t)2 * RETIRE_CURSOR * sizeof(int)));
-  HIP_TRY(hipHostMalloc((void**)&c.h_pin, (size_t)pin_len * sizeof(int), hipHostMallocMapped));
+  // (second half: per pass, the first position the NEXT pass evaluates -- see CatArgs::t_first_ptr)
+  HIP_TRY(hipHostMalloc((void**)&c.h_pin, (size_t)2 * pin_len * sizeof(int), hipHostMallocMapped));
   HIP_TRY(hipHostGetDevicePointer((void**)&c.d_pin, (void*)c.h_pin, 0));
   c.rows_cap = rows_cap;
   c.pin_len = pin_len;
@@ -429,7 +434,7 @@ extern "C" const char* made_last_error(void) { return g_last_error.c_str(); }
 
 extern "C" int made_last_stats(const made_model* m, int64_t* out, int32_t n) {
   if (!m || !out || n < 0) return fail(MADE_ERR_ARG, "made_last_stats: NULL argument");
-  for (int i = 0; i < n && i < 6; ++i) out[i] = m->stats[i];
+  for (int i = 0; i < n && i < 8; ++i) out[i] = m->stats[i];
   return MADE_OK;
 }
 
@@ -450,6 +455,11 @@ extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
   if (!m) return fail(MADE_ERR_ARG, "made_set_option: model is NULL");
   if (option == MADE_OPT_PERSISTENT) {
     m->use_persistent = value != 0;
+    return MADE_OK;
+  }
+  if (option == MADE_OPT_FROZEN_POSITIONS) {
+    if (value != 0 && value != 1) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_FROZEN_POSITIONS=%d must be 0 or 1", value);
+    m->frozen_positions = value;
     return MADE_OK;
   }
   if (option == MADE_OPT_LAZY_STOP_TEST) {
@@ -963,6 +973,8 @@ struct SampleIO {          // what the sampling epilogue reads and writes
   uint8_t* x;              // symbols; for a model with real states this is a float [N, D] buffer
   int t_lo, t_hi;
   RetireArgs retire;       // retire.enabled = 0: no stop test after this pass (sequential sampling)
+  const int* t_first_ptr = nullptr;   // 256-class output kernel: first position to evaluate / where the lowest changed
+  int* first_changed = nullptr;       // position is recorded (see CatArgs)
   unsigned* lazy_mask = nullptr;   // Bernoulli MLP: changed rows go here as bits and the next pass derives its list from
                                    // them (see DeriveArgs); retire.enabled is 0 then
 };
@@ -1217,6 +1229,8 @@ static int run_output_sample(made_model* m, const RowSet& rs, const SampleIO& io
     c.t_begin = whole ? 0 : io.t_lo;
     c.n_pos = whole ? m->D : io.t_hi - io.t_lo;
     c.pair_tiles = (rs.n_rows + 2 * TILE - 1) / (2 * TILE);
+    c.t_first_ptr = io.t_first_ptr;
+    c.first_changed = io.first_changed;
     c.retire = io.retire;
     prof_mark(m, m->L, false, s);
     if (m->dtype == MADE_BF16)
@@ -1719,7 +1733,7 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
       // outside this call's buffers)
       hipLaunchKernelGGL(reset_rows_kernel, dim3((padded + 255) / 256), dim3(256), 0, s, c.rows[0],
                          c.iters_cleared ? nullptr : c.rows[1], c.n_rows[0], c.first, c.count, padded, w.changed,
-                         c.iters_cleared ? nullptr : w.call_iters, c.done_ctr);
+                         c.iters_cleared ? nullptr : w.call_iters, c.done_ctr, c.done_ctr + FROZEN_WORDS);
       m->stats[2]++;
       c.iters_cleared = true;
     }
@@ -1774,6 +1788,21 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
     io.retire.last_pass = (k == blk.cap);
     io.retire.flag_unconverged = flag_unconverged;
     io.retire.enabled = lazy_out ? 0 : 1;
+    // Frozen positions (256-class output kernel): pass k starts at the position behind the lowest one pass k - 1
+    // changed (word (k - 1) & 1; a block's first pass finds 0 there), records the lowest position it changes in word
+    // 2 + (k & 1), and its tail turns that into the start of pass k + 1 and re-arms the other recording word.
+    c.frozen = m->frozen_positions && m->arch == 0 && m->C == CAT_C && m->fused_categorical && !m->real &&
+               n_bound < m->retire_split;
+    if (c.frozen) {
+      int* fw = c.done_ctr + FROZEN_WORDS;
+      io.t_first_ptr = fw + ((k - 1) & 1);
+      io.first_changed = fw + 2 + (k & 1);
+      io.retire.fc_in = fw + 2 + (k & 1);
+      io.retire.t_first_out = fw + (k & 1);
+      io.retire.fc_reset = fw + 2 + ((k + 1) & 1);
+      io.retire.host_t_first = c.d_pin + c.pin_len + c.pin_base + slot;
+      c.h_pin[c.pin_len + c.pin_base + slot] = NO_CHANGE;
+    }
     if (lazy_out) {
       io.lazy_mask = w.lazy_masks + (k % 3) * DERIVE_WORDS;
       m->stats[5]++;
@@ -1877,6 +1906,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
     c.lazy = m->lazy_retire && m->C == 1 && !m->real && blocks.size() == 1 && blocks[0].stop_test && !blocks[0].limited &&
              c.count <= DERIVE_MAX_ROWS && c.count < std::min(m->mid_batch, m->big_batch) && c.count < m->retire_split;
     r.lazy_masks = c.lazy ? w.lazy_masks : nullptr;
+    r.frozen_words = c.done_ctr + FROZEN_WORDS;
     TRY(launch_init_state(m, x_init, x, N, s, &r));
     c.block_started = true;
     c.iters_cleared = true;
@@ -1992,6 +2022,18 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
       if (active_in > 0) {
         passes++;
         m->stats[1] += active_in;
+      }
+      // visible output-layer weights this pass multiplied (Algorithm 1 of a 256-class model: the pass starts at the
+      // position its predecessor's tail reported)
+      if (active_in > 0 && m->arch == 0 && m->C == CAT_C && blocks.size() == 1 && blocks[0].stop_test) {
+        int t_first = 0;
+        if (c.frozen && !c.log_first[j]) {
+          const int reported = c.h_pin[c.pin_len + c.pin_base + j - 1];
+          t_first = std::min(m->D, std::max(0, reported));
+        }
+        const std::vector<int>& below = m->cnt_lt[m->L - 1];
+        for (int t = t_first; t < m->D; ++t) m->stats[6] += (int64_t)below[t + 1] * m->C;
+        m->stats[7] += (int64_t)(m->D - t_first) * active_in;
       }
       active_in = std::max(0, (int)c.h_pin[c.pin_base + j]);   // (an unreported pass is one that found the list empty)
     }

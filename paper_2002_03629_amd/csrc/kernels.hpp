@@ -155,7 +155,16 @@ struct RetireArgs {
   int last_pass;
   int flag_unconverged;
   int enabled;
+  // Frozen positions (categorical output kernel, see CatArgs::t_first_ptr): fc_in = the word in which this pass's
+  // workgroups recorded the lowest position that changed (NULL: not tracked); the tail turns it into the first
+  // position the next pass has to evaluate (*t_first_out), tells the host (host_t_first) and re-arms the word the
+  // next pass records into (*fc_reset).
+  int* fc_in;
+  int* t_first_out;
+  int* fc_reset;
+  int* host_t_first;
 };
+constexpr int NO_CHANGE = 0x7fffffff;
 
 // Stop test without a tail (short lists, at most DERIVE_MAX_ROWS samples).  retire_tail above costs the pass's last
 // kernel three dependent memory round trips after its arithmetic is done (counter atomics performed -> arrival
@@ -413,6 +422,15 @@ __device__ __forceinline__ void retire_tail(const RetireArgs& r, int pre_n, int 
   if (threadIdx.x == 0) {
     *r.n_out = base_s;
     *r.done_ctr = 0;
+    if (r.fc_in) {
+      // a sample that goes on changed first at position f >= *fc_in, so its positions up to f read unchanged inputs in
+      // the next pass and keep their symbols: the next pass starts behind the lowest f of the batch
+      const int fc = __hip_atomic_load(r.fc_in, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int t_first = fc == NO_CHANGE ? NO_CHANGE : fc + 1;
+      *r.t_first_out = t_first;
+      *r.fc_reset = NO_CHANGE;
+      __hip_atomic_store(r.host_t_first, t_first, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
     publish_pass_result(r, flagged_s != 0, base_s);
   }
 }
@@ -1722,6 +1740,12 @@ struct CatArgs {
   int t_lo, t_hi;        // positions whose symbol is re-drawn
   int t_begin, n_pos;    // positions this launch evaluates
   int pair_tiles;        // sample tiles of 64 this launch covers
+  // Frozen positions: if no position below t changed in the previous pass (for any sample that is still active),
+  // position t reads the inputs it read then and draws the symbol it drew then (its noise is fixed): the pass need
+  // not evaluate it -- Proposition 1's frozen prefix, measured instead of bounded.  *t_first_ptr = first position
+  // this pass evaluates (NULL: all); first_changed = where it records the lowest position it changes (NULL: nowhere).
+  const int* t_first_ptr;
+  int* first_changed;
   RetireArgs retire;
 };
 
@@ -1767,10 +1791,11 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
   __shared__ float sm_val[CAT_WAVES][64];
   __shared__ int sm_idx[CAT_WAVES][64];
   const int n_rows = a.n_rows_ptr ? *a.n_rows_ptr : a.n_rows;
+  const int t_first = a.t_first_ptr ? *a.t_first_ptr : 0;
   const int pos_i = blockIdx.x / a.pair_tiles, pair = blockIdx.x % a.pair_tiles;
   const int t = a.t_begin + a.n_pos - 1 - pos_i;
   const int row0 = pair * 64;
-  if (row0 < n_rows) {   // (uniform per workgroup)
+  if (row0 < n_rows && t >= t_first) {   // (uniform per workgroup)
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int r = lane & 31, h = lane >> 5;
     const bool two = row0 + 32 < n_rows;
@@ -1857,6 +1882,11 @@ __global__ __launch_bounds__(CAT_WAVES * 64) void categorical_output_kernel(CatA
         }
       }
       if (differs) count_changed(&a.changed[(size_t)sample * CHG], 1);
+      if (a.first_changed && __ballot(differs) != 0 && threadIdx.x == 0) {
+        // (returning atomic: performed before this workgroup reports in, like the counters above)
+        const int old = __hip_atomic_fetch_min(a.first_changed, t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("" ::"v"(old));
+      }
     }
   }
   if (a.retire.enabled) finish_pass(a.retire, gridDim.x);
@@ -2566,6 +2596,7 @@ struct CallReset {
   int* done_ctr;
   int* flags;
   unsigned* lazy_masks;  // [3 * DERIVE_WORDS] (see DeriveArgs), or NULL
+  int* frozen_words;     // [4] first position to evaluate (two, alternating by pass) and lowest changed position (two), or NULL
 };
 
 __device__ __forceinline__ void call_reset(const CallReset& r) {
@@ -2584,6 +2615,10 @@ __device__ __forceinline__ void call_reset(const CallReset& r) {
       *r.done_ctr = 0;
       r.done_ctr[RETIRE_CURSOR] = 0;
       *r.flags = 0;
+      if (r.frozen_words) {
+        r.frozen_words[0] = r.frozen_words[1] = 0;
+        r.frozen_words[2] = r.frozen_words[3] = NO_CHANGE;
+      }
     }
   }
 }
@@ -2689,7 +2724,7 @@ __global__ void init_state_real_kernel(const float* x_init, float* x, T* enc, in
 // Entries past the count, up to the list's padded length, are read as sample ids by the tile kernels (their
 // results are discarded), so they are set to a valid id of this call as well.
 __global__ void reset_rows_kernel(int* rows, int* rows_other, int* n_rows, int first, int count, int padded, int* changed,
-                                  int* iters, int* done_ctr) {
+                                  int* iters, int* done_ctr, int* frozen_words) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < padded) rows[i] = i < count ? first + i : first;
   if (i < padded && rows_other) rows_other[i] = first;   // (only needed once per call: see enqueue_pass)
@@ -2701,6 +2736,10 @@ __global__ void reset_rows_kernel(int* rows, int* rows_other, int* n_rows, int f
     *n_rows = count;
     *done_ctr = 0;
     done_ctr[RETIRE_CURSOR] = 0;
+    if (frozen_words) {      // (see CallReset)
+      frozen_words[0] = frozen_words[1] = 0;
+      frozen_words[2] = frozen_words[3] = NO_CHANGE;
+    }
   }
 }
 

@@ -413,3 +413,37 @@ def test_tail_less_stop_test_serves_the_call_and_changes_nothing():
                 assert a[3]["passes"] == b[3]["passes"] and a[3]["sample_passes"] == b[3]["sample_passes"]
                 if limit:
                     assert a[2] in (0, B.MADE_ERR_NOT_CONVERGED)
+
+
+@pytest.mark.parametrize("name", ["small_cat", "small_cat_onehot", "mid_cat_onehot"])
+def test_frozen_positions_change_nothing_but_the_work(name):
+    """MADE_OPT_FROZEN_POSITIONS: a pass of the 256-class output kernel skips the positions below the first one the
+    pass before changed.  Symbols and pass counts are those of full passes, for Jacobi (zeros and a random start)
+    and GS-Jacobi; the weights the passes multiply are fewer."""
+    import gpu_util
+    if gpu_util.CHAINS != 1 or not gpu_util.FUSED_CATEGORICAL or gpu_util.RETIRE_SPLIT is not None:
+        pytest.skip("runs on the single-chain paths with the fused output kernel")
+    w = S.workload(name)
+    net = S.make_network(w, with_bias=True)
+    noise = S.make_noise(w)
+    x0 = _symbols(w, np.random.default_rng(12), w.N)
+    with GpuModel(net) as g:
+        res = {}
+        for frozen in (1, 0):
+            B.made_set_option(g.h, B.MADE_OPT_FROZEN_POSITIONS, frozen)
+            x, it = g.jacobi(noise)
+            torch.cuda.synchronize()
+            st = g.stats()
+            xi, iti = g.jacobi(noise, x_init=x0)
+            xb, itb = g.gs_jacobi(noise, 5)
+            res[frozen] = (x, it, st, xi, iti, xb, itb)
+        a, b = res[1], res[0]
+        for i in (0, 1, 3, 4, 5, 6):
+            assert (a[i] == b[i]).all(), i
+        assert a[2]["passes"] == b[2]["passes"] and a[2]["sample_passes"] == b[2]["sample_passes"]
+        if w.C != 256:            # (other class counts take the unfused path: nothing to skip, nothing counted)
+            assert a[2]["output_weights_evaluated"] == 0
+            return
+        assert 0 < a[2]["output_weights_evaluated"] <= b[2]["output_weights_evaluated"]
+        if a[2]["passes"] >= 3:
+            assert a[2]["output_weights_evaluated"] < b[2]["output_weights_evaluated"], (a[2], b[2])
