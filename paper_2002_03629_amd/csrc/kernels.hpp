@@ -920,7 +920,7 @@ template <typename T, int EPI, int W>
 __global__ __launch_bounds__(256, W == 2 ? 2 : 1) void masked_layer_big_kernel(LayerArgs a) {
   constexpr int BIG_W = W, BIG_T = 2 * W, BIG_ROWS = BIG_T * TILE, BIG_STAGE = 2 * BIG_T * BIG_HALF;
   constexpr int KC = 2 * Elem<T>::EPL;
-  // ring stages, [block 0..7 = samples, 8..15 = units][128] each (separate arrays: see the main loop)
+  // ring of four stages, [block 0 .. 2W-1 = samples, 2W .. 4W-1 = units][128] each (one array, run-time stage index)
   __shared__ uint4 big_ring[4 * BIG_STAGE];
   const int n_rows = a.n_rows_ptr ? *a.n_rows_ptr : a.n_rows;
   const int big_cols = (a.n_launch_tiles + BIG_T - 1) / BIG_T;
@@ -964,14 +964,17 @@ __global__ __launch_bounds__(256, W == 2 ? 2 : 1) void masked_layer_big_kernel(L
 
     // Operand blocks go from global memory straight into LDS (global_load_lds_dwordx4: lane i of a wave
     // deposits its 16 bytes at the wave's LDS base + 16 i), so data in flight costs no registers.  A chunk is
-    // moved in two halves (MFMA steps 0-1 and 2-3 of all 16 blocks: 32 KB) through a ring of four stages, three
-    // halves in flight while one is multiplied: a load has three halves' worth of MFMA time (~1.3 us) to
-    // arrive.  The stages are four DISTINCT LDS arrays on purpose: the compiler orders every LDS read behind all
-    // outstanding LDS-bound loads it cannot prove to target other memory (with one array it put a full
-    // vmcnt(0) in front of each half's first read, right behind the prefetch it had just issued: load and
-    // multiply never overlapped, 2.4 us per chunk instead of <1).  Each thread copies 8 pieces of 16 bytes per
-    // half: element e = half * 128 + (tid & 127) of blocks 2 q + (tid >> 7); offsets in 16-byte units (the host
-    // refuses operand buffers of 64 GiB and more).
+    // moved in two halves (MFMA steps 0-1 and 2-3 of all 4 W blocks: 32 KB at W = 4) through a ring of four stages,
+    // three halves in flight while one is multiplied: a load has three halves' worth of MFMA time (~1.3 us) to
+    // arrive.  The copies are issued as assembly (see load_to_lds16), so the compiler knows of none of them: written
+    // with the builtin, it ordered every LDS read behind all outstanding LDS-bound loads (a full vmcnt(0) in front
+    // of each half's first read, right behind the prefetch it had just issued: load and multiply never overlapped,
+    // 2.4 us per chunk instead of < 1).  The waits are written by hand below.  Each thread copies 2 W pieces of
+    // 16 bytes per half: element e = half * 128 + (tid & 127) of blocks 2 q + (tid >> 7); offsets in 16-byte units
+    // (the host refuses operand buffers of 64 GiB and more).
+    // (Requesting the second column's first halves ahead of the first column's epilogue gains nothing: the
+    // epilogue's own loads then queue behind 128 KB of copies, and the copies' addresses, kept across the epilogue,
+    // are spilled and reloaded with compiler-placed waits that drain the ring inside the main loop.)
     const int sub = wave >> 1, e_lo = tid & 127;             // (sub: wave-uniform)
     uint32_t offA[BIG_W];
 #pragma unroll
