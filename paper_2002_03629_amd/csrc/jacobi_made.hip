@@ -1364,7 +1364,7 @@ static int run_conv_pass(made_model* m, int N, const SampleIO& io, bool first_pa
   c.state_hi = io.t_hi;
   // one workgroup per CU in all (3 colours x 85; the kernel runs one wave per SIMD); the 4 waves of workgroup
   // (colour, group) walk over the pixel rows 4 * group + wave, + 4 * groups, ...
-  c.groups = std::max(1, std::min((N * cv.H + 3) / 4, 85));
+  c.groups = std::max(1, std::min(N * cv.H, 85));
   if (!whole_network) {
     c.dirty_lo = cv.win;
     c.first_changed = cv.win + cv.win_pad;
@@ -1382,18 +1382,8 @@ static int run_conv_pass(made_model* m, int N, const SampleIO& io, bool first_pa
 
 static void launch_conv_head(made_model* m, const ConvHeadArgs& c, hipStream_t s) {
   ConvNet& cv = m->conv;
-  const size_t head_lds = (size_t)(CAT_C / TILE) * (cv.F / chunk_elems(m)) * 256 * 16;   // one colour's weights
   prof_mark(m, m->L, false, s);
-#define JM_LAUNCH_HEAD(T, FT)                                                                                      \
-  do {                                                                                                            \
-    static bool configured = false;                                                                               \
-    if (!configured) {                                                                                            \
-      (void)hipFuncSetAttribute((const void*)conv_head_kernel<T, FT>, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                (int)head_lds);                                                                   \
-      configured = true;                                                                                          \
-    }                                                                                                             \
-    hipLaunchKernelGGL((conv_head_kernel<T, FT>), dim3(3 * c.groups), dim3(256), head_lds, s, c);                 \
-  } while (0)
+#define JM_LAUNCH_HEAD(T, FT) hipLaunchKernelGGL((conv_head_kernel<T, FT>), dim3(3 * c.groups), dim3(256), 0, s, c)
   if (m->dtype == MADE_BF16) {
     if (cv.F == 128) JM_LAUNCH_HEAD(bf16_t, 4); else JM_LAUNCH_HEAD(bf16_t, 2);
   } else {
@@ -2538,7 +2528,7 @@ static int jacobi_gs_conv(made_model* m, const float* noise, int N, const uint8_
   c.H = cv.H;
   c.state_lo = 0;
   c.state_hi = D;
-  c.groups = std::max(1, std::min((V * cv.H + 3) / 4, 85));
+  c.groups = std::max(1, std::min(V * cv.H, 85));
   c.state_one = state_one;
   c.noise_images = N;
   const size_t n16 = (size_t)N * per_image / 16;

@@ -2267,22 +2267,30 @@ struct ConvHeadArgs {
 
 constexpr int HEAD_PATCH_PITCH = TILE + 4;   // floats per pixel row of the noise patch (16-byte reads of 16 lanes
                                              // then cover all 64 banks)
+constexpr int HEAD_BATCH = 16;               // rows a workgroup draws between two of its finishing phases
 
-// 1 x 1 head + Gumbel-max draw + change detection of the convolutional model.  A workgroup is bound to one
-// colour and first copies that colour's 256 x F weight block (and bias) to LDS; after that its 4 waves work
-// independently: a wave takes one row of 32 pixels at a time (rows wave, wave + stride, ...) and multiplies it
-// with one 32-class tile after the other.  The classes are the MFMA's row operand, so lane (r, h) holds 16
-// classes of pixel r per tile: the 256-way argmax is a running (value, class) pair per lane plus one exchange
-// between the half-waves.  The noise is the large stream of this launch (100 MB per pass at batch 32 against
-// 8 MB of activations); see load_noise for how it is fetched.  No barrier inside the loop.  FT = F / 32.
+// 1 x 1 head + Gumbel-max draw + change detection of the convolutional model.  A workgroup is bound to one colour
+// and walks rows of 32 pixels (rows group, group + groups, ...); its 4 waves split the 256 classes: wave w keeps the
+// weights of classes 64 w .. 64 w + 63 (two 32-class tiles) in registers for the whole launch -- nothing is staged
+// in LDS and no barrier stands between the launch and the first MFMA.  The classes are the MFMA's row operand, so
+// lane (r, h) holds 16 classes of pixel r per tile: a wave's argmax over its 64 classes is a running
+// (value, class) pair per lane plus one exchange between the half-waves.  The four partial results of a row go
+// through LDS; every HEAD_BATCH rows (and at the end) the workgroup meets once, picks the winner per pixel, compares
+// it with the old symbol and counts the changes.  The noise is the large stream of this launch (100 MB per pass at
+// batch 32 against 8 MB of activations); see load_row for how it is fetched.  FT = F / 32.
 template <typename T, int FT>
 __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
   constexpr int KC = 2 * Elem<T>::EPL;
   constexpr int KCH = FT * 32 / KC;
   constexpr int NCT = CAT_C / TILE;                     // class tiles
-  extern __shared__ uint4 head_w[];                     // [NCT][KCH][256] this colour's weights, fragment-major
-  __shared__ float4 bias_lds[CAT_C / 4];
+  constexpr int WT = NCT / 4;                           // class tiles per wave
+  constexpr int RR = sizeof(T) == 2 ? 3 : 2;            // rows whose inputs are in flight or in registers
+  static_assert(NCT % 4 == 0, "the class tiles are dealt to four waves");
   __shared__ __align__(16) float noise_patch[4][TILE * HEAD_PATCH_PITCH];
+  __shared__ float cand_v[HEAD_BATCH][4][TILE];         // per row of the batch and wave: the wave's best value ...
+  __shared__ int cand_c[HEAD_BATCH][4][TILE];           // ... and its class, per pixel
+  __shared__ int batch_row[HEAD_BATCH];
+  __shared__ uint8_t batch_x[HEAD_BATCH][TILE];         // the rows' old symbols
   const int t = blockIdx.x / a.groups, group = blockIdx.x % a.groups;
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 31, h = lane >> 5;
@@ -2299,11 +2307,10 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
     const int lo = a.first_pass ? a.row_lo : max(a.row_lo, a.dirty_lo[n]);
     return y >= lo && y <= a.row_hi;
   };
-  // The wave's rows are wave, wave + stride, ...; which of them are active is decided up front, 64 rows at a time,
-  // so that no load (the images' dirty rows) is issued between the noise requests of the main loop: loads
-  // return in order, and waiting for a young one means waiting for every noise load before it.
-  const int stride = a.groups * 4;
-  const int g_first = group * 4 + wave;
+  // The workgroup's rows are group, group + stride, ...; which of them are active is decided 64 rows at a time (every
+  // wave for itself, all with the same result: nothing these tests read is written before the launch's tail).
+  const int stride = a.groups;
+  const int g_first = group;
   int chunk = 0;                                        // rows g_first + (64 * chunk + k) * stride, k = 0..63
   auto active_mask = [&](int ch) {
     unsigned long long m = 0;
@@ -2327,125 +2334,146 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
     }
   };
   auto slot_of = [&](int gg) { return (gg - g_first) / stride - 64 * chunk; };
+  auto row_after = [&](int gg) { return gg < n_rows ? next_active(slot_of(gg) + 1) : n_rows; };
   JM_TSTAMP(0, 0);
-  int n_done = 0;
-  int g = next_active(0);
-  const bool wg_has_work = __syncthreads_or(g < n_rows);
 
-  // Noise: a ring of RING class tiles in registers.  A tile (32 pixels x 32 classes) is fetched by 4 loads in
-  // which 8 lanes cover one pixel's 128 bytes (lane = (pixel % 8, 4 classes)): whole cache lines per group of
-  // lanes, measured 5.6 TB/s on this stream like a linear read (4.2 TB/s when every lane fetches 16 bytes of
-  // its own pixel, 1.5 TB/s with 4-byte loads).  As soon as a tile is consumed, the tile RING places further
-  // on (of this row or of the wave's next row) is requested into its slot.  On consumption the tile is turned
-  // through a wave-private LDS patch into the accumulator layout (lane (r, h): classes 8q + 4h .. + 3 of
-  // pixel r for q = 0..3).
-  typedef __attribute__((__vector_size__(4 * sizeof(float)))) float vf4;   // (a native vector: stays in registers)
-  auto load_noise = [&](int g_row, int ct, vf4 (&dst)[4]) {
-    if (a.state_one) g_row = ((g_row / a.H) % a.noise_images) * a.H + g_row % a.H;   // (a virtual image: its real image's noise)
-    const float* nz = a.noise + ((size_t)(g_row * 32 + (lane >> 3)) * 3 + t) * CAT_C + ct * TILE + (lane & 7) * 4;
-    static_for<4>([&](auto I) {
-      constexpr int i = decltype(I)::value;
-      dst[i] = *(const vf4*)(nz + (size_t)i * 8 * 3 * CAT_C);
-    });
-  };
-  constexpr int RING = 4;
-  static_assert(NCT % RING == 0, "a row must be a whole number of ring turns");
-  vf4 gz[RING][4];
-  if (g < n_rows) {
-    static_for<RING>([&](auto CT) { load_noise(g, decltype(CT)::value, gz[decltype(CT)::value]); });
-  }
-
+  // ---- what stays in registers: the wave's weights and bias
   int k_end = a.tile_kend[t * NCT];
   if (k_end > FT * 32) k_end = FT * 32;
   const int n_chunks = (k_end + KC - 1) / KC;
-  if (wg_has_work) {
-    const uint4* Wsrc = (const uint4*)a.W + (size_t)t * NCT * KCH * 256;
-    constexpr int PIECES = NCT * KCH;                   // 16-byte pieces per thread
-    static_for<(PIECES + 7) / 8>([&](auto B) {
-      constexpr int b0 = decltype(B)::value * 8;
-      constexpr int cnt = PIECES - b0 < 8 ? PIECES - b0 : 8;
-      uint4 v[cnt];
+  const int ct0 = wave * WT;                            // the wave's first class tile
+  uint4 wf[WT][KCH][4];
+  {
+    const uint4* Wsrc = (const uint4*)a.W + ((size_t)t * NCT + ct0) * KCH * 256 + h * 32 + r;
 #pragma unroll
-      for (int i = 0; i < cnt; ++i) v[i] = Wsrc[(size_t)(b0 + i) * 256 + tid];
+    for (int j = 0; j < WT; ++j)
 #pragma unroll
-      for (int i = 0; i < cnt; ++i) head_w[(b0 + i) * 256 + tid] = v[i];
-    });
-    if (tid < CAT_C / 4) bias_lds[tid] = *(const float4*)(a.bias + t * CAT_C + 4 * tid);
+      for (int c = 0; c < KCH; ++c)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) wf[j][c][s] = Wsrc[(size_t)(j * KCH + c) * 256 + s * 64];
   }
-  __syncthreads();
-  JM_TSTAMP(1, 0);
-  int sink = 0;                                         // old values of the counter atomics (see below)
+  float4 bias4[WT][4];                                  // classes (ct0 + j) * 32 + 8 q + 4 h .. + 3
+#pragma unroll
+  for (int j = 0; j < WT; ++j)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) bias4[j][q] = *(const float4*)(a.bias + t * CAT_C + (ct0 + j) * TILE + 8 * q + 4 * h);
 
-  // Activations and old symbols are requested one row ahead, and BEFORE the row's noise reloads: loads return in
-  // order, so a young activation load that is needed at once would make the wave wait for every noise load
-  // issued before it.
-  uint4 af_next[KCH][4];
-  uint8_t x_old_next = 0;
-  auto load_row_inputs = [&](int g_row) {
+  // ---- a row's inputs: the activations of its 32 pixels (every wave needs all of them) and the wave's share of
+  // the noise, both into the same ring slot and requested together, RR rows ahead: loads return in order, so
+  // whatever a row needs must not sit behind requests of later rows.  A noise tile (32 pixels x 32 classes) is
+  // fetched by 4 loads in which 8 lanes cover one pixel's 128 bytes (lane = (pixel % 8, 4 classes)): whole cache
+  // lines per group of lanes, measured 5.6 TB/s on this stream like a linear read (4.2 TB/s when every lane
+  // fetches 16 bytes of its own pixel, 1.5 TB/s with 4-byte loads).  On consumption the tile is turned through a
+  // wave-private LDS patch into the accumulator layout (lane (r, h): classes 8q + 4h .. + 3 of pixel r, q = 0..3).
+  typedef __attribute__((__vector_size__(4 * sizeof(float)))) float vf4;   // (a native vector: stays in registers)
+  uint4 af[RR][KCH][4];
+  vf4 gz[RR][WT][4];
+  uint8_t xo[RR];                                       // old symbol of pixel r (used by wave 0 only)
+  auto load_row = [&](int g_row, uint4 (&af_dst)[KCH][4], vf4 (&gz_dst)[WT][4], uint8_t& xo_dst) {
+    xo_dst = a.x[((size_t)g_row * 32 + r) * 3 + t];
     const uint4* A0 = (const uint4*)a.A + (size_t)g_row * KCH * 256 + h * 32 + r;
     static_for<KCH>([&](auto C) {
       constexpr int c = decltype(C)::value;
 #pragma unroll
-      for (int s = 0; s < 4; ++s) af_next[c][s] = A0[c * 256 + s * 64];
+      for (int s = 0; s < 4; ++s) af_dst[c][s] = A0[c * 256 + s * 64];
     });
-    x_old_next = a.x[((size_t)g_row * 32 + r) * 3 + t];
+    int g_noise = g_row;
+    if (a.state_one) g_noise = ((g_row / a.H) % a.noise_images) * a.H + g_row % a.H;   // (a virtual image: its real image's noise)
+    const float* nz = a.noise + ((size_t)(g_noise * 32 + (lane >> 3)) * 3 + t) * CAT_C + ct0 * TILE + (lane & 7) * 4;
+    static_for<WT>([&](auto J) {
+      constexpr int j = decltype(J)::value;
+      static_for<4>([&](auto I) {
+        constexpr int i = decltype(I)::value;
+        gz_dst[j][i] = *(const vf4*)(nz + j * TILE + (size_t)i * 8 * 3 * CAT_C);
+      });
+    });
   };
-  if (g < n_rows) load_row_inputs(g);
-  uint4 wf[2][KCH][4];
-  while (g < n_rows) {                                  // (uniform over the wave)
-    const int n = g / a.H, y = g % a.H;
-    const int g_next = next_active(slot_of(g) + 1);
-    const size_t xi = ((size_t)g * 32 + r) * 3 + t;     // lane (r, 0) finishes pixel r
-    const uint8_t x_old = x_old_next;
-    uint4 af[KCH][4];
-#pragma unroll
-    for (int c = 0; c < KCH; ++c)
-#pragma unroll
-      for (int s = 0; s < 4; ++s) af[c][s] = af_next[c][s];
-    if (g_next < n_rows) load_row_inputs(g_next);
-    __builtin_amdgcn_sched_barrier(0);
+  // Active rows go through the slots round-robin, in order; g_slot[s] is the row whose inputs slot s holds
+  // (n_rows: none).  One cursor walks the active rows: the next one to request.
+  int g_req = next_active(0);
+  int g_slot[RR];
+  static_for<RR>([&](auto S) {
+    constexpr int s = decltype(S)::value;
+    g_slot[s] = g_req;
+    if (g_req < n_rows) {
+      load_row(g_req, af[s], gz[s], xo[s]);
+      g_req = row_after(g_req);
+    }
+  });
+  JM_TSTAMP(1, 0);
+  int sink = 0;                                         // old values of the counter atomics (see below)
+  int n_batch = 0;                                      // rows drawn since the last finishing phase
 
+  // ---- finishing phase: winner per pixel over the four waves, comparison with the old symbol, counters
+  auto finish_batch = [&]() {
+    __syncthreads();
+    for (int b = tid >> 5; b < n_batch; b += 8) {       // (half-waves take rows; both halves of a wave run the same trips
+                                                        //  or the upper half sits one out: no barrier inside)
+      const int g = batch_row[b];
+      const int n = g / a.H, y = g % a.H;
+      float best = cand_v[b][0][r];
+      int best_c = cand_c[b][0][r];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) {                     // (classes ascend with the wave: a strict compare keeps the lowest)
+        const float v = cand_v[b][w][r];
+        if (v > best) { best = v; best_c = cand_c[b][w][r]; }
+      }
+      const int st = (y * 32 + r) * 3 + t;
+      bool differs = false;
+      if (a.state_one ? st == a.state_one[n] : (st >= a.state_lo && st < a.state_hi)) {
+        const uint8_t xn = (uint8_t)best_c;
+        differs = xn != batch_x[b][r];
+        if (differs) a.x[((size_t)g * 32 + r) * 3 + t] = xn;
+      }
+      const unsigned long long both = __ballot(differs);
+      const unsigned changed_mask = h ? (unsigned)(both >> 32) : (unsigned)both;
+      if (r == 0 && changed_mask != 0 && !a.state_one) {
+        // returning atomics, so that "the value came back" means "performed"; the values are only consumed
+        // after the loop (before the tail counters)
+        sink += __hip_atomic_fetch_add(&a.changed[(size_t)n * CHG], __popc(changed_mask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (a.first_changed)
+          sink += __hip_atomic_fetch_min(&a.first_changed[n], y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    __syncthreads();
+    n_batch = 0;
+  };
+
+  // ---- the row loop, with the number of visible K chunks as a compile-time constant (a colour sees its own and
+  // the earlier colours' channel groups only; a run-time test per chunk would cut the row into scheduling regions)
+  auto row_loop = [&](auto NCH) {
+  constexpr int nch = decltype(NCH)::value;
+  // one row out of ring slot S
+  auto draw_row = [&](auto S) {
+    constexpr int s = decltype(S)::value;
     float best = -INFINITY;
     int best_c = 0;
-    if (n_done == 0) {   // (first row of this wave: the first tile's weights)
-#pragma unroll
-      for (int c = 0; c < KCH; ++c)
-#pragma unroll
-        for (int s = 0; s < 4; ++s) wf[0][c][s] = head_w[(size_t)c * 256 + s * 64 + h * 32 + r];
-    }
-    static_for<NCT>([&](auto CT) {
-      constexpr int ct = decltype(CT)::value;
+    static_for<WT>([&](auto J) {
+      constexpr int j = decltype(J)::value;
       f32x16 acc;
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[e] = 0.f;
-      // this tile's weight fragments were read from LDS during the previous tile; request the next tile's now
       static_for<KCH>([&](auto C) {
         constexpr int c = decltype(C)::value;
-        const uint4* Wl = head_w + (size_t)((ct + 1) % NCT) * KCH * 256 + c * 256 + h * 32 + r;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) wf[(ct + 1) & 1][c][s] = Wl[s * 64];
-      });
-      static_for<KCH>([&](auto C) {
-        constexpr int c = decltype(C)::value;
-        if (c < n_chunks) mfma_chunk<T>(wf[ct & 1][c], af[c], acc);
+        if constexpr (c < nch) mfma_chunk<T>(wf[j][c], af[s][c], acc);
       });
       // the tile's noise: from load layout (pixel 8i + lane/8, classes 4 (lane%8) ..) to accumulator layout
       float* patch = noise_patch[wave];
       static_for<4>([&](auto I) {
         constexpr int i = decltype(I)::value;
-        *(vf4*)(patch + (8 * i + (lane >> 3)) * HEAD_PATCH_PITCH + (lane & 7) * 4) = gz[ct % RING][i];
+        *(vf4*)(patch + (8 * i + (lane >> 3)) * HEAD_PATCH_PITCH + (lane & 7) * 4) = gz[s][j][i];
       });
       vf4 gq[4];
       static_for<4>([&](auto Q) {
         constexpr int q = decltype(Q)::value;
         gq[q] = *(const vf4*)(patch + r * HEAD_PATCH_PITCH + 8 * q + 4 * h);
       });
-      // acc[4q + j]: class ct*32 + 8q + 4h + j of pixel r; classes ascend along (ct, q, j), so a strict compare
+      // acc[4q + i]: class (ct0 + j)*32 + 8q + 4h + i of pixel r; classes ascend along (j, q, i), so a strict compare
       // keeps the lowest class of a tie
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int cb = ct * TILE + 8 * q + 4 * h;
-        const float4 bv = bias_lds[cb >> 2];
+        const int cb = (ct0 + j) * TILE + 8 * q + 4 * h;
+        const float4 bv = bias4[j][q];
         const vf4 gv = gq[q];
         const float v0 = (acc[4 * q + 0] + bv.x) + gv[0];
         const float v1 = (acc[4 * q + 1] + bv.y) + gv[1];
@@ -2456,40 +2484,38 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
         if (v2 > best) { best = v2; best_c = cb + 2; }
         if (v3 > best) { best = v3; best_c = cb + 3; }
       }
-      // (without this the compiler postpones the compare chains of all tiles to the end of the row and keeps
-      // every tile's sums and noise alive until then)
-      asm volatile("" : "+v"(best), "+v"(best_c));
-      if constexpr (ct + RING < NCT) load_noise(g, ct + RING, gz[ct % RING]);
-      else if (g_next < n_rows) load_noise(g_next, ct + RING - NCT, gz[ct % RING]);
-      __builtin_amdgcn_sched_barrier(0);          // (keeps the reload here instead of at its use much later)
     });
     {
       const float ob = __shfl_xor(best, 32);
       const int oc = __shfl_xor(best_c, 32);
       if (ob > best || (ob == best && oc < best_c)) { best = ob; best_c = oc; }
     }
-    bool differs = false;
     if (h == 0) {
-      const int st = (y * 32 + r) * 3 + t;
-      if (a.state_one ? st == a.state_one[n] : (st >= a.state_lo && st < a.state_hi)) {
-        const uint8_t xn = (uint8_t)best_c;
-        differs = xn != x_old;
-        if (differs) a.x[xi] = xn;
-      }
+      cand_v[n_batch][wave][r] = best;
+      cand_c[n_batch][wave][r] = best_c;
     }
-    const unsigned long long changed_mask = __ballot(differs);
-    if (lane == 0 && changed_mask != 0 && !a.state_one) {
-      // returning atomics, so that "the value came back" means "performed"; the values are only consumed
-      // after the loop (before the tail counters), so a row does not wait for them
-      sink += __hip_atomic_fetch_add(&a.changed[(size_t)n * CHG], __popcll(changed_mask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (a.first_changed)
-        sink += __hip_atomic_fetch_min(&a.first_changed[n], y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) batch_row[n_batch] = g_slot[s];
+    if (tid < TILE) batch_x[n_batch][r] = xo[s];
+    ++n_batch;
+    // the slot is free: the row RR places on goes into it
+    g_slot[s] = g_req;
+    if (g_req < n_rows) {
+      load_row(g_req, af[s], gz[s], xo[s]);
+      g_req = row_after(g_req);
     }
-    g = g_next;
-    if (n_done == 0) JM_TSTAMP(2, 0);
-    if (n_done == 1) JM_TSTAMP(3, 0);
-    ++n_done;
+    __builtin_amdgcn_sched_barrier(0);                  // (keeps the requests here instead of at their use much later)
+    if (n_batch == HEAD_BATCH) finish_batch();
+  };
+  while (g_slot[0] < n_rows) {                          // (uniform over the workgroup)
+    static_for<RR>([&](auto S) {
+      if (g_slot[decltype(S)::value] < n_rows) draw_row(S);
+    });
   }
+  };
+  static_for<KCH + 1>([&](auto NCH) {
+    if (n_chunks == decltype(NCH)::value) row_loop(NCH);
+  });
+  if (n_batch > 0) finish_batch();
   JM_TSTAMP(4, 0);
   asm volatile("" ::"v"(sink));                         // every counter atomic of this thread has been performed
 
