@@ -2312,14 +2312,9 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
   const int stride = a.groups;
   const int g_first = group;
   int chunk = 0;                                        // rows g_first + (64 * chunk + k) * stride, k = 0..63
-  auto active_mask = [&](int ch) {
-    unsigned long long m = 0;
-    for (int k = 0; k < 64; ++k) {
-      const int gg = g_first + (64 * ch + k) * stride;
-      if (gg >= n_rows) break;
-      if (row_active(gg)) m |= 1ull << k;
-    }
-    return m;
+  auto active_mask = [&](int ch) {                      // (lane k tests row k of the chunk)
+    const long long gg = g_first + (long long)(64 * ch + lane) * stride;
+    return (unsigned long long)__ballot(gg < n_rows && row_active((int)gg));
   };
   unsigned long long mask = active_mask(0);
   // first active row at or after position k of the current chunk (moves on to later chunks when needed)
