@@ -1362,8 +1362,8 @@ static int run_conv_pass(made_model* m, int N, const SampleIO& io, bool first_pa
   c.H = cv.H;
   c.state_lo = io.t_lo;
   c.state_hi = io.t_hi;
-  // one workgroup per CU in all (3 colours x 85; the kernel runs one wave per SIMD); the 4 waves of workgroup
-  // (colour, group) walk over the pixel rows 4 * group + wave, + 4 * groups, ...
+  // one workgroup per CU in all (3 colours x 85; the kernel runs one wave per SIMD); workgroup (colour, group)
+  // walks over the pixel rows group, group + groups, ..., its 4 waves splitting the classes of each row
   c.groups = std::max(1, std::min(N * cv.H, 85));
   if (!whole_network) {
     c.dirty_lo = cv.win;
