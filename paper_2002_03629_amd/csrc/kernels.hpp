@@ -1752,6 +1752,13 @@ struct CatArgs {
   RetireArgs retire;
 };
 
+// 16 bytes of a stream that is read once per launch: loaded with the non-temporal hint
+__device__ __forceinline__ uint4 load_stream16(const uint4* p) {
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 template <typename T, int CNT, bool TWO>
 __device__ __forceinline__ void cat_group(const uint4* W0, const uint4* W1, const uint4* A0, const uint4* A1, int c0,
                                           f32x16 (&acc)[2][2]) {
@@ -1761,8 +1768,8 @@ __device__ __forceinline__ void cat_group(const uint4* W0, const uint4* W1, cons
     const size_t o = (size_t)(c0 + p) * 256;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      w0[p][s] = W0[o + s * 64];
-      w1[p][s] = W1[o + s * 64];
+      w0[p][s] = load_stream16(W0 + o + s * 64);
+      w1[p][s] = load_stream16(W1 + o + s * 64);
       a0[p][s] = A0[o + s * 64];
       if (TWO) a1[p][s] = A1[o + s * 64];
     }
