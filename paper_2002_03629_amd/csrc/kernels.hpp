@@ -85,6 +85,17 @@ __device__ __forceinline__ void store_quad<float>(float* dst, float a, float b, 
   *(float4*)dst = make_float4(a, b, c, d);
 }
 
+// 16 bytes of a stream that is read once per launch (weights that exceed the caches, noise): loaded with the
+// non-temporal hint.  Measured on this chip, a plain read of 2 GiB in contiguous pieces per workgroup: 6.4 TB/s with
+// ordinary loads, 7.1 TB/s with these.  Only for loads that take whole 128-byte lines in one instruction: the
+// Bernoulli and categorical epilogues fetch a line of noise with four instructions of 16 bytes per lane and lose
+// (0.200 against 0.177 ms, 150 against 142 us per launch) when the line is not kept between them.
+__device__ __forceinline__ uint4 load_stream16(const uint4* p) {
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // frag_offset(row, k) = frag_row_offset(row) + frag_col_offset(k): for code that stores many (row, k) pairs
 template <typename T>
 __device__ __forceinline__ size_t frag_row_offset(int row, int k_chunks) {
@@ -1752,13 +1763,6 @@ struct CatArgs {
   RetireArgs retire;
 };
 
-// 16 bytes of a stream that is read once per launch: loaded with the non-temporal hint
-__device__ __forceinline__ uint4 load_stream16(const uint4* p) {
-  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-  const u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
-  return make_uint4(v.x, v.y, v.z, v.w);
-}
-
 template <typename T, int CNT, bool TWO>
 __device__ __forceinline__ void cat_group(const uint4* W0, const uint4* W1, const uint4* A0, const uint4* A1, int c0,
                                           f32x16 (&acc)[2][2]) {
@@ -2363,8 +2367,8 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
   // ---- a row's inputs: the activations of its 32 pixels (every wave needs all of them) and the wave's share of
   // the noise, both into the same ring slot and requested together, RR rows ahead: loads return in order, so
   // whatever a row needs must not sit behind requests of later rows.  A noise tile (32 pixels x 32 classes) is
-  // fetched by 4 loads in which 8 lanes cover one pixel's 128 bytes (lane = (pixel % 8, 4 classes)): whole cache
-  // lines per group of lanes, measured 5.6 TB/s on this stream like a linear read (4.2 TB/s when every lane
+  // fetched by 4 non-temporal loads in which 8 lanes cover one pixel's 128 bytes (lane = (pixel % 8, 4 classes)): whole
+  // cache lines per group of lanes, measured 5.6 TB/s on this stream like a linear read (4.2 TB/s when every lane
   // fetches 16 bytes of its own pixel, 1.5 TB/s with 4-byte loads).  On consumption the tile is turned through a
   // wave-private LDS patch into the accumulator layout (lane (r, h): classes 8q + 4h .. + 3 of pixel r, q = 0..3).
   typedef __attribute__((__vector_size__(4 * sizeof(float)))) float vf4;   // (a native vector: stays in registers)
@@ -2386,7 +2390,7 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
       constexpr int j = decltype(J)::value;
       static_for<4>([&](auto I) {
         constexpr int i = decltype(I)::value;
-        gz_dst[j][i] = *(const vf4*)(nz + j * TILE + (size_t)i * 8 * 3 * CAT_C);
+        gz_dst[j][i] = __builtin_nontemporal_load((const vf4*)(nz + j * TILE + (size_t)i * 8 * 3 * CAT_C));
       });
     });
   };

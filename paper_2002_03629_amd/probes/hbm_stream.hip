@@ -1,17 +1,30 @@
 // Measurement probe (not part of the library): what a plain streaming kernel reads and copies per second on this
-// chip -- every workgroup walks contiguous 16-byte pieces of a 2 GiB buffer (the reads are summed so that they are
-// not optimised away).  The figure the HBM-bound kernels are compared with next to the nominal 8 TB/s.
+// chip.  A 2 GiB buffer is read in 16-byte pieces per lane (the reads are summed so that they are not optimised
+// away), in three ways: every workgroup striding through the whole buffer, every workgroup walking one contiguous
+// piece of it, and the latter with non-temporal loads.  The figures the HBM-bound kernels are compared with next to
+// the nominal 8 TB/s.
 #include <hip/hip_runtime.h>
 #include <stdio.h>
-template <int UNROLL>
-__global__ __launch_bounds__(256) void rd(const uint4* __restrict__ src, size_t n16, unsigned* out) {
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+// PIECE: 0 = the grid strides through the buffer together, 1 = a workgroup owns a contiguous piece; NT: non-temporal loads
+template <int UNROLL, int PIECE, bool NT>
+__global__ __launch_bounds__(256) void rd(const u32x4* __restrict__ src, size_t n16, unsigned* out) {
   unsigned acc = 0;
-  const size_t stride = (size_t)gridDim.x * 256;
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  for (; i + (UNROLL - 1) * stride < n16; i += UNROLL * stride) {
-    uint4 v[UNROLL];
+  size_t i, end, stride;
+  if (PIECE == 0) {
+    stride = (size_t)gridDim.x * 256;
+    i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    end = n16;
+  } else {
+    const size_t per = n16 / gridDim.x;
+    stride = 256;
+    i = per * blockIdx.x + threadIdx.x;
+    end = per * (blockIdx.x + 1);
+  }
+  for (; i + (UNROLL - 1) * stride < end; i += UNROLL * stride) {
+    u32x4 v[UNROLL];
 #pragma unroll
-    for (int u = 0; u < UNROLL; ++u) v[u] = src[i + u * stride];
+    for (int u = 0; u < UNROLL; ++u) v[u] = NT ? __builtin_nontemporal_load(src + i + u * stride) : src[i + u * stride];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
   }
@@ -29,13 +42,15 @@ int main() {
   hipEvent_t e0, e1;
   (void)hipEventCreate(&e0);
   (void)hipEventCreate(&e1);
-  for (int blocks : {1024, 2048, 4096, 8192, 16384}) {
-    for (int variant = 0; variant < 3; ++variant) {
+  const char* names[4] = {"read, grid-strided        ", "read, piece per workgroup ", "read, piece, non-temporal ", "copy, grid-strided        "};
+  for (int blocks : {2048, 8192, 32768}) {
+    for (int variant = 0; variant < 4; ++variant) {
       float best = 1e9;
       for (int rep = 0; rep < 4; ++rep) {
         (void)hipEventRecord(e0);
-        if (variant == 0) hipLaunchKernelGGL(rd<4>, dim3(blocks), dim3(256), 0, 0, src, n16, out);
-        else if (variant == 1) hipLaunchKernelGGL(rd<8>, dim3(blocks), dim3(256), 0, 0, src, n16, out);
+        if (variant == 0) hipLaunchKernelGGL((rd<8, 0, false>), dim3(blocks), dim3(256), 0, 0, (const u32x4*)src, n16, out);
+        else if (variant == 1) hipLaunchKernelGGL((rd<8, 1, false>), dim3(blocks), dim3(256), 0, 0, (const u32x4*)src, n16, out);
+        else if (variant == 2) hipLaunchKernelGGL((rd<8, 1, true>), dim3(blocks), dim3(256), 0, 0, (const u32x4*)src, n16, out);
         else hipLaunchKernelGGL(cp, dim3(blocks), dim3(256), 0, 0, src, dst, n16);
         (void)hipEventRecord(e1);
         (void)hipEventSynchronize(e1);
@@ -43,8 +58,8 @@ int main() {
         (void)hipEventElapsedTime(&ms, e0, e1);
         if (rep && ms < best) best = ms;
       }
-      printf("%s blocks %5d: %.3f ms  %.2f TB/s %s\n", variant == 0 ? "read x4 " : variant == 1 ? "read x8 " : "copy    ", blocks, best,
-             bytes / best / 1e9 * (variant == 2 ? 2 : 1), variant == 2 ? "(read + write)" : "");
+      printf("%s blocks %5d: %.3f ms  %.2f TB/s %s\n", names[variant], blocks, best, bytes / best / 1e9 * (variant == 3 ? 2 : 1),
+             variant == 3 ? "(read + write)" : "");
     }
   }
   return 0;
