@@ -15,9 +15,9 @@ namespace jm {
 
 constexpr int ONEHOT_WAVES = 8;
 constexpr int ONEHOT_THREADS = 64 * ONEHOT_WAVES;
-constexpr int ONEHOT_UPT = 8;                     // units per lane: 16 bytes of bf16 per row
-constexpr int ONEHOT_UNITS = 64 * ONEHOT_UPT;     // units per workgroup
-constexpr int ONEHOT_DEPTH = 16;                  // rows a wave has in flight per lane
+constexpr int ONEHOT_SUB = 1;                     // sub-blocks of 512 units per workgroup (2: same time, 4: slower)
+constexpr int ONEHOT_UNITS = 512 * ONEHOT_SUB;    // units per workgroup
+constexpr int ONEHOT_DEPTH = 16;                   // rows a wave has in flight per lane
 
 struct OnehotArgs {
   const void* Wg;        // [D][C][pitch] of T
@@ -36,12 +36,12 @@ struct OnehotArgs {
 
 // what a lane reads instead of a row none of whose units it may see (a branch around the load would make every
 // load wait for the one before it)
-__device__ __align__(32) const float g_onehot_zeros[ONEHOT_UPT] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+__device__ __align__(32) const float g_onehot_zeros[8] = {};
 
 // acc += the lane's 8 units of one weight row
-template <typename T> __device__ __forceinline__ void add_row8(const T* p, float (&acc)[ONEHOT_UPT]);
-template <> __device__ __forceinline__ void add_row8<bf16_t>(const bf16_t* p, float (&acc)[ONEHOT_UPT]) {
-  const uint4 u = *(const uint4*)p;
+template <typename T> __device__ __forceinline__ void add_row8(const T* p, float (&acc)[8]);
+template <> __device__ __forceinline__ void add_row8<bf16_t>(const bf16_t* p, float (&acc)[8]) {
+  const uint4 u = load_stream16((const uint4*)p);
   const uint32_t w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -49,7 +49,7 @@ template <> __device__ __forceinline__ void add_row8<bf16_t>(const bf16_t* p, fl
     acc[2 * i + 1] += __uint_as_float(w[i] & 0xffff0000u);
   }
 }
-template <> __device__ __forceinline__ void add_row8<float>(const float* p, float (&acc)[ONEHOT_UPT]) {
+template <> __device__ __forceinline__ void add_row8<float>(const float* p, float (&acc)[8]) {
   const float4 v0 = *(const float4*)p, v1 = *(const float4*)(p + 4);
   acc[0] += v0.x; acc[1] += v0.y; acc[2] += v0.z; acc[3] += v0.w;
   acc[4] += v1.x; acc[5] += v1.y; acc[6] += v1.z; acc[7] += v1.w;
@@ -57,7 +57,11 @@ template <> __device__ __forceinline__ void add_row8<float>(const float* p, floa
 
 // A workgroup owns one sample and ONEHOT_UNITS consecutive units; its waves take the positions in interleaved
 // groups of ONEHOT_DEPTH (each wave adds its rows in position order, then the waves' partial sums are added in
-// wave order: a fixed order), so that 16 waves per CU keep enough rows in flight to cover the memory latency.
+// wave order: a fixed order), so that the waves of a compute unit keep enough rows in flight to cover the memory
+// latency.  A lane owns 8 units in each of the workgroup's ONEHOT_SUB sub-blocks of 512 units, so one load
+// instruction of a wave takes 1 KB of a row in whole cache lines, with the non-temporal hint: nothing of the 800 MB
+// is worth keeping, and without it the stream pushes the next layers' weights out of the caches (cfg4 with one-hot
+// input: this launch 52.8 -> 47.5 us, the second hidden layer 11.2 -> 9.8 us, the output layer 143.5 -> 140.9 us).
 template <typename T>
 __global__ __launch_bounds__(ONEHOT_THREADS) void onehot_first_layer_kernel(OnehotArgs a) {
   __shared__ uint8_t xs[4096];
@@ -67,12 +71,14 @@ __global__ __launch_bounds__(ONEHOT_THREADS) void onehot_first_layer_kernel(Oneh
   if ((int)blockIdx.y >= n_rows) return;
   const int sample = a.rows ? a.rows[blockIdx.y] : (int)blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int u0 = a.unit_begin + blockIdx.x * ONEHOT_UNITS + ONEHOT_UPT * lane;
-  const bool mine = u0 < a.unit_end;           // (unit_end is a multiple of 32, u0 of 8: all 8 units or none)
+  const int u0 = a.unit_begin + blockIdx.x * ONEHOT_UNITS + 8 * lane;   // sub-block b: units u0 + 512 b .. + 7
+  // (unit_end is a multiple of 32, the sub-blocks' first units of 8: all 8 units of a sub-block or none)
   const T* Wg = (const T*)a.Wg;
-  float acc[ONEHOT_UPT];
+  float acc[ONEHOT_SUB][8];
 #pragma unroll
-  for (int e = 0; e < ONEHOT_UPT; ++e) acc[e] = 0.f;
+  for (int b = 0; b < ONEHOT_SUB; ++b)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
   // positions are taken in slabs of 4096 symbols staged in LDS
   for (int s0 = 0; s0 < a.t_end; s0 += 4096) {
     const int s1 = min(a.t_end, s0 + 4096);
@@ -82,41 +88,49 @@ __global__ __launch_bounds__(ONEHOT_THREADS) void onehot_first_layer_kernel(Oneh
       first_s[i] = a.cnt_lt[s0 + i + 1];
     }
     __syncthreads();
-    if (mine) {
-      for (int t = s0 + wave * ONEHOT_DEPTH; t < s1; t += ONEHOT_WAVES * ONEHOT_DEPTH) {
-        // independent loads: all rows of a group are requested before the first add
-        float part[ONEHOT_DEPTH][ONEHOT_UPT];
+    for (int t = s0 + wave * ONEHOT_DEPTH; t < s1; t += ONEHOT_WAVES * ONEHOT_DEPTH) {
+      // independent loads: all rows of a group are requested before the first add
+      float part[ONEHOT_DEPTH][ONEHOT_SUB][8];
 #pragma unroll
-        for (int i = 0; i < ONEHOT_DEPTH; ++i) {
-          const int tt = min(t + i, s1 - 1);
-          const bool on = t + i < s1 && u0 + ONEHOT_UPT - 1 >= first_s[tt - s0];      // some of these units see position tt
-          const T* p = Wg + ((size_t)tt * a.C + min((int)xs[tt - s0], a.C - 1)) * a.pitch + u0;   // (a symbol >= C reads class C-1)
+      for (int i = 0; i < ONEHOT_DEPTH; ++i) {
+        const int tt = min(t + i, s1 - 1);
+        const int first = t + i < s1 ? first_s[tt - s0] : 0x7fffffff;
+        const T* p = Wg + ((size_t)tt * a.C + min((int)xs[tt - s0], a.C - 1)) * a.pitch + u0;   // (a symbol >= C reads class C-1)
 #pragma unroll
-          for (int e = 0; e < ONEHOT_UPT; ++e) part[i][e] = 0.f;
-          add_row8<T>(on ? p : (const T*)g_onehot_zeros, part[i]);
+        for (int b = 0; b < ONEHOT_SUB; ++b) {
+          const int ub = u0 + 512 * b;
+          const bool on = ub < a.unit_end && ub + 7 >= first;              // some of these units see position tt
+#pragma unroll
+          for (int e = 0; e < 8; ++e) part[i][b][e] = 0.f;
+          add_row8<T>(on ? p + 512 * b : (const T*)g_onehot_zeros, part[i][b]);
         }
-#pragma unroll
-        for (int i = 0; i < ONEHOT_DEPTH; ++i)
-#pragma unroll
-          for (int e = 0; e < ONEHOT_UPT; ++e) acc[e] += part[i][e];
       }
+#pragma unroll
+      for (int i = 0; i < ONEHOT_DEPTH; ++i)
+#pragma unroll
+        for (int b = 0; b < ONEHOT_SUB; ++b)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[b][e] += part[i][b][e];
     }
   }
 #pragma unroll
-  for (int e = 0; e < ONEHOT_UPT; ++e) part_s[wave][ONEHOT_UPT * lane + e] = acc[e];
+  for (int b = 0; b < ONEHOT_SUB; ++b)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part_s[wave][512 * b + 8 * lane + e] = acc[b][e];
   __syncthreads();
-  if (wave == 0 && mine) {
-    float v[ONEHOT_UPT];
+  if (wave < ONEHOT_SUB && u0 + 512 * wave < a.unit_end) {                 // wave b finishes sub-block b
+    const int ub = u0 + 512 * wave;
+    float v[8];
 #pragma unroll
-    for (int e = 0; e < ONEHOT_UPT; ++e) {
-      float s = part_s[0][ONEHOT_UPT * lane + e];
+    for (int e = 0; e < 8; ++e) {
+      float s = part_s[0][512 * wave + 8 * lane + e];
 #pragma unroll
-      for (int w = 1; w < ONEHOT_WAVES; ++w) s += part_s[w][ONEHOT_UPT * lane + e];
-      v[e] = fmaxf(s + a.bias[u0 + e], 0.f);
+      for (int w = 1; w < ONEHOT_WAVES; ++w) s += part_s[w][512 * wave + 8 * lane + e];
+      v[e] = fmaxf(s + a.bias[ub + e], 0.f);
     }
     const float lo[4] = {v[0], v[1], v[2], v[3]}, hi[4] = {v[4], v[5], v[6], v[7]};
-    store4<T>((T*)a.out + frag_offset<T>(sample, u0, a.out_chunks), lo);
-    store4<T>((T*)a.out + frag_offset<T>(sample, u0 + 4, a.out_chunks), hi);
+    store4<T>((T*)a.out + frag_offset<T>(sample, ub, a.out_chunks), lo);
+    store4<T>((T*)a.out + frag_offset<T>(sample, ub + 4, a.out_chunks), hi);
   }
 }
 
