@@ -1139,9 +1139,9 @@ static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, in
         const int chunks = (g.unit_end - g.unit_begin + ONEHOT_UNITS - 1) / ONEHOT_UNITS;
         prof_mark(m, 0, false, s);
         if (m->dtype == MADE_BF16)
-          hipLaunchKernelGGL(onehot_first_layer_kernel<bf16_t>, dim3(chunks, std::max(rs.n_rows, 1)), dim3(ONEHOT_THREADS), 0, s, g);
+          hipLaunchKernelGGL(onehot_first_layer_kernel<bf16_t>, dim3((chunks + 1) / 2, std::max(rs.n_rows, 1)), dim3(ONEHOT_THREADS), 0, s, g);
         else
-          hipLaunchKernelGGL(onehot_first_layer_kernel<float>, dim3(chunks, std::max(rs.n_rows, 1)), dim3(ONEHOT_THREADS), 0, s, g);
+          hipLaunchKernelGGL(onehot_first_layer_kernel<float>, dim3((chunks + 1) / 2, std::max(rs.n_rows, 1)), dim3(ONEHOT_THREADS), 0, s, g);
         prof_mark(m, 0, true, s);
         m->stats[2]++;
       }

@@ -55,82 +55,105 @@ template <> __device__ __forceinline__ void add_row8<float>(const float* p, floa
   acc[4] += v1.x; acc[5] += v1.y; acc[6] += v1.z; acc[7] += v1.w;
 }
 
-// A workgroup owns one sample and ONEHOT_UNITS consecutive units; its waves take the positions in interleaved
-// groups of ONEHOT_DEPTH (each wave adds its rows in position order, then the waves' partial sums are added in
-// wave order: a fixed order), so that the waves of a compute unit keep enough rows in flight to cover the memory
-// latency.  A lane owns 8 units in each of the workgroup's ONEHOT_SUB sub-blocks of 512 units, so one load
-// instruction of a wave takes 1 KB of a row in whole cache lines, with the non-temporal hint: nothing of the 800 MB
-// is worth keeping, and without it the stream pushes the next layers' weights out of the caches (cfg4 with one-hot
-// input: this launch 52.8 -> 47.5 us, the second hidden layer 11.2 -> 9.8 us, the output layer 143.5 -> 140.9 us).
+// A workgroup owns one sample and ONEHOT_UNITS consecutive units at a time; its waves take the positions in
+// interleaved groups of ONEHOT_DEPTH (each wave adds its rows in position order, then the waves' partial sums are
+// added in wave order: a fixed order), so that the waves of a compute unit keep enough rows in flight to cover the
+// memory latency.  A lane owns 8 units in each of the ONEHOT_SUB sub-blocks of 512 units, so one load instruction of a
+// wave takes 1 KB of a row in whole cache lines, with the non-temporal hint: nothing of the 800 MB is worth keeping,
+// and without it the stream pushes the next layers' weights out of the caches (cfg4 with one-hot input: this launch
+// 52.8 -> 47.5 us, the second hidden layer 11.2 -> 9.8 us, the output layer 143.5 -> 140.9 us).
+// Units are laid out by degree, so the positions a chunk of units can see are a PREFIX of the positions, longer the
+// higher the chunk: a chunk only walks its prefix (requests for rows nobody of the chunk sees would occupy the places
+// of real ones), and a workgroup takes TWO chunks, c from the end and c from the start, one after the other, so that
+// every workgroup walks about the same number of rows.
 template <typename T>
 __global__ __launch_bounds__(ONEHOT_THREADS) void onehot_first_layer_kernel(OnehotArgs a) {
   __shared__ uint8_t xs[4096];
   __shared__ int first_s[4096];      // per staged position: first unit that may see it
   __shared__ float part_s[ONEHOT_WAVES][ONEHOT_UNITS];
+  __shared__ int visible_s;
   const int n_rows = a.n_rows_ptr ? *a.n_rows_ptr : a.n_rows;
   if ((int)blockIdx.y >= n_rows) return;
   const int sample = a.rows ? a.rows[blockIdx.y] : (int)blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int u0 = a.unit_begin + blockIdx.x * ONEHOT_UNITS + 8 * lane;   // sub-block b: units u0 + 512 b .. + 7
-  // (unit_end is a multiple of 32, the sub-blocks' first units of 8: all 8 units of a sub-block or none)
+  const int chunks = (a.unit_end - a.unit_begin + ONEHOT_UNITS - 1) / ONEHOT_UNITS;
   const T* Wg = (const T*)a.Wg;
-  float acc[ONEHOT_SUB][8];
+  const bool one_slab = a.t_end <= 4096;         // (then the symbols are staged once, for both chunks)
+  for (int part = 0; part < 2; ++part) {
+    const int chunk = part == 0 ? chunks - 1 - (int)blockIdx.x : (int)blockIdx.x;
+    if (part == 1 && chunk >= chunks - 1 - (int)blockIdx.x) break;   // (an odd number of chunks: the middle one is part 0's)
+    const int u0 = a.unit_begin + chunk * ONEHOT_UNITS + 8 * lane;   // sub-block b: units u0 + 512 b .. + 7
+    // (unit_end is a multiple of 32, the sub-blocks' first units of 8: all 8 units of a sub-block or none)
+    const int u_last = min(a.unit_begin + (chunk + 1) * ONEHOT_UNITS, a.unit_end) - 1;
+    float acc[ONEHOT_SUB][8];
 #pragma unroll
-  for (int b = 0; b < ONEHOT_SUB; ++b)
+    for (int b = 0; b < ONEHOT_SUB; ++b)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
-  // positions are taken in slabs of 4096 symbols staged in LDS
-  for (int s0 = 0; s0 < a.t_end; s0 += 4096) {
-    const int s1 = min(a.t_end, s0 + 4096);
-    __syncthreads();
-    for (int i = threadIdx.x; i < s1 - s0; i += ONEHOT_THREADS) {
-      xs[i] = a.x[(size_t)sample * a.D + s0 + i];
-      first_s[i] = a.cnt_lt[s0 + i + 1];
-    }
-    __syncthreads();
-    for (int t = s0 + wave * ONEHOT_DEPTH; t < s1; t += ONEHOT_WAVES * ONEHOT_DEPTH) {
-      // independent loads: all rows of a group are requested before the first add
-      float part[ONEHOT_DEPTH][ONEHOT_SUB][8];
-#pragma unroll
-      for (int i = 0; i < ONEHOT_DEPTH; ++i) {
-        const int tt = min(t + i, s1 - 1);
-        const int first = t + i < s1 ? first_s[tt - s0] : 0x7fffffff;
-        const T* p = Wg + ((size_t)tt * a.C + min((int)xs[tt - s0], a.C - 1)) * a.pitch + u0;   // (a symbol >= C reads class C-1)
-#pragma unroll
-        for (int b = 0; b < ONEHOT_SUB; ++b) {
-          const int ub = u0 + 512 * b;
-          const bool on = ub < a.unit_end && ub + 7 >= first;              // some of these units see position tt
-#pragma unroll
-          for (int e = 0; e < 8; ++e) part[i][b][e] = 0.f;
-          add_row8<T>(on ? p + 512 * b : (const T*)g_onehot_zeros, part[i][b]);
+      for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
+    // positions are taken in slabs of 4096 symbols staged in LDS
+    for (int s0 = 0; s0 < a.t_end; s0 += 4096) {
+      const int s1 = min(a.t_end, s0 + 4096);
+      __syncthreads();                           // (the slab and the counter are free)
+      if (part == 0 || !one_slab)
+        for (int i = threadIdx.x; i < s1 - s0; i += ONEHOT_THREADS) {
+          xs[i] = a.x[(size_t)sample * a.D + s0 + i];
+          first_s[i] = a.cnt_lt[s0 + i + 1];
         }
+      if (threadIdx.x == 0) visible_s = 0;
+      __syncthreads();
+      // the slab's positions that some unit of the chunk sees: a prefix (first_s ascends)
+      int mine_visible = 0;
+      for (int i = threadIdx.x; i < s1 - s0; i += ONEHOT_THREADS) mine_visible += first_s[i] <= u_last ? 1 : 0;
+      if (mine_visible) atomicAdd(&visible_s, mine_visible);
+      __syncthreads();
+      const int sv = s0 + visible_s;             // positions [s0, sv) are walked
+      for (int t = s0 + wave * ONEHOT_DEPTH; t < sv; t += ONEHOT_WAVES * ONEHOT_DEPTH) {
+        // independent loads: all rows of a group are requested before the first add
+        float part_sum[ONEHOT_DEPTH][ONEHOT_SUB][8];
+#pragma unroll
+        for (int i = 0; i < ONEHOT_DEPTH; ++i) {
+          const int tt = min(t + i, sv - 1);
+          const int first = t + i < sv ? first_s[tt - s0] : 0x7fffffff;
+          const T* p = Wg + ((size_t)tt * a.C + min((int)xs[tt - s0], a.C - 1)) * a.pitch + u0;   // (a symbol >= C reads class C-1)
+#pragma unroll
+          for (int b = 0; b < ONEHOT_SUB; ++b) {
+            const int ub = u0 + 512 * b;
+            const bool on = ub < a.unit_end && ub + 7 >= first;            // some of these units see position tt
+#pragma unroll
+            for (int e = 0; e < 8; ++e) part_sum[i][b][e] = 0.f;
+            // (a lane that sees nothing reads zeros instead of branching around the load: a branch would make every
+            // load wait for the one before it)
+            add_row8<T>(on ? p + 512 * b : (const T*)g_onehot_zeros, part_sum[i][b]);
+          }
+        }
+#pragma unroll
+        for (int i = 0; i < ONEHOT_DEPTH; ++i)
+#pragma unroll
+          for (int b = 0; b < ONEHOT_SUB; ++b)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[b][e] += part_sum[i][b][e];
       }
-#pragma unroll
-      for (int i = 0; i < ONEHOT_DEPTH; ++i)
-#pragma unroll
-        for (int b = 0; b < ONEHOT_SUB; ++b)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[b][e] += part[i][b][e];
     }
-  }
+    if (part == 1) __syncthreads();              // (part 0's partial sums have been read)
 #pragma unroll
-  for (int b = 0; b < ONEHOT_SUB; ++b)
+    for (int b = 0; b < ONEHOT_SUB; ++b)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) part_s[wave][512 * b + 8 * lane + e] = acc[b][e];
-  __syncthreads();
-  if (wave < ONEHOT_SUB && u0 + 512 * wave < a.unit_end) {                 // wave b finishes sub-block b
-    const int ub = u0 + 512 * wave;
-    float v[8];
+      for (int e = 0; e < 8; ++e) part_s[wave][512 * b + 8 * lane + e] = acc[b][e];
+    __syncthreads();
+    if (wave < ONEHOT_SUB && u0 + 512 * wave < a.unit_end) {               // wave b finishes sub-block b
+      const int ub = u0 + 512 * wave;
+      float v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float s = part_s[0][512 * wave + 8 * lane + e];
+      for (int e = 0; e < 8; ++e) {
+        float s = part_s[0][512 * wave + 8 * lane + e];
 #pragma unroll
-      for (int w = 1; w < ONEHOT_WAVES; ++w) s += part_s[w][512 * wave + 8 * lane + e];
-      v[e] = fmaxf(s + a.bias[ub + e], 0.f);
+        for (int w = 1; w < ONEHOT_WAVES; ++w) s += part_s[w][512 * wave + 8 * lane + e];
+        v[e] = fmaxf(s + a.bias[ub + e], 0.f);
+      }
+      const float lo[4] = {v[0], v[1], v[2], v[3]}, hi[4] = {v[4], v[5], v[6], v[7]};
+      store4<T>((T*)a.out + frag_offset<T>(sample, ub, a.out_chunks), lo);
+      store4<T>((T*)a.out + frag_offset<T>(sample, ub + 4, a.out_chunks), hi);
     }
-    const float lo[4] = {v[0], v[1], v[2], v[3]}, hi[4] = {v[4], v[5], v[6], v[7]};
-    store4<T>((T*)a.out + frag_offset<T>(sample, ub, a.out_chunks), lo);
-    store4<T>((T*)a.out + frag_offset<T>(sample, ub + 4, a.out_chunks), hi);
   }
 }
 
