@@ -17,7 +17,7 @@ constexpr int ONEHOT_WAVES = 8;
 constexpr int ONEHOT_THREADS = 64 * ONEHOT_WAVES;
 constexpr int ONEHOT_SUB = 1;                     // sub-blocks of 512 units per workgroup (2: same time, 4: slower)
 constexpr int ONEHOT_UNITS = 512 * ONEHOT_SUB;    // units per workgroup
-constexpr int ONEHOT_DEPTH = 16;                   // rows a wave has in flight per lane
+constexpr int ONEHOT_DEPTH = 8;                    // rows per register set: a wave has one or two sets in flight
 
 struct OnehotArgs {
   const void* Wg;        // [D][C][pitch] of T
@@ -38,21 +38,26 @@ struct OnehotArgs {
 // load wait for the one before it)
 __device__ __align__(32) const float g_onehot_zeros[8] = {};
 
-// acc += the lane's 8 units of one weight row
-template <typename T> __device__ __forceinline__ void add_row8(const T* p, float (&acc)[8]);
-template <> __device__ __forceinline__ void add_row8<bf16_t>(const bf16_t* p, float (&acc)[8]) {
-  const uint4 u = load_stream16((const uint4*)p);
-  const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+// The lane's 8 units of one weight row as loaded (16 bytes of bf16, 32 of fp32; non-temporal loads), and their
+// addition to the lane's sums.
+template <typename T> struct RowPiece;
+template <> struct RowPiece<bf16_t> { uint4 a; };
+template <> struct RowPiece<float> { uint4 a, b; };
+__device__ __forceinline__ RowPiece<bf16_t> load_row8(const bf16_t* p) { return {load_stream16((const uint4*)p)}; }
+__device__ __forceinline__ RowPiece<float> load_row8(const float* p) {
+  return {load_stream16((const uint4*)p), load_stream16((const uint4*)p + 1)};
+}
+__device__ __forceinline__ void add_row8(const RowPiece<bf16_t>& r, float (&acc)[8]) {
+  const uint32_t w[4] = {r.a.x, r.a.y, r.a.z, r.a.w};
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     acc[2 * i] += __uint_as_float(w[i] << 16);
     acc[2 * i + 1] += __uint_as_float(w[i] & 0xffff0000u);
   }
 }
-template <> __device__ __forceinline__ void add_row8<float>(const float* p, float (&acc)[8]) {
-  const float4 v0 = *(const float4*)p, v1 = *(const float4*)(p + 4);
-  acc[0] += v0.x; acc[1] += v0.y; acc[2] += v0.z; acc[3] += v0.w;
-  acc[4] += v1.x; acc[5] += v1.y; acc[6] += v1.z; acc[7] += v1.w;
+__device__ __forceinline__ void add_row8(const RowPiece<float>& r, float (&acc)[8]) {
+  acc[0] += __uint_as_float(r.a.x); acc[1] += __uint_as_float(r.a.y); acc[2] += __uint_as_float(r.a.z); acc[3] += __uint_as_float(r.a.w);
+  acc[4] += __uint_as_float(r.b.x); acc[5] += __uint_as_float(r.b.y); acc[6] += __uint_as_float(r.b.z); acc[7] += __uint_as_float(r.b.w);
 }
 
 // A workgroup owns one sample and ONEHOT_UNITS consecutive units at a time; its waves take the positions in
@@ -107,9 +112,11 @@ __global__ __launch_bounds__(ONEHOT_THREADS) void onehot_first_layer_kernel(Oneh
       if (mine_visible) atomicAdd(&visible_s, mine_visible);
       __syncthreads();
       const int sv = s0 + visible_s;             // positions [s0, sv) are walked
-      for (int t = s0 + wave * ONEHOT_DEPTH; t < sv; t += ONEHOT_WAVES * ONEHOT_DEPTH) {
-        // independent loads: all rows of a group are requested before the first add
-        float part_sum[ONEHOT_DEPTH][ONEHOT_SUB][8];
+      // Two sets of ONEHOT_DEPTH rows: while one set's rows are added, the other set's are on their way (a wave that
+      // requests, waits and adds in turn has nothing in flight while it adds).  Rows are added in position order.
+      RowPiece<T> raw[2][ONEHOT_DEPTH][ONEHOT_SUB];
+      auto request = [&](int t, auto SET) {
+        constexpr int set = decltype(SET)::value;
 #pragma unroll
         for (int i = 0; i < ONEHOT_DEPTH; ++i) {
           const int tt = min(t + i, sv - 1);
@@ -119,19 +126,33 @@ __global__ __launch_bounds__(ONEHOT_THREADS) void onehot_first_layer_kernel(Oneh
           for (int b = 0; b < ONEHOT_SUB; ++b) {
             const int ub = u0 + 512 * b;
             const bool on = ub < a.unit_end && ub + 7 >= first;            // some of these units see position tt
-#pragma unroll
-            for (int e = 0; e < 8; ++e) part_sum[i][b][e] = 0.f;
             // (a lane that sees nothing reads zeros instead of branching around the load: a branch would make every
             // load wait for the one before it)
-            add_row8<T>(on ? p + 512 * b : (const T*)g_onehot_zeros, part_sum[i][b]);
+            raw[set][i][b] = load_row8(on ? p + 512 * b : (const T*)g_onehot_zeros);
           }
         }
+      };
+      auto add = [&](auto SET) {
+        constexpr int set = decltype(SET)::value;
 #pragma unroll
         for (int i = 0; i < ONEHOT_DEPTH; ++i)
 #pragma unroll
-          for (int b = 0; b < ONEHOT_SUB; ++b)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[b][e] += part_sum[i][b][e];
+          for (int b = 0; b < ONEHOT_SUB; ++b) add_row8(raw[set][i][b], acc[b]);
+      };
+      const std::integral_constant<int, 0> set0;
+      const std::integral_constant<int, 1> set1;
+      const int step = ONEHOT_WAVES * ONEHOT_DEPTH;
+      int t = s0 + wave * ONEHOT_DEPTH;
+      if (t < sv) request(t, set0);
+      for (; t < sv; t += 2 * step) {
+        if (t + step < sv) request(t + step, set1);
+        __builtin_amdgcn_sched_barrier(0);
+        add(set0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + 2 * step < sv) request(t + 2 * step, set0);
+        __builtin_amdgcn_sched_barrier(0);
+        if (t + step < sv) add(set1);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
     if (part == 1) __syncthreads();              // (part 0's partial sums have been read)
