@@ -68,6 +68,11 @@ def workload(name: str) -> Workload:
                                          SEED_BASE + 19, gain=3.0, onehot=True),
         "mid_cat_onehot": Workload("mid_cat_onehot", 70, 7, [300, 130], "bf16", 45, "random", "fan_in",
                                    SEED_BASE + 21, gain=2.5, onehot=True),
+        # first layers of several 512-unit chunks (three: an odd count, and two), which the one-hot kernel pairs up
+        "wide_cat_onehot": Workload("wide_cat_onehot", 40, 7, [1400, 96], "bf16", 37, "random", "fan_in",
+                                    SEED_BASE + 23, gain=2.0, onehot=True),
+        "wide_cat_onehot_f32": Workload("wide_cat_onehot_f32", 30, 5, [700], "f32", 9, "random", "fan_in",
+                                        SEED_BASE + 24, gain=2.5, onehot=True),
         # continuous states, logistic conditionals: the paper's own MADE (2 x 512 hidden, 100 images, T = 784)
         "made_logistic": Workload("made_logistic", 784, 2, [512, 512], "bf16", 100, "random", "fan_in", SEED_BASE + 6,
                                   real=True),

@@ -47,7 +47,7 @@ def execution_path(request):
 
 
 SMALL = ["cfg1", "small_f32", "small_bf16", "mid_bf16", "small_cat", "small_cat_f32", "small_cat_onehot",
-         "small_cat_onehot_f32", "mid_cat_onehot"]
+         "small_cat_onehot_f32", "mid_cat_onehot", "wide_cat_onehot", "wide_cat_onehot_f32"]
 
 
 def _symbols(w, rng, N):
