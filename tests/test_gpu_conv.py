@@ -371,3 +371,17 @@ def test_an_image_gets_the_same_bits_at_any_batch_position():
             assert (a2[l] == a1[l][perm]).all(), f"layer {l}"
         z1, z2 = g.logits(x1), g.logits(x1[perm])
         assert (z2 == z1[perm]).all()
+
+
+def test_a_large_batch_repeats_the_small_one():
+    """The benchmark's network on 7 images and on 70 (the same 7 noise arrays ten times over): every copy gets the
+    symbols and pass counts of its original.  At 70 images a workgroup of the head draws more rows than fit one of
+    its finishing phases, so the phases repeat within a launch."""
+    w = dataclasses.replace(S.conv_workload("cfg5"), N=7)
+    net = S.make_conv_network(w)
+    noise = S.make_conv_noise(w)
+    with ConvGpu(net) as g:
+        x1, it1 = g.run("jacobi", noise)
+        x2, it2 = g.run("jacobi", np.tile(noise, (10,) + (1,) * (noise.ndim - 1)))
+        assert (x2.reshape(10, 7, -1) == x1[None]).all()
+        assert (it2.reshape(10, 7) == it1[None]).all()
