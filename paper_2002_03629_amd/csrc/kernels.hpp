@@ -2276,8 +2276,6 @@ struct ConvHeadArgs {
   RetireArgs retire;
 };
 
-constexpr int HEAD_PATCH_PITCH = TILE + 4;   // floats per pixel row of the noise patch (16-byte reads of 16 lanes
-                                             // then cover all 64 banks)
 constexpr int HEAD_BATCH = 16;               // rows a workgroup draws between two of its finishing phases
 
 // 1 x 1 head + Gumbel-max draw + change detection of the convolutional model.  A workgroup is bound to one colour
@@ -2297,7 +2295,6 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
   constexpr int WT = NCT / 4;                           // class tiles per wave
   constexpr int RR = sizeof(T) == 2 ? 3 : 2;            // rows whose inputs are in flight or in registers
   static_assert(NCT % 4 == 0, "the class tiles are dealt to four waves");
-  __shared__ __align__(16) float noise_patch[4][TILE * HEAD_PATCH_PITCH];
   __shared__ float cand_v[HEAD_BATCH][4][TILE];         // per row of the batch and wave: the wave's best value ...
   __shared__ int cand_c[HEAD_BATCH][4][TILE];           // ... and its class, per pixel
   __shared__ int batch_row[HEAD_BATCH];
@@ -2366,11 +2363,12 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
 
   // ---- a row's inputs: the activations of its 32 pixels (every wave needs all of them) and the wave's share of
   // the noise, both into the same ring slot and requested together, RR rows ahead: loads return in order, so
-  // whatever a row needs must not sit behind requests of later rows.  A noise tile (32 pixels x 32 classes) is
-  // fetched by 4 non-temporal loads in which 8 lanes cover one pixel's 128 bytes (lane = (pixel % 8, 4 classes)): whole
-  // cache lines per group of lanes, measured 5.6 TB/s on this stream like a linear read (4.2 TB/s when every lane
-  // fetches 16 bytes of its own pixel, 1.5 TB/s with 4-byte loads).  On consumption the tile is turned through a
-  // wave-private LDS patch into the accumulator layout (lane (r, h): classes 8q + 4h .. + 3 of pixel r, q = 0..3).
+  // whatever a row needs must not sit behind requests of later rows.  The noise is fetched in the accumulator
+  // layout at once: lane (r, h) takes classes 8q + 4h .. + 3 of pixel r for q = 0..3 of each tile, 16 bytes a load
+  // (a pixel's 128-byte line of a tile is covered by the four loads of its two lanes and stays in the cache between
+  // them: no non-temporal hint here).  Fetching whole lines per group of 8 lanes and turning the tile through an
+  // LDS patch reads the stream faster on its own (5.6 against 4.2 TB/s, loads only) but the launch is bound by
+  // the dependent work per row, which the patch lengthens: 25.2 us per launch with it, 24.6 without.
   typedef __attribute__((__vector_size__(4 * sizeof(float)))) float vf4;   // (a native vector: stays in registers)
   uint4 af[RR][KCH][4];
   vf4 gz[RR][WT][4];
@@ -2385,12 +2383,12 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
     });
     int g_noise = g_row;
     if (a.state_one) g_noise = ((g_row / a.H) % a.noise_images) * a.H + g_row % a.H;   // (a virtual image: its real image's noise)
-    const float* nz = a.noise + ((size_t)(g_noise * 32 + (lane >> 3)) * 3 + t) * CAT_C + ct0 * TILE + (lane & 7) * 4;
+    const float* nz = a.noise + ((size_t)(g_noise * 32 + r) * 3 + t) * CAT_C + ct0 * TILE + 4 * h;
     static_for<WT>([&](auto J) {
       constexpr int j = decltype(J)::value;
-      static_for<4>([&](auto I) {
-        constexpr int i = decltype(I)::value;
-        gz_dst[j][i] = __builtin_nontemporal_load((const vf4*)(nz + j * TILE + (size_t)i * 8 * 3 * CAT_C));
+      static_for<4>([&](auto Q) {
+        constexpr int q = decltype(Q)::value;
+        gz_dst[j][q] = *(const vf4*)(nz + j * TILE + 8 * q);
       });
     });
   };
@@ -2463,24 +2461,13 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
         constexpr int c = decltype(C)::value;
         if constexpr (c < nch) mfma_chunk<T>(wf[j][c], af[s][c], acc);
       });
-      // the tile's noise: from load layout (pixel 8i + lane/8, classes 4 (lane%8) ..) to accumulator layout
-      float* patch = noise_patch[wave];
-      static_for<4>([&](auto I) {
-        constexpr int i = decltype(I)::value;
-        *(vf4*)(patch + (8 * i + (lane >> 3)) * HEAD_PATCH_PITCH + (lane & 7) * 4) = gz[s][j][i];
-      });
-      vf4 gq[4];
-      static_for<4>([&](auto Q) {
-        constexpr int q = decltype(Q)::value;
-        gq[q] = *(const vf4*)(patch + r * HEAD_PATCH_PITCH + 8 * q + 4 * h);
-      });
       // acc[4q + i]: class (ct0 + j)*32 + 8q + 4h + i of pixel r; classes ascend along (j, q, i), so a strict compare
       // keeps the lowest class of a tie
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int cb = (ct0 + j) * TILE + 8 * q + 4 * h;
         const float4 bv = bias4[j][q];
-        const vf4 gv = gq[q];
+        const vf4 gv = gz[s][j][q];
         const float v0 = (acc[4 * q + 0] + bv.x) + gv[0];
         const float v1 = (acc[4 * q + 1] + bv.y) + gv[1];
         const float v2 = (acc[4 * q + 2] + bv.z) + gv[2];
