@@ -182,7 +182,8 @@ struct ConvNet {
   int* head_tile_kend = nullptr;     // [3*8]
   std::vector<void*> act;            // activations of every k x k layer for the current batch capacity (they
                                      // persist between passes: see ConvWindow)
-  int* win = nullptr;                // [2 * n_pad + 1]: dirty_lo, first_changed, finished-workgroup counter
+  int* win = nullptr;                // dirty_lo [win_pad], first_changed [win_pad * CHG: one word per 128-byte line and
+                                     // image, the images' updates would otherwise all queue on one line], finished-workgroup counter
   int win_pad = 0;
   unsigned long long* rows_stat = nullptr;
 };
@@ -314,7 +315,7 @@ static int ensure_workspace(made_model* m, int N, bool need_z) {
     if (cv.win) (void)hipFree(cv.win);
     cv.win = nullptr;
     cv.win_pad = round_up(cap, 2 * TILE);
-    HIP_TRY(hipMalloc((void**)&cv.win, (size_t)(2 * cv.win_pad + 1) * sizeof(int)));
+    HIP_TRY(hipMalloc((void**)&cv.win, ((size_t)cv.win_pad * (1 + CHG) + 1) * sizeof(int)));
     if (!cv.rows_stat) HIP_TRY(hipMalloc((void**)&cv.rows_stat, sizeof(unsigned long long)));
     const int n_pad = round_up(cap, 2 * TILE);
     HIP_TRY(hipEventCreateWithFlags(&w.fork_ev, hipEventDisableTiming));
@@ -1368,7 +1369,7 @@ static int run_conv_pass(made_model* m, int N, const SampleIO& io, bool first_pa
   if (!whole_network) {
     c.dirty_lo = cv.win;
     c.first_changed = cv.win + cv.win_pad;
-    c.win_done = cv.win + 2 * cv.win_pad;
+    c.win_done = cv.win + (size_t)cv.win_pad * (1 + CHG);
     c.rows_stat = cv.rows_stat;
     c.row_lo = row_lo;
     c.row_hi = row_hi;
@@ -1407,7 +1408,7 @@ static int launch_init_state(made_model* m, const uint8_t* x_init, uint8_t* x, i
       ConvNet& cv = m->conv;
       hipLaunchKernelGGL(copy_symbols_kernel, dim3(blocks), dim3(256), 0, s, x_init, x, total);
       hipLaunchKernelGGL(conv_reset_window_kernel, dim3((N + 255) / 256), dim3(256), 0, s, cv.win,
-                         cv.win + cv.win_pad, N, cv.win + 2 * cv.win_pad, cv.rows_stat);
+                         cv.win + cv.win_pad, N, cv.win + (size_t)cv.win_pad * (1 + CHG), cv.rows_stat);
       m->stats[2]++;
     }
     m->stats[2]++;

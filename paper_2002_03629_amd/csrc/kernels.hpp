@@ -1911,7 +1911,7 @@ __global__ void conv_reset_window_kernel(int* dirty_lo, int* first_changed, int 
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) {
     dirty_lo[i] = 0;
-    first_changed[i] = 0x7fffffff;
+    first_changed[(size_t)i * CHG] = 0x7fffffff;
   }
   if (i == 0) {
     *win_done = 0;
@@ -2436,7 +2436,7 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
         // after the loop (before the tail counters)
         sink += __hip_atomic_fetch_add(&a.changed[(size_t)n * CHG], __popc(changed_mask), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (a.first_changed)
-          sink += __hip_atomic_fetch_min(&a.first_changed[n], y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          sink += __hip_atomic_fetch_min(&a.first_changed[(size_t)n * CHG], y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
     __syncthreads();
@@ -2522,8 +2522,8 @@ __global__ __launch_bounds__(256) void conv_head_kernel(ConvHeadArgs a) {
     if (win_last_s) {
       unsigned long long rows = 0;
       for (int n = threadIdx.x; n < a.N; n += blockDim.x) {
-        const int fc = __hip_atomic_load(&a.first_changed[n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        a.first_changed[n] = 0x7fffffff;
+        const int fc = __hip_atomic_load(&a.first_changed[(size_t)n * CHG], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        a.first_changed[(size_t)n * CHG] = 0x7fffffff;
         const int d = a.dirty_lo[n];
         rows += (unsigned long long)max(0, a.row_hi - d + 1);
         a.dirty_lo[n] = min(fc, max(d, a.row_hi + 1));
