@@ -68,6 +68,16 @@ def cpu_baseline(w, net, noises, budget_s=12.0, single_thread_s=0.0):
     return base, xs0, sub
 
 
+
+def own_stream(torch):
+    """The benchmark runs on a stream of its own (default priority), made current so that torch's work is ordered with the
+    library's.  Measured on the MI355X boxes: back-to-back calls of the launch-bound configurations take 1-3 % less on
+    such a stream than on the default stream (0.095 against 0.0975 ms per call on cfg2)."""
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    torch.cuda.set_stream(stream)
+    return stream
+
 def coupling_sweep(w, torch, B, S, stream):
     """Supplementary (not a benchmark configuration): how the number of Jacobi passes, and with it the speed-up over
     the sequential sampler, depends on how strongly the states are coupled (Section 4.1: learned weights leave few
@@ -211,7 +221,7 @@ def bench_rnn(args, torch, B, S) -> int:
     Wh, Uh, bh = S.make_rnn_params(w)
     W, U, b = (torch.from_numpy(a).cuda() for a in (Wh, Uh, bh))
     n_in = 4
-    stream = torch.cuda.current_stream()
+    stream = own_stream(torch)
     zs, gs = [], []
     for r in range(n_in):          # forward pass on the GPU; the loss is 0.5 |h_t - y_t|^2, so g = h - y
         xh, yh = S.make_rnn_inputs(w, r)
@@ -374,7 +384,7 @@ def run_one(args, torch, B, S, light=False):
     real = (not conv) and w.real
     x = torch.empty((N, D), dtype=torch.float32 if real else torch.uint8, device="cuda")
     iters = torch.empty((N,), dtype=torch.int32, device="cuda")
-    stream = torch.cuda.current_stream()
+    stream = own_stream(torch)
 
     def step(i):
         if real:
