@@ -317,6 +317,11 @@ def parse_args(argv=None):
                     help="batch size from which the 128 x 128 tile kernels are used (0 = library default)")
     ap.add_argument("--frozen-positions", type=int, default=-1, choices=[-1, 0, 1],
                     help="MADE_OPT_FROZEN_POSITIONS (-1 = library default)")
+    ap.add_argument("--call-graph", type=int, default=0, choices=[0, 1],
+                    help="MADE_OPT_CALL_GRAPH (library default 0): replay each call's launches as one HIP graph where the "
+                         "library supports it (Jacobi, Bernoulli MLP, per-layer launches, up to 256 samples); recorded "
+                         "before the warm-up.  cfg2: 0.101 ms per call whatever the host's launch cost, against "
+                         "0.095-0.098 / 0.105-0.110 ms launch by launch")
     ap.add_argument("--lazy-stop-test", type=int, default=-1, choices=[-1, 0, 1],
                     help="MADE_OPT_LAZY_STOP_TEST (-1 = library default)")
     ap.add_argument("--retire-split", type=int, default=0,
@@ -372,6 +377,8 @@ def run_one(args, torch, B, S, light=False):
         B.made_set_option(model, B.MADE_OPT_FROZEN_POSITIONS, args.frozen_positions)
     if args.lazy_stop_test >= 0 and not conv:
         B.made_set_option(model, B.MADE_OPT_LAZY_STOP_TEST, args.lazy_stop_test)
+    if not conv:
+        B.made_set_option(model, B.MADE_OPT_CALL_GRAPH, args.call_graph)
     n_layers = (w.n_conv if conv else len(net.hidden)) + 1
     nnz = B.made_layer_nnz(model, n_layers)
     n_slots = n_layers + 1                     # per-layer kernels + the persistent whole-call kernel
@@ -404,6 +411,16 @@ def run_one(args, torch, B, S, light=False):
         B.made_free(model)
         return {"pmc_probe": True, "copy_bytes_read": 64 << 20, "copy_bytes_written": 64 << 20}
 
+    # (recorded calls: the library runs the first call with given buffers launch by launch and records the second,
+    # for each half of its pass log, which alternates from call to call: four calls per noise buffer, all untimed)
+    call_graph = False
+    if (not conv) and (not real) and args.call_graph == 1:
+        step(0)
+        call_graph = B.made_last_stats(model)["tail_less_passes"] > 0     # (the calls the option covers)
+    if call_graph:
+        for r in range(n_noise):
+            for _ in range(4):
+                step(r)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -538,7 +555,7 @@ def run_one(args, torch, B, S, light=False):
                                 f"random degrees, fixed logistic noise") if real else
                                (f"{w.name}: MADE D={D} hidden={w.hidden} C={w.C} batch={N} Jacobi (Algorithm 1), "
                                 f"seeded N(0,1/fan_in) weights, random degrees, fixed U(0,1) noise"),
-                   "path": args.path},
+                   "path": args.path, **({"call_graph": 1} if call_graph else {})},
         "iters_mean": it_sum / args.steps,
         "iters_max": it_max,
         "passes_per_step": passes / args.steps,

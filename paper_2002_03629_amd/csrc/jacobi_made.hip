@@ -188,6 +188,29 @@ struct ConvNet {
   unsigned long long* rows_stat = nullptr;
 };
 
+// The launches of one jacobi_sample call (state set-up + `passes` passes) recorded as a HIP graph.  Kernel arguments
+// are baked into the graph, so it serves exactly the call it was recorded from: same buffers, batch, pass limit, stream
+// and half of the pass log.  The noise and the initial state may hold other values: every pass stops at the device-side
+// list of active samples, so passes recorded behind the one that empties the list do nothing, and a call that needs
+// more passes than were recorded gets them enqueued one by one behind the graph.
+struct CallGraph {
+  const void* noise = nullptr;
+  const void* x_init = nullptr;
+  void* x = nullptr;
+  int32_t* iters = nullptr;
+  hipStream_t stream = nullptr;
+  int N = 0, cap = 0, pin_base = 0;
+  bool flag_unconverged = false;
+  int needed = 0;                 // passes the last call with this key needed (0: none seen yet)
+  int passes = 0;                 // passes in the recorded graph
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+  std::vector<char> log_first;    // the host's pass log after the recording: the same after every replay
+  int64_t kernels = 0, tail_less = 0;
+  uint64_t used = 0;
+};
+constexpr int CALL_GRAPHS_MAX = 128;
+
 struct made_model {
   int arch = 0;                               // 0 masked MLP, 1 masked convolutional network
   bool poisoned = false;                      // a call gave up waiting for the device with its kernels still queued:
@@ -238,6 +261,9 @@ struct made_model {
                                               // (measured slower, see header)
   int frozen_positions = 1;                   // made_set_option(MADE_OPT_FROZEN_POSITIONS): 256-class output kernel skips the
                                               // positions below the first one that changed in the pass before
+  int call_graph = 0;                         // made_set_option(MADE_OPT_CALL_GRAPH): replay a call's launches as one HIP graph
+  std::vector<CallGraph> graphs;              // at most CALL_GRAPHS_MAX of them, least recently used goes first
+  uint64_t graph_clock = 0;
   int lazy_retire = 1;                        // made_set_option(MADE_OPT_LAZY_STOP_TEST): 1 = Jacobi on lists of up to 256 samples
                                               // derives a pass's list in its first kernel instead of in the previous one's tail
   int use_xcd = 1;                            // made_set_option(MADE_OPT_XCD_RESIDENT): 0 never, 1 where it pays, 2 whenever possible
@@ -261,6 +287,18 @@ static uint16_t host_f32_to_bf16(float f) {
 
 static size_t elem_size(const made_model* m) { return m->dtype == MADE_BF16 ? 2 : 4; }
 static int chunk_elems(const made_model* m) { return m->dtype == MADE_BF16 ? 64 : 32; }
+
+// Recorded calls point into the workspace and depend on the options: gone with either.  (A graph may still be
+// executing: wait for the device first.)
+static void drop_call_graphs(made_model* m) {
+  if (m->graphs.empty()) return;
+  (void)hipDeviceSynchronize();
+  for (CallGraph& g : m->graphs) {
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    if (g.graph) (void)hipGraphDestroy(g.graph);
+  }
+  m->graphs.clear();
+}
 
 static void free_workspace(Workspace& w) {
   if (w.enc) (void)hipFree(w.enc);
@@ -302,6 +340,7 @@ static int ensure_workspace(made_model* m, int N, bool need_z) {
   if (m->arch == 1) {
     if (N <= w.N_cap) return MADE_OK;
     const int cap = std::max(N, w.N_cap);
+    drop_call_graphs(m);
     free_workspace(w);
     ConvNet& cv = m->conv;
     for (void* p : cv.act)
@@ -331,6 +370,7 @@ static int ensure_workspace(made_model* m, int N, bool need_z) {
   if (N <= w.N_cap && (!need_z || w.zbuf)) return MADE_OK;
   const int cap = std::max(N, w.N_cap);
   const bool had_z = w.zbuf != nullptr;
+  drop_call_graphs(m);
   free_workspace(w);
   const int n_pad = round_up(cap, 2 * TILE);   // the 64-sample kernels read list entries of a whole tile pair
   const size_t es = elem_size(m);
@@ -378,6 +418,7 @@ static int ensure_chain(made_model* m, size_t i, int rows_cap, int pin_len) {
     HIP_TRY(hipDeviceSynchronize());
     w.pending = false;
   }
+  drop_call_graphs(m);
   free_chain(c);
   rows_cap = round_up(rows_cap, 2 * TILE);
   HIP_TRY(hipStreamCreateWithFlags(&c.own_stream, hipStreamNonBlocking));
@@ -401,6 +442,7 @@ static int ensure_chain(made_model* m, size_t i, int rows_cap, int pin_len) {
 extern "C" int made_free(made_model* m) {
   if (!m) return MADE_OK;
   if (m->ws.pending) (void)hipDeviceSynchronize();
+  drop_call_graphs(m);
   for (Layer& l : m->layers) {
     if (l.W) (void)hipFree(l.W);
     if (l.bias) (void)hipFree(l.bias);
@@ -454,6 +496,12 @@ extern "C" int made_last_profile(const made_model* m, double* ms, int64_t* launc
 
 extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
   if (!m) return fail(MADE_ERR_ARG, "made_set_option: model is NULL");
+  drop_call_graphs(m);   // (recorded calls were shaped by the options in force)
+  if (option == MADE_OPT_CALL_GRAPH) {
+    if (value != 0 && value != 1) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_CALL_GRAPH=%d must be 0 or 1", value);
+    m->call_graph = value;
+    return MADE_OK;
+  }
   if (option == MADE_OPT_PERSISTENT) {
     m->use_persistent = value != 0;
     return MADE_OK;
@@ -1712,7 +1760,7 @@ static int fill_partial_sums(made_model* m, const RowSet& rs, const Block& blk, 
 
 // Enqueue the next pass of chain c's current block on the chain's stream.
 static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* noise, uint8_t* x,
-                        bool flag_unconverged) {
+                        bool flag_unconverged, bool force_tail = false) {
   Workspace& w = m->ws;
   hipStream_t s = c.stream;
   if (!c.block_started) {
@@ -1742,7 +1790,7 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
   // Tail-less stop test (see DeriveArgs): pass k only records which rows changed; pass k + 1's first kernel derives
   // its list from that, reports pass k's result and counts it.  The last allowed pass keeps the ordinary tail (no
   // pass follows it), and so does everything the conditions below exclude.
-  const bool lazy_out = c.lazy && k < blk.cap;
+  const bool lazy_out = c.lazy && k < blk.cap && !force_tail;   // (force_tail: the last pass of a recorded call)
   const bool derive_in = c.lazy && k > 1;
   DeriveArgs dv;
   memset(&dv, 0, sizeof dv);
@@ -1877,6 +1925,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
   }
   w.call_iters = iters_out ? iters_out : w.iters;
   for (int i = 0; i < n_chains; ++i) w.chains[i].h_pin[w.chains[i].pin_base + w.chains[i].pin_half - 1] = 0;
+  CallGraph* cg = nullptr;   // the recorded form of this call, if it has one
   if (n_chains == 1 && m->arch == 0) {
     // one chain on the caller's stream: the kernel that sets up the iterate also resets the chain's list and counters
     Chain& c = w.chains[0];
@@ -1898,9 +1947,87 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
              c.count <= DERIVE_MAX_ROWS && c.count < std::min(m->mid_batch, m->big_batch) && c.count < m->retire_split;
     r.lazy_masks = c.lazy ? w.lazy_masks : nullptr;
     r.frozen_words = c.done_ctr + FROZEN_WORDS;
-    TRY(launch_init_state(m, x_init, x, N, s, &r));
-    c.block_started = true;
-    c.iters_cleared = true;
+    // A call of the tail-less kind is short (cfg2: 19 launches of ~5 us each) and bound by what the host pays per
+    // launch: on request it is recorded once and replayed as one graph launch (see CallGraph).  The first call with
+    // a key runs launch by launch and tells how many passes to record.
+    if (m->call_graph && c.lazy && !m->profiling && s != nullptr) {   // (the null stream cannot be captured)
+      for (CallGraph& g : m->graphs)
+        if (g.noise == noise && g.x_init == x_init && g.x == x && g.iters == w.call_iters && g.stream == s && g.N == N &&
+            g.cap == blocks[0].cap && g.pin_base == c.pin_base && g.flag_unconverged == flag_unconverged)
+          cg = &g;
+      if (!cg) {
+        if ((int)m->graphs.size() >= CALL_GRAPHS_MAX) {
+          size_t oldest = 0;
+          for (size_t i = 1; i < m->graphs.size(); ++i)
+            if (m->graphs[i].used < m->graphs[oldest].used) oldest = i;
+          CallGraph& g = m->graphs[oldest];
+          if (g.exec) {
+            HIP_TRY(hipStreamSynchronize(g.stream));   // (it may still be executing)
+            (void)hipGraphExecDestroy(g.exec);
+            (void)hipGraphDestroy(g.graph);
+          }
+          m->graphs.erase(m->graphs.begin() + (long)oldest);
+        }
+        m->graphs.emplace_back();
+        cg = &m->graphs.back();
+        cg->noise = noise; cg->x_init = x_init; cg->x = x; cg->iters = w.call_iters; cg->stream = s; cg->N = N;
+        cg->cap = blocks[0].cap; cg->pin_base = c.pin_base; cg->flag_unconverged = flag_unconverged;
+      }
+      cg->used = ++m->graph_clock;
+      if (cg->exec && cg->needed > cg->passes && cg->passes < cg->cap) {   // the last call ran out of recorded passes
+        HIP_TRY(hipStreamSynchronize(s));
+        (void)hipGraphExecDestroy(cg->exec);
+        (void)hipGraphDestroy(cg->graph);
+        cg->exec = nullptr;
+        cg->graph = nullptr;
+      }
+    }
+    if (cg && cg->exec) {
+      // replay: the host's bookkeeping of the recorded launches, then the launches themselves
+      for (int slot = 0; slot < cg->passes; ++slot) c.h_pin[c.pin_base + slot] = -1;
+      c.log_first = cg->log_first;
+      c.k_enq = cg->passes;
+      m->stats[2] += cg->kernels;
+      m->stats[5] += cg->tail_less;
+      HIP_TRY(hipGraphLaunch(cg->exec, s));
+      c.block_started = true;
+      c.iters_cleared = true;
+      c.lazy = false;   // (the graph's last pass kept the tail: passes behind it are ordinary ones)
+    } else if (cg && cg->needed > 0) {
+      const int n_rec = std::min(cg->cap, std::max(2, cg->needed));
+      const int64_t kernels0 = m->stats[2], tail_less0 = m->stats[5];
+      HIP_TRY(hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+      int rc = launch_init_state(m, x_init, x, N, s, &r);
+      c.block_started = true;
+      c.iters_cleared = true;
+      for (int k = 1; rc == MADE_OK && k <= n_rec; ++k)
+        rc = enqueue_pass(m, c, blocks[0], noise, x, flag_unconverged, k == n_rec);
+      hipGraph_t graph = nullptr;
+      const hipError_t end = hipStreamEndCapture(s, &graph);
+      if (rc != MADE_OK) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return rc;
+      }
+      HIP_TRY(end);
+      hipGraphExec_t exec = nullptr;
+      const hipError_t inst = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+      if (inst != hipSuccess) {
+        (void)hipGraphDestroy(graph);
+        HIP_TRY(inst);
+      }
+      cg->graph = graph;
+      cg->exec = exec;
+      cg->passes = n_rec;
+      cg->log_first = c.log_first;
+      cg->kernels = m->stats[2] - kernels0;
+      cg->tail_less = m->stats[5] - tail_less0;
+      HIP_TRY(hipGraphLaunch(cg->exec, s));
+      c.lazy = false;
+    } else {
+      TRY(launch_init_state(m, x_init, x, N, s, &r));
+      c.block_started = true;
+      c.iters_cleared = true;
+    }
   } else {
     TRY(launch_init_state(m, x_init, x, N, s));
     HIP_TRY(hipMemsetAsync(w.flags, 0, sizeof(int), s));
@@ -1942,6 +2069,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
         if (c.k_enq == blk.cap) block_done = true;   // nothing more may be enqueued for this block
       }
       if (block_done) {
+        if (cg) cg->needed = c.k_conf < c.k_enq && c.k_enq == blk.cap ? blk.cap : c.k_conf;
         c.block++;
         c.k_enq = c.k_conf = 0;
         c.block_started = false;
