@@ -320,8 +320,8 @@ def parse_args(argv=None):
     ap.add_argument("--call-graph", type=int, default=0, choices=[0, 1],
                     help="MADE_OPT_CALL_GRAPH (library default 0): replay each call's launches as one HIP graph where the "
                          "library supports it (Jacobi, Bernoulli MLP, per-layer launches, up to 256 samples); recorded "
-                         "before the warm-up.  cfg2: 0.101 ms per call whatever the host's launch cost, against "
-                         "0.095-0.098 / 0.105-0.110 ms launch by launch")
+                         "before the warm-up.  cfg2: 0.098 ms per call whatever the host's launch cost, against "
+                         "0.091 / 0.104-0.108 ms launch by launch")
     ap.add_argument("--lazy-stop-test", type=int, default=-1, choices=[-1, 0, 1],
                     help="MADE_OPT_LAZY_STOP_TEST (-1 = library default)")
     ap.add_argument("--retire-split", type=int, default=0,

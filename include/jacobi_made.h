@@ -279,6 +279,10 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   pass's first kernel derives that pass's list of active samples from the record -- in the memory round trip in
  *   which it would otherwise read the list -- instead of the previous pass's last workgroup compacting it in a tail
  *   of three dependent round trips.  Same results and pass counts; 0 keeps the tail.
+ *   MADE_OPT_ZERO_START (default 1; 0 or 1): jacobi_sample of a Bernoulli model with x_init = NULL (one chain, per-layer
+ *   launches): the first hidden layer of the first pass multiplies an all-zero input, so the kernel that sets the call up
+ *   writes its activations, ReLU(bias), itself, and the first pass starts at the second hidden layer: one launch less per
+ *   call, same results bit for bit.  0 = launch the layer.
  *   MADE_OPT_CALL_GRAPH (default 0; 0 or 1): calls that MADE_OPT_LAZY_STOP_TEST covers are short and bound by what the
  *   host pays per kernel launch.  With 1, the second call with the same arguments (noise, x_init, x_out and iters_out
  *   pointers, N, max_iters, flag, a stream other than the null stream; the buffers' contents may differ) records the
@@ -341,7 +345,7 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
 enum { MADE_OPT_PERSISTENT = 1, MADE_OPT_FUSED_CATEGORICAL = 2, MADE_OPT_CHAINS = 3, MADE_OPT_BIG_TILE_BATCH = 4,
        MADE_OPT_CONV_ROWS = 5, MADE_OPT_PREFIX_CACHE = 6, MADE_OPT_RESIDENT = 7, MADE_OPT_RETIRE_SPLIT = 8,
        MADE_OPT_MID_TILE_BATCH = 9, MADE_OPT_PARTIAL_SUM_BATCH = 10, MADE_OPT_XCD_RESIDENT = 11,
-       MADE_OPT_LAZY_STOP_TEST = 12, MADE_OPT_FROZEN_POSITIONS = 13, MADE_OPT_CALL_GRAPH = 14 };
+       MADE_OPT_LAZY_STOP_TEST = 12, MADE_OPT_FROZEN_POSITIONS = 13, MADE_OPT_CALL_GRAPH = 14, MADE_OPT_ZERO_START = 15 };
 int made_set_option(made_model* m, int32_t option, int32_t value);
 
 /*

@@ -285,6 +285,7 @@ MADE_OPT_PARTIAL_SUM_BATCH = 10
 MADE_OPT_XCD_RESIDENT = 11
 MADE_OPT_LAZY_STOP_TEST = 12
 MADE_OPT_CALL_GRAPH = 14
+MADE_OPT_ZERO_START = 15
 MADE_OPT_FROZEN_POSITIONS = 13
 
 

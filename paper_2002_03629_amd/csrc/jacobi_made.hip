@@ -127,6 +127,7 @@ struct Chain {
   bool block_started = false, finished = false, iters_cleared = false;
   bool lazy = false;                 // this call's passes use the tail-less stop test (see DeriveArgs)
   bool frozen = false;               // this call's passes skip the output positions that cannot change (CatArgs::t_first_ptr)
+  bool first_hidden_ready = false;   // the set-up kernel wrote the first hidden layer of the call's first pass (zero start)
   std::vector<char> log_first;       // per enqueued pass: was it the first of its block
 };
 
@@ -261,6 +262,7 @@ struct made_model {
                                               // (measured slower, see header)
   int frozen_positions = 1;                   // made_set_option(MADE_OPT_FROZEN_POSITIONS): 256-class output kernel skips the
                                               // positions below the first one that changed in the pass before
+  int zero_start_fill = 1;                    // made_set_option(MADE_OPT_ZERO_START): 1 = the set-up kernel writes the first hidden layer of a call started from zeros
   int call_graph = 0;                         // made_set_option(MADE_OPT_CALL_GRAPH): replay a call's launches as one HIP graph
   std::vector<CallGraph> graphs;              // at most CALL_GRAPHS_MAX of them, least recently used goes first
   uint64_t graph_clock = 0;
@@ -497,6 +499,11 @@ extern "C" int made_last_profile(const made_model* m, double* ms, int64_t* launc
 extern "C" int made_set_option(made_model* m, int32_t option, int32_t value) {
   if (!m) return fail(MADE_ERR_ARG, "made_set_option: model is NULL");
   drop_call_graphs(m);   // (recorded calls were shaped by the options in force)
+  if (option == MADE_OPT_ZERO_START) {
+    if (value != 0 && value != 1) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_ZERO_START=%d must be 0 or 1", value);
+    m->zero_start_fill = value;
+    return MADE_OK;
+  }
   if (option == MADE_OPT_CALL_GRAPH) {
     if (value != 0 && value != 1) return fail(MADE_ERR_ARG, "made_set_option: MADE_OPT_CALL_GRAPH=%d must be 0 or 1", value);
     m->call_graph = value;
@@ -1144,11 +1151,11 @@ struct PartialSums {
 
 static int run_hidden(made_model* m, const RowSet& rs, const int* unit_limit, int in_limit0, hipStream_t s,
                       const int* unit_first = nullptr, bool by_pos = false, const ActBuffers* buf = nullptr,
-                      const PartialSums* ps = nullptr, const DeriveArgs* derive = nullptr) {
+                      const PartialSums* ps = nullptr, const DeriveArgs* derive = nullptr, int first_layer = 0) {
   const int row_tiles = (rs.n_rows + TILE - 1) / TILE;
   const int kc = chunk_elems(m);
   int in_limit = in_limit0;
-  for (int l = 0; l < m->L; ++l) {
+  for (int l = first_layer; l < m->L; ++l) {   // (first_layer = 1: the call's set-up kernel has written layer 0's activations)
     const Layer& ly = m->layers[l];
     LayerArgs a = base_args(m, l, l == 0 ? (buf ? buf->enc : m->ws.enc) : (buf ? buf->act[l - 1] : m->ws.act[l - 1]), rs);
     a.out = buf ? buf->act[l] : m->ws.act[l];
@@ -1865,7 +1872,7 @@ static int enqueue_pass(made_model* m, Chain& c, const Block& blk, const float* 
     if (use_partial && k == 2) TRY(fill_partial_sums(m, rs, blk, s));
     TRY(run_hidden(m, rs, blk.limited ? blk.hidden_limit.data() : nullptr, blk.in_limit, s,
                    cached ? blk.hidden_frozen.data() : nullptr, by_pos, nullptr, use_partial ? &ps : nullptr,
-                   derive_in ? &dv : nullptr));
+                   derive_in ? &dv : nullptr, (k == 1 && c.block == 0 && c.first_hidden_ready) ? 1 : 0));
     // a long list is retired by a kernel of its own, spread over the chip, instead of by the output kernel's
     // last workgroup
     const RetireArgs retire = io.retire;
@@ -1920,6 +1927,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
     c.bound = c.count;
     c.block_started = c.finished = c.iters_cleared = false;
     c.lazy = false;
+    c.first_hidden_ready = false;
     c.log_first.clear();
     c.stream = n_chains == 1 ? s : c.own_stream;   // a single chain needs no fork and join
   }
@@ -1930,6 +1938,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
     // one chain on the caller's stream: the kernel that sets up the iterate also resets the chain's list and counters
     Chain& c = w.chains[0];
     CallReset r;
+    memset(&r, 0, sizeof r);
     r.enabled = 1;
     r.rows = c.rows[0];
     r.rows_other = c.rows[1];
@@ -1947,6 +1956,17 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
              c.count <= DERIVE_MAX_ROWS && c.count < std::min(m->mid_batch, m->big_batch) && c.count < m->retire_split;
     r.lazy_masks = c.lazy ? w.lazy_masks : nullptr;
     r.frozen_words = c.done_ctr + FROZEN_WORDS;
+    // Algorithm 1 of a Bernoulli MLP started from zeros: the first pass's first hidden layer multiplies a zero input,
+    // so the set-up kernel writes its activations (ReLU of the bias, the same for every sample) and the pass starts at
+    // the second hidden layer: one launch less per call.
+    if (m->zero_start_fill && !x_init && m->C == 1 && !m->real && !m->onehot && blocks.size() == 1 && !blocks[0].limited &&
+        blocks[0].stop_test) {
+      r.h0_bias = m->layers[0].bias;
+      r.h0_out = w.act[0];
+      r.h0_chunks = m->layers[1].k_chunks;
+      r.h0_units = m->layers[0].n_tiles * TILE;
+      c.first_hidden_ready = true;
+    }
     // A call of the tail-less kind is short (cfg2: 19 launches of ~5 us each) and bound by what the host pays per
     // launch: on request it is recorded once and replayed as one graph launch (see CallGraph).  The first call with
     // a key runs launch by launch and tells how many passes to record.

@@ -2619,6 +2619,12 @@ struct CallReset {
   int* flags;
   unsigned* lazy_masks;  // [3 * DERIVE_WORDS] (see DeriveArgs), or NULL
   int* frozen_words;     // [4] first position to evaluate (two, alternating by pass) and lowest changed position (two), or NULL
+  // Bernoulli model started from zeros (init_state_kernel): the first hidden layer of the first pass multiplies a zero
+  // input, so its activations are relu(bias) for every sample: written here (h0_out != NULL: fragment-major buffer of
+  // h0_chunks chunks, h0_units units, a multiple of 4), and the first pass starts at the second hidden layer.
+  const float* h0_bias;
+  void* h0_out;
+  int h0_chunks, h0_units;
 };
 
 __device__ __forceinline__ void call_reset(const CallReset& r) {
@@ -2655,6 +2661,23 @@ __global__ void init_state_kernel(const uint8_t* x_init, uint8_t* x, T* enc, int
     if (x) x[i] = v;
     const float e = (C == 1) ? (float)v : ((float)v - 128.0f) * (1.0f / 128.0f);
     enc[frag_offset<T>(n, t, enc_chunks)] = Elem<T>::from_f32(e);
+  }
+  if (reset.h0_out) {
+    // (what the layer kernel's epilogue computes from an all-zero product: 0 + bias, ReLU, rounded to T)
+    const int quads = reset.h0_units / 4;
+    const size_t items = (size_t)N * quads;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < items; i += (size_t)gridDim.x * blockDim.x) {
+      const int n = (int)(i / quads), j = 4 * (int)(i % quads);
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = fmaxf(0.f + reset.h0_bias[j + e], 0.f);
+      T* dst = (T*)reset.h0_out + frag_offset<T>(n, j, reset.h0_chunks);   // (4 consecutive units are contiguous)
+      if constexpr (sizeof(T) == 2)
+        *(uint2*)dst = make_uint2((uint32_t)Elem<T>::from_f32(v[0]) | ((uint32_t)Elem<T>::from_f32(v[1]) << 16),
+                                  (uint32_t)Elem<T>::from_f32(v[2]) | ((uint32_t)Elem<T>::from_f32(v[3]) << 16));
+      else
+        *(uint4*)dst = make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
+    }
   }
 }
 

@@ -415,6 +415,49 @@ def test_tail_less_stop_test_serves_the_call_and_changes_nothing():
                     assert a[2] in (0, B.MADE_ERR_NOT_CONVERGED)
 
 
+def test_zero_start_saves_a_launch_and_changes_nothing():
+    """MADE_OPT_ZERO_START: started from zeros, the first pass's first hidden layer is ReLU(bias) for every sample and
+    the set-up kernel writes it.  Symbols, pass counts and statistics are those of the launched layer, bit for bit
+    (with and without bias, one and several hidden layers, every tile kernel), with one kernel less; a call with an
+    x_init launches the layer as before."""
+    import gpu_util
+    if gpu_util.CHAINS != 1 or gpu_util.PERSISTENT or gpu_util.RESIDENT or gpu_util.XCD != 0:
+        pytest.skip("runs once, on one chain of per-layer launches")
+    cases = [("small_f32", None, True), ("small_bf16", None, True), ("mid_bf16", None, False), ("cfg1", None, True),
+             ("cfg2", None, True), ("small_bf16", 96, True)]
+    for name, big, with_bias in cases:
+        w = S.workload(name)
+        net = S.make_network(w, with_bias=with_bias)
+        noise = S.make_noise(w)
+        x0 = _symbols(w, np.random.default_rng(5), w.N)
+        kw = {} if big is None else {"big_tile_batch": big, "mid_tile_batch": big}
+        with GpuModel(net, **kw) as g:
+            res = {}
+            for fill in (1, 0):
+                B.made_set_option(g.h, B.MADE_OPT_ZERO_START, fill)
+                x, it = g.jacobi(noise)
+                torch.cuda.synchronize()
+                st = g.stats()
+                xl, itl = g.jacobi(noise, max_iters=w.D)
+                xi, iti = g.jacobi(noise, x_init=x0)
+                torch.cuda.synchronize()
+                sti = g.stats()
+                # a call of exactly one pass (nothing speculative): its kernel count is fixed
+                x1 = torch.empty((w.N, w.D), dtype=torch.uint8, device="cuda")
+                try:
+                    B.jacobi_sample(g.h, dev(noise), w.N, None, 1, x1, None)
+                except B.MadeError as e:
+                    assert e.code == B.MADE_ERR_NOT_CONVERGED
+                torch.cuda.synchronize()
+                res[fill] = (x, it, st, xl, itl, xi, iti, sti, x1.cpu().numpy(), g.stats()["kernels"])
+            a, b = res[1], res[0]
+            for i in (0, 1, 3, 4, 5, 6, 8):
+                assert (a[i] == b[i]).all(), (name, big, i)
+            assert a[2]["passes"] == b[2]["passes"] and a[2]["sample_passes"] == b[2]["sample_passes"]
+            assert a[7]["passes"] == b[7]["passes"] and a[7]["sample_passes"] == b[7]["sample_passes"]
+            assert a[9] == b[9] - 1, (name, big, a[9], b[9])
+
+
 @pytest.mark.parametrize("name", ["small_cat", "small_cat_onehot", "mid_cat_onehot"])
 def test_frozen_positions_change_nothing_but_the_work(name):
     """MADE_OPT_FROZEN_POSITIONS: a pass of the 256-class output kernel skips the positions below the first one the
