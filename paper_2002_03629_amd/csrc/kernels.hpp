@@ -2653,31 +2653,33 @@ __device__ __forceinline__ void call_reset(const CallReset& r) {
 
 template <typename T>
 __global__ void init_state_kernel(const uint8_t* x_init, uint8_t* x, T* enc, int enc_chunks, int N, int D, int C, CallReset reset) {
+  const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
+  // (zero start: the bias of this thread's first four units is requested before anything else, so that its way from
+  // memory overlaps with the rest of the kernel)
+  const int quads = reset.h0_out ? reset.h0_units / 4 : 1;
+  const size_t items = reset.h0_out ? (size_t)N * quads : 0;
+  float4 b_first = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (tid < items) b_first = *(const float4*)(reset.h0_bias + 4 * (int)(tid % quads));
   call_reset(reset);
   const size_t total = (size_t)N * D;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+  for (size_t i = tid; i < total; i += stride) {
     const int n = (int)(i / D), t = (int)(i % D);
     const uint8_t v = x_init ? x_init[i] : 0;
     if (x) x[i] = v;
     const float e = (C == 1) ? (float)v : ((float)v - 128.0f) * (1.0f / 128.0f);
     enc[frag_offset<T>(n, t, enc_chunks)] = Elem<T>::from_f32(e);
   }
-  if (reset.h0_out) {
-    // (what the layer kernel's epilogue computes from an all-zero product: 0 + bias, ReLU, rounded to T)
-    const int quads = reset.h0_units / 4;
-    const size_t items = (size_t)N * quads;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < items; i += (size_t)gridDim.x * blockDim.x) {
-      const int n = (int)(i / quads), j = 4 * (int)(i % quads);
-      float v[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = fmaxf(0.f + reset.h0_bias[j + e], 0.f);
-      T* dst = (T*)reset.h0_out + frag_offset<T>(n, j, reset.h0_chunks);   // (4 consecutive units are contiguous)
-      if constexpr (sizeof(T) == 2)
-        *(uint2*)dst = make_uint2((uint32_t)Elem<T>::from_f32(v[0]) | ((uint32_t)Elem<T>::from_f32(v[1]) << 16),
-                                  (uint32_t)Elem<T>::from_f32(v[2]) | ((uint32_t)Elem<T>::from_f32(v[3]) << 16));
-      else
-        *(uint4*)dst = make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
-    }
+  // (what the layer kernel's epilogue computes from an all-zero product: 0 + bias, ReLU, rounded to T)
+  for (size_t i = tid; i < items; i += stride) {
+    const int n = (int)(i / quads), j = 4 * (int)(i % quads);
+    const float4 b = i == tid ? b_first : *(const float4*)(reset.h0_bias + j);
+    const float v[4] = {fmaxf(0.f + b.x, 0.f), fmaxf(0.f + b.y, 0.f), fmaxf(0.f + b.z, 0.f), fmaxf(0.f + b.w, 0.f)};
+    T* dst = (T*)reset.h0_out + frag_offset<T>(n, j, reset.h0_chunks);   // (4 consecutive units are contiguous)
+    if constexpr (sizeof(T) == 2)
+      *(uint2*)dst = make_uint2((uint32_t)Elem<T>::from_f32(v[0]) | ((uint32_t)Elem<T>::from_f32(v[1]) << 16),
+                                (uint32_t)Elem<T>::from_f32(v[2]) | ((uint32_t)Elem<T>::from_f32(v[3]) << 16));
+    else
+      *(uint4*)dst = make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3]));
   }
 }
 
