@@ -1969,7 +1969,7 @@ static int run_chains(made_model* m, const std::vector<Block>& blocks, const flo
       r.h0_units = m->layers[0].n_tiles * TILE;
       c.first_hidden_ready = true;
     }
-    // A call of the tail-less kind is short (cfg2: 19 launches of ~5 us each) and bound by what the host pays per
+    // A call of the tail-less kind is short (cfg2: 18 launches of ~5 us each) and bound by what the host pays per
     // launch: on request it is recorded once and replayed as one graph launch (see CallGraph).  The first call with
     // a key runs launch by launch and tells how many passes to record.
     if (m->call_graph && c.lazy && !m->profiling && s != nullptr) {   // (the null stream cannot be captured)
