@@ -322,6 +322,9 @@ def parse_args(argv=None):
                          "library supports it (Jacobi, Bernoulli MLP, per-layer launches, up to 256 samples); recorded "
                          "before the warm-up.  cfg2: 0.098 ms per call whatever the host's launch cost, against "
                          "0.091 / 0.104-0.108 ms launch by launch")
+    ap.add_argument("--zero-start", type=int, default=1, choices=[0, 1],
+                    help="MADE_OPT_ZERO_START (library default 1): a Bernoulli MLP's call started from zeros gets the first "
+                         "hidden layer of its first pass (ReLU of the bias) from the set-up kernel; 0 launches the layer")
     ap.add_argument("--lazy-stop-test", type=int, default=-1, choices=[-1, 0, 1],
                     help="MADE_OPT_LAZY_STOP_TEST (-1 = library default)")
     ap.add_argument("--retire-split", type=int, default=0,
@@ -379,6 +382,7 @@ def run_one(args, torch, B, S, light=False):
         B.made_set_option(model, B.MADE_OPT_LAZY_STOP_TEST, args.lazy_stop_test)
     if not conv:
         B.made_set_option(model, B.MADE_OPT_CALL_GRAPH, args.call_graph)
+        B.made_set_option(model, B.MADE_OPT_ZERO_START, args.zero_start)
     n_layers = (w.n_conv if conv else len(net.hidden)) + 1
     nnz = B.made_layer_nnz(model, n_layers)
     n_slots = n_layers + 1                     # per-layer kernels + the persistent whole-call kernel
@@ -555,7 +559,8 @@ def run_one(args, torch, B, S, light=False):
                                 f"random degrees, fixed logistic noise") if real else
                                (f"{w.name}: MADE D={D} hidden={w.hidden} C={w.C} batch={N} Jacobi (Algorithm 1), "
                                 f"seeded N(0,1/fan_in) weights, random degrees, fixed U(0,1) noise"),
-                   "path": args.path, **({"call_graph": 1} if call_graph else {})},
+                   "path": args.path, **({"call_graph": 1} if call_graph else {}),
+                   **({"zero_start": args.zero_start} if (not conv and not real and w.C == 1) else {})},
         "iters_mean": it_sum / args.steps,
         "iters_max": it_max,
         "passes_per_step": passes / args.steps,
