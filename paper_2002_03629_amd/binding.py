@@ -220,6 +220,25 @@ def jacobi_sample(model: int, noise, N: int, x_init, max_iters: int, x_out, iter
                                _ptr(x_out, torch.uint8), _ptr(iters_out, torch.int32), _stream(stream)))
 
 
+class PreparedJacobi:
+    """jacobi_sample with its arguments marshalled once, for loops that call it again and again on the same buffers
+    (a call of cfg2's size takes ~90 us, of which checking and converting eight arguments costs ~2.5): calling the
+    object runs the call.  The tensors are kept alive; their contents may change between calls."""
+
+    def __init__(self, model: int, noise, N: int, x_init, max_iters: int, x_out, iters_out=None, stream=None):
+        import torch
+        self._keep = (noise, x_init, x_out, iters_out, stream)
+        self._fn = lib().jacobi_sample
+        self._args = (C.c_void_p(model), C.c_void_p(_ptr(noise, torch.float32)), C.c_int32(N),
+                      C.c_void_p(_ptr(x_init, torch.uint8)), C.c_int32(max_iters), C.c_void_p(_ptr(x_out, torch.uint8)),
+                      C.c_void_p(_ptr(iters_out, torch.int32)), C.c_void_p(_stream(stream)))
+
+    def __call__(self) -> None:
+        code = self._fn(*self._args)
+        if code != MADE_OK:
+            raise MadeError(code, made_last_error())
+
+
 def gs_jacobi_sample(model: int, noise, N: int, x_init, block: int, x_out, iters_out=None, stream=None) -> None:
     import torch
     _check(lib().gs_jacobi_sample(model, _ptr(noise, torch.float32), N, _ptr(x_init, torch.uint8), block,

@@ -84,3 +84,32 @@ def test_recorded_calls_replay_to_the_results_of_single_launches(name):
             if limit == 0:   # (under a pass limit the launch-by-launch call's last pass has a tail as well)
                 assert replays >= 8
         B.made_set_option(g.h, B.MADE_OPT_CALL_GRAPH, 0)
+
+
+def test_a_prepared_call_is_the_plain_call():
+    """binding.PreparedJacobi marshals the arguments once; every call of the object is jacobi_sample on them."""
+    w = S.workload("mid_bf16")
+    net = S.make_network(w, with_bias=True)
+    stream = torch.cuda.Stream()
+    with GpuModel(net) as g:
+        noise_d = torch.from_numpy(S.make_noise(w)).cuda()
+        x_a = torch.empty((w.N, w.D), dtype=torch.uint8, device="cuda")
+        it_a = torch.empty((w.N,), dtype=torch.int32, device="cuda")
+        x_b, it_b = torch.empty_like(x_a), torch.empty_like(it_a)
+        torch.cuda.synchronize()
+        B.jacobi_sample(g.h, noise_d, w.N, None, 0, x_a, it_a, stream=stream)
+        call = B.PreparedJacobi(g.h, noise_d, w.N, None, 0, x_b, it_b, stream=stream)
+        for rep in range(3):
+            x_b.fill_(9)
+            torch.cuda.synchronize()
+            call()
+            stream.synchronize()
+            assert (x_a == x_b).all() and (it_a == it_b).all(), rep
+            noise_d.copy_(torch.from_numpy(S.make_noise(w, rep=rep + 1)))     # (contents may change between calls)
+            torch.cuda.synchronize()
+            B.jacobi_sample(g.h, noise_d, w.N, None, 0, x_a, it_a, stream=stream)
+            stream.synchronize()
+        limited = B.PreparedJacobi(g.h, noise_d, w.N, None, 1, x_b, it_b, stream=stream)
+        with pytest.raises(B.MadeError) as e:
+            limited()
+        assert e.value.code == B.MADE_ERR_NOT_CONVERGED
