@@ -289,7 +289,9 @@ int made_last_profile(const made_model* m, double* ms, int64_t* launches, int32_
  *   pointers, N, max_iters, flag, a stream other than the null stream; the buffers' contents may differ) records the
  *   call's launches -- state set-up plus as many passes as the call before needed -- as a HIP graph, and that call and
  *   the later ones replay it with one launch; a call that needs more passes gets them enqueued behind the graph, and the
- *   next one records again.  Same results and pass counts.  The model keeps the 128 most recently used recordings; a
+ *   next one records again.  (The halves of the library's pass log alternate from call to call and are part of what a
+ *   recording fixes: a set of arguments called again and again has two recordings, made by its third and fourth call.)
+ *   Same results and pass counts.  The model keeps the 128 most recently used recordings; a
  *   change of any option or of the workspace size discards them.  The caller must not capture such a call itself.
  *   MADE_OPT_XCD_RESIDENT (default 1; 0, 1 or 2): jacobi_sample / gs_jacobi_sample of Bernoulli models in ONE launch in
  *   which every XCD (a group of compute units with an L2 of its own) iterates its own eighth of the samples through
